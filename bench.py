@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Throughput of the multi-tenant hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch: mt_submit_batch + mt_run
+(tenant segmentation, gather, every grouped layer launch, softmax/argmax head), inputs and
+models already resident in device memory.  Prints one JSON line.
+
+  value       inferences/sec over the K timed steps (wall clock between device syncs)
+  roofline    the grouped GEMM kernel against HBM bandwidth (weight-streaming mixes) or the
+              bf16 MFMA peak (c5), from its average launch duration measured with HIP events
+              on the run's stream in a second pass over the same K steps (event brackets cost
+              microseconds per kernel, so they stay out of the throughput pass)
+  cpu_baseline the fp64 oracle timed on the host cores on a bounded sample of the same batch
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+FP32_MATRIX_PEAK_TFLOPS = 157.3
+
+
+def gemm_launch_costs(w, es):
+    """Algorithmic flops and bytes of the grouped GEMM launch of every layer index: each active
+    tenant's weights and bias read once, its input rows read once, its output rows written once
+    (hidden: element type; logits: fp32)."""
+    import workloads as wl
+    flops, bytes_ = {}, {}
+    for t, m_t in w.counts().items():
+        model = w.tenants[t]
+        n = len(model.layers)
+        for l, L in enumerate(model.layers):
+            if L.kind == wl.GAP:
+                continue
+            if L.kind == wl.FC:
+                f = 2 * m_t * L.in_features * L.out_features
+            else:
+                oh, ow = L.out_hw()
+                f = 2 * m_t * oh * ow * 9 * L.in_features * L.out_features
+            b = model.weights[l].size * es + model.biases[l].size * 4
+            b += m_t * L.in_len() * es
+            b += m_t * L.out_len() * (4 if l == n - 1 else es)
+            flops[l] = flops.get(l, 0) + f
+            bytes_[l] = bytes_.get(l, 0) + b
+    return flops, bytes_
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time of the CPU baseline sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1901_06887_amd as mt
+    import workloads as wl
+    from paper_1901_06887_amd import torch_io
+
+    mt.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    w = wl.CONFIGS[args.config]()
+    es = 4 if w.dtype == "f32" else 2
+    R = w.n_requests
+    ctx = mt.context_for(w.tenants, w.dtype, R)
+    mt.register_tenants(ctx, w.tenants)
+    d_ids = torch.from_numpy(w.tenant_ids).cuda()
+    d_x = torch_io.to_device(w.inputs, w.dtype)
+    out = torch_io.alloc_outputs(R, ctx.cfg.max_classes)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        mt.serve(ctx, d_ids, d_x, out=out, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = R * args.steps / dt
+
+    # second pass over the same steps with per-kernel HIP events on the run's stream
+    ctx.set_profiling(True)
+    prof = []
+    for _ in range(args.steps):
+        step()
+        prof.append(ctx.get_profile())
+    ctx.set_profiling(False)
+    n_slots = mt.MT_MAX_LAYERS
+    gemm_ms = [float(np.mean([p["gemm_ms"][l] for p in prof])) for l in range(n_slots)]
+    flops, bytes_ = gemm_launch_costs(w, es)
+    launches = [l for l in range(n_slots) if gemm_ms[l] > 0 and l in bytes_]
+    avg_dur_s = sum(gemm_ms[l] for l in launches) / len(launches) * 1e-3
+    avg_bytes = sum(bytes_[l] for l in launches) / len(launches)
+    avg_flops = sum(flops[l] for l in launches) / len(launches)
+    cost = wl.algorithmic_cost(w)
+    intensity = cost["flops"] / cost["bytes"]
+    if w.dtype == "bf16" and intensity > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+        achieved = avg_flops / avg_dur_s / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+    else:
+        achieved = avg_bytes / avg_dur_s / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None}
+    roofline.update({"kernel": "gemm_kernel<%s>" % ("bf16" if es == 2 else "float"),
+                     "launches_per_step": len(launches),
+                     "avg_launch_us": avg_dur_s * 1e6,
+                     "algorithmic_bytes_per_launch": avg_bytes, "algorithmic_flops_per_launch": avg_flops})
+    kernels_us = {"batcher": float(np.mean([p["batcher_ms"] for p in prof])) * 1e3,
+                  "gather": float(np.mean([p["gather_ms"] for p in prof])) * 1e3,
+                  "gemm_by_layer": [g * 1e3 for g in gemm_ms if g > 0],
+                  "gap": float(np.sum([np.mean([p["gap_ms"][l] for p in prof]) for l in range(n_slots)])) * 1e3,
+                  "head": float(np.mean([p["head_ms"] for p in prof])) * 1e3,
+                  "device_total": float(np.mean([p["total_ms"] for p in prof])) * 1e3}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = min(16, os.cpu_count() or 1)
+        models = oracle.models_from_workload(w)
+        macs_per_row = np.array([models[int(t)].macs_per_request() for t in w.tenant_ids], dtype=np.float64)
+        # ~0.45 GMAC/s per thread for the plain fp64 loop nests; bounded sample of arrival-ordered rows
+        budget = args.cpu_seconds * 0.45e9 * threads
+        n_sample = int(min(R, max(threads, np.searchsorted(np.cumsum(macs_per_row), budget))))
+        t0 = time.perf_counter()
+        oracle.run_batch(models, w.tenant_ids[:n_sample], w.inputs[:n_sample].astype(np.float64), threads=threads)
+        cdt = time.perf_counter() - t0
+        cpu = {"value": n_sample / cdt, "unit": "inferences/sec", "cores": threads, "kind": "oracle",
+               "sample": "first %d of %d requests of %s in arrival order, fp64 loop nests, %.1f s" % (n_sample, R, w.name, cdt)}
+
+    line = {"metric": "inferences/sec across tenants at 1 GPU", "value": value, "unit": "inferences/sec",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f32" if es == 4 else "bf16", "data": "synthetic",
+            "config": {"workload": w.name, "tenants": len(w.tenants), "requests_per_step": R,
+                       "active_tenants": len(w.counts()), "algorithmic_flops_per_step": cost["flops"],
+                       "algorithmic_bytes_per_step": cost["bytes"],
+                       "whole_path_hbm_frac": cost["bytes"] / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
+                       "whole_path_mfma_frac": cost["flops"] / (ms_per_step * 1e-3) / (MFMA_BF16_PEAK_TFLOPS * 1e12)},
+            "roofline": roofline, "kernels_us": kernels_us, "cpu_baseline": cpu}
+    print(json.dumps(line))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,194 @@
+/*
+ * mt.h - C ABI of the multi-tenant inference worker runtime for one AMD MI355X.
+ *
+ * The library is the internal model-execution runtime of one worker of the
+ * shared inference system the paper proposes: tenants upload a DNN, then send
+ * inference requests (paper, section 3); a worker hosts the DNNs of many
+ * tenants at once and multiplexes their requests (section 3); models come as a
+ * description of structure plus parameters and are built only from a closed set
+ * of supported layer types, never from user code (section 3.1); a DNN is a
+ * fixed sequence of layers applied in turn, and the answer to a request is a
+ * vector of class probabilities (section 1.1).
+ *
+ * One mt_run serves every pending request of every tenant: requests are grouped
+ * by tenant on the device, then each layer index is executed as one grouped
+ * launch over all tenants (tenant-specific weights, per-tenant batch sizes), and
+ * predictions come back in submission order.
+ *
+ * Conventions
+ *   - Every call returns an mt_status; nothing aborts or throws across the ABI.
+ *     mt_last_error() gives a text for the last failing call on a context.
+ *   - "HOST" pointers are ordinary process memory; "DEVICE" pointers are HIP
+ *     device memory on the context's GPU (e.g. a torch tensor's data_ptr()).
+ *   - A context is not thread-safe; one mt_run may be in flight per context.
+ *   - Element type of weights, inputs and hidden activations is the context's
+ *     dtype: MT_F32 (4 bytes) or MT_BF16 (2 bytes, bfloat16 bit patterns).
+ *     Biases, logits and probabilities are always fp32.  With MT_BF16 every
+ *     hidden activation is rounded to bfloat16 (nearest even) after bias and
+ *     activation; accumulation over the fan-in is fp32 throughout.
+ */
+#ifndef MT_H
+#define MT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mt_ctx mt_ctx;
+
+typedef enum {
+    MT_OK = 0,
+    MT_EINVAL = 1,       /* null pointer, zero size, value out of range            */
+    MT_ENOMEM = 2,       /* weight arena or a device allocation exhausted          */
+    MT_ENOTFOUND = 3,    /* tenant has no registered model                         */
+    MT_EEXIST = 4,       /* tenant already has a model                             */
+    MT_EUNSUPPORTED = 5, /* layer kind / activation / geometry outside the closed set */
+    MT_EFULL = 6,        /* more than max_requests rows pending                    */
+    MT_ESTATE = 7,       /* call not valid in this state (e.g. host-only context)  */
+    MT_EDEVICE = 8       /* a HIP call failed; text in mt_last_error               */
+} mt_status;
+
+typedef enum { MT_FC = 0, MT_CONV2D = 1, MT_GAP = 2 } mt_kind;
+typedef enum { MT_ACT_NONE = 0, MT_ACT_RELU = 1, MT_ACT_GELU = 2 } mt_act;
+typedef enum { MT_F32 = 0, MT_BF16 = 1 } mt_dtype;
+
+#define MT_MAX_LAYERS 8
+
+/* One layer of a model (closed set, paper section 3.1).
+ *   MT_FC:     y[n] = act(b[n] + sum_k W[n][k] x[k]); in_features = K, out_features = N.
+ *   MT_CONV2D: 3x3 cross-correlation over an NHWC image of in_h x in_w x in_features,
+ *              zero padding 1, stride 1 or 2, out_features output channels, bias per
+ *              channel, then act.  kh = kw = 3 and pad = 1 are the only values accepted.
+ *   MT_GAP:    mean over in_h x in_w of every one of in_features channels
+ *              (out_features must equal in_features, act must be MT_ACT_NONE).
+ * The activation of a model's last layer must be MT_ACT_NONE: its outputs are the logits. */
+typedef struct {
+    uint32_t kind, act;
+    uint32_t in_features, out_features;
+    uint32_t in_h, in_w, kh, kw, stride, pad;
+} mt_layer_spec;
+
+typedef struct {
+    uint32_t max_tenants;   /* tenant ids are 0 .. max_tenants-1                         */
+    uint32_t max_requests;  /* most rows that may be pending for one mt_run              */
+    uint32_t max_width;     /* most elements any request occupies at any layer boundary  */
+    uint32_t max_classes;   /* most outputs of any model's last layer                    */
+    uint64_t arena_bytes;   /* size of the packed weight arena in device memory          */
+    uint32_t dtype;         /* mt_dtype of weights / inputs / hidden activations         */
+    int32_t  device;        /* HIP device ordinal; -1 = host-only context: registration,
+                               validation and accounting work, mt_run returns MT_ESTATE  */
+} mt_config;
+
+/* Where mt_run writes predictions.  All DEVICE memory owned by the caller, valid
+ * until the stream work of that mt_run has completed.  Row i belongs to the i-th
+ * submitted row.  logits and probs have row_stride floats per row; columns at and
+ * past n_classes[i] are written as 0.  A row whose tenant id was out of range or
+ * had no model gets label -1, n_classes 0 and zero rows.  logits, probs and
+ * n_classes may each be NULL to skip that output. */
+typedef struct {
+    int32_t*  labels;      /* [capacity]                                  */
+    float*    probs;       /* [capacity * row_stride]                     */
+    float*    logits;      /* [capacity * row_stride]                     */
+    int32_t*  n_classes;   /* [capacity]                                  */
+    uint32_t  capacity;    /* rows the buffers can hold, >= pending rows  */
+    uint32_t  row_stride;  /* floats per row, >= max_classes              */
+} mt_outputs;
+
+typedef struct {
+    uint32_t n_tenants;          /* models registered                                  */
+    uint64_t arena_used;         /* bytes of the arena in use (padded layouts)         */
+    uint64_t arena_bytes;
+    uint32_t last_run_rows;      /* rows consumed by the last mt_run                   */
+    uint32_t last_run_launches;  /* kernels the last mt_run enqueued                   */
+} mt_stats;
+
+/* Create a worker context: allocates the weight arena, the tenant table, the batch
+ * descriptors and two activation buffers of max_requests * max_width elements on
+ * cfg->device.  Errors: MT_EINVAL (null / zero sizes), MT_ENOMEM, MT_EDEVICE. */
+mt_status mt_create(mt_ctx** out, const mt_config* cfg);
+
+/* Free everything the context owns (synchronises the device first). */
+mt_status mt_destroy(mt_ctx* ctx);
+
+/* Upload a tenant's DNN (paper section 3: "users first upload a DNN").
+ *   specs[n_layers]: layer chain; out length of layer l must equal in length of l+1.
+ *   weights[l]: HOST, context dtype; FC [N][K] row-major, CONV [C_out][C_in][3][3];
+ *               ignored (may be NULL) for GAP.
+ *   biases[l]:  HOST fp32 [N] or [C_out]; NULL means zeros.
+ * Weights are copied and repacked into the arena before the call returns; the caller
+ * keeps ownership of its buffers.  Nothing is allocated when the call fails.
+ * Errors: MT_EINVAL, MT_EEXIST, MT_EUNSUPPORTED (kind/act/geometry outside the closed
+ * set, dims that do not chain, more than MT_MAX_LAYERS layers, widths beyond
+ * max_width / max_classes), MT_ENOMEM (arena full), MT_EDEVICE. */
+mt_status mt_register_model(mt_ctx* ctx, uint32_t tenant, const mt_layer_spec* specs, uint32_t n_layers,
+                            const void* const* weights, const void* const* biases);
+
+/* Remove a tenant's model and return its arena slice.  Must not be called while an
+ * mt_run that may serve the tenant is still executing.  Errors: MT_ENOTFOUND. */
+mt_status mt_unregister_model(mt_ctx* ctx, uint32_t tenant);
+
+/* Queue n_rows requests of ONE tenant for the next mt_run (paper section 3: "then
+ * start sending inference requests").  inputs: DEVICE, n_rows rows of the model's
+ * input length, contiguous, context dtype; borrowed until the next mt_run's stream
+ * work has completed.  *first_index (optional) receives the submission index of the
+ * first row.  Errors: MT_EINVAL, MT_ENOTFOUND, MT_EFULL. */
+mt_status mt_submit(mt_ctx* ctx, uint32_t tenant, const void* inputs, uint32_t n_rows, uint32_t* first_index);
+
+/* Queue n_rows requests of MIXED tenants in arrival order, with the tenant id of
+ * every row already in device memory (what a request front-end that lands ids and
+ * payloads in GPU memory would hand over).  tenant_ids: DEVICE int32 [n_rows];
+ * inputs: DEVICE, row i at inputs + i*row_stride elements, each row holding its
+ * tenant's input length; row_stride must be at least the longest input of any
+ * registered model (else MT_EINVAL), so that no row read can leave the buffer.  Ids are validated on the device: rows of
+ * unknown tenants are answered with label -1 and never touch any model's weights.
+ * Both buffers are borrowed like in mt_submit.  Errors: MT_EINVAL, MT_EFULL. */
+mt_status mt_submit_batch(mt_ctx* ctx, const int32_t* tenant_ids, const void* inputs, uint32_t n_rows,
+                          uint32_t row_stride, uint32_t* first_index);
+
+/* Serve everything pending: enqueue, on hip_stream (a hipStream_t, NULL = default
+ * stream), tenant segmentation, the gather into tenant-contiguous rows, one grouped
+ * launch per layer index and kind, and the softmax/argmax head; write predictions to
+ * *out in submission order.  Returns without waiting for the GPU; clears the pending
+ * list.  *n_rows (optional) receives the number of rows served.  With nothing pending
+ * it returns MT_OK and serves 0 rows.  Errors: MT_EINVAL (out too small), MT_ESTATE,
+ * MT_EDEVICE. */
+mt_status mt_run(mt_ctx* ctx, void* hip_stream, const mt_outputs* out, uint32_t* n_rows);
+
+/* After the stream work of the last mt_run has completed: copy the per-tenant row
+ * counts it computed on the device to HOST counts[max_tenants] (synchronises the
+ * stream it ran on).  For tests and accounting. */
+mt_status mt_last_counts(mt_ctx* ctx, uint32_t* counts);
+
+mt_status mt_get_stats(const mt_ctx* ctx, mt_stats* out);
+
+/* Per-kernel timing of mt_run, for measurement.  While enabled, mt_run brackets every
+ * kernel it enqueues with HIP events on the run's stream (this costs a few microseconds
+ * per kernel, so throughput is measured with it off).  mt_get_profile synchronises the
+ * stream of the last profiled mt_run and fills *out with elapsed milliseconds; entries
+ * of launches that did not happen are 0. */
+typedef struct {
+    float batcher_ms, gather_ms, head_ms;
+    float gemm_ms[MT_MAX_LAYERS];   /* grouped GEMM / conv launch of each layer index */
+    float gap_ms[MT_MAX_LAYERS];    /* pooling launch of each layer index             */
+    float total_ms;                 /* first kernel start to last kernel end          */
+} mt_profile;
+mt_status mt_set_profiling(mt_ctx* ctx, int enable);
+mt_status mt_get_profile(mt_ctx* ctx, mt_profile* out);
+
+/* Testing aid: fill the context's internal activation and logits buffers with NaN bit
+ * patterns (synchronous).  A correct run overwrites or zero-fills everything it later
+ * reads, so results must not change.  Errors: MT_ESTATE (host-only), MT_EDEVICE. */
+mt_status mt_debug_poison(mt_ctx* ctx);
+
+/* Text of the last error on this context ("" if none); valid until the next call. */
+const char* mt_last_error(const mt_ctx* ctx);
+
+/* Library version string, e.g. "mt 0.1 gfx950". */
+const char* mt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MT_H */

@@ -1,0 +1,204 @@
+"""ctypes binding of ``libmt.so`` (the C ABI in ``include/mt.h``).
+
+Argument marshalling only: every step of the inference path runs in the library's HIP
+kernels.  PyTorch appears here only as the owner of device buffers and streams.  If the
+shared library has not been built, importing a context raises; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmt.so")
+
+MT_OK = 0
+STATUS_NAMES = {0: "MT_OK", 1: "MT_EINVAL", 2: "MT_ENOMEM", 3: "MT_ENOTFOUND", 4: "MT_EEXIST",
+                5: "MT_EUNSUPPORTED", 6: "MT_EFULL", 7: "MT_ESTATE", 8: "MT_EDEVICE"}
+MT_FC, MT_CONV2D, MT_GAP = 0, 1, 2
+MT_ACT_NONE, MT_ACT_RELU, MT_ACT_GELU = 0, 1, 2
+MT_F32, MT_BF16 = 0, 1
+MT_MAX_LAYERS = 8
+
+
+class MtError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("%s: %s" % (STATUS_NAMES.get(status, status), text))
+        self.status = status
+
+
+class mt_layer_spec(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in
+                ("kind", "act", "in_features", "out_features", "in_h", "in_w", "kh", "kw", "stride", "pad")]
+
+
+class mt_config(ctypes.Structure):
+    _fields_ = [("max_tenants", ctypes.c_uint32), ("max_requests", ctypes.c_uint32),
+                ("max_width", ctypes.c_uint32), ("max_classes", ctypes.c_uint32),
+                ("arena_bytes", ctypes.c_uint64), ("dtype", ctypes.c_uint32), ("device", ctypes.c_int32)]
+
+
+class mt_outputs(ctypes.Structure):
+    _fields_ = [("labels", ctypes.c_void_p), ("probs", ctypes.c_void_p), ("logits", ctypes.c_void_p),
+                ("n_classes", ctypes.c_void_p), ("capacity", ctypes.c_uint32), ("row_stride", ctypes.c_uint32)]
+
+
+class mt_stats(ctypes.Structure):
+    _fields_ = [("n_tenants", ctypes.c_uint32), ("arena_used", ctypes.c_uint64), ("arena_bytes", ctypes.c_uint64),
+                ("last_run_rows", ctypes.c_uint32), ("last_run_launches", ctypes.c_uint32)]
+
+
+class mt_profile(ctypes.Structure):
+    _fields_ = [("batcher_ms", ctypes.c_float), ("gather_ms", ctypes.c_float), ("head_ms", ctypes.c_float),
+                ("gemm_ms", ctypes.c_float * MT_MAX_LAYERS), ("gap_ms", ctypes.c_float * MT_MAX_LAYERS),
+                ("total_ms", ctypes.c_float)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libmt.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("%s is missing: build it with `python -m paper_1901_06887_amd.build`" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    vp, u32 = ctypes.c_void_p, ctypes.c_uint32
+    L.mt_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(mt_config)]
+    L.mt_destroy.argtypes = [vp]
+    L.mt_register_model.argtypes = [vp, u32, ctypes.POINTER(mt_layer_spec), u32, ctypes.POINTER(vp), ctypes.POINTER(vp)]
+    L.mt_unregister_model.argtypes = [vp, u32]
+    L.mt_submit.argtypes = [vp, u32, vp, u32, ctypes.POINTER(u32)]
+    L.mt_submit_batch.argtypes = [vp, vp, vp, u32, u32, ctypes.POINTER(u32)]
+    L.mt_run.argtypes = [vp, vp, ctypes.POINTER(mt_outputs), ctypes.POINTER(u32)]
+    L.mt_last_counts.argtypes = [vp, ctypes.POINTER(u32)]
+    L.mt_get_stats.argtypes = [vp, ctypes.POINTER(mt_stats)]
+    L.mt_debug_poison.argtypes = [vp]
+    L.mt_set_profiling.argtypes = [vp, ctypes.c_int]
+    L.mt_get_profile.argtypes = [vp, ctypes.POINTER(mt_profile)]
+    L.mt_last_error.argtypes = [vp]
+    L.mt_last_error.restype = ctypes.c_char_p
+    L.mt_version.restype = ctypes.c_char_p
+    for name in ("mt_create", "mt_destroy", "mt_register_model", "mt_unregister_model", "mt_submit",
+                 "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_debug_poison",
+                 "mt_set_profiling", "mt_get_profile"):
+        getattr(L, name).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def layer_spec(kind, act=MT_ACT_NONE, in_features=0, out_features=0, in_h=0, in_w=0, stride=1) -> mt_layer_spec:
+    conv = kind == MT_CONV2D
+    return mt_layer_spec(kind, act, in_features, out_features, in_h, in_w, 3 if conv else 0, 3 if conv else 0,
+                         stride if conv else 0, 1 if conv else 0)
+
+
+def _host_array(a, dtype_code: int) -> np.ndarray:
+    """Contiguous host array in the context's element type (bf16 as uint16 bit patterns)."""
+    a = np.asarray(a)
+    if dtype_code == MT_BF16:
+        if a.dtype != np.uint16:
+            a32 = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+            if np.any(a32 & 0xFFFF):
+                raise ValueError("weights of a bf16 context must be bfloat16-representable or uint16 bit patterns")
+            a = (a32 >> 16).astype(np.uint16)
+        return np.ascontiguousarray(a)
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+class Context:
+    """One worker context (mt_ctx).  Methods mirror the C entry points one to one."""
+
+    def __init__(self, max_tenants: int, max_requests: int, max_width: int, max_classes: int,
+                 arena_bytes: int, dtype: int, device: int = 0):
+        self._lib = load_library()
+        self.dtype = dtype
+        self.cfg = mt_config(max_tenants, max_requests, max_width, max_classes, arena_bytes, dtype, device)
+        self._h = ctypes.c_void_p()
+        st = self._lib.mt_create(ctypes.byref(self._h), ctypes.byref(self.cfg))
+        if st != MT_OK:
+            raise MtError(st, "mt_create failed")
+
+    def _check(self, st: int):
+        if st != MT_OK:
+            raise MtError(st, self._lib.mt_last_error(self._h).decode())
+
+    def close(self):
+        if self._h:
+            self._lib.mt_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- mt_register_model ---------------------------------------------------------------
+    def register_model(self, tenant: int, specs: Sequence[mt_layer_spec], weights, biases):
+        n = len(specs)
+        arr = (mt_layer_spec * n)(*specs)
+        keep = []
+        wp = (ctypes.c_void_p * n)()
+        bp = (ctypes.c_void_p * n)()
+        for i in range(n):
+            if weights[i] is not None:
+                w = _host_array(weights[i], self.dtype); keep.append(w); wp[i] = w.ctypes.data
+            if biases is not None and biases[i] is not None:
+                b = np.ascontiguousarray(biases[i], dtype=np.float32); keep.append(b); bp[i] = b.ctypes.data
+        self._check(self._lib.mt_register_model(self._h, tenant, arr, n, wp, bp))
+
+    def unregister_model(self, tenant: int):
+        self._check(self._lib.mt_unregister_model(self._h, tenant))
+
+    # -- mt_submit / mt_submit_batch (device pointers) -------------------------------------
+    def submit(self, tenant: int, inputs_ptr: int, n_rows: int) -> int:
+        first = ctypes.c_uint32(0)
+        self._check(self._lib.mt_submit(self._h, tenant, ctypes.c_void_p(inputs_ptr), n_rows, ctypes.byref(first)))
+        return first.value
+
+    def submit_batch(self, tenant_ids_ptr: int, inputs_ptr: int, n_rows: int, row_stride: int) -> int:
+        first = ctypes.c_uint32(0)
+        self._check(self._lib.mt_submit_batch(self._h, ctypes.c_void_p(tenant_ids_ptr), ctypes.c_void_p(inputs_ptr),
+                                              n_rows, row_stride, ctypes.byref(first)))
+        return first.value
+
+    # -- mt_run ------------------------------------------------------------------------------
+    def run(self, stream_ptr: int, labels_ptr: int, probs_ptr: int, logits_ptr: int, n_classes_ptr: int,
+            capacity: int, row_stride: int) -> int:
+        out = mt_outputs(labels_ptr or None, probs_ptr or None, logits_ptr or None, n_classes_ptr or None,
+                         capacity, row_stride)
+        n = ctypes.c_uint32(0)
+        self._check(self._lib.mt_run(self._h, ctypes.c_void_p(stream_ptr or None), ctypes.byref(out), ctypes.byref(n)))
+        return n.value
+
+    def last_counts(self) -> np.ndarray:
+        counts = np.zeros(self.cfg.max_tenants, dtype=np.uint32)
+        self._check(self._lib.mt_last_counts(self._h, counts.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32))))
+        return counts
+
+    def set_profiling(self, enable: bool):
+        self._check(self._lib.mt_set_profiling(self._h, int(enable)))
+
+    def get_profile(self) -> dict:
+        p = mt_profile()
+        self._check(self._lib.mt_get_profile(self._h, ctypes.byref(p)))
+        return {"batcher_ms": p.batcher_ms, "gather_ms": p.gather_ms, "head_ms": p.head_ms,
+                "gemm_ms": list(p.gemm_ms), "gap_ms": list(p.gap_ms), "total_ms": p.total_ms}
+
+    def debug_poison(self):
+        self._check(self._lib.mt_debug_poison(self._h))
+
+    def stats(self) -> dict:
+        s = mt_stats()
+        self._check(self._lib.mt_get_stats(self._h, ctypes.byref(s)))
+        return {k: getattr(s, k) for k, _ in mt_stats._fields_}
+
+
+def version() -> str:
+    return load_library().mt_version().decode()

@@ -1,0 +1,647 @@
+// Host side of the multi-tenant worker runtime: the C ABI of include/mt.h, the tenant
+// registry (closed layer set, paper section 3.1), the packed weight arena in device memory
+// (models stay resident on the accelerator, section 3.3) and the fixed launch sequence of
+// mt_run (segmentation, gather, one grouped launch per layer index, head).
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "mt_internal.h"
+
+using namespace mt;
+
+namespace {
+
+constexpr uint32_t kMaxTenants = 2048;
+constexpr uint32_t kSegSlots = 4;
+constexpr uint64_t kArenaAlign = 256;
+// profiling slots: batcher, gather, head, then gemm and gap of every layer index
+constexpr uint32_t kProfBatcher = 0, kProfGather = 1, kProfHead = 2, kProfGemm = 3, kProfGap = 3 + MT_MAX_LAYERS;
+constexpr uint32_t kProfSlots = 3 + 2 * MT_MAX_LAYERS;
+
+inline uint32_t round_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }
+inline uint64_t round_up64(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+struct HostLayer {
+    mt_layer_spec spec;
+    LayerDev dev;
+    uint64_t w_bytes, b_bytes;
+};
+
+struct HostTenant {
+    bool registered = false;
+    uint32_t n_layers = 0;
+    HostLayer layers[MT_MAX_LAYERS];
+    TenantDev dev{};
+    uint64_t arena_off = 0, arena_len = 0;
+};
+
+struct FreeBlock { uint64_t off, len; };
+
+}  // namespace
+
+struct mt_ctx {
+    mt_config cfg{};
+    bool host_only = false;
+    uint32_t elem_size = 2;
+    uint32_t S = 0;        // elements between consecutive requests in an activation buffer
+    uint32_t C_pad = 0;    // floats between consecutive rows of the internal logits buffer
+    std::vector<HostTenant> tenants;
+    std::vector<FreeBlock> free_list;
+    uint64_t arena_used = 0;
+    uint32_t n_registered = 0;
+
+    // per layer index, over registered tenants: bounds that size the grouped launches
+    uint32_t n_layer_slots = 0;
+    uint32_t max_in_len = 0;
+    uint32_t max_rpr[MT_MAX_LAYERS]{}, max_nt[MT_MAX_LAYERS]{}, has_gap[MT_MAX_LAYERS]{};
+    uint64_t sum_nt[MT_MAX_LAYERS]{};
+
+    // device state
+    uint8_t* d_arena = nullptr;
+    TenantDev* d_tenants = nullptr;
+    LayerDev* d_layers = nullptr;
+    int32_t* d_row_tenant = nullptr;
+    uint32_t* d_row_rank = nullptr;
+    const void** d_row_src = nullptr;
+    int32_t* d_pos_of = nullptr;
+    uint32_t* d_perm = nullptr;
+    uint32_t* d_M = nullptr;
+    uint32_t* d_off = nullptr;
+    uint32_t* d_n_tiles = nullptr;
+    uint32_t* d_overflow = nullptr;
+    Tile* d_tiles = nullptr;
+    uint32_t tile_cap = 0;
+    void* d_act[2] = {nullptr, nullptr};
+    float* d_logits = nullptr;
+    Segment* h_segs[kSegSlots] = {};    // pinned, device-visible
+    Segment* d_segs[kSegSlots] = {};    // device addresses of the same memory
+    hipEvent_t seg_event[kSegSlots] = {};
+    bool seg_busy[kSegSlots] = {};
+    uint64_t run_count = 0;
+    hipStream_t last_stream = nullptr;
+
+    // pending submissions
+    std::vector<Segment> pending;
+    uint32_t pending_rows = 0;
+
+    uint32_t last_run_rows = 0, last_run_launches = 0;
+    std::string err;
+
+    // optional per-kernel timing: event 2*i / 2*i+1 bracket launch slot i
+    bool profiling = false;
+    std::vector<hipEvent_t> prof_events;
+    bool prof_used[kProfSlots] = {};
+    bool prof_valid = false;
+};
+
+namespace {
+
+mt_status fail(mt_ctx* c, mt_status st, const char* fmt, ...)
+{
+    if (c) {
+        char buf[512];
+        va_list ap; va_start(ap, fmt); vsnprintf(buf, sizeof buf, fmt, ap); va_end(ap);
+        c->err = buf;
+    }
+    return st;
+}
+
+#define HIP_TRY(c, expr)                                                                    \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return fail((c), e_ == hipErrorOutOfMemory ? MT_ENOMEM : MT_EDEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- arena: first-fit free list, blocks merged on release -----------------------------
+bool arena_alloc(mt_ctx* c, uint64_t len, uint64_t* off)
+{
+    len = round_up64(len, kArenaAlign);
+    for (size_t i = 0; i < c->free_list.size(); ++i) {
+        FreeBlock& b = c->free_list[i];
+        if (b.len >= len) {
+            *off = b.off;
+            b.off += len; b.len -= len;
+            if (b.len == 0) c->free_list.erase(c->free_list.begin() + (long)i);
+            c->arena_used += len;
+            return true;
+        }
+    }
+    return false;
+}
+
+void arena_free(mt_ctx* c, uint64_t off, uint64_t len)
+{
+    len = round_up64(len, kArenaAlign);
+    FreeBlock nb{off, len};
+    auto it = std::lower_bound(c->free_list.begin(), c->free_list.end(), nb,
+                               [](const FreeBlock& a, const FreeBlock& b) { return a.off < b.off; });
+    it = c->free_list.insert(it, nb);
+    if (it + 1 != c->free_list.end() && it->off + it->len == (it + 1)->off) { it->len += (it + 1)->len; c->free_list.erase(it + 1); }
+    if (it != c->free_list.begin() && (it - 1)->off + (it - 1)->len == it->off) { (it - 1)->len += it->len; c->free_list.erase(it); }
+    c->arena_used -= len;
+}
+
+void recompute_bounds(mt_ctx* c)
+{
+    c->n_layer_slots = 0;
+    c->max_in_len = 0;
+    for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) { c->max_rpr[l] = c->max_nt[l] = c->has_gap[l] = 0; c->sum_nt[l] = 0; }
+    for (const HostTenant& t : c->tenants) {
+        if (!t.registered) continue;
+        c->n_layer_slots = std::max(c->n_layer_slots, t.n_layers);
+        c->max_in_len = std::max(c->max_in_len, t.dev.in_len);
+        for (uint32_t l = 0; l < t.n_layers; ++l) {
+            const LayerDev& L = t.layers[l].dev;
+            if (L.kind == MT_GAP) { c->has_gap[l] = 1; continue; }
+            const uint32_t nt = (L.N + kBN - 1) / kBN;
+            c->max_rpr[l] = std::max(c->max_rpr[l], L.rows_per_req);
+            c->max_nt[l] = std::max(c->max_nt[l], nt);
+            c->sum_nt[l] += nt;
+        }
+    }
+}
+
+// Upper bound of sum_t ceil(M_t*rpr_t/BM)*nt_t over any split of R rows among tenants.
+uint64_t tile_bound(const mt_ctx* c, uint32_t l, uint64_t R)
+{
+    if (c->max_nt[l] == 0) return 0;
+    return (uint64_t)c->max_nt[l] * (R * c->max_rpr[l] / kBM) + c->sum_nt[l];
+}
+
+// ---- validation of a layer chain; fills dev layouts (without arena offsets) -------------
+mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, HostTenant* out)
+{
+    if (n_layers == 0 || n_layers > MT_MAX_LAYERS)
+        return fail(c, MT_EUNSUPPORTED, "a model needs 1..%d layers, got %u", MT_MAX_LAYERS, n_layers);
+    const uint32_t es = c->elem_size;
+    const uint32_t eps = kRowBytes / es;      // K granularity of the arena layout
+    uint32_t prev_out = 0;
+    out->n_layers = n_layers;
+    out->dev = TenantDev{};
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const mt_layer_spec& s = specs[l];
+        HostLayer& hl = out->layers[l];
+        hl.spec = s;
+        LayerDev d{};
+        d.kind = s.kind; d.act = s.act; d.is_last = (l == n_layers - 1);
+        d.stride = 1; d.out_w = 1; d.rows_per_req = 1;
+        if (s.act > MT_ACT_GELU) return fail(c, MT_EUNSUPPORTED, "layer %u: activation %u is not in the supported set", l, s.act);
+        if (d.is_last && s.act != MT_ACT_NONE) return fail(c, MT_EUNSUPPORTED, "layer %u: the last layer yields logits and takes no activation", l);
+        uint32_t in_len = 0;
+        if (s.kind == MT_FC) {
+            if (s.in_features == 0 || s.out_features == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized FC", l);
+            in_len = s.in_features;
+            d.K = round_up(s.in_features, eps); d.N = s.out_features;
+            d.out_len = s.out_features;
+            hl.w_bytes = (uint64_t)d.N * d.K * es; hl.b_bytes = (uint64_t)d.N * 4;
+        } else if (s.kind == MT_CONV2D) {
+            if (s.kh != 3 || s.kw != 3 || s.pad != 1 || (s.stride != 1 && s.stride != 2))
+                return fail(c, MT_EUNSUPPORTED, "layer %u: only 3x3 convolutions with pad 1 and stride 1 or 2 are supported", l);
+            if (s.in_features == 0 || s.out_features == 0 || s.in_h == 0 || s.in_w == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized conv", l);
+            if (d.is_last) return fail(c, MT_EUNSUPPORTED, "layer %u: the last layer must be fully connected", l);
+            if (s.out_features % kChanPad) return fail(c, MT_EUNSUPPORTED, "layer %u: conv output channels must be a multiple of %d", l, kChanPad);
+            if (l > 0 && s.in_features % kChanPad) return fail(c, MT_EUNSUPPORTED, "layer %u: conv input channels must be a multiple of %d past the first layer", l, kChanPad);
+            in_len = s.in_h * s.in_w * s.in_features;
+            const uint32_t oh = (s.in_h + 2 - 3) / s.stride + 1, ow = (s.in_w + 2 - 3) / s.stride + 1;
+            d.cin = round_up(s.in_features, kChanPad);
+            d.in_h = s.in_h; d.in_w = s.in_w; d.stride = s.stride; d.out_w = ow;
+            d.rows_per_req = oh * ow;
+            d.K = round_up(9 * d.cin, eps); d.N = s.out_features;
+            d.out_len = oh * ow * s.out_features;
+            if (d.out_len % kWidthAlign) return fail(c, MT_EUNSUPPORTED, "layer %u: conv output size %u is not a multiple of %d elements", l, d.out_len, kWidthAlign);
+            hl.w_bytes = (uint64_t)d.N * d.K * es; hl.b_bytes = (uint64_t)d.N * 4;
+        } else if (s.kind == MT_GAP) {
+            if (s.in_features == 0 || s.in_h == 0 || s.in_w == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized pool", l);
+            if (s.out_features != s.in_features || s.act != MT_ACT_NONE) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling keeps the channel count and has no activation", l);
+            if (d.is_last || l == 0) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling cannot be the first or the last layer", l);
+            in_len = s.in_h * s.in_w * s.in_features;
+            d.cin = s.in_features; d.in_h = s.in_h; d.in_w = s.in_w; d.N = s.in_features;
+            d.out_len = s.in_features;
+            hl.w_bytes = hl.b_bytes = 0;
+        } else {
+            return fail(c, MT_EUNSUPPORTED, "layer %u: kind %u is not in the supported set", l, s.kind);
+        }
+        if (l > 0 && in_len != prev_out) return fail(c, MT_EUNSUPPORTED, "layer %u takes %u values but layer %u yields %u", l, in_len, l - 1, prev_out);
+        d.out_fill = round_up(d.out_len, kWidthAlign);
+        if (l == 0) {
+            out->dev.in_len = in_len;
+            uint32_t staged = in_len;
+            if (s.kind == MT_CONV2D && d.cin != s.in_features) {
+                out->dev.in_cin = s.in_features; out->dev.in_cin_pad = d.cin;
+                staged = s.in_h * s.in_w * d.cin;
+            }
+            out->dev.in_fill = round_up(staged, kWidthAlign);
+            if (s.kind == MT_FC) out->dev.in_fill = std::max(out->dev.in_fill, d.K);
+            if (out->dev.in_fill > c->S) return fail(c, MT_EUNSUPPORTED, "input of %u values exceeds max_width", in_len);
+        }
+        if (!d.is_last && d.out_fill > c->S) return fail(c, MT_EUNSUPPORTED, "layer %u output of %u values exceeds max_width", l, d.out_len);
+        if (s.kind == MT_FC && d.K > c->S) return fail(c, MT_EUNSUPPORTED, "layer %u fan-in %u exceeds max_width", l, s.in_features);
+        if (d.is_last && d.out_len > c->cfg.max_classes) return fail(c, MT_EUNSUPPORTED, "%u classes exceed max_classes", d.out_len);
+        prev_out = d.out_len;
+        hl.dev = d;
+    }
+    out->dev.n_layers = n_layers;
+    out->dev.n_classes = prev_out;
+    return MT_OK;
+}
+
+// Arena image of one layer: weight rows padded with zeros to the K granularity; conv filters
+// reordered from [Co][Ci][3][3] to [Co][kh][kw][ci_padded] so that a GEMM k index walks the
+// NHWC input contiguously.
+template <typename T>
+void pack_weights(const HostLayer& hl, const void* w_src, uint8_t* dst)
+{
+    const LayerDev& d = hl.dev;
+    const T* src = (const T*)w_src;
+    T* out = (T*)dst;
+    std::memset(dst, 0, hl.w_bytes);
+    if (d.kind == MT_FC) {
+        const uint32_t K = hl.spec.in_features;
+        for (uint32_t n = 0; n < d.N; ++n) std::memcpy(out + (size_t)n * d.K, src + (size_t)n * K, (size_t)K * sizeof(T));
+    } else {
+        const uint32_t Ci = hl.spec.in_features;
+        for (uint32_t co = 0; co < d.N; ++co)
+            for (uint32_t ci = 0; ci < Ci; ++ci)
+                for (uint32_t kh = 0; kh < 3; ++kh)
+                    for (uint32_t kw = 0; kw < 3; ++kw)
+                        out[(size_t)co * d.K + (kh * 3 + kw) * d.cin + ci] = src[(((size_t)co * Ci + ci) * 3 + kh) * 3 + kw];
+    }
+}
+
+mt_status ensure_tiles(mt_ctx* c)
+{
+    uint64_t need = 1;
+    for (uint32_t l = 0; l < c->n_layer_slots; ++l) need = std::max(need, tile_bound(c, l, c->cfg.max_requests));
+    if (need <= c->tile_cap) return MT_OK;
+    need = round_up64(need + need / 8, 1024);
+    if (need * MT_MAX_LAYERS * sizeof(Tile) > (1ull << 32)) return fail(c, MT_ENOMEM, "tile lists would need %llu entries per layer", (unsigned long long)need);
+    HIP_TRY(c, hipDeviceSynchronize());
+    if (c->d_tiles) HIP_TRY(c, hipFree(c->d_tiles));
+    c->d_tiles = nullptr; c->tile_cap = 0;
+    HIP_TRY(c, hipMalloc((void**)&c->d_tiles, need * MT_MAX_LAYERS * sizeof(Tile)));
+    c->tile_cap = (uint32_t)need;
+    return MT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mt_version(void) { return "mt 0.1 gfx950"; }
+
+const char* mt_last_error(const mt_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+mt_status mt_create(mt_ctx** out, const mt_config* cfg)
+{
+    if (!out || !cfg) return MT_EINVAL;
+    *out = nullptr;
+    if (cfg->max_tenants == 0 || cfg->max_tenants > kMaxTenants || cfg->max_requests == 0 || cfg->max_width == 0 ||
+        cfg->max_classes == 0 || cfg->arena_bytes == 0 || cfg->dtype > MT_BF16)
+        return MT_EINVAL;
+    if ((uint64_t)cfg->max_requests * 4096 > (1ull << 31)) return MT_EINVAL;   // row indices and GEMM row counts stay in 32 bits
+    mt_ctx* c = new (std::nothrow) mt_ctx;
+    if (!c) return MT_ENOMEM;
+    c->cfg = *cfg;
+    c->host_only = cfg->device < 0;
+    c->elem_size = cfg->dtype == MT_BF16 ? 2 : 4;
+    c->S = round_up(cfg->max_width, kWidthAlign);
+    c->C_pad = round_up(cfg->max_classes, 4);
+    c->tenants.resize(cfg->max_tenants);
+    c->cfg.arena_bytes = cfg->arena_bytes / kArenaAlign * kArenaAlign;
+    c->free_list.push_back(FreeBlock{0, c->cfg.arena_bytes});
+    *out = c;
+    if (c->host_only) return MT_OK;
+
+    auto bail = [&](mt_status st) { mt_destroy(c); *out = nullptr; return st; };
+#define CREATE_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { fprintf(stderr, "mt_create: %s: %s\n", #expr, hipGetErrorString(e_)); return bail(e_ == hipErrorOutOfMemory ? MT_ENOMEM : MT_EDEVICE); } } while (0)
+    CREATE_TRY(hipSetDevice(cfg->device));
+    const uint64_t R = cfg->max_requests, T = cfg->max_tenants;
+    CREATE_TRY(hipMalloc((void**)&c->d_arena, c->cfg.arena_bytes));
+    CREATE_TRY(hipMalloc((void**)&c->d_tenants, T * sizeof(TenantDev)));
+    CREATE_TRY(hipMemset(c->d_tenants, 0, T * sizeof(TenantDev)));
+    CREATE_TRY(hipMalloc((void**)&c->d_layers, T * MT_MAX_LAYERS * sizeof(LayerDev)));
+    CREATE_TRY(hipMemset(c->d_layers, 0, T * MT_MAX_LAYERS * sizeof(LayerDev)));
+    CREATE_TRY(hipMalloc((void**)&c->d_row_tenant, R * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_row_rank, R * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_row_src, R * sizeof(void*)));
+    CREATE_TRY(hipMalloc((void**)&c->d_pos_of, R * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_perm, R * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_M, T * 4));
+    CREATE_TRY(hipMemset(c->d_M, 0, T * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_off, (T + 1) * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_n_tiles, MT_MAX_LAYERS * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_overflow, 4));
+    CREATE_TRY(hipMemset(c->d_overflow, 0, 4));
+    for (int i = 0; i < 2; ++i) {
+        CREATE_TRY(hipMalloc(&c->d_act[i], R * c->S * c->elem_size));
+    }
+    CREATE_TRY(hipMalloc((void**)&c->d_logits, R * c->C_pad * 4));
+    for (uint32_t i = 0; i < kSegSlots; ++i) {
+        CREATE_TRY(hipHostMalloc((void**)&c->h_segs[i], R * sizeof(Segment), hipHostMallocMapped));
+        CREATE_TRY(hipHostGetDevicePointer((void**)&c->d_segs[i], c->h_segs[i], 0));
+        CREATE_TRY(hipEventCreateWithFlags(&c->seg_event[i], hipEventDisableTiming));
+    }
+#undef CREATE_TRY
+    return MT_OK;
+}
+
+mt_status mt_destroy(mt_ctx* c)
+{
+    if (!c) return MT_EINVAL;
+    if (!c->host_only) {
+        (void)hipSetDevice(c->cfg.device);
+        (void)hipDeviceSynchronize();
+        void* bufs[] = {c->d_arena, c->d_tenants, c->d_layers, c->d_row_tenant, c->d_row_rank, (void*)c->d_row_src, c->d_pos_of, c->d_perm,
+                        c->d_M, c->d_off, c->d_n_tiles, c->d_overflow, c->d_tiles, c->d_act[0], c->d_act[1], c->d_logits};
+        for (void* p : bufs) if (p) (void)hipFree(p);
+        for (uint32_t i = 0; i < kSegSlots; ++i) {
+            if (c->h_segs[i]) (void)hipHostFree(c->h_segs[i]);
+            if (c->seg_event[i]) (void)hipEventDestroy(c->seg_event[i]);
+        }
+        for (hipEvent_t e : c->prof_events) if (e) (void)hipEventDestroy(e);
+    }
+    delete c;
+    return MT_OK;
+}
+
+mt_status mt_register_model(mt_ctx* c, uint32_t tenant, const mt_layer_spec* specs, uint32_t n_layers,
+                            const void* const* weights, const void* const* biases)
+{
+    if (!c) return MT_EINVAL;
+    if (!specs || !weights) return fail(c, MT_EINVAL, "null specs or weights");
+    if (tenant >= c->cfg.max_tenants) return fail(c, MT_EINVAL, "tenant %u is outside 0..%u", tenant, c->cfg.max_tenants - 1);
+    if (c->tenants[tenant].registered) return fail(c, MT_EEXIST, "tenant %u already has a model", tenant);
+    HostTenant ht;
+    mt_status st = plan_model(c, specs, n_layers, &ht);
+    if (st != MT_OK) return st;
+    for (uint32_t l = 0; l < n_layers; ++l)
+        if (ht.layers[l].dev.kind != MT_GAP && !weights[l]) return fail(c, MT_EINVAL, "layer %u: null weights", l);
+
+    uint64_t total = 0;
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        HostLayer& hl = ht.layers[l];
+        hl.dev.w_off = total; total += round_up64(hl.w_bytes, kArenaAlign);
+        hl.dev.b_off = total; total += round_up64(hl.b_bytes, kArenaAlign);
+    }
+    if (total == 0) total = kArenaAlign;
+    uint64_t off = 0;
+    if (!arena_alloc(c, total, &off))
+        return fail(c, MT_ENOMEM, "weight arena exhausted: model needs %llu bytes, %llu of %llu in use",
+                    (unsigned long long)total, (unsigned long long)c->arena_used, (unsigned long long)c->cfg.arena_bytes);
+    ht.arena_off = off; ht.arena_len = total;
+    for (uint32_t l = 0; l < n_layers; ++l) { ht.layers[l].dev.w_off += off; ht.layers[l].dev.b_off += off; }
+
+    if (!c->host_only) {
+        std::vector<uint8_t> image(total, 0);
+        for (uint32_t l = 0; l < n_layers; ++l) {
+            const HostLayer& hl = ht.layers[l];
+            if (hl.dev.kind == MT_GAP) continue;
+            uint8_t* w_dst = image.data() + (hl.dev.w_off - off);
+            if (c->elem_size == 2) pack_weights<uint16_t>(hl, weights[l], w_dst); else pack_weights<float>(hl, weights[l], w_dst);
+            if (biases && biases[l]) std::memcpy(image.data() + (hl.dev.b_off - off), biases[l], hl.b_bytes);
+        }
+        LayerDev rows[MT_MAX_LAYERS]{};
+        for (uint32_t l = 0; l < n_layers; ++l) rows[l] = ht.layers[l].dev;
+        TenantDev td = ht.dev; td.registered = 1;
+        hipError_t e = hipSetDevice(c->cfg.device);
+        if (e == hipSuccess) e = hipMemcpy(c->d_arena + off, image.data(), total, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(c->d_layers + (size_t)tenant * MT_MAX_LAYERS, rows, sizeof rows, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(c->d_tenants + tenant, &td, sizeof td, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            arena_free(c, off, total);
+            return fail(c, MT_EDEVICE, "upload of tenant %u failed: %s", tenant, hipGetErrorString(e));
+        }
+    }
+    ht.registered = true; ht.dev.registered = 1;
+    c->tenants[tenant] = ht;
+    c->n_registered++;
+    recompute_bounds(c);
+    return MT_OK;
+}
+
+mt_status mt_unregister_model(mt_ctx* c, uint32_t tenant)
+{
+    if (!c) return MT_EINVAL;
+    if (tenant >= c->cfg.max_tenants || !c->tenants[tenant].registered) return fail(c, MT_ENOTFOUND, "tenant %u has no model", tenant);
+    for (const Segment& s : c->pending)
+        if (!s.ids && s.tenant == (int32_t)tenant) return fail(c, MT_ESTATE, "tenant %u has pending requests", tenant);
+    if (!c->host_only) {
+        TenantDev td{};
+        HIP_TRY(c, hipSetDevice(c->cfg.device));
+        HIP_TRY(c, hipDeviceSynchronize());
+        HIP_TRY(c, hipMemcpy(c->d_tenants + tenant, &td, sizeof td, hipMemcpyHostToDevice));
+    }
+    arena_free(c, c->tenants[tenant].arena_off, c->tenants[tenant].arena_len);
+    c->tenants[tenant] = HostTenant{};
+    c->n_registered--;
+    recompute_bounds(c);
+    return MT_OK;
+}
+
+static mt_status push_segment(mt_ctx* c, const Segment& s, uint32_t* first_index)
+{
+    if ((uint64_t)c->pending_rows + s.n_rows > c->cfg.max_requests)
+        return fail(c, MT_EFULL, "%u rows pending, %u more exceed max_requests %u", c->pending_rows, s.n_rows, c->cfg.max_requests);
+    Segment seg = s;
+    seg.row_begin = c->pending_rows;
+    if (first_index) *first_index = c->pending_rows;
+    // consecutive submissions of one tenant from one contiguous buffer collapse into one run
+    if (!c->pending.empty()) {
+        Segment& b = c->pending.back();
+        if (!b.ids && !seg.ids && b.tenant == seg.tenant && b.row_stride == seg.row_stride &&
+            (const uint8_t*)b.src + (size_t)b.n_rows * b.row_stride * c->elem_size == (const uint8_t*)seg.src) {
+            b.n_rows += seg.n_rows; c->pending_rows += seg.n_rows;
+            return MT_OK;
+        }
+    }
+    c->pending.push_back(seg);
+    c->pending_rows += seg.n_rows;
+    return MT_OK;
+}
+
+mt_status mt_submit(mt_ctx* c, uint32_t tenant, const void* inputs, uint32_t n_rows, uint32_t* first_index)
+{
+    if (!c) return MT_EINVAL;
+    if (!inputs || n_rows == 0) return fail(c, MT_EINVAL, "null inputs or zero rows");
+    if (tenant >= c->cfg.max_tenants || !c->tenants[tenant].registered) return fail(c, MT_ENOTFOUND, "tenant %u has no model", tenant);
+    Segment s{};
+    s.ids = nullptr; s.src = inputs; s.n_rows = n_rows; s.row_stride = c->tenants[tenant].dev.in_len; s.tenant = (int32_t)tenant;
+    return push_segment(c, s, first_index);
+}
+
+mt_status mt_submit_batch(mt_ctx* c, const int32_t* tenant_ids, const void* inputs, uint32_t n_rows, uint32_t row_stride,
+                          uint32_t* first_index)
+{
+    if (!c) return MT_EINVAL;
+    if (!tenant_ids || !inputs || n_rows == 0 || row_stride == 0) return fail(c, MT_EINVAL, "null buffers, zero rows or zero stride");
+    if (row_stride < c->max_in_len)
+        return fail(c, MT_EINVAL, "row_stride %u is shorter than the longest registered input (%u)", row_stride, c->max_in_len);
+    Segment s{};
+    s.ids = tenant_ids; s.src = inputs; s.n_rows = n_rows; s.row_stride = row_stride; s.tenant = -1;
+    return push_segment(c, s, first_index);
+}
+
+mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n_rows)
+{
+    if (!c) return MT_EINVAL;
+    if (n_rows) *n_rows = 0;
+    if (c->host_only) return fail(c, MT_ESTATE, "host-only context cannot run");
+    const uint32_t R = c->pending_rows;
+    if (R == 0) { c->last_run_rows = 0; c->last_run_launches = 0; return MT_OK; }
+    if (!out || !out->labels) return fail(c, MT_EINVAL, "null outputs");
+    if (out->capacity < R) return fail(c, MT_EINVAL, "outputs hold %u rows, %u pending", out->capacity, R);
+    if ((out->probs || out->logits) && out->row_stride < c->cfg.max_classes)
+        return fail(c, MT_EINVAL, "row_stride %u is below max_classes %u", out->row_stride, c->cfg.max_classes);
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    mt_status st = ensure_tiles(c);
+    if (st != MT_OK) return st;
+
+    const uint32_t slot = (uint32_t)(c->run_count % kSegSlots);
+    if (c->seg_busy[slot]) { HIP_TRY(c, hipEventSynchronize(c->seg_event[slot])); c->seg_busy[slot] = false; }
+    std::memcpy(c->h_segs[slot], c->pending.data(), c->pending.size() * sizeof(Segment));
+    const uint32_t n_segs = (uint32_t)c->pending.size();
+    const uint32_t T = c->cfg.max_tenants;
+    uint32_t launches = 0;
+
+    BatchArgs b{};
+    b.segs = c->d_segs[slot]; b.n_segs = n_segs; b.R = R; b.T = T; b.n_layer_slots = c->n_layer_slots;
+    b.first = c->pending[0]; b.row_src = c->d_row_src; b.elem_size = c->elem_size;
+    b.tenants = c->d_tenants; b.layers = c->d_layers;
+    b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
+    b.M = c->d_M; b.off = c->d_off; b.tiles = c->d_tiles; b.tile_cap = c->tile_cap; b.n_tiles = c->d_n_tiles;
+    b.overflow = c->d_overflow;
+    if (c->profiling) for (uint32_t i = 0; i < kProfSlots; ++i) c->prof_used[i] = false;
+#define TIMED(slot, call)                                                                   \
+    do {                                                                                    \
+        if (c->profiling) HIP_TRY(c, hipEventRecord(c->prof_events[2 * (slot)], s));        \
+        HIP_TRY(c, call); ++launches;                                                       \
+        if (c->profiling) { HIP_TRY(c, hipEventRecord(c->prof_events[2 * (slot) + 1], s)); c->prof_used[slot] = true; } \
+    } while (0)
+    TIMED(kProfBatcher, launch_batcher(b, s));
+
+    GatherArgs g{};
+    g.row_src = c->d_row_src; g.R = R; g.tenants = c->d_tenants; g.row_tenant = c->d_row_tenant;
+    g.perm = c->d_perm; g.off = c->d_off; g.T = T; g.act = c->d_act[0]; g.S = c->S; g.elem_size = c->elem_size;
+    TIMED(kProfGather, launch_gather(g, s));
+
+    for (uint32_t l = 0; l < c->n_layer_slots; ++l) {
+        const void* in = c->d_act[l & 1];
+        void* outb = c->d_act[(l + 1) & 1];
+        const uint64_t grid = tile_bound(c, l, R);
+        if (grid > 0) {
+            GemmArgs ga{};
+            ga.tiles = c->d_tiles + (size_t)l * c->tile_cap; ga.n_tiles = c->d_n_tiles; ga.layer = l;
+            ga.layers = c->d_layers; ga.off = c->d_off; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
+            ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad;
+            TIMED(kProfGemm + l, launch_gemm(ga, c->cfg.dtype, (uint32_t)std::min<uint64_t>(grid, c->tile_cap), s));
+        }
+        if (c->has_gap[l]) {
+            GapArgs pa{};
+            pa.layer = l; pa.R = R; pa.layers = c->d_layers; pa.tenants = c->d_tenants; pa.row_tenant = c->d_row_tenant;
+            pa.perm = c->d_perm; pa.off = c->d_off; pa.T = T; pa.act_in = in; pa.act_out = outb; pa.S = c->S;
+            pa.elem_size = c->elem_size;
+            TIMED(kProfGap + l, launch_gap(pa, s));
+        }
+    }
+
+    HeadArgs h{};
+    h.R = R; h.tenants = c->d_tenants; h.row_tenant = c->d_row_tenant; h.pos_of = c->d_pos_of; h.logits = c->d_logits;
+    h.C_pad = c->C_pad; h.labels = out->labels; h.probs = out->probs; h.logits_out = out->logits;
+    h.n_classes = out->n_classes; h.row_stride = out->row_stride;
+    TIMED(kProfHead, launch_head(h, s));
+#undef TIMED
+    c->prof_valid = c->profiling;
+
+    HIP_TRY(c, hipEventRecord(c->seg_event[slot], s));
+    c->seg_busy[slot] = true;
+    c->run_count++;
+    c->last_stream = s;
+    c->pending.clear();
+    c->pending_rows = 0;
+    c->last_run_rows = R; c->last_run_launches = launches;
+    if (n_rows) *n_rows = R;
+    return MT_OK;
+}
+
+mt_status mt_last_counts(mt_ctx* c, uint32_t* counts)
+{
+    if (!c || !counts) return MT_EINVAL;
+    if (c->host_only) return fail(c, MT_ESTATE, "host-only context");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    HIP_TRY(c, hipMemcpy(counts, c->d_M, (size_t)c->cfg.max_tenants * 4, hipMemcpyDeviceToHost));
+    uint32_t ovf = 0;
+    HIP_TRY(c, hipMemcpy(&ovf, c->d_overflow, 4, hipMemcpyDeviceToHost));
+    if (ovf) return fail(c, MT_EDEVICE, "a tile list overflowed its bound");
+    return MT_OK;
+}
+
+mt_status mt_set_profiling(mt_ctx* c, int enable)
+{
+    if (!c) return MT_EINVAL;
+    if (c->host_only) return fail(c, MT_ESTATE, "host-only context");
+    if (enable && c->prof_events.empty()) {
+        HIP_TRY(c, hipSetDevice(c->cfg.device));
+        c->prof_events.resize(2 * kProfSlots);
+        for (hipEvent_t& e : c->prof_events) HIP_TRY(c, hipEventCreate(&e));
+    }
+    c->profiling = enable != 0;
+    if (!enable) c->prof_valid = false;
+    return MT_OK;
+}
+
+mt_status mt_get_profile(mt_ctx* c, mt_profile* out)
+{
+    if (!c || !out) return MT_EINVAL;
+    std::memset(out, 0, sizeof *out);
+    if (!c->prof_valid) return fail(c, MT_ESTATE, "no profiled run to read");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+    auto ms = [&](uint32_t slot, float* dst) -> hipError_t {
+        *dst = 0.0f;
+        if (!c->prof_used[slot]) return hipSuccess;
+        return hipEventElapsedTime(dst, c->prof_events[2 * slot], c->prof_events[2 * slot + 1]);
+    };
+    HIP_TRY(c, ms(kProfBatcher, &out->batcher_ms));
+    HIP_TRY(c, ms(kProfGather, &out->gather_ms));
+    HIP_TRY(c, ms(kProfHead, &out->head_ms));
+    for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
+        HIP_TRY(c, ms(kProfGemm + l, &out->gemm_ms[l]));
+        HIP_TRY(c, ms(kProfGap + l, &out->gap_ms[l]));
+    }
+    HIP_TRY(c, hipEventElapsedTime(&out->total_ms, c->prof_events[2 * kProfBatcher], c->prof_events[2 * kProfHead + 1]));
+    return MT_OK;
+}
+
+mt_status mt_debug_poison(mt_ctx* c)
+{
+    if (!c) return MT_EINVAL;
+    if (c->host_only) return fail(c, MT_ESTATE, "host-only context");
+    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    HIP_TRY(c, hipDeviceSynchronize());
+    const size_t act_bytes = (size_t)c->cfg.max_requests * c->S * c->elem_size;
+    HIP_TRY(c, hipMemset(c->d_act[0], 0xFF, act_bytes));
+    HIP_TRY(c, hipMemset(c->d_act[1], 0xFF, act_bytes));
+    HIP_TRY(c, hipMemset(c->d_logits, 0xFF, (size_t)c->cfg.max_requests * c->C_pad * 4));
+    HIP_TRY(c, hipDeviceSynchronize());
+    return MT_OK;
+}
+
+mt_status mt_get_stats(const mt_ctx* c, mt_stats* out)
+{
+    if (!c || !out) return MT_EINVAL;
+    out->n_tenants = c->n_registered;
+    out->arena_used = c->arena_used;
+    out->arena_bytes = c->cfg.arena_bytes;
+    out->last_run_rows = c->last_run_rows;
+    out->last_run_launches = c->last_run_launches;
+    return MT_OK;
+}
+
+}  // extern "C"

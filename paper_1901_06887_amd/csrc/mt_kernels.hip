@@ -1,0 +1,490 @@
+// Device code of the multi-tenant worker runtime, written for gfx950 (CDNA4, wave64).
+//
+//   batcher_kernel  tenant segmentation of the pending requests (counts, offsets, stable
+//                   permutation) and the per-layer grouped-work tile lists, all on device
+//   gather_kernel   submitted rows -> tenant-contiguous, zero-padded activation rows
+//   gemm_kernel     one layer index for all tenants: grouped GEMM / implicit-GEMM 3x3
+//                   convolution on MFMA with fused bias + activation (+ bf16 rounding)
+//   gap_kernel      global average pooling rows
+//   head_kernel     softmax + argmax, written in submission order
+//
+// A DNN is a fixed sequence of layers applied in turn (paper, section 1.1); a worker
+// hosts many tenants' DNNs and multiplexes their requests (section 3).  The grouping
+// of all tenants' work for one layer index into one launch is this runtime's way of
+// doing that multiplexing on one GPU.
+#include "mt_internal.h"
+
+namespace mt {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t kBatchThreads = 1024;
+constexpr uint32_t kMaxTenantsPadded = 2048;
+constexpr uint32_t kHistEntries = 8192;
+constexpr uint32_t kSegsInLds = 64;
+
+__device__ __forceinline__ uint32_t ceil_div(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
+
+// Index of the segment that holds submission row r (segments are sorted by row_begin).
+__device__ __forceinline__ uint32_t find_segment(const Segment* segs, uint32_t n, uint32_t r)
+{
+    uint32_t lo = 0, hi = n;            // invariant: segs[lo].row_begin <= r
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (segs[mid].row_begin <= r) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Exclusive scan of data[0..n) in LDS by the whole workgroup (n <= kMaxTenantsPadded);
+// returns the total.  tmp must hold 17 words.
+__device__ uint32_t block_exclusive_scan(uint32_t* data, uint32_t n, uint32_t* tmp)
+{
+    const uint32_t tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const uint32_t ipt = ceil_div(n, kBatchThreads);
+    const uint32_t begin = tid * ipt, end = min(begin + ipt, n);
+    uint32_t s = 0;
+    for (uint32_t i = begin; i < end; ++i) s += data[i];
+    uint32_t incl = s;
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t v = __shfl_up(incl, d);
+        if (lane >= (uint32_t)d) incl += v;
+    }
+    if (lane == 63) tmp[w] = incl;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t run = 0;
+        for (uint32_t i = 0; i < kBatchThreads / 64; ++i) { uint32_t c = tmp[i]; tmp[i] = run; run += c; }
+        tmp[16] = run;
+    }
+    __syncthreads();
+    uint32_t run = tmp[w] + incl - s;
+    for (uint32_t i = begin; i < end; ++i) { uint32_t c = data[i]; data[i] = run; run += c; }
+    uint32_t total = tmp[16];
+    __syncthreads();
+    return total;
+}
+
+// Tenant segmentation and tile lists.  One workgroup; every step is deterministic:
+// rows of a tenant keep their arrival order (stable counting sort).  Equal tenant ids
+// inside a wavefront are found with one ballot per id bit, so a step costs the same
+// whatever the tenant mix is.
+__global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
+{
+    __shared__ uint32_t hist[kHistEntries];
+    __shared__ uint32_t Ml[kMaxTenantsPadded];
+    __shared__ uint32_t offl[kMaxTenantsPadded];
+    __shared__ uint32_t cnt[kMaxTenantsPadded];
+    __shared__ uint32_t tmp[17];
+    __shared__ Segment seg_l[kSegsInLds];
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const uint32_t T = a.T, R = a.R;
+    // the segment table sits in host memory: stage it in LDS when it is small
+    const Segment* segs = a.segs;
+    if (a.n_segs <= kSegsInLds) {
+        if (a.n_segs == 1) { if (tid == 0) seg_l[0] = a.first; }
+        else for (uint32_t i = tid; i < a.n_segs; i += kBatchThreads) seg_l[i] = a.segs[i];
+        segs = seg_l;
+    }
+    uint32_t Tp = 64, bits = 6;
+    while (Tp < T) { Tp <<= 1; ++bits; }
+    const uint32_t nw = min(kBatchThreads / 64, kHistEntries / Tp);
+    const uint32_t chunk = ceil_div(ceil_div(R, nw), 64) * 64;
+
+    for (uint32_t i = tid; i < nw * Tp; i += kBatchThreads) hist[i] = 0;
+    __syncthreads();
+
+    // pass 1: per-wave histograms and in-wave ranks
+    if (w < nw) {
+        const uint32_t begin = w * chunk, end = min(begin + chunk, R);
+        for (uint32_t base = begin; base < end; base += 64) {
+            const uint32_t r = base + lane;
+            int32_t t = -1;
+            if (r < end) {
+                const Segment sg = segs[find_segment(segs, a.n_segs, r)];
+                t = sg.ids ? sg.ids[r - sg.row_begin] : sg.tenant;
+                if (t < 0 || (uint32_t)t >= T || !a.tenants[t].registered) t = -1;
+                a.row_tenant[r] = t;
+                a.row_src[r] = (const uint8_t*)sg.src + (size_t)(r - sg.row_begin) * sg.row_stride * a.elem_size;
+            }
+            uint64_t peers = __ballot(t >= 0);
+            for (uint32_t b = 0; b < bits; ++b) {
+                const bool bit = (t >> b) & 1;
+                const uint64_t m = __ballot(bit);
+                peers &= bit ? m : ~m;
+            }
+            const bool ok = t >= 0;
+            const uint32_t leader = ok ? (uint32_t)__ffsll((unsigned long long)peers) - 1 : lane;
+            const uint32_t rank = __popcll(peers & ((1ull << lane) - 1));
+            uint32_t old = 0;
+            if (ok && lane == leader) {
+                old = hist[w * Tp + t];
+                hist[w * Tp + t] = old + __popcll(peers);
+            }
+            old = __shfl(old, leader);
+            if (ok) a.row_rank[r] = old + rank;
+        }
+    }
+    __syncthreads();
+
+    // pass 2: per-tenant totals, per-wave bases, tenant offsets
+    for (uint32_t t = tid; t < Tp; t += kBatchThreads) {
+        uint32_t s = 0;
+        for (uint32_t i = 0; i < nw; ++i) { uint32_t c = hist[i * Tp + t]; hist[i * Tp + t] = s; s += c; }
+        Ml[t] = s; offl[t] = s;
+    }
+    __syncthreads();
+    const uint32_t total = block_exclusive_scan(offl, Tp, tmp);
+    for (uint32_t t = tid; t < T; t += kBatchThreads) { a.M[t] = Ml[t]; a.off[t] = offl[t]; }
+    if (tid == 0) a.off[T] = total;
+
+    // pass 3: packed position of every row
+    for (uint32_t r = tid; r < R; r += kBatchThreads) {
+        const int32_t t = a.row_tenant[r];
+        int32_t pos = -1;
+        if (t >= 0) {
+            pos = (int32_t)(offl[t] + hist[(r / chunk) * Tp + t] + a.row_rank[r]);
+            a.perm[pos] = r;
+        }
+        a.pos_of[r] = pos;
+    }
+
+    // pass 4: tile list of every layer index
+    for (uint32_t l = 0; l < a.n_layer_slots; ++l) {
+        __syncthreads();
+        for (uint32_t t = tid; t < Tp; t += kBatchThreads) {
+            uint32_t c = 0;
+            if (t < T && Ml[t] > 0 && a.tenants[t].registered && a.tenants[t].n_layers > l) {
+                const LayerDev& L = a.layers[t * MT_MAX_LAYERS + l];
+                if (L.kind != MT_GAP) c = ceil_div(Ml[t] * L.rows_per_req, kBM) * ceil_div(L.N, kBN);
+            }
+            cnt[t] = c;
+        }
+        __syncthreads();
+        uint32_t n = block_exclusive_scan(cnt, Tp, tmp);
+        if (n > a.tile_cap) { if (tid == 0) *a.overflow = 1; n = a.tile_cap; }
+        if (tid == 0) a.n_tiles[l] = n;
+        Tile* out = a.tiles + (size_t)l * a.tile_cap;
+        for (uint32_t i = tid; i < n; i += kBatchThreads) {
+            uint32_t lo = 0, hi = Tp;           // last t with cnt[t] <= i
+            while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (cnt[mid] <= i) lo = mid; else hi = mid; }
+            const LayerDev& L = a.layers[lo * MT_MAX_LAYERS + l];
+            const uint32_t rows = Ml[lo] * L.rows_per_req;
+            const uint32_t mt_ = ceil_div(rows, kBM);
+            const uint32_t local = i - cnt[lo];
+            Tile tl;
+            tl.tenant = lo;
+            tl.m0 = (local % mt_) * kBM;
+            tl.rows = min((uint32_t)kBM, rows - tl.m0);
+            tl.n0 = (local / mt_) * kBN;
+            out[i] = tl;
+        }
+    }
+}
+
+// ---- gather: one workgroup per packed row -----------------------------------------------
+template <typename T>
+__device__ void gather_row(const GatherArgs& a, uint32_t p)
+{
+    const uint32_t r = a.perm[p];
+    const int32_t t = a.row_tenant[r];
+    const TenantDev td = a.tenants[t];
+    const T* src = (const T*)a.row_src[r];
+    T* dst = (T*)a.act + (size_t)p * a.S;
+    constexpr uint32_t EPC = 16 / sizeof(T);
+    if (td.in_cin == 0) {
+        const uint32_t n = td.in_len;
+        if (((uintptr_t)src & 15) == 0 && (n % EPC) == 0) {
+            const u32x4* s4 = (const u32x4*)src; u32x4* d4 = (u32x4*)dst;
+            for (uint32_t i = threadIdx.x; i < n / EPC; i += blockDim.x) d4[i] = s4[i];
+        } else {
+            for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) dst[i] = src[i];
+        }
+        for (uint32_t i = n + threadIdx.x; i < td.in_fill; i += blockDim.x) dst[i] = (T)0.0f;
+    } else {
+        // channel padding of an NHWC image whose first layer is a convolution
+        const uint32_t ci = td.in_cin, cp = td.in_cin_pad, npix = td.in_len / ci;
+        for (uint32_t i = threadIdx.x; i < npix * cp; i += blockDim.x) {
+            const uint32_t pix = i / cp, c = i % cp;
+            dst[i] = c < ci ? src[pix * ci + c] : (T)0.0f;
+        }
+        for (uint32_t i = npix * cp + threadIdx.x; i < td.in_fill; i += blockDim.x) dst[i] = (T)0.0f;
+    }
+}
+
+__global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
+{
+    const uint32_t p = blockIdx.x;
+    if (p >= a.off[a.T]) return;
+    if (a.elem_size == 2) gather_row<__bf16>(a, p); else gather_row<float>(a, p);
+}
+
+// ---- grouped GEMM -----------------------------------------------------------------------
+__device__ __forceinline__ float activate(float z, uint32_t act)
+{
+    if (act == MT_ACT_RELU) return fmaxf(z, 0.0f);
+    if (act == MT_ACT_GELU) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+    return z;
+}
+
+constexpr int kLdsRow = kRowBytes + 16;            // padded LDS row, bytes
+constexpr int kTileBytes = kBM * kLdsRow;          // one operand tile of one stage
+
+template <typename T> struct Mma;
+// bf16: one 16-byte chunk is a whole MFMA operand (8 consecutive k of one row).
+template <> struct Mma<__bf16> {
+    static __device__ __forceinline__ void run(f32x16& acc, const u32x4& a, const u32x4& b)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+    }
+};
+// fp32: a chunk holds 4 consecutive k; four 32x32x2 MFMAs consume it, the two lane halves
+// supplying the two k slots of each (the same k assignment on both operands).
+template <> struct Mma<float> {
+    static __device__ __forceinline__ void run(f32x16& acc, const u32x4& a, const u32x4& b)
+    {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a[e]), __builtin_bit_cast(float, b[e]), acc, 0, 0, 0);
+    }
+};
+
+// One workgroup = 4 waves in a 2x2 grid over a 128x128 tile; a wave owns 64x64 = 2x2 MFMA
+// blocks of 32x32.  K is consumed 128 bytes per row per step through two LDS stages.
+template <typename T>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lds[4 * kTileBytes];
+    constexpr uint32_t EPC = 16 / sizeof(T);          // elements per 16-byte chunk
+    constexpr uint32_t EPS = kRowBytes / sizeof(T);   // elements of K per step
+
+    const uint32_t tile_id = blockIdx.x;
+    if (tile_id >= a.n_tiles[a.layer]) return;
+    const Tile tl = a.tiles[tile_id];
+    const LayerDev L = a.layers[tl.tenant * MT_MAX_LAYERS + a.layer];
+    const uint32_t seg0 = a.off[tl.tenant];
+    const bool conv = L.kind == MT_CONV2D;
+
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t wm = wave >> 1, wn = wave & 1;
+    const uint32_t li = lane & 31, lh = lane >> 5;
+
+    // --- global -> register staging: thread owns chunk `lc` of rows lr + 32*i ---------------
+    const uint32_t lc = tid & 7, lr = tid >> 3;
+    const T* act_in = (const T*)a.act_in;
+    const T* W = (const T*)(a.arena + L.w_off);
+    const T* a_ptr[4]; bool a_ok[4]; int32_t a_oh[4], a_ow[4];
+    const T* b_ptr[4]; bool b_ok[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t row = lr + 32 * i;
+        const uint32_t m = tl.m0 + row;
+        a_ok[i] = row < tl.rows;
+        const uint32_t req = m / L.rows_per_req, pix = m % L.rows_per_req;
+        a_ptr[i] = act_in + (size_t)(seg0 + req) * a.S;
+        a_oh[i] = (int32_t)((pix / L.out_w) * L.stride) - 1;
+        a_ow[i] = (int32_t)((pix % L.out_w) * L.stride) - 1;
+        const uint32_t n = tl.n0 + row;
+        b_ok[i] = n < L.N;
+        b_ptr[i] = W + (size_t)n * L.K;
+    }
+    const uint32_t n_steps = L.K / EPS;
+
+    u32x4 ra[4], rb[4];
+    auto load_step = [&](uint32_t step) {
+        const uint32_t k = step * EPS + lc * EPC;
+        if (!conv) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ra[i] = a_ok[i] ? *(const u32x4*)(a_ptr[i] + k) : u32x4{0, 0, 0, 0};
+        } else {
+            const uint32_t tap = k / L.cin, c0 = k % L.cin;
+            const int32_t kh = (int32_t)(tap / 3), kw = (int32_t)(tap % 3);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int32_t ih = a_oh[i] + kh, iw = a_ow[i] + kw;
+                const bool ok = a_ok[i] && tap < 9 && ih >= 0 && ih < (int32_t)L.in_h && iw >= 0 && iw < (int32_t)L.in_w;
+                ra[i] = ok ? *(const u32x4*)(a_ptr[i] + ((size_t)(ih * (int32_t)L.in_w + iw) * L.cin + c0)) : u32x4{0, 0, 0, 0};
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rb[i] = b_ok[i] ? *(const u32x4*)(b_ptr[i] + k) : u32x4{0, 0, 0, 0};
+    };
+    auto store_step = [&](uint32_t stage) {
+        uint8_t* As = lds + stage * 2 * kTileBytes;
+        uint8_t* Bs = As + kTileBytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *(u32x4*)(As + (lr + 32 * i) * kLdsRow + lc * 16) = ra[i];
+            *(u32x4*)(Bs + (lr + 32 * i) * kLdsRow + lc * 16) = rb[i];
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // waves whose 64 rows lie wholly past the tile's valid rows skip the MFMAs
+    const bool wave_active = wm * 64 < tl.rows;
+    const bool mb1_active = wm * 64 + 32 < tl.rows;
+
+    load_step(0);
+    store_step(0);
+    __syncthreads();
+    for (uint32_t step = 0; step < n_steps; ++step) {
+        const uint32_t cur = step & 1;
+        if (step + 1 < n_steps) load_step(step + 1);
+        if (wave_active) {
+            const uint8_t* As = lds + cur * 2 * kTileBytes + (wm * 64 + li) * kLdsRow + lh * 16;
+            const uint8_t* Bs = lds + cur * 2 * kTileBytes + kTileBytes + (wn * 64 + li) * kLdsRow + lh * 16;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const u32x4 a0 = *(const u32x4*)(As + s * 32);
+                const u32x4 b0 = *(const u32x4*)(Bs + s * 32);
+                const u32x4 b1 = *(const u32x4*)(Bs + 32 * kLdsRow + s * 32);
+                Mma<T>::run(acc[0][0], a0, b0);
+                Mma<T>::run(acc[0][1], a0, b1);
+                if (mb1_active) {
+                    const u32x4 a1 = *(const u32x4*)(As + 32 * kLdsRow + s * 32);
+                    Mma<T>::run(acc[1][0], a1, b0);
+                    Mma<T>::run(acc[1][1], a1, b1);
+                }
+            }
+        }
+        if (step + 1 < n_steps) store_step(cur ^ 1);
+        __syncthreads();
+    }
+
+    // --- epilogue: bias, activation, rounding, store --------------------------------------
+    if (!wave_active) return;
+    const float* bias = (const float*)(a.arena + L.b_off);
+    T* act_out = (T*)a.act_out;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const uint32_t n = tl.n0 + wn * 64 + nb * 32 + li;
+        const bool n_ok = n < L.N;
+        const float bv = n_ok ? bias[n] : 0.0f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+                if (row >= tl.rows) continue;
+                const uint32_t m = tl.m0 + row;
+                const float z = acc[mb][nb][v] + bv;
+                if (L.is_last) {
+                    if (n_ok) a.logits[(size_t)(seg0 + m) * a.C_pad + n] = z;
+                } else if (n < L.out_fill || conv) {
+                    const uint32_t req = m / L.rows_per_req, pix = m % L.rows_per_req;
+                    if (n_ok || !conv)
+                        act_out[(size_t)(seg0 + req) * a.S + (size_t)pix * L.N + n] = n_ok ? (T)activate(z, L.act) : (T)0.0f;
+                }
+            }
+        }
+    }
+}
+
+// ---- global average pool: one workgroup per packed row ---------------------------------
+template <typename T>
+__device__ void gap_row(const GapArgs& a, const LayerDev& L, uint32_t p)
+{
+    const T* in = (const T*)a.act_in + (size_t)p * a.S;
+    T* out = (T*)a.act_out + (size_t)p * a.S;
+    const uint32_t C = L.cin, HW = L.in_h * L.in_w;
+    const float inv = 1.0f / (float)HW;
+    for (uint32_t c = threadIdx.x; c < L.out_fill; c += blockDim.x) {
+        float s = 0.0f;
+        if (c < C) for (uint32_t q = 0; q < HW; ++q) s += (float)in[(size_t)q * C + c];
+        out[c] = (T)(s * inv);
+    }
+}
+
+__global__ __launch_bounds__(128) void gap_kernel(GapArgs a)
+{
+    const uint32_t p = blockIdx.x;
+    if (p >= a.off[a.T]) return;
+    const int32_t t = a.row_tenant[a.perm[p]];
+    if (a.tenants[t].n_layers <= a.layer) return;
+    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    if (L.kind != MT_GAP) return;
+    if (a.elem_size == 2) gap_row<__bf16>(a, L, p); else gap_row<float>(a, L, p);
+}
+
+// ---- head: one wave per submitted row --------------------------------------------------
+__global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= a.R) return;
+    const int32_t pos = a.pos_of[r];
+    uint32_t C = 0;
+    int32_t label = -1;
+    float mx = -INFINITY, sum = 0.0f;
+    const float* z = nullptr;
+    if (pos >= 0) {
+        C = a.tenants[a.row_tenant[r]].n_classes;
+        z = a.logits + (size_t)pos * a.C_pad;
+        int32_t best = 0x7fffffff;
+        for (uint32_t c = lane; c < C; c += 64) {
+            const float v = z[c];
+            if (v > mx) { mx = v; best = (int32_t)c; }      // strided: first hit is the lowest index of this lane
+        }
+        for (int d = 32; d >= 1; d >>= 1) {
+            const float omx = __shfl_xor(mx, d);
+            const int32_t ob = __shfl_xor(best, d);
+            if (omx > mx || (omx == mx && ob < best)) { mx = omx; best = ob; }
+        }
+        label = best;
+        for (uint32_t c = lane; c < C; c += 64) sum += __expf(z[c] - mx);
+        for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d);
+    }
+    const float inv = pos >= 0 ? 1.0f / sum : 0.0f;
+    for (uint32_t c = lane; c < a.row_stride; c += 64) {
+        const bool in = c < C;
+        if (a.probs) a.probs[(size_t)r * a.row_stride + c] = in ? __expf(z[c] - mx) * inv : 0.0f;
+        if (a.logits_out) a.logits_out[(size_t)r * a.row_stride + c] = in ? z[c] : 0.0f;
+    }
+    if (lane == 0) {
+        a.labels[r] = label;
+        if (a.n_classes) a.n_classes[r] = (int32_t)C;
+    }
+}
+
+// ---- launchers ------------------------------------------------------------------------------
+hipError_t launch_batcher(const BatchArgs& a, hipStream_t s)
+{
+    hipLaunchKernelGGL(batcher_kernel, dim3(1), dim3(kBatchThreads), 0, s, a);
+    return hipGetLastError();
+}
+hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
+{
+    hipLaunchKernelGGL(gather_kernel, dim3(a.R), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+hipError_t launch_gemm(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)
+{
+    if (grid == 0) return hipSuccess;
+    if (dtype == MT_BF16) hipLaunchKernelGGL(gemm_kernel<__bf16>, dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(gemm_kernel<float>, dim3(grid), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+hipError_t launch_gap(const GapArgs& a, hipStream_t s)
+{
+    // grid covers every packed row; rows of other layer kinds return at once
+    hipLaunchKernelGGL(gap_kernel, dim3(a.R), dim3(128), 0, s, a);
+    return hipGetLastError();
+}
+hipError_t launch_head(const HeadArgs& a, hipStream_t s)
+{
+    hipLaunchKernelGGL(head_kernel, dim3((a.R + 3) / 4), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace mt

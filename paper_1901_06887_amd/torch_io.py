@@ -1,0 +1,78 @@
+"""Glue between torch device tensors and the C ABI: allocation of the caller-owned buffers
+and pointer passing.  No arithmetic happens here."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class Served:
+    labels: torch.Tensor      # int32 [R]
+    probs: torch.Tensor       # float32 [R, row_stride]
+    logits: torch.Tensor      # float32 [R, row_stride]
+    n_classes: torch.Tensor   # int32 [R]
+
+
+def specs_of(layers) -> list:
+    """mt_layer_spec list from objects with kind/act/in_features/out_features/in_h/in_w/stride."""
+    return [B.layer_spec(l.kind, l.act, l.in_features, l.out_features, l.in_h, l.in_w, l.stride) for l in layers]
+
+
+def context_for(tenants: Dict[int, object], dtype: str, max_requests: int, device: int = 0,
+                max_tenants: Optional[int] = None, arena_slack: float = 1.05) -> B.Context:
+    """A context sized for the given tenant models (objects with .layers/.weights/.biases)."""
+    es = 4 if dtype == "f32" else 2
+    width, classes, arena = 64, 1, 0
+    for m in tenants.values():
+        n = len(m.layers)
+        for i, l in enumerate(m.layers):
+            in_len = l.in_len()
+            if l.kind == B.MT_CONV2D:
+                in_len = l.in_h * l.in_w * ((l.in_features + 7) // 8 * 8)
+            width = max(width, in_len + 64, (l.out_len() + 64) if i < n - 1 else 0)
+            if m.weights[i] is not None:
+                k = l.in_features if l.kind == B.MT_FC else 9 * ((l.in_features + 7) // 8 * 8)
+                arena += (l.out_features * ((k + 63) // 64 * 64) * es + 255) // 256 * 256 + (l.out_features * 4 + 255) // 256 * 256
+        classes = max(classes, m.layers[-1].out_len())
+    T = max_tenants if max_tenants is not None else (max(tenants) + 1 if tenants else 1)
+    return B.Context(T, max_requests, width, classes, int(arena * arena_slack) + (1 << 20),
+                     B.MT_F32 if dtype == "f32" else B.MT_BF16, device)
+
+
+def register_tenants(ctx: B.Context, tenants: Dict[int, object]):
+    for t, m in tenants.items():
+        ctx.register_model(int(t), specs_of(m.layers), m.weights, m.biases)
+
+
+def to_device(x: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    return t.to(device)
+
+
+def alloc_outputs(n: int, row_stride: int, device="cuda:0") -> Served:
+    return Served(torch.empty(n, dtype=torch.int32, device=device),
+                  torch.empty((n, row_stride), dtype=torch.float32, device=device),
+                  torch.empty((n, row_stride), dtype=torch.float32, device=device),
+                  torch.empty(n, dtype=torch.int32, device=device))
+
+
+def serve(ctx: B.Context, tenant_ids: torch.Tensor, inputs: torch.Tensor, out: Optional[Served] = None,
+          stream: Optional[torch.cuda.Stream] = None) -> Served:
+    """mt_submit_batch + mt_run on the given (or current) stream; returns without synchronising."""
+    n = int(tenant_ids.numel())
+    assert tenant_ids.dtype == torch.int32 and tenant_ids.is_cuda and inputs.is_cuda and inputs.is_contiguous()
+    if out is None:
+        out = alloc_outputs(n, ctx.cfg.max_classes, inputs.device)
+    s = stream if stream is not None else torch.cuda.current_stream(inputs.device)
+    ctx.submit_batch(tenant_ids.data_ptr(), inputs.data_ptr(), n, inputs.shape[1])
+    ctx.run(s.cuda_stream, out.labels.data_ptr(), out.probs.data_ptr(), out.logits.data_ptr(),
+            out.n_classes.data_ptr(), out.labels.numel(), out.probs.shape[1])
+    return out

@@ -1,0 +1,95 @@
+"""Shared helpers of the GPU parity tests: run a workload through the C ABI (via the thin
+binding) and through the oracle, and compare to the stated bar:
+
+  * relative Frobenius error <= 1e-3 per output tensor (each tenant's logits and probs
+    matrices, and the whole-batch matrices),
+  * labels bit-exact wherever the oracle's top-2 logit margin exceeds 1e-2; elsewhere the
+    label must be one of the oracle's two best classes.
+"""
+import numpy as np
+import torch
+
+import oracle
+import paper_1901_06887_amd as mt
+from paper_1901_06887_amd import torch_io
+
+REL_FRO_TOL = 1e-3
+MARGIN = 1e-2
+
+
+def make_context(w, max_requests=None, max_tenants=None):
+    ctx = mt.context_for(w.tenants, w.dtype, max_requests or max(1, w.n_requests), max_tenants=max_tenants)
+    mt.register_tenants(ctx, w.tenants)
+    return ctx
+
+
+def gpu_run(ctx, w, ids=None, inputs=None, poison=False):
+    ids = w.tenant_ids if ids is None else ids
+    inputs = w.inputs if inputs is None else inputs
+    d_ids = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).cuda()
+    d_x = torch_io.to_device(inputs, w.dtype)
+    if poison:
+        ctx.debug_poison()
+    out = mt.serve(ctx, d_ids, d_x)
+    torch.cuda.synchronize()
+    return (out.logits.cpu().numpy().astype(np.float64), out.probs.cpu().numpy().astype(np.float64),
+            out.labels.cpu().numpy(), out.n_classes.cpu().numpy())
+
+
+def rel_fro(g, o):
+    d = np.linalg.norm(g - o)
+    n = np.linalg.norm(o)
+    return d / n if n > 0 else d
+
+
+def compare(w, gpu, orc, rows=None, what=""):
+    """gpu/orc = (logits, probs, labels, n_classes) over the same rows (all, or `rows`)."""
+    g_lg, g_pr, g_lb, g_nc = gpu
+    o_lg, o_pr, o_lb, o_nc = orc
+    ids = w.tenant_ids if rows is None else w.tenant_ids[rows]
+    assert np.array_equal(g_nc, o_nc), what
+    C = o_lg.shape[1]
+    assert np.all(g_lg[:, C:] == 0) and np.all(g_pr[:, C:] == 0)
+    g_lg, g_pr = g_lg[:, :C], g_pr[:, :C]
+    assert np.all(np.isfinite(g_lg)) and np.all(np.isfinite(g_pr)), what
+    worst = 0.0
+    for t in np.unique(ids):
+        sel = ids == t
+        for g, o in ((g_lg[sel], o_lg[sel]), (g_pr[sel], o_pr[sel])):
+            e = rel_fro(g, o)
+            worst = max(worst, e)
+            assert e <= REL_FRO_TOL, "%s tenant %d rel fro %.3e" % (what, t, e)
+    assert rel_fro(g_lg, o_lg) <= REL_FRO_TOL and rel_fro(g_pr, o_pr) <= REL_FRO_TOL, what
+    # labels
+    srt = np.sort(o_lg + np.where(np.arange(C)[None, :] < o_nc[:, None], 0.0, -np.inf), axis=1)
+    margin = srt[:, -1] - srt[:, -2] if C > 1 else np.full(len(ids), np.inf)
+    clear = margin > MARGIN
+    assert np.array_equal(g_lb[clear], o_lb[clear]), "%s: %d label mismatches on clear-margin rows" % (
+        what, int(np.sum(g_lb[clear] != o_lb[clear])))
+    for i in np.nonzero(~clear)[0]:
+        top2 = np.argsort(-o_lg[i, :o_nc[i]], kind="stable")[:2]
+        assert g_lb[i] in top2, what
+    assert np.allclose(g_pr.sum(axis=1), 1.0, atol=1e-5), what
+    return worst
+
+
+def oracle_rows(w, rows=None, threads=16):
+    models = oracle.models_from_workload(w)
+    ids = w.tenant_ids if rows is None else w.tenant_ids[rows]
+    x = w.inputs if rows is None else w.inputs[rows]
+    lg, pr, lb, nc, _ = oracle.run_batch(models, ids, x.astype(np.float64), threads=threads)
+    return lg, pr, lb, nc
+
+
+def sample_rows(w, ctx_counts, n_random, bm=128, seed=0):
+    """Rows to check one by one at full size: for every tenant the first and last rows of its
+    segment and the rows around every 128-row tile boundary, plus a random sample."""
+    rng = np.random.default_rng(seed)
+    pick = set(rng.choice(w.n_requests, size=min(n_random, w.n_requests), replace=False).tolist())
+    for t in np.unique(w.tenant_ids):
+        idx = np.nonzero(w.tenant_ids == t)[0]          # arrival order == order inside the segment
+        edges = {0, len(idx) - 1}
+        for b in range(bm, len(idx), bm):
+            edges |= {b - 1, b}
+        pick |= {int(idx[e]) for e in edges if 0 <= e < len(idx)}
+    return np.array(sorted(pick), dtype=np.int64)

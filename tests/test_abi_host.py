@@ -1,0 +1,157 @@
+"""Host logic of the C ABI that needs no GPU: the library loads, exports every declared
+symbol, and a host-only context validates models, accounts for arena space and returns
+error codes (never aborts).  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1901_06887_amd as mt
+from paper_1901_06887_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def host_ctx(dtype=B.MT_BF16, arena=1 << 22, max_width=4096, max_classes=100, max_requests=1024, max_tenants=16):
+    return B.Context(max_tenants, max_requests, max_width, max_classes, arena, dtype, device=-1)
+
+
+def fc(k, n, act=B.MT_ACT_NONE):
+    return B.layer_spec(B.MT_FC, act, k, n)
+
+
+def zeros_for(specs, dtype=B.MT_BF16):
+    ws, bs = [], []
+    for s in specs:
+        if s.kind == B.MT_FC:
+            ws.append(np.zeros((s.out_features, s.in_features), dtype=np.uint16 if dtype == B.MT_BF16 else np.float32))
+            bs.append(np.zeros(s.out_features, dtype=np.float32))
+        elif s.kind == B.MT_CONV2D:
+            ws.append(np.zeros((s.out_features, s.in_features, 3, 3), dtype=np.uint16 if dtype == B.MT_BF16 else np.float32))
+            bs.append(np.zeros(s.out_features, dtype=np.float32))
+        else:
+            ws.append(None); bs.append(None)
+    return ws, bs
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "mt.h")).read()
+    names = set(re.findall(r"\b(mt_[a-z_]+)\s*\(", header))
+    assert {"mt_create", "mt_destroy", "mt_register_model", "mt_submit", "mt_submit_batch", "mt_run"} <= names
+    lib = B.load_library()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert "gfx950" in mt.version()
+
+
+def test_struct_layouts_match_header_sizes():
+    assert ctypes.sizeof(B.mt_layer_spec) == 40
+    assert ctypes.sizeof(B.mt_config) == 32
+    assert ctypes.sizeof(B.mt_outputs) == 40
+
+
+def test_create_rejects_bad_config():
+    for kw in (dict(max_tenants=0), dict(max_requests=0), dict(max_width=0), dict(max_classes=0), dict(arena=0),
+               dict(max_tenants=5000), dict(dtype=7)):
+        with pytest.raises(B.MtError) as e:
+            host_ctx(**kw)
+        assert e.value.status == 1
+
+
+def test_register_validates_the_closed_layer_set():
+    c = host_ctx()
+    good = [fc(64, 128, B.MT_ACT_RELU), fc(128, 10)]
+    c.register_model(0, good, *zeros_for(good))
+    cases = [
+        ([fc(64, 128, B.MT_ACT_RELU), fc(100, 10)], 5),                         # dims do not chain
+        ([B.layer_spec(9, 0, 64, 10)], 5),                                       # unknown kind
+        ([fc(64, 10, 7)], 5),                                                    # unknown activation
+        ([fc(64, 10, B.MT_ACT_RELU)], 5),                                        # activation on the logits layer
+        ([fc(64, 128)] * 0, 5),                                                  # empty
+        ([fc(64, 64, B.MT_ACT_RELU)] * 8 + [fc(64, 10)], 5),                     # too deep
+        ([fc(64, 500)], 5),                                                      # more classes than max_classes
+        ([fc(8192, 10)], 5),                                                     # wider than max_width
+        ([B.layer_spec(B.MT_CONV2D, B.MT_ACT_RELU, 3, 8, 8, 8, 3), fc(8 * 9, 10)], 5),   # stride 3
+        ([B.layer_spec(B.MT_CONV2D, B.MT_ACT_RELU, 3, 6, 8, 8, 1), fc(6 * 64, 10)], 5),  # C_out not multiple of 8
+    ]
+    for specs, status in cases:
+        with pytest.raises(B.MtError) as e:
+            ws, bs = zeros_for(specs)
+            c.register_model(1, specs, ws, bs)
+        assert e.value.status == status, (specs, str(e.value))
+    assert c.stats()["n_tenants"] == 1
+    with pytest.raises(B.MtError) as e:
+        c.register_model(0, good, *zeros_for(good))
+    assert e.value.status == 4                                                   # MT_EEXIST
+    with pytest.raises(B.MtError) as e:
+        c.register_model(99, good, *zeros_for(good))
+    assert e.value.status == 1
+
+
+def test_cnn_chain_is_accepted():
+    c = host_ctx(max_width=32 * 32 * 32, arena=1 << 22)
+    specs = [B.layer_spec(B.MT_CONV2D, B.MT_ACT_RELU, 3, 32, 32, 32, 1),
+             B.layer_spec(B.MT_CONV2D, B.MT_ACT_RELU, 32, 64, 32, 32, 2),
+             B.layer_spec(B.MT_CONV2D, B.MT_ACT_RELU, 64, 128, 16, 16, 2),
+             B.layer_spec(B.MT_GAP, B.MT_ACT_NONE, 128, 128, 8, 8),
+             fc(128, 10)]
+    c.register_model(3, specs, *zeros_for(specs))
+    # packed sizes: K padded to 64 elements per row (conv1: 9*8=72 -> 128), 256-byte aligned slices
+    exp = sum((n * k * 2 + 255) // 256 * 256 + (n * 4 + 255) // 256 * 256
+              for n, k in ((32, 128), (64, 320), (128, 576), (10, 128)))
+    assert c.stats()["arena_used"] == exp
+
+
+def test_arena_accounting_exhaustion_and_reuse():
+    c = host_ctx(arena=300_000)
+    specs = [fc(64, 512, B.MT_ACT_RELU), fc(512, 10)]            # 512*64*2 + 2048 + 10*512*2 + 256 = 78,080
+    per = 512 * 64 * 2 + 512 * 4 + 10 * 512 * 2 + 256
+    for t in range(3):
+        c.register_model(t, specs, *zeros_for(specs))
+    assert c.stats()["arena_used"] == 3 * per
+    with pytest.raises(B.MtError) as e:
+        c.register_model(3, specs, *zeros_for(specs))
+    assert e.value.status == 2                                   # MT_ENOMEM, nothing leaked
+    assert c.stats()["arena_used"] == 3 * per and c.stats()["n_tenants"] == 3
+    c.unregister_model(1)
+    assert c.stats()["arena_used"] == 2 * per
+    c.register_model(3, specs, *zeros_for(specs))                # the freed slice is reused
+    assert c.stats()["arena_used"] == 3 * per
+    for t in (0, 2, 3):
+        c.unregister_model(t)
+    assert c.stats()["arena_used"] == 0
+    with pytest.raises(B.MtError) as e:
+        c.unregister_model(0)
+    assert e.value.status == 3
+
+
+def test_submit_errors_and_host_only_run():
+    c = host_ctx(max_requests=8)
+    specs = [fc(64, 10)]
+    c.register_model(2, specs, *zeros_for(specs))
+    with pytest.raises(B.MtError) as e:
+        c.submit(5, 0x1000, 1)
+    assert e.value.status == 3                                   # unknown tenant
+    with pytest.raises(B.MtError) as e:
+        c.submit(2, 0, 1)
+    assert e.value.status == 1                                   # null inputs
+    assert c.submit(2, 0x1000, 5) == 0
+    assert c.submit(2, 0x9000, 3) == 5
+    with pytest.raises(B.MtError) as e:
+        c.submit(2, 0x1000, 1)
+    assert e.value.status == 6                                   # MT_EFULL
+    with pytest.raises(B.MtError) as e:
+        c.unregister_model(2)
+    assert e.value.status == 7                                   # pending requests
+    with pytest.raises(B.MtError) as e:
+        c.run(0, 0x1000, 0, 0, 0, 8, 10)
+    assert e.value.status == 7                                   # host-only context cannot run
+
+
+def test_bf16_weights_must_be_representable():
+    c = host_ctx()
+    specs = [fc(64, 10)]
+    with pytest.raises(ValueError):
+        c.register_model(0, specs, [np.full((10, 64), 0.1, dtype=np.float32)], [None])

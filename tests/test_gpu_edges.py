@@ -1,0 +1,142 @@
+"""GPU edge cases of the hot path: empty runs, tenants without traffic, rejected ids, the
+per-tenant submit call, determinism, statelessness (a request's answer does not depend on
+what shares its batch; paper section 1.1), full-capacity runs and reuse of a context."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1901_06887_amd as mt
+import workloads as wl
+from gpu_common import compare, gpu_run, make_context, oracle_rows
+from paper_1901_06887_amd import torch_io
+
+pytestmark = pytest.mark.gpu
+
+
+def small():
+    return wl.c2(n_tenants=6, n_requests=300, dims=(100, 192, 136, 10))
+
+
+def test_empty_run_serves_nothing():
+    w = small()
+    ctx = make_context(w)
+    out = torch_io.alloc_outputs(4, ctx.cfg.max_classes)
+    n = ctx.run(torch.cuda.current_stream().cuda_stream, out.labels.data_ptr(), out.probs.data_ptr(),
+                out.logits.data_ptr(), out.n_classes.data_ptr(), 4, ctx.cfg.max_classes)
+    assert n == 0 and ctx.stats()["last_run_rows"] == 0
+    ctx.close()
+
+
+def test_tenants_without_traffic_and_single_rows():
+    w = small()
+    ids = np.where(w.tenant_ids == 3, 1, w.tenant_ids).astype(np.int32)    # tenant 3 gets nothing
+    ids[:] = np.where(ids == 5, 0, ids)
+    ids[17] = 5                                                             # tenant 5 gets exactly one row
+    w.tenant_ids = ids
+    ctx = make_context(w)
+    gpu = gpu_run(ctx, w, poison=True)
+    counts = ctx.last_counts()
+    assert counts[3] == 0 and counts[5] == 1
+    compare(w, gpu, oracle_rows(w), what="sparse-traffic")
+    ctx.close()
+
+
+def test_unknown_tenant_ids_are_rejected_on_device():
+    w = small()
+    ctx = make_context(w, max_tenants=10)          # ids 6..9 exist but have no model
+    ids = w.tenant_ids.copy()
+    bad = np.array([0, 5, 77, 150, 299])
+    ids[bad] = [7, -1, 10, 1 << 20, 9]
+    lg, pr, lb, nc = gpu_run(ctx, w, ids=ids, poison=True)
+    assert np.all(lb[bad] == -1) and np.all(nc[bad] == 0)
+    assert np.all(lg[bad] == 0) and np.all(pr[bad] == 0)
+    good = np.setdiff1d(np.arange(w.n_requests), bad)
+    w2 = wl.Workload(w.name, w.dtype, w.tenants, ids[good], w.inputs[good])
+    compare(w2, (lg[good], pr[good], lb[good], nc[good]), oracle_rows(w2), what="rejected-ids")
+    assert ctx.last_counts().sum() == len(good)
+    ctx.close()
+
+
+def test_per_tenant_submit_matches_batch_submit():
+    w = small()
+    ctx = make_context(w)
+    ref = gpu_run(ctx, w)
+    d_x = torch_io.to_device(w.inputs, w.dtype)
+    # arrival order is kept: every maximal run of one tenant becomes one mt_submit call
+    ids = w.tenant_ids
+    starts = np.flatnonzero(np.r_[True, ids[1:] != ids[:-1]])
+    ends = np.r_[starts[1:], len(ids)]
+    es = d_x.element_size()
+    for s, e in zip(starts, ends):
+        first = ctx.submit(int(ids[s]), d_x.data_ptr() + int(s) * d_x.shape[1] * es, int(e - s))
+        assert first == s
+    out = torch_io.alloc_outputs(w.n_requests, ctx.cfg.max_classes)
+    n = ctx.run(torch.cuda.current_stream().cuda_stream, out.labels.data_ptr(), out.probs.data_ptr(),
+                out.logits.data_ptr(), out.n_classes.data_ptr(), w.n_requests, ctx.cfg.max_classes)
+    torch.cuda.synchronize()
+    assert n == w.n_requests
+    assert np.array_equal(out.logits.cpu().numpy().astype(np.float64), ref[0])
+    assert np.array_equal(out.labels.cpu().numpy(), ref[2])
+    ctx.close()
+
+
+def test_runs_are_bit_reproducible_and_context_is_reusable():
+    w = wl.c3(n_tenants=10, n_requests=700, in_dim=128, widths=(64, 128, 256), classes=100)
+    ctx = make_context(w)
+    a = gpu_run(ctx, w)
+    b = gpu_run(ctx, w, poison=True)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    # a different, smaller batch on the same context, then the first one again
+    half = w.n_requests // 3
+    w2 = wl.Workload(w.name, w.dtype, w.tenants, w.tenant_ids[:half][::-1].copy(), w.inputs[:half][::-1].copy())
+    compare(w2, gpu_run(ctx, w2), oracle_rows(w2), what="second-batch")
+    c = gpu_run(ctx, w)
+    assert np.array_equal(a[0], c[0]) and np.array_equal(a[2], c[2])
+    ctx.close()
+
+
+def test_answers_do_not_depend_on_the_batch():
+    w = small()
+    ctx = make_context(w)
+    full = gpu_run(ctx, w)
+    for i in (0, 123, 299):
+        one = gpu_run(ctx, w, ids=w.tenant_ids[i:i + 1], inputs=w.inputs[i:i + 1])
+        assert np.array_equal(one[0][0], full[0][i]) and one[2][0] == full[2][i]
+    # arrival order shuffled: same per-request answers
+    p = np.random.default_rng(3).permutation(w.n_requests)
+    sh = gpu_run(ctx, w, ids=w.tenant_ids[p], inputs=w.inputs[p])
+    assert np.array_equal(sh[0], full[0][p]) and np.array_equal(sh[2], full[2][p])
+    ctx.close()
+
+
+def test_full_capacity_and_capacity_errors():
+    w = small()
+    ctx = make_context(w, max_requests=w.n_requests)          # exactly full
+    gpu = gpu_run(ctx, w)
+    compare(w, gpu, oracle_rows(w), what="full-capacity")
+    d_ids = torch.from_numpy(w.tenant_ids).cuda()
+    d_x = torch_io.to_device(w.inputs, w.dtype)
+    ctx.submit_batch(d_ids.data_ptr(), d_x.data_ptr(), w.n_requests, d_x.shape[1])
+    with pytest.raises(mt.MtError) as e:
+        ctx.submit_batch(d_ids.data_ptr(), d_x.data_ptr(), 1, d_x.shape[1])
+    assert e.value.status == 6
+    out = torch_io.alloc_outputs(10, ctx.cfg.max_classes)
+    with pytest.raises(mt.MtError) as e:                       # outputs too small: nothing is launched
+        ctx.run(0, out.labels.data_ptr(), out.probs.data_ptr(), out.logits.data_ptr(), out.n_classes.data_ptr(),
+                10, ctx.cfg.max_classes)
+    assert e.value.status == 1
+    ctx.close()
+
+
+def test_unregister_then_serve_remaining_tenants():
+    w = small()
+    ctx = make_context(w)
+    ctx.unregister_model(2)
+    lg, pr, lb, nc = gpu_run(ctx, w)
+    gone = w.tenant_ids == 2
+    assert np.all(lb[gone] == -1)
+    keep = ~gone
+    w2 = wl.Workload(w.name, w.dtype, {t: m for t, m in w.tenants.items() if t != 2}, w.tenant_ids[keep], w.inputs[keep])
+    compare(w2, (lg[keep], pr[keep], lb[keep], nc[keep]), oracle_rows(w2), what="after-unregister")
+    ctx.close()

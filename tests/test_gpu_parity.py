@@ -1,0 +1,111 @@
+"""GPU parity: the HIP path behind the C ABI against the fp64 oracle, element by element on
+the same seeded inputs.  Reduced cases span several 128x128 tiles and ragged tails; the
+full-size cases run in the launch configuration the benchmark times and are checked on
+rows the oracle evaluates one by one (all rows where that takes seconds)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_common import compare, gpu_run, make_context, oracle_rows, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def run_and_compare(w, what, poison=True):
+    ctx = make_context(w)
+    gpu = gpu_run(ctx, w, poison=poison)
+    counts = ctx.last_counts()
+    exp = np.bincount(w.tenant_ids, minlength=len(counts))
+    assert np.array_equal(counts, exp), what
+    worst = compare(w, gpu, oracle_rows(w), what=what)
+    print("%s: worst per-tensor rel fro %.2e" % (what, worst), flush=True)
+    ctx.close()
+
+
+# ---- reduced cases (seconds on the oracle, several tiles, ragged tails) --------------------
+def test_c1_full_fp32():
+    run_and_compare(wl.c1(), "c1")
+
+
+def test_c1_fp32_is_tight():
+    w = wl.c1()
+    ctx = make_context(w)
+    lg, pr, lb, _ = gpu_run(ctx, w)
+    o = oracle_rows(w)
+    assert np.linalg.norm(lg[:, :10] - o[0]) / np.linalg.norm(o[0]) < 2e-6   # true fp32 arithmetic, not bf16
+    ctx.close()
+
+
+def test_c2_reduced_skewed_batches():
+    run_and_compare(wl.c2(n_tenants=12, n_requests=900, dims=(784, 320, 272, 10)), "c2-reduced")
+
+
+def test_c3_reduced_heterogeneous_depths():
+    w = wl.c3(n_tenants=24, n_requests=1200, in_dim=200, widths=(96, 160, 288), classes=100)
+    assert len({len(m.layers) for m in w.tenants.values()}) >= 4
+    run_and_compare(w, "c3-reduced")
+
+
+def test_c4_reduced_cnn():
+    run_and_compare(wl.c4(n_tenants=3, n_requests=24), "c4-reduced")
+
+
+def test_c4_small_images_stride_and_ragged_tiles():
+    run_and_compare(wl.c4(n_tenants=2, n_requests=7, hw=8, chans=(3, 16, 24, 40), classes=5), "c4-small")
+
+
+def test_c5_reduced_gelu_wide_head():
+    run_and_compare(wl.c5(n_tenants=2, n_requests=520, dims=(512, 384, 512, 256, 1000)), "c5-reduced")
+
+
+def test_fp32_cnn_and_gelu():
+    w = wl.c4(n_tenants=2, n_requests=6, hw=8, chans=(3, 8, 16, 16), classes=4)
+    w.dtype = "f32"
+    run_and_compare(w, "cnn-fp32")
+
+
+# ---- full-size configurations ---------------------------------------------------------------
+def test_c2_full():
+    run_and_compare(wl.c2(), "c2")
+
+
+def test_c3_full_sampled():
+    w = wl.c3()
+    ctx = make_context(w)
+    gpu = gpu_run(ctx, w, poison=True)
+    counts = ctx.last_counts()
+    assert np.array_equal(counts, np.bincount(w.tenant_ids, minlength=len(counts)))
+    rows = sample_rows(w, counts, n_random=2048)
+    worst = compare(w, tuple(a[rows] for a in gpu), oracle_rows(w, rows), rows=rows, what="c3")
+    print("c3: %d rows checked, worst rel fro %.2e" % (len(rows), worst), flush=True)
+    ctx.close()
+
+
+def test_c4_full_sampled():
+    w = wl.c4()
+    ctx = make_context(w)
+    gpu = gpu_run(ctx, w, poison=True)
+    rows = sample_rows(w, None, n_random=256)
+    worst = compare(w, tuple(a[rows] for a in gpu), oracle_rows(w, rows), rows=rows, what="c4")
+    print("c4: %d rows checked, worst rel fro %.2e" % (len(rows), worst), flush=True)
+    ctx.close()
+
+
+def test_c5_full_sampled():
+    w = wl.c5()
+    ctx = make_context(w)
+    gpu = gpu_run(ctx, w, poison=True)
+    counts = ctx.last_counts()
+    assert np.array_equal(counts, np.bincount(w.tenant_ids, minlength=len(counts)))
+    # every tenant's segment edges and every 128-row tile boundary, plus a random sample;
+    # the oracle needs ~54 M fp64 MACs per row, so the sample is bounded
+    rows = sample_rows(w, counts, n_random=512)
+    worst = compare(w, tuple(a[rows] for a in gpu), oracle_rows(w, rows), rows=rows, what="c5")
+    print("c5: %d rows checked, worst rel fro %.2e" % (len(rows), worst), flush=True)
+    # properties that hold at any size, on all rows
+    lg, pr, lb, nc = gpu
+    assert np.all(nc == 1000) and np.all(np.isfinite(lg))
+    assert np.allclose(pr.sum(axis=1), 1.0, atol=1e-5)
+    assert np.array_equal(lb, np.argmax(lg, axis=1))
+    ctx.close()
