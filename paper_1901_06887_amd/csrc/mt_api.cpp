@@ -213,7 +213,9 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
             d.rows_per_req = oh * ow;
             d.K = round_up(9 * d.cin, eps); d.N = s.out_features;
             d.out_len = oh * ow * s.out_features;
-            if (d.out_len % kWidthAlign) return fail(c, MT_EUNSUPPORTED, "layer %u: conv output size %u is not a multiple of %d elements", l, d.out_len, kWidthAlign);
+            // a following FC layer reads its fan-in up to the K padding: the conv epilogue writes no such tail
+            if (l + 1 < n_layers && specs[l + 1].kind == MT_FC && d.out_len % kWidthAlign)
+                return fail(c, MT_EUNSUPPORTED, "layer %u: a conv output of %u values feeding an FC layer must be a multiple of %d", l, d.out_len, kWidthAlign);
             hl.w_bytes = (uint64_t)d.N * d.K * es; hl.b_bytes = (uint64_t)d.N * 4;
         } else if (s.kind == MT_GAP) {
             if (s.in_features == 0 || s.in_h == 0 || s.in_w == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized pool", l);
