@@ -106,14 +106,18 @@ def main():
         prof.append(ctx.get_profile())
     ctx.set_profiling(False)
     n_slots = mt.MT_MAX_LAYERS
-    gemm_ms = [float(np.mean([p["gemm_ms"][l] for p in prof])) for l in range(n_slots)]
+    fc_ms = [float(np.mean([p["fc_ms"][l] for p in prof])) for l in range(n_slots)]
+    conv_ms = [float(np.mean([p["conv_ms"][l] for p in prof])) for l in range(n_slots)]
     flops, bytes_ = gemm_launch_costs(w, es)
-    launches = [l for l in range(n_slots) if gemm_ms[l] > 0 and l in bytes_]
-    avg_dur_s = sum(gemm_ms[l] for l in launches) / len(launches) * 1e-3
+    # the dominant kernel: the grouped FC kernel, or the grouped conv kernel for the CNN mix
+    dom_ms, dom_name = (fc_ms, "fc_kernel") if sum(fc_ms) >= sum(conv_ms) else (conv_ms, "conv_kernel")
+    other_ms = conv_ms if dom_ms is fc_ms else fc_ms
+    launches = [l for l in range(n_slots) if dom_ms[l] > 0 and other_ms[l] == 0 and l in bytes_]
+    avg_dur_s = sum(dom_ms[l] for l in launches) / len(launches) * 1e-3
     avg_bytes = sum(bytes_[l] for l in launches) / len(launches)
     avg_flops = sum(flops[l] for l in launches) / len(launches)
     cost = wl.algorithmic_cost(w)
-    intensity = cost["flops"] / cost["bytes"]
+    intensity = avg_flops / avg_bytes
     if w.dtype == "bf16" and intensity > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
         achieved = avg_flops / avg_dur_s / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -122,13 +126,14 @@ def main():
         achieved = avg_bytes / avg_dur_s / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": None}
-    roofline.update({"kernel": "gemm_kernel<%s>" % ("bf16" if es == 2 else "float"),
+    roofline.update({"kernel": "%s<%s>" % (dom_name, "bf16" if es == 2 else "float"),
                      "launches_per_step": len(launches),
                      "avg_launch_us": avg_dur_s * 1e6,
                      "algorithmic_bytes_per_launch": avg_bytes, "algorithmic_flops_per_launch": avg_flops})
     kernels_us = {"batcher": float(np.mean([p["batcher_ms"] for p in prof])) * 1e3,
                   "gather": float(np.mean([p["gather_ms"] for p in prof])) * 1e3,
-                  "gemm_by_layer": [g * 1e3 for g in gemm_ms if g > 0],
+                  "fc_by_layer": [g * 1e3 for g in fc_ms if g > 0],
+                  "conv_by_layer": [g * 1e3 for g in conv_ms if g > 0],
                   "gap": float(np.sum([np.mean([p["gap_ms"][l] for p in prof]) for l in range(n_slots)])) * 1e3,
                   "head": float(np.mean([p["head_ms"] for p in prof])) * 1e3,
                   "device_total": float(np.mean([p["total_ms"] for p in prof])) * 1e3}
@@ -139,14 +144,20 @@ def main():
         threads = min(16, os.cpu_count() or 1)
         models = oracle.models_from_workload(w)
         macs_per_row = np.array([models[int(t)].macs_per_request() for t in w.tenant_ids], dtype=np.float64)
-        # ~0.45 GMAC/s per thread for the plain fp64 loop nests; bounded sample of arrival-ordered rows
-        budget = args.cpu_seconds * 0.45e9 * threads
+        # bounded sample: arrival-ordered prefix of the batch worth ~cpu_seconds at ~1.5 GMAC/s per thread
+        budget = args.cpu_seconds * 1.5e9 * threads
         n_sample = int(min(R, max(threads, np.searchsorted(np.cumsum(macs_per_row), budget))))
-        t0 = time.perf_counter()
-        oracle.run_batch(models, w.tenant_ids[:n_sample], w.inputs[:n_sample].astype(np.float64), threads=threads)
-        cdt = time.perf_counter() - t0
-        cpu = {"value": n_sample / cdt, "unit": "inferences/sec", "cores": threads, "kind": "oracle",
-               "sample": "first %d of %d requests of %s in arrival order, fp64 loop nests, %.1f s" % (n_sample, R, w.name, cdt)}
+        x64 = w.inputs[:n_sample].astype(np.float64)
+        reps, t0 = 0, time.perf_counter()
+        while True:                       # a batch the oracle finishes in under a second is repeated for a stable figure
+            oracle.run_batch(models, w.tenant_ids[:n_sample], x64, threads=threads)
+            reps += 1
+            cdt = time.perf_counter() - t0
+            if cdt >= min(10.0, args.cpu_seconds) or reps >= 200:
+                break
+        cpu = {"value": n_sample * reps / cdt, "unit": "inferences/sec", "cores": threads, "kind": "oracle",
+               "sample": "first %d of %d requests of %s in arrival order, %d pass(es), fp64 loop nests, %.1f s" % (
+                   n_sample, R, w.name, reps, cdt)}
 
     line = {"metric": "inferences/sec across tenants at 1 GPU", "value": value, "unit": "inferences/sec",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -19,8 +20,9 @@ constexpr uint32_t kMaxTenants = 2048;
 constexpr uint32_t kSegSlots = 4;
 constexpr uint64_t kArenaAlign = 256;
 // profiling slots: batcher, gather, head, then gemm and gap of every layer index
-constexpr uint32_t kProfBatcher = 0, kProfGather = 1, kProfHead = 2, kProfGemm = 3, kProfGap = 3 + MT_MAX_LAYERS;
-constexpr uint32_t kProfSlots = 3 + 2 * MT_MAX_LAYERS;
+constexpr uint32_t kProfBatcher = 0, kProfGather = 1, kProfHead = 2, kProfFc = 3, kProfConv = 3 + MT_MAX_LAYERS,
+                   kProfGap = 3 + 2 * MT_MAX_LAYERS;
+constexpr uint32_t kProfSlots = 3 + 3 * MT_MAX_LAYERS;
 
 inline uint32_t round_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }
 inline uint64_t round_up64(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
@@ -57,8 +59,11 @@ struct mt_ctx {
     // per layer index, over registered tenants: bounds that size the grouped launches
     uint32_t n_layer_slots = 0;
     uint32_t max_in_len = 0;
-    uint32_t max_rpr[MT_MAX_LAYERS]{}, max_nt[MT_MAX_LAYERS]{}, has_gap[MT_MAX_LAYERS]{};
-    uint64_t sum_nt[MT_MAX_LAYERS]{};
+    // [kind][layer]: kind 0 = FC tiles, 1 = conv tiles
+    uint32_t max_rpr[2][MT_MAX_LAYERS]{}, max_nt[2][MT_MAX_LAYERS]{}, has_gap[MT_MAX_LAYERS]{};
+    uint64_t sum_nt[2][MT_MAX_LAYERS]{};
+    uint32_t fc_split_k = 0;   // tuning: FC tiles of one column block with K split four ways
+    uint32_t P_cap = 0;        // packed rows incl. per-tenant padding to 32
 
     // device state
     uint8_t* d_arena = nullptr;
@@ -68,10 +73,10 @@ struct mt_ctx {
     uint32_t* d_row_rank = nullptr;
     const void** d_row_src = nullptr;
     int32_t* d_pos_of = nullptr;
-    uint32_t* d_perm = nullptr;
+    int32_t* d_perm = nullptr;
     uint32_t* d_M = nullptr;
     uint32_t* d_off = nullptr;
-    uint32_t* d_n_tiles = nullptr;
+    uint32_t* d_n_tiles = nullptr;     // [2][MT_MAX_LAYERS]: FC counts, then conv counts
     uint32_t* d_overflow = nullptr;
     Tile* d_tiles = nullptr;
     uint32_t tile_cap = 0;
@@ -146,11 +151,22 @@ void arena_free(mt_ctx* c, uint64_t off, uint64_t len)
     c->arena_used -= len;
 }
 
+// how an FC layer's column blocks are grouped into tiles (must match the device code)
+uint32_t fc_groups(uint32_t n_pad, uint32_t split_k)
+{
+    const uint32_t nblk = n_pad / kBrickRows;
+    const uint32_t split = split_k ? 1u : (nblk >= 3 ? 4u : nblk);
+    return (nblk + split - 1) / split;
+}
+
 void recompute_bounds(mt_ctx* c)
 {
     c->n_layer_slots = 0;
     c->max_in_len = 0;
-    for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) { c->max_rpr[l] = c->max_nt[l] = c->has_gap[l] = 0; c->sum_nt[l] = 0; }
+    for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
+        c->has_gap[l] = 0;
+        for (int k = 0; k < 2; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
+    }
     for (const HostTenant& t : c->tenants) {
         if (!t.registered) continue;
         c->n_layer_slots = std::max(c->n_layer_slots, t.n_layers);
@@ -158,19 +174,20 @@ void recompute_bounds(mt_ctx* c)
         for (uint32_t l = 0; l < t.n_layers; ++l) {
             const LayerDev& L = t.layers[l].dev;
             if (L.kind == MT_GAP) { c->has_gap[l] = 1; continue; }
-            const uint32_t nt = (L.N + kBN - 1) / kBN;
-            c->max_rpr[l] = std::max(c->max_rpr[l], L.rows_per_req);
-            c->max_nt[l] = std::max(c->max_nt[l], nt);
-            c->sum_nt[l] += nt;
+            const int k = L.kind == MT_FC ? 0 : 1;
+            const uint32_t nt = k == 0 ? fc_groups(L.N_pad, c->fc_split_k) : (L.N + kTileCols - 1) / kTileCols;
+            c->max_rpr[k][l] = std::max(c->max_rpr[k][l], L.rows_per_req);
+            c->max_nt[k][l] = std::max(c->max_nt[k][l], nt);
+            c->sum_nt[k][l] += nt;
         }
     }
 }
 
-// Upper bound of sum_t ceil(M_t*rpr_t/BM)*nt_t over any split of R rows among tenants.
-uint64_t tile_bound(const mt_ctx* c, uint32_t l, uint64_t R)
+// Upper bound of sum_t ceil(M_t*rpr_t/128)*nt_t over any split of R rows among tenants.
+uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R)
 {
-    if (c->max_nt[l] == 0) return 0;
-    return (uint64_t)c->max_nt[l] * (R * c->max_rpr[l] / kBM) + c->sum_nt[l];
+    if (c->max_nt[kind][l] == 0) return 0;
+    return (uint64_t)c->max_nt[kind][l] * (R * c->max_rpr[kind][l] / kTileRows) + c->sum_nt[kind][l];
 }
 
 // ---- validation of a layer chain; fills dev layouts (without arena offsets) -------------
@@ -179,7 +196,6 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
     if (n_layers == 0 || n_layers > MT_MAX_LAYERS)
         return fail(c, MT_EUNSUPPORTED, "a model needs 1..%d layers, got %u", MT_MAX_LAYERS, n_layers);
     const uint32_t es = c->elem_size;
-    const uint32_t eps = kRowBytes / es;      // K granularity of the arena layout
     uint32_t prev_out = 0;
     out->n_layers = n_layers;
     out->dev = TenantDev{};
@@ -195,10 +211,13 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
         uint32_t in_len = 0;
         if (s.kind == MT_FC) {
             if (s.in_features == 0 || s.out_features == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized FC", l);
+            if (l > 0 && specs[l - 1].kind == MT_CONV2D)
+                return fail(c, MT_EUNSUPPORTED, "layer %u: an FC layer cannot read a convolution's output directly; pool first", l);
             in_len = s.in_features;
-            d.K = round_up(s.in_features, eps); d.N = s.out_features;
+            d.K = round_up(s.in_features, kWidthAlign); d.N = s.out_features;
+            d.N_pad = round_up(s.out_features, d.is_last ? kBrickRows : kWidthAlign);
             d.out_len = s.out_features;
-            hl.w_bytes = (uint64_t)d.N * d.K * es; hl.b_bytes = (uint64_t)d.N * 4;
+            hl.w_bytes = (uint64_t)d.N_pad * d.K * es; hl.b_bytes = (uint64_t)d.N_pad * 4;
         } else if (s.kind == MT_CONV2D) {
             if (s.kh != 3 || s.kw != 3 || s.pad != 1 || (s.stride != 1 && s.stride != 2))
                 return fail(c, MT_EUNSUPPORTED, "layer %u: only 3x3 convolutions with pad 1 and stride 1 or 2 are supported", l);
@@ -211,18 +230,16 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
             d.cin = round_up(s.in_features, kChanPad);
             d.in_h = s.in_h; d.in_w = s.in_w; d.stride = s.stride; d.out_w = ow;
             d.rows_per_req = oh * ow;
-            d.K = round_up(9 * d.cin, eps); d.N = s.out_features;
+            d.K = round_up(9 * d.cin, kWidthAlign); d.N = s.out_features; d.N_pad = s.out_features;
             d.out_len = oh * ow * s.out_features;
-            // a following FC layer reads its fan-in up to the K padding: the conv epilogue writes no such tail
-            if (l + 1 < n_layers && specs[l + 1].kind == MT_FC && d.out_len % kWidthAlign)
-                return fail(c, MT_EUNSUPPORTED, "layer %u: a conv output of %u values feeding an FC layer must be a multiple of %d", l, d.out_len, kWidthAlign);
             hl.w_bytes = (uint64_t)d.N * d.K * es; hl.b_bytes = (uint64_t)d.N * 4;
         } else if (s.kind == MT_GAP) {
             if (s.in_features == 0 || s.in_h == 0 || s.in_w == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized pool", l);
             if (s.out_features != s.in_features || s.act != MT_ACT_NONE) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling keeps the channel count and has no activation", l);
             if (d.is_last || l == 0) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling cannot be the first or the last layer", l);
             in_len = s.in_h * s.in_w * s.in_features;
-            d.cin = s.in_features; d.in_h = s.in_h; d.in_w = s.in_w; d.N = s.in_features;
+            if (specs[l - 1].kind != MT_CONV2D) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling must follow a convolution", l);
+            d.cin = s.in_features; d.in_h = s.in_h; d.in_w = s.in_w; d.N = s.in_features; d.N_pad = s.in_features;
             d.out_len = s.in_features;
             hl.w_bytes = hl.b_bytes = 0;
         } else {
@@ -238,7 +255,7 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
                 staged = s.in_h * s.in_w * d.cin;
             }
             out->dev.in_fill = round_up(staged, kWidthAlign);
-            if (s.kind == MT_FC) out->dev.in_fill = std::max(out->dev.in_fill, d.K);
+            out->dev.in_layout = s.kind == MT_FC ? kLayoutBricks : kLayoutRows;
             if (out->dev.in_fill > c->S) return fail(c, MT_EUNSUPPORTED, "input of %u values exceeds max_width", in_len);
         }
         if (!d.is_last && d.out_fill > c->S) return fail(c, MT_EUNSUPPORTED, "layer %u output of %u values exceeds max_width", l, d.out_len);
@@ -252,9 +269,10 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
     return MT_OK;
 }
 
-// Arena image of one layer: weight rows padded with zeros to the K granularity; conv filters
-// reordered from [Co][Ci][3][3] to [Co][kh][kw][ci_padded] so that a GEMM k index walks the
-// NHWC input contiguously.
+// Arena image of one layer.  FC: bricks[n_block][k_block][lane][EPC] with lane = row + 32*half
+// (zero rows and columns as padding), the order in which a wavefront consumes MFMA operands.
+// Conv: filters reordered from [Co][Ci][3][3] to rows [Co][kh][kw][ci_padded] so that a GEMM k
+// index walks the NHWC input contiguously, each row zero-padded to the K granularity.
 template <typename T>
 void pack_weights(const HostLayer& hl, const void* w_src, uint8_t* dst)
 {
@@ -263,8 +281,15 @@ void pack_weights(const HostLayer& hl, const void* w_src, uint8_t* dst)
     T* out = (T*)dst;
     std::memset(dst, 0, hl.w_bytes);
     if (d.kind == MT_FC) {
-        const uint32_t K = hl.spec.in_features;
-        for (uint32_t n = 0; n < d.N; ++n) std::memcpy(out + (size_t)n * d.K, src + (size_t)n * K, (size_t)K * sizeof(T));
+        constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+        const uint32_t K = hl.spec.in_features, nKB = d.K / KB;
+        for (uint32_t n = 0; n < d.N; ++n) {
+            const uint32_t nb = n / kBrickRows, i = n % kBrickRows;
+            for (uint32_t k = 0; k < K; ++k) {
+                const uint32_t kb = k / KB, h = (k % KB) / EPC, e = k % EPC;
+                out[(((size_t)nb * nKB + kb) * 64 + i + 32 * h) * EPC + e] = src[(size_t)n * K + k];
+            }
+        }
     } else {
         const uint32_t Ci = hl.spec.in_features;
         for (uint32_t co = 0; co < d.N; ++co)
@@ -278,14 +303,15 @@ void pack_weights(const HostLayer& hl, const void* w_src, uint8_t* dst)
 mt_status ensure_tiles(mt_ctx* c)
 {
     uint64_t need = 1;
-    for (uint32_t l = 0; l < c->n_layer_slots; ++l) need = std::max(need, tile_bound(c, l, c->cfg.max_requests));
+    for (uint32_t l = 0; l < c->n_layer_slots; ++l)
+        for (int k = 0; k < 2; ++k) need = std::max(need, tile_bound(c, k, l, c->cfg.max_requests));
     if (need <= c->tile_cap) return MT_OK;
     need = round_up64(need + need / 8, 1024);
-    if (need * MT_MAX_LAYERS * sizeof(Tile) > (1ull << 32)) return fail(c, MT_ENOMEM, "tile lists would need %llu entries per layer", (unsigned long long)need);
+    if (need * 2 * MT_MAX_LAYERS * sizeof(Tile) > (1ull << 32)) return fail(c, MT_ENOMEM, "tile lists would need %llu entries per layer", (unsigned long long)need);
     HIP_TRY(c, hipDeviceSynchronize());
     if (c->d_tiles) HIP_TRY(c, hipFree(c->d_tiles));
     c->d_tiles = nullptr; c->tile_cap = 0;
-    HIP_TRY(c, hipMalloc((void**)&c->d_tiles, need * MT_MAX_LAYERS * sizeof(Tile)));
+    HIP_TRY(c, hipMalloc((void**)&c->d_tiles, need * 2 * MT_MAX_LAYERS * sizeof(Tile)));   // FC lists, then conv lists
     c->tile_cap = (uint32_t)need;
     return MT_OK;
 }
@@ -313,6 +339,8 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     c->elem_size = cfg->dtype == MT_BF16 ? 2 : 4;
     c->S = round_up(cfg->max_width, kWidthAlign);
     c->C_pad = round_up(cfg->max_classes, 4);
+    c->P_cap = round_up(cfg->max_requests, kBrickRows) + kBrickRows * std::min(cfg->max_tenants, cfg->max_requests);
+    if (const char* e = getenv("MT_FC_SPLIT_K")) c->fc_split_k = atoi(e) != 0;
     c->tenants.resize(cfg->max_tenants);
     c->cfg.arena_bytes = cfg->arena_bytes / kArenaAlign * kArenaAlign;
     c->free_list.push_back(FreeBlock{0, c->cfg.arena_bytes});
@@ -332,17 +360,17 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     CREATE_TRY(hipMalloc((void**)&c->d_row_rank, R * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_row_src, R * sizeof(void*)));
     CREATE_TRY(hipMalloc((void**)&c->d_pos_of, R * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_perm, R * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_perm, (uint64_t)c->P_cap * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_M, T * 4));
     CREATE_TRY(hipMemset(c->d_M, 0, T * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_off, (T + 1) * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_n_tiles, MT_MAX_LAYERS * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_n_tiles, 2 * MT_MAX_LAYERS * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_overflow, 4));
     CREATE_TRY(hipMemset(c->d_overflow, 0, 4));
     for (int i = 0; i < 2; ++i) {
-        CREATE_TRY(hipMalloc(&c->d_act[i], R * c->S * c->elem_size));
+        CREATE_TRY(hipMalloc(&c->d_act[i], (uint64_t)c->P_cap * c->S * c->elem_size));
     }
-    CREATE_TRY(hipMalloc((void**)&c->d_logits, R * c->C_pad * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_logits, (uint64_t)c->P_cap * c->C_pad * 4));
     for (uint32_t i = 0; i < kSegSlots; ++i) {
         CREATE_TRY(hipHostMalloc((void**)&c->h_segs[i], R * sizeof(Segment), hipHostMallocMapped));
         CREATE_TRY(hipHostGetDevicePointer((void**)&c->d_segs[i], c->h_segs[i], 0));
@@ -405,7 +433,7 @@ mt_status mt_register_model(mt_ctx* c, uint32_t tenant, const mt_layer_spec* spe
             if (hl.dev.kind == MT_GAP) continue;
             uint8_t* w_dst = image.data() + (hl.dev.w_off - off);
             if (c->elem_size == 2) pack_weights<uint16_t>(hl, weights[l], w_dst); else pack_weights<float>(hl, weights[l], w_dst);
-            if (biases && biases[l]) std::memcpy(image.data() + (hl.dev.b_off - off), biases[l], hl.b_bytes);
+            if (biases && biases[l]) std::memcpy(image.data() + (hl.dev.b_off - off), biases[l], (size_t)hl.dev.N * 4);
         }
         LayerDev rows[MT_MAX_LAYERS]{};
         for (uint32_t l = 0; l < n_layers; ++l) rows[l] = ht.layers[l].dev;
@@ -516,8 +544,10 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     b.first = c->pending[0]; b.row_src = c->d_row_src; b.elem_size = c->elem_size;
     b.tenants = c->d_tenants; b.layers = c->d_layers;
     b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
-    b.M = c->d_M; b.off = c->d_off; b.tiles = c->d_tiles; b.tile_cap = c->tile_cap; b.n_tiles = c->d_n_tiles;
-    b.overflow = c->d_overflow;
+    b.M = c->d_M; b.off = c->d_off; b.tile_cap = c->tile_cap;
+    b.fc_tiles = c->d_tiles; b.conv_tiles = c->d_tiles + (size_t)MT_MAX_LAYERS * c->tile_cap;
+    b.n_fc_tiles = c->d_n_tiles; b.n_conv_tiles = c->d_n_tiles + MT_MAX_LAYERS;
+    b.overflow = c->d_overflow; b.fc_split_k = c->fc_split_k;
     if (c->profiling) for (uint32_t i = 0; i < kProfSlots; ++i) c->prof_used[i] = false;
 #define TIMED(slot, call)                                                                   \
     do {                                                                                    \
@@ -528,24 +558,30 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     TIMED(kProfBatcher, launch_batcher(b, s));
 
     GatherArgs g{};
-    g.row_src = c->d_row_src; g.R = R; g.tenants = c->d_tenants; g.row_tenant = c->d_row_tenant;
+    // packed rows: every tenant with traffic pads its segment to a multiple of 32
+    const uint32_t P = std::min<uint64_t>(c->P_cap, (uint64_t)round_up(R, kBrickRows) + (uint64_t)kBrickRows * std::min(R, c->n_registered));
+    g.row_src = c->d_row_src; g.P = P; g.tenants = c->d_tenants; g.layers = c->d_layers; g.row_tenant = c->d_row_tenant;
     g.perm = c->d_perm; g.off = c->d_off; g.T = T; g.act = c->d_act[0]; g.S = c->S; g.elem_size = c->elem_size;
     TIMED(kProfGather, launch_gather(g, s));
 
     for (uint32_t l = 0; l < c->n_layer_slots; ++l) {
         const void* in = c->d_act[l & 1];
         void* outb = c->d_act[(l + 1) & 1];
-        const uint64_t grid = tile_bound(c, l, R);
-        if (grid > 0) {
+        for (int kind = 0; kind < 2; ++kind) {
+            const uint64_t grid = tile_bound(c, kind, l, R);
+            if (grid == 0) continue;
             GemmArgs ga{};
-            ga.tiles = c->d_tiles + (size_t)l * c->tile_cap; ga.n_tiles = c->d_n_tiles; ga.layer = l;
-            ga.layers = c->d_layers; ga.off = c->d_off; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
+            ga.tiles = c->d_tiles + ((size_t)kind * MT_MAX_LAYERS + l) * c->tile_cap;
+            ga.n_tiles = c->d_n_tiles + kind * MT_MAX_LAYERS; ga.layer = l;
+            ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad;
-            TIMED(kProfGemm + l, launch_gemm(ga, c->cfg.dtype, (uint32_t)std::min<uint64_t>(grid, c->tile_cap), s));
+            const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, c->tile_cap);
+            if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
+            else TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, g32, s));
         }
         if (c->has_gap[l]) {
             GapArgs pa{};
-            pa.layer = l; pa.R = R; pa.layers = c->d_layers; pa.tenants = c->d_tenants; pa.row_tenant = c->d_row_tenant;
+            pa.layer = l; pa.P = P; pa.layers = c->d_layers; pa.tenants = c->d_tenants; pa.row_tenant = c->d_row_tenant;
             pa.perm = c->d_perm; pa.off = c->d_off; pa.T = T; pa.act_in = in; pa.act_out = outb; pa.S = c->S;
             pa.elem_size = c->elem_size;
             TIMED(kProfGap + l, launch_gap(pa, s));
@@ -614,7 +650,8 @@ mt_status mt_get_profile(mt_ctx* c, mt_profile* out)
     HIP_TRY(c, ms(kProfGather, &out->gather_ms));
     HIP_TRY(c, ms(kProfHead, &out->head_ms));
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        HIP_TRY(c, ms(kProfGemm + l, &out->gemm_ms[l]));
+        HIP_TRY(c, ms(kProfFc + l, &out->fc_ms[l]));
+        HIP_TRY(c, ms(kProfConv + l, &out->conv_ms[l]));
         HIP_TRY(c, ms(kProfGap + l, &out->gap_ms[l]));
     }
     HIP_TRY(c, hipEventElapsedTime(&out->total_ms, c->prof_events[2 * kProfBatcher], c->prof_events[2 * kProfHead + 1]));
@@ -627,10 +664,10 @@ mt_status mt_debug_poison(mt_ctx* c)
     if (c->host_only) return fail(c, MT_ESTATE, "host-only context");
     HIP_TRY(c, hipSetDevice(c->cfg.device));
     HIP_TRY(c, hipDeviceSynchronize());
-    const size_t act_bytes = (size_t)c->cfg.max_requests * c->S * c->elem_size;
+    const size_t act_bytes = (size_t)c->P_cap * c->S * c->elem_size;
     HIP_TRY(c, hipMemset(c->d_act[0], 0xFF, act_bytes));
     HIP_TRY(c, hipMemset(c->d_act[1], 0xFF, act_bytes));
-    HIP_TRY(c, hipMemset(c->d_logits, 0xFF, (size_t)c->cfg.max_requests * c->C_pad * 4));
+    HIP_TRY(c, hipMemset(c->d_logits, 0xFF, (size_t)c->P_cap * c->C_pad * 4));
     HIP_TRY(c, hipDeviceSynchronize());
     return MT_OK;
 }

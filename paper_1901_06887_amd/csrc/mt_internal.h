@@ -8,18 +8,31 @@
 
 namespace mt {
 
-// ---- tile geometry of the grouped GEMM (all sizes in elements unless noted) ----
-constexpr int kBM = 128;            // rows of a workgroup tile
-constexpr int kBN = 128;            // columns of a workgroup tile
-constexpr int kRowBytes = 128;      // bytes of K one pipeline step consumes per row
+// ---- geometry ---------------------------------------------------------------------------
+// "Brick": the unit of the fully-connected data layout.  A brick is one MFMA operand of a
+// whole wavefront, stored contiguously: 32 rows x KB reduction elements as 64 lanes x 16
+// bytes, lane = row + 32*half, each lane holding EPC = 16/sizeof(T) consecutive k (KB =
+// 2*EPC: 16 for bf16, 8 for fp32).  A matrix [rows][K] is stored as
+// bricks[row_block][k_block][lane][EPC].  Weights are packed this way at registration and
+// fully-connected activations are produced this way by the gather, the pooling kernel and
+// the FC epilogue, so the hot loop issues nothing but 1 KiB contiguous wavefront loads that
+// land directly in MFMA operand order.
+constexpr int kBrickRows = 32;
+constexpr int kBrickBytes = 1024;
+constexpr int kTileRows = 128;      // rows (4 row blocks) of a grouped-GEMM workgroup tile
+constexpr int kTileCols = 128;      // columns (4 column blocks) of a workgroup tile
+constexpr int kRowBytes = 128;      // conv path: bytes of K one pipeline step consumes per row
 constexpr int kChanPad = 8;         // conv input channels are padded to a multiple of this
-constexpr int kWidthAlign = 64;     // activation rows are zero-filled up to a multiple of this
+constexpr int kWidthAlign = 64;     // K and activation widths are zero-padded to a multiple of this
+
+enum : uint32_t { kLayoutRows = 0, kLayoutBricks = 1 };
 
 // One layer of one tenant, as the kernels see it (lives in device memory).
 struct LayerDev {
     uint32_t kind, act;
-    uint32_t K;          // reduction length actually stored per weight row (padded, elements)
+    uint32_t K;          // reduction length as stored (padded to kWidthAlign), elements
     uint32_t N;          // output features (FC) / output channels (CONV)
+    uint32_t N_pad;      // FC: weight rows as stored (multiple of 32; of 64 for hidden layers)
     uint32_t in_h, in_w; // CONV / GAP input geometry
     uint32_t cin;        // CONV: padded input channels (multiple of kChanPad); GAP: channels
     uint32_t stride;     // CONV
@@ -28,9 +41,8 @@ struct LayerDev {
     uint32_t out_len;    // elements one request's output occupies
     uint32_t out_fill;   // out_len rounded up to kWidthAlign (zero-filled tail)
     uint32_t is_last;    // outputs are the logits
-    uint32_t pad0;
     uint64_t w_off;      // byte offset of the packed weights in the arena
-    uint64_t b_off;      // byte offset of the fp32 bias in the arena
+    uint64_t b_off;      // byte offset of the fp32 bias in the arena (N_pad entries for FC)
 };
 
 struct TenantDev {
@@ -41,7 +53,7 @@ struct TenantDev {
     uint32_t in_cin;     // first layer CONV with channel padding: submitted channels, else 0
     uint32_t in_cin_pad; // ... and the padded count
     uint32_t in_fill;    // elements of the staged input row incl. zero tail
-    uint32_t pad0;
+    uint32_t in_layout;  // kLayoutBricks if the first layer is FC, else kLayoutRows
 };
 
 // One run of submitted rows (lives in pinned host memory, read by the batcher kernel).
@@ -54,47 +66,53 @@ struct Segment {
     int32_t tenant;       // used when ids == nullptr
 };
 
-// One unit of grouped-GEMM work.
+// One unit of grouped work.  FC: rows [m0, m0+rows) of the tenant (m0 a multiple of 32,
+// rows <= kTileRows), column blocks starting at n0; `split` = number of column blocks the
+// four waves cover side by side (4, 2 or 1), the remaining factor 4/split splits K.
+// CONV: a kTileRows x kTileCols output tile of the implicit GEMM.
 struct Tile {
-    uint32_t tenant;
-    uint32_t m0;      // first GEMM row inside the tenant's segment
-    uint32_t rows;    // valid rows (<= kBM)
-    uint32_t n0;      // first output column
+    uint32_t tenant;      // low 16 bits tenant, bits 16..23 split
+    uint32_t m0;
+    uint32_t rows;
+    uint32_t n0;
 };
 
 struct BatchArgs {
     const Segment* segs; uint32_t n_segs; uint32_t R; uint32_t T; uint32_t n_layer_slots;
     Segment first;         // copy of segs[0]: the common one-segment run never reads host memory
-    const void** row_src;  // [R] device address of each submitted row's input
     uint32_t elem_size;
+    uint32_t fc_split_k;   // 1: FC tiles take one column block each and split K four ways
     const TenantDev* tenants; const LayerDev* layers;
     int32_t* row_tenant;   // [R] tenant of each submitted row, -1 if rejected
     uint32_t* row_rank;    // [R] scratch
+    const void** row_src;  // [R] device address of each submitted row's input
     int32_t* pos_of;       // [R] packed position of each submitted row, -1 if rejected
-    uint32_t* perm;        // [R] packed position -> submission index
+    int32_t* perm;         // [P] packed position -> submission index, -1 for padding rows
     uint32_t* M;           // [T]
-    uint32_t* off;         // [T+1]
-    Tile* tiles; uint32_t tile_cap;   // n_layer_slots lists of tile_cap entries
-    uint32_t* n_tiles;     // [n_layer_slots]
+    uint32_t* off;         // [T+1] packed position of each tenant's first row (multiple of 32)
+    Tile* fc_tiles; Tile* conv_tiles; uint32_t tile_cap;   // n_layer_slots lists of tile_cap entries each
+    uint32_t* n_fc_tiles;  // [n_layer_slots]
+    uint32_t* n_conv_tiles;
     uint32_t* overflow;    // set to 1 if a tile list would not fit (never expected)
 };
 
 struct GatherArgs {
-    const void* const* row_src; uint32_t R;
-    const TenantDev* tenants; const int32_t* row_tenant; const uint32_t* perm; const uint32_t* off; uint32_t T;
+    const void* const* row_src; uint32_t P;      // P = upper bound of packed rows (multiple of 32)
+    const TenantDev* tenants; const LayerDev* layers; const int32_t* row_tenant; const int32_t* perm;
+    const uint32_t* off; uint32_t T;
     void* act; uint32_t S; uint32_t elem_size;
 };
 
 struct GemmArgs {
     const Tile* tiles; const uint32_t* n_tiles; uint32_t layer;
-    const LayerDev* layers; const uint32_t* off;
+    const LayerDev* layers; const uint32_t* off; const uint32_t* M;
     const void* act_in; void* act_out; const uint8_t* arena;
     float* logits; uint32_t S; uint32_t C_pad;
 };
 
 struct GapArgs {
-    uint32_t layer; uint32_t R; const LayerDev* layers; const TenantDev* tenants;
-    const int32_t* row_tenant; const uint32_t* perm; const uint32_t* off; uint32_t T;
+    uint32_t layer; uint32_t P; const LayerDev* layers; const TenantDev* tenants;
+    const int32_t* row_tenant; const int32_t* perm; const uint32_t* off; uint32_t T;
     const void* act_in; void* act_out; uint32_t S; uint32_t elem_size;
 };
 
@@ -107,7 +125,8 @@ struct HeadArgs {
 // Launchers (defined in mt_kernels.hip).  All enqueue on `s` and return the launch status.
 hipError_t launch_batcher(const BatchArgs& a, hipStream_t s);
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
-hipError_t launch_gemm(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
+hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, hipStream_t s);
 hipError_t launch_head(const HeadArgs& a, hipStream_t s);
 

@@ -1,11 +1,15 @@
 // Device code of the multi-tenant worker runtime, written for gfx950 (CDNA4, wave64).
 //
-//   batcher_kernel  tenant segmentation of the pending requests (counts, offsets, stable
-//                   permutation) and the per-layer grouped-work tile lists, all on device
-//   gather_kernel   submitted rows -> tenant-contiguous, zero-padded activation rows
-//   gemm_kernel     one layer index for all tenants: grouped GEMM / implicit-GEMM 3x3
-//                   convolution on MFMA with fused bias + activation (+ bf16 rounding)
-//   gap_kernel      global average pooling rows
+//   batcher_kernel  tenant segmentation of the pending requests (counts, 32-aligned offsets,
+//                   stable permutation) and the per-layer grouped-work tile lists, on device
+//   gather_kernel   submitted rows -> tenant-contiguous staged inputs (bricks for FC models,
+//                   channel-padded NHWC rows for CNN models)
+//   fc_kernel       one FC layer index for all tenants: grouped GEMM that streams weight and
+//                   activation bricks straight from memory into MFMA operands, fused bias +
+//                   activation (+ bf16 rounding), brick output or fp32 logits
+//   conv_kernel     one conv layer index for all tenants: implicit-GEMM 3x3 convolution on
+//                   MFMA through LDS, fused bias + activation
+//   gap_kernel      global average pooling, NHWC rows -> bricks
 //   head_kernel     softmax + argmax, written in submission order
 //
 // A DNN is a fixed sequence of layers applied in turn (paper, section 1.1); a worker
@@ -68,6 +72,15 @@ __device__ uint32_t block_exclusive_scan(uint32_t* data, uint32_t n, uint32_t* t
     return total;
 }
 
+// Number of column groups an FC layer is cut into and how the four waves share one group.
+__device__ __forceinline__ void fc_shape(uint32_t n_pad, uint32_t split_k, uint32_t* split, uint32_t* groups)
+{
+    const uint32_t nblk = n_pad / kBrickRows;
+    uint32_t s = split_k ? 1u : (nblk >= 3 ? 4u : nblk);
+    *split = s;
+    *groups = ceil_div(nblk, s);
+}
+
 // Tenant segmentation and tile lists.  One workgroup; every step is deterministic:
 // rows of a tenant keep their arrival order (stable counting sort).  Equal tenant ids
 // inside a wavefront are found with one ballot per id bit, so a step costs the same
@@ -78,6 +91,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     __shared__ uint32_t Ml[kMaxTenantsPadded];
     __shared__ uint32_t offl[kMaxTenantsPadded];
     __shared__ uint32_t cnt[kMaxTenantsPadded];
+    __shared__ uint32_t cnt2[kMaxTenantsPadded];
     __shared__ uint32_t tmp[17];
     __shared__ Segment seg_l[kSegsInLds];
 
@@ -131,15 +145,19 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     }
     __syncthreads();
 
-    // pass 2: per-tenant totals, per-wave bases, tenant offsets
+    // pass 2: per-tenant totals, per-wave bases, tenant offsets (each tenant starts a 32-row block)
     for (uint32_t t = tid; t < Tp; t += kBatchThreads) {
         uint32_t s = 0;
         for (uint32_t i = 0; i < nw; ++i) { uint32_t c = hist[i * Tp + t]; hist[i * Tp + t] = s; s += c; }
-        Ml[t] = s; offl[t] = s;
+        Ml[t] = s; offl[t] = ceil_div(s, kBrickRows) * kBrickRows;
     }
     __syncthreads();
     const uint32_t total = block_exclusive_scan(offl, Tp, tmp);
-    for (uint32_t t = tid; t < T; t += kBatchThreads) { a.M[t] = Ml[t]; a.off[t] = offl[t]; }
+    for (uint32_t t = tid; t < T; t += kBatchThreads) {
+        a.M[t] = Ml[t]; a.off[t] = offl[t];
+        const uint32_t end = offl[t] + ceil_div(Ml[t], kBrickRows) * kBrickRows;
+        for (uint32_t p = offl[t] + Ml[t]; p < end; ++p) a.perm[p] = -1;      // padding rows of the last block
+    }
     if (tid == 0) a.off[T] = total;
 
     // pass 3: packed position of every row
@@ -148,91 +166,133 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         int32_t pos = -1;
         if (t >= 0) {
             pos = (int32_t)(offl[t] + hist[(r / chunk) * Tp + t] + a.row_rank[r]);
-            a.perm[pos] = r;
+            a.perm[pos] = (int32_t)r;
         }
         a.pos_of[r] = pos;
     }
 
-    // pass 4: tile list of every layer index
+    // pass 4: tile lists of every layer index (FC and conv separately)
     for (uint32_t l = 0; l < a.n_layer_slots; ++l) {
         __syncthreads();
         for (uint32_t t = tid; t < Tp; t += kBatchThreads) {
-            uint32_t c = 0;
+            uint32_t cf = 0, cc = 0;
             if (t < T && Ml[t] > 0 && a.tenants[t].registered && a.tenants[t].n_layers > l) {
                 const LayerDev& L = a.layers[t * MT_MAX_LAYERS + l];
-                if (L.kind != MT_GAP) c = ceil_div(Ml[t] * L.rows_per_req, kBM) * ceil_div(L.N, kBN);
+                if (L.kind == MT_FC) {
+                    uint32_t split, groups;
+                    fc_shape(L.N_pad, a.fc_split_k, &split, &groups);
+                    cf = ceil_div(Ml[t], kTileRows) * groups;
+                } else if (L.kind == MT_CONV2D) {
+                    cc = ceil_div(Ml[t] * L.rows_per_req, kTileRows) * ceil_div(L.N, kTileCols);
+                }
             }
-            cnt[t] = c;
+            cnt[t] = cf; cnt2[t] = cc;
         }
         __syncthreads();
-        uint32_t n = block_exclusive_scan(cnt, Tp, tmp);
-        if (n > a.tile_cap) { if (tid == 0) *a.overflow = 1; n = a.tile_cap; }
-        if (tid == 0) a.n_tiles[l] = n;
-        Tile* out = a.tiles + (size_t)l * a.tile_cap;
-        for (uint32_t i = tid; i < n; i += kBatchThreads) {
-            uint32_t lo = 0, hi = Tp;           // last t with cnt[t] <= i
-            while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (cnt[mid] <= i) lo = mid; else hi = mid; }
-            const LayerDev& L = a.layers[lo * MT_MAX_LAYERS + l];
-            const uint32_t rows = Ml[lo] * L.rows_per_req;
-            const uint32_t mt_ = ceil_div(rows, kBM);
-            const uint32_t local = i - cnt[lo];
-            Tile tl;
-            tl.tenant = lo;
-            tl.m0 = (local % mt_) * kBM;
-            tl.rows = min((uint32_t)kBM, rows - tl.m0);
-            tl.n0 = (local / mt_) * kBN;
-            out[i] = tl;
+        for (int kind = 0; kind < 2; ++kind) {
+            uint32_t* c = kind == 0 ? cnt : cnt2;
+            uint32_t n = block_exclusive_scan(c, Tp, tmp);
+            if (n > a.tile_cap) { if (tid == 0) *a.overflow = 1; n = a.tile_cap; }
+            if (tid == 0) (kind == 0 ? a.n_fc_tiles : a.n_conv_tiles)[l] = n;
+            Tile* out = (kind == 0 ? a.fc_tiles : a.conv_tiles) + (size_t)l * a.tile_cap;
+            for (uint32_t i = tid; i < n; i += kBatchThreads) {
+                uint32_t lo = 0, hi = Tp;           // last t with c[t] <= i
+                while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (c[mid] <= i) lo = mid; else hi = mid; }
+                const LayerDev& L = a.layers[lo * MT_MAX_LAYERS + l];
+                const uint32_t local = i - c[lo];
+                Tile tl;
+                if (kind == 0) {
+                    uint32_t split, groups;
+                    fc_shape(L.N_pad, a.fc_split_k, &split, &groups);
+                    const uint32_t mt_ = ceil_div(Ml[lo], kTileRows);
+                    tl.tenant = lo | (split << 16);
+                    tl.m0 = (local % mt_) * kTileRows;
+                    tl.rows = min((uint32_t)kTileRows, Ml[lo] - tl.m0);
+                    tl.n0 = (local / mt_) * split * kBrickRows;
+                } else {
+                    const uint32_t rows = Ml[lo] * L.rows_per_req;
+                    const uint32_t mt_ = ceil_div(rows, kTileRows);
+                    tl.tenant = lo;
+                    tl.m0 = (local % mt_) * kTileRows;
+                    tl.rows = min((uint32_t)kTileRows, rows - tl.m0);
+                    tl.n0 = (local / mt_) * kTileCols;
+                }
+                out[i] = tl;
+            }
         }
     }
 }
 
-// ---- gather: one workgroup per packed row -----------------------------------------------
+// ---- gather: one workgroup per block of 32 packed rows ------------------------------------
 template <typename T>
-__device__ void gather_row(const GatherArgs& a, uint32_t p)
+__device__ void gather_rows_layout(const GatherArgs& a, const TenantDev& td, uint32_t p0)
 {
-    const uint32_t r = a.perm[p];
-    const int32_t t = a.row_tenant[r];
-    const TenantDev td = a.tenants[t];
-    const T* src = (const T*)a.row_src[r];
-    T* dst = (T*)a.act + (size_t)p * a.S;
-    constexpr uint32_t EPC = 16 / sizeof(T);
-    if (td.in_cin == 0) {
-        const uint32_t n = td.in_len;
-        if (((uintptr_t)src & 15) == 0 && (n % EPC) == 0) {
-            const u32x4* s4 = (const u32x4*)src; u32x4* d4 = (u32x4*)dst;
-            for (uint32_t i = threadIdx.x; i < n / EPC; i += blockDim.x) d4[i] = s4[i];
-        } else {
-            for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) dst[i] = src[i];
+    // NHWC rows (first layer is a convolution), channels padded with zeros
+    for (uint32_t i = 0; i < kBrickRows; ++i) {
+        const int32_t r = a.perm[p0 + i];
+        if (r < 0) continue;
+        const T* src = (const T*)a.row_src[r];
+        T* dst = (T*)a.act + (size_t)(p0 + i) * a.S;
+        const uint32_t ci = td.in_cin ? td.in_cin : 1, cp = td.in_cin ? td.in_cin_pad : 1;
+        const uint32_t npix = td.in_len / ci;
+        for (uint32_t e = threadIdx.x; e < npix * cp; e += blockDim.x) {
+            const uint32_t pix = e / cp, c = e % cp;
+            dst[e] = c < ci ? src[pix * ci + c] : (T)0.0f;
         }
-        for (uint32_t i = n + threadIdx.x; i < td.in_fill; i += blockDim.x) dst[i] = (T)0.0f;
-    } else {
-        // channel padding of an NHWC image whose first layer is a convolution
-        const uint32_t ci = td.in_cin, cp = td.in_cin_pad, npix = td.in_len / ci;
-        for (uint32_t i = threadIdx.x; i < npix * cp; i += blockDim.x) {
-            const uint32_t pix = i / cp, c = i % cp;
-            dst[i] = c < ci ? src[pix * ci + c] : (T)0.0f;
+        for (uint32_t e = npix * cp + threadIdx.x; e < td.in_fill; e += blockDim.x) dst[e] = (T)0.0f;
+    }
+}
+
+template <typename T>
+__device__ void gather_bricks(const GatherArgs& a, const TenantDev& td, uint32_t t, uint32_t p0)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t li = lane & 31, lh = lane >> 5;
+    const uint32_t nKB = a.layers[t * MT_MAX_LAYERS].K / KB;
+    const uint32_t seg0 = a.off[t];
+    const int32_t r = a.perm[p0 + li];
+    const T* src = r >= 0 ? (const T*)a.row_src[r] : nullptr;
+    u32x4* dst = (u32x4*)((T*)a.act + (size_t)seg0 * a.S) + (size_t)((p0 - seg0) / kBrickRows) * nKB * 64 + lane;
+    const uint32_t n = td.in_len;
+    for (uint32_t kb = wave; kb < nKB; kb += 4) {
+        const uint32_t k = kb * KB + lh * EPC;
+        u32x4 v = {0, 0, 0, 0};
+        if (src && k < n) {
+            if (k + EPC <= n && (((uintptr_t)(src + k)) & 15) == 0) {
+                v = *(const u32x4*)(src + k);
+            } else {
+                alignas(16) T tmp[EPC];
+#pragma unroll
+                for (uint32_t e = 0; e < EPC; ++e) tmp[e] = k + e < n ? src[k + e] : (T)0.0f;
+                v = *(const u32x4*)tmp;
+            }
         }
-        for (uint32_t i = npix * cp + threadIdx.x; i < td.in_fill; i += blockDim.x) dst[i] = (T)0.0f;
+        dst[(size_t)kb * 64] = v;
     }
 }
 
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
 {
-    const uint32_t p = blockIdx.x;
-    if (p >= a.off[a.T]) return;
-    if (a.elem_size == 2) gather_row<__bf16>(a, p); else gather_row<float>(a, p);
+    const uint32_t p0 = blockIdx.x * kBrickRows;
+    if (p0 >= a.off[a.T]) return;
+    const int32_t r0 = a.perm[p0];        // the first row of a block is always a real request
+    const uint32_t t = (uint32_t)a.row_tenant[r0];
+    const TenantDev td = a.tenants[t];
+    if (td.in_layout == kLayoutBricks) {
+        if (a.elem_size == 2) gather_bricks<__bf16>(a, td, t, p0); else gather_bricks<float>(a, td, t, p0);
+    } else {
+        if (a.elem_size == 2) gather_rows_layout<__bf16>(a, td, p0); else gather_rows_layout<float>(a, td, p0);
+    }
 }
 
-// ---- grouped GEMM -----------------------------------------------------------------------
+// ---- shared pieces of the GEMM kernels -----------------------------------------------------
 __device__ __forceinline__ float activate(float z, uint32_t act)
 {
     if (act == MT_ACT_RELU) return fmaxf(z, 0.0f);
     if (act == MT_ACT_GELU) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
     return z;
 }
-
-constexpr int kLdsRow = kRowBytes + 16;            // padded LDS row, bytes
-constexpr int kTileBytes = kBM * kLdsRow;          // one operand tile of one stage
 
 template <typename T> struct Mma;
 // bf16: one 16-byte chunk is a whole MFMA operand (8 consecutive k of one row).
@@ -255,10 +315,171 @@ template <> struct Mma<float> {
     }
 };
 
-// One workgroup = 4 waves in a 2x2 grid over a 128x128 tile; a wave owns 64x64 = 2x2 MFMA
-// blocks of 32x32.  K is consumed 128 bytes per row per step through two LDS stages.
+// ---- grouped FC ------------------------------------------------------------------------------
+// A workgroup of four waves owns up to 128 rows (RB row blocks of 32) of one tenant and
+// `split` column blocks of 32; with split < 4 the waves also split K between them and the
+// partial sums are added in a fixed order through LDS.  Every wave streams its weight bricks
+// and the activation bricks it needs straight from memory into MFMA operands, keeping a ring
+// of P bricks in flight; there is no LDS staging and no barrier in the K loop.
+constexpr uint32_t kRedFloats = 4 * 16 * 64;                 // one f32x16 per lane per wave
+constexpr uint32_t kTrRowBytes = 32 * 4 + 16;                // transposition scratch row (fp32 worst case)
+constexpr uint32_t kTrBytes = 32 * kTrRowBytes;
+
+template <typename T, int RB, int P>
+__device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const LayerDev& L, uint32_t t, uint32_t split,
+                                        float* red, uint8_t* tr)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t li = lane & 31, lh = lane >> 5;
+    const uint32_t ks = 4 / split;
+    const uint32_t nb = tl.n0 / kBrickRows + (wave % split), kq = wave / split;
+    const uint32_t nKB = L.K / KB;
+    const bool active = nb < L.N_pad / kBrickRows;
+    const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
+    const uint32_t cnt = nKB / ks, kb0 = kq * cnt;
+    const uint32_t seg0 = a.off[t];
+
+    f32x16 acc[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[r][v] = 0.0f;
+
+    if (active) {
+        const u32x4* wp = (const u32x4*)(a.arena + L.w_off) + ((size_t)nb * nKB + kb0) * 64 + lane;
+        const u32x4* xbase = (const u32x4*)((const T*)a.act_in + (size_t)seg0 * a.S) + lane;
+        const u32x4* xp[RB];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            const uint32_t rbi = tl.m0 / kBrickRows + min((uint32_t)r, nrb - 1);   // blocks past the tile repeat its last one
+            xp[r] = xbase + ((size_t)rbi * nKB + kb0) * 64;
+        }
+        u32x4 bq[P], aq[RB][P];
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+            const uint32_t kk = min((uint32_t)j, cnt - 1);
+            bq[j] = wp[(size_t)kk * 64];
+#pragma unroll
+            for (int r = 0; r < RB; ++r) aq[r][j] = xp[r][(size_t)kk * 64];
+        }
+        // steady state: straight-line groups of P bricks, each slot refilled right after use, so
+        // P-1 slots stay in flight behind every MFMA; the clamped refill index re-reads the last
+        // brick instead of branching
+        const uint32_t full = cnt / P;
+        for (uint32_t g = 0; g < full; ++g) {
+#pragma unroll
+            for (int j = 0; j < P; ++j) {
+#pragma unroll
+                for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], aq[r][j], bq[j]);
+                const uint32_t kk = min(g * P + j + P, cnt - 1);
+                bq[j] = wp[(size_t)kk * 64];
+#pragma unroll
+                for (int r = 0; r < RB; ++r) aq[r][j] = xp[r][(size_t)kk * 64];
+            }
+        }
+        // tail: the slots already hold bricks full*P .. full*P+P-1 (clamped)
+        const uint32_t rem = cnt - full * P;
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+            if ((uint32_t)j < rem) {
+#pragma unroll
+                for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], aq[r][j], bq[j]);
+            }
+        }
+    }
+
+    // K-split: waves with kq > 0 hand their partial sums to the kq == 0 wave of the same column block
+    if (ks > 1) {
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            __syncthreads();
+            if (active && kq > 0 && (uint32_t)r < nrb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) red[wave * 1024 + v * 64 + lane] = acc[r][v];
+            }
+            __syncthreads();
+            if (active && kq == 0 && (uint32_t)r < nrb) {
+                for (uint32_t q = 1; q < ks; ++q) {
+                    const uint32_t src = (wave % split) + split * q;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[r][v] += red[src * 1024 + v * 64 + lane];
+                }
+            }
+        }
+    }
+
+    const bool writer = active && kq == 0;
+    const uint32_t n = nb * kBrickRows + li;
+    const float* bias = (const float*)(a.arena + L.b_off);
+    const float bv = writer ? bias[n] : 0.0f;
+    if (L.is_last) {
+        if (!writer || n >= L.N) return;
+        const uint32_t Mt = a.M[t];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t m = tl.m0 + r * kBrickRows + 8 * (v >> 2) + 4 * lh + (v & 3);
+                if ((uint32_t)r < nrb && m < Mt) a.logits[(size_t)(seg0 + m) * a.C_pad + n] = acc[r][v] + bv;
+            }
+        }
+        return;
+    }
+    // hidden layer: bias, activation, rounding; transpose the 32x32 block through LDS so that
+    // every lane ends up with 16 contiguous output bytes, then store whole bricks
+    constexpr uint32_t TRS = 32 * sizeof(T) + 16;
+    uint8_t* trw = tr + wave * kTrBytes;
+    const uint32_t nKB_out = L.out_fill / KB;
+    u32x4* obase = (u32x4*)((T*)a.act_out + (size_t)seg0 * a.S) + lane;
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        __syncthreads();
+        if (writer && (uint32_t)r < nrb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t ml = 8 * (v >> 2) + 4 * lh + (v & 3);
+                const float y = n < L.N ? activate(acc[r][v] + bv, L.act) : 0.0f;
+                *(T*)(trw + ml * TRS + li * sizeof(T)) = (T)y;
+            }
+        }
+        __syncthreads();
+        if (writer && (uint32_t)r < nrb) {
+#pragma unroll
+            for (uint32_t c = 0; c < kBrickRows / KB; ++c) {
+                const u32x4 chunk = *(const u32x4*)(trw + li * TRS + (c * KB + lh * EPC) * sizeof(T));
+                const uint32_t kb_out = nb * (kBrickRows / KB) + c;
+                obase[((size_t)(tl.m0 / kBrickRows + r) * nKB_out + kb_out) * 64] = chunk;
+            }
+        }
+    }
+}
+
 template <typename T>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a)
+__global__ __launch_bounds__(256) void fc_kernel(GemmArgs a)
+{
+    __shared__ __attribute__((aligned(16))) float red[kRedFloats];
+    __shared__ __attribute__((aligned(16))) uint8_t tr[4 * kTrBytes];
+    const uint32_t tile_id = blockIdx.x;
+    if (tile_id >= a.n_tiles[a.layer]) return;
+    const Tile tl = a.tiles[tile_id];
+    const uint32_t t = tl.tenant & 0xffff, split = (tl.tenant >> 16) & 0xff;
+    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
+    if (nrb <= 1) fc_tile<T, 1, 8>(a, tl, L, t, split, red, tr);
+    else if (nrb == 2) fc_tile<T, 2, 6>(a, tl, L, t, split, red, tr);
+    else fc_tile<T, 4, 4>(a, tl, L, t, split, red, tr);
+}
+
+// ---- grouped 3x3 convolution as implicit GEMM ---------------------------------------------
+// One workgroup = 4 waves in a 2x2 grid over a 128x128 tile of (output pixels) x (output
+// channels); a wave owns 64x64 = 2x2 MFMA blocks.  K = 9 * C_in walks the NHWC input tap by
+// tap, 128 bytes per row per step, through two LDS stages; out-of-image taps load zeros.
+constexpr int kLdsRow = kRowBytes + 16;            // padded LDS row, bytes
+constexpr int kTileBytes = kTileRows * kLdsRow;    // one operand tile of one stage
+
+template <typename T>
+__global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lds[4 * kTileBytes];
     constexpr uint32_t EPC = 16 / sizeof(T);          // elements per 16-byte chunk
@@ -269,13 +490,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a)
     const Tile tl = a.tiles[tile_id];
     const LayerDev L = a.layers[tl.tenant * MT_MAX_LAYERS + a.layer];
     const uint32_t seg0 = a.off[tl.tenant];
-    const bool conv = L.kind == MT_CONV2D;
 
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t wm = wave >> 1, wn = wave & 1;
     const uint32_t li = lane & 31, lh = lane >> 5;
 
-    // --- global -> register staging: thread owns chunk `lc` of rows lr + 32*i ---------------
+    // global -> register staging: thread owns chunk `lc` of rows lr + 32*i
     const uint32_t lc = tid & 7, lr = tid >> 3;
     const T* act_in = (const T*)a.act_in;
     const T* W = (const T*)(a.arena + L.w_off);
@@ -299,18 +519,13 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a)
     u32x4 ra[4], rb[4];
     auto load_step = [&](uint32_t step) {
         const uint32_t k = step * EPS + lc * EPC;
-        if (!conv) {
+        const uint32_t tap = k / L.cin, c0 = k % L.cin;
+        const int32_t kh = (int32_t)(tap / 3), kw = (int32_t)(tap % 3);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) ra[i] = a_ok[i] ? *(const u32x4*)(a_ptr[i] + k) : u32x4{0, 0, 0, 0};
-        } else {
-            const uint32_t tap = k / L.cin, c0 = k % L.cin;
-            const int32_t kh = (int32_t)(tap / 3), kw = (int32_t)(tap % 3);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int32_t ih = a_oh[i] + kh, iw = a_ow[i] + kw;
-                const bool ok = a_ok[i] && tap < 9 && ih >= 0 && ih < (int32_t)L.in_h && iw >= 0 && iw < (int32_t)L.in_w;
-                ra[i] = ok ? *(const u32x4*)(a_ptr[i] + ((size_t)(ih * (int32_t)L.in_w + iw) * L.cin + c0)) : u32x4{0, 0, 0, 0};
-            }
+        for (int i = 0; i < 4; ++i) {
+            const int32_t ih = a_oh[i] + kh, iw = a_ow[i] + kw;
+            const bool ok = a_ok[i] && tap < 9 && ih >= 0 && ih < (int32_t)L.in_h && iw >= 0 && iw < (int32_t)L.in_w;
+            ra[i] = ok ? *(const u32x4*)(a_ptr[i] + ((size_t)(ih * (int32_t)L.in_w + iw) * L.cin + c0)) : u32x4{0, 0, 0, 0};
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) rb[i] = b_ok[i] ? *(const u32x4*)(b_ptr[i] + k) : u32x4{0, 0, 0, 0};
@@ -333,9 +548,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    // waves whose 64 rows lie wholly past the tile's valid rows skip the MFMAs
-    const bool wave_active = wm * 64 < tl.rows;
+    // waves whose rows or columns lie wholly past the valid part of the tile skip the MFMAs
+    const bool wave_active = wm * 64 < tl.rows && tl.n0 + wn * 64 < L.N;
     const bool mb1_active = wm * 64 + 32 < tl.rows;
+    const bool nb1_active = tl.n0 + wn * 64 + 32 < L.N;
 
     load_step(0);
     store_step(0);
@@ -350,13 +566,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a)
             for (int s = 0; s < 4; ++s) {
                 const u32x4 a0 = *(const u32x4*)(As + s * 32);
                 const u32x4 b0 = *(const u32x4*)(Bs + s * 32);
-                const u32x4 b1 = *(const u32x4*)(Bs + 32 * kLdsRow + s * 32);
                 Mma<T>::run(acc[0][0], a0, b0);
-                Mma<T>::run(acc[0][1], a0, b1);
-                if (mb1_active) {
+                if (nb1_active) {
+                    const u32x4 b1 = *(const u32x4*)(Bs + 32 * kLdsRow + s * 32);
+                    Mma<T>::run(acc[0][1], a0, b1);
+                    if (mb1_active) {
+                        const u32x4 a1 = *(const u32x4*)(As + 32 * kLdsRow + s * 32);
+                        Mma<T>::run(acc[1][0], a1, b0);
+                        Mma<T>::run(acc[1][1], a1, b1);
+                    }
+                } else if (mb1_active) {
                     const u32x4 a1 = *(const u32x4*)(As + 32 * kLdsRow + s * 32);
                     Mma<T>::run(acc[1][0], a1, b0);
-                    Mma<T>::run(acc[1][1], a1, b1);
                 }
             }
         }
@@ -364,15 +585,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a)
         __syncthreads();
     }
 
-    // --- epilogue: bias, activation, rounding, store --------------------------------------
+    // epilogue: bias, activation, rounding, NHWC store
     if (!wave_active) return;
     const float* bias = (const float*)(a.arena + L.b_off);
     T* act_out = (T*)a.act_out;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
         const uint32_t n = tl.n0 + wn * 64 + nb * 32 + li;
-        const bool n_ok = n < L.N;
-        const float bv = n_ok ? bias[n] : 0.0f;
+        if (n >= L.N) continue;
+        const float bv = bias[n];
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
 #pragma unroll
@@ -380,31 +601,29 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a)
                 const uint32_t row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                 if (row >= tl.rows) continue;
                 const uint32_t m = tl.m0 + row;
-                const float z = acc[mb][nb][v] + bv;
-                if (L.is_last) {
-                    if (n_ok) a.logits[(size_t)(seg0 + m) * a.C_pad + n] = z;
-                } else if (n < L.out_fill || conv) {
-                    const uint32_t req = m / L.rows_per_req, pix = m % L.rows_per_req;
-                    if (n_ok || !conv)
-                        act_out[(size_t)(seg0 + req) * a.S + (size_t)pix * L.N + n] = n_ok ? (T)activate(z, L.act) : (T)0.0f;
-                }
+                const uint32_t req = m / L.rows_per_req, pix = m % L.rows_per_req;
+                act_out[(size_t)(seg0 + req) * a.S + (size_t)pix * L.N + n] = (T)activate(acc[mb][nb][v] + bv, L.act);
             }
         }
     }
 }
 
-// ---- global average pool: one workgroup per packed row ---------------------------------
+// ---- global average pool: one workgroup per packed row, NHWC row in, brick slice out ------
 template <typename T>
-__device__ void gap_row(const GapArgs& a, const LayerDev& L, uint32_t p)
+__device__ void gap_row(const GapArgs& a, const LayerDev& L, uint32_t p, uint32_t seg0)
 {
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
     const T* in = (const T*)a.act_in + (size_t)p * a.S;
-    T* out = (T*)a.act_out + (size_t)p * a.S;
     const uint32_t C = L.cin, HW = L.in_h * L.in_w;
+    const uint32_t m = p - seg0, rb = m / kBrickRows, i = m % kBrickRows;
+    const uint32_t nKB = L.out_fill / KB;
+    T* out = (T*)a.act_out + (size_t)seg0 * a.S + (size_t)rb * nKB * 64 * EPC;
     const float inv = 1.0f / (float)HW;
     for (uint32_t c = threadIdx.x; c < L.out_fill; c += blockDim.x) {
         float s = 0.0f;
         if (c < C) for (uint32_t q = 0; q < HW; ++q) s += (float)in[(size_t)q * C + c];
-        out[c] = (T)(s * inv);
+        const uint32_t kb = c / KB, h = (c % KB) / EPC, e = c % EPC;
+        out[((size_t)kb * 64 + i + 32 * h) * EPC + e] = (T)(s * inv);
     }
 }
 
@@ -412,11 +631,13 @@ __global__ __launch_bounds__(128) void gap_kernel(GapArgs a)
 {
     const uint32_t p = blockIdx.x;
     if (p >= a.off[a.T]) return;
-    const int32_t t = a.row_tenant[a.perm[p]];
+    const int32_t r = a.perm[p];
+    if (r < 0) return;
+    const uint32_t t = (uint32_t)a.row_tenant[r];
     if (a.tenants[t].n_layers <= a.layer) return;
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     if (L.kind != MT_GAP) return;
-    if (a.elem_size == 2) gap_row<__bf16>(a, L, p); else gap_row<float>(a, L, p);
+    if (a.elem_size == 2) gap_row<__bf16>(a, L, p, a.off[t]); else gap_row<float>(a, L, p, a.off[t]);
 }
 
 // ---- head: one wave per submitted row --------------------------------------------------
@@ -467,20 +688,27 @@ hipError_t launch_batcher(const BatchArgs& a, hipStream_t s)
 }
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
 {
-    hipLaunchKernelGGL(gather_kernel, dim3(a.R), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(gather_kernel, dim3(a.P / kBrickRows), dim3(256), 0, s, a);
     return hipGetLastError();
 }
-hipError_t launch_gemm(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)
+hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)
 {
     if (grid == 0) return hipSuccess;
-    if (dtype == MT_BF16) hipLaunchKernelGGL(gemm_kernel<__bf16>, dim3(grid), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(gemm_kernel<float>, dim3(grid), dim3(256), 0, s, a);
+    if (dtype == MT_BF16) hipLaunchKernelGGL(fc_kernel<__bf16>, dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(fc_kernel<float>, dim3(grid), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)
+{
+    if (grid == 0) return hipSuccess;
+    if (dtype == MT_BF16) hipLaunchKernelGGL(conv_kernel<__bf16>, dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(conv_kernel<float>, dim3(grid), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_gap(const GapArgs& a, hipStream_t s)
 {
     // grid covers every packed row; rows of other layer kinds return at once
-    hipLaunchKernelGGL(gap_kernel, dim3(a.R), dim3(128), 0, s, a);
+    hipLaunchKernelGGL(gap_kernel, dim3(a.P), dim3(128), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_head(const HeadArgs& a, hipStream_t s)

@@ -38,7 +38,8 @@ def context_for(tenants: Dict[int, object], dtype: str, max_requests: int, devic
             width = max(width, in_len + 64, (l.out_len() + 64) if i < n - 1 else 0)
             if m.weights[i] is not None:
                 k = l.in_features if l.kind == B.MT_FC else 9 * ((l.in_features + 7) // 8 * 8)
-                arena += (l.out_features * ((k + 63) // 64 * 64) * es + 255) // 256 * 256 + (l.out_features * 4 + 255) // 256 * 256
+                n_pad = (l.out_features + 63) // 64 * 64
+                arena += (n_pad * ((k + 63) // 64 * 64) * es + 255) // 256 * 256 + (n_pad * 4 + 255) // 256 * 256
         classes = max(classes, m.layers[-1].out_len())
     T = max_tenants if max_tenants is not None else (max(tenants) + 1 if tenants else 1)
     return B.Context(T, max_requests, width, classes, int(arena * arena_slack) + (1 << 20),

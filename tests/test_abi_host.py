@@ -98,16 +98,17 @@ def test_cnn_chain_is_accepted():
              B.layer_spec(B.MT_GAP, B.MT_ACT_NONE, 128, 128, 8, 8),
              fc(128, 10)]
     c.register_model(3, specs, *zeros_for(specs))
-    # packed sizes: K padded to 64 elements per row (conv1: 9*8=72 -> 128), 256-byte aligned slices
+    # packed sizes: K padded to 64 elements per row (conv1: 9*8=72 -> 128), the logits layer's
+    # rows padded to 32, 256-byte aligned slices
     exp = sum((n * k * 2 + 255) // 256 * 256 + (n * 4 + 255) // 256 * 256
-              for n, k in ((32, 128), (64, 320), (128, 576), (10, 128)))
+              for n, k in ((32, 128), (64, 320), (128, 576), (32, 128)))
     assert c.stats()["arena_used"] == exp
 
 
 def test_arena_accounting_exhaustion_and_reuse():
-    c = host_ctx(arena=300_000)
-    specs = [fc(64, 512, B.MT_ACT_RELU), fc(512, 10)]            # 512*64*2 + 2048 + 10*512*2 + 256 = 78,080
-    per = 512 * 64 * 2 + 512 * 4 + 10 * 512 * 2 + 256
+    c = host_ctx(arena=310_000)
+    specs = [fc(64, 512, B.MT_ACT_RELU), fc(512, 10)]            # logits rows are stored padded to 32
+    per = 512 * 64 * 2 + 512 * 4 + 32 * 512 * 2 + 256
     for t in range(3):
         c.register_model(t, specs, *zeros_for(specs))
     assert c.stats()["arena_used"] == 3 * per
