@@ -76,10 +76,7 @@ struct mt_ctx {
     int32_t* d_perm = nullptr;
     uint32_t* d_M = nullptr;
     uint32_t* d_off = nullptr;
-    uint32_t* d_n_tiles = nullptr;     // [2][MT_MAX_LAYERS]: FC counts, then conv counts
-    uint32_t* d_overflow = nullptr;
-    Tile* d_tiles = nullptr;
-    uint32_t tile_cap = 0;
+    uint32_t* d_tile_base = nullptr;   // [2][MT_MAX_LAYERS][T+1]: FC arrays, then conv arrays
     void* d_act[2] = {nullptr, nullptr};
     float* d_logits = nullptr;
     Segment* h_segs[kSegSlots] = {};    // pinned, device-visible
@@ -300,22 +297,6 @@ void pack_weights(const HostLayer& hl, const void* w_src, uint8_t* dst)
     }
 }
 
-mt_status ensure_tiles(mt_ctx* c)
-{
-    uint64_t need = 1;
-    for (uint32_t l = 0; l < c->n_layer_slots; ++l)
-        for (int k = 0; k < 2; ++k) need = std::max(need, tile_bound(c, k, l, c->cfg.max_requests));
-    if (need <= c->tile_cap) return MT_OK;
-    need = round_up64(need + need / 8, 1024);
-    if (need * 2 * MT_MAX_LAYERS * sizeof(Tile) > (1ull << 32)) return fail(c, MT_ENOMEM, "tile lists would need %llu entries per layer", (unsigned long long)need);
-    HIP_TRY(c, hipDeviceSynchronize());
-    if (c->d_tiles) HIP_TRY(c, hipFree(c->d_tiles));
-    c->d_tiles = nullptr; c->tile_cap = 0;
-    HIP_TRY(c, hipMalloc((void**)&c->d_tiles, need * 2 * MT_MAX_LAYERS * sizeof(Tile)));   // FC lists, then conv lists
-    c->tile_cap = (uint32_t)need;
-    return MT_OK;
-}
-
 }  // namespace
 
 extern "C" {
@@ -364,9 +345,8 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     CREATE_TRY(hipMalloc((void**)&c->d_M, T * 4));
     CREATE_TRY(hipMemset(c->d_M, 0, T * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_off, (T + 1) * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_n_tiles, 2 * MT_MAX_LAYERS * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_overflow, 4));
-    CREATE_TRY(hipMemset(c->d_overflow, 0, 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_tile_base, 2 * MT_MAX_LAYERS * (T + 1) * 4));
+    CREATE_TRY(hipMemset(c->d_tile_base, 0, 2 * MT_MAX_LAYERS * (T + 1) * 4));
     for (int i = 0; i < 2; ++i) {
         CREATE_TRY(hipMalloc(&c->d_act[i], (uint64_t)c->P_cap * c->S * c->elem_size));
     }
@@ -387,7 +367,7 @@ mt_status mt_destroy(mt_ctx* c)
         (void)hipSetDevice(c->cfg.device);
         (void)hipDeviceSynchronize();
         void* bufs[] = {c->d_arena, c->d_tenants, c->d_layers, c->d_row_tenant, c->d_row_rank, (void*)c->d_row_src, c->d_pos_of, c->d_perm,
-                        c->d_M, c->d_off, c->d_n_tiles, c->d_overflow, c->d_tiles, c->d_act[0], c->d_act[1], c->d_logits};
+                        c->d_M, c->d_off, c->d_tile_base, c->d_act[0], c->d_act[1], c->d_logits};
         for (void* p : bufs) if (p) (void)hipFree(p);
         for (uint32_t i = 0; i < kSegSlots; ++i) {
             if (c->h_segs[i]) (void)hipHostFree(c->h_segs[i]);
@@ -529,8 +509,6 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         return fail(c, MT_EINVAL, "row_stride %u is below max_classes %u", out->row_stride, c->cfg.max_classes);
     hipStream_t s = (hipStream_t)hip_stream;
     HIP_TRY(c, hipSetDevice(c->cfg.device));
-    mt_status st = ensure_tiles(c);
-    if (st != MT_OK) return st;
 
     const uint32_t slot = (uint32_t)(c->run_count % kSegSlots);
     if (c->seg_busy[slot]) { HIP_TRY(c, hipEventSynchronize(c->seg_event[slot])); c->seg_busy[slot] = false; }
@@ -544,10 +522,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     b.first = c->pending[0]; b.row_src = c->d_row_src; b.elem_size = c->elem_size;
     b.tenants = c->d_tenants; b.layers = c->d_layers;
     b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
-    b.M = c->d_M; b.off = c->d_off; b.tile_cap = c->tile_cap;
-    b.fc_tiles = c->d_tiles; b.conv_tiles = c->d_tiles + (size_t)MT_MAX_LAYERS * c->tile_cap;
-    b.n_fc_tiles = c->d_n_tiles; b.n_conv_tiles = c->d_n_tiles + MT_MAX_LAYERS;
-    b.overflow = c->d_overflow; b.fc_split_k = c->fc_split_k;
+    b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.fc_split_k = c->fc_split_k;
     if (c->profiling) for (uint32_t i = 0; i < kProfSlots; ++i) c->prof_used[i] = false;
 #define TIMED(slot, call)                                                                   \
     do {                                                                                    \
@@ -571,11 +546,11 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             const uint64_t grid = tile_bound(c, kind, l, R);
             if (grid == 0) continue;
             GemmArgs ga{};
-            ga.tiles = c->d_tiles + ((size_t)kind * MT_MAX_LAYERS + l) * c->tile_cap;
-            ga.n_tiles = c->d_n_tiles + kind * MT_MAX_LAYERS; ga.layer = l;
+            ga.tile_base = c->d_tile_base + ((size_t)kind * MT_MAX_LAYERS + l) * (T + 1);
+            ga.T = T; ga.layer = l; ga.fc_split_k = c->fc_split_k;
             ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad;
-            const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, c->tile_cap);
+            const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, 0x7ffffff0u);
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
             else TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, g32, s));
         }
@@ -614,9 +589,6 @@ mt_status mt_last_counts(mt_ctx* c, uint32_t* counts)
     HIP_TRY(c, hipSetDevice(c->cfg.device));
     HIP_TRY(c, hipStreamSynchronize(c->last_stream));
     HIP_TRY(c, hipMemcpy(counts, c->d_M, (size_t)c->cfg.max_tenants * 4, hipMemcpyDeviceToHost));
-    uint32_t ovf = 0;
-    HIP_TRY(c, hipMemcpy(&ovf, c->d_overflow, 4, hipMemcpyDeviceToHost));
-    if (ovf) return fail(c, MT_EDEVICE, "a tile list overflowed its bound");
     return MT_OK;
 }
 

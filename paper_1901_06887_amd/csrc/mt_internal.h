@@ -66,17 +66,13 @@ struct Segment {
     int32_t tenant;       // used when ids == nullptr
 };
 
-// One unit of grouped work.  FC: rows [m0, m0+rows) of the tenant (m0 a multiple of 32,
-// rows <= kTileRows), column blocks starting at n0; `split` = number of column blocks the
-// four waves cover side by side (4, 2 or 1), the remaining factor 4/split splits K.
-// CONV: a kTileRows x kTileCols output tile of the implicit GEMM.
-struct Tile {
-    uint32_t tenant;      // low 16 bits tenant, bits 16..23 split
-    uint32_t m0;
-    uint32_t rows;
-    uint32_t n0;
-};
-
+// Grouped work of one layer index is described by one array per kind (FC, conv):
+// tile_base[t] = number of workgroup tiles of all tenants before t, tile_base[T] = total.
+// A workgroup finds its tenant by searching that array and derives its tile from the rest:
+//   FC:   tiles of a tenant are numbered column-group-major, 128-row tile minor; a column
+//         group is `split` column blocks of 32 (4, 2 or 1) that the four waves cover side
+//         by side, the remaining factor 4/split splitting K between the waves.
+//   CONV: kTileRows x kTileCols output tiles of the implicit GEMM, column-major likewise.
 struct BatchArgs {
     const Segment* segs; uint32_t n_segs; uint32_t R; uint32_t T; uint32_t n_layer_slots;
     Segment first;         // copy of segs[0]: the common one-segment run never reads host memory
@@ -90,10 +86,7 @@ struct BatchArgs {
     int32_t* perm;         // [P] packed position -> submission index, -1 for padding rows
     uint32_t* M;           // [T]
     uint32_t* off;         // [T+1] packed position of each tenant's first row (multiple of 32)
-    Tile* fc_tiles; Tile* conv_tiles; uint32_t tile_cap;   // n_layer_slots lists of tile_cap entries each
-    uint32_t* n_fc_tiles;  // [n_layer_slots]
-    uint32_t* n_conv_tiles;
-    uint32_t* overflow;    // set to 1 if a tile list would not fit (never expected)
+    uint32_t* tile_base;   // [2][MT_MAX_LAYERS][T+1]: FC arrays, then conv arrays
 };
 
 struct GatherArgs {
@@ -104,7 +97,7 @@ struct GatherArgs {
 };
 
 struct GemmArgs {
-    const Tile* tiles; const uint32_t* n_tiles; uint32_t layer;
+    const uint32_t* tile_base; uint32_t T; uint32_t layer; uint32_t fc_split_k;
     const LayerDev* layers; const uint32_t* off; const uint32_t* M;
     const void* act_in; void* act_out; const uint8_t* arena;
     float* logits; uint32_t S; uint32_t C_pad;

@@ -81,22 +81,60 @@ __device__ __forceinline__ void fc_shape(uint32_t n_pad, uint32_t split_k, uint3
     *groups = ceil_div(nblk, s);
 }
 
-// Tenant segmentation and tile lists.  One workgroup; every step is deterministic:
-// rows of a tenant keep their arrival order (stable counting sort).  Equal tenant ids
-// inside a wavefront are found with one ballot per id bit, so a step costs the same
-// whatever the tenant mix is.
+constexpr uint32_t kLists = 2 * MT_MAX_LAYERS;       // FC and conv tile-count arrays of every layer index
+
+// Tenant segmentation and grouped-work descriptors.  One workgroup; every step is
+// deterministic: rows of a tenant keep their arrival order (stable counting sort).  Equal
+// tenant ids inside a wavefront are found with one ballot per id bit, so a step costs the
+// same whatever the tenant mix is.  Latency, not bandwidth, bounds this kernel, so everything
+// that does not depend on the rows (tenant and layer facts) is fetched up front, tenant ids
+// are fetched one step ahead, and all tile-count arrays are scanned in one pass.
 __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 {
     __shared__ uint32_t hist[kHistEntries];
     __shared__ uint32_t Ml[kMaxTenantsPadded];
     __shared__ uint32_t offl[kMaxTenantsPadded];
-    __shared__ uint32_t cnt[kMaxTenantsPadded];
-    __shared__ uint32_t cnt2[kMaxTenantsPadded];
+    __shared__ uint8_t regl[kMaxTenantsPadded];
     __shared__ uint32_t tmp[17];
+    __shared__ uint32_t wtot[kBatchThreads / 64 + 1][kLists];
     __shared__ Segment seg_l[kSegsInLds];
 
     const uint32_t tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const uint32_t T = a.T, R = a.R;
+    const uint32_t T = a.T, R = a.R, NL = a.n_layer_slots;
+    uint32_t Tp = 64, bits = 6;
+    while (Tp < T) { Tp <<= 1; ++bits; }
+    const uint32_t nslots = Tp > kBatchThreads ? 2 : 1;
+
+    // tenant and layer facts of tenants tid and tid + 1024: column groups per layer (0 = no
+    // tiles) and rows per request with the kind in the top bit (1 = conv)
+    uint32_t grp[2][MT_MAX_LAYERS], rpr[2][MT_MAX_LAYERS];
+#pragma unroll
+    for (uint32_t slot = 0; slot < 2; ++slot) {
+        const uint32_t t = tid + slot * kBatchThreads;
+        uint32_t nl = 0;
+        if (slot < nslots && t < Tp) {
+            const bool reg = t < T && a.tenants[t].registered;
+            regl[t] = reg;
+            nl = reg ? a.tenants[t].n_layers : 0;
+        }
+#pragma unroll
+        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
+            grp[slot][l] = 0; rpr[slot][l] = 1;
+            if (l < nl) {
+                const LayerDev& L = a.layers[t * MT_MAX_LAYERS + l];
+                const uint32_t kind = L.kind;
+                if (kind == MT_FC) {
+                    uint32_t split, groups;
+                    fc_shape(L.N_pad, a.fc_split_k, &split, &groups);
+                    grp[slot][l] = groups;
+                } else if (kind == MT_CONV2D) {
+                    grp[slot][l] = ceil_div(L.N, kTileCols);
+                    rpr[slot][l] = L.rows_per_req | 0x80000000u;
+                }
+            }
+        }
+    }
+
     // the segment table sits in host memory: stage it in LDS when it is small
     const Segment* segs = a.segs;
     if (a.n_segs <= kSegsInLds) {
@@ -104,27 +142,27 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         else for (uint32_t i = tid; i < a.n_segs; i += kBatchThreads) seg_l[i] = a.segs[i];
         segs = seg_l;
     }
-    uint32_t Tp = 64, bits = 6;
-    while (Tp < T) { Tp <<= 1; ++bits; }
     const uint32_t nw = min(kBatchThreads / 64, kHistEntries / Tp);
     const uint32_t chunk = ceil_div(ceil_div(R, nw), 64) * 64;
-
     for (uint32_t i = tid; i < nw * Tp; i += kBatchThreads) hist[i] = 0;
     __syncthreads();
 
     // pass 1: per-wave histograms and in-wave ranks
     if (w < nw) {
         const uint32_t begin = w * chunk, end = min(begin + chunk, R);
+        auto fetch_id = [&](uint32_t r) -> int32_t {
+            if (r >= end) return -1;
+            const Segment& sg = segs[find_segment(segs, a.n_segs, r)];
+            a.row_src[r] = (const uint8_t*)sg.src + (size_t)(r - sg.row_begin) * sg.row_stride * a.elem_size;
+            return sg.ids ? sg.ids[r - sg.row_begin] : sg.tenant;
+        };
+        int32_t t_next = begin < end ? fetch_id(begin + lane) : -1;
         for (uint32_t base = begin; base < end; base += 64) {
             const uint32_t r = base + lane;
-            int32_t t = -1;
-            if (r < end) {
-                const Segment sg = segs[find_segment(segs, a.n_segs, r)];
-                t = sg.ids ? sg.ids[r - sg.row_begin] : sg.tenant;
-                if (t < 0 || (uint32_t)t >= T || !a.tenants[t].registered) t = -1;
-                a.row_tenant[r] = t;
-                a.row_src[r] = (const uint8_t*)sg.src + (size_t)(r - sg.row_begin) * sg.row_stride * a.elem_size;
-            }
+            int32_t t = t_next;
+            if (base + 64 < end) t_next = fetch_id(r + 64);
+            if (t < 0 || (uint32_t)t >= T || !regl[t]) t = -1;
+            if (r < end) a.row_tenant[r] = t;
             uint64_t peers = __ballot(t >= 0);
             for (uint32_t b = 0; b < bits; ++b) {
                 const bool bit = (t >> b) & 1;
@@ -161,6 +199,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     if (tid == 0) a.off[T] = total;
 
     // pass 3: packed position of every row
+#pragma unroll 4
     for (uint32_t r = tid; r < R; r += kBatchThreads) {
         const int32_t t = a.row_tenant[r];
         int32_t pos = -1;
@@ -171,56 +210,48 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         a.pos_of[r] = pos;
     }
 
-    // pass 4: tile lists of every layer index (FC and conv separately)
-    for (uint32_t l = 0; l < a.n_layer_slots; ++l) {
-        __syncthreads();
-        for (uint32_t t = tid; t < Tp; t += kBatchThreads) {
-            uint32_t cf = 0, cc = 0;
-            if (t < T && Ml[t] > 0 && a.tenants[t].registered && a.tenants[t].n_layers > l) {
-                const LayerDev& L = a.layers[t * MT_MAX_LAYERS + l];
-                if (L.kind == MT_FC) {
-                    uint32_t split, groups;
-                    fc_shape(L.N_pad, a.fc_split_k, &split, &groups);
-                    cf = ceil_div(Ml[t], kTileRows) * groups;
-                } else if (L.kind == MT_CONV2D) {
-                    cc = ceil_div(Ml[t] * L.rows_per_req, kTileRows) * ceil_div(L.N, kTileCols);
-                }
+    // pass 4: tile counts of every (kind, layer) list, scanned over tenants in one vector scan
+    uint32_t carry[kLists];
+#pragma unroll
+    for (uint32_t i = 0; i < kLists; ++i) carry[i] = 0;
+    for (uint32_t slot = 0; slot < nslots; ++slot) {
+        const uint32_t t = tid + slot * kBatchThreads;
+        const uint32_t Mt = t < Tp ? Ml[t] : 0;
+        uint32_t c[kLists], incl[kLists];
+#pragma unroll
+        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
+            const uint32_t g = slot == 0 ? grp[0][l] : grp[1][l], rr = slot == 0 ? rpr[0][l] : rpr[1][l];
+            const uint32_t tiles = (g && Mt) ? ceil_div(Mt * (rr & 0x7fffffffu), kTileRows) * g : 0;
+            const bool conv = rr >> 31;
+            c[l] = conv ? 0 : tiles;
+            c[MT_MAX_LAYERS + l] = conv ? tiles : 0;
+        }
+#pragma unroll
+        for (uint32_t i = 0; i < kLists; ++i) {
+            uint32_t v = c[i];
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t o = __shfl_up(v, d);
+                if (lane >= (uint32_t)d) v += o;
             }
-            cnt[t] = cf; cnt2[t] = cc;
+            incl[i] = v;
+            if (lane == 63) wtot[w][i] = v;
         }
         __syncthreads();
-        for (int kind = 0; kind < 2; ++kind) {
-            uint32_t* c = kind == 0 ? cnt : cnt2;
-            uint32_t n = block_exclusive_scan(c, Tp, tmp);
-            if (n > a.tile_cap) { if (tid == 0) *a.overflow = 1; n = a.tile_cap; }
-            if (tid == 0) (kind == 0 ? a.n_fc_tiles : a.n_conv_tiles)[l] = n;
-            Tile* out = (kind == 0 ? a.fc_tiles : a.conv_tiles) + (size_t)l * a.tile_cap;
-            for (uint32_t i = tid; i < n; i += kBatchThreads) {
-                uint32_t lo = 0, hi = Tp;           // last t with c[t] <= i
-                while (hi - lo > 1) { uint32_t mid = (lo + hi) >> 1; if (c[mid] <= i) lo = mid; else hi = mid; }
-                const LayerDev& L = a.layers[lo * MT_MAX_LAYERS + l];
-                const uint32_t local = i - c[lo];
-                Tile tl;
-                if (kind == 0) {
-                    uint32_t split, groups;
-                    fc_shape(L.N_pad, a.fc_split_k, &split, &groups);
-                    const uint32_t mt_ = ceil_div(Ml[lo], kTileRows);
-                    tl.tenant = lo | (split << 16);
-                    tl.m0 = (local % mt_) * kTileRows;
-                    tl.rows = min((uint32_t)kTileRows, Ml[lo] - tl.m0);
-                    tl.n0 = (local / mt_) * split * kBrickRows;
-                } else {
-                    const uint32_t rows = Ml[lo] * L.rows_per_req;
-                    const uint32_t mt_ = ceil_div(rows, kTileRows);
-                    tl.tenant = lo;
-                    tl.m0 = (local % mt_) * kTileRows;
-                    tl.rows = min((uint32_t)kTileRows, rows - tl.m0);
-                    tl.n0 = (local / mt_) * kTileCols;
-                }
-                out[i] = tl;
-            }
+        if (tid < kLists) {
+            uint32_t run = 0;
+            for (uint32_t ww = 0; ww < kBatchThreads / 64; ++ww) { const uint32_t x = wtot[ww][tid]; wtot[ww][tid] = run; run += x; }
+            wtot[kBatchThreads / 64][tid] = run;
         }
+        __syncthreads();
+#pragma unroll
+        for (uint32_t i = 0; i < kLists; ++i) {
+            if ((i % MT_MAX_LAYERS) < NL && t < T)
+                a.tile_base[(size_t)i * (T + 1) + t] = carry[i] + wtot[w][i] + incl[i] - c[i];
+            carry[i] += wtot[kBatchThreads / 64][i];
+        }
+        __syncthreads();
     }
+    if (tid < kLists && (tid % MT_MAX_LAYERS) < NL) a.tile_base[(size_t)tid * (T + 1) + T] = carry[tid];
 }
 
 // ---- gather: one workgroup per block of 32 packed rows ------------------------------------
@@ -315,30 +346,193 @@ template <> struct Mma<float> {
     }
 };
 
+// What a workgroup works on, derived from its block index and the list's tile_base array.
+struct Tile {
+    uint32_t tenant, m0, rows, n0, split;
+};
+
+// XCD-aware numbering: consecutive block indices go to different XCDs (each with its own L2),
+// so the logical tile index is chosen such that every XCD gets one contiguous run of tiles;
+// tiles that re-read the same weight panel (the 128-row tiles of one column group) then
+// share an L2.  Returns false for blocks past the end of the list.
+__device__ __forceinline__ bool logical_tile(uint32_t n_tiles, uint32_t* logical)
+{
+    const uint32_t per_xcd = (n_tiles + 7) / 8, b = blockIdx.x;
+    *logical = (b & 7) * per_xcd + (b >> 3);
+    return (b >> 3) < per_xcd && *logical < n_tiles;
+}
+
+// Tenant that owns logical tile `idx`: last t with base[t] <= idx (base is in LDS, base[T] > idx).
+__device__ __forceinline__ uint32_t find_tenant(const uint32_t* base, uint32_t T, uint32_t idx)
+{
+    uint32_t lo = 0, hi = T;
+    while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (base[mid] <= idx) lo = mid; else hi = mid; }
+    return lo;
+}
+
 // ---- grouped FC ------------------------------------------------------------------------------
 // A workgroup of four waves owns up to 128 rows (RB row blocks of 32) of one tenant and
-// `split` column blocks of 32; with split < 4 the waves also split K between them and the
-// partial sums are added in a fixed order through LDS.  Every wave streams its weight bricks
-// and the activation bricks it needs straight from memory into MFMA operands, keeping a ring
-// of P bricks in flight; there is no LDS staging and no barrier in the K loop.
+// `split` column blocks of 32.  Weight bricks never touch LDS: every wave streams the bricks
+// of its own column block straight from memory into MFMA B operands through a ring of
+// registers that keeps P bricks in flight.
+//   split == 4 (the common case): the four waves share the same activation bricks, so those
+//     are staged once per workgroup in LDS, 16 bricks per chunk, double buffered, one barrier
+//     per chunk; LDS reads of a brick are 16 contiguous bytes per lane, conflict free.
+//   split < 4 (layers with at most 64 outputs): the waves also split K between them, read
+//     their own activation bricks directly, and the partial sums are added in a fixed order
+//     through LDS (deterministic, no atomics).
 constexpr uint32_t kRedFloats = 4 * 16 * 64;                 // one f32x16 per lane per wave
 constexpr uint32_t kTrRowBytes = 32 * 4 + 16;                // transposition scratch row (fp32 worst case)
 constexpr uint32_t kTrBytes = 32 * kTrRowBytes;
+constexpr uint32_t kChunkBricks = 16;                        // activation bricks per LDS stage
+constexpr uint32_t kStageBytes = kChunkBricks * kBrickBytes;
+// LDS of the FC kernel, 34 KiB so that four workgroups fit a CU.  K loop: two activation
+// stages (split == 4).  After the K loop: reduction scratch (split < 4 only) at offset 0 and
+// transposition scratch at kTrOffset; both alias the stages, separated from them by barriers.
+constexpr uint32_t kTrOffset = kRedFloats * 4;
+constexpr uint32_t kFcLdsBytes = kTrOffset + 4 * kTrBytes;
+static_assert(kFcLdsBytes >= 2 * kStageBytes, "the two activation stages must fit");
+
+// split == 4: activations through LDS, weights through the register ring.
+template <typename T, int RB>
+__device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Tile& tl, const LayerDev& L, uint32_t seg0,
+                                                     uint32_t nb, bool active, uint8_t* stages, f32x16 (&acc)[RB])
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    constexpr uint32_t KC = kChunkBricks / RB;               // k steps per chunk
+    constexpr uint32_t P = KC < 8 ? KC : 8;                  // weight bricks in flight per wave
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t nKB = L.K / KB;
+    const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
+    const uint32_t nb_eff = active ? nb : 0;                 // idle waves still help staging; they stream block 0 and drop it
+    const u32x4* wp = (const u32x4*)(a.arena + L.w_off) + (size_t)nb_eff * nKB * 64 + lane;
+    const u32x4* xbase = (const u32x4*)((const T*)a.act_in + (size_t)seg0 * a.S) + lane;
+
+    // this wave stages bricks q = 4*wave .. 4*wave+3 of every chunk: row block q / KC, k step q % KC
+    const u32x4* xsrc[4]; uint32_t xkk[4];
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) {
+        const uint32_t q = wave * 4 + j, r = q / KC;
+        xkk[j] = q % KC;
+        const uint32_t rbi = tl.m0 / kBrickRows + min(r, nrb - 1);     // blocks past the tile repeat its last one
+        xsrc[j] = xbase + (size_t)rbi * nKB * 64;
+    }
+    auto load_chunk = [&](uint32_t c, u32x4 (&xr)[4]) {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) xr[j] = xsrc[j][(size_t)min(c * KC + xkk[j], nKB - 1) * 64];
+    };
+    auto store_chunk = [&](uint32_t stage, const u32x4 (&xr)[4]) {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) *(u32x4*)(stages + stage * kStageBytes + (wave * 4 + j) * kBrickBytes + lane * 16) = xr[j];
+    };
+
+    u32x4 bq[P], xr[4];
+#pragma unroll
+    for (uint32_t j = 0; j < P; ++j) bq[j] = wp[(size_t)min(j, nKB - 1) * 64];
+    const uint32_t n_chunks = (nKB + KC - 1) / KC, full_chunks = nKB / KC;
+    load_chunk(0, xr);
+    store_chunk(0, xr);
+    load_chunk(1, xr);                                        // clamped when there is no chunk 1
+    for (uint32_t c = 0; c < full_chunks; ++c) {
+        __syncthreads();                                      // stage c&1 is complete; stage (c+1)&1 is free again
+        store_chunk((c + 1) & 1, xr);
+        load_chunk(c + 2, xr);
+        const uint8_t* st = stages + (c & 1) * kStageBytes + lane * 16;
+        // groups of P k steps; the scheduling fences keep the compiler from hoisting every LDS
+        // read of the chunk to its top (which would cost registers, hence resident waves)
+        for (uint32_t g = 0; g < KC / P; ++g) {
+#pragma unroll
+            for (uint32_t j = 0; j < P; ++j) {
+                const uint32_t kk = g * P + j;
+                u32x4 av[RB];
+#pragma unroll
+                for (int r = 0; r < RB; ++r) av[r] = *(const u32x4*)(st + (r * KC + kk) * kBrickBytes);
+#pragma unroll
+                for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], av[r], bq[j]);
+                bq[j] = wp[(size_t)min(c * KC + kk + P, nKB - 1) * 64];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    if (full_chunks < n_chunks) {                             // ragged last chunk
+        __syncthreads();
+        const uint32_t c = full_chunks, rem = nKB - c * KC;
+        const uint8_t* st = stages + (c & 1) * kStageBytes + lane * 16;
+#pragma unroll
+        for (uint32_t kk = 0; kk < KC; ++kk) {
+            if (kk < rem) {
+#pragma unroll
+                for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], *(const u32x4*)(st + (r * KC + kk) * kBrickBytes), bq[kk % P]);
+                bq[kk % P] = wp[(size_t)min(c * KC + kk + P, nKB - 1) * 64];      // rem may exceed the ring
+            }
+        }
+    }
+}
+
+// split < 4: every wave reads the activation bricks of its own K range directly.
+template <typename T, int RB, int P>
+__device__ __forceinline__ void fc_accumulate_direct(const GemmArgs& a, const Tile& tl, const LayerDev& L, uint32_t seg0,
+                                                     uint32_t nb, uint32_t kq, uint32_t ks, f32x16 (&acc)[RB])
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t nKB = L.K / KB;
+    const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
+    const uint32_t cnt = nKB / ks, kb0 = kq * cnt;
+    const u32x4* wp = (const u32x4*)(a.arena + L.w_off) + ((size_t)nb * nKB + kb0) * 64 + lane;
+    const u32x4* xbase = (const u32x4*)((const T*)a.act_in + (size_t)seg0 * a.S) + lane;
+    const u32x4* xp[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        const uint32_t rbi = tl.m0 / kBrickRows + min((uint32_t)r, nrb - 1);
+        xp[r] = xbase + ((size_t)rbi * nKB + kb0) * 64;
+    }
+    u32x4 bq[P], aq[RB][P];
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        const uint32_t kk = min((uint32_t)j, cnt - 1);
+        bq[j] = wp[(size_t)kk * 64];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) aq[r][j] = xp[r][(size_t)kk * 64];
+    }
+    // steady state: straight-line groups of P bricks, each slot refilled right after use; the
+    // clamped refill index re-reads the last brick instead of branching
+    const uint32_t full = cnt / P;
+    for (uint32_t g = 0; g < full; ++g) {
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], aq[r][j], bq[j]);
+            const uint32_t kk = min(g * P + j + P, cnt - 1);
+            bq[j] = wp[(size_t)kk * 64];
+#pragma unroll
+            for (int r = 0; r < RB; ++r) aq[r][j] = xp[r][(size_t)kk * 64];
+        }
+    }
+    const uint32_t rem = cnt - full * P;                      // the slots already hold the remaining bricks
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        if ((uint32_t)j < rem) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], aq[r][j], bq[j]);
+        }
+    }
+}
 
 template <typename T, int RB, int P>
-__device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const LayerDev& L, uint32_t t, uint32_t split,
-                                        float* red, uint8_t* tr)
+__device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const LayerDev& L, uint32_t Mt, uint8_t* smem)
 {
+    const uint32_t t = tl.tenant, split = tl.split;
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t li = lane & 31, lh = lane >> 5;
     const uint32_t ks = 4 / split;
     const uint32_t nb = tl.n0 / kBrickRows + (wave % split), kq = wave / split;
-    const uint32_t nKB = L.K / KB;
     const bool active = nb < L.N_pad / kBrickRows;
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
-    const uint32_t cnt = nKB / ks, kb0 = kq * cnt;
     const uint32_t seg0 = a.off[t];
+    float* red = (float*)smem;                                // both alias the stages, used after the K loop only
+    uint8_t* tr = smem + kTrOffset;
 
     f32x16 acc[RB];
 #pragma unroll
@@ -346,51 +540,11 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[r][v] = 0.0f;
 
-    if (active) {
-        const u32x4* wp = (const u32x4*)(a.arena + L.w_off) + ((size_t)nb * nKB + kb0) * 64 + lane;
-        const u32x4* xbase = (const u32x4*)((const T*)a.act_in + (size_t)seg0 * a.S) + lane;
-        const u32x4* xp[RB];
-#pragma unroll
-        for (int r = 0; r < RB; ++r) {
-            const uint32_t rbi = tl.m0 / kBrickRows + min((uint32_t)r, nrb - 1);   // blocks past the tile repeat its last one
-            xp[r] = xbase + ((size_t)rbi * nKB + kb0) * 64;
-        }
-        u32x4 bq[P], aq[RB][P];
-#pragma unroll
-        for (int j = 0; j < P; ++j) {
-            const uint32_t kk = min((uint32_t)j, cnt - 1);
-            bq[j] = wp[(size_t)kk * 64];
-#pragma unroll
-            for (int r = 0; r < RB; ++r) aq[r][j] = xp[r][(size_t)kk * 64];
-        }
-        // steady state: straight-line groups of P bricks, each slot refilled right after use, so
-        // P-1 slots stay in flight behind every MFMA; the clamped refill index re-reads the last
-        // brick instead of branching
-        const uint32_t full = cnt / P;
-        for (uint32_t g = 0; g < full; ++g) {
-#pragma unroll
-            for (int j = 0; j < P; ++j) {
-#pragma unroll
-                for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], aq[r][j], bq[j]);
-                const uint32_t kk = min(g * P + j + P, cnt - 1);
-                bq[j] = wp[(size_t)kk * 64];
-#pragma unroll
-                for (int r = 0; r < RB; ++r) aq[r][j] = xp[r][(size_t)kk * 64];
-            }
-        }
-        // tail: the slots already hold bricks full*P .. full*P+P-1 (clamped)
-        const uint32_t rem = cnt - full * P;
-#pragma unroll
-        for (int j = 0; j < P; ++j) {
-            if ((uint32_t)j < rem) {
-#pragma unroll
-                for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], aq[r][j], bq[j]);
-            }
-        }
-    }
-
-    // K-split: waves with kq > 0 hand their partial sums to the kq == 0 wave of the same column block
-    if (ks > 1) {
+    if (ks == 1) {
+        fc_accumulate_shared<T, RB>(a, tl, L, seg0, nb, active, smem, acc);
+    } else {
+        if (active) fc_accumulate_direct<T, RB, P>(a, tl, L, seg0, nb, kq, ks, acc);
+        // waves with kq > 0 hand their partial sums to the kq == 0 wave of the same column block
 #pragma unroll
         for (int r = 0; r < RB; ++r) {
             __syncthreads();
@@ -415,7 +569,6 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
     const float bv = writer ? bias[n] : 0.0f;
     if (L.is_last) {
         if (!writer || n >= L.N) return;
-        const uint32_t Mt = a.M[t];
 #pragma unroll
         for (int r = 0; r < RB; ++r) {
 #pragma unroll
@@ -456,19 +609,32 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void fc_kernel(GemmArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void fc_kernel(GemmArgs a)
 {
-    __shared__ __attribute__((aligned(16))) float red[kRedFloats];
-    __shared__ __attribute__((aligned(16))) uint8_t tr[4 * kTrBytes];
-    const uint32_t tile_id = blockIdx.x;
-    if (tile_id >= a.n_tiles[a.layer]) return;
-    const Tile tl = a.tiles[tile_id];
-    const uint32_t t = tl.tenant & 0xffff, split = (tl.tenant >> 16) & 0xff;
-    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    __shared__ __attribute__((aligned(16))) uint8_t smem[kFcLdsBytes];    // also holds tile_base during the lookup
+    uint32_t* base_l = (uint32_t*)smem;
+    static_assert(kFcLdsBytes >= (kMaxTenantsPadded + 1) * 4, "tile_base must fit");
+    const uint32_t n_tiles = a.tile_base[a.T];
+    for (uint32_t i = threadIdx.x; i <= a.T; i += 256) base_l[i] = a.tile_base[i];
+    uint32_t idx;
+    if (!logical_tile(n_tiles, &idx)) return;
+    __syncthreads();
+    Tile tl;
+    tl.tenant = find_tenant(base_l, a.T, idx);
+    const uint32_t local = idx - base_l[tl.tenant];
+    __syncthreads();                                          // the lookup is over before anything reuses smem
+    const LayerDev L = a.layers[tl.tenant * MT_MAX_LAYERS + a.layer];
+    const uint32_t Mt = a.M[tl.tenant];
+    uint32_t groups;
+    fc_shape(L.N_pad, a.fc_split_k, &tl.split, &groups);
+    const uint32_t mt_ = ceil_div(Mt, kTileRows);
+    tl.m0 = (local % mt_) * kTileRows;
+    tl.rows = min((uint32_t)kTileRows, Mt - tl.m0);
+    tl.n0 = (local / mt_) * tl.split * kBrickRows;
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
-    if (nrb <= 1) fc_tile<T, 1, 8>(a, tl, L, t, split, red, tr);
-    else if (nrb == 2) fc_tile<T, 2, 6>(a, tl, L, t, split, red, tr);
-    else fc_tile<T, 4, 4>(a, tl, L, t, split, red, tr);
+    if (nrb <= 1) fc_tile<T, 1, 8>(a, tl, L, Mt, smem);
+    else if (nrb == 2) fc_tile<T, 2, 4>(a, tl, L, Mt, smem);
+    else fc_tile<T, 4, 2>(a, tl, L, Mt, smem);
 }
 
 // ---- grouped 3x3 convolution as implicit GEMM ---------------------------------------------
@@ -485,13 +651,26 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
     constexpr uint32_t EPC = 16 / sizeof(T);          // elements per 16-byte chunk
     constexpr uint32_t EPS = kRowBytes / sizeof(T);   // elements of K per step
 
-    const uint32_t tile_id = blockIdx.x;
-    if (tile_id >= a.n_tiles[a.layer]) return;
-    const Tile tl = a.tiles[tile_id];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t* base_l = (uint32_t*)lds;                 // tile_base during the lookup, operand tiles afterwards
+    const uint32_t n_tiles = a.tile_base[a.T];
+    for (uint32_t i = tid; i <= a.T; i += 256) base_l[i] = a.tile_base[i];
+    uint32_t idx;
+    if (!logical_tile(n_tiles, &idx)) return;
+    __syncthreads();
+    Tile tl;
+    tl.tenant = find_tenant(base_l, a.T, idx);
+    const uint32_t local = idx - base_l[tl.tenant];
+    __syncthreads();                                   // everyone is done with base_l before the tiles overwrite it
     const LayerDev L = a.layers[tl.tenant * MT_MAX_LAYERS + a.layer];
     const uint32_t seg0 = a.off[tl.tenant];
-
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    {
+        const uint32_t rows = a.M[tl.tenant] * L.rows_per_req, mt_ = ceil_div(rows, kTileRows);
+        tl.m0 = (local % mt_) * kTileRows;
+        tl.rows = min((uint32_t)kTileRows, rows - tl.m0);
+        tl.n0 = (local / mt_) * kTileCols;
+        tl.split = 0;
+    }
     const uint32_t wm = wave >> 1, wn = wave & 1;
     const uint32_t li = lane & 31, lh = lane >> 5;
 
@@ -694,6 +873,7 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
 hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)
 {
     if (grid == 0) return hipSuccess;
+    grid = (grid + 7) / 8 * 8;
     if (dtype == MT_BF16) hipLaunchKernelGGL(fc_kernel<__bf16>, dim3(grid), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(fc_kernel<float>, dim3(grid), dim3(256), 0, s, a);
     return hipGetLastError();
@@ -701,6 +881,7 @@ hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream
 hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)
 {
     if (grid == 0) return hipSuccess;
+    grid = (grid + 7) / 8 * 8;
     if (dtype == MT_BF16) hipLaunchKernelGGL(conv_kernel<__bf16>, dim3(grid), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(conv_kernel<float>, dim3(grid), dim3(256), 0, s, a);
     return hipGetLastError();
