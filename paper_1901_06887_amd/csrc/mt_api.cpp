@@ -63,6 +63,9 @@ struct mt_ctx {
     uint32_t max_rpr[2][MT_MAX_LAYERS]{}, max_nt[2][MT_MAX_LAYERS]{}, has_gap[MT_MAX_LAYERS]{};
     uint64_t sum_nt[2][MT_MAX_LAYERS]{};
     uint32_t fc_split_k = 0;   // tuning: FC tiles of one column block with K split four ways
+    uint32_t no_fused_gather = 0;  // tuning/testing: always stage FC inputs with the gather kernel
+    bool fc_first_chunked = true;  // every registered FC-first model's input is a whole number of 16-byte chunks
+    bool any_conv_first = false, any_fc_first = false;
     uint32_t P_cap = 0;        // packed rows incl. per-tenant padding to 32
 
     // device state
@@ -160,6 +163,7 @@ void recompute_bounds(mt_ctx* c)
 {
     c->n_layer_slots = 0;
     c->max_in_len = 0;
+    c->fc_first_chunked = true; c->any_conv_first = c->any_fc_first = false;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
         c->has_gap[l] = 0;
         for (int k = 0; k < 2; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
@@ -168,6 +172,12 @@ void recompute_bounds(mt_ctx* c)
         if (!t.registered) continue;
         c->n_layer_slots = std::max(c->n_layer_slots, t.n_layers);
         c->max_in_len = std::max(c->max_in_len, t.dev.in_len);
+        if (t.dev.in_layout == kLayoutBricks) {
+            c->any_fc_first = true;
+            if ((t.dev.in_len * c->elem_size) % 16) c->fc_first_chunked = false;
+        } else {
+            c->any_conv_first = true;
+        }
         for (uint32_t l = 0; l < t.n_layers; ++l) {
             const LayerDev& L = t.layers[l].dev;
             if (L.kind == MT_GAP) { c->has_gap[l] = 1; continue; }
@@ -184,7 +194,9 @@ void recompute_bounds(mt_ctx* c)
 uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R)
 {
     if (c->max_nt[kind][l] == 0) return 0;
-    return (uint64_t)c->max_nt[kind][l] * (R * c->max_rpr[kind][l] / kTileRows) + c->sum_nt[kind][l];
+    // FC tiles may be as short as 64 rows (layers with at most 64 outputs)
+    const uint64_t tile_rows = kind == 0 ? kTileRows / 2 : kTileRows;
+    return (uint64_t)c->max_nt[kind][l] * (R * c->max_rpr[kind][l] / tile_rows) + c->sum_nt[kind][l];
 }
 
 // ---- validation of a layer chain; fills dev layouts (without arena offsets) -------------
@@ -211,7 +223,7 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
             if (l > 0 && specs[l - 1].kind == MT_CONV2D)
                 return fail(c, MT_EUNSUPPORTED, "layer %u: an FC layer cannot read a convolution's output directly; pool first", l);
             in_len = s.in_features;
-            d.K = round_up(s.in_features, kWidthAlign); d.N = s.out_features;
+            d.K = round_up(s.in_features, kWidthAlign); d.k_valid = s.in_features; d.N = s.out_features;
             d.N_pad = round_up(s.out_features, d.is_last ? kBrickRows : kWidthAlign);
             d.out_len = s.out_features;
             hl.w_bytes = (uint64_t)d.N_pad * d.K * es; hl.b_bytes = (uint64_t)d.N_pad * 4;
@@ -322,6 +334,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     c->C_pad = round_up(cfg->max_classes, 4);
     c->P_cap = round_up(cfg->max_requests, kBrickRows) + kBrickRows * std::min(cfg->max_tenants, cfg->max_requests);
     if (const char* e = getenv("MT_FC_SPLIT_K")) c->fc_split_k = atoi(e) != 0;
+    if (const char* e = getenv("MT_NO_FUSED_GATHER")) c->no_fused_gather = atoi(e) != 0;
     c->tenants.resize(cfg->max_tenants);
     c->cfg.arena_bytes = cfg->arena_bytes / kArenaAlign * kArenaAlign;
     c->free_list.push_back(FreeBlock{0, c->cfg.arena_bytes});
@@ -532,12 +545,21 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     } while (0)
     TIMED(kProfBatcher, launch_batcher(b, s));
 
-    GatherArgs g{};
+    // The FC kernel of layer 0 reads the submitted rows itself when every row is 16-byte aligned
+    // and a whole number of 16-byte chunks long; otherwise (and for CNN models, whose images are
+    // channel-padded) a gather pass stages the inputs first.
+    bool fuse_gather = c->any_fc_first && c->fc_first_chunked && !c->no_fused_gather;
+    for (const Segment& sg : c->pending)
+        if (((uintptr_t)sg.src & 15) || ((uint64_t)sg.row_stride * c->elem_size) % 16) fuse_gather = false;
     // packed rows: every tenant with traffic pads its segment to a multiple of 32
     const uint32_t P = std::min<uint64_t>(c->P_cap, (uint64_t)round_up(R, kBrickRows) + (uint64_t)kBrickRows * std::min(R, c->n_registered));
-    g.row_src = c->d_row_src; g.P = P; g.tenants = c->d_tenants; g.layers = c->d_layers; g.row_tenant = c->d_row_tenant;
-    g.perm = c->d_perm; g.off = c->d_off; g.T = T; g.act = c->d_act[0]; g.S = c->S; g.elem_size = c->elem_size;
-    TIMED(kProfGather, launch_gather(g, s));
+    if (!fuse_gather || c->any_conv_first) {
+        GatherArgs g{};
+        g.row_src = c->d_row_src; g.P = P; g.tenants = c->d_tenants; g.layers = c->d_layers; g.row_tenant = c->d_row_tenant;
+        g.perm = c->d_perm; g.off = c->d_off; g.T = T; g.act = c->d_act[0]; g.S = c->S; g.elem_size = c->elem_size;
+        g.skip_bricks = fuse_gather;
+        TIMED(kProfGather, launch_gather(g, s));
+    }
 
     for (uint32_t l = 0; l < c->n_layer_slots; ++l) {
         const void* in = c->d_act[l & 1];
@@ -548,6 +570,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             GemmArgs ga{};
             ga.tile_base = c->d_tile_base + ((size_t)kind * MT_MAX_LAYERS + l) * (T + 1);
             ga.T = T; ga.layer = l; ga.fc_split_k = c->fc_split_k;
+            ga.gather = (kind == 0 && l == 0 && fuse_gather); ga.perm = c->d_perm; ga.row_src = c->d_row_src;
             ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad;
             const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, 0x7ffffff0u);

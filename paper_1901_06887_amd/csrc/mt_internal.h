@@ -31,6 +31,7 @@ enum : uint32_t { kLayoutRows = 0, kLayoutBricks = 1 };
 struct LayerDev {
     uint32_t kind, act;
     uint32_t K;          // reduction length as stored (padded to kWidthAlign), elements
+    uint32_t k_valid;    // FC: true fan-in (the rest of K is zero padding)
     uint32_t N;          // output features (FC) / output channels (CONV)
     uint32_t N_pad;      // FC: weight rows as stored (multiple of 32; of 64 for hidden layers)
     uint32_t in_h, in_w; // CONV / GAP input geometry
@@ -94,10 +95,14 @@ struct GatherArgs {
     const TenantDev* tenants; const LayerDev* layers; const int32_t* row_tenant; const int32_t* perm;
     const uint32_t* off; uint32_t T;
     void* act; uint32_t S; uint32_t elem_size;
+    uint32_t skip_bricks;   // 1: FC-first tenants are gathered by the FC kernel itself
 };
 
 struct GemmArgs {
     const uint32_t* tile_base; uint32_t T; uint32_t layer; uint32_t fc_split_k;
+    // FC layer 0 can read the submitted rows itself (16-byte aligned rows whose length is a
+    // whole number of 16-byte chunks), which saves the staging pass:
+    uint32_t gather; const int32_t* perm; const void* const* row_src;
     const LayerDev* layers; const uint32_t* off; const uint32_t* M;
     const void* act_in; void* act_out; const uint8_t* arena;
     float* logits; uint32_t S; uint32_t C_pad;

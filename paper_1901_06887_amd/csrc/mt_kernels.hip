@@ -72,13 +72,17 @@ __device__ uint32_t block_exclusive_scan(uint32_t* data, uint32_t n, uint32_t* t
     return total;
 }
 
-// Number of column groups an FC layer is cut into and how the four waves share one group.
-__device__ __forceinline__ void fc_shape(uint32_t n_pad, uint32_t split_k, uint32_t* split, uint32_t* groups)
+// How an FC layer is cut into workgroup tiles: `split` column blocks side by side per
+// group (the four waves cover them; with split < 4 they also split K), `groups` column
+// groups, and the rows of a tile: 128 normally, 64 for the K-split shapes (layers with at
+// most 64 outputs), whose waves keep their activation bricks in registers.
+__device__ __forceinline__ void fc_shape(uint32_t n_pad, uint32_t split_k, uint32_t* split, uint32_t* groups, uint32_t* tile_rows)
 {
     const uint32_t nblk = n_pad / kBrickRows;
     uint32_t s = split_k ? 1u : (nblk >= 3 ? 4u : nblk);
     *split = s;
     *groups = ceil_div(nblk, s);
+    *tile_rows = s == 4 ? kTileRows : kTileRows / 2;
 }
 
 constexpr uint32_t kLists = 2 * MT_MAX_LAYERS;       // FC and conv tile-count arrays of every layer index
@@ -124,9 +128,10 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
                 const LayerDev& L = a.layers[t * MT_MAX_LAYERS + l];
                 const uint32_t kind = L.kind;
                 if (kind == MT_FC) {
-                    uint32_t split, groups;
-                    fc_shape(L.N_pad, a.fc_split_k, &split, &groups);
+                    uint32_t split, groups, trows;
+                    fc_shape(L.N_pad, a.fc_split_k, &split, &groups, &trows);
                     grp[slot][l] = groups;
+                    rpr[slot][l] = kTileRows / trows;            // 64-row tiles count as two per 128 rows
                 } else if (kind == MT_CONV2D) {
                     grp[slot][l] = ceil_div(L.N, kTileCols);
                     rpr[slot][l] = L.rows_per_req | 0x80000000u;
@@ -221,8 +226,9 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 #pragma unroll
         for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
             const uint32_t g = slot == 0 ? grp[0][l] : grp[1][l], rr = slot == 0 ? rpr[0][l] : rpr[1][l];
-            const uint32_t tiles = (g && Mt) ? ceil_div(Mt * (rr & 0x7fffffffu), kTileRows) * g : 0;
             const bool conv = rr >> 31;
+            // conv: rows = requests * output pixels, 128 per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
+            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
             c[l] = conv ? 0 : tiles;
             c[MT_MAX_LAYERS + l] = conv ? tiles : 0;
         }
@@ -311,6 +317,7 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
     const uint32_t t = (uint32_t)a.row_tenant[r0];
     const TenantDev td = a.tenants[t];
     if (td.in_layout == kLayoutBricks) {
+        if (a.skip_bricks) return;
         if (a.elem_size == 2) gather_bricks<__bf16>(a, td, t, p0); else gather_bricks<float>(a, td, t, p0);
     } else {
         if (a.elem_size == 2) gather_rows_layout<__bf16>(a, td, p0); else gather_rows_layout<float>(a, td, p0);
@@ -394,7 +401,7 @@ constexpr uint32_t kFcLdsBytes = kTrOffset + 4 * kTrBytes;
 static_assert(kFcLdsBytes >= 2 * kStageBytes, "the two activation stages must fit");
 
 // split == 4: activations through LDS, weights through the register ring.
-template <typename T, int RB>
+template <typename T, int RB, bool GATHER>
 __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Tile& tl, const LayerDev& L, uint32_t seg0,
                                                      uint32_t nb, bool active, uint8_t* stages, f32x16 (&acc)[RB])
 {
@@ -417,9 +424,24 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
         const uint32_t rbi = tl.m0 / kBrickRows + min(r, nrb - 1);     // blocks past the tile repeat its last one
         xsrc[j] = xbase + (size_t)rbi * nKB * 64;
     }
+    // GATHER (layer 0): the bricks are formed on the fly from the submitted rows; this wave's
+    // four bricks lie in one row block, so a lane reads from one row (null for padding rows)
+    const T* rowp = nullptr;
+    if (GATHER) {
+        const uint32_t rbi = tl.m0 / kBrickRows + min(wave * 4 / KC, nrb - 1);
+        const int32_t r = a.perm[seg0 + rbi * kBrickRows + (lane & 31)];
+        if (r >= 0) rowp = (const T*)a.row_src[r];
+    }
     auto load_chunk = [&](uint32_t c, u32x4 (&xr)[4]) {
 #pragma unroll
-        for (uint32_t j = 0; j < 4; ++j) xr[j] = xsrc[j][(size_t)min(c * KC + xkk[j], nKB - 1) * 64];
+        for (uint32_t j = 0; j < 4; ++j) {
+            if (GATHER) {
+                const uint32_t k = (c * KC + xkk[j]) * KB + (lane >> 5) * EPC;
+                xr[j] = (rowp && k < L.k_valid) ? *(const u32x4*)(rowp + k) : u32x4{0, 0, 0, 0};
+            } else {
+                xr[j] = xsrc[j][(size_t)min(c * KC + xkk[j], nKB - 1) * 64];
+            }
+        }
     };
     auto store_chunk = [&](uint32_t stage, const u32x4 (&xr)[4]) {
 #pragma unroll
@@ -470,7 +492,7 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
 }
 
 // split < 4: every wave reads the activation bricks of its own K range directly.
-template <typename T, int RB, int P>
+template <typename T, int RB, int P, bool GATHER>
 __device__ __forceinline__ void fc_accumulate_direct(const GemmArgs& a, const Tile& tl, const LayerDev& L, uint32_t seg0,
                                                      uint32_t nb, uint32_t kq, uint32_t ks, f32x16 (&acc)[RB])
 {
@@ -487,13 +509,30 @@ __device__ __forceinline__ void fc_accumulate_direct(const GemmArgs& a, const Ti
         const uint32_t rbi = tl.m0 / kBrickRows + min((uint32_t)r, nrb - 1);
         xp[r] = xbase + ((size_t)rbi * nKB + kb0) * 64;
     }
+    const T* rowp[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        rowp[r] = nullptr;
+        if (GATHER) {
+            const uint32_t rbi = tl.m0 / kBrickRows + min((uint32_t)r, nrb - 1);
+            const int32_t row = a.perm[seg0 + rbi * kBrickRows + (lane & 31)];
+            if (row >= 0) rowp[r] = (const T*)a.row_src[row];
+        }
+    }
+    auto load_x = [&](int r, uint32_t kk) -> u32x4 {
+        if (GATHER) {
+            const uint32_t k = (kb0 + kk) * KB + (lane >> 5) * EPC;
+            return (rowp[r] && k < L.k_valid) ? *(const u32x4*)(rowp[r] + k) : u32x4{0, 0, 0, 0};
+        }
+        return xp[r][(size_t)kk * 64];
+    };
     u32x4 bq[P], aq[RB][P];
 #pragma unroll
     for (int j = 0; j < P; ++j) {
         const uint32_t kk = min((uint32_t)j, cnt - 1);
         bq[j] = wp[(size_t)kk * 64];
 #pragma unroll
-        for (int r = 0; r < RB; ++r) aq[r][j] = xp[r][(size_t)kk * 64];
+        for (int r = 0; r < RB; ++r) aq[r][j] = load_x(r, kk);
     }
     // steady state: straight-line groups of P bricks, each slot refilled right after use; the
     // clamped refill index re-reads the last brick instead of branching
@@ -506,7 +545,7 @@ __device__ __forceinline__ void fc_accumulate_direct(const GemmArgs& a, const Ti
             const uint32_t kk = min(g * P + j + P, cnt - 1);
             bq[j] = wp[(size_t)kk * 64];
 #pragma unroll
-            for (int r = 0; r < RB; ++r) aq[r][j] = xp[r][(size_t)kk * 64];
+            for (int r = 0; r < RB; ++r) aq[r][j] = load_x(r, kk);
         }
     }
     const uint32_t rem = cnt - full * P;                      // the slots already hold the remaining bricks
@@ -519,7 +558,7 @@ __device__ __forceinline__ void fc_accumulate_direct(const GemmArgs& a, const Ti
     }
 }
 
-template <typename T, int RB, int P>
+template <typename T, int RB, int P, bool GATHER>
 __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const LayerDev& L, uint32_t Mt, uint8_t* smem)
 {
     const uint32_t t = tl.tenant, split = tl.split;
@@ -541,9 +580,9 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
         for (int v = 0; v < 16; ++v) acc[r][v] = 0.0f;
 
     if (ks == 1) {
-        fc_accumulate_shared<T, RB>(a, tl, L, seg0, nb, active, smem, acc);
+        fc_accumulate_shared<T, RB, GATHER>(a, tl, L, seg0, nb, active, smem, acc);
     } else {
-        if (active) fc_accumulate_direct<T, RB, P>(a, tl, L, seg0, nb, kq, ks, acc);
+        if (active) fc_accumulate_direct<T, RB, P, GATHER>(a, tl, L, seg0, nb, kq, ks, acc);
         // waves with kq > 0 hand their partial sums to the kq == 0 wave of the same column block
 #pragma unroll
         for (int r = 0; r < RB; ++r) {
@@ -625,16 +664,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     __syncthreads();                                          // the lookup is over before anything reuses smem
     const LayerDev L = a.layers[tl.tenant * MT_MAX_LAYERS + a.layer];
     const uint32_t Mt = a.M[tl.tenant];
-    uint32_t groups;
-    fc_shape(L.N_pad, a.fc_split_k, &tl.split, &groups);
-    const uint32_t mt_ = ceil_div(Mt, kTileRows);
-    tl.m0 = (local % mt_) * kTileRows;
-    tl.rows = min((uint32_t)kTileRows, Mt - tl.m0);
+    uint32_t groups, trows;
+    fc_shape(L.N_pad, a.fc_split_k, &tl.split, &groups, &trows);
+    const uint32_t mt_ = ceil_div(Mt, trows);
+    tl.m0 = (local % mt_) * trows;
+    tl.rows = min(trows, Mt - tl.m0);
     tl.n0 = (local / mt_) * tl.split * kBrickRows;
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
-    if (nrb <= 1) fc_tile<T, 1, 8>(a, tl, L, Mt, smem);
-    else if (nrb == 2) fc_tile<T, 2, 4>(a, tl, L, Mt, smem);
-    else fc_tile<T, 4, 2>(a, tl, L, Mt, smem);
+    if (a.gather) {
+        if (nrb <= 1) fc_tile<T, 1, 8, true>(a, tl, L, Mt, smem);
+        else if (nrb == 2) fc_tile<T, 2, 4, true>(a, tl, L, Mt, smem);
+        else fc_tile<T, 4, 2, true>(a, tl, L, Mt, smem);
+    } else {
+        if (nrb <= 1) fc_tile<T, 1, 8, false>(a, tl, L, Mt, smem);
+        else if (nrb == 2) fc_tile<T, 2, 4, false>(a, tl, L, Mt, smem);
+        else fc_tile<T, 4, 2, false>(a, tl, L, Mt, smem);   // 3 or 4 row blocks: split == 4 tiles only
+    }
 }
 
 // ---- grouped 3x3 convolution as implicit GEMM ---------------------------------------------
