@@ -66,6 +66,9 @@ struct mt_ctx {
     uint32_t no_fused_gather = 0;  // tuning/testing: always stage FC inputs with the gather kernel
     bool fc_first_chunked = true;  // every registered FC-first model's input is a whole number of 16-byte chunks
     bool any_conv_first = false, any_fc_first = false;
+    uint32_t list_mask = 0;        // bit kind*MT_MAX_LAYERS + l: some registered model has that kind at layer l
+    uint32_t max_reg_classes = 0, min_reg_classes = 0;
+    uint32_t no_fused_head = 0;    // tuning/testing: always run the separate head kernel
     uint32_t P_cap = 0;        // packed rows incl. per-tenant padding to 32
 
     // device state
@@ -101,6 +104,7 @@ struct mt_ctx {
     std::vector<hipEvent_t> prof_events;
     bool prof_used[kProfSlots] = {};
     bool prof_valid = false;
+    uint32_t prof_last = 0;
 };
 
 namespace {
@@ -164,6 +168,7 @@ void recompute_bounds(mt_ctx* c)
     c->n_layer_slots = 0;
     c->max_in_len = 0;
     c->fc_first_chunked = true; c->any_conv_first = c->any_fc_first = false;
+    c->list_mask = 0; c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
         c->has_gap[l] = 0;
         for (int k = 0; k < 2; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
@@ -172,6 +177,8 @@ void recompute_bounds(mt_ctx* c)
         if (!t.registered) continue;
         c->n_layer_slots = std::max(c->n_layer_slots, t.n_layers);
         c->max_in_len = std::max(c->max_in_len, t.dev.in_len);
+        c->max_reg_classes = std::max(c->max_reg_classes, t.dev.n_classes);
+        c->min_reg_classes = std::min(c->min_reg_classes, t.dev.n_classes);
         if (t.dev.in_layout == kLayoutBricks) {
             c->any_fc_first = true;
             if ((t.dev.in_len * c->elem_size) % 16) c->fc_first_chunked = false;
@@ -182,6 +189,7 @@ void recompute_bounds(mt_ctx* c)
             const LayerDev& L = t.layers[l].dev;
             if (L.kind == MT_GAP) { c->has_gap[l] = 1; continue; }
             const int k = L.kind == MT_FC ? 0 : 1;
+            c->list_mask |= 1u << (k * MT_MAX_LAYERS + l);
             const uint32_t nt = k == 0 ? fc_groups(L.N_pad, c->fc_split_k) : (L.N + kTileCols - 1) / kTileCols;
             c->max_rpr[k][l] = std::max(c->max_rpr[k][l], L.rows_per_req);
             c->max_nt[k][l] = std::max(c->max_nt[k][l], nt);
@@ -335,6 +343,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     c->P_cap = round_up(cfg->max_requests, kBrickRows) + kBrickRows * std::min(cfg->max_tenants, cfg->max_requests);
     if (const char* e = getenv("MT_FC_SPLIT_K")) c->fc_split_k = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_GATHER")) c->no_fused_gather = atoi(e) != 0;
+    if (const char* e = getenv("MT_NO_FUSED_HEAD")) c->no_fused_head = atoi(e) != 0;
     c->tenants.resize(cfg->max_tenants);
     c->cfg.arena_bytes = cfg->arena_bytes / kArenaAlign * kArenaAlign;
     c->free_list.push_back(FreeBlock{0, c->cfg.arena_bytes});
@@ -536,12 +545,19 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     b.tenants = c->d_tenants; b.layers = c->d_layers;
     b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
     b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.fc_split_k = c->fc_split_k;
+    b.list_mask = c->list_mask;
+    const OutPtrs outp{out->labels, out->probs, out->logits, out->n_classes, out->row_stride};
+    b.out = outp;
+    // A last layer of at most 32 classes is one column block: its FC tiles finish their rows
+    // themselves (only with the default tile shapes, where such a layer always has split 1).
+    const bool fuse_head = !c->no_fused_head && !c->fc_split_k && c->min_reg_classes <= kBrickRows;
+    const uint32_t head_min_classes = fuse_head ? kBrickRows + 1 : 0;
     if (c->profiling) for (uint32_t i = 0; i < kProfSlots; ++i) c->prof_used[i] = false;
 #define TIMED(slot, call)                                                                   \
     do {                                                                                    \
         if (c->profiling) HIP_TRY(c, hipEventRecord(c->prof_events[2 * (slot)], s));        \
         HIP_TRY(c, call); ++launches;                                                       \
-        if (c->profiling) { HIP_TRY(c, hipEventRecord(c->prof_events[2 * (slot) + 1], s)); c->prof_used[slot] = true; } \
+        if (c->profiling) { HIP_TRY(c, hipEventRecord(c->prof_events[2 * (slot) + 1], s)); c->prof_used[slot] = true; c->prof_last = (slot); } \
     } while (0)
     TIMED(kProfBatcher, launch_batcher(b, s));
 
@@ -571,6 +587,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             ga.tile_base = c->d_tile_base + ((size_t)kind * MT_MAX_LAYERS + l) * (T + 1);
             ga.T = T; ga.layer = l; ga.fc_split_k = c->fc_split_k;
             ga.gather = (kind == 0 && l == 0 && fuse_gather); ga.perm = c->d_perm; ga.row_src = c->d_row_src;
+            ga.fuse_head = fuse_head; ga.out = outp;
             ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad;
             const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, 0x7ffffff0u);
@@ -586,11 +603,12 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         }
     }
 
-    HeadArgs h{};
-    h.R = R; h.tenants = c->d_tenants; h.row_tenant = c->d_row_tenant; h.pos_of = c->d_pos_of; h.logits = c->d_logits;
-    h.C_pad = c->C_pad; h.labels = out->labels; h.probs = out->probs; h.logits_out = out->logits;
-    h.n_classes = out->n_classes; h.row_stride = out->row_stride;
-    TIMED(kProfHead, launch_head(h, s));
+    if (!fuse_head || c->max_reg_classes > kBrickRows) {
+        HeadArgs h{};
+        h.R = R; h.tenants = c->d_tenants; h.row_tenant = c->d_row_tenant; h.pos_of = c->d_pos_of; h.logits = c->d_logits;
+        h.C_pad = c->C_pad; h.out = outp; h.min_classes = head_min_classes;
+        TIMED(kProfHead, launch_head(h, s));
+    }
 #undef TIMED
     c->prof_valid = c->profiling;
 
@@ -649,7 +667,7 @@ mt_status mt_get_profile(mt_ctx* c, mt_profile* out)
         HIP_TRY(c, ms(kProfConv + l, &out->conv_ms[l]));
         HIP_TRY(c, ms(kProfGap + l, &out->gap_ms[l]));
     }
-    HIP_TRY(c, hipEventElapsedTime(&out->total_ms, c->prof_events[2 * kProfBatcher], c->prof_events[2 * kProfHead + 1]));
+    HIP_TRY(c, hipEventElapsedTime(&out->total_ms, c->prof_events[2 * kProfBatcher], c->prof_events[2 * c->prof_last + 1]));
     return MT_OK;
 }
 

@@ -67,6 +67,11 @@ struct Segment {
     int32_t tenant;       // used when ids == nullptr
 };
 
+// Where predictions go (caller's buffers, submission order).
+struct OutPtrs {
+    int32_t* labels; float* probs; float* logits; int32_t* n_classes; uint32_t row_stride;
+};
+
 // Grouped work of one layer index is described by one array per kind (FC, conv):
 // tile_base[t] = number of workgroup tiles of all tenants before t, tile_base[T] = total.
 // A workgroup finds its tenant by searching that array and derives its tile from the rest:
@@ -88,6 +93,8 @@ struct BatchArgs {
     uint32_t* M;           // [T]
     uint32_t* off;         // [T+1] packed position of each tenant's first row (multiple of 32)
     uint32_t* tile_base;   // [2][MT_MAX_LAYERS][T+1]: FC arrays, then conv arrays
+    uint32_t list_mask;    // bit kind*MT_MAX_LAYERS + l set if any registered model has that kind at layer l
+    OutPtrs out;           // rejected rows are answered here (label -1, zero rows)
 };
 
 struct GatherArgs {
@@ -103,6 +110,8 @@ struct GemmArgs {
     // FC layer 0 can read the submitted rows itself (16-byte aligned rows whose length is a
     // whole number of 16-byte chunks), which saves the staging pass:
     uint32_t gather; const int32_t* perm; const void* const* row_src;
+    // a last layer of at most 32 classes finishes its rows itself (softmax, argmax, outputs):
+    uint32_t fuse_head; OutPtrs out;
     const LayerDev* layers; const uint32_t* off; const uint32_t* M;
     const void* act_in; void* act_out; const uint8_t* arena;
     float* logits; uint32_t S; uint32_t C_pad;
@@ -117,7 +126,8 @@ struct GapArgs {
 struct HeadArgs {
     uint32_t R; const TenantDev* tenants; const int32_t* row_tenant; const int32_t* pos_of;
     const float* logits; uint32_t C_pad;
-    int32_t* labels; float* probs; float* logits_out; int32_t* n_classes; uint32_t row_stride;
+    OutPtrs out;
+    uint32_t min_classes;   // rows of models with fewer classes were finished by the FC kernel
 };
 
 // Launchers (defined in mt_kernels.hip).  All enqueue on `s` and return the launch status.

@@ -93,6 +93,7 @@ constexpr uint32_t kLists = 2 * MT_MAX_LAYERS;       // FC and conv tile-count a
 // same whatever the tenant mix is.  Latency, not bandwidth, bounds this kernel, so everything
 // that does not depend on the rows (tenant and layer facts) is fetched up front, tenant ids
 // are fetched one step ahead, and all tile-count arrays are scanned in one pass.
+template <bool ONE_SEG>
 __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 {
     __shared__ uint32_t hist[kHistEntries];
@@ -142,9 +143,8 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 
     // the segment table sits in host memory: stage it in LDS when it is small
     const Segment* segs = a.segs;
-    if (a.n_segs <= kSegsInLds) {
-        if (a.n_segs == 1) { if (tid == 0) seg_l[0] = a.first; }
-        else for (uint32_t i = tid; i < a.n_segs; i += kBatchThreads) seg_l[i] = a.segs[i];
+    if (!ONE_SEG && a.n_segs <= kSegsInLds) {
+        for (uint32_t i = tid; i < a.n_segs; i += kBatchThreads) seg_l[i] = a.segs[i];
         segs = seg_l;
     }
     const uint32_t nw = min(kBatchThreads / 64, kHistEntries / Tp);
@@ -157,6 +157,10 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         const uint32_t begin = w * chunk, end = min(begin + chunk, R);
         auto fetch_id = [&](uint32_t r) -> int32_t {
             if (r >= end) return -1;
+            if (ONE_SEG) {                      // the whole batch is one submission: no table lookup
+                a.row_src[r] = (const uint8_t*)a.first.src + (size_t)r * a.first.row_stride * a.elem_size;
+                return a.first.ids ? a.first.ids[r] : a.first.tenant;
+            }
             const Segment& sg = segs[find_segment(segs, a.n_segs, r)];
             a.row_src[r] = (const uint8_t*)sg.src + (size_t)(r - sg.row_begin) * sg.row_stride * a.elem_size;
             return sg.ids ? sg.ids[r - sg.row_begin] : sg.tenant;
@@ -211,6 +215,13 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         if (t >= 0) {
             pos = (int32_t)(offl[t] + hist[(r / chunk) * Tp + t] + a.row_rank[r]);
             a.perm[pos] = (int32_t)r;
+        } else {                                // rejected: unknown tenant or no model
+            a.out.labels[r] = -1;
+            if (a.out.n_classes) a.out.n_classes[r] = 0;
+            for (uint32_t c = 0; c < a.out.row_stride; ++c) {
+                if (a.out.probs) a.out.probs[(size_t)r * a.out.row_stride + c] = 0.0f;
+                if (a.out.logits) a.out.logits[(size_t)r * a.out.row_stride + c] = 0.0f;
+            }
         }
         a.pos_of[r] = pos;
     }
@@ -235,9 +246,11 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 #pragma unroll
         for (uint32_t i = 0; i < kLists; ++i) {
             uint32_t v = c[i];
-            for (int d = 1; d < 64; d <<= 1) {
-                const uint32_t o = __shfl_up(v, d);
-                if (lane >= (uint32_t)d) v += o;
+            if ((a.list_mask >> i) & 1) {       // lists no registered model contributes to are skipped
+                for (int d = 1; d < 64; d <<= 1) {
+                    const uint32_t o = __shfl_up(v, d);
+                    if (lane >= (uint32_t)d) v += o;
+                }
             }
             incl[i] = v;
             if (lane == 63) wtot[w][i] = v;
@@ -606,6 +619,39 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
     const uint32_t n = nb * kBrickRows + li;
     const float* bias = (const float*)(a.arena + L.b_off);
     const float bv = writer ? bias[n] : 0.0f;
+    if (L.is_last && a.fuse_head && split == 1) {
+        // at most 32 classes: the writer wave holds whole rows of logits.  Transpose them
+        // through LDS so that one lane owns one request, then softmax, argmax and the outputs.
+        float* trw = (float*)(smem + kTrOffset + wave * kTrBytes);
+        constexpr uint32_t FRS = kTrRowBytes / 4;
+        const uint32_t C = L.N;
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            __syncthreads();
+            if (writer && (uint32_t)r < nrb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) trw[(8 * (v >> 2) + 4 * lh + (v & 3)) * FRS + li] = acc[r][v] + bv;
+            }
+            __syncthreads();
+            const uint32_t m = tl.m0 + r * kBrickRows + li;
+            if (writer && (uint32_t)r < nrb && lh == 0 && m < Mt) {
+                const float* z = trw + li * FRS;
+                const uint32_t sub = (uint32_t)a.perm[seg0 + m];
+                float mx = z[0]; int32_t best = 0;
+                for (uint32_t c = 1; c < C; ++c) if (z[c] > mx) { mx = z[c]; best = (int32_t)c; }   // lowest index on ties
+                float sum = 0.0f;
+                for (uint32_t c = 0; c < C; ++c) sum += __expf(z[c] - mx);
+                const float inv = 1.0f / sum;
+                a.out.labels[sub] = best;
+                if (a.out.n_classes) a.out.n_classes[sub] = (int32_t)C;
+                for (uint32_t c = 0; c < a.out.row_stride; ++c) {
+                    if (a.out.probs) a.out.probs[(size_t)sub * a.out.row_stride + c] = c < C ? __expf(z[c] - mx) * inv : 0.0f;
+                    if (a.out.logits) a.out.logits[(size_t)sub * a.out.row_stride + c] = c < C ? z[c] : 0.0f;
+                }
+            }
+        }
+        return;
+    }
     if (L.is_last) {
         if (!writer || n >= L.N) return;
 #pragma unroll
@@ -875,8 +921,10 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
     int32_t label = -1;
     float mx = -INFINITY, sum = 0.0f;
     const float* z = nullptr;
-    if (pos >= 0) {
-        C = a.tenants[a.row_tenant[r]].n_classes;
+    if (pos < 0) return;                                    // rejected rows were answered by the batcher
+    C = a.tenants[a.row_tenant[r]].n_classes;
+    if (C < a.min_classes) return;                          // finished by the FC kernel
+    {
         z = a.logits + (size_t)pos * a.C_pad;
         int32_t best = 0x7fffffff;
         for (uint32_t c = lane; c < C; c += 64) {
@@ -892,22 +940,23 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
         for (uint32_t c = lane; c < C; c += 64) sum += __expf(z[c] - mx);
         for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d);
     }
-    const float inv = pos >= 0 ? 1.0f / sum : 0.0f;
-    for (uint32_t c = lane; c < a.row_stride; c += 64) {
+    const float inv = 1.0f / sum;
+    for (uint32_t c = lane; c < a.out.row_stride; c += 64) {
         const bool in = c < C;
-        if (a.probs) a.probs[(size_t)r * a.row_stride + c] = in ? __expf(z[c] - mx) * inv : 0.0f;
-        if (a.logits_out) a.logits_out[(size_t)r * a.row_stride + c] = in ? z[c] : 0.0f;
+        if (a.out.probs) a.out.probs[(size_t)r * a.out.row_stride + c] = in ? __expf(z[c] - mx) * inv : 0.0f;
+        if (a.out.logits) a.out.logits[(size_t)r * a.out.row_stride + c] = in ? z[c] : 0.0f;
     }
     if (lane == 0) {
-        a.labels[r] = label;
-        if (a.n_classes) a.n_classes[r] = (int32_t)C;
+        a.out.labels[r] = label;
+        if (a.out.n_classes) a.out.n_classes[r] = (int32_t)C;
     }
 }
 
 // ---- launchers ------------------------------------------------------------------------------
 hipError_t launch_batcher(const BatchArgs& a, hipStream_t s)
 {
-    hipLaunchKernelGGL(batcher_kernel, dim3(1), dim3(kBatchThreads), 0, s, a);
+    if (a.n_segs == 1) hipLaunchKernelGGL(batcher_kernel<true>, dim3(1), dim3(kBatchThreads), 0, s, a);
+    else hipLaunchKernelGGL(batcher_kernel<false>, dim3(1), dim3(kBatchThreads), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s)

@@ -140,3 +140,33 @@ def test_unregister_then_serve_remaining_tenants():
     w2 = wl.Workload(w.name, w.dtype, {t: m for t, m in w.tenants.items() if t != 2}, w.tenant_ids[keep], w.inputs[keep])
     compare(w2, (lg[keep], pr[keep], lb[keep], nc[keep]), oracle_rows(w2), what="after-unregister")
     ctx.close()
+
+
+def test_staged_and_separate_head_paths_match_the_fused_ones(monkeypatch):
+    """The FC kernel may gather layer-0 inputs and finish <=32-class rows itself; the staged
+    gather pass and the separate head kernel must give the same answers."""
+    w = wl.c2(n_tenants=5, n_requests=260, dims=(96, 160, 128, 10))     # 96 bf16 = 12 chunks: fused gather applies
+    ctx = make_context(w)
+    fused = gpu_run(ctx, w, poison=True)
+    ctx.close()
+    compare(w, fused, oracle_rows(w), what="fused")
+    monkeypatch.setenv("MT_NO_FUSED_GATHER", "1")
+    monkeypatch.setenv("MT_NO_FUSED_HEAD", "1")
+    ctx = make_context(w)
+    plain = gpu_run(ctx, w, poison=True)
+    assert ctx.stats()["last_run_launches"] == 6                          # batcher, gather, 3 layers, head
+    ctx.close()
+    assert np.array_equal(fused[0], plain[0]) and np.array_equal(fused[2], plain[2])
+    assert np.allclose(fused[1], plain[1], rtol=1e-6, atol=1e-7)
+
+
+def test_mixed_class_counts_use_both_head_paths():
+    a = wl.c2(n_tenants=3, n_requests=150, dims=(64, 128, 10), seed=11)
+    b = wl.c2(n_tenants=3, n_requests=150, dims=(64, 128, 70), seed=12)
+    tenants = {0: a.tenants[0], 1: b.tenants[0], 2: a.tenants[1], 3: b.tenants[2]}
+    ids = np.random.default_rng(5).integers(0, 4, 150).astype(np.int32)
+    w = wl.Workload("mixed", "bf16", tenants, ids, a.inputs)
+    ctx = make_context(w)
+    gpu = gpu_run(ctx, w, poison=True)
+    compare(w, gpu, oracle_rows(w), what="mixed-classes")
+    ctx.close()
