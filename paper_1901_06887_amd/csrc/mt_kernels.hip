@@ -32,6 +32,11 @@ constexpr uint32_t kSegsInLds = 64;
 
 __device__ __forceinline__ uint32_t ceil_div(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every global
+// load in flight (it fences all address spaces), which would empty the prefetch rings of the
+// GEMM loops at each LDS hand-over; here only the LDS counter is waited on.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Index of the segment that holds submission row r (segments are sorted by row_begin).
 __device__ __forceinline__ uint32_t find_segment(const Segment* segs, uint32_t n, uint32_t r)
 {
@@ -419,8 +424,10 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
                                                      uint32_t nb, bool active, uint8_t* stages, f32x16 (&acc)[RB])
 {
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
-    constexpr uint32_t KC = kChunkBricks / RB;               // k steps per chunk
-    constexpr uint32_t P = KC < 8 ? KC : 8;                  // weight bricks in flight per wave
+    constexpr uint32_t KC = kChunkBricks / RB;               // k steps per chunk: 16, 8, 4
+    constexpr uint32_t P = RB == 1 ? 16 : 8;                 // weight bricks in flight per wave
+    constexpr uint32_t U = P > KC ? P : KC;                  // unrolled block of k steps
+    static_assert(U == P && U % KC == 0, "the tail relies on U == P");
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t nKB = L.K / KB;
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
@@ -439,18 +446,24 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
     }
     // GATHER (layer 0): the bricks are formed on the fly from the submitted rows; this wave's
     // four bricks lie in one row block, so a lane reads from one row (null for padding rows)
-    const T* rowp = nullptr;
+    typedef const __attribute__((address_space(1))) u32x4* gptr_t;     // submitted rows live in global memory
+    gptr_t rowp = nullptr;
+    bool row_ok = false;
     if (GATHER) {
-        const uint32_t rbi = tl.m0 / kBrickRows + min(wave * 4 / KC, nrb - 1);
-        const int32_t r = a.perm[seg0 + rbi * kBrickRows + (lane & 31)];
-        if (r >= 0) rowp = (const T*)a.row_src[r];
+        const uint32_t p0 = seg0 + (tl.m0 / kBrickRows + min(wave * 4 / KC, nrb - 1)) * kBrickRows;
+        const int32_t r = a.perm[p0 + (lane & 31)];
+        row_ok = r >= 0;
+        // padding rows read the block's first row (always a real request) and discard it: no branch around the load
+        rowp = (gptr_t)a.row_src[row_ok ? r : a.perm[p0]];
     }
     auto load_chunk = [&](uint32_t c, u32x4 (&xr)[4]) {
 #pragma unroll
         for (uint32_t j = 0; j < 4; ++j) {
             if (GATHER) {
                 const uint32_t k = (c * KC + xkk[j]) * KB + (lane >> 5) * EPC;
-                xr[j] = (rowp && k < L.k_valid) ? *(const u32x4*)(rowp + k) : u32x4{0, 0, 0, 0};
+                const bool ok = row_ok && k < L.k_valid;
+                const u32x4 v = rowp[(ok ? k : 0) / EPC];
+                xr[j] = ok ? v : u32x4{0, 0, 0, 0};
             } else {
                 xr[j] = xsrc[j][(size_t)min(c * KC + xkk[j], nKB - 1) * 64];
             }
@@ -461,45 +474,46 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
         for (uint32_t j = 0; j < 4; ++j) *(u32x4*)(stages + stage * kStageBytes + (wave * 4 + j) * kBrickBytes + lane * 16) = xr[j];
     };
 
+    // K is walked in blocks of U steps, unrolled, so that ring slots (step % P) and, where a
+    // block spans two chunks, LDS stages are compile-time constants.  Slot s % P holds step s
+    // from P steps before its use until its MFMAs; it is refilled with step s + P right after.
     u32x4 bq[P], xr[4];
 #pragma unroll
     for (uint32_t j = 0; j < P; ++j) bq[j] = wp[(size_t)min(j, nKB - 1) * 64];
-    const uint32_t n_chunks = (nKB + KC - 1) / KC, full_chunks = nKB / KC;
     load_chunk(0, xr);
     store_chunk(0, xr);
-    load_chunk(1, xr);                                        // clamped when there is no chunk 1
-    for (uint32_t c = 0; c < full_chunks; ++c) {
-        __syncthreads();                                      // stage c&1 is complete; stage (c+1)&1 is free again
+    load_chunk(1, xr);                                        // zeros / clamped when there is no chunk 1
+    uint32_t c = 0;                                           // chunk being consumed; it lives in stage c & 1
+    const uint8_t* st = stages + lane * 16;
+    auto next_chunk = [&]() {
+        lds_barrier();                                        // stage c&1 is complete; stage (c+1)&1 is free again
         store_chunk((c + 1) & 1, xr);
         load_chunk(c + 2, xr);
-        const uint8_t* st = stages + (c & 1) * kStageBytes + lane * 16;
-        // groups of P k steps; the scheduling fences keep the compiler from hoisting every LDS
-        // read of the chunk to its top (which would cost registers, hence resident waves)
-        for (uint32_t g = 0; g < KC / P; ++g) {
+        st = stages + (c & 1) * kStageBytes + lane * 16;
+        ++c;
+    };
+    const uint32_t n_blocks = nKB / U;
+    for (uint32_t blk = 0; blk < n_blocks; ++blk) {
 #pragma unroll
-            for (uint32_t j = 0; j < P; ++j) {
-                const uint32_t kk = g * P + j;
-                u32x4 av[RB];
+        for (uint32_t u = 0; u < U; ++u) {
+            if (u % KC == 0) next_chunk();
+            u32x4 av[RB];
 #pragma unroll
-                for (int r = 0; r < RB; ++r) av[r] = *(const u32x4*)(st + (r * KC + kk) * kBrickBytes);
+            for (int r = 0; r < RB; ++r) av[r] = *(const u32x4*)(st + (r * KC + u % KC) * kBrickBytes);
 #pragma unroll
-                for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], av[r], bq[j]);
-                bq[j] = wp[(size_t)min(c * KC + kk + P, nKB - 1) * 64];
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], av[r], bq[u % P]);
+            bq[u % P] = wp[(size_t)min(blk * U + u + P, nKB - 1) * 64];
+            // keeps the compiler from hoisting every LDS read of the block to its top (registers)
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    if (full_chunks < n_chunks) {                             // ragged last chunk
-        __syncthreads();
-        const uint32_t c = full_chunks, rem = nKB - c * KC;
-        const uint8_t* st = stages + (c & 1) * kStageBytes + lane * 16;
+    const uint32_t rem = nKB - n_blocks * U;                  // < U == P: the ring already holds these steps
 #pragma unroll
-        for (uint32_t kk = 0; kk < KC; ++kk) {
-            if (kk < rem) {
+    for (uint32_t u = 0; u < U; ++u) {
+        if (u < rem) {
+            if (u % KC == 0) next_chunk();
 #pragma unroll
-                for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], *(const u32x4*)(st + (r * KC + kk) * kBrickBytes), bq[kk % P]);
-                bq[kk % P] = wp[(size_t)min(c * KC + kk + P, nKB - 1) * 64];      // rem may exceed the ring
-            }
+            for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], *(const u32x4*)(st + (r * KC + u % KC) * kBrickBytes), bq[u % P]);
         }
     }
 }
@@ -522,20 +536,24 @@ __device__ __forceinline__ void fc_accumulate_direct(const GemmArgs& a, const Ti
         const uint32_t rbi = tl.m0 / kBrickRows + min((uint32_t)r, nrb - 1);
         xp[r] = xbase + ((size_t)rbi * nKB + kb0) * 64;
     }
-    const T* rowp[RB];
+    typedef const __attribute__((address_space(1))) u32x4* gptr_t;     // submitted rows live in global memory
+    gptr_t rowp[RB]; bool row_ok[RB];
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
-        rowp[r] = nullptr;
+        rowp[r] = nullptr; row_ok[r] = false;
         if (GATHER) {
-            const uint32_t rbi = tl.m0 / kBrickRows + min((uint32_t)r, nrb - 1);
-            const int32_t row = a.perm[seg0 + rbi * kBrickRows + (lane & 31)];
-            if (row >= 0) rowp[r] = (const T*)a.row_src[row];
+            const uint32_t p0 = seg0 + (tl.m0 / kBrickRows + min((uint32_t)r, nrb - 1)) * kBrickRows;
+            const int32_t row = a.perm[p0 + (lane & 31)];
+            row_ok[r] = row >= 0;
+            rowp[r] = (gptr_t)a.row_src[row_ok[r] ? row : a.perm[p0]];   // padding rows read a real row and discard it
         }
     }
     auto load_x = [&](int r, uint32_t kk) -> u32x4 {
         if (GATHER) {
             const uint32_t k = (kb0 + kk) * KB + (lane >> 5) * EPC;
-            return (rowp[r] && k < L.k_valid) ? *(const u32x4*)(rowp[r] + k) : u32x4{0, 0, 0, 0};
+            const bool ok = row_ok[r] && k < L.k_valid;
+            const u32x4 v = rowp[r][(ok ? k : 0) / EPC];
+            return ok ? v : u32x4{0, 0, 0, 0};
         }
         return xp[r][(size_t)kk * 64];
     };
@@ -694,7 +712,7 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void fc_kernel(GemmArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void fc_kernel(GemmArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint8_t smem[kFcLdsBytes];    // also holds tile_base during the lookup
     uint32_t* base_l = (uint32_t*)smem;
@@ -825,7 +843,7 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
 
     load_step(0);
     store_step(0);
-    __syncthreads();
+    lds_barrier();
     for (uint32_t step = 0; step < n_steps; ++step) {
         const uint32_t cur = step & 1;
         if (step + 1 < n_steps) load_step(step + 1);
@@ -852,7 +870,7 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
             }
         }
         if (step + 1 < n_steps) store_step(cur ^ 1);
-        __syncthreads();
+        lds_barrier();
     }
 
     // epilogue: bias, activation, rounding, NHWC store
