@@ -106,12 +106,15 @@ def main():
         prof.append(ctx.get_profile())
     ctx.set_profiling(False)
     n_slots = mt.MT_MAX_LAYERS
-    fc_ms = [float(np.mean([p["fc_ms"][l] for p in prof])) for l in range(n_slots)]
+    fc_ms = [float(np.mean([p["fc_ms"][l] + p["fc_big_ms"][l] for p in prof])) for l in range(n_slots)]
+    big_ms = [float(np.mean([p["fc_big_ms"][l] for p in prof])) for l in range(n_slots)]
     conv_ms = [float(np.mean([p["conv_ms"][l] for p in prof])) for l in range(n_slots)]
     flops, bytes_ = gemm_launch_costs(w, es)
     # the dominant kernel: the grouped FC kernel, or the grouped conv kernel for the CNN mix
     dom_ms, dom_name = (fc_ms, "fc_kernel") if sum(fc_ms) >= sum(conv_ms) else (conv_ms, "conv_kernel")
-    other_ms = conv_ms if dom_ms is fc_ms else fc_ms
+    if dom_ms is fc_ms and sum(big_ms) > 0.5 * sum(fc_ms):
+        dom_ms, dom_name = big_ms, "fc_big_kernel"
+    other_ms = fc_ms if dom_ms is conv_ms else conv_ms
     launches = [l for l in range(n_slots) if dom_ms[l] > 0 and other_ms[l] == 0 and l in bytes_]
     avg_dur_s = sum(dom_ms[l] for l in launches) / len(launches) * 1e-3
     avg_bytes = sum(bytes_[l] for l in launches) / len(launches)
@@ -133,6 +136,7 @@ def main():
     kernels_us = {"batcher": float(np.mean([p["batcher_ms"] for p in prof])) * 1e3,
                   "gather": float(np.mean([p["gather_ms"] for p in prof])) * 1e3,
                   "fc_by_layer": [g * 1e3 for g in fc_ms if g > 0],
+                  "fc_big_by_layer": [g * 1e3 for g in big_ms if g > 0],
                   "conv_by_layer": [g * 1e3 for g in conv_ms if g > 0],
                   "gap": float(np.sum([np.mean([p["gap_ms"][l] for p in prof]) for l in range(n_slots)])) * 1e3,
                   "head": float(np.mean([p["head_ms"] for p in prof])) * 1e3,

@@ -171,6 +171,7 @@ mt_status mt_get_stats(const mt_ctx* ctx, mt_stats* out);
 typedef struct {
     float batcher_ms, gather_ms, head_ms;
     float fc_ms[MT_MAX_LAYERS];     /* grouped FC launch of each layer index          */
+    float fc_big_ms[MT_MAX_LAYERS]; /* grouped big-tile FC launch of each layer index */
     float conv_ms[MT_MAX_LAYERS];   /* grouped convolution launch of each layer index */
     float gap_ms[MT_MAX_LAYERS];    /* pooling launch of each layer index             */
     float total_ms;                 /* first kernel start to last kernel end          */

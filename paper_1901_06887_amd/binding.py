@@ -53,7 +53,7 @@ class mt_stats(ctypes.Structure):
 
 class mt_profile(ctypes.Structure):
     _fields_ = [("batcher_ms", ctypes.c_float), ("gather_ms", ctypes.c_float), ("head_ms", ctypes.c_float),
-                ("fc_ms", ctypes.c_float * MT_MAX_LAYERS), ("conv_ms", ctypes.c_float * MT_MAX_LAYERS),
+                ("fc_ms", ctypes.c_float * MT_MAX_LAYERS), ("fc_big_ms", ctypes.c_float * MT_MAX_LAYERS), ("conv_ms", ctypes.c_float * MT_MAX_LAYERS),
                 ("gap_ms", ctypes.c_float * MT_MAX_LAYERS),
                 ("total_ms", ctypes.c_float)]
 
@@ -190,7 +190,7 @@ class Context:
         p = mt_profile()
         self._check(self._lib.mt_get_profile(self._h, ctypes.byref(p)))
         return {"batcher_ms": p.batcher_ms, "gather_ms": p.gather_ms, "head_ms": p.head_ms,
-                "fc_ms": list(p.fc_ms), "conv_ms": list(p.conv_ms), "gap_ms": list(p.gap_ms), "total_ms": p.total_ms}
+                "fc_ms": list(p.fc_ms), "fc_big_ms": list(p.fc_big_ms), "conv_ms": list(p.conv_ms), "gap_ms": list(p.gap_ms), "total_ms": p.total_ms}
 
     def debug_poison(self):
         self._check(self._lib.mt_debug_poison(self._h))

@@ -21,8 +21,8 @@ constexpr uint32_t kSegSlots = 4;
 constexpr uint64_t kArenaAlign = 256;
 // profiling slots: batcher, gather, head, then gemm and gap of every layer index
 constexpr uint32_t kProfBatcher = 0, kProfGather = 1, kProfHead = 2, kProfFc = 3, kProfConv = 3 + MT_MAX_LAYERS,
-                   kProfGap = 3 + 2 * MT_MAX_LAYERS;
-constexpr uint32_t kProfSlots = 3 + 3 * MT_MAX_LAYERS;
+                   kProfGap = 3 + 2 * MT_MAX_LAYERS, kProfBig = 3 + 3 * MT_MAX_LAYERS;
+constexpr uint32_t kProfSlots = 3 + 4 * MT_MAX_LAYERS;
 
 inline uint32_t round_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }
 inline uint64_t round_up64(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
@@ -59,9 +59,9 @@ struct mt_ctx {
     // per layer index, over registered tenants: bounds that size the grouped launches
     uint32_t n_layer_slots = 0;
     uint32_t max_in_len = 0;
-    // [kind][layer]: kind 0 = FC tiles, 1 = conv tiles
-    uint32_t max_rpr[2][MT_MAX_LAYERS]{}, max_nt[2][MT_MAX_LAYERS]{}, has_gap[MT_MAX_LAYERS]{};
-    uint64_t sum_nt[2][MT_MAX_LAYERS]{};
+    // [kind][layer]: kind 0 = FC tiles, 1 = conv tiles, 2 = big FC tiles
+    uint32_t max_rpr[kListKinds][MT_MAX_LAYERS]{}, max_nt[kListKinds][MT_MAX_LAYERS]{}, has_gap[MT_MAX_LAYERS]{};
+    uint64_t sum_nt[kListKinds][MT_MAX_LAYERS]{};
     uint32_t fc_split_k = 0;   // tuning: FC tiles of one column block with K split four ways
     uint32_t no_fused_gather = 0;  // tuning/testing: always stage FC inputs with the gather kernel
     bool fc_first_chunked = true;  // every registered FC-first model's input is a whole number of 16-byte chunks
@@ -171,7 +171,7 @@ void recompute_bounds(mt_ctx* c)
     c->list_mask = 0; c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
         c->has_gap[l] = 0;
-        for (int k = 0; k < 2; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
+        for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
     }
     for (const HostTenant& t : c->tenants) {
         if (!t.registered) continue;
@@ -194,14 +194,20 @@ void recompute_bounds(mt_ctx* c)
             c->max_rpr[k][l] = std::max(c->max_rpr[k][l], L.rows_per_req);
             c->max_nt[k][l] = std::max(c->max_nt[k][l], nt);
             c->sum_nt[k][l] += nt;
+            if (k == 0 && L.N_pad >= (uint32_t)kBigMinCols) {      // may be served with big tiles when it gets enough rows
+                c->list_mask |= 1u << (2 * MT_MAX_LAYERS + l);
+                c->max_nt[2][l] = std::max(c->max_nt[2][l], (L.N_pad + kBigTile - 1) / kBigTile);
+            }
         }
     }
 }
 
-// Upper bound of sum_t ceil(M_t*rpr_t/128)*nt_t over any split of R rows among tenants.
+// Upper bound of the number of tiles of one list over any split of R rows among tenants.
 uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R)
 {
     if (c->max_nt[kind][l] == 0) return 0;
+    if (kind == 2)      // big FC tiles: only tenants with >= kBigMinRows rows; sum ceil(M_t/256) <= R/256 + R/kBigMinRows
+        return R < (uint64_t)kBigMinBatch ? 0 : (uint64_t)c->max_nt[2][l] * (R / kBigTile + R / kBigMinRows);
     // FC tiles may be as short as 64 rows (layers with at most 64 outputs)
     const uint64_t tile_rows = kind == 0 ? kTileRows / 2 : kTileRows;
     return (uint64_t)c->max_nt[kind][l] * (R * c->max_rpr[kind][l] / tile_rows) + c->sum_nt[kind][l];
@@ -367,8 +373,8 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     CREATE_TRY(hipMalloc((void**)&c->d_M, T * 4));
     CREATE_TRY(hipMemset(c->d_M, 0, T * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_off, (T + 1) * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_tile_base, 2 * MT_MAX_LAYERS * (T + 1) * 4));
-    CREATE_TRY(hipMemset(c->d_tile_base, 0, 2 * MT_MAX_LAYERS * (T + 1) * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_tile_base, kListKinds * MT_MAX_LAYERS * (T + 1) * 4));
+    CREATE_TRY(hipMemset(c->d_tile_base, 0, kListKinds * MT_MAX_LAYERS * (T + 1) * 4));
     for (int i = 0; i < 2; ++i) {
         CREATE_TRY(hipMalloc(&c->d_act[i], (uint64_t)c->P_cap * c->S * c->elem_size));
     }
@@ -539,13 +545,14 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     const uint32_t T = c->cfg.max_tenants;
     uint32_t launches = 0;
 
+    const bool big_enabled = R >= (uint32_t)kBigMinBatch;
     BatchArgs b{};
     b.segs = c->d_segs[slot]; b.n_segs = n_segs; b.R = R; b.T = T; b.n_layer_slots = c->n_layer_slots;
     b.first = c->pending[0]; b.row_src = c->d_row_src; b.elem_size = c->elem_size;
     b.tenants = c->d_tenants; b.layers = c->d_layers;
     b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
     b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.fc_split_k = c->fc_split_k;
-    b.list_mask = c->list_mask;
+    b.list_mask = c->list_mask; b.big_enabled = big_enabled;
     const OutPtrs outp{out->labels, out->probs, out->logits, out->n_classes, out->row_stride};
     b.out = outp;
     // A last layer of at most 32 classes is one column block: its FC tiles finish their rows
@@ -564,7 +571,9 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     // The FC kernel of layer 0 reads the submitted rows itself when every row is 16-byte aligned
     // and a whole number of 16-byte chunks long; otherwise (and for CNN models, whose images are
     // channel-padded) a gather pass stages the inputs first.
-    bool fuse_gather = c->any_fc_first && c->fc_first_chunked && !c->no_fused_gather;
+    // The big-tile kernel reads bricks only: whenever a tenant could reach it at layer 0, stage.
+    const bool big_possible = big_enabled && c->max_nt[2][0] > 0;
+    bool fuse_gather = c->any_fc_first && c->fc_first_chunked && !c->no_fused_gather && !big_possible;
     for (const Segment& sg : c->pending)
         if (((uintptr_t)sg.src & 15) || ((uint64_t)sg.row_stride * c->elem_size) % 16) fuse_gather = false;
     // packed rows: every tenant with traffic pads its segment to a multiple of 32
@@ -580,7 +589,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     for (uint32_t l = 0; l < c->n_layer_slots; ++l) {
         const void* in = c->d_act[l & 1];
         void* outb = c->d_act[(l + 1) & 1];
-        for (int kind = 0; kind < 2; ++kind) {
+        for (int kind = 0; kind < kListKinds; ++kind) {
             const uint64_t grid = tile_bound(c, kind, l, R);
             if (grid == 0) continue;
             GemmArgs ga{};
@@ -592,7 +601,8 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad;
             const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, 0x7ffffff0u);
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
-            else TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, g32, s));
+            else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, g32, s));
+            else TIMED(kProfBig + l, launch_fc_big(ga, c->cfg.dtype, g32, s));
         }
         if (c->has_gap[l]) {
             GapArgs pa{};
@@ -665,6 +675,7 @@ mt_status mt_get_profile(mt_ctx* c, mt_profile* out)
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
         HIP_TRY(c, ms(kProfFc + l, &out->fc_ms[l]));
         HIP_TRY(c, ms(kProfConv + l, &out->conv_ms[l]));
+        HIP_TRY(c, ms(kProfBig + l, &out->fc_big_ms[l]));
         HIP_TRY(c, ms(kProfGap + l, &out->gap_ms[l]));
     }
     HIP_TRY(c, hipEventElapsedTime(&out->total_ms, c->prof_events[2 * kProfBatcher], c->prof_events[2 * c->prof_last + 1]));

@@ -21,6 +21,13 @@ constexpr int kBrickRows = 32;
 constexpr int kBrickBytes = 1024;
 constexpr int kTileRows = 128;      // rows (4 row blocks) of a grouped-GEMM workgroup tile
 constexpr int kTileCols = 128;      // columns (4 column blocks) of a workgroup tile
+// A tenant-layer with at least kBigMinRows requests and kBigMinCols (padded) outputs is
+// compute bound; it is cut into kBigTile x kBigTile tiles and served by the big-tile FC kernel.
+constexpr int kBigTile = 256;
+constexpr int kBigMinRows = 2048;
+constexpr int kBigMinCols = 192;
+constexpr int kBigMinBatch = 8192;  // runs with fewer rows are latency/HBM bound as a whole: no big tiles
+constexpr int kListKinds = 3;       // tile lists per layer index: FC (streaming), conv, FC (big tiles)
 constexpr int kRowBytes = 128;      // conv path: bytes of K one pipeline step consumes per row
 constexpr int kChanPad = 8;         // conv input channels are padded to a multiple of this
 constexpr int kWidthAlign = 64;     // K and activation widths are zero-padded to a multiple of this
@@ -84,6 +91,7 @@ struct BatchArgs {
     Segment first;         // copy of segs[0]: the common one-segment run never reads host memory
     uint32_t elem_size;
     uint32_t fc_split_k;   // 1: FC tiles take one column block each and split K four ways
+    uint32_t big_enabled;  // 0: no tenant-layer is given big tiles in this run (small batches)
     const TenantDev* tenants; const LayerDev* layers;
     int32_t* row_tenant;   // [R] tenant of each submitted row, -1 if rejected
     uint32_t* row_rank;    // [R] scratch
@@ -92,8 +100,8 @@ struct BatchArgs {
     int32_t* perm;         // [P] packed position -> submission index, -1 for padding rows
     uint32_t* M;           // [T]
     uint32_t* off;         // [T+1] packed position of each tenant's first row (multiple of 32)
-    uint32_t* tile_base;   // [2][MT_MAX_LAYERS][T+1]: FC arrays, then conv arrays
-    uint32_t list_mask;    // bit kind*MT_MAX_LAYERS + l set if any registered model has that kind at layer l
+    uint32_t* tile_base;   // [kListKinds][MT_MAX_LAYERS][T+1]: FC, conv, big-FC arrays
+    uint32_t list_mask;    // bit kind*MT_MAX_LAYERS + l set if any registered model can have such tiles at layer l
     OutPtrs out;           // rejected rows are answered here (label -1, zero rows)
 };
 
@@ -134,6 +142,7 @@ struct HeadArgs {
 hipError_t launch_batcher(const BatchArgs& a, hipStream_t s);
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
 hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
+hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
 hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, hipStream_t s);
 hipError_t launch_head(const HeadArgs& a, hipStream_t s);

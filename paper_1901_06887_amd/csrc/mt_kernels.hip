@@ -90,7 +90,9 @@ __device__ __forceinline__ void fc_shape(uint32_t n_pad, uint32_t split_k, uint3
     *tile_rows = s == 4 ? kTileRows : kTileRows / 2;
 }
 
-constexpr uint32_t kLists = 2 * MT_MAX_LAYERS;       // FC and conv tile-count arrays of every layer index
+constexpr uint32_t kLists = kListKinds * MT_MAX_LAYERS;   // FC, conv and big-FC tile-count arrays of every layer index
+
+__device__ __forceinline__ bool fc_is_big(uint32_t rows, uint32_t n_pad) { return rows >= kBigMinRows && n_pad >= kBigMinCols; }
 
 // Tenant segmentation and grouped-work descriptors.  One workgroup; every step is
 // deterministic: rows of a tenant keep their arrival order (stable counting sort).  Equal
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 
     // tenant and layer facts of tenants tid and tid + 1024: column groups per layer (0 = no
     // tiles) and rows per request with the kind in the top bit (1 = conv)
-    uint32_t grp[2][MT_MAX_LAYERS], rpr[2][MT_MAX_LAYERS];
+    uint32_t grp[2][MT_MAX_LAYERS], rpr[2][MT_MAX_LAYERS], npad[2][MT_MAX_LAYERS];
 #pragma unroll
     for (uint32_t slot = 0; slot < 2; ++slot) {
         const uint32_t t = tid + slot * kBatchThreads;
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         }
 #pragma unroll
         for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-            grp[slot][l] = 0; rpr[slot][l] = 1;
+            grp[slot][l] = 0; rpr[slot][l] = 1; npad[slot][l] = 0;
             if (l < nl) {
                 const LayerDev& L = a.layers[t * MT_MAX_LAYERS + l];
                 const uint32_t kind = L.kind;
@@ -138,6 +140,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
                     fc_shape(L.N_pad, a.fc_split_k, &split, &groups, &trows);
                     grp[slot][l] = groups;
                     rpr[slot][l] = kTileRows / trows;            // 64-row tiles count as two per 128 rows
+                    npad[slot][l] = L.N_pad;
                 } else if (kind == MT_CONV2D) {
                     grp[slot][l] = ceil_div(L.N, kTileCols);
                     rpr[slot][l] = L.rows_per_req | 0x80000000u;
@@ -242,11 +245,14 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 #pragma unroll
         for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
             const uint32_t g = slot == 0 ? grp[0][l] : grp[1][l], rr = slot == 0 ? rpr[0][l] : rpr[1][l];
+            const uint32_t np = slot == 0 ? npad[0][l] : npad[1][l];
             const bool conv = rr >> 31;
+            const bool big = !conv && a.big_enabled && fc_is_big(Mt, np);
             // conv: rows = requests * output pixels, 128 per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
             const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
-            c[l] = conv ? 0 : tiles;
+            c[l] = (conv || big) ? 0 : tiles;
             c[MT_MAX_LAYERS + l] = conv ? tiles : 0;
+            c[2 * MT_MAX_LAYERS + l] = big ? ceil_div(Mt, kBigTile) * ceil_div(np, kBigTile) : 0;
         }
 #pragma unroll
         for (uint32_t i = 0; i < kLists; ++i) {
@@ -343,10 +349,25 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
 }
 
 // ---- shared pieces of the GEMM kernels -----------------------------------------------------
+// GELU(x) = x * Phi(x) with the exact (erf) definition, evaluated through the complementary
+// error function of |x|/sqrt(2) (Abramowitz & Stegun 7.1.26: a degree-5 polynomial in
+// 1/(1+p z) times exp(-z^2), absolute error below 1.5e-7).  Phi is formed from erfc on the
+// negative side, so the small negative tail keeps its relative accuracy; the error is far
+// below half a bfloat16 ulp of the result, and a library erf costs four times as much, which
+// showed in the epilogue of the compute-bound tiles.
+__device__ __forceinline__ float gelu(float x)
+{
+    const float z = fabsf(x) * 0.70710678118654752f;
+    const float t = __frcp_rn(1.0f + 0.3275911f * z);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float half_erfc = 0.5f * poly * __expf(-z * z);
+    return x * (x >= 0.0f ? 1.0f - half_erfc : half_erfc);
+}
+
 __device__ __forceinline__ float activate(float z, uint32_t act)
 {
     if (act == MT_ACT_RELU) return fmaxf(z, 0.0f);
-    if (act == MT_ACT_GELU) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+    if (act == MT_ACT_GELU) return gelu(z);
     return z;
 }
 
@@ -385,6 +406,18 @@ __device__ __forceinline__ bool logical_tile(uint32_t n_tiles, uint32_t* logical
     const uint32_t per_xcd = (n_tiles + 7) / 8, b = blockIdx.x;
     *logical = (b & 7) * per_xcd + (b >> 3);
     return (b >> 3) < per_xcd && *logical < n_tiles;
+}
+
+// Variant for the big-tile kernel: the tile order is dealt to the XCDs in chunks of kXcdChunk
+// tiles (round robin), so that at any time the whole GPU works on a narrow window of the order
+// (about two tenants' panels, which fit the memory-side cache) while the tiles that run together
+// on one XCD are still neighbours (L2 reuse).  The grid must be a multiple of 8 * kXcdChunk.
+constexpr uint32_t kXcdChunk = 64;
+__device__ __forceinline__ bool logical_tile_chunked(uint32_t n_tiles, uint32_t* logical)
+{
+    const uint32_t b = blockIdx.x, xcd = b & 7, i = b >> 3;
+    *logical = ((i / kXcdChunk) * 8 + xcd) * kXcdChunk + (i % kXcdChunk);
+    return *logical < n_tiles;
 }
 
 // Tenant that owns logical tile `idx`: last t with base[t] <= idx (base is in LDS, base[T] > idx).
@@ -746,6 +779,184 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
 }
 
+// ---- grouped FC, big tiles ---------------------------------------------------------------
+// Tenant-layers with at least kBigMinRows requests are compute bound.  They are cut into
+// 256x256 output tiles; a workgroup of eight waves (2x4, 128x64 = 4x2 MFMA blocks per wave, two
+// waves per SIMD so that one wave's operand fetches overlap the other's MFMAs) walks K four
+// bricks at a time through two 64 KiB LDS stages.  Both operands arrive as bricks, so a stage is
+// filled with straight 1 KiB copies (each wave copies two of the 16 row/column blocks) and read
+// back with conflict-free 16-byte-per-lane loads.  Per k step a workgroup moves 16 KiB from L2
+// for 64 MFMAs (half the operand traffic per flop of the 128x128 streaming tile) and reads
+// 48 KiB from LDS, ~60 % of what the LDS pipe sustains with two waves per SIMD.
+constexpr uint32_t kBigKS = 4;                                                   // k steps per stage
+constexpr uint32_t kBigBlocks = kBigTile / kBrickRows;                            // 8 row blocks, 8 column blocks
+constexpr uint32_t kBigStageBytes = 2 * kBigBlocks * kBigKS * kBrickBytes;        // 64 KiB
+constexpr uint32_t kBigGroup = 4;                                                 // row tiles that sweep the columns together
+constexpr uint32_t kBigThreads = 512;
+
+// One 32x32 accumulator block of the big-tile kernel -> logits rows.
+__device__ __forceinline__ void big_logits_block(const f32x16& v, float bv, float* p, uint32_t C_pad, uint32_t rows_left, uint32_t lh)
+{
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const uint32_t r = 8 * (e >> 2) + 4 * lh + (e & 3);
+        if (r < rows_left) p[(size_t)r * C_pad] = v[e] + bv;
+    }
+}
+
+// One 32x32 accumulator block -> bias, activation, rounding, transposition through the wave's
+// LDS scratch, whole-brick stores (`out` points at this lane's 16 bytes of the first brick).
+template <typename T>
+__device__ __forceinline__ void big_hidden_block(const f32x16& v, float bv, bool col_ok, uint32_t act, uint8_t* trw, u32x4* out,
+                                                 uint32_t li, uint32_t lh)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC, TRS = 32 * sizeof(T) + 16;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const uint32_t ml = 8 * (e >> 2) + 4 * lh + (e & 3);
+        const float y = col_ok ? activate(v[e] + bv, act) : 0.0f;
+        *(T*)(trw + ml * TRS + li * sizeof(T)) = (T)y;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // the wave's own LDS writes have landed
+#pragma unroll
+    for (uint32_t c = 0; c < kBrickRows / KB; ++c)
+        out[c * 64] = *(const u32x4*)(trw + li * TRS + (c * KB + lh * EPC) * sizeof(T));
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // reads done before the next block overwrites the scratch
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t stages[2 * kBigStageBytes];
+    uint8_t* const stage0 = stages;
+    uint8_t* const stage1 = stages + kBigStageBytes;
+    static_assert(2 * kBigStageBytes >= 8 * kTrBytes && kBigStageBytes >= (kMaxTenantsPadded + 1) * 4, "scratch aliases the stages");
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t li = lane & 31, lh = lane >> 5;
+
+    uint32_t* base_l = (uint32_t*)stage0;                   // tile_base during the lookup
+    const uint32_t n_tiles = a.tile_base[a.T];
+    for (uint32_t i = tid; i <= a.T; i += kBigThreads) base_l[i] = a.tile_base[i];
+    uint32_t idx;
+    if (!logical_tile_chunked(n_tiles, &idx)) return;
+    __syncthreads();
+    const uint32_t t = find_tenant(base_l, a.T, idx);
+    const uint32_t local = idx - base_l[t];
+    __syncthreads();
+    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    const uint32_t Mt = a.M[t], seg0 = a.off[t];
+    const uint32_t nKB = L.K / KB;
+    // tile order inside a tenant: groups of kBigGroup row tiles sweep all column tiles together, so
+    // the tiles that run at the same time on one XCD share few activation and weight panels (L2 reuse)
+    const uint32_t mt_ = ceil_div(Mt, kBigTile), nt_ = ceil_div(L.N_pad, kBigTile);
+    const uint32_t per_group = kBigGroup * nt_, grp = local / per_group, first_m = grp * kBigGroup;
+    const uint32_t gsz = min(mt_ - first_m, kBigGroup), in_grp = local - grp * per_group;
+    const uint32_t m0 = (first_m + in_grp % gsz) * kBigTile, n0 = (in_grp / gsz) * kBigTile;
+    const uint32_t rows = min((uint32_t)kBigTile, Mt - m0), nrb = ceil_div(rows, kBrickRows);
+    const uint32_t ncb = min(kBigBlocks, L.N_pad / kBrickRows - n0 / kBrickRows);
+    const uint32_t wm = wave >> 2, wn = wave & 3;
+
+    // staging: waves 0..3 copy the 8 activation row blocks, waves 4..7 the 8 weight column blocks
+    // (blocks past the tile or the layer repeat the last valid one)
+    const u32x4* lp[2];
+    {
+        const u32x4* xbase = (const u32x4*)((const T*)a.act_in + (size_t)seg0 * a.S) + lane;
+        const u32x4* wbase = (const u32x4*)(a.arena + L.w_off) + lane;
+#pragma unroll
+        for (uint32_t i = 0; i < 2; ++i) {
+            if (wave < 4) lp[i] = xbase + (size_t)(m0 / kBrickRows + min(wave * 2 + i, nrb - 1)) * nKB * 64;
+            else lp[i] = wbase + (size_t)(n0 / kBrickRows + min((wave - 4) * 2 + i, ncb - 1)) * nKB * 64;
+        }
+    }
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    u32x4 sr[2][kBigKS];
+    auto load_stage = [&](uint32_t s) {
+#pragma unroll
+        for (uint32_t i = 0; i < 2; ++i)
+#pragma unroll
+            for (uint32_t kk = 0; kk < kBigKS; ++kk) sr[i][kk] = lp[i][(size_t)(s * kBigKS + kk) * 64];
+        // pin the loads here: left alone, the scheduler sinks them to the end of the stage, a few
+        // cycles before their first use
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto store_stage = [&](uint8_t* buf) {
+#pragma unroll
+        for (uint32_t i = 0; i < 2; ++i)
+#pragma unroll
+            for (uint32_t kk = 0; kk < kBigKS; ++kk)
+                *(u32x4*)(buf + ((wave * 2 + i) * kBigKS + kk) * kBrickBytes + lane * 16) = sr[i][kk];
+    };
+    auto stage_compute = [&](const uint8_t* buf) {
+        const uint8_t* ab = buf + (wm * 4 * kBigKS) * kBrickBytes + lane * 16;
+        const uint8_t* bb = buf + ((kBigBlocks + wn * 2) * kBigKS) * kBrickBytes + lane * 16;
+#pragma unroll
+        for (uint32_t kk = 0; kk < kBigKS; ++kk) {
+            u32x4 av[4], bv[2];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) av[i] = *(const u32x4*)(ab + (i * kBigKS + kk) * kBrickBytes);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) bv[j] = *(const u32x4*)(bb + (j * kBigKS + kk) * kBrickBytes);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) Mma<T>::run(acc[i][j], av[i], bv[j]);
+        }
+    };
+
+    const uint32_t n_stages = nKB / kBigKS, last = n_stages - 1;
+    load_stage(0);
+    store_stage(stage0);
+    load_stage(min(1u, last));
+    lds_barrier();
+    for (uint32_t s = 0; s < n_stages; s += 2) {
+        store_stage(stage1);                                 // stage s+1 (a harmless repeat when it does not exist)
+        load_stage(min(s + 2, last));
+        stage_compute(stage0);
+        lds_barrier();
+        if (s + 1 < n_stages) {
+            store_stage(stage0);
+            load_stage(min(s + 3, last));
+            stage_compute(stage1);
+            lds_barrier();
+        }
+    }
+
+    // epilogue; the stages are free now, each wave transposes through its own scratch.  The
+    // blocks of a wave are spelled out one by one (constant accumulator indices) with a scheduling
+    // fence after each, which keeps the register need of the epilogue at one block.
+    const float* bias = (const float*)(a.arena + L.b_off);
+    float bvs[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) bvs[j] = wn * 2 + j < ncb ? bias[n0 + (wn * 2 + j) * kBrickRows + li] : 0.0f;
+    uint8_t* trw = stage0 + wave * kTrBytes;
+    const uint32_t nKB_out = L.out_fill / KB;
+    auto block = [&](const f32x16& blk, uint32_t i, uint32_t j) {
+        const uint32_t rb = wm * 4 + i;
+        if (rb < nrb && wn * 2 + j < ncb) {
+            const uint32_t nb = n0 / kBrickRows + wn * 2 + j, n = nb * kBrickRows + li;
+            const uint32_t mb = m0 + rb * kBrickRows;          // first row of the block inside the tenant
+            if (L.is_last) {
+                if (n < L.N) big_logits_block(blk, bvs[j], a.logits + (size_t)(seg0 + mb) * a.C_pad + n, a.C_pad, Mt - mb, lh);
+            } else {
+                u32x4* out = (u32x4*)((T*)a.act_out + (size_t)seg0 * a.S) +
+                             ((size_t)(mb / kBrickRows) * nKB_out + nb * (kBrickRows / KB)) * 64 + lane;
+                big_hidden_block<T>(blk, bvs[j], n < L.N, L.act, trw, out, li, lh);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    block(acc[0][0], 0, 0); block(acc[0][1], 0, 1); block(acc[1][0], 1, 0); block(acc[1][1], 1, 1);
+    block(acc[2][0], 2, 0); block(acc[2][1], 2, 1); block(acc[3][0], 3, 0); block(acc[3][1], 3, 1);
+}
+
 // ---- grouped 3x3 convolution as implicit GEMM ---------------------------------------------
 // One workgroup = 4 waves in a 2x2 grid over a 128x128 tile of (output pixels) x (output
 // channels); a wave owns 64x64 = 2x2 MFMA blocks.  K = 9 * C_in walks the NHWC input tap by
@@ -988,6 +1199,14 @@ hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream
     grid = (grid + 7) / 8 * 8;
     if (dtype == MT_BF16) hipLaunchKernelGGL(fc_kernel<__bf16>, dim3(grid), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(fc_kernel<float>, dim3(grid), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)
+{
+    if (grid == 0) return hipSuccess;
+    grid = (grid + 8 * kXcdChunk - 1) / (8 * kXcdChunk) * (8 * kXcdChunk);
+    if (dtype == MT_BF16) hipLaunchKernelGGL(fc_big_kernel<__bf16>, dim3(grid), dim3(kBigThreads), 0, s, a);
+    else hipLaunchKernelGGL(fc_big_kernel<float>, dim3(grid), dim3(kBigThreads), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)

@@ -59,6 +59,27 @@ def test_c5_reduced_gelu_wide_head():
     run_and_compare(wl.c5(n_tenants=2, n_requests=520, dims=(512, 384, 512, 256, 1000)), "c5-reduced")
 
 
+def test_big_tile_path_reduced():
+    # >= 1024 rows per tenant: the compute-bound 256x256 tiles, with ragged row and column tiles,
+    # a hidden GELU epilogue and a wide (200-class) logits epilogue
+    w = wl.c5(n_tenants=3, n_requests=8400, dims=(192, 320, 448, 200))
+    assert min(w.counts().values()) >= 2048
+    run_and_compare(w, "c5-big-reduced")
+
+
+def test_big_and_streaming_tenants_in_one_run():
+    w = wl.c2(n_tenants=5, n_requests=8300, dims=(128, 320, 256, 40), s=2.2)    # one tenant dominates
+    c = w.counts()
+    assert max(c.values()) >= 2048 and min(c.values()) < 256
+    run_and_compare(w, "big+streaming")
+
+
+def test_fp32_big_tiles():
+    w = wl.c1(n_tenants=2, n_requests=8200, dims=(64, 256, 10))
+    assert min(w.counts().values()) >= 2048
+    run_and_compare(w, "fp32-big")
+
+
 def test_fp32_cnn_and_gelu():
     w = wl.c4(n_tenants=2, n_requests=6, hw=8, chans=(3, 8, 16, 16), classes=4)
     w.dtype = "f32"
