@@ -21,8 +21,8 @@ constexpr uint32_t kSegSlots = 4;
 constexpr uint64_t kArenaAlign = 256;
 // profiling slots: batcher, gather, head, then gemm and gap of every layer index
 constexpr uint32_t kProfBatcher = 0, kProfGather = 1, kProfHead = 2, kProfFc = 3, kProfConv = 3 + MT_MAX_LAYERS,
-                   kProfGap = 3 + 2 * MT_MAX_LAYERS, kProfBig = 3 + 3 * MT_MAX_LAYERS;
-constexpr uint32_t kProfSlots = 3 + 4 * MT_MAX_LAYERS;
+                   kProfGap = 3 + 2 * MT_MAX_LAYERS, kProfBig = 3 + 3 * MT_MAX_LAYERS, kProfGatherImg = 3 + 4 * MT_MAX_LAYERS;
+constexpr uint32_t kProfSlots = 4 + 4 * MT_MAX_LAYERS;
 
 inline uint32_t round_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }
 inline uint64_t round_up64(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
@@ -61,6 +61,7 @@ struct mt_ctx {
     uint32_t max_in_len = 0;
     // [kind][layer]: kind 0 = FC tiles, 1 = conv tiles, 2 = big FC tiles
     uint32_t max_rpr[kListKinds][MT_MAX_LAYERS]{}, max_nt[kListKinds][MT_MAX_LAYERS]{}, has_gap[MT_MAX_LAYERS]{};
+    uint32_t max_conv_cb[MT_MAX_LAYERS]{};           // widest conv tile (32-channel blocks, at most 4) of a layer index
     uint64_t sum_nt[kListKinds][MT_MAX_LAYERS]{};
     uint32_t fc_split_k = 0;   // tuning: FC tiles of one column block with K split four ways
     uint32_t no_fused_gather = 0;  // tuning/testing: always stage FC inputs with the gather kernel
@@ -170,7 +171,7 @@ void recompute_bounds(mt_ctx* c)
     c->fc_first_chunked = true; c->any_conv_first = c->any_fc_first = false;
     c->list_mask = 0; c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        c->has_gap[l] = 0;
+        c->has_gap[l] = 0; c->max_conv_cb[l] = 0;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
     }
     for (const HostTenant& t : c->tenants) {
@@ -194,6 +195,7 @@ void recompute_bounds(mt_ctx* c)
             c->max_rpr[k][l] = std::max(c->max_rpr[k][l], L.rows_per_req);
             c->max_nt[k][l] = std::max(c->max_nt[k][l], nt);
             c->sum_nt[k][l] += nt;
+            if (k == 1) c->max_conv_cb[l] = std::max(c->max_conv_cb[l], std::min<uint32_t>(L.N_pad / kBrickRows, kTileCols / kBrickRows));
             if (k == 0 && L.N_pad >= (uint32_t)kBigMinCols) {      // may be served with big tiles when it gets enough rows
                 c->list_mask |= 1u << (2 * MT_MAX_LAYERS + l);
                 c->max_nt[2][l] = std::max(c->max_nt[2][l], (L.N_pad + kBigTile - 1) / kBigTile);
@@ -209,7 +211,7 @@ uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R)
     if (kind == 2)      // big FC tiles: only tenants with >= kBigMinRows rows; sum ceil(M_t/256) <= R/256 + R/kBigMinRows
         return R < (uint64_t)kBigMinBatch ? 0 : (uint64_t)c->max_nt[2][l] * (R / kBigTile + R / kBigMinRows);
     // FC tiles may be as short as 64 rows (layers with at most 64 outputs)
-    const uint64_t tile_rows = kind == 0 ? kTileRows / 2 : kTileRows;
+    const uint64_t tile_rows = kind == 0 ? kTileRows / 2 : kConvTileRows;
     return (uint64_t)c->max_nt[kind][l] * (R * c->max_rpr[kind][l] / tile_rows) + c->sum_nt[kind][l];
 }
 
@@ -253,9 +255,9 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
             d.cin = round_up(s.in_features, kChanPad);
             d.in_h = s.in_h; d.in_w = s.in_w; d.stride = s.stride; d.out_w = ow;
             d.rows_per_req = oh * ow;
-            d.K = round_up(9 * d.cin, kWidthAlign); d.N = s.out_features; d.N_pad = s.out_features;
+            d.K = round_up(9 * d.cin, kWidthAlign); d.k_valid = 9 * d.cin; d.N = s.out_features; d.N_pad = round_up(s.out_features, kBrickRows);
             d.out_len = oh * ow * s.out_features;
-            hl.w_bytes = (uint64_t)d.N * d.K * es; hl.b_bytes = (uint64_t)d.N * 4;
+            hl.w_bytes = (uint64_t)d.N_pad * d.K * es; hl.b_bytes = (uint64_t)d.N_pad * 4;
         } else if (s.kind == MT_GAP) {
             if (s.in_features == 0 || s.in_h == 0 || s.in_w == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized pool", l);
             if (s.out_features != s.in_features || s.act != MT_ACT_NONE) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling keeps the channel count and has no activation", l);
@@ -292,10 +294,10 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
     return MT_OK;
 }
 
-// Arena image of one layer.  FC: bricks[n_block][k_block][lane][EPC] with lane = row + 32*half
-// (zero rows and columns as padding), the order in which a wavefront consumes MFMA operands.
-// Conv: filters reordered from [Co][Ci][3][3] to rows [Co][kh][kw][ci_padded] so that a GEMM k
-// index walks the NHWC input contiguously, each row zero-padded to the K granularity.
+// Arena image of one layer: bricks[n_block][k_block][lane][EPC] with lane = row + 32*half (zero
+// rows and columns as padding), the order in which a wavefront consumes MFMA operands.  The
+// reduction index k is the fan-in for FC; for conv the filters [Co][Ci][3][3] are read as
+// k = (kh*3 + kw) * ci_padded + ci, so that a GEMM k index walks the NHWC input contiguously.
 template <typename T>
 void pack_weights(const HostLayer& hl, const void* w_src, uint8_t* dst)
 {
@@ -303,23 +305,23 @@ void pack_weights(const HostLayer& hl, const void* w_src, uint8_t* dst)
     const T* src = (const T*)w_src;
     T* out = (T*)dst;
     std::memset(dst, 0, hl.w_bytes);
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    const uint32_t nKB = d.K / KB;
+    auto put = [&](uint32_t n, uint32_t k, T v) {
+        const uint32_t nb = n / kBrickRows, i = n % kBrickRows, kb = k / KB, h = (k % KB) / EPC, e = k % EPC;
+        out[(((size_t)nb * nKB + kb) * 64 + i + 32 * h) * EPC + e] = v;
+    };
     if (d.kind == MT_FC) {
-        constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
-        const uint32_t K = hl.spec.in_features, nKB = d.K / KB;
-        for (uint32_t n = 0; n < d.N; ++n) {
-            const uint32_t nb = n / kBrickRows, i = n % kBrickRows;
-            for (uint32_t k = 0; k < K; ++k) {
-                const uint32_t kb = k / KB, h = (k % KB) / EPC, e = k % EPC;
-                out[(((size_t)nb * nKB + kb) * 64 + i + 32 * h) * EPC + e] = src[(size_t)n * K + k];
-            }
-        }
+        const uint32_t K = hl.spec.in_features;
+        for (uint32_t n = 0; n < d.N; ++n)
+            for (uint32_t k = 0; k < K; ++k) put(n, k, src[(size_t)n * K + k]);
     } else {
         const uint32_t Ci = hl.spec.in_features;
         for (uint32_t co = 0; co < d.N; ++co)
             for (uint32_t ci = 0; ci < Ci; ++ci)
                 for (uint32_t kh = 0; kh < 3; ++kh)
                     for (uint32_t kw = 0; kw < 3; ++kw)
-                        out[(size_t)co * d.K + (kh * 3 + kw) * d.cin + ci] = src[(((size_t)co * Ci + ci) * 3 + kh) * 3 + kw];
+                        put(co, (kh * 3 + kw) * d.cin + ci, src[(((size_t)co * Ci + ci) * 3 + kh) * 3 + kw]);
     }
 }
 
@@ -578,12 +580,12 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         if (((uintptr_t)sg.src & 15) || ((uint64_t)sg.row_stride * c->elem_size) % 16) fuse_gather = false;
     // packed rows: every tenant with traffic pads its segment to a multiple of 32
     const uint32_t P = std::min<uint64_t>(c->P_cap, (uint64_t)round_up(R, kBrickRows) + (uint64_t)kBrickRows * std::min(R, c->n_registered));
-    if (!fuse_gather || c->any_conv_first) {
+    {
         GatherArgs g{};
         g.row_src = c->d_row_src; g.P = P; g.tenants = c->d_tenants; g.layers = c->d_layers; g.row_tenant = c->d_row_tenant;
         g.perm = c->d_perm; g.off = c->d_off; g.T = T; g.act = c->d_act[0]; g.S = c->S; g.elem_size = c->elem_size;
-        g.skip_bricks = fuse_gather;
-        TIMED(kProfGather, launch_gather(g, s));
+        if (c->any_fc_first && !fuse_gather) TIMED(kProfGather, launch_gather(g, s));
+        if (c->any_conv_first) TIMED(kProfGatherImg, launch_gather_image(g, s));
     }
 
     for (uint32_t l = 0; l < c->n_layer_slots; ++l) {
@@ -601,7 +603,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad;
             const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, 0x7ffffff0u);
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
-            else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, g32, s));
+            else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], g32, s));
             else TIMED(kProfBig + l, launch_fc_big(ga, c->cfg.dtype, g32, s));
         }
         if (c->has_gap[l]) {
@@ -671,6 +673,7 @@ mt_status mt_get_profile(mt_ctx* c, mt_profile* out)
     };
     HIP_TRY(c, ms(kProfBatcher, &out->batcher_ms));
     HIP_TRY(c, ms(kProfGather, &out->gather_ms));
+    { float img = 0.0f; HIP_TRY(c, ms(kProfGatherImg, &img)); out->gather_ms += img; }
     HIP_TRY(c, ms(kProfHead, &out->head_ms));
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
         HIP_TRY(c, ms(kProfFc + l, &out->fc_ms[l]));

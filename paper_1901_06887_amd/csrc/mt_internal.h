@@ -21,6 +21,7 @@ constexpr int kBrickRows = 32;
 constexpr int kBrickBytes = 1024;
 constexpr int kTileRows = 128;      // rows (4 row blocks) of a grouped-GEMM workgroup tile
 constexpr int kTileCols = 128;      // columns (4 column blocks) of a workgroup tile
+constexpr int kConvTileRows = 128;  // GEMM rows (output pixels) of a conv workgroup tile: one 32-row block per wave
 // A tenant-layer with at least kBigMinRows requests and kBigMinCols (padded) outputs is
 // compute bound; it is cut into kBigTile x kBigTile tiles and served by the big-tile FC kernel.
 constexpr int kBigTile = 256;
@@ -38,7 +39,7 @@ enum : uint32_t { kLayoutRows = 0, kLayoutBricks = 1 };
 struct LayerDev {
     uint32_t kind, act;
     uint32_t K;          // reduction length as stored (padded to kWidthAlign), elements
-    uint32_t k_valid;    // FC: true fan-in (the rest of K is zero padding)
+    uint32_t k_valid;    // FC: true fan-in; CONV: 9 * cin (the rest of K is zero padding)
     uint32_t N;          // output features (FC) / output channels (CONV)
     uint32_t N_pad;      // FC: weight rows as stored (multiple of 32; of 64 for hidden layers)
     uint32_t in_h, in_w; // CONV / GAP input geometry
@@ -110,7 +111,6 @@ struct GatherArgs {
     const TenantDev* tenants; const LayerDev* layers; const int32_t* row_tenant; const int32_t* perm;
     const uint32_t* off; uint32_t T;
     void* act; uint32_t S; uint32_t elem_size;
-    uint32_t skip_bricks;   // 1: FC-first tenants are gathered by the FC kernel itself
 };
 
 struct GemmArgs {
@@ -141,9 +141,11 @@ struct HeadArgs {
 // Launchers (defined in mt_kernels.hip).  All enqueue on `s` and return the launch status.
 hipError_t launch_batcher(const BatchArgs& a, hipStream_t s);
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
+hipError_t launch_gather_image(const GatherArgs& a, hipStream_t s);
 hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
 hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
-hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
+// max_cb: the widest tile of this layer index over the registered tenants, in 32-channel blocks (1..4)
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, uint32_t grid, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, hipStream_t s);
 hipError_t launch_head(const HeadArgs& a, hipStream_t s);
 

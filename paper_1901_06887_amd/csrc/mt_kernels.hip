@@ -248,8 +248,8 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             const uint32_t np = slot == 0 ? npad[0][l] : npad[1][l];
             const bool conv = rr >> 31;
             const bool big = !conv && a.big_enabled && fc_is_big(Mt, np);
-            // conv: rows = requests * output pixels, 128 per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
-            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
+            // conv: rows = requests * output pixels, 512 per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
+            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
             c[l] = (conv || big) ? 0 : tiles;
             c[MT_MAX_LAYERS + l] = conv ? tiles : 0;
             c[2 * MT_MAX_LAYERS + l] = big ? ceil_div(Mt, kBigTile) * ceil_div(np, kBigTile) : 0;
@@ -284,26 +284,41 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     if (tid < kLists && (tid % MT_MAX_LAYERS) < NL) a.tile_base[(size_t)tid * (T + 1) + T] = carry[tid];
 }
 
-// ---- gather: one workgroup per block of 32 packed rows ------------------------------------
+// ---- gather ------------------------------------------------------------------------------
+// Images (first layer is a convolution): one workgroup per packed row, one thread per pixel;
+// channels are padded with zeros to a multiple of 8 so that every tap of the implicit GEMM is
+// a whole number of 16-byte chunks.
 template <typename T>
-__device__ void gather_rows_layout(const GatherArgs& a, const TenantDev& td, uint32_t p0)
+__device__ void gather_image(const GatherArgs& a, const TenantDev& td, uint32_t p, uint32_t r)
 {
-    // NHWC rows (first layer is a convolution), channels padded with zeros
-    for (uint32_t i = 0; i < kBrickRows; ++i) {
-        const int32_t r = a.perm[p0 + i];
-        if (r < 0) continue;
-        const T* src = (const T*)a.row_src[r];
-        T* dst = (T*)a.act + (size_t)(p0 + i) * a.S;
-        const uint32_t ci = td.in_cin ? td.in_cin : 1, cp = td.in_cin ? td.in_cin_pad : 1;
-        const uint32_t npix = td.in_len / ci;
-        for (uint32_t e = threadIdx.x; e < npix * cp; e += blockDim.x) {
-            const uint32_t pix = e / cp, c = e % cp;
-            dst[e] = c < ci ? src[pix * ci + c] : (T)0.0f;
+    constexpr uint32_t EPC = 16 / sizeof(T);
+    const T* src = (const T*)a.row_src[r];
+    T* dst = (T*)a.act + (size_t)p * a.S;
+    const uint32_t ci = td.in_cin ? td.in_cin : kChanPad, cp = td.in_cin ? td.in_cin_pad : kChanPad;
+    const uint32_t npix = td.in_len / ci;
+    for (uint32_t pix = threadIdx.x; pix < npix; pix += blockDim.x) {
+        for (uint32_t g = 0; g < cp; g += EPC) {
+            alignas(16) T tmp[EPC];
+#pragma unroll
+            for (uint32_t c = 0; c < EPC; ++c) tmp[c] = g + c < ci ? src[(size_t)pix * ci + g + c] : (T)0.0f;
+            *(u32x4*)(dst + (size_t)pix * cp + g) = *(const u32x4*)tmp;
         }
-        for (uint32_t e = npix * cp + threadIdx.x; e < td.in_fill; e += blockDim.x) dst[e] = (T)0.0f;
     }
+    for (uint32_t e = npix * cp + threadIdx.x; e < td.in_fill; e += blockDim.x) dst[e] = (T)0.0f;
 }
 
+__global__ __launch_bounds__(256) void gather_image_kernel(GatherArgs a)
+{
+    const uint32_t p = blockIdx.x;
+    if (p >= a.off[a.T]) return;
+    const int32_t r = a.perm[p];
+    if (r < 0) return;
+    const TenantDev td = a.tenants[a.row_tenant[r]];
+    if (td.in_layout == kLayoutBricks) return;
+    if (a.elem_size == 2) gather_image<__bf16>(a, td, p, (uint32_t)r); else gather_image<float>(a, td, p, (uint32_t)r);
+}
+
+// Vectors (first layer is FC): one workgroup per block of 32 packed rows, written as bricks.
 template <typename T>
 __device__ void gather_bricks(const GatherArgs& a, const TenantDev& td, uint32_t t, uint32_t p0)
 {
@@ -340,12 +355,8 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
     const int32_t r0 = a.perm[p0];        // the first row of a block is always a real request
     const uint32_t t = (uint32_t)a.row_tenant[r0];
     const TenantDev td = a.tenants[t];
-    if (td.in_layout == kLayoutBricks) {
-        if (a.skip_bricks) return;
-        if (a.elem_size == 2) gather_bricks<__bf16>(a, td, t, p0); else gather_bricks<float>(a, td, t, p0);
-    } else {
-        if (a.elem_size == 2) gather_rows_layout<__bf16>(a, td, p0); else gather_rows_layout<float>(a, td, p0);
-    }
+    if (td.in_layout != kLayoutBricks) return;               // images have their own kernel
+    if (a.elem_size == 2) gather_bricks<__bf16>(a, td, t, p0); else gather_bricks<float>(a, td, t, p0);
 }
 
 // ---- shared pieces of the GEMM kernels -----------------------------------------------------
@@ -958,151 +969,141 @@ __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
 }
 
 // ---- grouped 3x3 convolution as implicit GEMM ---------------------------------------------
-// One workgroup = 4 waves in a 2x2 grid over a 128x128 tile of (output pixels) x (output
-// channels); a wave owns 64x64 = 2x2 MFMA blocks.  K = 9 * C_in walks the NHWC input tap by
-// tap, 128 bytes per row per step, through two LDS stages; out-of-image taps load zeros.
-constexpr int kLdsRow = kRowBytes + 16;            // padded LDS row, bytes
-constexpr int kTileBytes = kTileRows * kLdsRow;    // one operand tile of one stage
+// GEMM view: rows = (request, output pixel), columns = output channels, K = (kh, kw, c_in).
+// A workgroup takes 128 consecutive rows of one tenant and up to 128 output channels; each of
+// its four waves owns 32 rows and all the channels, and no operand is shared between waves:
+// the activation operand of a k step is gathered straight from the NHWC input into MFMA
+// registers (16 bytes per lane = 8 channels of one tap; taps outside the image read as
+// zeros), the filter bricks come from L1/L2 (a layer's filters are at most ~150 KB and shared
+// by every tile of the tenant).  The MFMA takes the filter brick as its row operand and the
+// pixels as its column operand, so a lane ends up with runs of four consecutive channels of
+// ITS pixel and stores them straight to the NHWC output: no LDS, no barrier, and the pixel's
+// address is the one the lane already derived for its loads.
+template <typename T, int CB>
+__device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, uint32_t seg0, uint32_t m0, uint32_t rows_total, uint32_t nb0)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC, P = 4;
+    typedef const __attribute__((address_space(1))) u32x4* gptr_t;
+    const uint32_t lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
+    const uint32_t nKB = L.K / KB, nKBv = ceil_div(L.k_valid, KB);  // bricks per filter row; k steps that hold real taps
+    const uint32_t rpr = L.rows_per_req, cin = L.cin;
 
-template <typename T>
+    // this lane's GEMM row: request, output pixel, top-left input coordinate
+    const uint32_t m = m0 + li;
+    const bool row_ok = m < rows_total;
+    const uint32_t mm = row_ok ? m : m0;                           // rows past the end repeat the first one and are dropped
+    const uint32_t req = mm / rpr, pix = mm % rpr;
+    const int32_t ih0 = (int32_t)((pix / L.out_w) * L.stride) - 1, iw0 = (int32_t)((pix % L.out_w) * L.stride) - 1;
+    gptr_t img = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
+    gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)nb0 * nKB * 64 + lane);
+
+    // The lane's position in K, kept incrementally: tap (th, tw) and channel c0 inside it.  A
+    // k step moves KB channels on, which crosses at most two taps because cin >= 8.
+    uint32_t c0 = lh * EPC;
+    int32_t th = 0, tw = 0;
+    auto wrap = [&]() { if (c0 >= cin) { c0 -= cin; if (++tw == 3) { tw = 0; ++th; } } };
+    wrap(); wrap();
+    auto load_a = [&]() -> u32x4 {                                 // the next k step's chunk; steps past the last tap read as zeros
+        const int32_t ih = ih0 + th, iw = iw0 + tw;
+        const bool ok = row_ok && th < 3 && ih >= 0 && ih < (int32_t)L.in_h && iw >= 0 && iw < (int32_t)L.in_w;
+        const uint32_t off = ok ? ((uint32_t)(ih * (int32_t)L.in_w + iw) * cin + c0) / EPC : 0;   // a safe address either way
+        const u32x4 v = img[off];
+        c0 += KB; wrap(); wrap();
+        return ok ? v : u32x4{0, 0, 0, 0};
+    };
+
+    f32x16 acc[CB];
+#pragma unroll
+    for (int c = 0; c < CB; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][v] = 0.0f;
+    // both operands of a k step travel P steps ahead of their use in register rings
+    u32x4 aq[P], wq[P][CB];
+    auto load_w = [&](uint32_t j, uint32_t kb) {
+#pragma unroll
+        for (int c = 0; c < CB; ++c) wq[j][c] = wp[((size_t)c * nKB + kb) * 64];
+    };
+#pragma unroll
+    for (uint32_t j = 0; j < P; ++j) {
+        aq[j] = load_a();
+        load_w(j, min(j, nKBv - 1));
+    }
+    const uint32_t full = nKBv / P;
+    for (uint32_t g = 0; g < full; ++g) {
+#pragma unroll
+        for (uint32_t j = 0; j < P; ++j) {
+            const uint32_t kb = g * P + j;
+#pragma unroll
+            for (int c = 0; c < CB; ++c) Mma<T>::run(acc[c], wq[j][c], aq[j]);   // rows = channels, columns = pixels
+            aq[j] = load_a();
+            load_w(j, min(kb + P, nKBv - 1));
+            __builtin_amdgcn_sched_barrier(0);                     // keeps the refills here, P steps ahead of their use
+        }
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < P; ++j) {
+        const uint32_t kb = full * P + j;
+        if (kb < nKBv) {
+#pragma unroll
+            for (int c = 0; c < CB; ++c) Mma<T>::run(acc[c], wq[j][c], aq[j]);
+        }
+    }
+
+    // epilogue: the lane holds, for pixel li, channels 8g + 4 lh + {0..3} (g = 0..3) of every
+    // channel block: bias, activation, rounding, and one store of four channels per run
+    if (!row_ok) return;
+    const float* bias = (const float*)(a.arena + L.b_off);
+    T* out = (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N;
+#pragma unroll
+    for (int c = 0; c < CB; ++c) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint32_t n = (nb0 + c) * kBrickRows + 8 * g + 4 * lh;
+            const f32x4 bv = *(const f32x4*)(bias + n);             // bias is padded to N_pad
+            T r[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = (T)activate(acc[c][4 * g + i] + bv[i], L.act);
+            if (n < L.N) {                                          // N is a multiple of 8: a run is in or out as a whole
+                if constexpr (sizeof(T) == 2) *(uint64_t*)(out + n) = __builtin_bit_cast(uint64_t, r);
+                else *(u32x4*)(out + n) = __builtin_bit_cast(u32x4, r);
+            }
+        }
+    }
+}
+
+// MAXCB bounds the channel blocks of any tile in the launch: narrow layers get a kernel with
+// few registers and many resident waves, which is what hides the latency of their short K loops.
+template <typename T, int MAXCB>
 __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[4 * kTileBytes];
-    constexpr uint32_t EPC = 16 / sizeof(T);          // elements per 16-byte chunk
-    constexpr uint32_t EPS = kRowBytes / sizeof(T);   // elements of K per step
-
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint32_t* base_l = (uint32_t*)lds;                 // tile_base during the lookup, operand tiles afterwards
+    __shared__ uint32_t base_l[kMaxTenantsPadded + 1];
+    const uint32_t tid = threadIdx.x, wave = tid >> 6;
     const uint32_t n_tiles = a.tile_base[a.T];
     for (uint32_t i = tid; i <= a.T; i += 256) base_l[i] = a.tile_base[i];
     uint32_t idx;
     if (!logical_tile(n_tiles, &idx)) return;
     __syncthreads();
-    Tile tl;
-    tl.tenant = find_tenant(base_l, a.T, idx);
-    const uint32_t local = idx - base_l[tl.tenant];
-    __syncthreads();                                   // everyone is done with base_l before the tiles overwrite it
-    const LayerDev L = a.layers[tl.tenant * MT_MAX_LAYERS + a.layer];
-    const uint32_t seg0 = a.off[tl.tenant];
-    {
-        const uint32_t rows = a.M[tl.tenant] * L.rows_per_req, mt_ = ceil_div(rows, kTileRows);
-        tl.m0 = (local % mt_) * kTileRows;
-        tl.rows = min((uint32_t)kTileRows, rows - tl.m0);
-        tl.n0 = (local / mt_) * kTileCols;
-        tl.split = 0;
-    }
-    const uint32_t wm = wave >> 1, wn = wave & 1;
-    const uint32_t li = lane & 31, lh = lane >> 5;
-
-    // global -> register staging: thread owns chunk `lc` of rows lr + 32*i
-    const uint32_t lc = tid & 7, lr = tid >> 3;
-    const T* act_in = (const T*)a.act_in;
-    const T* W = (const T*)(a.arena + L.w_off);
-    const T* a_ptr[4]; bool a_ok[4]; int32_t a_oh[4], a_ow[4];
-    const T* b_ptr[4]; bool b_ok[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t row = lr + 32 * i;
-        const uint32_t m = tl.m0 + row;
-        a_ok[i] = row < tl.rows;
-        const uint32_t req = m / L.rows_per_req, pix = m % L.rows_per_req;
-        a_ptr[i] = act_in + (size_t)(seg0 + req) * a.S;
-        a_oh[i] = (int32_t)((pix / L.out_w) * L.stride) - 1;
-        a_ow[i] = (int32_t)((pix % L.out_w) * L.stride) - 1;
-        const uint32_t n = tl.n0 + row;
-        b_ok[i] = n < L.N;
-        b_ptr[i] = W + (size_t)n * L.K;
-    }
-    const uint32_t n_steps = L.K / EPS;
-
-    u32x4 ra[4], rb[4];
-    auto load_step = [&](uint32_t step) {
-        const uint32_t k = step * EPS + lc * EPC;
-        const uint32_t tap = k / L.cin, c0 = k % L.cin;
-        const int32_t kh = (int32_t)(tap / 3), kw = (int32_t)(tap % 3);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int32_t ih = a_oh[i] + kh, iw = a_ow[i] + kw;
-            const bool ok = a_ok[i] && tap < 9 && ih >= 0 && ih < (int32_t)L.in_h && iw >= 0 && iw < (int32_t)L.in_w;
-            ra[i] = ok ? *(const u32x4*)(a_ptr[i] + ((size_t)(ih * (int32_t)L.in_w + iw) * L.cin + c0)) : u32x4{0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) rb[i] = b_ok[i] ? *(const u32x4*)(b_ptr[i] + k) : u32x4{0, 0, 0, 0};
-    };
-    auto store_step = [&](uint32_t stage) {
-        uint8_t* As = lds + stage * 2 * kTileBytes;
-        uint8_t* Bs = As + kTileBytes;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *(u32x4*)(As + (lr + 32 * i) * kLdsRow + lc * 16) = ra[i];
-            *(u32x4*)(Bs + (lr + 32 * i) * kLdsRow + lc * 16) = rb[i];
-        }
-    };
-
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    // waves whose rows or columns lie wholly past the valid part of the tile skip the MFMAs
-    const bool wave_active = wm * 64 < tl.rows && tl.n0 + wn * 64 < L.N;
-    const bool mb1_active = wm * 64 + 32 < tl.rows;
-    const bool nb1_active = tl.n0 + wn * 64 + 32 < L.N;
-
-    load_step(0);
-    store_step(0);
-    lds_barrier();
-    for (uint32_t step = 0; step < n_steps; ++step) {
-        const uint32_t cur = step & 1;
-        if (step + 1 < n_steps) load_step(step + 1);
-        if (wave_active) {
-            const uint8_t* As = lds + cur * 2 * kTileBytes + (wm * 64 + li) * kLdsRow + lh * 16;
-            const uint8_t* Bs = lds + cur * 2 * kTileBytes + kTileBytes + (wn * 64 + li) * kLdsRow + lh * 16;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const u32x4 a0 = *(const u32x4*)(As + s * 32);
-                const u32x4 b0 = *(const u32x4*)(Bs + s * 32);
-                Mma<T>::run(acc[0][0], a0, b0);
-                if (nb1_active) {
-                    const u32x4 b1 = *(const u32x4*)(Bs + 32 * kLdsRow + s * 32);
-                    Mma<T>::run(acc[0][1], a0, b1);
-                    if (mb1_active) {
-                        const u32x4 a1 = *(const u32x4*)(As + 32 * kLdsRow + s * 32);
-                        Mma<T>::run(acc[1][0], a1, b0);
-                        Mma<T>::run(acc[1][1], a1, b1);
-                    }
-                } else if (mb1_active) {
-                    const u32x4 a1 = *(const u32x4*)(As + 32 * kLdsRow + s * 32);
-                    Mma<T>::run(acc[1][0], a1, b0);
-                }
-            }
-        }
-        if (step + 1 < n_steps) store_step(cur ^ 1);
-        lds_barrier();
-    }
-
-    // epilogue: bias, activation, rounding, NHWC store
-    if (!wave_active) return;
-    const float* bias = (const float*)(a.arena + L.b_off);
-    T* act_out = (T*)a.act_out;
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const uint32_t n = tl.n0 + wn * 64 + nb * 32 + li;
-        if (n >= L.N) continue;
-        const float bv = bias[n];
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const uint32_t row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-                if (row >= tl.rows) continue;
-                const uint32_t m = tl.m0 + row;
-                const uint32_t req = m / L.rows_per_req, pix = m % L.rows_per_req;
-                act_out[(size_t)(seg0 + req) * a.S + (size_t)pix * L.N + n] = (T)activate(acc[mb][nb][v] + bv, L.act);
-            }
+    const uint32_t t = find_tenant(base_l, a.T, idx);
+    const uint32_t local = idx - base_l[t];
+    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    const uint32_t seg0 = a.off[t];
+    const uint32_t rows_total = a.M[t] * L.rows_per_req, mt_ = ceil_div(rows_total, kConvTileRows);
+    const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
+    const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
+    // no barrier below: the waves are independent; wave w takes row blocks w, w+4, ... of the tile
+    for (uint32_t rb = wave; rb < kConvTileRows / kBrickRows; rb += 4) {
+        const uint32_t m0 = (local % mt_) * kConvTileRows + rb * kBrickRows;
+        if (m0 >= rows_total) break;
+        if constexpr (MAXCB == 1) {
+            conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0);
+        } else if constexpr (MAXCB == 2) {
+            if (ncb == 1) conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0);
+            else conv_wave<T, 2>(a, L, seg0, m0, rows_total, nb0);
+        } else {
+            if (ncb == 1) conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0);
+            else if (ncb == 2) conv_wave<T, 2>(a, L, seg0, m0, rows_total, nb0);
+            else if (ncb == 3) conv_wave<T, 3>(a, L, seg0, m0, rows_total, nb0);
+            else conv_wave<T, 4>(a, L, seg0, m0, rows_total, nb0);
         }
     }
 }
@@ -1193,6 +1194,11 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     hipLaunchKernelGGL(gather_kernel, dim3(a.P / kBrickRows), dim3(256), 0, s, a);
     return hipGetLastError();
 }
+hipError_t launch_gather_image(const GatherArgs& a, hipStream_t s)
+{
+    hipLaunchKernelGGL(gather_image_kernel, dim3(a.P), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
 hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)
 {
     if (grid == 0) return hipSuccess;
@@ -1209,12 +1215,20 @@ hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipSt
     else hipLaunchKernelGGL(fc_big_kernel<float>, dim3(grid), dim3(kBigThreads), 0, s, a);
     return hipGetLastError();
 }
-hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)
+template <typename T>
+static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, uint32_t grid, hipStream_t s)
+{
+    if (max_cb <= 1) hipLaunchKernelGGL((conv_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a);
+    else if (max_cb == 2) hipLaunchKernelGGL((conv_kernel<T, 2>), dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((conv_kernel<T, 4>), dim3(grid), dim3(256), 0, s, a);
+}
+
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, uint32_t grid, hipStream_t s)
 {
     if (grid == 0) return hipSuccess;
     grid = (grid + 7) / 8 * 8;
-    if (dtype == MT_BF16) hipLaunchKernelGGL(conv_kernel<__bf16>, dim3(grid), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(conv_kernel<float>, dim3(grid), dim3(256), 0, s, a);
+    if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, grid, s);
+    else launch_conv_t<float>(a, max_cb, grid, s);
     return hipGetLastError();
 }
 hipError_t launch_gap(const GapArgs& a, hipStream_t s)

@@ -101,7 +101,7 @@ def test_cnn_chain_is_accepted():
     # packed sizes: K padded to 64 elements per row (conv1: 9*8=72 -> 128), the logits layer's
     # rows padded to 32, 256-byte aligned slices
     exp = sum((n * k * 2 + 255) // 256 * 256 + (n * 4 + 255) // 256 * 256
-              for n, k in ((32, 128), (64, 320), (128, 576), (32, 128)))
+              for n, k in ((32, 128), (64, 320), (128, 576), (32, 128)))     # conv rows are padded to 32 too (32, 64, 128 already are)
     assert c.stats()["arena_used"] == exp
 
 
