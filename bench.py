@@ -9,7 +9,15 @@ models already resident in device memory.  Prints one JSON line.
   roofline    the grouped GEMM kernel against HBM bandwidth (weight-streaming mixes) or the
               bf16 MFMA peak (c5), from its average launch duration measured with HIP events
               on the run's stream in a second pass over the same K steps (event brackets cost
-              microseconds per kernel, so they stay out of the throughput pass)
+              microseconds per kernel, so they stay out of the throughput pass); the duration
+              is the bracket (`avg_bracket_us`) less what an empty bracket reads
+              (`empty_bracket_us`), which is what makes it agree with a kernel trace
+              `traffic` is the HBM bytes per launch of that kernel from stored hardware-counter
+              runs (profiles/), null when there is none for this workload or the device code
+              has changed since they were taken
+  device_ms   per-step device time between two events around the run (median, p99/mean), and
+              the same with the caches flushed between steps (`cold`): a batch whose weights
+              fit the last-level cache is otherwise partly served from it on repeated runs
   cpu_baseline the fp64 oracle timed on the host cores on a bounded sample of the same batch
 """
 import argparse
@@ -60,6 +68,8 @@ def main():
     ap.add_argument("--config", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time of the CPU baseline sample")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="first run the library's plain copy kernel over this many MiB (byte-counter yardstick)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -87,6 +97,14 @@ def main():
     def step():
         mt.serve(ctx, d_ids, d_x, out=out, stream=stream)
 
+    if args.calibrate_copy_mib:
+        nb = args.calibrate_copy_mib << 20
+        a_buf, b_buf = torch.zeros(nb, dtype=torch.uint8, device="cuda"), torch.empty(nb, dtype=torch.uint8, device="cuda")
+        for _ in range(4):
+            mt.debug_copy(b_buf.data_ptr(), a_buf.data_ptr(), nb, stream.cuda_stream)
+        torch.cuda.synchronize()
+        del a_buf, b_buf
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -97,6 +115,36 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
     value = R * args.steps / dt
+
+    # per-step device time (two events around each step), warm and with caches flushed between steps
+    def device_times(n, flush=None):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for e0, e1 in ev:
+            if flush is not None:
+                flush.add_(1)
+            e0.record(stream)
+            step()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        return np.array([e0.elapsed_time(e1) for e0, e1 in ev])
+    warm = device_times(args.steps)
+    n_cold = max(5, min(args.steps, 30))
+    flush = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")       # 4x the last-level cache
+    cold = device_times(n_cold, flush)
+    del flush
+    device_ms = {"median": float(np.median(warm)), "mean": float(warm.mean()), "p99_over_mean": float(np.percentile(warm, 99) / warm.mean()),
+                 "cold_median": float(np.median(cold)), "cold_steps": n_cold,
+                 "cold_inferences_per_sec": float(R / (np.median(cold) * 1e-3))}
+
+    # what a pair of events reads with nothing between them: every per-kernel bracket below
+    # carries that much on top of the kernel's own duration
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
+    for e0, e1 in pairs:
+        step()                                     # same queue state as in the profiled pass: work ahead of the bracket
+        e0.record(stream)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    bracket_ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in pairs]))
 
     # second pass over the same steps with per-kernel HIP events on the run's stream
     ctx.set_profiling(True)
@@ -116,7 +164,8 @@ def main():
         dom_ms, dom_name = big_ms, "fc_big_kernel"
     other_ms = fc_ms if dom_ms is conv_ms else conv_ms
     launches = [l for l in range(n_slots) if dom_ms[l] > 0 and other_ms[l] == 0 and l in bytes_]
-    avg_dur_s = sum(dom_ms[l] for l in launches) / len(launches) * 1e-3
+    raw_dur_s = sum(dom_ms[l] for l in launches) / len(launches) * 1e-3
+    avg_dur_s = max(raw_dur_s - bracket_ms * 1e-3, 0.5 * raw_dur_s)
     avg_bytes = sum(bytes_[l] for l in launches) / len(launches)
     avg_flops = sum(flops[l] for l in launches) / len(launches)
     cost = wl.algorithmic_cost(w)
@@ -129,9 +178,12 @@ def main():
         achieved = avg_bytes / avg_dur_s / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": None}
+    from paper_1901_06887_amd import profile_summary
+    traffic_file = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.md" % (dom_name, w.name))
+    roofline["traffic"] = profile_summary.read_traffic(traffic_file)
     roofline.update({"kernel": "%s<%s>" % (dom_name, "bf16" if es == 2 else "float"),
                      "launches_per_step": len(launches),
-                     "avg_launch_us": avg_dur_s * 1e6,
+                     "avg_launch_us": avg_dur_s * 1e6, "avg_bracket_us": raw_dur_s * 1e6, "empty_bracket_us": bracket_ms * 1e3,
                      "algorithmic_bytes_per_launch": avg_bytes, "algorithmic_flops_per_launch": avg_flops})
     kernels_us = {"batcher": float(np.mean([p["batcher_ms"] for p in prof])) * 1e3,
                   "gather": float(np.mean([p["gather_ms"] for p in prof])) * 1e3,
@@ -172,7 +224,7 @@ def main():
                        "algorithmic_bytes_per_step": cost["bytes"],
                        "whole_path_hbm_frac": cost["bytes"] / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
                        "whole_path_mfma_frac": cost["flops"] / (ms_per_step * 1e-3) / (MFMA_BF16_PEAK_TFLOPS * 1e12)},
-            "roofline": roofline, "kernels_us": kernels_us, "cpu_baseline": cpu}
+            "roofline": roofline, "device_ms": device_ms, "kernels_us": kernels_us, "cpu_baseline": cpu}
     print(json.dumps(line))
     ctx.close()
 

@@ -184,6 +184,13 @@ mt_status mt_get_profile(mt_ctx* ctx, mt_profile* out);
  * reads, so results must not change.  Errors: MT_ESTATE (host-only), MT_EDEVICE. */
 mt_status mt_debug_poison(mt_ctx* ctx);
 
+/* Measurement aid: one plain copy kernel (16 bytes per lane, grid-stride) of `bytes` bytes
+ * (a multiple of 16) from `src` to `dst`, both device memory owned by the caller, on `stream`
+ * of the current device.  It reads and writes exactly `bytes` bytes once each, which is what
+ * hardware byte counters are calibrated against.  Errors: MT_EINVAL (null pointer, size not
+ * a multiple of 16), MT_EDEVICE (launch failure). */
+mt_status mt_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+
 /* Text of the last error on this context ("" if none); valid until the next call. */
 const char* mt_last_error(const mt_ctx* ctx);
 

@@ -80,13 +80,14 @@ def load_library() -> ctypes.CDLL:
     L.mt_last_counts.argtypes = [vp, ctypes.POINTER(u32)]
     L.mt_get_stats.argtypes = [vp, ctypes.POINTER(mt_stats)]
     L.mt_debug_poison.argtypes = [vp]
+    L.mt_debug_copy.argtypes = [vp, vp, ctypes.c_uint64, vp]
     L.mt_set_profiling.argtypes = [vp, ctypes.c_int]
     L.mt_get_profile.argtypes = [vp, ctypes.POINTER(mt_profile)]
     L.mt_last_error.argtypes = [vp]
     L.mt_last_error.restype = ctypes.c_char_p
     L.mt_version.restype = ctypes.c_char_p
     for name in ("mt_create", "mt_destroy", "mt_register_model", "mt_unregister_model", "mt_submit",
-                 "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_debug_poison",
+                 "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_debug_poison", "mt_debug_copy",
                  "mt_set_profiling", "mt_get_profile"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -199,6 +200,13 @@ class Context:
         s = mt_stats()
         self._check(self._lib.mt_get_stats(self._h, ctypes.byref(s)))
         return {k: getattr(s, k) for k, _ in mt_stats._fields_}
+
+
+def debug_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
+    """Plain device copy kernel of a known size (a yardstick for byte counters)."""
+    st = load_library().mt_debug_copy(dst, src, nbytes, stream)
+    if st != 0:
+        raise MtError(st, "mt_debug_copy failed")
 
 
 def version() -> str:

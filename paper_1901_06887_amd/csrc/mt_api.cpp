@@ -70,6 +70,7 @@ struct mt_ctx {
     uint32_t list_mask = 0;        // bit kind*MT_MAX_LAYERS + l: some registered model has that kind at layer l
     uint32_t max_reg_classes = 0, min_reg_classes = 0;
     uint32_t no_fused_head = 0;    // tuning/testing: always run the separate head kernel
+    uint32_t big_min_tiles = kBigMinTiles;   // testing: MT_BIG_MIN_TILES=1 sends every qualifying tenant-layer to big tiles
     uint32_t P_cap = 0;        // packed rows incl. per-tenant padding to 32
 
     // device state
@@ -352,6 +353,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     if (const char* e = getenv("MT_FC_SPLIT_K")) c->fc_split_k = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_GATHER")) c->no_fused_gather = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_HEAD")) c->no_fused_head = atoi(e) != 0;
+    if (const char* e = getenv("MT_BIG_MIN_TILES")) c->big_min_tiles = (uint32_t)std::max(1, atoi(e));
     c->tenants.resize(cfg->max_tenants);
     c->cfg.arena_bytes = cfg->arena_bytes / kArenaAlign * kArenaAlign;
     c->free_list.push_back(FreeBlock{0, c->cfg.arena_bytes});
@@ -554,7 +556,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     b.tenants = c->d_tenants; b.layers = c->d_layers;
     b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
     b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.fc_split_k = c->fc_split_k;
-    b.list_mask = c->list_mask; b.big_enabled = big_enabled;
+    b.list_mask = c->list_mask; b.big_enabled = big_enabled; b.big_min_tiles = c->big_min_tiles;
     const OutPtrs outp{out->labels, out->probs, out->logits, out->n_classes, out->row_stride};
     b.out = outp;
     // A last layer of at most 32 classes is one column block: its FC tiles finish their rows
@@ -573,8 +575,10 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     // The FC kernel of layer 0 reads the submitted rows itself when every row is 16-byte aligned
     // and a whole number of 16-byte chunks long; otherwise (and for CNN models, whose images are
     // channel-padded) a gather pass stages the inputs first.
-    // The big-tile kernel reads bricks only: whenever a tenant could reach it at layer 0, stage.
-    const bool big_possible = big_enabled && c->max_nt[2][0] > 0;
+    // The big-tile kernel reads bricks only (it was measured slower when it gathers rows itself,
+    // since every row is then fetched in 16-byte pieces by each of a layer's column tiles):
+    // whenever a tenant could reach it at layer 0, stage.
+    const bool big_possible = big_enabled && c->max_nt[2][0] > 0 && tile_bound(c, 2, 0, R) >= c->big_min_tiles;
     bool fuse_gather = c->any_fc_first && c->fc_first_chunked && !c->no_fused_gather && !big_possible;
     for (const Segment& sg : c->pending)
         if (((uintptr_t)sg.src & 15) || ((uint64_t)sg.row_stride * c->elem_size) % 16) fuse_gather = false;
@@ -593,7 +597,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         void* outb = c->d_act[(l + 1) & 1];
         for (int kind = 0; kind < kListKinds; ++kind) {
             const uint64_t grid = tile_bound(c, kind, l, R);
-            if (grid == 0) continue;
+            if (grid == 0 || (kind == 2 && grid < c->big_min_tiles)) continue;   // too few big tiles possible: the batcher made none
             GemmArgs ga{};
             ga.tile_base = c->d_tile_base + ((size_t)kind * MT_MAX_LAYERS + l) * (T + 1);
             ga.T = T; ga.layer = l; ga.fc_split_k = c->fc_split_k;
@@ -683,6 +687,12 @@ mt_status mt_get_profile(mt_ctx* c, mt_profile* out)
     }
     HIP_TRY(c, hipEventElapsedTime(&out->total_ms, c->prof_events[2 * kProfBatcher], c->prof_events[2 * c->prof_last + 1]));
     return MT_OK;
+}
+
+mt_status mt_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream)
+{
+    if (!dst || !src || bytes % 16) return MT_EINVAL;
+    return launch_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? MT_OK : MT_EDEVICE;
 }
 
 mt_status mt_debug_poison(mt_ctx* c)

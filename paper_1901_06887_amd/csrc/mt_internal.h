@@ -27,6 +27,7 @@ constexpr int kConvTileRows = 128;  // GEMM rows (output pixels) of a conv workg
 constexpr int kBigTile = 256;
 constexpr int kBigMinRows = 2048;
 constexpr int kBigMinCols = 192;
+constexpr int kBigMinTiles = 512;   // a layer index is served with big tiles only when it has at least two per compute unit
 constexpr int kBigMinBatch = 8192;  // runs with fewer rows are latency/HBM bound as a whole: no big tiles
 constexpr int kListKinds = 3;       // tile lists per layer index: FC (streaming), conv, FC (big tiles)
 constexpr int kRowBytes = 128;      // conv path: bytes of K one pipeline step consumes per row
@@ -93,6 +94,7 @@ struct BatchArgs {
     uint32_t elem_size;
     uint32_t fc_split_k;   // 1: FC tiles take one column block each and split K four ways
     uint32_t big_enabled;  // 0: no tenant-layer is given big tiles in this run (small batches)
+    uint32_t big_min_tiles; // a layer index uses big tiles only when its qualifying tenants make at least this many
     const TenantDev* tenants; const LayerDev* layers;
     int32_t* row_tenant;   // [R] tenant of each submitted row, -1 if rejected
     uint32_t* row_rank;    // [R] scratch
@@ -145,6 +147,7 @@ hipError_t launch_gather_image(const GatherArgs& a, hipStream_t s);
 hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
 hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
 // max_cb: the widest tile of this layer index over the registered tenants, in 32-channel blocks (1..4)
+hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s);
 hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, uint32_t grid, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, hipStream_t s);
 hipError_t launch_head(const HeadArgs& a, hipStream_t s);

@@ -16,6 +16,7 @@
 // hosts many tenants' DNNs and multiplexes their requests (section 3).  The grouping
 // of all tenants' work for one layer index into one launch is this runtime's way of
 // doing that multiplexing on one GPU.
+#include <algorithm>
 #include "mt_internal.h"
 
 namespace mt {
@@ -110,9 +111,11 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     __shared__ uint32_t tmp[17];
     __shared__ uint32_t wtot[kBatchThreads / 64 + 1][kLists];
     __shared__ Segment seg_l[kSegsInLds];
+    __shared__ uint32_t big_total[MT_MAX_LAYERS];
 
     const uint32_t tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const uint32_t T = a.T, R = a.R, NL = a.n_layer_slots;
+    if (tid < MT_MAX_LAYERS) big_total[tid] = 0;       // first read is several barriers away
     uint32_t Tp = 64, bits = 6;
     while (Tp < T) { Tp <<= 1; ++bits; }
     const uint32_t nslots = Tp > kBatchThreads ? 2 : 1;
@@ -234,6 +237,36 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         a.pos_of[r] = pos;
     }
 
+    // Big tiles pay only when a layer index has enough of them to fill the chip; below that the
+    // streaming kernel takes those tenants too, side by side with everyone else's tiles.
+    uint32_t big_layers = 0;                   // bit l: layer index l is served with big tiles where a tenant qualifies
+    if (a.big_enabled) {
+        uint32_t bt[MT_MAX_LAYERS];
+#pragma unroll
+        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) bt[l] = 0;
+        for (uint32_t slot = 0; slot < nslots; ++slot) {
+            const uint32_t t = tid + slot * kBatchThreads;
+            const uint32_t Mt = t < Tp ? Ml[t] : 0;
+#pragma unroll
+            for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
+                const uint32_t rr = slot == 0 ? rpr[0][l] : rpr[1][l], np = slot == 0 ? npad[0][l] : npad[1][l];
+                const uint32_t g = slot == 0 ? grp[0][l] : grp[1][l];
+                if (g && !(rr >> 31) && fc_is_big(Mt, np)) bt[l] += ceil_div(Mt, kBigTile) * ceil_div(np, kBigTile);
+            }
+        }
+#pragma unroll
+        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
+            uint32_t v = bt[l];
+            if (__any(v != 0)) {
+                for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+                if (lane == 0) atomicAdd(&big_total[l], v);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) big_layers |= (big_total[l] >= a.big_min_tiles ? 1u : 0u) << l;
+    }
+
     // pass 4: tile counts of every (kind, layer) list, scanned over tenants in one vector scan
     uint32_t carry[kLists];
 #pragma unroll
@@ -247,7 +280,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             const uint32_t g = slot == 0 ? grp[0][l] : grp[1][l], rr = slot == 0 ? rpr[0][l] : rpr[1][l];
             const uint32_t np = slot == 0 ? npad[0][l] : npad[1][l];
             const bool conv = rr >> 31;
-            const bool big = !conv && a.big_enabled && fc_is_big(Mt, np);
+            const bool big = !conv && ((big_layers >> l) & 1) && fc_is_big(Mt, np);
             // conv: rows = requests * output pixels, 512 per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
             const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
             c[l] = (conv || big) ? 0 : tiles;
@@ -1215,6 +1248,21 @@ hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipSt
     else hipLaunchKernelGGL(fc_big_kernel<float>, dim3(grid), dim3(kBigThreads), 0, s, a);
     return hipGetLastError();
 }
+// ---- plain copy: the yardstick for byte counters and streaming bandwidth -------------------
+__global__ __launch_bounds__(256) void copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, uint64_t n)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s)
+{
+    const uint64_t n = bytes / 16;
+    if (n == 0) return hipSuccess;
+    const uint32_t grid = (uint32_t)std::min<uint64_t>((n + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, s, (u32x4*)dst, (const u32x4*)src, n);
+    return hipGetLastError();
+}
+
 template <typename T>
 static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, uint32_t grid, hipStream_t s)
 {

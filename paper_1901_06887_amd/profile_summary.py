@@ -1,0 +1,136 @@
+"""Turn rocprofv3 CSV output into the short text summaries kept next to the benchmarks.
+
+  python -m paper_1901_06887_amd.profile_summary stats <..._kernel_stats.csv>
+      per-kernel calls / average / share table of a `--kernel-trace --stats` run
+
+  python -m paper_1901_06887_amd.profile_summary traffic --fetch <..._counter_collection.csv>
+          --write <..._counter_collection.csv> --kernel fc_kernel --copy-bytes N
+      HBM bytes per launch of one kernel from two `--pmc` runs (FETCH_SIZE, then WRITE_SIZE,
+      both in KiB per dispatch), each scaled by what the same counter reads for the library's
+      plain copy kernel moving N bytes in the same run.  Prints `key: value` lines; the
+      benchmark reads `traffic_bytes_per_launch` and `kernel_source_sha256` back.
+"""
+import argparse
+import csv
+import hashlib
+import os
+import re
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+KERNEL_SOURCES = ("csrc/mt_kernels.hip", "csrc/mt_internal.h")
+
+
+def kernel_source_sha256() -> str:
+    """Fingerprint of the device code: counters taken before a change to it no longer apply."""
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(HERE, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def short_name(name: str) -> str:
+    """'_ZN2mt9fc_kernelIDF16bEEvNS_8GemmArgsE' or 'mt::fc_kernel<__bf16>(...)' -> a readable name."""
+    m = re.match(r"_ZN2mt\d+([a-z_]+)I(DF16b|f)(?:Li(\d+))?(?:Lb([01]))?", name)
+    if m:
+        args = ["bf16" if m.group(2) == "DF16b" else "float"] + [g for g in m.groups()[2:] if g is not None]
+        return "mt::%s<%s>" % (m.group(1), ",".join(args))
+    m = re.match(r"_ZN2mt\d+([a-z_]+)ILb([01])", name)
+    if m:
+        return "mt::%s<%s>" % (m.group(1), m.group(2))
+    return re.sub(r"\(.*", "", name)
+
+
+def stats(path: str, top: int = 12) -> str:
+    rows = list(csv.DictReader(open(path)))
+    rows.sort(key=lambda r: -float(r["TotalDurationNs"]))
+    out = ["%-44s %8s %12s %10s %10s %7s" % ("kernel", "calls", "avg_us", "min_us", "max_us", "share%")]
+    for r in rows[:top]:
+        out.append("%-44s %8d %12.2f %10.2f %10.2f %7.2f" % (
+            short_name(r["Name"])[:44], int(r["Calls"]), float(r["AverageNs"]) / 1e3, float(r["MinNs"]) / 1e3,
+            float(r["MaxNs"]) / 1e3, float(r["Percentage"])))
+    return "\n".join(out)
+
+
+def counter_means(path: str, counter: str) -> dict:
+    """Mean counter value per dispatch, by readable kernel name."""
+    acc = {}
+    for r in csv.DictReader(open(path)):
+        if r["Counter_Name"] != counter:
+            continue
+        s, n = acc.get(short_name(r["Kernel_Name"]), (0.0, 0))
+        acc[short_name(r["Kernel_Name"])] = (s + float(r["Counter_Value"]), n + 1)
+    return {k: (s / n, n) for k, (s, n) in acc.items()}
+
+
+def pick(means: dict, needle: str):
+    hits = [k for k in means if needle in k]
+    if len(hits) != 1:
+        raise SystemExit("kernel %r matches %r" % (needle, hits))
+    return hits[0], means[hits[0]]
+
+
+def traffic(fetch_csv: str, write_csv: str, kernel: str, copy_bytes: int) -> str:
+    f, w = counter_means(fetch_csv, "FETCH_SIZE"), counter_means(write_csv, "WRITE_SIZE")
+    (_, (cf, ncf)), (_, (cw, ncw)) = pick(f, "copy_kernel"), pick(w, "copy_kernel")
+    (name, (kf, nkf)), (_, (kw, nkw)) = pick(f, kernel), pick(w, kernel)
+    fetch_scale = copy_bytes / (cf * 1024.0)          # true bytes per counted byte
+    write_scale = copy_bytes / (cw * 1024.0)
+    fetch_b, write_b = kf * 1024.0 * fetch_scale, kw * 1024.0 * write_scale
+    lines = [
+        "kernel: %s" % name,
+        "copy_kernel_bytes: %d" % copy_bytes,
+        "copy_kernel_FETCH_SIZE_KiB: %.1f (%d dispatches)  -> scale %.3f" % (cf, ncf, fetch_scale),
+        "copy_kernel_WRITE_SIZE_KiB: %.1f (%d dispatches)  -> scale %.3f" % (cw, ncw, write_scale),
+        "kernel_FETCH_SIZE_KiB_per_launch: %.1f (%d dispatches)" % (kf, nkf),
+        "kernel_WRITE_SIZE_KiB_per_launch: %.1f (%d dispatches)" % (kw, nkw),
+        "fetch_bytes_per_launch: %.0f" % fetch_b,
+        "write_bytes_per_launch: %.0f" % write_b,
+        "traffic_bytes_per_launch: %.0f" % (fetch_b + write_b),
+        "kernel_source_sha256: %s" % kernel_source_sha256(),
+    ]
+    return "\n".join(lines)
+
+
+def read_traffic(path: str):
+    """`traffic_bytes_per_launch` of a stored summary, or None when the device code has changed since."""
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    sha = re.search(r"^kernel_source_sha256: ([0-9a-f]{64})$", text, re.M)
+    val = re.search(r"^traffic_bytes_per_launch: (\d+)$", text, re.M)
+    if not sha or not val or sha.group(1) != kernel_source_sha256():
+        return None
+    return float(val.group(1))
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    s = sub.add_parser("stats")
+    s.add_argument("csv")
+    s.add_argument("--top", type=int, default=12)
+    t = sub.add_parser("traffic")
+    t.add_argument("--fetch", required=True)
+    t.add_argument("--write", required=True)
+    t.add_argument("--kernel", required=True)
+    t.add_argument("--copy-bytes", type=int, required=True)
+    c = sub.add_parser("counters")
+    c.add_argument("csv")
+    c.add_argument("--kernel", required=True)
+    a = ap.parse_args(argv)
+    if a.cmd == "stats":
+        print(stats(a.csv, a.top))
+    elif a.cmd == "traffic":
+        print(traffic(a.fetch, a.write, a.kernel, a.copy_bytes))
+    else:
+        names = sorted({r["Counter_Name"] for r in csv.DictReader(open(a.csv))})
+        for n in names:
+            k, (v, cnt) = pick(counter_means(a.csv, n), a.kernel)
+            print("%s %s: %.4g (mean of %d dispatches)" % (k, n, v, cnt))
+
+
+if __name__ == "__main__":
+    main(sys.argv[1:])
