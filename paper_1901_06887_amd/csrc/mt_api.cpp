@@ -61,6 +61,7 @@ struct mt_ctx {
     uint32_t max_in_len = 0;
     // [kind][layer]: kind 0 = FC tiles, 1 = conv tiles, 2 = big FC tiles
     uint32_t max_rpr[kListKinds][MT_MAX_LAYERS]{}, max_nt[kListKinds][MT_MAX_LAYERS]{}, has_gap[MT_MAX_LAYERS]{};
+    double sum_macs = 0.0;                           // multiply-accumulates of one request, summed over the registered tenants
     uint32_t max_conv_cb[MT_MAX_LAYERS]{};           // widest conv tile (32-channel blocks, at most 4) of a layer index
     uint64_t sum_nt[kListKinds][MT_MAX_LAYERS]{};
     uint32_t fc_split_k = 0;   // tuning: FC tiles of one column block with K split four ways
@@ -170,7 +171,7 @@ void recompute_bounds(mt_ctx* c)
     c->n_layer_slots = 0;
     c->max_in_len = 0;
     c->fc_first_chunked = true; c->any_conv_first = c->any_fc_first = false;
-    c->list_mask = 0; c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu;
+    c->list_mask = 0; c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
         c->has_gap[l] = 0; c->max_conv_cb[l] = 0;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
@@ -191,6 +192,7 @@ void recompute_bounds(mt_ctx* c)
             const LayerDev& L = t.layers[l].dev;
             if (L.kind == MT_GAP) { c->has_gap[l] = 1; continue; }
             const int k = L.kind == MT_FC ? 0 : 1;
+            c->sum_macs += (double)L.k_valid * L.N * L.rows_per_req;
             c->list_mask |= 1u << (k * MT_MAX_LAYERS + l);
             const uint32_t nt = k == 0 ? fc_groups(L.N_pad, c->fc_split_k) : (L.N + kTileCols - 1) / kTileCols;
             c->max_rpr[k][l] = std::max(c->max_rpr[k][l], L.rows_per_req);
@@ -549,7 +551,11 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     const uint32_t T = c->cfg.max_tenants;
     uint32_t launches = 0;
 
-    const bool big_enabled = R >= (uint32_t)kBigMinBatch;
+    // Big tiles are for runs that are compute bound as a whole: enough rows, and more flops per
+    // byte of registered weights than the chip's ridge point.  Weight-streaming mixes keep every
+    // tenant in the streaming kernel (no second launch per layer, layer 0 reads submitted rows).
+    const double run_flops = 2.0 * R * (c->n_registered ? c->sum_macs / c->n_registered : 0.0);
+    const bool big_enabled = R >= (uint32_t)kBigMinBatch && run_flops >= kRidgeFlopsPerByte * (double)c->arena_used;
     BatchArgs b{};
     b.segs = c->d_segs[slot]; b.n_segs = n_segs; b.R = R; b.T = T; b.n_layer_slots = c->n_layer_slots;
     b.first = c->pending[0]; b.row_src = c->d_row_src; b.elem_size = c->elem_size;
@@ -597,7 +603,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         void* outb = c->d_act[(l + 1) & 1];
         for (int kind = 0; kind < kListKinds; ++kind) {
             const uint64_t grid = tile_bound(c, kind, l, R);
-            if (grid == 0 || (kind == 2 && grid < c->big_min_tiles)) continue;   // too few big tiles possible: the batcher made none
+            if (grid == 0 || (kind == 2 && (!big_enabled || grid < c->big_min_tiles))) continue;   // no big tiles possible: the batcher made none
             GemmArgs ga{};
             ga.tile_base = c->d_tile_base + ((size_t)kind * MT_MAX_LAYERS + l) * (T + 1);
             ga.T = T; ga.layer = l; ga.fc_split_k = c->fc_split_k;

@@ -28,6 +28,7 @@ constexpr int kBigTile = 256;
 constexpr int kBigMinRows = 2048;
 constexpr int kBigMinCols = 192;
 constexpr int kBigMinTiles = 512;   // a layer index is served with big tiles only when it has at least two per compute unit
+constexpr double kRidgeFlopsPerByte = 312.0;   // dense bf16 MFMA peak over HBM bandwidth (2.5 PFLOP/s / 8 TB/s)
 constexpr int kBigMinBatch = 8192;  // runs with fewer rows are latency/HBM bound as a whole: no big tiles
 constexpr int kListKinds = 3;       // tile lists per layer index: FC (streaming), conv, FC (big tiles)
 constexpr int kRowBytes = 128;      // conv path: bytes of K one pipeline step consumes per row
