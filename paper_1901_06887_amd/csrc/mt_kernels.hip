@@ -30,6 +30,7 @@ constexpr uint32_t kBatchThreads = 1024;
 constexpr uint32_t kMaxTenantsPadded = 2048;
 constexpr uint32_t kHistEntries = 8192;
 constexpr uint32_t kSegsInLds = 64;
+constexpr uint32_t kRegIters = 8;          // batcher: rows a lane may keep in registers (64 * kRegIters rows per wave)
 
 __device__ __forceinline__ uint32_t ceil_div(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
 
@@ -109,9 +110,10 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     __shared__ uint32_t offl[kMaxTenantsPadded];
     __shared__ uint8_t regl[kMaxTenantsPadded];
     __shared__ uint32_t tmp[17];
-    __shared__ uint32_t wtot[kBatchThreads / 64 + 1][kLists];
+    __shared__ uint32_t wtot[kBatchThreads / 64][kLists];
     __shared__ Segment seg_l[kSegsInLds];
     __shared__ uint32_t big_total[MT_MAX_LAYERS];
+    __shared__ uint32_t carry_l[kLists];
 
     const uint32_t tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const uint32_t T = a.T, R = a.R, NL = a.n_layer_slots;
@@ -120,33 +122,59 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     while (Tp < T) { Tp <<= 1; ++bits; }
     const uint32_t nslots = Tp > kBatchThreads ? 2 : 1;
 
-    // tenant and layer facts of tenants tid and tid + 1024: column groups per layer (0 = no
-    // tiles) and rows per request with the kind in the top bit (1 = conv)
+    // Every global load the kernel depends on is issued before the first wait: the lane's tenant
+    // ids (register path, below), the tenant facts and -- unconditionally, so that they do not
+    // wait for the tenant facts -- the layer facts of tenants tid and tid + 1024.
+    const uint32_t nw = min(kBatchThreads / 64, kHistEntries / Tp);
+    const uint32_t chunk = ceil_div(ceil_div(R, nw), 64) * 64;          // rows per wave
+    const bool in_regs = ONE_SEG && chunk <= 64 * kRegIters;             // a lane keeps its rows' ids and ranks in registers
+    const uint32_t begin = w * chunk, end = w < nw ? min(begin + chunk, R) : begin;
+    int32_t tq[kRegIters];
+    uint32_t rk[kRegIters];
+    if (in_regs) {
+#pragma unroll
+        for (uint32_t it = 0; it < kRegIters; ++it) {
+            const uint32_t r = begin + it * 64 + lane;
+            tq[it] = -1; rk[it] = 0;
+            if (r < end) {
+                a.row_src[r] = (const uint8_t*)a.first.src + (size_t)r * a.first.row_stride * a.elem_size;
+                tq[it] = a.first.ids ? a.first.ids[r] : a.first.tenant;
+            }
+        }
+    }
+
+    // column groups per layer (0 = no tiles), rows per request with the kind in the top bit
+    // (1 = conv), padded width
     uint32_t grp[2][MT_MAX_LAYERS], rpr[2][MT_MAX_LAYERS], npad[2][MT_MAX_LAYERS];
 #pragma unroll
     for (uint32_t slot = 0; slot < 2; ++slot) {
         const uint32_t t = tid + slot * kBatchThreads;
-        uint32_t nl = 0;
-        if (slot < nslots && t < Tp) {
-            const bool reg = t < T && a.tenants[t].registered;
-            regl[t] = reg;
-            nl = reg ? a.tenants[t].n_layers : 0;
+        const bool live = slot < nslots && t < T;
+        uint32_t kind[MT_MAX_LAYERS], n[MT_MAX_LAYERS], np[MT_MAX_LAYERS], rr[MT_MAX_LAYERS];
+        uint32_t reg = 0, nl = 0;
+        if (live) {
+#pragma unroll
+            for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
+                const LayerDev& L = a.layers[t * MT_MAX_LAYERS + l];
+                kind[l] = L.kind; n[l] = L.N; np[l] = L.N_pad; rr[l] = L.rows_per_req;
+            }
+            reg = a.tenants[t].registered; nl = a.tenants[t].n_layers;
         }
+        if (slot < nslots && t < Tp) regl[t] = live && reg;
+        if (!reg) nl = 0;
 #pragma unroll
         for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
             grp[slot][l] = 0; rpr[slot][l] = 1; npad[slot][l] = 0;
-            if (l < nl) {
-                const LayerDev& L = a.layers[t * MT_MAX_LAYERS + l];
-                const uint32_t kind = L.kind;
-                if (kind == MT_FC) {
+            if (live && l < nl) {
+                if (kind[l] == MT_FC) {
                     uint32_t split, groups, trows;
-                    fc_shape(L.N_pad, a.fc_split_k, &split, &groups, &trows);
+                    fc_shape(np[l], a.fc_split_k, &split, &groups, &trows);
                     grp[slot][l] = groups;
                     rpr[slot][l] = kTileRows / trows;            // 64-row tiles count as two per 128 rows
-                    npad[slot][l] = L.N_pad;
-                } else if (kind == MT_CONV2D) {
-                    grp[slot][l] = ceil_div(L.N, kTileCols);
-                    rpr[slot][l] = L.rows_per_req | 0x80000000u;
+                    npad[slot][l] = np[l];
+                } else if (kind[l] == MT_CONV2D) {
+                    grp[slot][l] = ceil_div(n[l], kTileCols);
+                    rpr[slot][l] = rr[l] | 0x80000000u;
                 }
             }
         }
@@ -158,14 +186,40 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         for (uint32_t i = tid; i < a.n_segs; i += kBatchThreads) seg_l[i] = a.segs[i];
         segs = seg_l;
     }
-    const uint32_t nw = min(kBatchThreads / 64, kHistEntries / Tp);
-    const uint32_t chunk = ceil_div(ceil_div(R, nw), 64) * 64;
     for (uint32_t i = tid; i < nw * Tp; i += kBatchThreads) hist[i] = 0;
     __syncthreads();
 
-    // pass 1: per-wave histograms and in-wave ranks
-    if (w < nw) {
-        const uint32_t begin = w * chunk, end = min(begin + chunk, R);
+    // pass 1: per-wave histograms and in-wave ranks.  One step ranks 64 rows: equal tenant ids
+    // are matched with one ballot per id bit.
+    auto rank_step = [&](int32_t& t, uint32_t& rank_out) {
+        if (t < 0 || (uint32_t)t >= T || !regl[t]) t = -1;
+        uint64_t peers = __ballot(t >= 0);
+        for (uint32_t b = 0; b < bits; ++b) {
+            const bool bit = (t >> b) & 1;
+            const uint64_t m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        const bool ok = t >= 0;
+        const uint32_t leader = ok ? (uint32_t)__ffsll((unsigned long long)peers) - 1 : lane;
+        const uint32_t rank = __popcll(peers & ((1ull << lane) - 1));
+        uint32_t old = 0;
+        if (ok && lane == leader) {
+            old = hist[w * Tp + t];
+            hist[w * Tp + t] = old + __popcll(peers);
+        }
+        old = __shfl(old, leader);
+        rank_out = old + rank;
+    };
+    if (in_regs) {
+#pragma unroll
+        for (uint32_t it = 0; it < kRegIters; ++it) {
+            if (begin + it * 64 < end) {                     // wave-uniform
+                rank_step(tq[it], rk[it]);
+                const uint32_t r = begin + it * 64 + lane;
+                if (r < end) a.row_tenant[r] = tq[it];
+            }
+        }
+    } else if (w < nw) {
         auto fetch_id = [&](uint32_t r) -> int32_t {
             if (r >= end) return -1;
             if (ONE_SEG) {                      // the whole batch is one submission: no table lookup
@@ -181,24 +235,9 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             const uint32_t r = base + lane;
             int32_t t = t_next;
             if (base + 64 < end) t_next = fetch_id(r + 64);
-            if (t < 0 || (uint32_t)t >= T || !regl[t]) t = -1;
-            if (r < end) a.row_tenant[r] = t;
-            uint64_t peers = __ballot(t >= 0);
-            for (uint32_t b = 0; b < bits; ++b) {
-                const bool bit = (t >> b) & 1;
-                const uint64_t m = __ballot(bit);
-                peers &= bit ? m : ~m;
-            }
-            const bool ok = t >= 0;
-            const uint32_t leader = ok ? (uint32_t)__ffsll((unsigned long long)peers) - 1 : lane;
-            const uint32_t rank = __popcll(peers & ((1ull << lane) - 1));
-            uint32_t old = 0;
-            if (ok && lane == leader) {
-                old = hist[w * Tp + t];
-                hist[w * Tp + t] = old + __popcll(peers);
-            }
-            old = __shfl(old, leader);
-            if (ok) a.row_rank[r] = old + rank;
+            uint32_t rank;
+            rank_step(t, rank);
+            if (r < end) { a.row_tenant[r] = t; if (t >= 0) a.row_rank[r] = rank; }
         }
     }
     __syncthreads();
@@ -213,18 +252,16 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     const uint32_t total = block_exclusive_scan(offl, Tp, tmp);
     for (uint32_t t = tid; t < T; t += kBatchThreads) {
         a.M[t] = Ml[t]; a.off[t] = offl[t];
-        const uint32_t end = offl[t] + ceil_div(Ml[t], kBrickRows) * kBrickRows;
-        for (uint32_t p = offl[t] + Ml[t]; p < end; ++p) a.perm[p] = -1;      // padding rows of the last block
+        const uint32_t pend = offl[t] + ceil_div(Ml[t], kBrickRows) * kBrickRows;
+        for (uint32_t p = offl[t] + Ml[t]; p < pend; ++p) a.perm[p] = -1;      // padding rows of the last block
     }
     if (tid == 0) a.off[T] = total;
 
     // pass 3: packed position of every row
-#pragma unroll 4
-    for (uint32_t r = tid; r < R; r += kBatchThreads) {
-        const int32_t t = a.row_tenant[r];
+    auto place = [&](uint32_t r, int32_t t, uint32_t rank, uint32_t wave_of_row) {
         int32_t pos = -1;
         if (t >= 0) {
-            pos = (int32_t)(offl[t] + hist[(r / chunk) * Tp + t] + a.row_rank[r]);
+            pos = (int32_t)(offl[t] + hist[wave_of_row * Tp + t] + rank);
             a.perm[pos] = (int32_t)r;
         } else {                                // rejected: unknown tenant or no model
             a.out.labels[r] = -1;
@@ -235,6 +272,19 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             }
         }
         a.pos_of[r] = pos;
+    };
+    if (in_regs) {
+#pragma unroll
+        for (uint32_t it = 0; it < kRegIters; ++it) {
+            const uint32_t r = begin + it * 64 + lane;
+            if (r < end) place(r, tq[it], rk[it], w);
+        }
+    } else {
+#pragma unroll 4
+        for (uint32_t r = tid; r < R; r += kBatchThreads) {
+            const int32_t t = a.row_tenant[r];
+            place(r, t, t >= 0 ? a.row_rank[r] : 0, r / chunk);
+        }
     }
 
     // Big tiles pay only when a layer index has enough of them to fill the chip; below that the
@@ -267,54 +317,50 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) big_layers |= (big_total[l] >= a.big_min_tiles ? 1u : 0u) << l;
     }
 
-    // pass 4: tile counts of every (kind, layer) list, scanned over tenants in one vector scan
-    uint32_t carry[kLists];
-#pragma unroll
-    for (uint32_t i = 0; i < kLists; ++i) carry[i] = 0;
+    // pass 4: tile counts of every (kind, layer) list, scanned over tenants in one vector scan.
+    // Only the exclusive in-wave prefix of each list stays in registers across the barriers; the
+    // running total over slots lives in LDS.
+    if (tid < kLists) carry_l[tid] = 0;
     for (uint32_t slot = 0; slot < nslots; ++slot) {
         const uint32_t t = tid + slot * kBatchThreads;
         const uint32_t Mt = t < Tp ? Ml[t] : 0;
-        uint32_t c[kLists], incl[kLists];
-#pragma unroll
-        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-            const uint32_t g = slot == 0 ? grp[0][l] : grp[1][l], rr = slot == 0 ? rpr[0][l] : rpr[1][l];
-            const uint32_t np = slot == 0 ? npad[0][l] : npad[1][l];
-            const bool conv = rr >> 31;
-            const bool big = !conv && ((big_layers >> l) & 1) && fc_is_big(Mt, np);
-            // conv: rows = requests * output pixels, 512 per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
-            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
-            c[l] = (conv || big) ? 0 : tiles;
-            c[MT_MAX_LAYERS + l] = conv ? tiles : 0;
-            c[2 * MT_MAX_LAYERS + l] = big ? ceil_div(Mt, kBigTile) * ceil_div(np, kBigTile) : 0;
-        }
-#pragma unroll
-        for (uint32_t i = 0; i < kLists; ++i) {
-            uint32_t v = c[i];
+        uint32_t excl[kLists];
+        auto wave_scan = [&](uint32_t i, uint32_t c) {
+            uint32_t v = c;
             if ((a.list_mask >> i) & 1) {       // lists no registered model contributes to are skipped
                 for (int d = 1; d < 64; d <<= 1) {
                     const uint32_t o = __shfl_up(v, d);
                     if (lane >= (uint32_t)d) v += o;
                 }
             }
-            incl[i] = v;
+            excl[i] = v - c;
             if (lane == 63) wtot[w][i] = v;
+        };
+#pragma unroll
+        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
+            const uint32_t g = slot == 0 ? grp[0][l] : grp[1][l], rr = slot == 0 ? rpr[0][l] : rpr[1][l];
+            const uint32_t np = slot == 0 ? npad[0][l] : npad[1][l];
+            const bool conv = rr >> 31;
+            const bool big = !conv && ((big_layers >> l) & 1) && fc_is_big(Mt, np);
+            // conv: rows = requests * output pixels per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
+            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
+            wave_scan(l, (conv || big) ? 0 : tiles);
+            wave_scan(MT_MAX_LAYERS + l, conv ? tiles : 0);
+            wave_scan(2 * MT_MAX_LAYERS + l, big ? ceil_div(Mt, kBigTile) * ceil_div(np, kBigTile) : 0);
         }
         __syncthreads();
         if (tid < kLists) {
-            uint32_t run = 0;
+            uint32_t run = carry_l[tid];
             for (uint32_t ww = 0; ww < kBatchThreads / 64; ++ww) { const uint32_t x = wtot[ww][tid]; wtot[ww][tid] = run; run += x; }
-            wtot[kBatchThreads / 64][tid] = run;
+            carry_l[tid] = run;
         }
         __syncthreads();
 #pragma unroll
-        for (uint32_t i = 0; i < kLists; ++i) {
-            if ((i % MT_MAX_LAYERS) < NL && t < T)
-                a.tile_base[(size_t)i * (T + 1) + t] = carry[i] + wtot[w][i] + incl[i] - c[i];
-            carry[i] += wtot[kBatchThreads / 64][i];
-        }
+        for (uint32_t i = 0; i < kLists; ++i)
+            if ((i % MT_MAX_LAYERS) < NL && t < T) a.tile_base[(size_t)i * (T + 1) + t] = wtot[w][i] + excl[i];
         __syncthreads();
     }
-    if (tid < kLists && (tid % MT_MAX_LAYERS) < NL) a.tile_base[(size_t)tid * (T + 1) + T] = carry[tid];
+    if (tid < kLists && (tid % MT_MAX_LAYERS) < NL) a.tile_base[(size_t)tid * (T + 1) + T] = carry_l[tid];
 }
 
 // ---- gather ------------------------------------------------------------------------------
