@@ -85,6 +85,7 @@ struct mt_ctx {
     int32_t* d_perm = nullptr;
     uint32_t* d_M = nullptr;
     uint32_t* d_off = nullptr;
+    void* d_zeros = nullptr;           // 256 bytes of zeros: where masked operand loads point instead of branching
     uint32_t* d_tile_base = nullptr;   // [2][MT_MAX_LAYERS][T+1]: FC arrays, then conv arrays
     void* d_act[2] = {nullptr, nullptr};
     float* d_logits = nullptr;
@@ -381,6 +382,8 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     CREATE_TRY(hipMalloc((void**)&c->d_off, (T + 1) * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_tile_base, kListKinds * MT_MAX_LAYERS * (T + 1) * 4));
     CREATE_TRY(hipMemset(c->d_tile_base, 0, kListKinds * MT_MAX_LAYERS * (T + 1) * 4));
+    CREATE_TRY(hipMalloc(&c->d_zeros, 256));
+    CREATE_TRY(hipMemset(c->d_zeros, 0, 256));
     for (int i = 0; i < 2; ++i) {
         CREATE_TRY(hipMalloc(&c->d_act[i], (uint64_t)c->P_cap * c->S * c->elem_size));
     }
@@ -401,7 +404,7 @@ mt_status mt_destroy(mt_ctx* c)
         (void)hipSetDevice(c->cfg.device);
         (void)hipDeviceSynchronize();
         void* bufs[] = {c->d_arena, c->d_tenants, c->d_layers, c->d_row_tenant, c->d_row_rank, (void*)c->d_row_src, c->d_pos_of, c->d_perm,
-                        c->d_M, c->d_off, c->d_tile_base, c->d_act[0], c->d_act[1], c->d_logits};
+                        c->d_M, c->d_off, c->d_tile_base, c->d_zeros, c->d_act[0], c->d_act[1], c->d_logits};
         for (void* p : bufs) if (p) (void)hipFree(p);
         for (uint32_t i = 0; i < kSegSlots; ++i) {
             if (c->h_segs[i]) (void)hipHostFree(c->h_segs[i]);
@@ -610,7 +613,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             ga.gather = (kind == 0 && l == 0 && fuse_gather); ga.perm = c->d_perm; ga.row_src = c->d_row_src;
             ga.fuse_head = fuse_head; ga.out = outp;
             ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
-            ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad;
+            ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad; ga.zeros = c->d_zeros;
             const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, 0x7ffffff0u);
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
             else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], g32, s));

@@ -126,6 +126,7 @@ struct GemmArgs {
     const LayerDev* layers; const uint32_t* off; const uint32_t* M;
     const void* act_in; void* act_out; const uint8_t* arena;
     float* logits; uint32_t S; uint32_t C_pad;
+    const void* zeros;     // >= 16 readable zero bytes
 };
 
 struct GapArgs {

@@ -872,15 +872,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 // ---- grouped FC, big tiles ---------------------------------------------------------------
 // Tenant-layers with at least kBigMinRows requests are compute bound.  They are cut into
 // 256x256 output tiles; a workgroup of eight waves (2x4, 128x64 = 4x2 MFMA blocks per wave, two
-// waves per SIMD so that one wave's operand fetches overlap the other's MFMAs) walks K four
-// bricks at a time through two 64 KiB LDS stages.  Both operands arrive as bricks, so a stage is
-// filled with straight 1 KiB copies (each wave copies two of the 16 row/column blocks) and read
-// back with conflict-free 16-byte-per-lane loads.  Per k step a workgroup moves 16 KiB from L2
+// waves per SIMD so that one wave's operand fetches overlap the other's MFMAs) walks K two
+// bricks at a time through a ring of four 32 KiB LDS stages.  Both operands arrive as bricks, so a
+// stage is filled with straight 1 KiB copies (each wave copies two of the 16 row/column blocks) and
+// read back with conflict-free 16-byte-per-lane loads.  Per k step a workgroup moves 16 KiB from L2
 // for 64 MFMAs (half the operand traffic per flop of the 128x128 streaming tile) and reads
 // 48 KiB from LDS, ~60 % of what the LDS pipe sustains with two waves per SIMD.
-constexpr uint32_t kBigKS = 4;                                                   // k steps per stage
+constexpr uint32_t kBigKS = 2;                                                   // k steps per stage
+constexpr uint32_t kBigNS = 4;                                                   // stages in the LDS ring
 constexpr uint32_t kBigBlocks = kBigTile / kBrickRows;                            // 8 row blocks, 8 column blocks
-constexpr uint32_t kBigStageBytes = 2 * kBigBlocks * kBigKS * kBrickBytes;        // 64 KiB
+constexpr uint32_t kBigStageBytes = 2 * kBigBlocks * kBigKS * kBrickBytes;        // 32 KiB
 constexpr uint32_t kBigGroup = 4;                                                 // row tiles that sweep the columns together
 constexpr uint32_t kBigThreads = 512;
 
@@ -917,10 +918,9 @@ __device__ __forceinline__ void big_hidden_block(const f32x16& v, float bv, bool
 template <typename T>
 __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t stages[2 * kBigStageBytes];
+    __shared__ __attribute__((aligned(16))) uint8_t stages[kBigNS * kBigStageBytes];
     uint8_t* const stage0 = stages;
-    uint8_t* const stage1 = stages + kBigStageBytes;
-    static_assert(2 * kBigStageBytes >= 8 * kTrBytes && kBigStageBytes >= (kMaxTenantsPadded + 1) * 4, "scratch aliases the stages");
+    static_assert(kBigNS * kBigStageBytes >= 8 * kTrBytes && kBigStageBytes >= (kMaxTenantsPadded + 1) * 4, "scratch aliases the stages");
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t li = lane & 31, lh = lane >> 5;
@@ -967,57 +967,94 @@ __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    u32x4 sr[2][kBigKS];
-    auto load_stage = [&](uint32_t s) {
-#pragma unroll
-        for (uint32_t i = 0; i < 2; ++i)
-#pragma unroll
-            for (uint32_t kk = 0; kk < kBigKS; ++kk) sr[i][kk] = lp[i][(size_t)(s * kBigKS + kk) * 64];
-        // pin the loads here: left alone, the scheduler sinks them to the end of the stage, a few
-        // cycles before their first use
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    auto store_stage = [&](uint8_t* buf) {
+    // Operands travel HBM/L2 -> LDS without passing through registers (16 bytes per lane, the
+    // hardware places lane l at base + 16 l, which is exactly a brick), three stages ahead of
+    // their use.  A wave issues four such loads per stage, so "stage s has landed" is "at most
+    // eight of my loads are outstanding"; the barrier that follows extends that to every wave's
+    // share and also says that everyone is done reading the stage about to be overwritten.
+    typedef const __attribute__((address_space(1))) void* gvoid_t;
+    typedef __attribute__((address_space(3))) void* lvoid_t;
+    auto issue_stage = [&](uint32_t slot, uint32_t s) {      // data of stage s into ring slot `slot`
+        uint8_t* dst = stages + (slot % kBigNS) * kBigStageBytes + (wave * 2) * kBigKS * kBrickBytes;
 #pragma unroll
         for (uint32_t i = 0; i < 2; ++i)
 #pragma unroll
             for (uint32_t kk = 0; kk < kBigKS; ++kk)
-                *(u32x4*)(buf + ((wave * 2 + i) * kBigKS + kk) * kBrickBytes + lane * 16) = sr[i][kk];
+                __builtin_amdgcn_global_load_lds((gvoid_t)(lp[i] + (size_t)(s * kBigKS + kk) * 64),
+                                                 (lvoid_t)(dst + (i * kBigKS + kk) * kBrickBytes), 16, 0, 0);
     };
-    auto stage_compute = [&](const uint8_t* buf) {
+    // MFMA operands of one k step: 4 activation bricks and 2 weight bricks of this wave
+    auto read_ops = [&](const uint8_t* buf, uint32_t kk, u32x4 (&a4)[4], u32x4 (&b2)[2]) {
         const uint8_t* ab = buf + (wm * 4 * kBigKS) * kBrickBytes + lane * 16;
         const uint8_t* bb = buf + ((kBigBlocks + wn * 2) * kBigKS) * kBrickBytes + lane * 16;
 #pragma unroll
-        for (uint32_t kk = 0; kk < kBigKS; ++kk) {
-            u32x4 av[4], bv[2];
+        for (int i = 0; i < 4; ++i) a4[i] = *(const u32x4*)(ab + (i * kBigKS + kk) * kBrickBytes);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) av[i] = *(const u32x4*)(ab + (i * kBigKS + kk) * kBrickBytes);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) bv[j] = *(const u32x4*)(bb + (j * kBigKS + kk) * kBrickBytes);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) Mma<T>::run(acc[i][j], av[i], bv[j]);
-        }
+        for (int j = 0; j < 2; ++j) b2[j] = *(const u32x4*)(bb + (j * kBigKS + kk) * kBrickBytes);
     };
+    auto mma_rows = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[2], int i0, int i1) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) Mma<T>::run(acc[i][j], a4[i], b2[j]);
+    };
+    auto mma_all = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[2]) { mma_rows(a4, b2, 0, 4); };
+    static_assert(kBigKS == 2, "the loop below is written for two k steps per stage");
 
-    const uint32_t n_stages = nKB / kBigKS, last = n_stages - 1;
-    load_stage(0);
-    store_stage(stage0);
-    load_stage(min(1u, last));
-    lds_barrier();
-    for (uint32_t s = 0; s < n_stages; s += 2) {
-        store_stage(stage1);                                 // stage s+1 (a harmless repeat when it does not exist)
-        load_stage(min(s + 2, last));
-        stage_compute(stage0);
-        lds_barrier();
-        if (s + 1 < n_stages) {
-            store_stage(stage0);
-            load_stage(min(s + 3, last));
-            stage_compute(stage1);
-            lds_barrier();
+    // The two k steps of a stage use two operand register sets, X and Y.  LDS reads of one set
+    // are always issued in front of the MFMAs of the other, and the second k step of a stage is
+    // multiplied after the next stage's barrier, so neither the LDS latency nor the barrier
+    // leaves the MFMA pipe without work.
+    const uint32_t n_stages = nKB / kBigKS, last = n_stages - 1;   // nKB is a multiple of 4: at least two stages
+    // The waits are spelled with the builtin so that the compiler's own wait-count bookkeeping
+    // sees them (an asm wait is invisible to it, and it would then wait again, too strictly);
+    // the empty asm statements keep memory operations from moving across the barrier.
+    // Encoding: vmcnt in bits 3:0 (and 15:14), expcnt 6:4, lgkmcnt 11:8; a field at its maximum does not wait.
+    constexpr int kWaitVm8 = 0x0F78, kWaitVm8Lgkm0 = 0x0078;
+    auto ring_barrier = [&](int wait) {
+        if (wait == kWaitVm8) __builtin_amdgcn_s_waitcnt(kWaitVm8); else __builtin_amdgcn_s_waitcnt(kWaitVm8Lgkm0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+#pragma unroll
+    for (uint32_t s = 0; s < kBigNS - 1; ++s) issue_stage(s, min(s, last));
+    ring_barrier(kWaitVm8);                                                     // stage 0 is complete for every wave
+    issue_stage(kBigNS - 1, min(kBigNS - 1, last));
+    // A wave whose four row blocks all lie past the end of a ragged tile only helps with staging
+    // and barriers (its own loop, so that the working loop stays free of branches); its SIMD's
+    // MFMA pipe is left to the wave that has rows.
+    if (__builtin_amdgcn_readfirstlane(wm * 4 < nrb)) {
+        u32x4 xa[4], xb[2], ya[4], yb[2];
+        read_ops(stages, 0, xa, xb);
+        read_ops(stages, 1, ya, yb);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_all(xa, xb);
+        for (uint32_t s = 1; s < n_stages; ++s) {
+            // stage s is complete for every wave; every wave holds what it needs of stage s - 1 in
+            // registers, so ring slot (s + 3) % 4 can be refilled
+            ring_barrier(kWaitVm8Lgkm0);
+            issue_stage(s + kBigNS - 1, min(s + kBigNS - 1, last));   // past the end: a harmless repeat keeps the count uniform
+            const uint8_t* buf = stages + (s % kBigNS) * kBigStageBytes;
+            read_ops(buf, 0, xa, xb);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_all(ya, yb);                                          // second k step of stage s - 1
+            __builtin_amdgcn_sched_barrier(0);
+            mma_rows(xa, xb, 0, 1);                                   // first k step of stage s; its operands had the MFMAs above to arrive
+            __builtin_amdgcn_sched_barrier(0);
+            read_ops(buf, 1, ya, yb);                                 // issued behind the wait for X, so that wait does not cover them
+            __builtin_amdgcn_sched_barrier(0);
+            mma_rows(xa, xb, 1, 4);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        mma_all(ya, yb);
+    } else {
+        for (uint32_t s = 1; s < n_stages; ++s) {
+            ring_barrier(kWaitVm8Lgkm0);
+            issue_stage(s + kBigNS - 1, min(s + kBigNS - 1, last));
         }
     }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // trailing repeats landed, all reads done
 
     // epilogue; the stages are free now, each wave transposes through its own scratch.  The
     // blocks of a wave are spelled out one by one (constant accumulator indices) with a scheduling
@@ -1082,13 +1119,17 @@ __device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, 
     int32_t th = 0, tw = 0;
     auto wrap = [&]() { if (c0 >= cin) { c0 -= cin; if (++tw == 3) { tw = 0; ++th; } } };
     wrap(); wrap();
-    auto load_a = [&]() -> u32x4 {                                 // the next k step's chunk; steps past the last tap read as zeros
+    // The next k step's chunk.  Taps outside the image, steps past the last tap and rows past the
+    // end read a block of zeros instead: the choice is made on the address, so nothing waits on
+    // the loaded value before its MFMA.
+    gptr_t zeros = (gptr_t)a.zeros;
+    auto load_a = [&]() -> u32x4 {
         const int32_t ih = ih0 + th, iw = iw0 + tw;
-        const bool ok = row_ok && th < 3 && ih >= 0 && ih < (int32_t)L.in_h && iw >= 0 && iw < (int32_t)L.in_w;
-        const uint32_t off = ok ? ((uint32_t)(ih * (int32_t)L.in_w + iw) * cin + c0) / EPC : 0;   // a safe address either way
-        const u32x4 v = img[off];
+        const bool ok = row_ok & (th < 3) & (ih >= 0) & (ih < (int32_t)L.in_h) & (iw >= 0) & (iw < (int32_t)L.in_w);
+        const uint32_t off = ((uint32_t)(ih * (int32_t)L.in_w + iw) * cin + c0) / EPC;
+        gptr_t p = ok ? img + off : zeros;
         c0 += KB; wrap(); wrap();
-        return ok ? v : u32x4{0, 0, 0, 0};
+        return *p;
     };
 
     f32x16 acc[CB];
