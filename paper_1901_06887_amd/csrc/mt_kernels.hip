@@ -883,7 +883,6 @@ constexpr uint32_t kBigNS = 4;                                                  
 constexpr uint32_t kBigBlocks = kBigTile / kBrickRows;                            // 8 row blocks, 8 column blocks
 constexpr uint32_t kBigStageBytes = 2 * kBigBlocks * kBigKS * kBrickBytes;        // 32 KiB
 constexpr uint32_t kBigGroup = 4;                                                 // row tiles that sweep the columns together
-constexpr uint32_t kBigThreads = 512;
 
 // One 32x32 accumulator block of the big-tile kernel -> logits rows.
 __device__ __forceinline__ void big_logits_block(const f32x16& v, float bv, float* p, uint32_t C_pad, uint32_t rows_left, uint32_t lh)
@@ -915,9 +914,15 @@ __device__ __forceinline__ void big_hidden_block(const f32x16& v, float bv, bool
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // reads done before the next block overwrites the scratch
 }
 
-template <typename T>
-__global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
+// WV waves per workgroup: 8 (2x4, 128x64 per wave) or 4 (2x2, 128x128 per wave, one wave per SIMD
+// with its accumulators in the second half of the 512-entry register file).
+template <typename T, int WV>
+__global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
 {
+    constexpr uint32_t WN = WV / 2;                          // waves side by side
+    constexpr uint32_t CJ = kBigBlocks / WN;                 // column blocks per wave (2 or 4)
+    constexpr uint32_t BPW = 2 * kBigBlocks / WV;            // row/column blocks a wave stages (2 or 4)
+    constexpr uint32_t LPS = BPW * kBigKS;                   // loads a wave issues per stage
     __shared__ __attribute__((aligned(16))) uint8_t stages[kBigNS * kBigStageBytes];
     uint8_t* const stage0 = stages;
     static_assert(kBigNS * kBigStageBytes >= 8 * kTrBytes && kBigStageBytes >= (kMaxTenantsPadded + 1) * 4, "scratch aliases the stages");
@@ -927,7 +932,7 @@ __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
 
     uint32_t* base_l = (uint32_t*)stage0;                   // tile_base during the lookup
     const uint32_t n_tiles = a.tile_base[a.T];
-    for (uint32_t i = tid; i <= a.T; i += kBigThreads) base_l[i] = a.tile_base[i];
+    for (uint32_t i = tid; i <= a.T; i += WV * 64) base_l[i] = a.tile_base[i];
     uint32_t idx;
     if (!logical_tile_chunked(n_tiles, &idx)) return;
     __syncthreads();
@@ -945,25 +950,27 @@ __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
     const uint32_t m0 = (first_m + in_grp % gsz) * kBigTile, n0 = (in_grp / gsz) * kBigTile;
     const uint32_t rows = min((uint32_t)kBigTile, Mt - m0), nrb = ceil_div(rows, kBrickRows);
     const uint32_t ncb = min(kBigBlocks, L.N_pad / kBrickRows - n0 / kBrickRows);
-    const uint32_t wm = wave >> 2, wn = wave & 3;
+    const uint32_t wm = wave / WN, wn = wave % WN;
 
     // staging: waves 0..3 copy the 8 activation row blocks, waves 4..7 the 8 weight column blocks
     // (blocks past the tile or the layer repeat the last valid one)
-    const u32x4* lp[2];
+    // staging: the first half of the waves copies the 8 activation row blocks, the second half the
+    // 8 weight column blocks, BPW blocks each (blocks past the tile or the layer repeat the last valid one)
+    const u32x4* lp[BPW];
     {
         const u32x4* xbase = (const u32x4*)((const T*)a.act_in + (size_t)seg0 * a.S) + lane;
         const u32x4* wbase = (const u32x4*)(a.arena + L.w_off) + lane;
 #pragma unroll
-        for (uint32_t i = 0; i < 2; ++i) {
-            if (wave < 4) lp[i] = xbase + (size_t)(m0 / kBrickRows + min(wave * 2 + i, nrb - 1)) * nKB * 64;
-            else lp[i] = wbase + (size_t)(n0 / kBrickRows + min((wave - 4) * 2 + i, ncb - 1)) * nKB * 64;
+        for (uint32_t i = 0; i < BPW; ++i) {
+            if (wave < WV / 2) lp[i] = xbase + (size_t)(m0 / kBrickRows + min(wave * BPW + i, nrb - 1)) * nKB * 64;
+            else lp[i] = wbase + (size_t)(n0 / kBrickRows + min((wave - WV / 2) * BPW + i, ncb - 1)) * nKB * 64;
         }
     }
-    f32x16 acc[4][2];
+    f32x16 acc[4][CJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < (int)CJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
@@ -975,30 +982,30 @@ __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
     typedef const __attribute__((address_space(1))) void* gvoid_t;
     typedef __attribute__((address_space(3))) void* lvoid_t;
     auto issue_stage = [&](uint32_t slot, uint32_t s) {      // data of stage s into ring slot `slot`
-        uint8_t* dst = stages + (slot % kBigNS) * kBigStageBytes + (wave * 2) * kBigKS * kBrickBytes;
+        uint8_t* dst = stages + (slot % kBigNS) * kBigStageBytes + (wave * BPW) * kBigKS * kBrickBytes;
 #pragma unroll
-        for (uint32_t i = 0; i < 2; ++i)
+        for (uint32_t i = 0; i < BPW; ++i)
 #pragma unroll
             for (uint32_t kk = 0; kk < kBigKS; ++kk)
                 __builtin_amdgcn_global_load_lds((gvoid_t)(lp[i] + (size_t)(s * kBigKS + kk) * 64),
                                                  (lvoid_t)(dst + (i * kBigKS + kk) * kBrickBytes), 16, 0, 0);
     };
     // MFMA operands of one k step: 4 activation bricks and 2 weight bricks of this wave
-    auto read_ops = [&](const uint8_t* buf, uint32_t kk, u32x4 (&a4)[4], u32x4 (&b2)[2]) {
+    auto read_ops = [&](const uint8_t* buf, uint32_t kk, u32x4 (&a4)[4], u32x4 (&b2)[CJ]) {
         const uint8_t* ab = buf + (wm * 4 * kBigKS) * kBrickBytes + lane * 16;
-        const uint8_t* bb = buf + ((kBigBlocks + wn * 2) * kBigKS) * kBrickBytes + lane * 16;
+        const uint8_t* bb = buf + ((kBigBlocks + wn * CJ) * kBigKS) * kBrickBytes + lane * 16;
 #pragma unroll
         for (int i = 0; i < 4; ++i) a4[i] = *(const u32x4*)(ab + (i * kBigKS + kk) * kBrickBytes);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b2[j] = *(const u32x4*)(bb + (j * kBigKS + kk) * kBrickBytes);
+        for (int j = 0; j < (int)CJ; ++j) b2[j] = *(const u32x4*)(bb + (j * kBigKS + kk) * kBrickBytes);
     };
-    auto mma_rows = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[2], int i0, int i1) {
+    auto mma_rows = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[CJ], int i0, int i1) {
 #pragma unroll
         for (int i = i0; i < i1; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) Mma<T>::run(acc[i][j], a4[i], b2[j]);
+            for (int j = 0; j < (int)CJ; ++j) Mma<T>::run(acc[i][j], a4[i], b2[j]);
     };
-    auto mma_all = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[2]) { mma_rows(a4, b2, 0, 4); };
+    auto mma_all = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[CJ]) { mma_rows(a4, b2, 0, 4); };
     static_assert(kBigKS == 2, "the loop below is written for two k steps per stage");
 
     // The two k steps of a stage use two operand register sets, X and Y.  LDS reads of one set
@@ -1010,22 +1017,23 @@ __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
     // sees them (an asm wait is invisible to it, and it would then wait again, too strictly);
     // the empty asm statements keep memory operations from moving across the barrier.
     // Encoding: vmcnt in bits 3:0 (and 15:14), expcnt 6:4, lgkmcnt 11:8; a field at its maximum does not wait.
-    constexpr int kWaitVm8 = 0x0F78, kWaitVm8Lgkm0 = 0x0078;
-    auto ring_barrier = [&](int wait) {
-        if (wait == kWaitVm8) __builtin_amdgcn_s_waitcnt(kWaitVm8); else __builtin_amdgcn_s_waitcnt(kWaitVm8Lgkm0);
+    constexpr uint32_t kOut = 2 * LPS;                       // loads of the two younger stages may stay in flight
+    constexpr int kWaitVm = (int)((kOut & 15) | ((kOut >> 4) << 14) | 0x0070 | 0x0F00), kWaitVmLgkm0 = kWaitVm & ~0x0F00;
+    auto ring_barrier = [&](bool lds_too) {
+        if (lds_too) __builtin_amdgcn_s_waitcnt(kWaitVmLgkm0); else __builtin_amdgcn_s_waitcnt(kWaitVm);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     };
 #pragma unroll
     for (uint32_t s = 0; s < kBigNS - 1; ++s) issue_stage(s, min(s, last));
-    ring_barrier(kWaitVm8);                                                     // stage 0 is complete for every wave
+    ring_barrier(false);                                                     // stage 0 is complete for every wave
     issue_stage(kBigNS - 1, min(kBigNS - 1, last));
     // A wave whose four row blocks all lie past the end of a ragged tile only helps with staging
     // and barriers (its own loop, so that the working loop stays free of branches); its SIMD's
     // MFMA pipe is left to the wave that has rows.
     if (__builtin_amdgcn_readfirstlane(wm * 4 < nrb)) {
-        u32x4 xa[4], xb[2], ya[4], yb[2];
+        u32x4 xa[4], xb[CJ], ya[4], yb[CJ];
         read_ops(stages, 0, xa, xb);
         read_ops(stages, 1, ya, yb);
         __builtin_amdgcn_sched_barrier(0);
@@ -1033,7 +1041,7 @@ __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
         for (uint32_t s = 1; s < n_stages; ++s) {
             // stage s is complete for every wave; every wave holds what it needs of stage s - 1 in
             // registers, so ring slot (s + 3) % 4 can be refilled
-            ring_barrier(kWaitVm8Lgkm0);
+            ring_barrier(true);
             issue_stage(s + kBigNS - 1, min(s + kBigNS - 1, last));   // past the end: a harmless repeat keeps the count uniform
             const uint8_t* buf = stages + (s % kBigNS) * kBigStageBytes;
             read_ops(buf, 0, xa, xb);
@@ -1050,7 +1058,7 @@ __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
         mma_all(ya, yb);
     } else {
         for (uint32_t s = 1; s < n_stages; ++s) {
-            ring_barrier(kWaitVm8Lgkm0);
+            ring_barrier(true);
             issue_stage(s + kBigNS - 1, min(s + kBigNS - 1, last));
         }
     }
@@ -1060,15 +1068,15 @@ __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
     // blocks of a wave are spelled out one by one (constant accumulator indices) with a scheduling
     // fence after each, which keeps the register need of the epilogue at one block.
     const float* bias = (const float*)(a.arena + L.b_off);
-    float bvs[2];
+    float bvs[CJ];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) bvs[j] = wn * 2 + j < ncb ? bias[n0 + (wn * 2 + j) * kBrickRows + li] : 0.0f;
+    for (int j = 0; j < (int)CJ; ++j) bvs[j] = wn * CJ + j < ncb ? bias[n0 + (wn * CJ + j) * kBrickRows + li] : 0.0f;
     uint8_t* trw = stage0 + wave * kTrBytes;
     const uint32_t nKB_out = L.out_fill / KB;
     auto block = [&](const f32x16& blk, uint32_t i, uint32_t j) {
         const uint32_t rb = wm * 4 + i;
-        if (rb < nrb && wn * 2 + j < ncb) {
-            const uint32_t nb = n0 / kBrickRows + wn * 2 + j, n = nb * kBrickRows + li;
+        if (rb < nrb && wn * CJ + j < ncb) {
+            const uint32_t nb = n0 / kBrickRows + wn * CJ + j, n = nb * kBrickRows + li;
             const uint32_t mb = m0 + rb * kBrickRows;          // first row of the block inside the tenant
             if (L.is_last) {
                 if (n < L.N) big_logits_block(blk, bvs[j], a.logits + (size_t)(seg0 + mb) * a.C_pad + n, a.C_pad, Mt - mb, lh);
@@ -1080,8 +1088,10 @@ __global__ __launch_bounds__(kBigThreads) void fc_big_kernel(GemmArgs a)
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    block(acc[0][0], 0, 0); block(acc[0][1], 0, 1); block(acc[1][0], 1, 0); block(acc[1][1], 1, 1);
-    block(acc[2][0], 2, 0); block(acc[2][1], 2, 1); block(acc[3][0], 3, 0); block(acc[3][1], 3, 1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < (int)CJ; ++j) block(acc[i][j], i, j);
 }
 
 // ---- grouped 3x3 convolution as implicit GEMM ---------------------------------------------
@@ -1331,8 +1341,10 @@ hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipSt
 {
     if (grid == 0) return hipSuccess;
     grid = (grid + 8 * kXcdChunk - 1) / (8 * kXcdChunk) * (8 * kXcdChunk);
-    if (dtype == MT_BF16) hipLaunchKernelGGL(fc_big_kernel<__bf16>, dim3(grid), dim3(kBigThreads), 0, s, a);
-    else hipLaunchKernelGGL(fc_big_kernel<float>, dim3(grid), dim3(kBigThreads), 0, s, a);
+    // (the 4-wave shape, 128x128 per wave at one wave per SIMD, reads a third less from LDS per
+    // MFMA but was measured 1.5x slower: a single wave per SIMD leaves the MFMA pipe idle at every wait)
+    if (dtype == MT_BF16) hipLaunchKernelGGL((fc_big_kernel<__bf16, 8>), dim3(grid), dim3(512), 0, s, a);
+    else hipLaunchKernelGGL((fc_big_kernel<float, 8>), dim3(grid), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 // ---- plain copy: the yardstick for byte counters and streaming bandwidth -------------------
