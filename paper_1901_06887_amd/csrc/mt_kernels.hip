@@ -30,7 +30,7 @@ constexpr uint32_t kBatchThreads = 1024;
 constexpr uint32_t kMaxTenantsPadded = 2048;
 constexpr uint32_t kHistEntries = 8192;
 constexpr uint32_t kSegsInLds = 64;
-constexpr uint32_t kRegIters = 8;          // batcher: rows a lane may keep in registers (64 * kRegIters rows per wave)
+constexpr uint32_t kRegIters = 16;         // batcher: rows a lane may keep in registers (64 * kRegIters rows per wave)
 
 __device__ __forceinline__ uint32_t ceil_div(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
 
@@ -38,6 +38,18 @@ __device__ __forceinline__ uint32_t ceil_div(uint32_t a, uint32_t b) { return (a
 // load in flight (it fences all address spaces), which would empty the prefetch rings of the
 // GEMM loops at each LDS hand-over; here only the LDS counter is waited on.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Direct global -> LDS load of 16 bytes per lane: lane l's bytes land at lds_dst + 16 l
+// (lds_dst is wave-uniform and travels in M0).  Written as asm on purpose: the compiler's
+// wait-count pass gives up exact vmcnt bookkeeping (it waits for zero) once it sees such loads
+// in flight together with ordinary register loads.  A kernel that uses this helper issues no
+// register loads while such loads are in flight and waits for the LDS data itself, with an
+// explicit vmcnt before the barrier that publishes it.  Nothing else keeps a value in M0.
+__device__ __forceinline__ void lds_dma16(const __attribute__((address_space(1))) void* src, void* lds_dst)
+{
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(m0v), "v"(src) : "memory", "m0");
+}
 
 // Index of the segment that holds submission row r (segments are sorted by row_begin).
 __device__ __forceinline__ uint32_t find_segment(const Segment* segs, uint32_t n, uint32_t r)
@@ -129,13 +141,13 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     const uint32_t chunk = ceil_div(ceil_div(R, nw), 64) * 64;          // rows per wave
     const bool in_regs = ONE_SEG && chunk <= 64 * kRegIters;             // a lane keeps its rows' ids and ranks in registers
     const uint32_t begin = w * chunk, end = w < nw ? min(begin + chunk, R) : begin;
-    int32_t tq[kRegIters];
-    uint32_t rk[kRegIters];
+    int32_t tq[kRegIters];               // first the submitted id, then rank << 11 | tenant (or -1): ids and in-wave ranks are below 2048
+    static_assert(kMaxTenantsPadded <= 2048 && 64 * kRegIters <= 2048, "packing of tenant and rank");
     if (in_regs) {
 #pragma unroll
         for (uint32_t it = 0; it < kRegIters; ++it) {
             const uint32_t r = begin + it * 64 + lane;
-            tq[it] = -1; rk[it] = 0;
+            tq[it] = -1;
             if (r < end) {
                 a.row_src[r] = (const uint8_t*)a.first.src + (size_t)r * a.first.row_stride * a.elem_size;
                 tq[it] = a.first.ids ? a.first.ids[r] : a.first.tenant;
@@ -214,9 +226,11 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 #pragma unroll
         for (uint32_t it = 0; it < kRegIters; ++it) {
             if (begin + it * 64 < end) {                     // wave-uniform
-                rank_step(tq[it], rk[it]);
+                uint32_t rank;
+                rank_step(tq[it], rank);
                 const uint32_t r = begin + it * 64 + lane;
                 if (r < end) a.row_tenant[r] = tq[it];
+                if (tq[it] >= 0) tq[it] |= (int32_t)(rank << 11);
             }
         }
     } else if (w < nw) {
@@ -277,7 +291,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 #pragma unroll
         for (uint32_t it = 0; it < kRegIters; ++it) {
             const uint32_t r = begin + it * 64 + lane;
-            if (r < end) place(r, tq[it], rk[it], w);
+            if (r < end) place(r, tq[it] < 0 ? -1 : (tq[it] & 2047), (uint32_t)tq[it] >> 11, w);
         }
     } else {
 #pragma unroll 4
@@ -343,7 +357,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             const bool conv = rr >> 31;
             const bool big = !conv && ((big_layers >> l) & 1) && fc_is_big(Mt, np);
             // conv: rows = requests * output pixels per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
-            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
+            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), a.conv_tile_rows[l]) : ceil_div(Mt, kTileRows / rr)) * g : 0;
             wave_scan(l, (conv || big) ? 0 : tiles);
             wave_scan(MT_MAX_LAYERS + l, conv ? tiles : 0);
             wave_scan(2 * MT_MAX_LAYERS + l, big ? ceil_div(Mt, kBigTile) * ceil_div(np, kBigTile) : 0);
@@ -1217,12 +1231,12 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
     const uint32_t local = idx - base_l[t];
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     const uint32_t seg0 = a.off[t];
-    const uint32_t rows_total = a.M[t] * L.rows_per_req, mt_ = ceil_div(rows_total, kConvTileRows);
+    const uint32_t rows_total = a.M[t] * L.rows_per_req, mt_ = ceil_div(rows_total, a.conv_tile_rows);
     const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
     const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
     // no barrier below: the waves are independent; wave w takes row blocks w, w+4, ... of the tile
-    for (uint32_t rb = wave; rb < kConvTileRows / kBrickRows; rb += 4) {
-        const uint32_t m0 = (local % mt_) * kConvTileRows + rb * kBrickRows;
+    for (uint32_t rb = wave; rb < a.conv_tile_rows / kBrickRows; rb += 4) {
+        const uint32_t m0 = (local % mt_) * a.conv_tile_rows + rb * kBrickRows;
         if (m0 >= rows_total) break;
         if constexpr (MAXCB == 1) {
             conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0);
@@ -1234,6 +1248,145 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
             else if (ncb == 2) conv_wave<T, 2>(a, L, seg0, m0, rows_total, nb0);
             else if (ncb == 3) conv_wave<T, 3>(a, L, seg0, m0, rows_total, nb0);
             else conv_wave<T, 4>(a, L, seg0, m0, rows_total, nb0);
+        }
+    }
+}
+
+// ---- convolution tiles of two or more channel blocks: activation operand shared through LDS --
+// Same tile (128 pixels x <= 128 channels) and tile list as conv_kernel, other division of
+// labour.  With every wave gathering its own 32 pixels, each wave also streams the whole
+// filter bank; here the waves stand side by side instead (NCB = 4: one 32-channel block and
+// all four pixel blocks per wave; NCB = 2: 2x2), so a wave streams the filters of one channel
+// block only and the gathered activation bricks are shared.  Neither operand passes through
+// registers: wave w forms the bricks of pixel block w, and fetches the filter bricks of its
+// own channel block, with direct global->LDS loads, one per k step, each lane supplying the
+// address of its 16 bytes (for the activations: 8 channels of one tap, or a block of zeros
+// for taps outside the image) and the hardware placing lane l at base + 16 l, which is brick
+// order.  K is walked in chunks of kConvKC k steps through a ring of kConvNS stages, chunks
+// kConvNS - 1 ahead of their use.
+constexpr uint32_t kConvKC = 2, kConvNS = 4;
+constexpr uint32_t kConvStageBytes = 8 * kConvKC * kBrickBytes;      // 4 pixel blocks + 4 filter areas, kConvKC k steps each
+
+template <typename T, int NCB>
+__global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    constexpr uint32_t WR = 4 / NCB, RBW = 4 / WR;                  // wave rows; pixel blocks per wave
+    typedef const __attribute__((address_space(1))) u32x4* gptr_t;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kConvNS * kConvStageBytes];
+    static_assert(kConvNS * kConvStageBytes >= (kMaxTenantsPadded + 1) * 4, "tile_base must fit");
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lh = lane >> 5;
+    uint32_t* base_l = (uint32_t*)lds;
+    const uint32_t n_tiles = a.tile_base[a.T];
+    for (uint32_t i = tid; i <= a.T; i += 256) base_l[i] = a.tile_base[i];
+    uint32_t idx;
+    if (!logical_tile(n_tiles, &idx)) return;
+    __syncthreads();
+    const uint32_t t = find_tenant(base_l, a.T, idx);
+    const uint32_t local = idx - base_l[t];
+    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    const uint32_t seg0 = a.off[t];
+    const uint32_t rpr = L.rows_per_req, cin = L.cin;
+    const uint32_t rows_total = a.M[t] * rpr, mt_ = ceil_div(rows_total, kConvTileRows);
+    const uint32_t m0 = (local % mt_) * kConvTileRows;
+    const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
+    const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
+    const uint32_t nKB = L.K / KB, nKBv = ceil_div(L.k_valid, KB);
+    const uint32_t n_chunks = ceil_div(nKBv, kConvKC);             // n_chunks * kConvKC <= nKB: K is padded to 64
+    const uint32_t wc = wave % NCB, wr = wave / NCB;
+    const bool active = wc < ncb;                                  // idle waves still gather; they stream block 0 and drop it
+
+    // gather role: pixel block `wave`, this lane's pixel and its walk through K (tap, channel)
+    const uint32_t gm = m0 + wave * kBrickRows + li;
+    const bool row_ok = gm < rows_total;
+    gptr_t zeros = (gptr_t)a.zeros;
+    gptr_t img = zeros;
+    int32_t ih0 = 0, iw0 = 0;
+    {
+        const uint32_t mm = row_ok ? gm : m0;
+        const uint32_t req = mm / rpr, pix = mm % rpr;
+        ih0 = (int32_t)((pix / L.out_w) * L.stride) - 1; iw0 = (int32_t)((pix % L.out_w) * L.stride) - 1;
+        img = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
+    }
+    gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
+    const uint32_t last_kb = n_chunks * kConvKC - 1;
+    uint32_t c0 = lh * EPC;
+    int32_t th = 0, tw = 0;
+    auto wrap = [&]() { if (c0 >= cin) { c0 -= cin; if (++tw == 3) { tw = 0; ++th; } } };
+    wrap(); wrap();
+    // The next kConvKC k steps of this wave's pixel block and of its filter block: 2 * kConvKC
+    // loads.  Chunks past the end gather zeros (th >= 3) and repeat the last filter bricks, which
+    // keeps the number of loads per round, and with it the wait below, uniform.
+    auto fetch_chunk = [&](uint32_t c) {
+        uint8_t* dst = lds + (c % kConvNS) * kConvStageBytes;
+#pragma unroll
+        for (uint32_t kk = 0; kk < kConvKC; ++kk) {
+            const int32_t ih = ih0 + th, iw = iw0 + tw;
+            const bool ok = row_ok & (th < 3) & (ih >= 0) & (ih < (int32_t)L.in_h) & (iw >= 0) & (iw < (int32_t)L.in_w);
+            const uint32_t off = ((uint32_t)(ih * (int32_t)L.in_w + iw) * cin + c0) / EPC;
+            gptr_t p = ok ? img + off : zeros;
+            lds_dma16(p, dst + (wave * kConvKC + kk) * kBrickBytes);
+            lds_dma16(wp + (size_t)min(c * kConvKC + kk, last_kb) * 64, dst + ((4 + wave) * kConvKC + kk) * kBrickBytes);
+            c0 += KB; wrap(); wrap();
+        }
+    };
+
+    f32x16 acc[RBW];
+#pragma unroll
+    for (uint32_t r = 0; r < RBW; ++r)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[r][v] = 0.0f;
+
+    __syncthreads();                                               // the lookup is over before the ring reuses the memory
+#pragma unroll
+    for (uint32_t c = 0; c < kConvNS - 1; ++c) fetch_chunk(c);
+    // when chunk c is needed, the loads of the kConvNS - 2 younger chunks may still be in flight
+    constexpr uint32_t kOut = (kConvNS - 2) * 2 * kConvKC;
+    constexpr int kWaitVm = (int)((kOut & 15) | ((kOut >> 4) << 14) | 0x0070 | 0x0F00);
+    for (uint32_t c = 0; c < n_chunks; ++c) {
+        __builtin_amdgcn_s_waitcnt(kWaitVm);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();                              // chunk c is complete for every wave; everyone is done with chunk c - 1
+        asm volatile("" ::: "memory");
+        fetch_chunk(c + kConvNS - 1);
+        const uint8_t* st = lds + (c % kConvNS) * kConvStageBytes + lane * 16;
+#pragma unroll
+        for (uint32_t kk = 0; kk < kConvKC; ++kk) {
+            const u32x4 wv = *(const u32x4*)(st + ((4 + wave) * kConvKC + kk) * kBrickBytes);
+#pragma unroll
+            for (uint32_t r = 0; r < RBW; ++r) {
+                const u32x4 av = *(const u32x4*)(st + ((wr * RBW + r) * kConvKC + kk) * kBrickBytes);
+                Mma<T>::run(acc[r], wv, av);                       // rows = channels, columns = pixels
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // this wave's LDS reads of the chunk are done before its next barrier
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");               // trailing loads have landed before the workgroup's LDS is released
+
+    // epilogue: lane holds, for pixel li of each of its pixel blocks, channels 8g + 4 lh + {0..3}
+    if (!active) return;
+    const float* bias = (const float*)(a.arena + L.b_off);
+    const uint32_t nbase = (nb0 + wc) * kBrickRows + 4 * lh;
+    f32x4 bv[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) bv[g] = *(const f32x4*)(bias + nbase + 8 * g);   // bias is padded to N_pad
+#pragma unroll
+    for (uint32_t r = 0; r < RBW; ++r) {
+        const uint32_t m = m0 + (wr * RBW + r) * kBrickRows + li;
+        if (m < rows_total) {
+            const uint32_t req = m / rpr, pix = m % rpr;
+            T* out = (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const uint32_t n = nbase + 8 * g;
+                T o[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = (T)activate(acc[r][4 * g + i] + bv[g][i], L.act);
+                if (n < L.N) {                                      // N is a multiple of 8: a run is in or out as a whole
+                    if constexpr (sizeof(T) == 2) *(uint64_t*)(out + n) = __builtin_bit_cast(uint64_t, o);
+                    else *(u32x4*)(out + n) = __builtin_bit_cast(u32x4, o);
+                }
+            }
         }
     }
 }
@@ -1366,8 +1519,8 @@ template <typename T>
 static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, uint32_t grid, hipStream_t s)
 {
     if (max_cb <= 1) hipLaunchKernelGGL((conv_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a);
-    else if (max_cb == 2) hipLaunchKernelGGL((conv_kernel<T, 2>), dim3(grid), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((conv_kernel<T, 4>), dim3(grid), dim3(256), 0, s, a);
+    else if (max_cb == 2) hipLaunchKernelGGL((conv_lds_kernel<T, 2>), dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((conv_lds_kernel<T, 4>), dim3(grid), dim3(256), 0, s, a);
 }
 
 hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, uint32_t grid, hipStream_t s)
