@@ -65,10 +65,15 @@ def counter_means(path: str, counter: str) -> dict:
 
 
 def pick(means: dict, needle: str):
-    hits = [k for k in means if needle in k]
-    if len(hits) != 1:
+    """The entry whose name contains `needle`; a trailing '*' pools every match (dispatch-weighted mean)."""
+    pool = needle.endswith("*")
+    hits = [k for k in means if needle.rstrip("*") in k]
+    if not hits or (len(hits) != 1 and not pool):
         raise SystemExit("kernel %r matches %r" % (needle, hits))
-    return hits[0], means[hits[0]]
+    if not pool:
+        return hits[0], means[hits[0]]
+    n = sum(means[k][1] for k in hits)
+    return " + ".join(sorted(hits)), (sum(means[k][0] * means[k][1] for k in hits) / n, n)
 
 
 def traffic(fetch_csv: str, write_csv: str, kernel: str, copy_bytes: int) -> str:
