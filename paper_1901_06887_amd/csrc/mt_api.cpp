@@ -637,6 +637,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         HeadArgs h{};
         h.R = R; h.tenants = c->d_tenants; h.row_tenant = c->d_row_tenant; h.pos_of = c->d_pos_of; h.logits = c->d_logits;
         h.C_pad = c->C_pad; h.out = outp; h.min_classes = head_min_classes;
+        h.vec_ok = out->row_stride % 4 == 0 && ((uintptr_t)out->probs & 15) == 0 && ((uintptr_t)out->logits & 15) == 0;
         TIMED(kProfHead, launch_head(h, s));
     }
 #undef TIMED

@@ -143,6 +143,7 @@ struct HeadArgs {
     const float* logits; uint32_t C_pad;
     OutPtrs out;
     uint32_t min_classes;   // rows of models with fewer classes were finished by the FC kernel
+    uint32_t vec_ok;        // output rows can be written 16 bytes at a time (aligned buffers, row stride a multiple of 4)
 };
 
 // Launchers (defined in mt_kernels.hip).  All enqueue on `s` and return the launch status.

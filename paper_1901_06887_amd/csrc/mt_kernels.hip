@@ -1437,8 +1437,51 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
     if (pos < 0) return;                                    // rejected rows were answered by the batcher
     C = a.tenants[a.row_tenant[r]].n_classes;
     if (C < a.min_classes) return;                          // finished by the FC kernel
-    {
-        z = a.logits + (size_t)pos * a.C_pad;
+    z = a.logits + (size_t)pos * a.C_pad;
+    if (a.vec_ok && C <= 1024) {
+        // the row lives in registers: 16 logits per lane (four 16-byte loads), read once
+        f32x4 v[4];
+        int32_t best = 0x7fffffff;
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            const uint32_t c = (q * 64 + lane) * 4;
+            v[q] = c < a.C_pad ? *(const f32x4*)(z + c) : f32x4{0, 0, 0, 0};   // C_pad is a multiple of 32
+#pragma unroll
+            for (uint32_t i = 0; i < 4; ++i) {
+                if (c + i >= C) v[q][i] = -INFINITY;
+                if (v[q][i] > mx) { mx = v[q][i]; best = (int32_t)(c + i); }      // increasing index: the first hit is this lane's lowest
+            }
+        }
+        for (int d = 32; d >= 1; d >>= 1) {
+            const float omx = __shfl_xor(mx, d);
+            const int32_t ob = __shfl_xor(best, d);
+            if (omx > mx || (omx == mx && ob < best)) { mx = omx; best = ob; }
+        }
+        label = best;
+        f32x4 e[4];
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q)
+#pragma unroll
+            for (uint32_t i = 0; i < 4; ++i) { e[q][i] = __expf(v[q][i] - mx); sum += e[q][i]; }   // exp(-inf) = 0 past the last class
+        for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d);
+        const float inv = 1.0f / sum;
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            const uint32_t c = (q * 64 + lane) * 4;
+            if (c < a.out.row_stride) {
+                f32x4 pr, lg;
+#pragma unroll
+                for (uint32_t i = 0; i < 4; ++i) { const bool in = c + i < C; pr[i] = in ? e[q][i] * inv : 0.0f; lg[i] = in ? v[q][i] : 0.0f; }
+                if (a.out.probs) *(f32x4*)(a.out.probs + (size_t)r * a.out.row_stride + c) = pr;
+                if (a.out.logits) *(f32x4*)(a.out.logits + (size_t)r * a.out.row_stride + c) = lg;
+            }
+        }
+        // rows wider than 1024 entries: zero the rest
+        for (uint32_t c = 1024 + lane; c < a.out.row_stride; c += 64) {
+            if (a.out.probs) a.out.probs[(size_t)r * a.out.row_stride + c] = 0.0f;
+            if (a.out.logits) a.out.logits[(size_t)r * a.out.row_stride + c] = 0.0f;
+        }
+    } else {
         int32_t best = 0x7fffffff;
         for (uint32_t c = lane; c < C; c += 64) {
             const float v = z[c];
@@ -1452,12 +1495,12 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
         label = best;
         for (uint32_t c = lane; c < C; c += 64) sum += __expf(z[c] - mx);
         for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d);
-    }
-    const float inv = 1.0f / sum;
-    for (uint32_t c = lane; c < a.out.row_stride; c += 64) {
-        const bool in = c < C;
-        if (a.out.probs) a.out.probs[(size_t)r * a.out.row_stride + c] = in ? __expf(z[c] - mx) * inv : 0.0f;
-        if (a.out.logits) a.out.logits[(size_t)r * a.out.row_stride + c] = in ? z[c] : 0.0f;
+        const float inv = 1.0f / sum;
+        for (uint32_t c = lane; c < a.out.row_stride; c += 64) {
+            const bool in = c < C;
+            if (a.out.probs) a.out.probs[(size_t)r * a.out.row_stride + c] = in ? __expf(z[c] - mx) * inv : 0.0f;
+            if (a.out.logits) a.out.logits[(size_t)r * a.out.row_stride + c] = in ? z[c] : 0.0f;
+        }
     }
     if (lane == 0) {
         a.out.labels[r] = label;
