@@ -601,7 +601,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     {
         GatherArgs g{};
         g.row_src = c->d_row_src; g.P = P; g.tenants = c->d_tenants; g.layers = c->d_layers; g.row_tenant = c->d_row_tenant;
-        g.perm = c->d_perm; g.off = c->d_off; g.T = T; g.act = c->d_act[0]; g.S = c->S; g.elem_size = c->elem_size;
+        g.perm = c->d_perm; g.off = c->d_off; g.T = T; g.act = c->d_act[0]; g.S = c->S; g.elem_size = c->elem_size; g.zeros = c->d_zeros;
         if (c->any_fc_first && !fuse_gather) TIMED(kProfGather, launch_gather(g, s));
         if (c->any_conv_first) TIMED(kProfGatherImg, launch_gather_image(g, s));
     }

@@ -116,6 +116,7 @@ struct GatherArgs {
     const TenantDev* tenants; const LayerDev* layers; const int32_t* row_tenant; const int32_t* perm;
     const uint32_t* off; uint32_t T;
     void* act; uint32_t S; uint32_t elem_size;
+    const void* zeros;     // >= 16 readable zero bytes
 };
 
 struct GemmArgs {

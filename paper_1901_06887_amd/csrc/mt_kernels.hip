@@ -30,7 +30,6 @@ constexpr uint32_t kBatchThreads = 1024;
 constexpr uint32_t kMaxTenantsPadded = 2048;
 constexpr uint32_t kHistEntries = 8192;
 constexpr uint32_t kSegsInLds = 64;
-constexpr uint32_t kRegIters = 16;         // batcher: rows a lane may keep in registers (64 * kRegIters rows per wave)
 
 __device__ __forceinline__ uint32_t ceil_div(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
 
@@ -114,7 +113,9 @@ __device__ __forceinline__ bool fc_is_big(uint32_t rows, uint32_t n_pad) { retur
 // same whatever the tenant mix is.  Latency, not bandwidth, bounds this kernel, so everything
 // that does not depend on the rows (tenant and layer facts) is fetched up front, tenant ids
 // are fetched one step ahead, and all tile-count arrays are scanned in one pass.
-template <bool ONE_SEG>
+// NSLOT: tenants per thread (1 for up to 1024 tenants, else 2); with one slot the registers that
+// would hold the second tenant's layer facts let a lane keep twice as many rows instead.
+template <bool ONE_SEG, int NSLOT>
 __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 {
     __shared__ uint32_t hist[kHistEntries];
@@ -132,7 +133,8 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     if (tid < MT_MAX_LAYERS) big_total[tid] = 0;       // first read is several barriers away
     uint32_t Tp = 64, bits = 6;
     while (Tp < T) { Tp <<= 1; ++bits; }
-    const uint32_t nslots = Tp > kBatchThreads ? 2 : 1;
+    constexpr uint32_t nslots = NSLOT;
+    constexpr uint32_t kRegIters = NSLOT == 1 ? 32 : 16;   // rows a lane may keep in registers (64 * kRegIters rows per wave)
 
     // Every global load the kernel depends on is issued before the first wait: the lane's tenant
     // ids (register path, below), the tenant facts and -- unconditionally, so that they do not
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     const bool in_regs = ONE_SEG && chunk <= 64 * kRegIters;             // a lane keeps its rows' ids and ranks in registers
     const uint32_t begin = w * chunk, end = w < nw ? min(begin + chunk, R) : begin;
     int32_t tq[kRegIters];               // first the submitted id, then rank << 11 | tenant (or -1): ids and in-wave ranks are below 2048
-    static_assert(kMaxTenantsPadded <= 2048 && 64 * kRegIters <= 2048, "packing of tenant and rank");
+    static_assert(kMaxTenantsPadded <= 2048 && 64 * kRegIters <= (1u << 21), "packing of tenant and rank");
     if (in_regs) {
 #pragma unroll
         for (uint32_t it = 0; it < kRegIters; ++it) {
@@ -157,11 +159,11 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 
     // column groups per layer (0 = no tiles), rows per request with the kind in the top bit
     // (1 = conv), padded width
-    uint32_t grp[2][MT_MAX_LAYERS], rpr[2][MT_MAX_LAYERS], npad[2][MT_MAX_LAYERS];
+    uint32_t grp[NSLOT][MT_MAX_LAYERS], rpr[NSLOT][MT_MAX_LAYERS], npad[NSLOT][MT_MAX_LAYERS];
 #pragma unroll
-    for (uint32_t slot = 0; slot < 2; ++slot) {
+    for (uint32_t slot = 0; slot < nslots; ++slot) {
         const uint32_t t = tid + slot * kBatchThreads;
-        const bool live = slot < nslots && t < T;
+        const bool live = t < T;
         uint32_t kind[MT_MAX_LAYERS], n[MT_MAX_LAYERS], np[MT_MAX_LAYERS], rr[MT_MAX_LAYERS];
         uint32_t reg = 0, nl = 0;
         if (live) {
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             }
             reg = a.tenants[t].registered; nl = a.tenants[t].n_layers;
         }
-        if (slot < nslots && t < Tp) regl[t] = live && reg;
+        if (t < Tp) regl[t] = live && reg;
         if (!reg) nl = 0;
 #pragma unroll
         for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
@@ -308,13 +310,14 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         uint32_t bt[MT_MAX_LAYERS];
 #pragma unroll
         for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) bt[l] = 0;
+#pragma unroll
         for (uint32_t slot = 0; slot < nslots; ++slot) {
             const uint32_t t = tid + slot * kBatchThreads;
             const uint32_t Mt = t < Tp ? Ml[t] : 0;
 #pragma unroll
             for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-                const uint32_t rr = slot == 0 ? rpr[0][l] : rpr[1][l], np = slot == 0 ? npad[0][l] : npad[1][l];
-                const uint32_t g = slot == 0 ? grp[0][l] : grp[1][l];
+                const uint32_t rr = rpr[slot][l], np = npad[slot][l];
+                const uint32_t g = grp[slot][l];
                 if (g && !(rr >> 31) && fc_is_big(Mt, np)) bt[l] += ceil_div(Mt, kBigTile) * ceil_div(np, kBigTile);
             }
         }
@@ -335,6 +338,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     // Only the exclusive in-wave prefix of each list stays in registers across the barriers; the
     // running total over slots lives in LDS.
     if (tid < kLists) carry_l[tid] = 0;
+#pragma unroll
     for (uint32_t slot = 0; slot < nslots; ++slot) {
         const uint32_t t = tid + slot * kBatchThreads;
         const uint32_t Mt = t < Tp ? Ml[t] : 0;
@@ -352,8 +356,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         };
 #pragma unroll
         for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-            const uint32_t g = slot == 0 ? grp[0][l] : grp[1][l], rr = slot == 0 ? rpr[0][l] : rpr[1][l];
-            const uint32_t np = slot == 0 ? npad[0][l] : npad[1][l];
+            const uint32_t g = grp[slot][l], rr = rpr[slot][l], np = npad[slot][l];
             const bool conv = rr >> 31;
             const bool big = !conv && ((big_layers >> l) & 1) && fc_is_big(Mt, np);
             // conv: rows = requests * output pixels per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
@@ -424,6 +427,27 @@ __device__ void gather_bricks(const GatherArgs& a, const TenantDev& td, uint32_t
     const T* src = r >= 0 ? (const T*)a.row_src[r] : nullptr;
     u32x4* dst = (u32x4*)((T*)a.act + (size_t)seg0 * a.S) + (size_t)((p0 - seg0) / kBrickRows) * nKB * 64 + lane;
     const uint32_t n = td.in_len;
+    // Rows that are 16-byte aligned and a whole number of chunks long (the usual case) are copied
+    // with four loads in flight per lane and no branch around them: chunks past the row's end
+    // and padding rows read a block of zeros instead.
+    const bool lane_ok = src == nullptr || (((uintptr_t)src & 15) == 0);
+    if (n % EPC == 0 && __all(lane_ok)) {
+        typedef const __attribute__((address_space(1))) u32x4* gptr_t;
+        gptr_t row = (gptr_t)src, zeros = (gptr_t)a.zeros;
+        const uint32_t nch = src ? n / EPC : 0;              // chunks this lane may read
+        for (uint32_t kb0 = wave; kb0 < nKB; kb0 += 16) {
+            u32x4 v[4];
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) {
+                const uint32_t ch = (kb0 + 4 * j) * 2 + lh;
+                v[j] = *(ch < nch ? row + ch : zeros);
+            }
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j)
+                if (kb0 + 4 * j < nKB) dst[(size_t)(kb0 + 4 * j) * 64] = v[j];
+        }
+        return;
+    }
     for (uint32_t kb = wave; kb < nKB; kb += 4) {
         const uint32_t k = kb * KB + lh * EPC;
         u32x4 v = {0, 0, 0, 0};
@@ -1511,8 +1535,11 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
 // ---- launchers ------------------------------------------------------------------------------
 hipError_t launch_batcher(const BatchArgs& a, hipStream_t s)
 {
-    if (a.n_segs == 1) hipLaunchKernelGGL(batcher_kernel<true>, dim3(1), dim3(kBatchThreads), 0, s, a);
-    else hipLaunchKernelGGL(batcher_kernel<false>, dim3(1), dim3(kBatchThreads), 0, s, a);
+    const bool one = a.n_segs == 1, wide = a.T > kBatchThreads;
+    if (one && !wide) hipLaunchKernelGGL((batcher_kernel<true, 1>), dim3(1), dim3(kBatchThreads), 0, s, a);
+    else if (one) hipLaunchKernelGGL((batcher_kernel<true, 2>), dim3(1), dim3(kBatchThreads), 0, s, a);
+    else if (!wide) hipLaunchKernelGGL((batcher_kernel<false, 1>), dim3(1), dim3(kBatchThreads), 0, s, a);
+    else hipLaunchKernelGGL((batcher_kernel<false, 2>), dim3(1), dim3(kBatchThreads), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
