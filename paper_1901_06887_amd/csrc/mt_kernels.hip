@@ -1416,6 +1416,7 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
 }
 
 // ---- global average pool: one workgroup per packed row, NHWC row in, brick slice out ------
+constexpr uint32_t kGapThreads = 128;
 template <typename T>
 __device__ void gap_row(const GapArgs& a, const LayerDev& L, uint32_t p, uint32_t seg0)
 {
@@ -1426,6 +1427,34 @@ __device__ void gap_row(const GapArgs& a, const LayerDev& L, uint32_t p, uint32_
     const uint32_t nKB = L.out_fill / KB;
     T* out = (T*)a.act_out + (size_t)seg0 * a.S + (size_t)rb * nKB * 64 * EPC;
     const float inv = 1.0f / (float)HW;
+    const uint32_t CPP = C / EPC;                              // 16-byte chunks per pixel (C is a multiple of 8)
+    if (C % EPC == 0 && CPP <= kGapThreads && kGapThreads % CPP == 0) {
+        // 16 bytes per load: thread (pg, cg) sums chunk cg of pixels pg, pg + G, ...; the G partial
+        // sums of a channel are then added in a fixed order through LDS
+        __shared__ float part[kGapThreads * EPC];
+        const uint32_t G = kGapThreads / CPP, cg = threadIdx.x % CPP, pg = threadIdx.x / CPP;
+        float s[EPC];
+#pragma unroll
+        for (uint32_t e = 0; e < EPC; ++e) s[e] = 0.0f;
+        const u32x4* src = (const u32x4*)in + cg;
+#pragma unroll 4
+        for (uint32_t q = pg; q < HW; q += G) {
+            const u32x4 v = src[(size_t)q * CPP];
+            const T* ve = (const T*)&v;
+#pragma unroll
+            for (uint32_t e = 0; e < EPC; ++e) s[e] += (float)ve[e];
+        }
+#pragma unroll
+        for (uint32_t e = 0; e < EPC; ++e) part[(pg * CPP + cg) * EPC + e] = s[e];
+        __syncthreads();
+        for (uint32_t c = threadIdx.x; c < L.out_fill; c += kGapThreads) {
+            float t = 0.0f;
+            if (c < C) for (uint32_t g = 0; g < G; ++g) t += part[g * C + c];
+            const uint32_t kb = c / KB, h = (c % KB) / EPC, e = c % EPC;
+            out[((size_t)kb * 64 + i + 32 * h) * EPC + e] = (T)(t * inv);
+        }
+        return;
+    }
     for (uint32_t c = threadIdx.x; c < L.out_fill; c += blockDim.x) {
         float s = 0.0f;
         if (c < C) for (uint32_t q = 0; q < HW; ++q) s += (float)in[(size_t)q * C + c];
@@ -1434,7 +1463,7 @@ __device__ void gap_row(const GapArgs& a, const LayerDev& L, uint32_t p, uint32_
     }
 }
 
-__global__ __launch_bounds__(128) void gap_kernel(GapArgs a)
+__global__ __launch_bounds__(kGapThreads) void gap_kernel(GapArgs a)
 {
     const uint32_t p = blockIdx.x;
     if (p >= a.off[a.T]) return;
@@ -1604,7 +1633,7 @@ hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, uint3
 hipError_t launch_gap(const GapArgs& a, hipStream_t s)
 {
     // grid covers every packed row; rows of other layer kinds return at once
-    hipLaunchKernelGGL(gap_kernel, dim3(a.P), dim3(128), 0, s, a);
+    hipLaunchKernelGGL(gap_kernel, dim3(a.P), dim3(kGapThreads), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_head(const HeadArgs& a, hipStream_t s)

@@ -100,6 +100,33 @@ def test_fp32_cnn_and_gelu():
     run_and_compare(w, "cnn-fp32")
 
 
+def test_cnn_wide_layers_three_channel_blocks():
+    # 72 and 96 output channels: convolution tiles of 3 channel blocks (the 4-wide kernel with an
+    # idle wave), ragged pixel tiles, stride 1 and 2
+    run_and_compare(wl.c4(n_tenants=2, n_requests=9, hw=12, chans=(3, 72, 96, 40), strides=(1, 2, 1), classes=7), "cnn-wide")
+
+
+def test_cnn_fp32_wide_layers():
+    w = wl.c4(n_tenants=2, n_requests=5, hw=8, chans=(3, 64, 128, 16), strides=(2, 1, 2), classes=4)
+    w.dtype = "f32"
+    run_and_compare(w, "cnn-fp32-wide")
+
+
+def test_cnn_tenants_of_different_widths_share_a_launch():
+    # same layer indices, different channel counts: the launch is sized for the widest tenant and
+    # the narrow tenant's tiles leave waves idle
+    a = wl.c4(n_tenants=2, n_requests=10, hw=8, chans=(3, 16, 32, 24), classes=6, seed=21)
+    b = wl.c4(n_tenants=2, n_requests=10, hw=8, chans=(3, 64, 128, 64), classes=6, seed=22)
+    tenants = {0: a.tenants[0], 1: b.tenants[0], 2: b.tenants[1]}
+    ids = np.random.default_rng(9).integers(0, 3, 10).astype(np.int32)
+    run_and_compare(wl.Workload("cnn-mixed", "bf16", tenants, ids, a.inputs), "cnn-mixed-widths")
+
+
+def test_more_than_1024_classes():
+    # the head kernel holds rows of up to 1024 logits in registers; wider rows take its loop
+    run_and_compare(wl.c2(n_tenants=3, n_requests=70, dims=(64, 96, 1100)), "wide-head")
+
+
 # ---- full-size configurations ---------------------------------------------------------------
 def test_c2_full():
     run_and_compare(wl.c2(), "c2")
