@@ -208,10 +208,6 @@ void recompute_bounds(mt_ctx* c)
     }
 }
 
-// Output pixels per conv tile of a layer index: wide tiles for layers that are one channel block
-// wide everywhere (they run the per-wave kernel, whose tile set-up is then shared by 16 blocks).
-static uint32_t conv_tile_rows(const mt_ctx* c, uint32_t l) { return c->max_conv_cb[l] <= 1 ? kConvNarrowTileRows : kConvTileRows; }
-
 // Upper bound of the number of tiles of one list over any split of R rows among tenants.
 uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R)
 {
@@ -219,7 +215,7 @@ uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R)
     if (kind == 2)      // big FC tiles: only tenants with >= kBigMinRows rows; sum ceil(M_t/256) <= R/256 + R/kBigMinRows
         return R < (uint64_t)kBigMinBatch ? 0 : (uint64_t)c->max_nt[2][l] * (R / kBigTile + R / kBigMinRows);
     // FC tiles may be as short as 64 rows (layers with at most 64 outputs)
-    const uint64_t tile_rows = kind == 0 ? kTileRows / 2 : conv_tile_rows(c, l);
+    const uint64_t tile_rows = kind == 0 ? kTileRows / 2 : kConvTileRows;
     return (uint64_t)c->max_nt[kind][l] * (R * c->max_rpr[kind][l] / tile_rows) + c->sum_nt[kind][l];
 }
 
@@ -570,7 +566,6 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
     b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.fc_split_k = c->fc_split_k;
     b.list_mask = c->list_mask; b.big_enabled = big_enabled; b.big_min_tiles = c->big_min_tiles;
-    for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) b.conv_tile_rows[l] = conv_tile_rows(c, l);
     const OutPtrs outp{out->labels, out->probs, out->logits, out->n_classes, out->row_stride};
     b.out = outp;
     // A last layer of at most 32 classes is one column block: its FC tiles finish their rows
@@ -618,7 +613,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             ga.gather = (kind == 0 && l == 0 && fuse_gather); ga.perm = c->d_perm; ga.row_src = c->d_row_src;
             ga.fuse_head = fuse_head; ga.out = outp;
             ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
-            ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad; ga.zeros = c->d_zeros; ga.conv_tile_rows = conv_tile_rows(c, l);
+            ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad; ga.zeros = c->d_zeros;
             const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, 0x7ffffff0u);
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
             else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], g32, s));

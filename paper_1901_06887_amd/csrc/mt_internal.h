@@ -21,8 +21,7 @@ constexpr int kBrickRows = 32;
 constexpr int kBrickBytes = 1024;
 constexpr int kTileRows = 128;      // rows (4 row blocks) of a grouped-GEMM workgroup tile
 constexpr int kTileCols = 128;      // columns (4 column blocks) of a workgroup tile
-constexpr int kConvTileRows = 128;  // GEMM rows (output pixels) of a conv workgroup tile: one 32-row block per wave
-constexpr int kConvNarrowTileRows = 128;   // ... of a layer index whose tiles are all one channel block wide (512 was measured slower: fewer resident waves to hide latency)
+constexpr int kConvTileRows = 128;  // GEMM rows (output pixels) of a conv workgroup tile: one 32-row block per wave (512 measured slower)
 // A tenant-layer with at least kBigMinRows requests and kBigMinCols (padded) outputs is
 // compute bound; it is cut into kBigTile x kBigTile tiles and served by the big-tile FC kernel.
 constexpr int kBigTile = 256;
@@ -96,7 +95,6 @@ struct BatchArgs {
     uint32_t elem_size;
     uint32_t fc_split_k;   // 1: FC tiles take one column block each and split K four ways
     uint32_t big_enabled;  // 0: no tenant-layer is given big tiles in this run (small batches)
-    uint32_t conv_tile_rows[MT_MAX_LAYERS];   // output pixels per conv tile of each layer index
     uint32_t big_min_tiles; // a layer index uses big tiles only when its qualifying tenants make at least this many
     const TenantDev* tenants; const LayerDev* layers;
     int32_t* row_tenant;   // [R] tenant of each submitted row, -1 if rejected
@@ -130,7 +128,6 @@ struct GemmArgs {
     const void* act_in; void* act_out; const uint8_t* arena;
     float* logits; uint32_t S; uint32_t C_pad;
     const void* zeros;     // >= 16 readable zero bytes
-    uint32_t conv_tile_rows;   // output pixels per conv tile of this layer index
 };
 
 struct GapArgs {

@@ -360,7 +360,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             const bool conv = rr >> 31;
             const bool big = !conv && ((big_layers >> l) & 1) && fc_is_big(Mt, np);
             // conv: rows = requests * output pixels per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
-            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), a.conv_tile_rows[l]) : ceil_div(Mt, kTileRows / rr)) * g : 0;
+            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
             wave_scan(l, (conv || big) ? 0 : tiles);
             wave_scan(MT_MAX_LAYERS + l, conv ? tiles : 0);
             wave_scan(2 * MT_MAX_LAYERS + l, big ? ceil_div(Mt, kBigTile) * ceil_div(np, kBigTile) : 0);
@@ -1255,12 +1255,12 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
     const uint32_t local = idx - base_l[t];
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     const uint32_t seg0 = a.off[t];
-    const uint32_t rows_total = a.M[t] * L.rows_per_req, mt_ = ceil_div(rows_total, a.conv_tile_rows);
+    const uint32_t rows_total = a.M[t] * L.rows_per_req, mt_ = ceil_div(rows_total, kConvTileRows);
     const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
     const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
     // no barrier below: the waves are independent; wave w takes row blocks w, w+4, ... of the tile
-    for (uint32_t rb = wave; rb < a.conv_tile_rows / kBrickRows; rb += 4) {
-        const uint32_t m0 = (local % mt_) * a.conv_tile_rows + rb * kBrickRows;
+    for (uint32_t rb = wave; rb < kConvTileRows / kBrickRows; rb += 4) {
+        const uint32_t m0 = (local % mt_) * kConvTileRows + rb * kBrickRows;
         if (m0 >= rows_total) break;
         if constexpr (MAXCB == 1) {
             conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0);
@@ -1288,7 +1288,7 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
 // for taps outside the image) and the hardware placing lane l at base + 16 l, which is brick
 // order.  K is walked in chunks of kConvKC k steps through a ring of kConvNS stages, chunks
 // kConvNS - 1 ahead of their use.
-constexpr uint32_t kConvKC = 2, kConvNS = 4;
+constexpr uint32_t kConvKC = 2, kConvNS = 3;
 constexpr uint32_t kConvStageBytes = 8 * kConvKC * kBrickBytes;      // 4 pixel blocks + 4 filter areas, kConvKC k steps each
 
 template <typename T, int NCB>
