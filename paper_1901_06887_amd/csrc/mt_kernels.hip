@@ -113,9 +113,10 @@ __device__ __forceinline__ bool fc_is_big(uint32_t rows, uint32_t n_pad) { retur
 // same whatever the tenant mix is.  Latency, not bandwidth, bounds this kernel, so everything
 // that does not depend on the rows (tenant and layer facts) is fetched up front, tenant ids
 // are fetched one step ahead, and all tile-count arrays are scanned in one pass.
-// NSLOT: tenants per thread (1 for up to 1024 tenants, else 2); with one slot the registers that
-// would hold the second tenant's layer facts let a lane keep twice as many rows instead.
-template <bool ONE_SEG, int NSLOT>
+// NSLOT: tenants per thread (1 for up to 1024 tenants, else 2).  ITERS: rows a lane may keep in
+// registers (64 * ITERS rows per wave); the launcher picks the smallest instantiation that
+// covers the batch, because the unrolled steps of a larger one cost small batches microseconds.
+template <bool ONE_SEG, int NSLOT, int ITERS>
 __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 {
     __shared__ uint32_t hist[kHistEntries];
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     uint32_t Tp = 64, bits = 6;
     while (Tp < T) { Tp <<= 1; ++bits; }
     constexpr uint32_t nslots = NSLOT;
-    constexpr uint32_t kRegIters = NSLOT == 1 ? 32 : 16;   // rows a lane may keep in registers (64 * kRegIters rows per wave)
+    constexpr uint32_t kRegIters = ITERS;
 
     // Every global load the kernel depends on is issued before the first wait: the lane's tenant
     // ids (register path, below), the tenant facts and -- unconditionally, so that they do not
@@ -1565,10 +1566,19 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
 hipError_t launch_batcher(const BatchArgs& a, hipStream_t s)
 {
     const bool one = a.n_segs == 1, wide = a.T > kBatchThreads;
-    if (one && !wide) hipLaunchKernelGGL((batcher_kernel<true, 1>), dim3(1), dim3(kBatchThreads), 0, s, a);
-    else if (one) hipLaunchKernelGGL((batcher_kernel<true, 2>), dim3(1), dim3(kBatchThreads), 0, s, a);
-    else if (!wide) hipLaunchKernelGGL((batcher_kernel<false, 1>), dim3(1), dim3(kBatchThreads), 0, s, a);
-    else hipLaunchKernelGGL((batcher_kernel<false, 2>), dim3(1), dim3(kBatchThreads), 0, s, a);
+    // rows per lane of the register path, as the kernel derives them
+    uint32_t Tp = 64;
+    while (Tp < a.T) Tp <<= 1;
+    const uint32_t nw = std::min<uint32_t>(kBatchThreads / 64, kHistEntries / Tp);
+    const uint32_t iters = (((a.R + nw - 1) / nw) + 63) / 64;
+#define MT_BATCHER(SEG, NS, IT) hipLaunchKernelGGL((batcher_kernel<SEG, NS, IT>), dim3(1), dim3(kBatchThreads), 0, s, a)
+    if (!one) { if (wide) MT_BATCHER(false, 2, 4); else MT_BATCHER(false, 1, 4); }      // many submissions: no register path
+    else if (wide) MT_BATCHER(true, 2, 16);
+    else if (iters <= 4) MT_BATCHER(true, 1, 4);
+    else if (iters <= 8) MT_BATCHER(true, 1, 8);
+    else if (iters <= 16) MT_BATCHER(true, 1, 16);
+    else MT_BATCHER(true, 1, 32);
+#undef MT_BATCHER
     return hipGetLastError();
 }
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
