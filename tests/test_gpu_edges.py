@@ -170,3 +170,16 @@ def test_mixed_class_counts_use_both_head_paths():
     gpu = gpu_run(ctx, w, poison=True)
     compare(w, gpu, oracle_rows(w), what="mixed-classes")
     ctx.close()
+
+
+def test_more_than_1024_tenants():
+    # two tenants per batcher thread (the wide instantiation of the segmentation kernel), most with
+    # one or two rows, some with none
+    w = wl.c2(n_tenants=1500, n_requests=2600, dims=(24, 40, 6), s=0.3)
+    assert len(w.counts()) < 1500
+    ctx = make_context(w)
+    gpu = gpu_run(ctx, w, poison=True)
+    counts = ctx.last_counts()
+    assert np.array_equal(counts, np.bincount(w.tenant_ids, minlength=len(counts)))
+    compare(w, gpu, oracle_rows(w), what="1500-tenants")
+    ctx.close()
