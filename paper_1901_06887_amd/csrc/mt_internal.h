@@ -19,7 +19,8 @@ namespace mt {
 // land directly in MFMA operand order.
 constexpr int kBrickRows = 32;
 constexpr int kBrickBytes = 1024;
-constexpr int kTileRows = 128;      // rows (4 row blocks) of a grouped-GEMM workgroup tile
+constexpr int kTileRows = 64;       // rows (2 row blocks) of a grouped-GEMM workgroup tile: 128-row tiles leave room for only 8 weight
+                                    // bricks in flight per wave, which made them the slowest tiles of a launch
 constexpr int kTileCols = 128;      // columns (4 column blocks) of a workgroup tile
 constexpr int kConvTileRows = 128;  // GEMM rows (output pixels) of a conv workgroup tile: one 32-row block per wave (512 measured slower)
 // A tenant-layer with at least kBigMinRows requests and kBigMinCols (padded) outputs is
@@ -85,10 +86,10 @@ struct OutPtrs {
 // Grouped work of one layer index is described by one array per kind (FC, conv):
 // tile_base[t] = number of workgroup tiles of all tenants before t, tile_base[T] = total.
 // A workgroup finds its tenant by searching that array and derives its tile from the rest:
-//   FC:   tiles of a tenant are numbered column-group-major, 128-row tile minor; a column
+//   FC:   tiles of a tenant are numbered column-group-major, 64-row tile minor; a column
 //         group is `split` column blocks of 32 (4, 2 or 1) that the four waves cover side
 //         by side, the remaining factor 4/split splitting K between the waves.
-//   CONV: kTileRows x kTileCols output tiles of the implicit GEMM, column-major likewise.
+//   CONV: kConvTileRows x kTileCols output tiles of the implicit GEMM, column-major likewise.
 struct BatchArgs {
     const Segment* segs; uint32_t n_segs; uint32_t R; uint32_t T; uint32_t n_layer_slots;
     Segment first;         // copy of segs[0]: the common one-segment run never reads host memory

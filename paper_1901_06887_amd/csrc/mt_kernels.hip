@@ -92,15 +92,14 @@ __device__ uint32_t block_exclusive_scan(uint32_t* data, uint32_t n, uint32_t* t
 
 // How an FC layer is cut into workgroup tiles: `split` column blocks side by side per
 // group (the four waves cover them; with split < 4 they also split K), `groups` column
-// groups, and the rows of a tile: 128 normally, 64 for the K-split shapes (layers with at
-// most 64 outputs), whose waves keep their activation bricks in registers.
+// groups, and the rows of a tile (64 for every shape).
 __device__ __forceinline__ void fc_shape(uint32_t n_pad, uint32_t split_k, uint32_t* split, uint32_t* groups, uint32_t* tile_rows)
 {
     const uint32_t nblk = n_pad / kBrickRows;
     uint32_t s = split_k ? 1u : (nblk >= 3 ? 4u : nblk);
     *split = s;
     *groups = ceil_div(nblk, s);
-    *tile_rows = s == 4 ? kTileRows : kTileRows / 2;
+    *tile_rows = kTileRows;
 }
 
 constexpr uint32_t kLists = kListKinds * MT_MAX_LAYERS;   // FC, conv and big-FC tile-count arrays of every layer index
@@ -185,7 +184,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
                     uint32_t split, groups, trows;
                     fc_shape(np[l], a.fc_split_k, &split, &groups, &trows);
                     grp[slot][l] = groups;
-                    rpr[slot][l] = kTileRows / trows;            // 64-row tiles count as two per 128 rows
+                    rpr[slot][l] = kTileRows / trows;            // 1: every FC shape uses kTileRows rows
                     npad[slot][l] = np[l];
                 } else if (kind[l] == MT_CONV2D) {
                     grp[slot][l] = ceil_div(n[l], kTileCols);
@@ -360,7 +359,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             const uint32_t g = grp[slot][l], rr = rpr[slot][l], np = npad[slot][l];
             const bool conv = rr >> 31;
             const bool big = !conv && ((big_layers >> l) & 1) && fc_is_big(Mt, np);
-            // conv: rows = requests * output pixels per tile; FC: rr = 1 (128-row tiles) or 2 (64-row tiles)
+            // conv: rows = requests * output pixels per tile; FC: rr = 1
             const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
             wave_scan(l, (conv || big) ? 0 : tiles);
             wave_scan(MT_MAX_LAYERS + l, conv ? tiles : 0);
@@ -528,7 +527,7 @@ struct Tile {
 
 // XCD-aware numbering: consecutive block indices go to different XCDs (each with its own L2),
 // so the logical tile index is chosen such that every XCD gets one contiguous run of tiles;
-// tiles that re-read the same weight panel (the 128-row tiles of one column group) then
+// tiles that re-read the same weight panel (the row tiles of one column group) then
 // share an L2.  Returns false for blocks past the end of the list.
 __device__ __forceinline__ bool logical_tile(uint32_t n_tiles, uint32_t* logical)
 {
@@ -558,7 +557,7 @@ __device__ __forceinline__ uint32_t find_tenant(const uint32_t* base, uint32_t T
 }
 
 // ---- grouped FC ------------------------------------------------------------------------------
-// A workgroup of four waves owns up to 128 rows (RB row blocks of 32) of one tenant and
+// A workgroup of four waves owns up to 64 rows (RB row blocks of 32) of one tenant and
 // `split` column blocks of 32.  Weight bricks never touch LDS: every wave streams the bricks
 // of its own column block straight from memory into MFMA B operands through a ring of
 // registers that keeps P bricks in flight.
@@ -586,8 +585,8 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
                                                      uint32_t nb, bool active, uint8_t* stages, f32x16 (&acc)[RB])
 {
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
-    constexpr uint32_t KC = kChunkBricks / RB;               // k steps per chunk: 16, 8, 4
-    constexpr uint32_t P = RB == 1 ? 16 : 8;                 // weight bricks in flight per wave
+    constexpr uint32_t KC = kChunkBricks / RB;               // k steps per chunk: 16 or 8
+    constexpr uint32_t P = 16;                               // weight bricks in flight per wave
     constexpr uint32_t U = P > KC ? P : KC;                  // unrolled block of k steps
     static_assert(U == P && U % KC == 0, "the tail relies on U == P");
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -899,12 +898,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
     if (a.gather) {
         if (nrb <= 1) fc_tile<T, 1, 8, true>(a, tl, L, Mt, smem);
-        else if (nrb == 2) fc_tile<T, 2, 4, true>(a, tl, L, Mt, smem);
-        else fc_tile<T, 4, 2, true>(a, tl, L, Mt, smem);
+        else fc_tile<T, 2, 4, true>(a, tl, L, Mt, smem);
     } else {
         if (nrb <= 1) fc_tile<T, 1, 8, false>(a, tl, L, Mt, smem);
-        else if (nrb == 2) fc_tile<T, 2, 4, false>(a, tl, L, Mt, smem);
-        else fc_tile<T, 4, 2, false>(a, tl, L, Mt, smem);   // 3 or 4 row blocks: split == 4 tiles only
+        else fc_tile<T, 2, 4, false>(a, tl, L, Mt, smem);
     }
 }
 

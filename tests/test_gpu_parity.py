@@ -1,5 +1,5 @@
 """GPU parity: the HIP path behind the C ABI against the fp64 oracle, element by element on
-the same seeded inputs.  Reduced cases span several 128x128 tiles and ragged tails; the
+the same seeded inputs.  Reduced cases span several workgroup tiles and ragged tails; the
 full-size cases run in the launch configuration the benchmark times and are checked on
 rows the oracle evaluates one by one (all rows where that takes seconds)."""
 import numpy as np
