@@ -214,7 +214,8 @@ uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R)
     if (c->max_nt[kind][l] == 0) return 0;
     if (kind == 2)      // big FC tiles: only tenants with >= kBigMinRows rows; sum ceil(M_t/256) <= R/256 + R/kBigMinRows
         return R < (uint64_t)kBigMinBatch ? 0 : (uint64_t)c->max_nt[2][l] * (R / kBigTile + R / kBigMinRows);
-    const uint64_t tile_rows = kind == 0 ? kTileRows : kConvTileRows;
+    // FC tiles may be as short as 32 rows (layers with at most 64 outputs)
+    const uint64_t tile_rows = kind == 0 ? kTileRows / 2 : kConvTileRows;
     return (uint64_t)c->max_nt[kind][l] * (R * c->max_rpr[kind][l] / tile_rows) + c->sum_nt[kind][l];
 }
 

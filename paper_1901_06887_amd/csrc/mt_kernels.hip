@@ -92,14 +92,16 @@ __device__ uint32_t block_exclusive_scan(uint32_t* data, uint32_t n, uint32_t* t
 
 // How an FC layer is cut into workgroup tiles: `split` column blocks side by side per
 // group (the four waves cover them; with split < 4 they also split K), `groups` column
-// groups, and the rows of a tile (64 for every shape).
+// groups, and the rows of a tile: 64 normally, 32 for the K-split shapes (layers with at
+// most 64 outputs): their tiles are short-lived and latency bound, so more and smaller ones
+// finish sooner.
 __device__ __forceinline__ void fc_shape(uint32_t n_pad, uint32_t split_k, uint32_t* split, uint32_t* groups, uint32_t* tile_rows)
 {
     const uint32_t nblk = n_pad / kBrickRows;
     uint32_t s = split_k ? 1u : (nblk >= 3 ? 4u : nblk);
     *split = s;
     *groups = ceil_div(nblk, s);
-    *tile_rows = kTileRows;
+    *tile_rows = s == 4 ? kTileRows : kTileRows / 2;
 }
 
 constexpr uint32_t kLists = kListKinds * MT_MAX_LAYERS;   // FC, conv and big-FC tile-count arrays of every layer index
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
                     uint32_t split, groups, trows;
                     fc_shape(np[l], a.fc_split_k, &split, &groups, &trows);
                     grp[slot][l] = groups;
-                    rpr[slot][l] = kTileRows / trows;            // 1: every FC shape uses kTileRows rows
+                    rpr[slot][l] = kTileRows / trows;            // 32-row tiles count as two per 64 rows
                     npad[slot][l] = np[l];
                 } else if (kind[l] == MT_CONV2D) {
                     grp[slot][l] = ceil_div(n[l], kTileCols);
@@ -359,7 +361,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             const uint32_t g = grp[slot][l], rr = rpr[slot][l], np = npad[slot][l];
             const bool conv = rr >> 31;
             const bool big = !conv && ((big_layers >> l) & 1) && fc_is_big(Mt, np);
-            // conv: rows = requests * output pixels per tile; FC: rr = 1
+            // conv: rows = requests * output pixels per tile; FC: rr = 1 (64-row tiles) or 2 (32-row tiles)
             const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
             wave_scan(l, (conv || big) ? 0 : tiles);
             wave_scan(MT_MAX_LAYERS + l, conv ? tiles : 0);
