@@ -480,18 +480,23 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a)
 
 // ---- shared pieces of the GEMM kernels -----------------------------------------------------
 // GELU(x) = x * Phi(x) with the exact (erf) definition, evaluated through the complementary
-// error function of |x|/sqrt(2) (Abramowitz & Stegun 7.1.26: a degree-5 polynomial in
-// 1/(1+p z) times exp(-z^2), absolute error below 1.5e-7).  Phi is formed from erfc on the
-// negative side, so the small negative tail keeps its relative accuracy; the error is far
-// below half a bfloat16 ulp of the result, and a library erf costs four times as much, which
-// showed in the epilogue of the compute-bound tiles.
+// error function of z = |x|/sqrt(2) (Abramowitz & Stegun 7.1.26: a degree-5 polynomial in
+// t = 1/(1 + p z) times exp(-z^2), absolute error below 1.5e-7).  With h = erfc(z)/2, Phi is
+// 1 - h on the positive side and h on the negative one, so x Phi(x) = max(x, 0) - |x| h on both
+// (the small negative tail keeps its relative accuracy).  z is carried pre-scaled by
+// sqrt(log2 e) so that exp(-z^2) is one multiply and one exp2; the 1/2 sits in the polynomial's
+// coefficients.  The error is far below half a bfloat16 ulp of the result, and a library erf
+// costs four times as much, which showed in the epilogue of the compute-bound tiles.
 __device__ __forceinline__ float gelu(float x)
 {
-    const float z = fabsf(x) * 0.70710678118654752f;
-    const float t = __frcp_rn(1.0f + 0.3275911f * z);
-    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-    const float half_erfc = 0.5f * poly * __expf(-z * z);
-    return x * (x >= 0.0f ? 1.0f - half_erfc : half_erfc);
+    constexpr float kScale = 0.84932180028801904f;           // sqrt(log2(e) / 2): zs = z * sqrt(log2 e)
+    constexpr float kP = 0.3275911f / 1.2011224087864498f;   // p / sqrt(log2 e)
+    const float ax = fabsf(x);
+    const float zs = ax * kScale;
+    const float t = __frcp_rn(fmaf(kP, zs, 1.0f));
+    const float poly = t * (0.127414796f + t * (-0.142248368f + t * (0.7107068705f + t * (-0.7265760135f + t * 0.5307027145f))));
+    const float h = poly * __builtin_amdgcn_exp2f(-zs * zs);
+    return fmaf(-ax, h, fmaxf(x, 0.0f));
 }
 
 __device__ __forceinline__ float activate(float z, uint32_t act)
@@ -499,6 +504,23 @@ __device__ __forceinline__ float activate(float z, uint32_t act)
     if (act == MT_ACT_RELU) return fmaxf(z, 0.0f);
     if (act == MT_ACT_GELU) return gelu(z);
     return z;
+}
+
+// The same on a block of values, with the choice made once, outside the loops.
+template <int G>
+__device__ __forceinline__ void activate_block(f32x4 (&y)[G], uint32_t act)
+{
+    if (act == MT_ACT_GELU) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[g][e] = gelu(y[g][e]);
+    } else if (act == MT_ACT_RELU) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[g][e] = fmaxf(y[g][e], 0.0f);
+    }
 }
 
 template <typename T> struct Mma;
@@ -886,8 +908,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     if (!logical_tile(n_tiles, &idx)) return;
     __syncthreads();
     Tile tl;
-    tl.tenant = find_tenant(base_l, a.T, idx);
-    const uint32_t local = idx - base_l[tl.tenant];
+    tl.tenant = __builtin_amdgcn_readfirstlane(find_tenant(base_l, a.T, idx));   // uniform: the tenant's facts come through scalar loads
+    const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[tl.tenant]);
     __syncthreads();                                          // the lookup is over before anything reuses smem
     const LayerDev L = a.layers[tl.tenant * MT_MAX_LAYERS + a.layer];
     const uint32_t Mt = a.M[tl.tenant];
@@ -922,36 +944,6 @@ constexpr uint32_t kBigBlocks = kBigTile / kBrickRows;                          
 constexpr uint32_t kBigStageBytes = 2 * kBigBlocks * kBigKS * kBrickBytes;        // 32 KiB
 constexpr uint32_t kBigGroup = 4;                                                 // row tiles that sweep the columns together
 
-// One 32x32 accumulator block of the big-tile kernel -> logits rows.
-__device__ __forceinline__ void big_logits_block(const f32x16& v, float bv, float* p, uint32_t C_pad, uint32_t rows_left, uint32_t lh)
-{
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        const uint32_t r = 8 * (e >> 2) + 4 * lh + (e & 3);
-        if (r < rows_left) p[(size_t)r * C_pad] = v[e] + bv;
-    }
-}
-
-// One 32x32 accumulator block -> bias, activation, rounding, transposition through the wave's
-// LDS scratch, whole-brick stores (`out` points at this lane's 16 bytes of the first brick).
-template <typename T>
-__device__ __forceinline__ void big_hidden_block(const f32x16& v, float bv, bool col_ok, uint32_t act, uint8_t* trw, u32x4* out,
-                                                 uint32_t li, uint32_t lh)
-{
-    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC, TRS = 32 * sizeof(T) + 16;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        const uint32_t ml = 8 * (e >> 2) + 4 * lh + (e & 3);
-        const float y = col_ok ? activate(v[e] + bv, act) : 0.0f;
-        *(T*)(trw + ml * TRS + li * sizeof(T)) = (T)y;
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // the wave's own LDS writes have landed
-#pragma unroll
-    for (uint32_t c = 0; c < kBrickRows / KB; ++c)
-        out[c * 64] = *(const u32x4*)(trw + li * TRS + (c * KB + lh * EPC) * sizeof(T));
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // reads done before the next block overwrites the scratch
-}
-
 // WV waves per workgroup: 8 (2x4, 128x64 per wave) or 4 (2x2, 128x128 per wave, one wave per SIMD
 // with its accumulators in the second half of the 512-entry register file).
 template <typename T, int WV>
@@ -963,7 +955,7 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     constexpr uint32_t LPS = BPW * kBigKS;                   // loads a wave issues per stage
     __shared__ __attribute__((aligned(16))) uint8_t stages[kBigNS * kBigStageBytes];
     uint8_t* const stage0 = stages;
-    static_assert(kBigNS * kBigStageBytes >= 8 * kTrBytes && kBigStageBytes >= (kMaxTenantsPadded + 1) * 4, "scratch aliases the stages");
+    static_assert(kBigStageBytes >= (kMaxTenantsPadded + 1) * 4, "tile_base must fit the first stage");
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t li = lane & 31, lh = lane >> 5;
@@ -1041,7 +1033,7 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
 #pragma unroll
         for (int i = i0; i < i1; ++i)
 #pragma unroll
-            for (int j = 0; j < (int)CJ; ++j) Mma<T>::run(acc[i][j], a4[i], b2[j]);
+            for (int j = 0; j < (int)CJ; ++j) Mma<T>::run(acc[i][j], b2[j], a4[i]);   // weights as the row operand: see the epilogue
     };
     auto mma_all = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[CJ]) { mma_rows(a4, b2, 0, 4); };
     static_assert(kBigKS == 2, "the loop below is written for two k steps per stage");
@@ -1102,26 +1094,61 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // trailing repeats landed, all reads done
 
-    // epilogue; the stages are free now, each wave transposes through its own scratch.  The
-    // blocks of a wave are spelled out one by one (constant accumulator indices) with a scheduling
-    // fence after each, which keeps the register need of the epilogue at one block.
+    // epilogue.  The MFMAs took the weight bricks as their row operand, so a lane holds, for
+    // activation row li of each block, outputs n = 8g + 4 lh + {0..3} (g = 0..3): runs of four
+    // consecutive outputs of ITS row.  fp32: a run is a lane's 16 bytes of an output brick.
+    // bf16: two lanes (lh = 0, 1) hold the halves of every 8-output run; one exchange between
+    // the wave's halves per dword (v_permlane32_swap) leaves lanes lh = 0 with runs 0 and 2 and
+    // lanes lh = 1 with runs 1 and 3, again a lane's 16 bytes of an output brick.  No LDS.  The
+    // blocks are walked with a scheduling fence after each, which keeps the register need of the
+    // epilogue at one block.
     const float* bias = (const float*)(a.arena + L.b_off);
-    float bvs[CJ];
-#pragma unroll
-    for (int j = 0; j < (int)CJ; ++j) bvs[j] = wn * CJ + j < ncb ? bias[n0 + (wn * CJ + j) * kBrickRows + li] : 0.0f;
-    uint8_t* trw = stage0 + wave * kTrBytes;
     const uint32_t nKB_out = L.out_fill / KB;
     auto block = [&](const f32x16& blk, uint32_t i, uint32_t j) {
         const uint32_t rb = wm * 4 + i;
         if (rb < nrb && wn * CJ + j < ncb) {
-            const uint32_t nb = n0 / kBrickRows + wn * CJ + j, n = nb * kBrickRows + li;
+            const uint32_t nb = n0 / kBrickRows + wn * CJ + j, nl = nb * kBrickRows + 4 * lh;   // first output of this lane's runs
             const uint32_t mb = m0 + rb * kBrickRows;          // first row of the block inside the tenant
+            f32x4 y[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 bq = *(const f32x4*)(bias + nl + 8 * g);                            // bias is padded to N_pad
+#pragma unroll
+                for (int e = 0; e < 4; ++e) y[g][e] = blk[4 * g + e] + bq[e];
+            }
             if (L.is_last) {
-                if (n < L.N) big_logits_block(blk, bvs[j], a.logits + (size_t)(seg0 + mb) * a.C_pad + n, a.C_pad, Mt - mb, lh);
+                if (mb + li < Mt) {
+                    float* row = a.logits + (size_t)(seg0 + mb + li) * a.C_pad;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        if (nl + 8 * g < L.N) *(f32x4*)(row + nl + 8 * g) = y[g];                 // may run into the row's padding (C_pad >= N_pad)
+                }
             } else {
                 u32x4* out = (u32x4*)((T*)a.act_out + (size_t)seg0 * a.S) +
                              ((size_t)(mb / kBrickRows) * nKB_out + nb * (kBrickRows / KB)) * 64 + lane;
-                big_hidden_block<T>(blk, bvs[j], n < L.N, L.act, trw, out, li, lh);
+                // outputs past N need no masking: their weight rows and bias are zero padding, and
+                // every activation of the layer set maps 0 to 0
+                activate_block<4>(y, L.act);
+                if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) out[g * 64] = __builtin_bit_cast(u32x4, y[g]);   // brick g of the block, half lh
+                } else {
+                    uint32_t pk[4][2];                                                          // run halves as two packed dwords
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        T o[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (T)y[g][e];
+                        const uint64_t q = __builtin_bit_cast(uint64_t, o);
+                        pk[g][0] = (uint32_t)q; pk[g][1] = (uint32_t)(q >> 32);
+                    }
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {                                              // runs (0,1) -> brick 0 of the block, (2,3) -> brick 1
+                        const auto s0 = __builtin_amdgcn_permlane32_swap(pk[2 * h][0], pk[2 * h + 1][0], false, false);
+                        const auto s1 = __builtin_amdgcn_permlane32_swap(pk[2 * h][1], pk[2 * h + 1][1], false, false);
+                        out[h * 64] = u32x4{s0[0], s1[0], s0[1], s1[1]};
+                    }
+                }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
