@@ -877,11 +877,14 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
     for (int r = 0; r < RB; ++r) {
         __syncthreads();
         if (writer && (uint32_t)r < nrb) {
+            f32x4 y[4];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) y[v >> 2][v & 3] = acc[r][v] + bv;
+            activate_block<4>(y, L.act);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const uint32_t ml = 8 * (v >> 2) + 4 * lh + (v & 3);
-                const float y = n < L.N ? activate(acc[r][v] + bv, L.act) : 0.0f;
-                *(T*)(trw + ml * TRS + li * sizeof(T)) = (T)y;
+                *(T*)(trw + ml * TRS + li * sizeof(T)) = (T)(n < L.N ? y[v >> 2][v & 3] : 0.0f);
             }
         }
         __syncthreads();
@@ -1255,9 +1258,13 @@ __device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, 
         for (int g = 0; g < 4; ++g) {
             const uint32_t n = (nb0 + c) * kBrickRows + 8 * g + 4 * lh;
             const f32x4 bv = *(const f32x4*)(bias + n);             // bias is padded to N_pad
+            f32x4 y[1];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) y[0][i] = acc[c][4 * g + i] + bv[i];
+            activate_block<1>(y, L.act);
             T r[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) r[i] = (T)activate(acc[c][4 * g + i] + bv[i], L.act);
+            for (int i = 0; i < 4; ++i) r[i] = (T)y[0][i];
             if (n < L.N) {                                          // N is a multiple of 8: a run is in or out as a whole
                 if constexpr (sizeof(T) == 2) *(uint64_t*)(out + n) = __builtin_bit_cast(uint64_t, r);
                 else *(u32x4*)(out + n) = __builtin_bit_cast(u32x4, r);
@@ -1430,9 +1437,13 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const uint32_t n = nbase + 8 * g;
+                f32x4 y[1];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) y[0][i] = acc[r][4 * g + i] + bv[g][i];
+                activate_block<1>(y, L.act);
                 T o[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = (T)activate(acc[r][4 * g + i] + bv[g][i], L.act);
+                for (int i = 0; i < 4; ++i) o[i] = (T)y[0][i];
                 if (n < L.N) {                                      // N is a multiple of 8: a run is in or out as a whole
                     if constexpr (sizeof(T) == 2) *(uint64_t*)(out + n) = __builtin_bit_cast(uint64_t, o);
                     else *(u32x4*)(out + n) = __builtin_bit_cast(u32x4, o);
