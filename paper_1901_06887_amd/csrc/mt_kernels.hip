@@ -1,16 +1,23 @@
 // Device code of the multi-tenant worker runtime, written for gfx950 (CDNA4, wave64).
 //
-//   batcher_kernel  tenant segmentation of the pending requests (counts, 32-aligned offsets,
-//                   stable permutation) and the per-layer grouped-work tile lists, on device
-//   gather_kernel   submitted rows -> tenant-contiguous staged inputs (bricks for FC models,
-//                   channel-padded NHWC rows for CNN models)
-//   fc_kernel       one FC layer index for all tenants: grouped GEMM that streams weight and
-//                   activation bricks straight from memory into MFMA operands, fused bias +
-//                   activation (+ bf16 rounding), brick output or fp32 logits
-//   conv_kernel     one conv layer index for all tenants: implicit-GEMM 3x3 convolution on
-//                   MFMA through LDS, fused bias + activation
-//   gap_kernel      global average pooling, NHWC rows -> bricks
-//   head_kernel     softmax + argmax, written in submission order
+//   batcher_kernel      tenant segmentation of the pending requests (counts, 32-aligned offsets,
+//                       stable permutation) and the per-layer grouped-work tile lists, on device
+//   gather_kernel       submitted rows -> tenant-contiguous bricks (FC models whose layer 0
+//                       cannot read the submitted rows itself)
+//   gather_image_kernel submitted images -> channel-padded NHWC rows (CNN models)
+//   fc_kernel           one FC layer index for all tenants, weight-streaming tiles: weight bricks
+//                       go from memory into MFMA operands through a register ring, activation
+//                       bricks are shared through LDS; fused bias + activation (+ rounding),
+//                       brick output, fp32 logits, or softmax/argmax for at most 32 classes
+//   fc_big_kernel       the same layer index, compute-bound tenant-layers: 256x256 tiles, both
+//                       operands through an LDS ring filled by direct global->LDS loads
+//   conv_kernel         one conv layer index for all tenants, layers at most 32 channels wide:
+//                       implicit-GEMM 3x3 convolution, every wave gathers its own pixels
+//   conv_lds_kernel     wider conv layers: activation bricks gathered once per tile into LDS by
+//                       direct global->LDS loads and shared by waves side by side over channels
+//   gap_kernel          global average pooling, NHWC rows -> bricks
+//   head_kernel         softmax + argmax, written in submission order
+//   copy_kernel         plain copy, the yardstick for byte counters
 //
 // A DNN is a fixed sequence of layers applied in turn (paper, section 1.1); a worker
 // hosts many tenants' DNNs and multiplexes their requests (section 3).  The grouping
