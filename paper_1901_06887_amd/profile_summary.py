@@ -22,11 +22,15 @@ KERNEL_SOURCES = ("csrc/mt_kernels.hip", "csrc/mt_internal.h")
 
 
 def kernel_source_sha256() -> str:
-    """Fingerprint of the device code: counters taken before a change to it no longer apply."""
+    """Fingerprint of the device code: counters taken before a change to it no longer apply.
+    Comments and white space are left out, so that editing a comment does not void a measurement."""
     h = hashlib.sha256()
     for rel in KERNEL_SOURCES:
-        with open(os.path.join(HERE, rel), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(HERE, rel), "r") as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)     # block comments
+        text = re.sub(r"//[^\n]*", " ", text)                  # line comments (the sources hold no string with //)
+        h.update(" ".join(text.split()).encode())
     return h.hexdigest()
 
 
