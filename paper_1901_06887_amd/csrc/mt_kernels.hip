@@ -976,8 +976,8 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     uint32_t idx;
     if (!logical_tile_chunked(n_tiles, &idx)) return;
     __syncthreads();
-    const uint32_t t = find_tenant(base_l, a.T, idx);
-    const uint32_t local = idx - base_l[t];
+    const uint32_t t = __builtin_amdgcn_readfirstlane(find_tenant(base_l, a.T, idx));   // uniform: the tenant's facts come through scalar loads
+    const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[t]);
     __syncthreads();
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     const uint32_t Mt = a.M[t], seg0 = a.off[t];
@@ -1169,6 +1169,46 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
         for (int j = 0; j < (int)CJ; ++j) block(acc[i][j], i, j);
 }
 
+// ---- NHWC store of one 32-pixel x 32-channel unit held in the transposed accumulator layout ----
+// After an MFMA with the filter brick as row operand, lane (li, lh) holds channels 8g + 4 lh +
+// {0..3} of pixel li: stored from there, a wave instruction writes 64 separate 8- or 16-byte
+// pieces, and the texture path counts (and takes time for) every one of them; the counters
+// showed the convolution kernels bound by exactly that rate.  So the unit goes through a
+// wave-private LDS scratch as [pixel][channel] rows and is read back so that consecutive
+// lanes hold consecutive 16-byte chunks of a pixel's row: a pixel's 64 (bf16) or 128 (fp32)
+// bytes leave in one piece.  Each pixel's destination travels through the scratch as well
+// (null for pixels past the end), so the storing lane needs no index arithmetic.
+template <typename T> constexpr uint32_t unit_row_stride() { return kBrickRows * sizeof(T) + 16; }
+template <typename T> constexpr uint32_t unit_scratch_bytes() { return kBrickRows * unit_row_stride<T>() + kBrickRows * 8; }
+
+template <typename T>
+__device__ __forceinline__ void store_unit_nhwc(const f32x4 (&y)[4], T* my_pixel_out, uint32_t n_valid, uint8_t* scratch)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), RS = unit_row_stride<T>();
+    constexpr uint32_t CP = kBrickRows / EPC;                       // 16-byte chunks per pixel row: 4 (bf16) or 8 (fp32)
+    const uint32_t lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
+    T** dests = (T**)(scratch + kBrickRows * RS);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        T o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (T)y[g][e];
+        uint8_t* p = scratch + li * RS + (8 * g + 4 * lh) * sizeof(T);
+        if constexpr (sizeof(T) == 2) *(uint64_t*)p = __builtin_bit_cast(uint64_t, o);
+        else *(u32x4*)p = __builtin_bit_cast(u32x4, o);
+    }
+    if (lh == 0) dests[li] = my_pixel_out;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // the wave's own LDS writes have landed
+#pragma unroll
+    for (uint32_t pass = 0; pass < CP / 2; ++pass) {
+        const uint32_t px = pass * (64 / CP) + lane / CP, ch = lane % CP;
+        T* dst = dests[px];
+        const u32x4 v = *(const u32x4*)(scratch + px * RS + ch * 16);
+        if (dst != nullptr && ch * EPC < n_valid) *(u32x4*)(dst + ch * EPC) = v;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // reads done before the next unit overwrites the scratch
+}
+
 // ---- grouped 3x3 convolution as implicit GEMM ---------------------------------------------
 // GEMM view: rows = (request, output pixel), columns = output channels, K = (kh, kw, c_in).
 // A workgroup takes 128 consecutive rows of one tenant and up to 128 output channels; each of
@@ -1181,7 +1221,7 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
 // ITS pixel and stores them straight to the NHWC output: no LDS, no barrier, and the pixel's
 // address is the one the lane already derived for its loads.
 template <typename T, int CB>
-__device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, uint32_t seg0, uint32_t m0, uint32_t rows_total, uint32_t nb0)
+__device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, uint32_t seg0, uint32_t m0, uint32_t rows_total, uint32_t nb0, uint8_t* scratch)
 {
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC, P = 4;
     typedef const __attribute__((address_space(1))) u32x4* gptr_t;
@@ -1255,28 +1295,22 @@ __device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, 
     }
 
     // epilogue: the lane holds, for pixel li, channels 8g + 4 lh + {0..3} (g = 0..3) of every
-    // channel block: bias, activation, rounding, and one store of four channels per run
-    if (!row_ok) return;
+    // channel block: bias, activation, rounding, coalesced store through the wave's scratch
     const float* bias = (const float*)(a.arena + L.b_off);
-    T* out = (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N;
+    T* out = row_ok ? (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N : nullptr;
 #pragma unroll
     for (int c = 0; c < CB; ++c) {
+        const uint32_t nbase = (nb0 + c) * kBrickRows;
+        f32x4 y[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const uint32_t n = (nb0 + c) * kBrickRows + 8 * g + 4 * lh;
-            const f32x4 bv = *(const f32x4*)(bias + n);             // bias is padded to N_pad
-            f32x4 y[1];
+            const f32x4 bv = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);   // bias is padded to N_pad
 #pragma unroll
-            for (int i = 0; i < 4; ++i) y[0][i] = acc[c][4 * g + i] + bv[i];
-            activate_block<1>(y, L.act);
-            T r[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) r[i] = (T)y[0][i];
-            if (n < L.N) {                                          // N is a multiple of 8: a run is in or out as a whole
-                if constexpr (sizeof(T) == 2) *(uint64_t*)(out + n) = __builtin_bit_cast(uint64_t, r);
-                else *(u32x4*)(out + n) = __builtin_bit_cast(u32x4, r);
-            }
+            for (int i = 0; i < 4; ++i) y[g][i] = acc[c][4 * g + i] + bv[i];
         }
+        activate_block<4>(y, L.act);
+        // N is a multiple of 8, so the channels of this block that exist are whole 16-byte chunks for bf16 and pairs of them for fp32
+        store_unit_nhwc<T>(y, out ? out + nbase : nullptr, min((uint32_t)kBrickRows, L.N - nbase), scratch);
     }
 }
 
@@ -1286,14 +1320,16 @@ template <typename T, int MAXCB>
 __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
 {
     __shared__ uint32_t base_l[kMaxTenantsPadded + 1];
+    __shared__ __attribute__((aligned(16))) uint8_t unit_scratch[4 * unit_scratch_bytes<T>()];
     const uint32_t tid = threadIdx.x, wave = tid >> 6;
+    uint8_t* scratch = unit_scratch + wave * unit_scratch_bytes<T>();
     const uint32_t n_tiles = a.tile_base[a.T];
     for (uint32_t i = tid; i <= a.T; i += 256) base_l[i] = a.tile_base[i];
     uint32_t idx;
     if (!logical_tile(n_tiles, &idx)) return;
     __syncthreads();
-    const uint32_t t = find_tenant(base_l, a.T, idx);
-    const uint32_t local = idx - base_l[t];
+    const uint32_t t = __builtin_amdgcn_readfirstlane(find_tenant(base_l, a.T, idx));   // uniform: the tenant's facts come through scalar loads
+    const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[t]);
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     const uint32_t seg0 = a.off[t];
     const uint32_t rows_total = a.M[t] * L.rows_per_req, mt_ = ceil_div(rows_total, kConvTileRows);
@@ -1304,15 +1340,15 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
         const uint32_t m0 = (local % mt_) * kConvTileRows + rb * kBrickRows;
         if (m0 >= rows_total) break;
         if constexpr (MAXCB == 1) {
-            conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0);
+            conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0, scratch);
         } else if constexpr (MAXCB == 2) {
-            if (ncb == 1) conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0);
-            else conv_wave<T, 2>(a, L, seg0, m0, rows_total, nb0);
+            if (ncb == 1) conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0, scratch);
+            else conv_wave<T, 2>(a, L, seg0, m0, rows_total, nb0, scratch);
         } else {
-            if (ncb == 1) conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0);
-            else if (ncb == 2) conv_wave<T, 2>(a, L, seg0, m0, rows_total, nb0);
-            else if (ncb == 3) conv_wave<T, 3>(a, L, seg0, m0, rows_total, nb0);
-            else conv_wave<T, 4>(a, L, seg0, m0, rows_total, nb0);
+            if (ncb == 1) conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0, scratch);
+            else if (ncb == 2) conv_wave<T, 2>(a, L, seg0, m0, rows_total, nb0, scratch);
+            else if (ncb == 3) conv_wave<T, 3>(a, L, seg0, m0, rows_total, nb0, scratch);
+            else conv_wave<T, 4>(a, L, seg0, m0, rows_total, nb0, scratch);
         }
     }
 }
@@ -1347,8 +1383,8 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
     uint32_t idx;
     if (!logical_tile(n_tiles, &idx)) return;
     __syncthreads();
-    const uint32_t t = find_tenant(base_l, a.T, idx);
-    const uint32_t local = idx - base_l[t];
+    const uint32_t t = __builtin_amdgcn_readfirstlane(find_tenant(base_l, a.T, idx));   // uniform: the tenant's facts come through scalar loads
+    const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[t]);
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     const uint32_t seg0 = a.off[t];
     const uint32_t rpr = L.rows_per_req, cin = L.cin;
@@ -1426,37 +1462,34 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // this wave's LDS reads of the chunk are done before its next barrier
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");               // trailing loads have landed before the workgroup's LDS is released
+    // trailing loads have landed and every wave is done with the ring: its memory now serves as
+    // the waves' store scratch
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    static_assert(kConvNS * kConvStageBytes >= 4 * unit_scratch_bytes<T>(), "store scratch aliases the ring");
 
     // epilogue: lane holds, for pixel li of each of its pixel blocks, channels 8g + 4 lh + {0..3}
     if (!active) return;
+    uint8_t* scratch = lds + wave * unit_scratch_bytes<T>();
     const float* bias = (const float*)(a.arena + L.b_off);
-    const uint32_t nbase = (nb0 + wc) * kBrickRows + 4 * lh;
-    f32x4 bv[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) bv[g] = *(const f32x4*)(bias + nbase + 8 * g);   // bias is padded to N_pad
+    const uint32_t nbase = (nb0 + wc) * kBrickRows;
 #pragma unroll
     for (uint32_t r = 0; r < RBW; ++r) {
         const uint32_t m = m0 + (wr * RBW + r) * kBrickRows + li;
+        T* out = nullptr;
         if (m < rows_total) {
             const uint32_t req = m / rpr, pix = m % rpr;
-            T* out = (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const uint32_t n = nbase + 8 * g;
-                f32x4 y[1];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) y[0][i] = acc[r][4 * g + i] + bv[g][i];
-                activate_block<1>(y, L.act);
-                T o[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = (T)y[0][i];
-                if (n < L.N) {                                      // N is a multiple of 8: a run is in or out as a whole
-                    if constexpr (sizeof(T) == 2) *(uint64_t*)(out + n) = __builtin_bit_cast(uint64_t, o);
-                    else *(u32x4*)(out + n) = __builtin_bit_cast(u32x4, o);
-                }
-            }
+            out = (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N + nbase;
         }
+        f32x4 y[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 bv = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);   // bias is padded to N_pad; re-read per block (L1) to keep registers free
+#pragma unroll
+            for (int i = 0; i < 4; ++i) y[g][i] = acc[r][4 * g + i] + bv[i];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        activate_block<4>(y, L.act);
+        store_unit_nhwc<T>(y, out, min((uint32_t)kBrickRows, L.N - nbase), scratch);
     }
 }
 
