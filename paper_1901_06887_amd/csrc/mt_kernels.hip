@@ -1169,6 +1169,47 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
         for (int j = 0; j < (int)CJ; ++j) block(acc[i][j], i, j);
 }
 
+// ---- helpers of the implicit-GEMM convolutions ---------------------------------------------
+// Quotient and remainder by a wave-uniform divisor; image sizes are mostly powers of two, and a
+// general 32-bit division costs some thirty vector instructions per lane.
+__device__ __forceinline__ void divmod_uniform(uint32_t x, uint32_t d, uint32_t* q, uint32_t* r)
+{
+    if ((d & (d - 1)) == 0) { *q = x >> __builtin_ctz(d); *r = x & (d - 1); }
+    else { *q = x / d; *r = x - *q * d; }
+}
+
+// A lane's walk through K = (kernel row, kernel column, channel), one k step at a time.  Inside
+// a kernel row the three taps of a pixel are one contiguous run of 3 * cin input elements, so the
+// position is kept as (kernel row th, offset lin inside the run) and the element offset `cur`
+// moves by KB per step plus a jump at the end of a run.  Validity is two range tests: the
+// left/right tap falls outside the image only at the image's left/right edge, the top/bottom
+// kernel row only at its top/bottom edge.  Steps past the last tap have th == 3: invalid.
+template <typename T>
+struct TapWalk {
+    static constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    uint32_t lin, th, run, lo, hi, tlo, thi;
+    int32_t cur, jump;
+    __device__ __forceinline__ void init(const LayerDev& L, int32_t ih0, int32_t iw0, bool row_ok, uint32_t lh)
+    {
+        const int32_t cin = (int32_t)L.cin;
+        run = 3 * L.cin; lin = lh * EPC; th = 0;
+        lo = iw0 < 0 ? L.cin : 0; hi = iw0 + 2 >= (int32_t)L.in_w ? 2 * L.cin : 3 * L.cin;
+        tlo = ih0 < 0 ? 1 : 0; thi = row_ok ? (ih0 + 2 >= (int32_t)L.in_h ? 2 : 3) : 0;
+        cur = (ih0 * (int32_t)L.in_w + iw0) * cin + (int32_t)lin;
+        jump = ((int32_t)L.in_w - 3) * cin;
+    }
+    // the 16-byte chunk of this k step inside the image, or -1 when the step reads zeros; moves on
+    __device__ __forceinline__ int32_t next()
+    {
+        const bool ok = (lin >= lo) & (lin < hi) & (th >= tlo) & (th < thi);
+        const int32_t chunk = ok ? (int32_t)((uint32_t)cur / EPC) : -1;
+        lin += KB; cur += (int32_t)KB;
+        const bool wrap = lin >= run;                               // at most once per step: KB <= 16 < 3 * cin
+        lin = wrap ? lin - run : lin; th += wrap ? 1u : 0u; cur = wrap ? cur + jump : cur;
+        return chunk;
+    }
+};
+
 // ---- NHWC store of one 32-pixel x 32-channel unit held in the transposed accumulator layout ----
 // After an MFMA with the filter brick as row operand, lane (li, lh) holds channels 8g + 4 lh +
 // {0..3} of pixel li: stored from there, a wave instruction writes 64 separate 8- or 16-byte
@@ -1218,8 +1259,8 @@ __device__ __forceinline__ void store_unit_nhwc(const f32x4 (&y)[4], T* my_pixel
 // zeros), the filter bricks come from L1/L2 (a layer's filters are at most ~150 KB and shared
 // by every tile of the tenant).  The MFMA takes the filter brick as its row operand and the
 // pixels as its column operand, so a lane ends up with runs of four consecutive channels of
-// ITS pixel and stores them straight to the NHWC output: no LDS, no barrier, and the pixel's
-// address is the one the lane already derived for its loads.
+// ITS pixel, whose address it already derived for its loads; the unit then leaves through the
+// wave's store scratch (store_unit_nhwc).  No barrier anywhere.
 template <typename T, int CB>
 __device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, uint32_t seg0, uint32_t m0, uint32_t rows_total, uint32_t nb0, uint8_t* scratch)
 {
@@ -1227,33 +1268,28 @@ __device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, 
     typedef const __attribute__((address_space(1))) u32x4* gptr_t;
     const uint32_t lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
     const uint32_t nKB = L.K / KB, nKBv = ceil_div(L.k_valid, KB);  // bricks per filter row; k steps that hold real taps
-    const uint32_t rpr = L.rows_per_req, cin = L.cin;
+    const uint32_t rpr = L.rows_per_req;
 
     // this lane's GEMM row: request, output pixel, top-left input coordinate
     const uint32_t m = m0 + li;
     const bool row_ok = m < rows_total;
     const uint32_t mm = row_ok ? m : m0;                           // rows past the end repeat the first one and are dropped
-    const uint32_t req = mm / rpr, pix = mm % rpr;
-    const int32_t ih0 = (int32_t)((pix / L.out_w) * L.stride) - 1, iw0 = (int32_t)((pix % L.out_w) * L.stride) - 1;
+    uint32_t req, pix, oh, ow;
+    divmod_uniform(mm, rpr, &req, &pix);
+    divmod_uniform(pix, L.out_w, &oh, &ow);
+    const int32_t ih0 = (int32_t)(oh * L.stride) - 1, iw0 = (int32_t)(ow * L.stride) - 1;
     gptr_t img = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
     gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)nb0 * nKB * 64 + lane);
 
-    // The lane's position in K, kept incrementally: tap (th, tw) and channel c0 inside it.  A
-    // k step moves KB channels on, which crosses at most two taps because cin >= 8.
-    uint32_t c0 = lh * EPC;
-    int32_t th = 0, tw = 0;
-    auto wrap = [&]() { if (c0 >= cin) { c0 -= cin; if (++tw == 3) { tw = 0; ++th; } } };
-    wrap(); wrap();
     // The next k step's chunk.  Taps outside the image, steps past the last tap and rows past the
     // end read a block of zeros instead: the choice is made on the address, so nothing waits on
     // the loaded value before its MFMA.
     gptr_t zeros = (gptr_t)a.zeros;
+    TapWalk<T> walk;
+    walk.init(L, ih0, iw0, row_ok, lh);
     auto load_a = [&]() -> u32x4 {
-        const int32_t ih = ih0 + th, iw = iw0 + tw;
-        const bool ok = row_ok & (th < 3) & (ih >= 0) & (ih < (int32_t)L.in_h) & (iw >= 0) & (iw < (int32_t)L.in_w);
-        const uint32_t off = ((uint32_t)(ih * (int32_t)L.in_w + iw) * cin + c0) / EPC;
-        gptr_t p = ok ? img + off : zeros;
-        c0 += KB; wrap(); wrap();
+        const int32_t chunk = walk.next();
+        gptr_t p = chunk >= 0 ? img + chunk : zeros;
         return *p;
     };
 
@@ -1387,7 +1423,7 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
     const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[t]);
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     const uint32_t seg0 = a.off[t];
-    const uint32_t rpr = L.rows_per_req, cin = L.cin;
+    const uint32_t rpr = L.rows_per_req;
     const uint32_t rows_total = a.M[t] * rpr, mt_ = ceil_div(rows_total, kConvTileRows);
     const uint32_t m0 = (local % mt_) * kConvTileRows;
     const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
@@ -1405,16 +1441,16 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
     int32_t ih0 = 0, iw0 = 0;
     {
         const uint32_t mm = row_ok ? gm : m0;
-        const uint32_t req = mm / rpr, pix = mm % rpr;
-        ih0 = (int32_t)((pix / L.out_w) * L.stride) - 1; iw0 = (int32_t)((pix % L.out_w) * L.stride) - 1;
+        uint32_t req, pix, oh, ow;
+        divmod_uniform(mm, rpr, &req, &pix);
+        divmod_uniform(pix, L.out_w, &oh, &ow);
+        ih0 = (int32_t)(oh * L.stride) - 1; iw0 = (int32_t)(ow * L.stride) - 1;
         img = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
     }
     gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
     const uint32_t last_kb = n_chunks * kConvKC - 1;
-    uint32_t c0 = lh * EPC;
-    int32_t th = 0, tw = 0;
-    auto wrap = [&]() { if (c0 >= cin) { c0 -= cin; if (++tw == 3) { tw = 0; ++th; } } };
-    wrap(); wrap();
+    TapWalk<T> walk;
+    walk.init(L, ih0, iw0, row_ok, lh);
     // The next kConvKC k steps of this wave's pixel block and of its filter block: 2 * kConvKC
     // loads.  Chunks past the end gather zeros (th >= 3) and repeat the last filter bricks, which
     // keeps the number of loads per round, and with it the wait below, uniform.
@@ -1422,13 +1458,10 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
         uint8_t* dst = lds + (c % kConvNS) * kConvStageBytes;
 #pragma unroll
         for (uint32_t kk = 0; kk < kConvKC; ++kk) {
-            const int32_t ih = ih0 + th, iw = iw0 + tw;
-            const bool ok = row_ok & (th < 3) & (ih >= 0) & (ih < (int32_t)L.in_h) & (iw >= 0) & (iw < (int32_t)L.in_w);
-            const uint32_t off = ((uint32_t)(ih * (int32_t)L.in_w + iw) * cin + c0) / EPC;
-            gptr_t p = ok ? img + off : zeros;
+            const int32_t chunk = walk.next();
+            gptr_t p = chunk >= 0 ? img + chunk : zeros;
             lds_dma16(p, dst + (wave * kConvKC + kk) * kBrickBytes);
             lds_dma16(wp + (size_t)min(c * kConvKC + kk, last_kb) * 64, dst + ((4 + wave) * kConvKC + kk) * kBrickBytes);
-            c0 += KB; wrap(); wrap();
         }
     };
 
@@ -1477,7 +1510,8 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
         const uint32_t m = m0 + (wr * RBW + r) * kBrickRows + li;
         T* out = nullptr;
         if (m < rows_total) {
-            const uint32_t req = m / rpr, pix = m % rpr;
+            uint32_t req, pix;
+            divmod_uniform(m, rpr, &req, &pix);
             out = (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N + nbase;
         }
         f32x4 y[4];
