@@ -62,7 +62,8 @@ struct mt_ctx {
     // [kind][layer]: kind 0 = FC tiles, 1 = conv tiles, 2 = big FC tiles
     uint32_t max_rpr[kListKinds][MT_MAX_LAYERS]{}, max_nt[kListKinds][MT_MAX_LAYERS]{}, has_gap[MT_MAX_LAYERS]{};
     double sum_macs = 0.0;                           // multiply-accumulates of one request, summed over the registered tenants
-    uint32_t max_conv_cb[MT_MAX_LAYERS]{};           // widest conv tile (32-channel blocks, at most 4) of a layer index
+    uint32_t max_conv_cb[MT_MAX_LAYERS]{};
+    bool conv_quad[MT_MAX_LAYERS]{};                 // every conv of a layer index has input channels in multiples of four 16-byte chunks           // widest conv tile (32-channel blocks, at most 4) of a layer index
     uint64_t sum_nt[kListKinds][MT_MAX_LAYERS]{};
     uint32_t fc_split_k = 0;   // tuning: FC tiles of one column block with K split four ways
     uint32_t no_fused_gather = 0;  // tuning/testing: always stage FC inputs with the gather kernel
@@ -174,7 +175,7 @@ void recompute_bounds(mt_ctx* c)
     c->fc_first_chunked = true; c->any_conv_first = c->any_fc_first = false;
     c->list_mask = 0; c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        c->has_gap[l] = 0; c->max_conv_cb[l] = 0;
+        c->has_gap[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
     }
     for (const HostTenant& t : c->tenants) {
@@ -199,7 +200,10 @@ void recompute_bounds(mt_ctx* c)
             c->max_rpr[k][l] = std::max(c->max_rpr[k][l], L.rows_per_req);
             c->max_nt[k][l] = std::max(c->max_nt[k][l], nt);
             c->sum_nt[k][l] += nt;
-            if (k == 1) c->max_conv_cb[l] = std::max(c->max_conv_cb[l], std::min<uint32_t>(L.N_pad / kBrickRows, kTileCols / kBrickRows));
+            if (k == 1) {
+                c->max_conv_cb[l] = std::max(c->max_conv_cb[l], std::min<uint32_t>(L.N_pad / kBrickRows, kTileCols / kBrickRows));
+                if (L.cin % (4 * (16 / c->elem_size))) c->conv_quad[l] = false;
+            }
             if (k == 0 && L.N_pad >= (uint32_t)kBigMinCols) {      // may be served with big tiles when it gets enough rows
                 c->list_mask |= 1u << (2 * MT_MAX_LAYERS + l);
                 c->max_nt[2][l] = std::max(c->max_nt[2][l], (L.N_pad + kBigTile - 1) / kBigTile);
@@ -616,7 +620,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad; ga.zeros = c->d_zeros;
             const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, 0x7ffffff0u);
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
-            else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], g32, s));
+            else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], c->conv_quad[l], g32, s));
             else TIMED(kProfBig + l, launch_fc_big(ga, c->cfg.dtype, g32, s));
         }
         if (c->has_gap[l]) {

@@ -1187,12 +1187,14 @@ __device__ __forceinline__ void divmod_uniform(uint32_t x, uint32_t d, uint32_t*
 template <typename T>
 struct TapWalk {
     static constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
-    uint32_t lin, th, run, lo, hi, tlo, thi;
+    uint32_t lin, th, run, lo, hi, tlo, thi, step;
     int32_t cur, jump;
-    __device__ __forceinline__ void init(const LayerDev& L, int32_t ih0, int32_t iw0, bool row_ok, uint32_t lh)
+    // first: the lane's first element inside the run; step_el: elements per call of next()
+    // (at most one run ends per call: step_el <= 3 * cin)
+    __device__ __forceinline__ void init(const LayerDev& L, int32_t ih0, int32_t iw0, bool row_ok, uint32_t first, uint32_t step_el)
     {
         const int32_t cin = (int32_t)L.cin;
-        run = 3 * L.cin; lin = lh * EPC; th = 0;
+        run = 3 * L.cin; lin = first; th = 0; step = step_el;
         lo = iw0 < 0 ? L.cin : 0; hi = iw0 + 2 >= (int32_t)L.in_w ? 2 * L.cin : 3 * L.cin;
         tlo = ih0 < 0 ? 1 : 0; thi = row_ok ? (ih0 + 2 >= (int32_t)L.in_h ? 2 : 3) : 0;
         cur = (ih0 * (int32_t)L.in_w + iw0) * cin + (int32_t)lin;
@@ -1203,8 +1205,8 @@ struct TapWalk {
     {
         const bool ok = (lin >= lo) & (lin < hi) & (th >= tlo) & (th < thi);
         const int32_t chunk = ok ? (int32_t)((uint32_t)cur / EPC) : -1;
-        lin += KB; cur += (int32_t)KB;
-        const bool wrap = lin >= run;                               // at most once per step: KB <= 16 < 3 * cin
+        lin += step; cur += (int32_t)step;
+        const bool wrap = lin >= run;
         lin = wrap ? lin - run : lin; th += wrap ? 1u : 0u; cur = wrap ? cur + jump : cur;
         return chunk;
     }
@@ -1286,7 +1288,7 @@ __device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, 
     // the loaded value before its MFMA.
     gptr_t zeros = (gptr_t)a.zeros;
     TapWalk<T> walk;
-    walk.init(L, ih0, iw0, row_ok, lh);
+    walk.init(L, ih0, iw0, row_ok, lh * EPC, KB);
     auto load_a = [&]() -> u32x4 {
         const int32_t chunk = walk.next();
         gptr_t p = chunk >= 0 ? img + chunk : zeros;
@@ -1404,9 +1406,17 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
 constexpr uint32_t kConvKC = 2, kConvNS = 3;
 constexpr uint32_t kConvStageBytes = 8 * kConvKC * kBrickBytes;      // 4 pixel blocks + 4 filter areas, kConvKC k steps each
 
-template <typename T, int NCB>
+// QUAD (every tenant's input channels are a multiple of 4 chunks, i.e. a pixel's share of two k
+// steps is 64 contiguous bytes): a gather instruction then takes 16 pixels with four consecutive
+// lanes on one pixel's 64 bytes, instead of 32 pixels with one 16-byte piece per lane.  The
+// texture path handles a lane quad on one cache line as one access, so the gather costs a quarter
+// of the accesses.  The hardware's lane placement then yields [pixel][chunk] order instead of
+// brick order; the MFMA operand read picks its 16 bytes from there (a 2-way bank conflict, on a
+// path that has the time).
+template <typename T, int NCB, bool QUAD>
 __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
 {
+    static_assert(!QUAD || kConvKC == 2, "a quad gather covers exactly two k steps");
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
     constexpr uint32_t WR = 4 / NCB, RBW = 4 / WR;                  // wave rows; pixel blocks per wave
     typedef const __attribute__((address_space(1))) u32x4* gptr_t;
@@ -1433,24 +1443,26 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
     const uint32_t wc = wave % NCB, wr = wave / NCB;
     const bool active = wc < ncb;                                  // idle waves still gather; they stream block 0 and drop it
 
-    // gather role: pixel block `wave`, this lane's pixel and its walk through K (tap, channel)
-    const uint32_t gm = m0 + wave * kBrickRows + li;
-    const bool row_ok = gm < rows_total;
+    // gather role: pixel block `wave`.  Plain: this lane's pixel li, 16 bytes per k step.  QUAD:
+    // pixels lane/4 and lane/4 + 16, chunk lane%4 of the 64 bytes that two k steps take of each.
+    constexpr uint32_t NPX = QUAD ? 2 : 1;
     gptr_t zeros = (gptr_t)a.zeros;
-    gptr_t img = zeros;
-    int32_t ih0 = 0, iw0 = 0;
-    {
+    gptr_t img[NPX];
+    TapWalk<T> walk[NPX];
+#pragma unroll
+    for (uint32_t i = 0; i < NPX; ++i) {
+        const uint32_t gm = m0 + wave * kBrickRows + (QUAD ? (lane >> 2) + 16 * i : li);
+        const bool row_ok = gm < rows_total;
         const uint32_t mm = row_ok ? gm : m0;
         uint32_t req, pix, oh, ow;
         divmod_uniform(mm, rpr, &req, &pix);
         divmod_uniform(pix, L.out_w, &oh, &ow);
-        ih0 = (int32_t)(oh * L.stride) - 1; iw0 = (int32_t)(ow * L.stride) - 1;
-        img = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
+        img[i] = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
+        walk[i].init(L, (int32_t)(oh * L.stride) - 1, (int32_t)(ow * L.stride) - 1, row_ok,
+                     QUAD ? (lane & 3) * EPC : lh * EPC, QUAD ? 2 * KB : KB);
     }
     gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
     const uint32_t last_kb = n_chunks * kConvKC - 1;
-    TapWalk<T> walk;
-    walk.init(L, ih0, iw0, row_ok, lh);
     // The next kConvKC k steps of this wave's pixel block and of its filter block: 2 * kConvKC
     // loads.  Chunks past the end gather zeros (th >= 3) and repeat the last filter bricks, which
     // keeps the number of loads per round, and with it the wait below, uniform.
@@ -1458,12 +1470,16 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
         uint8_t* dst = lds + (c % kConvNS) * kConvStageBytes;
 #pragma unroll
         for (uint32_t kk = 0; kk < kConvKC; ++kk) {
-            const int32_t chunk = walk.next();
-            gptr_t p = chunk >= 0 ? img + chunk : zeros;
+            // plain: k step kk of all 32 pixels; QUAD: both k steps of pixels 16 kk .. 16 kk + 15
+            const int32_t chunk = walk[QUAD ? kk : 0].next();
+            gptr_t p = chunk >= 0 ? img[QUAD ? kk : 0] + chunk : zeros;
             lds_dma16(p, dst + (wave * kConvKC + kk) * kBrickBytes);
             lds_dma16(wp + (size_t)min(c * kConvKC + kk, last_kb) * 64, dst + ((4 + wave) * kConvKC + kk) * kBrickBytes);
         }
     };
+    // where lane (li, lh) finds its 16 bytes of k step kk inside a pixel block's area of a stage
+    const uint32_t a_lane = QUAD ? (li * 4 + lh) * 16 : lane * 16;
+    constexpr uint32_t a_kk = QUAD ? 32 : kBrickBytes;
 
     f32x16 acc[RBW];
 #pragma unroll
@@ -1483,13 +1499,13 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
         __builtin_amdgcn_s_barrier();                              // chunk c is complete for every wave; everyone is done with chunk c - 1
         asm volatile("" ::: "memory");
         fetch_chunk(c + kConvNS - 1);
-        const uint8_t* st = lds + (c % kConvNS) * kConvStageBytes + lane * 16;
+        const uint8_t* st = lds + (c % kConvNS) * kConvStageBytes;
 #pragma unroll
         for (uint32_t kk = 0; kk < kConvKC; ++kk) {
-            const u32x4 wv = *(const u32x4*)(st + ((4 + wave) * kConvKC + kk) * kBrickBytes);
+            const u32x4 wv = *(const u32x4*)(st + ((4 + wave) * kConvKC + kk) * kBrickBytes + lane * 16);
 #pragma unroll
             for (uint32_t r = 0; r < RBW; ++r) {
-                const u32x4 av = *(const u32x4*)(st + ((wr * RBW + r) * kConvKC + kk) * kBrickBytes);
+                const u32x4 av = *(const u32x4*)(st + (wr * RBW + r) * kConvKC * kBrickBytes + kk * a_kk + a_lane);
                 Mma<T>::run(acc[r], wv, av);                       // rows = channels, columns = pixels
             }
         }
@@ -1736,19 +1752,21 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s
 }
 
 template <typename T>
-static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, uint32_t grid, hipStream_t s)
+static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, uint32_t grid, hipStream_t s)
 {
     if (max_cb <= 1) hipLaunchKernelGGL((conv_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a);
-    else if (max_cb == 2) hipLaunchKernelGGL((conv_lds_kernel<T, 2>), dim3(grid), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((conv_lds_kernel<T, 4>), dim3(grid), dim3(256), 0, s, a);
+    else if (max_cb == 2 && quad) hipLaunchKernelGGL((conv_lds_kernel<T, 2, true>), dim3(grid), dim3(256), 0, s, a);
+    else if (max_cb == 2) hipLaunchKernelGGL((conv_lds_kernel<T, 2, false>), dim3(grid), dim3(256), 0, s, a);
+    else if (quad) hipLaunchKernelGGL((conv_lds_kernel<T, 4, true>), dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((conv_lds_kernel<T, 4, false>), dim3(grid), dim3(256), 0, s, a);
 }
 
-hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, uint32_t grid, hipStream_t s)
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t grid, hipStream_t s)
 {
     if (grid == 0) return hipSuccess;
     grid = (grid + 7) / 8 * 8;
-    if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, grid, s);
-    else launch_conv_t<float>(a, max_cb, grid, s);
+    if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, quad, grid, s);
+    else launch_conv_t<float>(a, max_cb, quad, grid, s);
     return hipGetLastError();
 }
 hipError_t launch_gap(const GapArgs& a, hipStream_t s)
