@@ -35,17 +35,21 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_MATRIX_PEAK_TFLOPS = 157.3
 
 
-def gemm_launch_costs(w, es):
+def gemm_launch_costs(w, es, rows_of=None):
     """Algorithmic flops and bytes of the grouped GEMM launch of every layer index: each active
     tenant's weights and bias read once, its input rows read once, its output rows written once
-    (hidden: element type; logits: fp32)."""
+    (hidden: element type; logits: fp32).  `rows_of(rows, layer)`: the rows of a tenant-layer
+    that the kernel in question serves (default: all of them)."""
     import workloads as wl
     flops, bytes_ = {}, {}
-    for t, m_t in w.counts().items():
+    for t, rows_t in w.counts().items():
         model = w.tenants[t]
         n = len(model.layers)
         for l, L in enumerate(model.layers):
             if L.kind == wl.GAP:
+                continue
+            m_t = rows_t if rows_of is None else rows_of(rows_t, L)
+            if m_t == 0:
                 continue
             if L.kind == wl.FC:
                 f = 2 * m_t * L.in_features * L.out_features
@@ -162,6 +166,9 @@ def main():
     dom_ms, dom_name = (fc_ms, "fc_kernel") if sum(fc_ms) >= sum(conv_ms) else (conv_ms, "conv_kernel")
     if dom_ms is fc_ms and sum(big_ms) > 0.5 * sum(fc_ms):
         dom_ms, dom_name = big_ms, "fc_big_kernel"
+        # the big-tile kernel is credited only with the rows it serves (a short remainder of a
+        # tenant's rows goes to the streaming kernel)
+        flops, bytes_ = gemm_launch_costs(w, es, lambda rows, L: mt.debug_big_tile_rows(rows, L.out_features) if L.kind == wl.FC else 0)
     other_ms = fc_ms if dom_ms is conv_ms else conv_ms
     launches = [l for l in range(n_slots) if dom_ms[l] > 0 and other_ms[l] == 0 and l in bytes_]
     raw_dur_s = sum(dom_ms[l] for l in launches) / len(launches) * 1e-3

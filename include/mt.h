@@ -191,6 +191,15 @@ mt_status mt_debug_poison(mt_ctx* ctx);
  * a multiple of 16), MT_EDEVICE (launch failure). */
 mt_status mt_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream);
 
+/* Measurement aid: how the library would split a fully-connected layer of one tenant that
+ * has `rows` requests in a run and `out_features` outputs, in a run that uses its
+ * compute-bound kernel (large batches; the decision per run and per layer index is the
+ * library's): the number of rows that kernel serves, the remaining rows being served by the
+ * weight-streaming kernel; 0 if the layer does not qualify at all.  Pure function of its
+ * arguments; needs no context and no device.  Lets a benchmark attribute flops to the
+ * kernel that performed them. */
+uint32_t mt_debug_big_tile_rows(uint32_t rows, uint32_t out_features);
+
 /* Text of the last error on this context ("" if none); valid until the next call. */
 const char* mt_last_error(const mt_ctx* ctx);
 

@@ -81,6 +81,8 @@ def load_library() -> ctypes.CDLL:
     L.mt_get_stats.argtypes = [vp, ctypes.POINTER(mt_stats)]
     L.mt_debug_poison.argtypes = [vp]
     L.mt_debug_copy.argtypes = [vp, vp, ctypes.c_uint64, vp]
+    L.mt_debug_big_tile_rows.argtypes = [u32, u32]
+    L.mt_debug_big_tile_rows.restype = u32
     L.mt_set_profiling.argtypes = [vp, ctypes.c_int]
     L.mt_get_profile.argtypes = [vp, ctypes.POINTER(mt_profile)]
     L.mt_last_error.argtypes = [vp]
@@ -207,6 +209,11 @@ def debug_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
     st = load_library().mt_debug_copy(dst, src, nbytes, stream)
     if st != 0:
         raise MtError(st, "mt_debug_copy failed")
+
+
+def debug_big_tile_rows(rows: int, out_features: int) -> int:
+    """Rows of a tenant's FC layer that the compute-bound kernel serves when a run uses it (0: none)."""
+    return int(load_library().mt_debug_big_tile_rows(rows, out_features))
 
 
 def version() -> str:

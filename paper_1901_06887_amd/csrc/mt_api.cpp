@@ -65,6 +65,7 @@ struct mt_ctx {
     uint32_t max_conv_cb[MT_MAX_LAYERS]{};
     bool conv_quad[MT_MAX_LAYERS]{};                 // every conv of a layer index has input channels in multiples of four 16-byte chunks           // widest conv tile (32-channel blocks, at most 4) of a layer index
     uint64_t sum_nt[kListKinds][MT_MAX_LAYERS]{};
+    uint32_t max_fc_per64[MT_MAX_LAYERS]{};   // streaming FC tiles per 64 rows of one tenant, maximum over the registered models
     uint32_t fc_split_k = 0;   // tuning: FC tiles of one column block with K split four ways
     uint32_t no_fused_gather = 0;  // tuning/testing: always stage FC inputs with the gather kernel
     bool fc_first_chunked = true;  // every registered FC-first model's input is a whole number of 16-byte chunks
@@ -87,7 +88,7 @@ struct mt_ctx {
     uint32_t* d_M = nullptr;
     uint32_t* d_off = nullptr;
     void* d_zeros = nullptr;           // 256 bytes of zeros: where masked operand loads point instead of branching
-    uint32_t* d_tile_base = nullptr;   // [2][MT_MAX_LAYERS][T+1]: FC arrays, then conv arrays
+    uint32_t* d_tile_base = nullptr;   // [kListKinds][MT_MAX_LAYERS][T+1]: FC, conv and big-FC arrays, then one word: the big-tile layer mask
     void* d_act[2] = {nullptr, nullptr};
     float* d_logits = nullptr;
     Segment* h_segs[kSegSlots] = {};    // pinned, device-visible
@@ -167,6 +168,11 @@ uint32_t fc_groups(uint32_t n_pad, uint32_t split_k)
     const uint32_t split = split_k ? 1u : (nblk >= 3 ? 4u : nblk);
     return (nblk + split - 1) / split;
 }
+// ... and the rows of such a tile: 64 where the four waves stand side by side, else 32
+uint32_t fc_tile_rows(uint32_t n_pad, uint32_t split_k)
+{
+    return (!split_k && n_pad / kBrickRows >= 3) ? kTileRows : kTileRows / 2;
+}
 
 void recompute_bounds(mt_ctx* c)
 {
@@ -177,6 +183,7 @@ void recompute_bounds(mt_ctx* c)
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
         c->has_gap[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
+        c->max_fc_per64[l] = 0;
     }
     for (const HostTenant& t : c->tenants) {
         if (!t.registered) continue;
@@ -200,6 +207,7 @@ void recompute_bounds(mt_ctx* c)
             c->max_rpr[k][l] = std::max(c->max_rpr[k][l], L.rows_per_req);
             c->max_nt[k][l] = std::max(c->max_nt[k][l], nt);
             c->sum_nt[k][l] += nt;
+            if (k == 0) c->max_fc_per64[l] = std::max(c->max_fc_per64[l], nt * (kTileRows / fc_tile_rows(L.N_pad, c->fc_split_k)));
             if (k == 1) {
                 c->max_conv_cb[l] = std::max(c->max_conv_cb[l], std::min<uint32_t>(L.N_pad / kBrickRows, kTileCols / kBrickRows));
                 if (L.cin % (4 * (16 / c->elem_size))) c->conv_quad[l] = false;
@@ -218,9 +226,9 @@ uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R)
     if (c->max_nt[kind][l] == 0) return 0;
     if (kind == 2)      // big FC tiles: only tenants with >= kBigMinRows rows; sum ceil(M_t/256) <= R/256 + R/kBigMinRows
         return R < (uint64_t)kBigMinBatch ? 0 : (uint64_t)c->max_nt[2][l] * (R / kBigTile + R / kBigMinRows);
-    // FC tiles may be as short as 32 rows (layers with at most 64 outputs)
-    const uint64_t tile_rows = kind == 0 ? kTileRows / 2 : kConvTileRows;
-    return (uint64_t)c->max_nt[kind][l] * (R * c->max_rpr[kind][l] / tile_rows) + c->sum_nt[kind][l];
+    // sum over tenants of ceil(M_t / rows_t) * groups_t <= R * max(groups_t / rows_t) + sum(groups_t)
+    if (kind == 0) return ((uint64_t)c->max_fc_per64[l] * R + kTileRows - 1) / kTileRows + c->sum_nt[0][l];
+    return (uint64_t)c->max_nt[kind][l] * (R * c->max_rpr[kind][l] / kConvTileRows) + c->sum_nt[kind][l];
 }
 
 // ---- validation of a layer chain; fills dev layouts (without arena offsets) -------------
@@ -384,8 +392,8 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     CREATE_TRY(hipMalloc((void**)&c->d_M, T * 4));
     CREATE_TRY(hipMemset(c->d_M, 0, T * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_off, (T + 1) * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_tile_base, kListKinds * MT_MAX_LAYERS * (T + 1) * 4));
-    CREATE_TRY(hipMemset(c->d_tile_base, 0, kListKinds * MT_MAX_LAYERS * (T + 1) * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_tile_base, (kListKinds * MT_MAX_LAYERS * (T + 1) + 1) * 4));
+    CREATE_TRY(hipMemset(c->d_tile_base, 0, (kListKinds * MT_MAX_LAYERS * (T + 1) + 1) * 4));
     CREATE_TRY(hipMalloc(&c->d_zeros, 256));
     CREATE_TRY(hipMemset(c->d_zeros, 0, 256));
     for (int i = 0; i < 2; ++i) {
@@ -568,7 +576,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     b.first = c->pending[0]; b.row_src = c->d_row_src; b.elem_size = c->elem_size;
     b.tenants = c->d_tenants; b.layers = c->d_layers;
     b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
-    b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.fc_split_k = c->fc_split_k;
+    b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.big_layers = c->d_tile_base + (size_t)kListKinds * MT_MAX_LAYERS * (T + 1); b.fc_split_k = c->fc_split_k;
     b.list_mask = c->list_mask; b.big_enabled = big_enabled; b.big_min_tiles = c->big_min_tiles;
     const OutPtrs outp{out->labels, out->probs, out->logits, out->n_classes, out->row_stride};
     b.out = outp;
@@ -613,7 +621,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             if (grid == 0 || (kind == 2 && (!big_enabled || grid < c->big_min_tiles))) continue;   // no big tiles possible: the batcher made none
             GemmArgs ga{};
             ga.tile_base = c->d_tile_base + ((size_t)kind * MT_MAX_LAYERS + l) * (T + 1);
-            ga.T = T; ga.layer = l; ga.fc_split_k = c->fc_split_k;
+            ga.T = T; ga.layer = l; ga.fc_split_k = c->fc_split_k; ga.big_layers = b.big_layers;
             ga.gather = (kind == 0 && l == 0 && fuse_gather); ga.perm = c->d_perm; ga.row_src = c->d_row_src;
             ga.fuse_head = fuse_head; ga.out = outp;
             ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
@@ -707,6 +715,11 @@ mt_status mt_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream
 {
     if (!dst || !src || bytes % 16) return MT_EINVAL;
     return launch_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? MT_OK : MT_EDEVICE;
+}
+
+uint32_t mt_debug_big_tile_rows(uint32_t rows, uint32_t out_features)
+{
+    return fc_is_big(rows, round_up(out_features, (uint32_t)kBrickRows)) ? big_rows(rows) : 0;
 }
 
 mt_status mt_debug_poison(mt_ctx* c)

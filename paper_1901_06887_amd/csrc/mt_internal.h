@@ -27,10 +27,22 @@ constexpr int kConvTileRows = 128;  // GEMM rows (output pixels) of a conv workg
 // compute bound; it is cut into kBigTile x kBigTile tiles and served by the big-tile FC kernel.
 constexpr int kBigTile = 256;
 constexpr int kBigMinRows = 2048;
+// ... except a last row tile of at most kBigRemRows rows: alone on a compute unit it would take a
+// whole tile's time (and, at the end of a launch, hold the chip for a round of its own), so
+// those rows go to the streaming kernel, which reads the tenant's weights once more instead.
+constexpr int kBigRemRows = 128;
 constexpr int kBigMinCols = 192;
 constexpr int kBigMinTiles = 512;   // a layer index is served with big tiles only when it has at least two per compute unit
 constexpr double kRidgeFlopsPerByte = 312.0;   // dense bf16 MFMA peak over HBM bandwidth (2.5 PFLOP/s / 8 TB/s)
 constexpr int kBigMinBatch = 8192;  // runs with fewer rows are latency/HBM bound as a whole: no big tiles
+inline __host__ __device__ bool fc_is_big(uint32_t rows, uint32_t n_pad) { return rows >= (uint32_t)kBigMinRows && n_pad >= (uint32_t)kBigMinCols; }
+// Rows of a big tenant-layer that the big tiles serve: all of them, unless the last row tile
+// would hold at most kBigRemRows rows; those rows are left to the streaming kernel.
+inline __host__ __device__ uint32_t big_rows(uint32_t rows)
+{
+    const uint32_t rem = rows % kBigTile;
+    return rem && rem <= (uint32_t)kBigRemRows ? rows - rem : rows;
+}
 constexpr int kListKinds = 3;       // tile lists per layer index: FC (streaming), conv, FC (big tiles)
 constexpr int kRowBytes = 128;      // conv path: bytes of K one pipeline step consumes per row
 constexpr int kChanPad = 8;         // conv input channels are padded to a multiple of this
@@ -106,6 +118,7 @@ struct BatchArgs {
     uint32_t* M;           // [T]
     uint32_t* off;         // [T+1] packed position of each tenant's first row (multiple of 32)
     uint32_t* tile_base;   // [kListKinds][MT_MAX_LAYERS][T+1]: FC, conv, big-FC arrays
+    uint32_t* big_layers;  // [1] out: bit l set if layer index l is served with big tiles where a tenant qualifies
     uint32_t list_mask;    // bit kind*MT_MAX_LAYERS + l set if any registered model can have such tiles at layer l
     OutPtrs out;           // rejected rows are answered here (label -1, zero rows)
 };
@@ -120,6 +133,7 @@ struct GatherArgs {
 
 struct GemmArgs {
     const uint32_t* tile_base; uint32_t T; uint32_t layer; uint32_t fc_split_k;
+    const uint32_t* big_layers;   // the batcher's decision per layer index (see BatchArgs)
     // FC layer 0 can read the submitted rows itself (16-byte aligned rows whose length is a
     // whole number of 16-byte chunks), which saves the staging pass:
     uint32_t gather; const int32_t* perm; const void* const* row_src;

@@ -113,8 +113,6 @@ __device__ __forceinline__ void fc_shape(uint32_t n_pad, uint32_t split_k, uint3
 
 constexpr uint32_t kLists = kListKinds * MT_MAX_LAYERS;   // FC, conv and big-FC tile-count arrays of every layer index
 
-__device__ __forceinline__ bool fc_is_big(uint32_t rows, uint32_t n_pad) { return rows >= kBigMinRows && n_pad >= kBigMinCols; }
-
 // Tenant segmentation and grouped-work descriptors.  One workgroup; every step is
 // deterministic: rows of a tenant keep their arrival order (stable counting sort).  Equal
 // tenant ids inside a wavefront are found with one ballot per id bit, so a step costs the
@@ -327,7 +325,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
                 const uint32_t rr = rpr[slot][l], np = npad[slot][l];
                 const uint32_t g = grp[slot][l];
-                if (g && !(rr >> 31) && fc_is_big(Mt, np)) bt[l] += ceil_div(Mt, kBigTile) * ceil_div(np, kBigTile);
+                if (g && !(rr >> 31) && fc_is_big(Mt, np)) bt[l] += ceil_div(big_rows(Mt), kBigTile) * ceil_div(np, kBigTile);
             }
         }
 #pragma unroll
@@ -342,6 +340,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 #pragma unroll
         for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) big_layers |= (big_total[l] >= a.big_min_tiles ? 1u : 0u) << l;
     }
+    if (tid == 0) *a.big_layers = big_layers;   // the FC kernels split a qualifying tenant's rows by it
 
     // pass 4: tile counts of every (kind, layer) list, scanned over tenants in one vector scan.
     // Only the exclusive in-wave prefix of each list stays in registers across the barriers; the
@@ -368,11 +367,13 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
             const uint32_t g = grp[slot][l], rr = rpr[slot][l], np = npad[slot][l];
             const bool conv = rr >> 31;
             const bool big = !conv && ((big_layers >> l) & 1) && fc_is_big(Mt, np);
-            // conv: rows = requests * output pixels per tile; FC: rr = 1 (64-row tiles) or 2 (32-row tiles)
-            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) : ceil_div(Mt, kTileRows / rr)) * g : 0;
-            wave_scan(l, (conv || big) ? 0 : tiles);
+            // conv: rows = requests * output pixels per tile; FC: rr = 1 (64-row tiles) or 2 (32-row tiles),
+            // over the rows that big tiles leave
+            const uint32_t Mb = big ? big_rows(Mt) : 0;
+            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) : ceil_div(Mt - Mb, kTileRows / rr)) * g : 0;
+            wave_scan(l, conv ? 0 : tiles);
             wave_scan(MT_MAX_LAYERS + l, conv ? tiles : 0);
-            wave_scan(2 * MT_MAX_LAYERS + l, big ? ceil_div(Mt, kBigTile) * ceil_div(np, kBigTile) : 0);
+            wave_scan(2 * MT_MAX_LAYERS + l, ceil_div(Mb, kBigTile) * ceil_div(np, kBigTile));
         }
         __syncthreads();
         if (tid < kLists) {
@@ -925,8 +926,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const uint32_t Mt = a.M[tl.tenant];
     uint32_t groups, trows;
     fc_shape(L.N_pad, a.fc_split_k, &tl.split, &groups, &trows);
-    const uint32_t mt_ = ceil_div(Mt, trows);
-    tl.m0 = (local % mt_) * trows;
+    // where big tiles serve this tenant-layer, only the rows they leave are tiled here
+    const bool big = ((*a.big_layers >> a.layer) & 1) && fc_is_big(Mt, L.N_pad);
+    const uint32_t first = big ? big_rows(Mt) : 0;
+    const uint32_t mt_ = ceil_div(Mt - first, trows);
+    tl.m0 = first + (local % mt_) * trows;
     tl.rows = min(trows, Mt - tl.m0);
     tl.n0 = (local / mt_) * tl.split * kBrickRows;
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
@@ -984,11 +988,12 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     const uint32_t nKB = L.K / KB;
     // tile order inside a tenant: groups of kBigGroup row tiles sweep all column tiles together, so
     // the tiles that run at the same time on one XCD share few activation and weight panels (L2 reuse)
-    const uint32_t mt_ = ceil_div(Mt, kBigTile), nt_ = ceil_div(L.N_pad, kBigTile);
+    const uint32_t Mb = big_rows(Mt);                      // a short remainder is the streaming kernel's
+    const uint32_t mt_ = ceil_div(Mb, kBigTile), nt_ = ceil_div(L.N_pad, kBigTile);
     const uint32_t per_group = kBigGroup * nt_, grp = local / per_group, first_m = grp * kBigGroup;
     const uint32_t gsz = min(mt_ - first_m, kBigGroup), in_grp = local - grp * per_group;
     const uint32_t m0 = (first_m + in_grp % gsz) * kBigTile, n0 = (in_grp / gsz) * kBigTile;
-    const uint32_t rows = min((uint32_t)kBigTile, Mt - m0), nrb = ceil_div(rows, kBrickRows);
+    const uint32_t rows = min((uint32_t)kBigTile, Mb - m0), nrb = ceil_div(rows, kBrickRows);
     const uint32_t ncb = min(kBigBlocks, L.N_pad / kBrickRows - n0 / kBrickRows);
     const uint32_t wm = wave / WN, wn = wave % WN;
 

@@ -74,6 +74,16 @@ def test_big_tile_path_reduced(big_tiles_always):
     run_and_compare(w, "c5-big-reduced")
 
 
+def test_big_tenants_leave_a_short_remainder_to_the_streaming_kernel(big_tiles_always):
+    # rows past the last full 256-row tile: 40 and 128 (streamed), 129 (a ragged big tile), 0
+    counts = [2048 + 40, 2304 + 128, 2048 + 129, 2304]
+    base = wl.c5(n_tenants=4, n_requests=sum(counts), dims=(192, 320, 448, 200), seed=15)
+    ids = np.random.default_rng(15).permutation(np.repeat(np.arange(4), counts)).astype(np.int32)
+    w = wl.Workload("big+remainder", base.dtype, base.tenants, ids, base.inputs)
+    assert [w.counts()[t] for t in range(4)] == counts
+    run_and_compare(w, "big+remainder")
+
+
 def test_big_and_streaming_tenants_in_one_run(big_tiles_always):
     w = wl.c2(n_tenants=5, n_requests=8300, dims=(128, 320, 256, 40), s=2.2)    # one tenant dominates
     c = w.counts()
