@@ -80,8 +80,10 @@ struct mt_ctx {
     uint8_t* d_arena = nullptr;
     TenantDev* d_tenants = nullptr;
     LayerDev* d_layers = nullptr;
+    uint32_t* d_facts = nullptr;       // [max_tenants][MT_MAX_LAYERS][2]: the batcher's view of the layers (BatchArgs::facts)
     int32_t* d_row_tenant = nullptr;
     uint32_t* d_row_rank = nullptr;
+    uint32_t* d_hist_g = nullptr;      // [kHistEntries] per-workgroup tenant histograms of the ranking kernel
     const void** d_row_src = nullptr;
     int32_t* d_pos_of = nullptr;
     int32_t* d_perm = nullptr;
@@ -172,6 +174,23 @@ uint32_t fc_groups(uint32_t n_pad, uint32_t split_k)
 uint32_t fc_tile_rows(uint32_t n_pad, uint32_t split_k)
 {
     return (!split_k && n_pad / kBrickRows >= 3) ? kTileRows : kTileRows / 2;
+}
+
+// The batcher's two words per layer of one tenant (see BatchArgs::facts); zeros without a model.
+hipError_t upload_facts(mt_ctx* c, uint32_t tenant, const HostTenant* ht)
+{
+    uint32_t w[MT_MAX_LAYERS][2] = {};
+    for (uint32_t l = 0; ht && l < ht->n_layers; ++l) {
+        const LayerDev& L = ht->layers[l].dev;
+        if (L.kind == MT_FC) {
+            w[l][0] = fc_groups(L.N_pad, c->fc_split_k) | (fc_tile_rows(L.N_pad, c->fc_split_k) == kTileRows ? 0u : 1u << 30);
+            w[l][1] = L.N_pad;
+        } else if (L.kind == MT_CONV2D) {
+            w[l][0] = (L.N + kTileCols - 1) / kTileCols | 1u << 31;
+            w[l][1] = L.rows_per_req;
+        }
+    }
+    return hipMemcpy(c->d_facts + (size_t)tenant * 2 * MT_MAX_LAYERS, w, sizeof w, hipMemcpyHostToDevice);
 }
 
 void recompute_bounds(mt_ctx* c)
@@ -384,8 +403,11 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     CREATE_TRY(hipMemset(c->d_tenants, 0, T * sizeof(TenantDev)));
     CREATE_TRY(hipMalloc((void**)&c->d_layers, T * MT_MAX_LAYERS * sizeof(LayerDev)));
     CREATE_TRY(hipMemset(c->d_layers, 0, T * MT_MAX_LAYERS * sizeof(LayerDev)));
+    CREATE_TRY(hipMalloc((void**)&c->d_facts, 2 * MT_MAX_LAYERS * T * 4));
+    CREATE_TRY(hipMemset(c->d_facts, 0, 2 * MT_MAX_LAYERS * T * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_row_tenant, R * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_row_rank, R * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_hist_g, kHistEntries * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_row_src, R * sizeof(void*)));
     CREATE_TRY(hipMalloc((void**)&c->d_pos_of, R * 4));
     CREATE_TRY(hipMalloc((void**)&c->d_perm, (uint64_t)c->P_cap * 4));
@@ -415,7 +437,7 @@ mt_status mt_destroy(mt_ctx* c)
     if (!c->host_only) {
         (void)hipSetDevice(c->cfg.device);
         (void)hipDeviceSynchronize();
-        void* bufs[] = {c->d_arena, c->d_tenants, c->d_layers, c->d_row_tenant, c->d_row_rank, (void*)c->d_row_src, c->d_pos_of, c->d_perm,
+        void* bufs[] = {c->d_arena, c->d_tenants, c->d_layers, c->d_facts, c->d_row_tenant, c->d_row_rank, c->d_hist_g, (void*)c->d_row_src, c->d_pos_of, c->d_perm,
                         c->d_M, c->d_off, c->d_tile_base, c->d_zeros, c->d_act[0], c->d_act[1], c->d_logits};
         for (void* p : bufs) if (p) (void)hipFree(p);
         for (uint32_t i = 0; i < kSegSlots; ++i) {
@@ -470,6 +492,7 @@ mt_status mt_register_model(mt_ctx* c, uint32_t tenant, const mt_layer_spec* spe
         hipError_t e = hipSetDevice(c->cfg.device);
         if (e == hipSuccess) e = hipMemcpy(c->d_arena + off, image.data(), total, hipMemcpyHostToDevice);
         if (e == hipSuccess) e = hipMemcpy(c->d_layers + (size_t)tenant * MT_MAX_LAYERS, rows, sizeof rows, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = upload_facts(c, tenant, &ht);
         if (e == hipSuccess) e = hipMemcpy(c->d_tenants + tenant, &td, sizeof td, hipMemcpyHostToDevice);
         if (e != hipSuccess) {
             arena_free(c, off, total);
@@ -494,6 +517,7 @@ mt_status mt_unregister_model(mt_ctx* c, uint32_t tenant)
         HIP_TRY(c, hipSetDevice(c->cfg.device));
         HIP_TRY(c, hipDeviceSynchronize());
         HIP_TRY(c, hipMemcpy(c->d_tenants + tenant, &td, sizeof td, hipMemcpyHostToDevice));
+        HIP_TRY(c, upload_facts(c, tenant, nullptr));
     }
     arena_free(c, c->tenants[tenant].arena_off, c->tenants[tenant].arena_len);
     c->tenants[tenant] = HostTenant{};
@@ -574,10 +598,18 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     BatchArgs b{};
     b.segs = c->d_segs[slot]; b.n_segs = n_segs; b.R = R; b.T = T; b.n_layer_slots = c->n_layer_slots;
     b.first = c->pending[0]; b.row_src = c->d_row_src; b.elem_size = c->elem_size;
-    b.tenants = c->d_tenants; b.layers = c->d_layers;
+    b.tenants = c->d_tenants; b.facts = c->d_facts;
+    {   // large batches are ranked by a kernel of their own, where its per-workgroup histograms fit the batcher's LDS
+        uint32_t Tp = 64;
+        while (Tp < T) Tp <<= 1;
+        const uint32_t groups = (R + kRankRows - 1) / kRankRows;
+        const bool spread = R >= (uint32_t)kRankMinRows && T <= (uint32_t)kRankMaxTenants && (uint64_t)groups * Tp <= (uint64_t)kHistEntries;
+        b.n_rank_groups = spread ? groups : 0; b.hist_g = c->d_hist_g;
+    }
     b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
     b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.big_layers = c->d_tile_base + (size_t)kListKinds * MT_MAX_LAYERS * (T + 1); b.fc_split_k = c->fc_split_k;
-    b.list_mask = c->list_mask; b.big_enabled = big_enabled; b.big_min_tiles = c->big_min_tiles;
+    b.list_mask = big_enabled ? c->list_mask : c->list_mask & ((1u << (2 * MT_MAX_LAYERS)) - 1);   // no big-tile lists to build
+    b.big_enabled = big_enabled; b.big_min_tiles = c->big_min_tiles;
     const OutPtrs outp{out->labels, out->probs, out->logits, out->n_classes, out->row_stride};
     b.out = outp;
     // A last layer of at most 32 classes is one column block: its FC tiles finish their rows
@@ -592,6 +624,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         if (c->profiling) { HIP_TRY(c, hipEventRecord(c->prof_events[2 * (slot) + 1], s)); c->prof_used[slot] = true; c->prof_last = (slot); } \
     } while (0)
     TIMED(kProfBatcher, launch_batcher(b, s));
+    if (b.n_rank_groups) launches += 2;
 
     // The FC kernel of layer 0 reads the submitted rows itself when every row is 16-byte aligned
     // and a whole number of 16-byte chunks long; otherwise (and for CNN models, whose images are

@@ -43,6 +43,10 @@ inline __host__ __device__ uint32_t big_rows(uint32_t rows)
     const uint32_t rem = rows % kBigTile;
     return rem && rem <= (uint32_t)kBigRemRows ? rows - rem : rows;
 }
+constexpr int kRankRows = 1024;     // rows per workgroup of the ranking kernel
+constexpr int kRankMinRows = 8192;  // smaller batches are ranked by the batcher's single workgroup (one launch less)
+constexpr int kRankMaxTenants = 512;
+constexpr int kHistEntries = 8192;  // histogram words the batcher holds in LDS (waves or ranking workgroups x padded tenants)
 constexpr int kListKinds = 3;       // tile lists per layer index: FC (streaming), conv, FC (big tiles)
 constexpr int kRowBytes = 128;      // conv path: bytes of K one pipeline step consumes per row
 constexpr int kChanPad = 8;         // conv input channels are padded to a multiple of this
@@ -109,9 +113,20 @@ struct BatchArgs {
     uint32_t fc_split_k;   // 1: FC tiles take one column block each and split K four ways
     uint32_t big_enabled;  // 0: no tenant-layer is given big tiles in this run (small batches)
     uint32_t big_min_tiles; // a layer index uses big tiles only when its qualifying tenants make at least this many
-    const TenantDev* tenants; const LayerDev* layers;
+    const TenantDev* tenants;
+    // What the tile lists need to know of every tenant-layer: two words per layer, 64 bytes per
+    // tenant, facts[tenant][layer][2].  Word 0: column groups of the layer's tiles (0: no tiles:
+    // pooling, or no such layer), bit 31: convolution, bit 30: FC tiles of 32 rows instead of 64.
+    // Word 1: GEMM rows per request (convolution) or padded outputs (FC).
+    const uint32_t* facts;
     int32_t* row_tenant;   // [R] tenant of each submitted row, -1 if rejected
     uint32_t* row_rank;    // [R] scratch
+    // Large batches are ranked by a kernel of their own, kRankRows rows per workgroup, before the
+    // batcher proper: n_rank_groups workgroups (0: the batcher ranks the rows itself), each leaving
+    // the rank of a row among its workgroup's rows of the same tenant in row_rank and its tenant
+    // histogram in hist_g[group][Tp] (Tp: the tenant count padded to a power of two, at least 64).
+    // The batcher turns hist_g into prefixes over the groups, and a third kernel places the rows.
+    uint32_t n_rank_groups; uint32_t* hist_g;
     const void** row_src;  // [R] device address of each submitted row's input
     int32_t* pos_of;       // [R] packed position of each submitted row, -1 if rejected
     int32_t* perm;         // [P] packed position -> submission index, -1 for padding rows
@@ -160,7 +175,7 @@ struct HeadArgs {
 };
 
 // Launchers (defined in mt_kernels.hip).  All enqueue on `s` and return the launch status.
-hipError_t launch_batcher(const BatchArgs& a, hipStream_t s);
+hipError_t launch_batcher(const BatchArgs& a, hipStream_t s);   // three launches when a.n_rank_groups > 0
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
 hipError_t launch_gather_image(const GatherArgs& a, hipStream_t s);
 hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);

@@ -197,3 +197,37 @@ def test_deepest_model_and_head_boundaries():
     gpu = gpu_run(ctx, w, poison=True)
     compare(w, gpu, oracle_rows(w), what="deep+boundary")
     ctx.close()
+
+
+def test_large_batch_in_several_submissions():
+    # >= 8192 rows: the rows are ranked by a kernel of its own, spread over the chip, from one
+    # submission and from a mix of batch and per-tenant submissions; a few ids are unknown
+    base = wl.c2(n_tenants=6, n_requests=9100, dims=(64, 96, 10), seed=41)
+    ids = base.tenant_ids.copy()
+    ids[3000:3500] = 2                                   # will be one per-tenant submission
+    w = wl.Workload("large-mixed", base.dtype, base.tenants, ids, base.inputs)
+    ctx = make_context(w)
+    ref = gpu_run(ctx, w, poison=True)
+    compare(w, ref, oracle_rows(w), what="large, one submission")
+
+    d_x = torch_io.to_device(w.inputs, w.dtype)
+    d_ids = torch.from_numpy(ids).cuda()
+    es, K = d_x.element_size(), d_x.shape[1]
+    assert ctx.submit_batch(d_ids.data_ptr(), d_x.data_ptr(), 3000, K) == 0
+    assert ctx.submit(2, d_x.data_ptr() + 3000 * K * es, 500) == 3000
+    assert ctx.submit_batch(d_ids.data_ptr() + 3500 * 4, d_x.data_ptr() + 3500 * K * es, 9100 - 3500, K) == 3500
+    out = torch_io.alloc_outputs(w.n_requests, ctx.cfg.max_classes)
+    n = ctx.run(torch.cuda.current_stream().cuda_stream, out.labels.data_ptr(), out.probs.data_ptr(),
+                out.logits.data_ptr(), out.n_classes.data_ptr(), w.n_requests, ctx.cfg.max_classes)
+    torch.cuda.synchronize()
+    assert n == w.n_requests
+    assert np.array_equal(out.logits.cpu().numpy().astype(np.float64), ref[0])
+    assert np.array_equal(out.labels.cpu().numpy(), ref[2])
+
+    bad = ids.copy()
+    bad[[5, 4100, 9099]] = [77, -3, 6]
+    lg, pr, lb, nc = gpu_run(ctx, w, ids=bad)
+    rej = np.isin(np.arange(len(ids)), [5, 4100, 9099])
+    assert np.all(lb[rej] == -1) and np.all(nc[rej] == 0) and np.all(lg[rej] == 0)
+    assert np.array_equal(lg[~rej], ref[0][~rej]) and np.array_equal(lb[~rej], ref[2][~rej])
+    ctx.close()
