@@ -43,6 +43,9 @@ def short_name(name: str) -> str:
     m = re.match(r"_ZN2mt\d+([a-z_]+)ILb([01])", name)
     if m:
         return "mt::%s<%s>" % (m.group(1), m.group(2))
+    m = re.match(r"_ZN2mt\d+([a-z_]+)E", name)
+    if m:
+        return "mt::%s" % m.group(1)
     return re.sub(r"\(.*", "", name)
 
 
