@@ -762,18 +762,28 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
     // K is walked in blocks of U steps, unrolled, so that ring slots (step % P) and, where a
     // block spans two chunks, LDS stages are compile-time constants.  Slot s % P holds step s
     // from P steps before its use until its MFMAs; it is refilled with step s + P right after.
-    u32x4 bq[P], xr[4];
+    // Loads return in order, so waiting for an activation load also waits for every weight
+    // load issued before it.  The activation bricks of a chunk are therefore fetched as far
+    // ahead as the weight ring reaches (NX chunks = P steps): by the time they are waited for,
+    // every older weight load is one whose MFMA is due anyway, and the ring keeps its depth
+    // across chunk boundaries (with one chunk of lookahead the 64-row tiles, whose chunks are 8
+    // steps, had only the newest 8 weight loads in flight at every boundary; worth 1-2 % on the
+    // skewed mixes).
+    constexpr uint32_t NX = P / KC;                           // 1 (32-row tiles) or 2
+    static_assert(NX >= 1 && U % (NX * KC) == 0, "a block of U steps starts with staging slot 0");
+    u32x4 bq[P], xr[NX][4];
 #pragma unroll
     for (uint32_t j = 0; j < P; ++j) bq[j] = wp[(size_t)min(j, nKB - 1) * 64];
-    load_chunk(0, xr);
-    store_chunk(0, xr);
-    load_chunk(1, xr);                                        // zeros / clamped when there is no chunk 1
+    load_chunk(0, xr[0]);
+    store_chunk(0, xr[0]);
+#pragma unroll
+    for (uint32_t i = 1; i <= NX; ++i) load_chunk(i, xr[i % NX]);   // zeros / clamped past the last chunk
     uint32_t c = 0;                                           // chunk being consumed; it lives in stage c & 1
     const uint8_t* st = stages + lane * 16;
-    auto next_chunk = [&]() {
+    auto next_chunk = [&](uint32_t slot) {                    // slot = (c + 1) % NX, a constant at every call site
         lds_barrier();                                        // stage c&1 is complete; stage (c+1)&1 is free again
-        store_chunk((c + 1) & 1, xr);
-        load_chunk(c + 2, xr);
+        store_chunk((c + 1) & 1, xr[slot]);
+        load_chunk(c + 1 + NX, xr[slot]);
         st = stages + (c & 1) * kStageBytes + lane * 16;
         ++c;
     };
@@ -781,7 +791,7 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
     for (uint32_t blk = 0; blk < n_blocks; ++blk) {
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
-            if (u % KC == 0) next_chunk();
+            if (u % KC == 0) next_chunk((u / KC + 1) % NX);
             u32x4 av[RB];
 #pragma unroll
             for (int r = 0; r < RB; ++r) av[r] = *(const u32x4*)(st + (r * KC + u % KC) * kBrickBytes);
@@ -796,7 +806,7 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
 #pragma unroll
     for (uint32_t u = 0; u < U; ++u) {
         if (u < rem) {
-            if (u % KC == 0) next_chunk();
+            if (u % KC == 0) next_chunk((u / KC + 1) % NX);
 #pragma unroll
             for (int r = 0; r < RB; ++r) Mma<T>::run(acc[r], *(const u32x4*)(st + (r * KC + u % KC) * kBrickBytes), bq[u % P]);
         }
