@@ -20,7 +20,11 @@
  *     mt_last_error() gives a text for the last failing call on a context.
  *   - "HOST" pointers are ordinary process memory; "DEVICE" pointers are HIP
  *     device memory on the context's GPU (e.g. a torch tensor's data_ptr()).
- *   - A context is not thread-safe; one mt_run may be in flight per context.
+ *   - A context is not thread-safe.  One mt_run may be in flight per context, or
+ *     cfg.run_slots of them when they are enqueued on different streams: mt_run
+ *     number i uses slot i % run_slots and first makes its stream wait for the run
+ *     that used the slot before.  Result queries (mt_last_counts) refer to the run
+ *     enqueued last.
  *   - Element type of weights, inputs and hidden activations is the context's
  *     dtype: MT_F32 (4 bytes) or MT_BF16 (2 bytes, bfloat16 bit patterns).
  *     Biases, logits and probabilities are always fp32.  With MT_BF16 every
@@ -79,6 +83,10 @@ typedef struct {
     uint32_t dtype;         /* mt_dtype of weights / inputs / hidden activations         */
     int32_t  device;        /* HIP device ordinal; -1 = host-only context: registration,
                                validation and accounting work, mt_run returns MT_ESTATE  */
+    uint32_t run_slots;     /* runs that may be in flight at once, each on a stream of its
+                               own (batch interleaving, footnote of paper section 1.3): 0
+                               or 1 = one; at most 4.  Every slot has its own batch
+                               descriptors and activation buffers; the weights are shared */
 } mt_config;
 
 /* Where mt_run writes predictions.  All DEVICE memory owned by the caller, valid

@@ -38,7 +38,8 @@ class mt_layer_spec(ctypes.Structure):
 class mt_config(ctypes.Structure):
     _fields_ = [("max_tenants", ctypes.c_uint32), ("max_requests", ctypes.c_uint32),
                 ("max_width", ctypes.c_uint32), ("max_classes", ctypes.c_uint32),
-                ("arena_bytes", ctypes.c_uint64), ("dtype", ctypes.c_uint32), ("device", ctypes.c_int32)]
+                ("arena_bytes", ctypes.c_uint64), ("dtype", ctypes.c_uint32), ("device", ctypes.c_int32),
+                ("run_slots", ctypes.c_uint32)]
 
 
 class mt_outputs(ctypes.Structure):
@@ -119,10 +120,10 @@ class Context:
     """One worker context (mt_ctx).  Methods mirror the C entry points one to one."""
 
     def __init__(self, max_tenants: int, max_requests: int, max_width: int, max_classes: int,
-                 arena_bytes: int, dtype: int, device: int = 0):
+                 arena_bytes: int, dtype: int, device: int = 0, run_slots: int = 1):
         self._lib = load_library()
         self.dtype = dtype
-        self.cfg = mt_config(max_tenants, max_requests, max_width, max_classes, arena_bytes, dtype, device)
+        self.cfg = mt_config(max_tenants, max_requests, max_width, max_classes, arena_bytes, dtype, device, run_slots)
         self._h = ctypes.c_void_p()
         st = self._lib.mt_create(ctypes.byref(self._h), ctypes.byref(self.cfg))
         if st != MT_OK:

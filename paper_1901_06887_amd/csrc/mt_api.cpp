@@ -18,6 +18,7 @@ namespace {
 
 constexpr uint32_t kMaxTenants = 2048;
 constexpr uint32_t kSegSlots = 4;
+constexpr uint32_t kMaxRunSlots = 4;      // runs in flight at once (each with its own device scratch); <= kSegSlots
 constexpr uint64_t kArenaAlign = 256;
 // profiling slots: batcher, gather, head, then gemm and gap of every layer index
 constexpr uint32_t kProfBatcher = 0, kProfGather = 1, kProfHead = 2, kProfFc = 3, kProfConv = 3 + MT_MAX_LAYERS,
@@ -42,6 +43,18 @@ struct HostTenant {
 };
 
 struct FreeBlock { uint64_t off, len; };
+
+// Device scratch of one run in flight: batch descriptors, activation buffers, logits.  A run owns
+// one slot from its batcher to its last kernel; the weights and model tables are shared.
+struct RunSlot {
+    int32_t* d_row_tenant = nullptr; uint32_t* d_row_rank = nullptr; uint32_t* d_hist_g = nullptr;
+    const void** d_row_src = nullptr; int32_t* d_pos_of = nullptr; int32_t* d_perm = nullptr;
+    uint32_t* d_M = nullptr; uint32_t* d_off = nullptr; uint32_t* d_tile_base = nullptr;
+    void* d_act[2] = {nullptr, nullptr}; float* d_logits = nullptr;
+    hipEvent_t done = nullptr;      // recorded behind the slot's last run
+    hipStream_t stream = nullptr;   // ... which was enqueued here
+    bool used = false;
+};
 
 }  // namespace
 
@@ -76,7 +89,9 @@ struct mt_ctx {
     uint32_t big_min_tiles = kBigMinTiles;   // testing: MT_BIG_MIN_TILES=1 sends every qualifying tenant-layer to big tiles
     uint32_t P_cap = 0;        // packed rows incl. per-tenant padding to 32
 
-    // device state
+    // device state.  The per-run pointers below (d_row_tenant .. d_logits) are those of the run
+    // slot bound last (bind_slot): the slot of the run being enqueued, then of the last run.
+    std::vector<RunSlot> slots;
     uint8_t* d_arena = nullptr;
     TenantDev* d_tenants = nullptr;
     LayerDev* d_layers = nullptr;
@@ -125,6 +140,13 @@ mt_status fail(mt_ctx* c, mt_status st, const char* fmt, ...)
         c->err = buf;
     }
     return st;
+}
+
+void bind_slot(mt_ctx* c, const RunSlot& r)
+{
+    c->d_row_tenant = r.d_row_tenant; c->d_row_rank = r.d_row_rank; c->d_hist_g = r.d_hist_g; c->d_row_src = r.d_row_src;
+    c->d_pos_of = r.d_pos_of; c->d_perm = r.d_perm; c->d_M = r.d_M; c->d_off = r.d_off; c->d_tile_base = r.d_tile_base;
+    c->d_act[0] = r.d_act[0]; c->d_act[1] = r.d_act[1]; c->d_logits = r.d_logits;
 }
 
 #define HIP_TRY(c, expr)                                                                    \
@@ -373,7 +395,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     if (!out || !cfg) return MT_EINVAL;
     *out = nullptr;
     if (cfg->max_tenants == 0 || cfg->max_tenants > kMaxTenants || cfg->max_requests == 0 || cfg->max_width == 0 ||
-        cfg->max_classes == 0 || cfg->arena_bytes == 0 || cfg->dtype > MT_BF16)
+        cfg->max_classes == 0 || cfg->arena_bytes == 0 || cfg->dtype > MT_BF16 || cfg->run_slots > kMaxRunSlots)
         return MT_EINVAL;
     if ((uint64_t)cfg->max_requests * 4096 > (1ull << 31)) return MT_EINVAL;   // row indices and GEMM row counts stay in 32 bits
     mt_ctx* c = new (std::nothrow) mt_ctx;
@@ -405,23 +427,28 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     CREATE_TRY(hipMemset(c->d_layers, 0, T * MT_MAX_LAYERS * sizeof(LayerDev)));
     CREATE_TRY(hipMalloc((void**)&c->d_facts, 2 * MT_MAX_LAYERS * T * 4));
     CREATE_TRY(hipMemset(c->d_facts, 0, 2 * MT_MAX_LAYERS * T * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_row_tenant, R * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_row_rank, R * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_hist_g, kHistEntries * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_row_src, R * sizeof(void*)));
-    CREATE_TRY(hipMalloc((void**)&c->d_pos_of, R * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_perm, (uint64_t)c->P_cap * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_M, T * 4));
-    CREATE_TRY(hipMemset(c->d_M, 0, T * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_off, (T + 1) * 4));
-    CREATE_TRY(hipMalloc((void**)&c->d_tile_base, (kListKinds * MT_MAX_LAYERS * (T + 1) + 1) * 4));
-    CREATE_TRY(hipMemset(c->d_tile_base, 0, (kListKinds * MT_MAX_LAYERS * (T + 1) + 1) * 4));
     CREATE_TRY(hipMalloc(&c->d_zeros, 256));
     CREATE_TRY(hipMemset(c->d_zeros, 0, 256));
-    for (int i = 0; i < 2; ++i) {
-        CREATE_TRY(hipMalloc(&c->d_act[i], (uint64_t)c->P_cap * c->S * c->elem_size));
+    c->slots.resize(std::max<uint32_t>(1, cfg->run_slots));
+    for (RunSlot& r : c->slots) {          // (a failed allocation leaves the rest null; mt_destroy frees what exists)
+        CREATE_TRY(hipMalloc((void**)&r.d_row_tenant, R * 4));
+        CREATE_TRY(hipMalloc((void**)&r.d_row_rank, R * 4));
+        CREATE_TRY(hipMalloc((void**)&r.d_hist_g, kHistEntries * 4));
+        CREATE_TRY(hipMalloc((void**)&r.d_row_src, R * sizeof(void*)));
+        CREATE_TRY(hipMalloc((void**)&r.d_pos_of, R * 4));
+        CREATE_TRY(hipMalloc((void**)&r.d_perm, (uint64_t)c->P_cap * 4));
+        CREATE_TRY(hipMalloc((void**)&r.d_M, T * 4));
+        CREATE_TRY(hipMemset(r.d_M, 0, T * 4));
+        CREATE_TRY(hipMalloc((void**)&r.d_off, (T + 1) * 4));
+        CREATE_TRY(hipMalloc((void**)&r.d_tile_base, (kListKinds * MT_MAX_LAYERS * (T + 1) + 1) * 4));
+        CREATE_TRY(hipMemset(r.d_tile_base, 0, (kListKinds * MT_MAX_LAYERS * (T + 1) + 1) * 4));
+        for (int i = 0; i < 2; ++i) {
+            CREATE_TRY(hipMalloc(&r.d_act[i], (uint64_t)c->P_cap * c->S * c->elem_size));
+        }
+        CREATE_TRY(hipMalloc((void**)&r.d_logits, (uint64_t)c->P_cap * c->C_pad * 4));
+        CREATE_TRY(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
     }
-    CREATE_TRY(hipMalloc((void**)&c->d_logits, (uint64_t)c->P_cap * c->C_pad * 4));
+    bind_slot(c, c->slots[0]);
     for (uint32_t i = 0; i < kSegSlots; ++i) {
         CREATE_TRY(hipHostMalloc((void**)&c->h_segs[i], R * sizeof(Segment), hipHostMallocMapped));
         CREATE_TRY(hipHostGetDevicePointer((void**)&c->d_segs[i], c->h_segs[i], 0));
@@ -437,9 +464,14 @@ mt_status mt_destroy(mt_ctx* c)
     if (!c->host_only) {
         (void)hipSetDevice(c->cfg.device);
         (void)hipDeviceSynchronize();
-        void* bufs[] = {c->d_arena, c->d_tenants, c->d_layers, c->d_facts, c->d_row_tenant, c->d_row_rank, c->d_hist_g, (void*)c->d_row_src, c->d_pos_of, c->d_perm,
-                        c->d_M, c->d_off, c->d_tile_base, c->d_zeros, c->d_act[0], c->d_act[1], c->d_logits};
+        void* bufs[] = {c->d_arena, c->d_tenants, c->d_layers, c->d_facts, c->d_zeros};
         for (void* p : bufs) if (p) (void)hipFree(p);
+        for (RunSlot& r : c->slots) {
+            void* rb[] = {r.d_row_tenant, r.d_row_rank, r.d_hist_g, (void*)r.d_row_src, r.d_pos_of, r.d_perm, r.d_M, r.d_off, r.d_tile_base,
+                          r.d_act[0], r.d_act[1], r.d_logits};
+            for (void* p : rb) if (p) (void)hipFree(p);
+            if (r.done) (void)hipEventDestroy(r.done);
+        }
         for (uint32_t i = 0; i < kSegSlots; ++i) {
             if (c->h_segs[i]) (void)hipHostFree(c->h_segs[i]);
             if (c->seg_event[i]) (void)hipEventDestroy(c->seg_event[i]);
@@ -583,6 +615,10 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     hipStream_t s = (hipStream_t)hip_stream;
     HIP_TRY(c, hipSetDevice(c->cfg.device));
 
+    // the run's slot of device scratch; a stream other than the one that used it last waits for that run
+    RunSlot& rs = c->slots[c->run_count % c->slots.size()];
+    if (rs.used && rs.stream != s) HIP_TRY(c, hipStreamWaitEvent(s, rs.done, 0));
+    bind_slot(c, rs);
     const uint32_t slot = (uint32_t)(c->run_count % kSegSlots);
     if (c->seg_busy[slot]) { HIP_TRY(c, hipEventSynchronize(c->seg_event[slot])); c->seg_busy[slot] = false; }
     std::memcpy(c->h_segs[slot], c->pending.data(), c->pending.size() * sizeof(Segment));
@@ -685,6 +721,8 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
 
     HIP_TRY(c, hipEventRecord(c->seg_event[slot], s));
     c->seg_busy[slot] = true;
+    HIP_TRY(c, hipEventRecord(rs.done, s));
+    rs.used = true; rs.stream = s;
     c->run_count++;
     c->last_stream = s;
     c->pending.clear();
@@ -762,9 +800,11 @@ mt_status mt_debug_poison(mt_ctx* c)
     HIP_TRY(c, hipSetDevice(c->cfg.device));
     HIP_TRY(c, hipDeviceSynchronize());
     const size_t act_bytes = (size_t)c->P_cap * c->S * c->elem_size;
-    HIP_TRY(c, hipMemset(c->d_act[0], 0xFF, act_bytes));
-    HIP_TRY(c, hipMemset(c->d_act[1], 0xFF, act_bytes));
-    HIP_TRY(c, hipMemset(c->d_logits, 0xFF, (size_t)c->P_cap * c->C_pad * 4));
+    for (RunSlot& r : c->slots) {
+        HIP_TRY(c, hipMemset(r.d_act[0], 0xFF, act_bytes));
+        HIP_TRY(c, hipMemset(r.d_act[1], 0xFF, act_bytes));
+        HIP_TRY(c, hipMemset(r.d_logits, 0xFF, (size_t)c->P_cap * c->C_pad * 4));
+    }
     HIP_TRY(c, hipDeviceSynchronize());
     return MT_OK;
 }

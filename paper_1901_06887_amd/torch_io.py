@@ -25,7 +25,7 @@ def specs_of(layers) -> list:
 
 
 def context_for(tenants: Dict[int, object], dtype: str, max_requests: int, device: int = 0,
-                max_tenants: Optional[int] = None, arena_slack: float = 1.05) -> B.Context:
+                max_tenants: Optional[int] = None, arena_slack: float = 1.05, run_slots: int = 1) -> B.Context:
     """A context sized for the given tenant models (objects with .layers/.weights/.biases)."""
     es = 4 if dtype == "f32" else 2
     width, classes, arena = 64, 1, 0
@@ -43,7 +43,7 @@ def context_for(tenants: Dict[int, object], dtype: str, max_requests: int, devic
         classes = max(classes, m.layers[-1].out_len())
     T = max_tenants if max_tenants is not None else (max(tenants) + 1 if tenants else 1)
     return B.Context(T, max_requests, width, classes, int(arena * arena_slack) + (1 << 20),
-                     B.MT_F32 if dtype == "f32" else B.MT_BF16, device)
+                     B.MT_F32 if dtype == "f32" else B.MT_BF16, device, run_slots)
 
 
 def register_tenants(ctx: B.Context, tenants: Dict[int, object]):

@@ -14,8 +14,8 @@ from paper_1901_06887_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def host_ctx(dtype=B.MT_BF16, arena=1 << 22, max_width=4096, max_classes=100, max_requests=1024, max_tenants=16):
-    return B.Context(max_tenants, max_requests, max_width, max_classes, arena, dtype, device=-1)
+def host_ctx(dtype=B.MT_BF16, arena=1 << 22, max_width=4096, max_classes=100, max_requests=1024, max_tenants=16, run_slots=1):
+    return B.Context(max_tenants, max_requests, max_width, max_classes, arena, dtype, device=-1, run_slots=run_slots)
 
 
 def fc(k, n, act=B.MT_ACT_NONE):
@@ -48,13 +48,13 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_layouts_match_header_sizes():
     assert ctypes.sizeof(B.mt_layer_spec) == 40
-    assert ctypes.sizeof(B.mt_config) == 32
+    assert ctypes.sizeof(B.mt_config) == 40
     assert ctypes.sizeof(B.mt_outputs) == 40
 
 
 def test_create_rejects_bad_config():
     for kw in (dict(max_tenants=0), dict(max_requests=0), dict(max_width=0), dict(max_classes=0), dict(arena=0),
-               dict(max_tenants=5000), dict(dtype=7)):
+               dict(max_tenants=5000), dict(dtype=7), dict(run_slots=5)):
         with pytest.raises(B.MtError) as e:
             host_ctx(**kw)
         assert e.value.status == 1

@@ -231,3 +231,34 @@ def test_large_batch_in_several_submissions():
     assert np.all(lb[rej] == -1) and np.all(nc[rej] == 0) and np.all(lg[rej] == 0)
     assert np.array_equal(lg[~rej], ref[0][~rej]) and np.array_equal(lb[~rej], ref[2][~rej])
     ctx.close()
+
+
+def test_two_runs_in_flight_on_two_streams():
+    # run_slots = 2: consecutive runs alternate between two sets of device scratch and may overlap on
+    # different streams; every run still gives exactly the answers of a run on its own
+    wa = wl.c2(n_tenants=6, n_requests=700, dims=(100, 192, 136, 10), seed=51)
+    wb = wl.Workload("other batch", wa.dtype, wa.tenants, wl.c2(n_tenants=6, n_requests=450, dims=(100, 192, 136, 10), seed=52).tenant_ids,
+                     wl.c2(n_tenants=6, n_requests=450, dims=(100, 192, 136, 10), seed=52).inputs)
+    single = make_context(wa)
+    ref_a, ref_b = gpu_run(single, wa), gpu_run(single, wb)
+    single.close()
+    compare(wa, ref_a, oracle_rows(wa), what="batch a"); compare(wb, ref_b, oracle_rows(wb), what="batch b")
+
+    ctx = mt.context_for(wa.tenants, wa.dtype, 700, run_slots=2)
+    mt.register_tenants(ctx, wa.tenants)
+    dev = [(torch.from_numpy(w.tenant_ids).cuda(), torch_io.to_device(w.inputs, w.dtype)) for w in (wa, wb)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    outs = []
+    for i in range(6):                                   # a, b, a, b, ... without waiting in between
+        ids, x = dev[i % 2]
+        outs.append(mt.serve(ctx, ids, x, stream=streams[i % 2]))
+    # a third stream takes a slot that another stream used last: it has to wait for that run
+    outs.append(mt.serve(ctx, *dev[0], stream=torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for i, o in enumerate(outs):
+        ref = ref_a if i % 2 == 0 else ref_b
+        assert np.array_equal(o.logits.cpu().numpy().astype(np.float64), ref[0]), i
+        assert np.array_equal(o.labels.cpu().numpy(), ref[2]), i
+    assert ctx.last_counts().sum() == 700
+    ctx.close()

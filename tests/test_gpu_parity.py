@@ -142,6 +142,28 @@ def test_c2_full():
     run_and_compare(wl.c2(), "c2")
 
 
+def test_c2_full_three_runs_in_flight():
+    # the configuration the benchmark times: three runs in flight, each on a stream of its own
+    import torch
+    import paper_1901_06887_amd as mt
+    from paper_1901_06887_amd import torch_io
+    w = wl.c2()
+    ctx = mt.context_for(w.tenants, w.dtype, w.n_requests, run_slots=3)
+    mt.register_tenants(ctx, w.tenants)
+    d_ids, d_x = torch.from_numpy(w.tenant_ids).cuda(), torch_io.to_device(w.inputs, w.dtype)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    ctx.debug_poison()
+    torch.cuda.synchronize()
+    outs = [mt.serve(ctx, d_ids, d_x, stream=streams[i % 3]) for i in range(6)]
+    torch.cuda.synchronize()
+    orc = oracle_rows(w)
+    for i, o in enumerate(outs):
+        gpu = (o.logits.cpu().numpy().astype(np.float64), o.probs.cpu().numpy().astype(np.float64),
+               o.labels.cpu().numpy(), o.n_classes.cpu().numpy())
+        compare(w, gpu, orc, what="c2, run %d of 6 in flight" % i)
+    ctx.close()
+
+
 def test_c3_full_sampled():
     w = wl.c3()
     ctx = make_context(w)
