@@ -169,6 +169,41 @@ mt_status mt_run(mt_ctx* ctx, void* hip_stream, const mt_outputs* out, uint32_t*
  * stream it ran on).  For tests and accounting. */
 mt_status mt_last_counts(mt_ctx* ctx, uint32_t* counts);
 
+/* Per-tenant accounting.  A request's cost follows from the model description alone
+ * (paper section 3.2: the flops of every layer are known a priori), so billing by work
+ * done (section 1.3) needs only a count of the requests served, which the batcher keeps
+ * on the device.  flops_per_request = 2 x multiply-accumulates over all layers with the
+ * true dimensions (convolutions count all nine taps at every output pixel);
+ * weight_bytes = the parameters (true dimensions, the context's element type) and fp32
+ * biases; io_bytes_per_request = the request's input, every hidden activation written
+ * once and read once, logits, probabilities and label.
+ * requests / runs count what every mt_run enqueued so far has served of this tenant and
+ * in how many runs it had at least one request (the call synchronises the device; 0 for a
+ * host-only context).  Errors: MT_EINVAL, MT_ENOTFOUND (no model), MT_EDEVICE. */
+typedef struct {
+    uint64_t requests, runs;
+    uint64_t flops_per_request, weight_bytes, io_bytes_per_request;
+} mt_tenant_account;
+mt_status mt_tenant_account_get(mt_ctx* ctx, uint32_t tenant, mt_tenant_account* out);
+
+/* Predicted cost of one mt_run that serves counts[t] requests of tenant t (HOST array of
+ * max_tenants entries; tenants without a model must have 0), from the registered
+ * descriptors alone, before anything is enqueued (section 3.2: inference is a fixed
+ * sequence of operations, so its cost is predictable; an admission controller picks
+ * what enters the next run from this).  flops and hbm_bytes are the algorithmic work
+ * (weights of active tenants read once, activations written once and read once);
+ * launches is the number of kernels mt_run will enqueue; device_ms is the predicted
+ * time of the run alone on the GPU, from a per-kernel model (fixed cost per launch +
+ * bytes through HBM + bytes re-read through L2, or tile rounds for compute-bound
+ * launches) whose constants were fitted on one MI355X.  Works on a host-only context.
+ * Errors: MT_EINVAL (null, or more rows than max_requests), MT_ENOTFOUND (rows for a
+ * tenant without a model). */
+typedef struct {
+    double flops, hbm_bytes, device_ms;
+    uint32_t rows, launches;
+} mt_run_estimate;
+mt_status mt_estimate_run(mt_ctx* ctx, const uint32_t* counts, mt_run_estimate* out);
+
 mt_status mt_get_stats(const mt_ctx* ctx, mt_stats* out);
 
 /* Per-kernel timing of mt_run, for measurement.  While enabled, mt_run brackets every

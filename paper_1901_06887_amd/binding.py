@@ -42,6 +42,16 @@ class mt_config(ctypes.Structure):
                 ("run_slots", ctypes.c_uint32)]
 
 
+class mt_tenant_account(ctypes.Structure):
+    _fields_ = [("requests", ctypes.c_uint64), ("runs", ctypes.c_uint64), ("flops_per_request", ctypes.c_uint64),
+                ("weight_bytes", ctypes.c_uint64), ("io_bytes_per_request", ctypes.c_uint64)]
+
+
+class mt_run_estimate(ctypes.Structure):
+    _fields_ = [("flops", ctypes.c_double), ("hbm_bytes", ctypes.c_double), ("device_ms", ctypes.c_double),
+                ("rows", ctypes.c_uint32), ("launches", ctypes.c_uint32)]
+
+
 class mt_outputs(ctypes.Structure):
     _fields_ = [("labels", ctypes.c_void_p), ("probs", ctypes.c_void_p), ("logits", ctypes.c_void_p),
                 ("n_classes", ctypes.c_void_p), ("capacity", ctypes.c_uint32), ("row_stride", ctypes.c_uint32)]
@@ -80,6 +90,8 @@ def load_library() -> ctypes.CDLL:
     L.mt_run.argtypes = [vp, vp, ctypes.POINTER(mt_outputs), ctypes.POINTER(u32)]
     L.mt_last_counts.argtypes = [vp, ctypes.POINTER(u32)]
     L.mt_get_stats.argtypes = [vp, ctypes.POINTER(mt_stats)]
+    L.mt_tenant_account_get.argtypes = [vp, u32, ctypes.POINTER(mt_tenant_account)]
+    L.mt_estimate_run.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(mt_run_estimate)]
     L.mt_debug_poison.argtypes = [vp]
     L.mt_debug_copy.argtypes = [vp, vp, ctypes.c_uint64, vp]
     L.mt_debug_big_tile_rows.argtypes = [u32, u32]
@@ -90,7 +102,7 @@ def load_library() -> ctypes.CDLL:
     L.mt_last_error.restype = ctypes.c_char_p
     L.mt_version.restype = ctypes.c_char_p
     for name in ("mt_create", "mt_destroy", "mt_register_model", "mt_unregister_model", "mt_submit",
-                 "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_debug_poison", "mt_debug_copy",
+                 "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_tenant_account_get", "mt_estimate_run", "mt_debug_poison", "mt_debug_copy",
                  "mt_set_profiling", "mt_get_profile"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -198,6 +210,17 @@ class Context:
 
     def debug_poison(self):
         self._check(self._lib.mt_debug_poison(self._h))
+
+    def tenant_account(self, tenant: int) -> dict:
+        a = mt_tenant_account()
+        self._check(self._lib.mt_tenant_account_get(self._h, tenant, ctypes.byref(a)))
+        return {k: int(getattr(a, k)) for k, _ in mt_tenant_account._fields_}
+
+    def estimate_run(self, counts) -> dict:
+        arr = (ctypes.c_uint32 * self.cfg.max_tenants)(*[int(x) for x in counts])
+        e = mt_run_estimate()
+        self._check(self._lib.mt_estimate_run(self._h, arr, ctypes.byref(e)))
+        return {k: getattr(e, k) for k, _ in mt_run_estimate._fields_}
 
     def stats(self) -> dict:
         s = mt_stats()

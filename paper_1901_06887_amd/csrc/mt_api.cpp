@@ -95,6 +95,7 @@ struct mt_ctx {
     uint8_t* d_arena = nullptr;
     TenantDev* d_tenants = nullptr;
     LayerDev* d_layers = nullptr;
+    uint64_t* d_served = nullptr;      // [max_tenants][2]: requests served, runs with at least one request (accounting)
     uint32_t* d_facts = nullptr;       // [max_tenants][MT_MAX_LAYERS][2]: the batcher's view of the layers (BatchArgs::facts)
     int32_t* d_row_tenant = nullptr;
     uint32_t* d_row_rank = nullptr;
@@ -427,6 +428,8 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     CREATE_TRY(hipMemset(c->d_layers, 0, T * MT_MAX_LAYERS * sizeof(LayerDev)));
     CREATE_TRY(hipMalloc((void**)&c->d_facts, 2 * MT_MAX_LAYERS * T * 4));
     CREATE_TRY(hipMemset(c->d_facts, 0, 2 * MT_MAX_LAYERS * T * 4));
+    CREATE_TRY(hipMalloc((void**)&c->d_served, T * 16));
+    CREATE_TRY(hipMemset(c->d_served, 0, T * 16));
     CREATE_TRY(hipMalloc(&c->d_zeros, 256));
     CREATE_TRY(hipMemset(c->d_zeros, 0, 256));
     c->slots.resize(std::max<uint32_t>(1, cfg->run_slots));
@@ -464,7 +467,7 @@ mt_status mt_destroy(mt_ctx* c)
     if (!c->host_only) {
         (void)hipSetDevice(c->cfg.device);
         (void)hipDeviceSynchronize();
-        void* bufs[] = {c->d_arena, c->d_tenants, c->d_layers, c->d_facts, c->d_zeros};
+        void* bufs[] = {c->d_arena, c->d_tenants, c->d_layers, c->d_facts, c->d_served, c->d_zeros};
         for (void* p : bufs) if (p) (void)hipFree(p);
         for (RunSlot& r : c->slots) {
             void* rb[] = {r.d_row_tenant, r.d_row_rank, r.d_hist_g, (void*)r.d_row_src, r.d_pos_of, r.d_perm, r.d_M, r.d_off, r.d_tile_base,
@@ -634,7 +637,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     BatchArgs b{};
     b.segs = c->d_segs[slot]; b.n_segs = n_segs; b.R = R; b.T = T; b.n_layer_slots = c->n_layer_slots;
     b.first = c->pending[0]; b.row_src = c->d_row_src; b.elem_size = c->elem_size;
-    b.tenants = c->d_tenants; b.facts = c->d_facts;
+    b.tenants = c->d_tenants; b.facts = c->d_facts; b.served = (unsigned long long*)c->d_served;
     {   // large batches are ranked by a kernel of their own, where its per-workgroup histograms fit the batcher's LDS
         uint32_t Tp = 64;
         while (Tp < T) Tp <<= 1;
@@ -739,6 +742,180 @@ mt_status mt_last_counts(mt_ctx* c, uint32_t* counts)
     HIP_TRY(c, hipSetDevice(c->cfg.device));
     HIP_TRY(c, hipStreamSynchronize(c->last_stream));
     HIP_TRY(c, hipMemcpy(counts, c->d_M, (size_t)c->cfg.max_tenants * 4, hipMemcpyDeviceToHost));
+    return MT_OK;
+}
+
+// ---- accounting and cost prediction (paper section 3.2) -------------------------------------
+namespace {
+
+// Algorithmic cost of one request of a model, from its description alone.
+void request_cost(const mt_ctx* c, const HostTenant& ht, uint64_t* flops, uint64_t* weight_bytes, uint64_t* io_bytes)
+{
+    const uint64_t es = c->elem_size;
+    *flops = *weight_bytes = *io_bytes = 0;
+    for (uint32_t l = 0; l < ht.n_layers; ++l) {
+        const mt_layer_spec& s = ht.layers[l].spec;
+        const LayerDev& d = ht.layers[l].dev;
+        uint64_t in_len = 0;
+        if (s.kind == MT_FC) {
+            *flops += 2ull * s.in_features * s.out_features;
+            *weight_bytes += (uint64_t)s.in_features * s.out_features * es + (uint64_t)s.out_features * 4;
+            in_len = s.in_features;
+        } else if (s.kind == MT_CONV2D) {
+            *flops += 2ull * d.rows_per_req * 9 * s.in_features * s.out_features;
+            *weight_bytes += 9ull * s.in_features * s.out_features * es + (uint64_t)s.out_features * 4;
+            in_len = (uint64_t)s.in_h * s.in_w * s.in_features;
+        } else {
+            in_len = (uint64_t)s.in_h * s.in_w * s.in_features;
+        }
+        if (l == 0) *io_bytes += in_len * es;
+        if (l + 1 < ht.n_layers) *io_bytes += 2ull * d.out_len * es;
+        else *io_bytes += 2ull * d.out_len * 4 + 4;
+    }
+}
+
+// Per-kernel time model, microseconds and megabytes; constants fitted on one MI355X (the
+// measurements are in the design notes).  A streaming FC launch costs a fixed part, its bytes
+// from HBM (weights of the active tenants) and the bytes its tiles re-read through L2 (weight
+// panels re-read by further row tiles, activation rows re-read by every column group; three
+// times that when layer 0 gathers the submitted rows in 16-byte pieces); it cannot be shorter
+// than the chain of dependent loads through K of one tile.
+// Weights that fit the 256 MB memory-side cache and are read by every run stream faster than
+// weights that come from HBM every time (steady serving of the same tenants is assumed).
+constexpr double kUsLaunchGap = 4.0;
+constexpr double kUsFcFixed = 3.7, kUsPerMbCached = 0.132, kUsPerMbHbm = 0.18, kCachedMb = 240.0;
+constexpr double kUsPerMbL2 = 0.056, kUsFcChainFixed = 4.0, kUsPerKStep = 0.12;
+constexpr double kUsBigFixed = 4.0, kUsBigTileFixed = 7.0, kUsBigTilePer4096 = 120.0;
+constexpr double kUsConvFixed = 5.0, kConvMbPerUs = 3.7, kConvMflopPerUs = 0.5e3;      // 3.7 TB/s, 0.5 PFLOP/s
+constexpr double kUsSmallFixed = 3.0, kCopyMbPerUs = 3.7, kHeadMbPerUs = 5.7, kUsHeadPerRow = 0.0008;
+constexpr double kComputeUnits = 256.0;
+
+}  // namespace
+
+mt_status mt_tenant_account_get(mt_ctx* c, uint32_t tenant, mt_tenant_account* out)
+{
+    if (!c || !out) return MT_EINVAL;
+    if (tenant >= c->cfg.max_tenants) return fail(c, MT_EINVAL, "tenant %u is outside 0..%u", tenant, c->cfg.max_tenants - 1);
+    if (!c->tenants[tenant].registered) return fail(c, MT_ENOTFOUND, "tenant %u has no model", tenant);
+    *out = mt_tenant_account{};
+    request_cost(c, c->tenants[tenant], &out->flops_per_request, &out->weight_bytes, &out->io_bytes_per_request);
+    if (!c->host_only) {
+        uint64_t counters[2] = {0, 0};
+        HIP_TRY(c, hipSetDevice(c->cfg.device));
+        HIP_TRY(c, hipDeviceSynchronize());
+        HIP_TRY(c, hipMemcpy(counters, c->d_served + 2 * (size_t)tenant, sizeof counters, hipMemcpyDeviceToHost));
+        out->requests = counters[0]; out->runs = counters[1];
+    }
+    return MT_OK;
+}
+
+mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* out)
+{
+    if (!c || !counts || !out) return MT_EINVAL;
+    *out = mt_run_estimate{};
+    const uint32_t T = c->cfg.max_tenants;
+    const double es = c->elem_size, MB = 1e6;
+    uint64_t R = 0;
+    for (uint32_t t = 0; t < T; ++t) {
+        if (!counts[t]) continue;
+        if (!c->tenants[t].registered) return fail(c, MT_ENOTFOUND, "tenant %u has no model", t);
+        R += counts[t];
+        uint64_t f, wb, io;
+        request_cost(c, c->tenants[t], &f, &wb, &io);
+        out->flops += (double)f * counts[t];
+        out->hbm_bytes += (double)wb + (double)io * counts[t];
+    }
+    if (R > c->cfg.max_requests) return fail(c, MT_EINVAL, "%llu rows exceed max_requests %u", (unsigned long long)R, c->cfg.max_requests);
+    out->rows = (uint32_t)R;
+    if (R == 0) return MT_OK;
+
+    // the same decisions as mt_run and the batcher take
+    const double run_flops = 2.0 * R * (c->n_registered ? c->sum_macs / c->n_registered : 0.0);
+    const bool big_enabled = R >= (uint64_t)kBigMinBatch && run_flops >= kRidgeFlopsPerByte * (double)c->arena_used;
+    const bool big_possible = big_enabled && c->max_nt[2][0] > 0 && tile_bound(c, 2, 0, R) >= c->big_min_tiles;
+    const bool fuse_gather = c->any_fc_first && c->fc_first_chunked && !c->no_fused_gather && !big_possible;
+    const bool fuse_head = !c->no_fused_head && !c->fc_split_k && c->min_reg_classes <= (uint32_t)kBrickRows;
+    uint32_t Tp = 64;
+    while (Tp < T) Tp <<= 1;
+    const uint64_t groups_r = (R + kRankRows - 1) / kRankRows;
+    const bool spread = R >= (uint64_t)kRankMinRows && T <= (uint32_t)kRankMaxTenants && groups_r * Tp <= (uint64_t)kHistEntries;
+
+    double weights_mb = 0.0;                 // weights this run reads, all layers
+    for (uint32_t t = 0; t < T; ++t) {
+        if (!counts[t]) continue;
+        uint64_t f, wb, io;
+        request_cost(c, c->tenants[t], &f, &wb, &io);
+        weights_mb += wb / MB;
+    }
+    const double us_per_mb = weights_mb <= kCachedMb ? kUsPerMbCached : kUsPerMbHbm;
+    double us = 0.0;
+    uint32_t launches = 0;
+    auto launch = [&](double t) { us += t + (launches ? kUsLaunchGap : 0.0); ++launches; };
+    if (spread) { launch(20.0 + 0.15 * R / 1024.0); launches += 2; }       // ranking, scan, placement
+    else launch(10.0 + 0.7 * R / 1024.0);
+
+    double fc_in_mb = 0.0, img_in_mb = 0.0, img_out_mb = 0.0;
+    for (uint32_t t = 0; t < T; ++t) {
+        if (!counts[t]) continue;
+        const HostTenant& ht = c->tenants[t];
+        if (ht.dev.in_layout == kLayoutBricks) fc_in_mb += counts[t] * (double)ht.dev.in_len * es / MB;
+        else { img_in_mb += counts[t] * (double)ht.dev.in_len * es / MB; img_out_mb += counts[t] * (double)ht.dev.in_fill * es / MB; }
+    }
+    if (c->any_fc_first && !fuse_gather) launch(kUsSmallFixed + 2.0 * fc_in_mb / kCopyMbPerUs);
+    if (c->any_conv_first) launch(kUsSmallFixed + (img_in_mb + img_out_mb) / kCopyMbPerUs);
+
+    for (uint32_t l = 0; l < c->n_layer_slots; ++l) {
+        // which tenants take big tiles at this layer index (the batcher's rule)
+        uint64_t big_tiles = 0;
+        if (big_enabled && c->max_nt[2][l] > 0)
+            for (uint32_t t = 0; t < T; ++t) {
+                if (!counts[t] || l >= c->tenants[t].n_layers) continue;
+                const LayerDev& d = c->tenants[t].layers[l].dev;
+                if (d.kind == MT_FC && fc_is_big(counts[t], d.N_pad))
+                    big_tiles += (uint64_t)((big_rows(counts[t]) + kBigTile - 1) / kBigTile) * ((d.N_pad + kBigTile - 1) / kBigTile);
+            }
+        const bool big_layer = big_tiles >= c->big_min_tiles;
+        double w_mb = 0.0, l2_mb = 0.0, chain = 0.0, big_us = 0.0, conv_mb = 0.0, conv_mflop = 0.0, gap_mb = 0.0;
+        double big_rounds_k = 0.0;
+        for (uint32_t t = 0; t < T; ++t) {
+            if (!counts[t] || l >= c->tenants[t].n_layers) continue;
+            const LayerDev& d = c->tenants[t].layers[l].dev;
+            const double M = counts[t];
+            if (d.kind == MT_FC) {
+                const bool big = big_layer && fc_is_big(counts[t], d.N_pad);
+                const uint32_t Mb = big ? big_rows(counts[t]) : 0, Ms = counts[t] - Mb;
+                if (big) big_rounds_k += (double)((Mb + kBigTile - 1) / kBigTile) * ((d.N_pad + kBigTile - 1) / kBigTile) * d.K;
+                if (Ms) {
+                    const uint32_t groups = fc_groups(d.N_pad, c->fc_split_k), trows = fc_tile_rows(d.N_pad, c->fc_split_k);
+                    const double panel_mb = (double)d.N_pad * d.K * es / MB / groups;
+                    const double row_tiles = (Ms + trows - 1) / trows;
+                    const double act_mb = (double)Ms * d.K * es / MB;
+                    w_mb += panel_mb * groups;
+                    l2_mb += panel_mb * groups * (row_tiles - 1) + act_mb * groups * ((l == 0 && fuse_gather) ? 3.0 : 1.0);
+                    const uint32_t nblk = d.N_pad / kBrickRows, split = c->fc_split_k ? 1u : (nblk >= 3 ? 4u : nblk);
+                    const double k_steps = d.K * es / 32.0 / (4 / split);       // bricks one wave walks (the waves split K when split < 4)
+                    chain = std::max(chain, kUsFcChainFixed + kUsPerKStep * k_steps);
+                }
+            } else if (d.kind == MT_CONV2D) {
+                conv_mb += (M * ((double)d.in_h * d.in_w * d.cin + d.out_len) * es + (double)d.N_pad * d.K * es) / MB;
+                conv_mflop += 2.0 * M * d.rows_per_req * d.k_valid * d.N / 1e6;
+            } else {
+                gap_mb += M * ((double)d.in_h * d.in_w * d.cin + d.out_len) * es / MB;
+            }
+        }
+        if (c->max_nt[0][l] > 0) launch(std::max(chain, kUsFcFixed + us_per_mb * w_mb + kUsPerMbL2 * l2_mb));
+        if (c->max_nt[1][l] > 0) launch(kUsConvFixed + std::max(conv_mb / kConvMbPerUs, conv_mflop / kConvMflopPerUs));
+        if (big_enabled && c->max_nt[2][l] > 0 && tile_bound(c, 2, l, R) >= c->big_min_tiles) {
+            // tiles share the chip in rounds of one per compute unit; a tile's time grows with K
+            if (big_layer) big_us = std::ceil(big_tiles / kComputeUnits) * kUsBigTileFixed + big_rounds_k / kComputeUnits / 4096.0 * kUsBigTilePer4096;
+            launch(kUsBigFixed + big_us);
+        }
+        if (c->has_gap[l]) launch(kUsSmallFixed + gap_mb / kCopyMbPerUs);
+    }
+    if (!fuse_head || c->max_reg_classes > (uint32_t)kBrickRows)
+        launch(kUsSmallFixed + std::max(3.0 * R * c->C_pad * 4.0 / MB / kHeadMbPerUs, kUsHeadPerRow * R));
+    out->launches = launches;
+    out->device_ms = us * 1e-3;
     return MT_OK;
 }
 

@@ -119,6 +119,7 @@ struct BatchArgs {
     // pooling, or no such layer), bit 31: convolution, bit 30: FC tiles of 32 rows instead of 64.
     // Word 1: GEMM rows per request (convolution) or padded outputs (FC).
     const uint32_t* facts;
+    unsigned long long* served;   // [T][2]: requests served and runs with requests, per tenant, over all runs (atomic adds: runs may overlap)
     int32_t* row_tenant;   // [R] tenant of each submitted row, -1 if rejected
     uint32_t* row_rank;    // [R] scratch
     // Large batches are ranked by a kernel of their own, kRankRows rows per workgroup, before the

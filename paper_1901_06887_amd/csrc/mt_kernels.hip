@@ -376,6 +376,7 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     const uint32_t total = block_exclusive_scan(offl, Tp, tmp);
     for (uint32_t t = tid; t < T; t += kBatchThreads) {
         a.M[t] = Ml[t]; a.off[t] = offl[t];
+        if (Ml[t]) { atomicAdd(&a.served[2 * t], (unsigned long long)Ml[t]); atomicAdd(&a.served[2 * t + 1], 1ull); }
         const uint32_t pend = offl[t] + ceil_div(Ml[t], kBrickRows) * kBrickRows;
         for (uint32_t p = offl[t] + Ml[t]; p < pend; ++p) a.perm[p] = -1;      // padding rows of the last block
     }

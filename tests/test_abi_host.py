@@ -156,3 +156,37 @@ def test_bf16_weights_must_be_representable():
     specs = [fc(64, 10)]
     with pytest.raises(ValueError):
         c.register_model(0, specs, [np.full((10, 64), 0.1, dtype=np.float32)], [None])
+
+
+def test_request_cost_and_run_estimate_follow_the_model_description():
+    # section 3.2: the cost of a request is known from the model description alone.  The library's
+    # figures must equal the closed forms the workload module computes from the layer shapes.
+    import paper_1901_06887_amd as mt
+    import workloads as wl
+    for w in (wl.c2(n_tenants=5, n_requests=300, dims=(100, 192, 136, 10)), wl.c4(n_tenants=3, n_requests=20, hw=8, chans=(3, 16, 24, 40), classes=5)):
+        ctx = mt.context_for(w.tenants, w.dtype, w.n_requests, device=-1)
+        mt.register_tenants(ctx, w.tenants)
+        counts = np.bincount(w.tenant_ids, minlength=ctx.cfg.max_tenants)
+        est = ctx.estimate_run(counts)
+        cost = wl.algorithmic_cost(w)
+        assert est["rows"] == w.n_requests and est["flops"] == cost["flops"] and est["hbm_bytes"] == cost["bytes"]
+        assert est["launches"] >= 1 + len(next(iter(w.tenants.values())).layers) - (w.name == "c4") and est["device_ms"] > 0
+        one = wl.Workload("one", w.dtype, w.tenants, w.tenant_ids[:1], w.inputs[:1])
+        c1 = wl.algorithmic_cost(one)
+        acc = ctx.tenant_account(int(w.tenant_ids[0]))
+        assert acc["flops_per_request"] == c1["flops"] and acc["weight_bytes"] == c1["weight_bytes"]
+        assert acc["io_bytes_per_request"] == c1["act_bytes"] + c1["out_bytes"] and acc["requests"] == 0
+        # more work never costs less; an empty run costs nothing
+        assert ctx.estimate_run(counts * 2 // 3)["device_ms"] <= est["device_ms"]
+        assert ctx.estimate_run(counts * 0)["device_ms"] == 0
+        with pytest.raises(B.MtError) as e:
+            ctx.estimate_run(counts * 50)
+        assert e.value.status == 1
+        ctx.unregister_model(0)
+        with pytest.raises(B.MtError) as e:
+            ctx.estimate_run(counts + 1)
+        assert e.value.status == 3
+        with pytest.raises(B.MtError) as e:
+            ctx.tenant_account(0)
+        assert e.value.status == 3
+        ctx.close()

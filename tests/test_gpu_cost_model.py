@@ -1,0 +1,73 @@
+"""Accounting and cost prediction on the GPU (paper section 3.2: the cost of inference is known a
+priori; section 1.3: users should pay for the work done).  The per-tenant counters the batcher
+keeps must equal the submitted rows exactly; the run-time estimate, computed from the registered
+descriptors before anything is enqueued, must be close to the measured device time of the run."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1901_06887_amd as mt
+import workloads as wl
+from paper_1901_06887_amd import torch_io
+
+pytestmark = pytest.mark.gpu
+
+# The estimate is a per-kernel model with constants fitted on one MI355X; machines of the pool
+# differ by several percent and the model's own error is up to ~15 % per kernel.
+REL_TOL = 0.20          # the five mixes the constants were fitted on
+REL_TOL_OTHER = 0.30    # mixes the fit has not seen
+
+
+def other_mixes():
+    c2 = wl.c2()
+    uniform = wl.Workload("c2-uniform", c2.dtype, c2.tenants, np.random.default_rng(9).permutation(np.arange(4096, dtype=np.int32) % 64), c2.inputs)
+    return {"c2-uniform": lambda: uniform, "c3-other-seed": lambda: wl.c3(seed=11), "c3-half-batch": lambda: wl.c3(n_requests=8192),
+            "c4-half-batch": lambda: wl.c4(n_requests=1024), "c5-half-batch": lambda: wl.c5(n_requests=16384),
+            "c5-six-tenants": lambda: wl.c5(n_tenants=6, n_requests=24576)}
+
+
+def test_served_requests_are_counted_per_tenant():
+    w = wl.c2(n_tenants=6, n_requests=300, dims=(100, 192, 136, 10))
+    ctx = mt.context_for(w.tenants, w.dtype, w.n_requests, max_tenants=8, run_slots=2)
+    mt.register_tenants(ctx, w.tenants)
+    d_x = torch_io.to_device(w.inputs, w.dtype)
+    ids = w.tenant_ids.copy()
+    ids[[3, 77]] = [7, -1]                                  # two rejected rows: served for nobody
+    only_some = np.where(ids == 4, 2, ids)                  # second mix: tenant 4 has no traffic
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for i, v in enumerate((ids, only_some, ids)):
+        mt.serve(ctx, torch.from_numpy(v.astype(np.int32)).cuda(), d_x, stream=streams[i % 2])
+    torch.cuda.synchronize()
+    for t in range(6):
+        acc = ctx.tenant_account(t)
+        expect = 2 * int((ids == t).sum()) + int((only_some == t).sum())
+        assert acc["requests"] == expect, t
+        assert acc["runs"] == (2 if t == 4 else 3), t
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5", "c2-uniform", "c3-other-seed", "c3-half-batch", "c4-half-batch",
+                                  "c5-half-batch", "c5-six-tenants"])
+def test_estimated_run_time_matches_the_measured_one(name):
+    w = wl.CONFIGS[name]() if name in wl.CONFIGS else other_mixes()[name]()
+    ctx = mt.context_for(w.tenants, w.dtype, w.n_requests)
+    mt.register_tenants(ctx, w.tenants)
+    est = ctx.estimate_run(np.bincount(w.tenant_ids, minlength=ctx.cfg.max_tenants))
+    d_ids, d_x = torch.from_numpy(w.tenant_ids).cuda(), torch_io.to_device(w.inputs, w.dtype)
+    out = torch_io.alloc_outputs(w.n_requests, ctx.cfg.max_classes)
+    for _ in range(5):
+        mt.serve(ctx, d_ids, d_x, out=out)
+    torch.cuda.synchronize()
+    assert est["launches"] == ctx.stats()["last_run_launches"]
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+    for e0, e1 in ev:
+        e0.record()
+        mt.serve(ctx, d_ids, d_x, out=out)
+        e1.record()
+    torch.cuda.synchronize()
+    measured = float(np.median([e0.elapsed_time(e1) for e0, e1 in ev]))
+    ratio = est["device_ms"] / measured
+    print("%s: estimated %.4f ms, measured %.4f ms, ratio %.2f" % (name, est["device_ms"], measured, ratio), flush=True)
+    assert abs(ratio - 1.0) <= (REL_TOL if name in wl.CONFIGS else REL_TOL_OTHER)
+    ctx.close()
