@@ -87,6 +87,13 @@ typedef struct {
                                own (batch interleaving, footnote of paper section 1.3): 0
                                or 1 = one; at most 4.  Every slot has its own batch
                                descriptors and activation buffers; the weights are shared */
+    uint32_t cache;         /* 1: the arena is a cache of the registered models (paper
+                               section 3.3): every model's packed weights stay in pinned
+                               host memory, registering or prefetching a model when the
+                               arena is full evicts the models used least recently, and
+                               evicted models are reloaded on demand (mt_prefetch).
+                               0: every registered model stays resident; a full arena
+                               is MT_ENOMEM                                              */
 } mt_config;
 
 /* Where mt_run writes predictions.  All DEVICE memory owned by the caller, valid
@@ -169,6 +176,29 @@ mt_status mt_run(mt_ctx* ctx, void* hip_stream, const mt_outputs* out, uint32_t*
  * stream it ran on).  For tests and accounting. */
 mt_status mt_last_counts(mt_ctx* ctx, uint32_t* counts);
 
+/* Model cache (cfg.cache; paper section 3.3: a worker alternates between many tenants'
+ * models, most requests find their model cached, and the cost of a miss is predictable
+ * because a model's footprint is fixed).  mt_prefetch makes the n named models resident:
+ * models that are not are copied from their pinned host images to the arena on `stream`
+ * without waiting, after the least recently used other models have given way (a model
+ * named in this call never gives way to another one of it).  The copies queue up behind
+ * every run in flight, and a later mt_run on any stream waits for them on the device;
+ * nothing blocks the host.  mt_run itself prefetches the tenants of pending mt_submit
+ * calls; tenants that appear only in mt_submit_batch id arrays have to be prefetched by the
+ * caller (the router knows them), else their rows are answered like rows of a tenant without
+ * a model.  "Used" means registered or named in a prefetch.  Outside cache mode the call only
+ * checks its arguments.  Errors: MT_EINVAL, MT_ENOTFOUND (a tenant without a model),
+ * MT_ENOMEM (the named models do not fit the arena together; those named first may have
+ * been brought in), MT_EDEVICE. */
+mt_status mt_prefetch(mt_ctx* ctx, const uint32_t* tenants, uint32_t n, void* hip_stream);
+
+typedef struct {
+    uint32_t resident_models;
+    uint64_t uploads, upload_bytes;   /* models copied to the arena so far (registration included) */
+    uint64_t evictions;               /* models that gave way                                       */
+} mt_cache_stats;
+mt_status mt_cache_stats_get(const mt_ctx* ctx, mt_cache_stats* out);
+
 /* Per-tenant accounting.  A request's cost follows from the model description alone
  * (paper section 3.2: the flops of every layer are known a priori), so billing by work
  * done (section 1.3) needs only a count of the requests served, which the batcher keeps
@@ -183,6 +213,8 @@ mt_status mt_last_counts(mt_ctx* ctx, uint32_t* counts);
 typedef struct {
     uint64_t requests, runs;
     uint64_t flops_per_request, weight_bytes, io_bytes_per_request;
+    uint64_t resident;      /* 1: the model is in the device arena now                    */
+    uint64_t arena_bytes;   /* bytes it occupies there (padded layouts): what an upload moves */
 } mt_tenant_account;
 mt_status mt_tenant_account_get(mt_ctx* ctx, uint32_t tenant, mt_tenant_account* out);
 
@@ -201,6 +233,8 @@ mt_status mt_tenant_account_get(mt_ctx* ctx, uint32_t tenant, mt_tenant_account*
 typedef struct {
     double flops, hbm_bytes, device_ms;
     uint32_t rows, launches;
+    double upload_bytes, upload_ms;   /* models with requests that are not resident now: bytes to
+                                         bring in first, and the predicted time of that copy  */
 } mt_run_estimate;
 mt_status mt_estimate_run(mt_ctx* ctx, const uint32_t* counts, mt_run_estimate* out);
 

@@ -39,17 +39,24 @@ class mt_config(ctypes.Structure):
     _fields_ = [("max_tenants", ctypes.c_uint32), ("max_requests", ctypes.c_uint32),
                 ("max_width", ctypes.c_uint32), ("max_classes", ctypes.c_uint32),
                 ("arena_bytes", ctypes.c_uint64), ("dtype", ctypes.c_uint32), ("device", ctypes.c_int32),
-                ("run_slots", ctypes.c_uint32)]
+                ("run_slots", ctypes.c_uint32), ("cache", ctypes.c_uint32)]
 
 
 class mt_tenant_account(ctypes.Structure):
     _fields_ = [("requests", ctypes.c_uint64), ("runs", ctypes.c_uint64), ("flops_per_request", ctypes.c_uint64),
-                ("weight_bytes", ctypes.c_uint64), ("io_bytes_per_request", ctypes.c_uint64)]
+                ("weight_bytes", ctypes.c_uint64), ("io_bytes_per_request", ctypes.c_uint64),
+                ("resident", ctypes.c_uint64), ("arena_bytes", ctypes.c_uint64)]
+
+
+class mt_cache_stats(ctypes.Structure):
+    _fields_ = [("resident_models", ctypes.c_uint32), ("uploads", ctypes.c_uint64), ("upload_bytes", ctypes.c_uint64),
+                ("evictions", ctypes.c_uint64)]
 
 
 class mt_run_estimate(ctypes.Structure):
     _fields_ = [("flops", ctypes.c_double), ("hbm_bytes", ctypes.c_double), ("device_ms", ctypes.c_double),
-                ("rows", ctypes.c_uint32), ("launches", ctypes.c_uint32)]
+                ("rows", ctypes.c_uint32), ("launches", ctypes.c_uint32),
+                ("upload_bytes", ctypes.c_double), ("upload_ms", ctypes.c_double)]
 
 
 class mt_outputs(ctypes.Structure):
@@ -92,6 +99,8 @@ def load_library() -> ctypes.CDLL:
     L.mt_get_stats.argtypes = [vp, ctypes.POINTER(mt_stats)]
     L.mt_tenant_account_get.argtypes = [vp, u32, ctypes.POINTER(mt_tenant_account)]
     L.mt_estimate_run.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(mt_run_estimate)]
+    L.mt_prefetch.argtypes = [vp, ctypes.POINTER(u32), u32, vp]
+    L.mt_cache_stats_get.argtypes = [vp, ctypes.POINTER(mt_cache_stats)]
     L.mt_debug_poison.argtypes = [vp]
     L.mt_debug_copy.argtypes = [vp, vp, ctypes.c_uint64, vp]
     L.mt_debug_big_tile_rows.argtypes = [u32, u32]
@@ -102,7 +111,7 @@ def load_library() -> ctypes.CDLL:
     L.mt_last_error.restype = ctypes.c_char_p
     L.mt_version.restype = ctypes.c_char_p
     for name in ("mt_create", "mt_destroy", "mt_register_model", "mt_unregister_model", "mt_submit",
-                 "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_tenant_account_get", "mt_estimate_run", "mt_debug_poison", "mt_debug_copy",
+                 "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_tenant_account_get", "mt_estimate_run", "mt_prefetch", "mt_cache_stats_get", "mt_debug_poison", "mt_debug_copy",
                  "mt_set_profiling", "mt_get_profile"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -132,10 +141,10 @@ class Context:
     """One worker context (mt_ctx).  Methods mirror the C entry points one to one."""
 
     def __init__(self, max_tenants: int, max_requests: int, max_width: int, max_classes: int,
-                 arena_bytes: int, dtype: int, device: int = 0, run_slots: int = 1):
+                 arena_bytes: int, dtype: int, device: int = 0, run_slots: int = 1, cache: bool = False):
         self._lib = load_library()
         self.dtype = dtype
-        self.cfg = mt_config(max_tenants, max_requests, max_width, max_classes, arena_bytes, dtype, device, run_slots)
+        self.cfg = mt_config(max_tenants, max_requests, max_width, max_classes, arena_bytes, dtype, device, run_slots, int(cache))
         self._h = ctypes.c_void_p()
         st = self._lib.mt_create(ctypes.byref(self._h), ctypes.byref(self.cfg))
         if st != MT_OK:
@@ -221,6 +230,15 @@ class Context:
         e = mt_run_estimate()
         self._check(self._lib.mt_estimate_run(self._h, arr, ctypes.byref(e)))
         return {k: getattr(e, k) for k, _ in mt_run_estimate._fields_}
+
+    def prefetch(self, tenants, stream_ptr: int = 0) -> None:
+        arr = (ctypes.c_uint32 * max(1, len(tenants)))(*[int(t) for t in tenants])
+        self._check(self._lib.mt_prefetch(self._h, arr, len(tenants), ctypes.c_void_p(stream_ptr or None)))
+
+    def cache_stats(self) -> dict:
+        st = mt_cache_stats()
+        self._check(self._lib.mt_cache_stats_get(self._h, ctypes.byref(st)))
+        return {k: int(getattr(st, k)) for k, _ in mt_cache_stats._fields_}
 
     def stats(self) -> dict:
         s = mt_stats()

@@ -30,8 +30,9 @@ inline uint64_t round_up64(uint64_t v, uint64_t a) { return (v + a - 1) / a * a;
 
 struct HostLayer {
     mt_layer_spec spec;
-    LayerDev dev;
+    LayerDev dev;               // w_off / b_off: absolute arena offsets while the model is resident
     uint64_t w_bytes, b_bytes;
+    uint64_t w_rel, b_rel;      // the same offsets relative to the model's arena block
 };
 
 struct HostTenant {
@@ -40,6 +41,12 @@ struct HostTenant {
     HostLayer layers[MT_MAX_LAYERS];
     TenantDev dev{};
     uint64_t arena_off = 0, arena_len = 0;
+    // Model cache (cfg.cache): the packed weights stay in pinned host memory (`stage`: the arena
+    // image followed by the device table rows of this tenant) and the arena holds the models used
+    // most recently.  Outside cache mode every registered model is resident and stage is null.
+    bool resident = false;
+    uint64_t last_use = 0;
+    uint8_t* stage = nullptr;
 };
 
 struct FreeBlock { uint64_t off, len; };
@@ -116,6 +123,15 @@ struct mt_ctx {
     uint64_t run_count = 0;
     hipStream_t last_stream = nullptr;
 
+    // model cache
+    bool cache = false;
+    uint64_t use_clock = 0;                 // stamps HostTenant::last_use
+    uint8_t* h_zero_rows = nullptr;         // pinned zeros: TenantDev and facts of an evicted tenant
+    hipEvent_t cache_event = nullptr;       // recorded behind the last asynchronous residency change
+    hipStream_t cache_stream = nullptr;
+    bool cache_pending = false;
+    uint64_t n_uploads = 0, upload_bytes = 0, n_evictions = 0;
+
     // pending submissions
     std::vector<Segment> pending;
     uint32_t pending_rows = 0;
@@ -174,6 +190,13 @@ bool arena_alloc(mt_ctx* c, uint64_t len, uint64_t* off)
     return false;
 }
 
+bool arena_fits(const mt_ctx* c, uint64_t len)
+{
+    len = round_up64(len, kArenaAlign);
+    for (const FreeBlock& b : c->free_list) if (b.len >= len) return true;
+    return false;
+}
+
 void arena_free(mt_ctx* c, uint64_t off, uint64_t len)
 {
     len = round_up64(len, kArenaAlign);
@@ -199,12 +222,12 @@ uint32_t fc_tile_rows(uint32_t n_pad, uint32_t split_k)
     return (!split_k && n_pad / kBrickRows >= 3) ? kTileRows : kTileRows / 2;
 }
 
-// The batcher's two words per layer of one tenant (see BatchArgs::facts); zeros without a model.
-hipError_t upload_facts(mt_ctx* c, uint32_t tenant, const HostTenant* ht)
+// The batcher's two words per layer of one tenant (see BatchArgs::facts).
+void fill_facts(const mt_ctx* c, const HostTenant& ht, uint32_t (*w)[2])
 {
-    uint32_t w[MT_MAX_LAYERS][2] = {};
-    for (uint32_t l = 0; ht && l < ht->n_layers; ++l) {
-        const LayerDev& L = ht->layers[l].dev;
+    for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) w[l][0] = w[l][1] = 0;
+    for (uint32_t l = 0; l < ht.n_layers; ++l) {
+        const LayerDev& L = ht.layers[l].dev;
         if (L.kind == MT_FC) {
             w[l][0] = fc_groups(L.N_pad, c->fc_split_k) | (fc_tile_rows(L.N_pad, c->fc_split_k) == kTileRows ? 0u : 1u << 30);
             w[l][1] = L.N_pad;
@@ -213,7 +236,90 @@ hipError_t upload_facts(mt_ctx* c, uint32_t tenant, const HostTenant* ht)
             w[l][1] = L.rows_per_req;
         }
     }
-    return hipMemcpy(c->d_facts + (size_t)tenant * 2 * MT_MAX_LAYERS, w, sizeof w, hipMemcpyHostToDevice);
+}
+
+// What a tenant's device state is uploaded from, in one host block: the arena image
+// (arena_len bytes), then its rows of the three device tables.
+struct StageTail {
+    LayerDev rows[MT_MAX_LAYERS];
+    TenantDev td;
+    uint32_t facts[MT_MAX_LAYERS][2];
+};
+size_t stage_tail_offset(uint64_t arena_len) { return (size_t)round_up64(arena_len, 256); }
+size_t stage_bytes(uint64_t arena_len) { return stage_tail_offset(arena_len) + sizeof(StageTail); }
+
+// Point the tenant's layer descriptors at arena block `off` and refresh the table rows in its stage.
+void place_tenant(const mt_ctx* c, HostTenant& ht, uint64_t off, uint8_t* stage)
+{
+    ht.arena_off = off;
+    StageTail* tail = (StageTail*)(stage + stage_tail_offset(ht.arena_len));
+    *tail = StageTail{};
+    for (uint32_t l = 0; l < ht.n_layers; ++l) {
+        ht.layers[l].dev.w_off = off + ht.layers[l].w_rel;
+        ht.layers[l].dev.b_off = off + ht.layers[l].b_rel;
+        tail->rows[l] = ht.layers[l].dev;
+    }
+    tail->td = ht.dev; tail->td.registered = 1;
+    fill_facts(c, ht, tail->facts);
+}
+
+// Copy a placed tenant's weights and table rows to the device: on `s` without waiting (the stage
+// must be pinned and stay untouched until the copies are done), or synchronously.
+hipError_t upload_tenant(mt_ctx* c, uint32_t tenant, const HostTenant& ht, const uint8_t* stage, hipStream_t s, bool async)
+{
+    const StageTail* tail = (const StageTail*)(stage + stage_tail_offset(ht.arena_len));
+    struct { void* dst; const void* src; size_t n; } copies[] = {
+        {c->d_arena + ht.arena_off, stage, (size_t)ht.arena_len},
+        {c->d_layers + (size_t)tenant * MT_MAX_LAYERS, tail->rows, sizeof tail->rows},
+        {c->d_facts + (size_t)tenant * 2 * MT_MAX_LAYERS, tail->facts, sizeof tail->facts},
+        {c->d_tenants + tenant, &tail->td, sizeof tail->td},          // last: the tenant becomes visible to the batcher
+    };
+    for (const auto& cp : copies) {
+        const hipError_t e = async ? hipMemcpyAsync(cp.dst, cp.src, cp.n, hipMemcpyHostToDevice, s)
+                                   : hipMemcpy(cp.dst, cp.src, cp.n, hipMemcpyHostToDevice);
+        if (e != hipSuccess) return e;
+    }
+    c->n_uploads++; c->upload_bytes += ht.arena_len;
+    return hipSuccess;
+}
+
+// Take a tenant's model off the device: the batcher no longer sees it, its arena block is free.
+hipError_t hide_tenant(mt_ctx* c, uint32_t tenant, hipStream_t s, bool async)
+{
+    static const StageTail zeros{};
+    const StageTail* z = async ? (const StageTail*)c->h_zero_rows : &zeros;
+    struct { void* dst; const void* src; size_t n; } copies[] = {
+        {c->d_tenants + tenant, &z->td, sizeof z->td},
+        {c->d_facts + (size_t)tenant * 2 * MT_MAX_LAYERS, z->facts, sizeof z->facts},
+    };
+    for (const auto& cp : copies) {
+        const hipError_t e = async ? hipMemcpyAsync(cp.dst, cp.src, cp.n, hipMemcpyHostToDevice, s)
+                                   : hipMemcpy(cp.dst, cp.src, cp.n, hipMemcpyHostToDevice);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// Find `len` bytes of arena.  In cache mode, models used least recently (and before `protect`)
+// give way until the block fits; their stages stay in host memory.
+bool make_room(mt_ctx* c, uint64_t len, uint64_t protect, hipStream_t s, bool async, uint64_t* off, hipError_t* err)
+{
+    *err = hipSuccess;
+    while (!arena_alloc(c, len, off)) {
+        if (!c->cache) return false;
+        int victim = -1;
+        for (uint32_t t = 0; t < c->cfg.max_tenants; ++t) {
+            const HostTenant& h = c->tenants[t];
+            if (h.registered && h.resident && h.last_use < protect && (victim < 0 || h.last_use < c->tenants[victim].last_use)) victim = (int)t;
+        }
+        if (victim < 0) return false;
+        HostTenant& v = c->tenants[victim];
+        if (!c->host_only) { *err = hide_tenant(c, (uint32_t)victim, s, async); if (*err != hipSuccess) return false; }
+        arena_free(c, v.arena_off, v.arena_len);
+        v.resident = false;
+        c->n_evictions++;
+    }
+    return true;
 }
 
 void recompute_bounds(mt_ctx* c)
@@ -411,6 +517,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     if (const char* e = getenv("MT_NO_FUSED_GATHER")) c->no_fused_gather = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_HEAD")) c->no_fused_head = atoi(e) != 0;
     if (const char* e = getenv("MT_BIG_MIN_TILES")) c->big_min_tiles = (uint32_t)std::max(1, atoi(e));
+    c->cache = cfg->cache != 0;
     c->tenants.resize(cfg->max_tenants);
     c->cfg.arena_bytes = cfg->arena_bytes / kArenaAlign * kArenaAlign;
     c->free_list.push_back(FreeBlock{0, c->cfg.arena_bytes});
@@ -452,6 +559,11 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
         CREATE_TRY(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
     }
     bind_slot(c, c->slots[0]);
+    if (c->cache) {
+        CREATE_TRY(hipHostMalloc((void**)&c->h_zero_rows, sizeof(StageTail), hipHostMallocDefault));
+        std::memset(c->h_zero_rows, 0, sizeof(StageTail));
+        CREATE_TRY(hipEventCreateWithFlags(&c->cache_event, hipEventDisableTiming));
+    }
     for (uint32_t i = 0; i < kSegSlots; ++i) {
         CREATE_TRY(hipHostMalloc((void**)&c->h_segs[i], R * sizeof(Segment), hipHostMallocMapped));
         CREATE_TRY(hipHostGetDevicePointer((void**)&c->d_segs[i], c->h_segs[i], 0));
@@ -480,6 +592,9 @@ mt_status mt_destroy(mt_ctx* c)
             if (c->seg_event[i]) (void)hipEventDestroy(c->seg_event[i]);
         }
         for (hipEvent_t e : c->prof_events) if (e) (void)hipEventDestroy(e);
+        for (HostTenant& t : c->tenants) if (t.stage) (void)hipHostFree(t.stage);
+        if (c->h_zero_rows) (void)hipHostFree(c->h_zero_rows);
+        if (c->cache_event) (void)hipEventDestroy(c->cache_event);
     }
     delete c;
     return MT_OK;
@@ -501,43 +616,111 @@ mt_status mt_register_model(mt_ctx* c, uint32_t tenant, const mt_layer_spec* spe
     uint64_t total = 0;
     for (uint32_t l = 0; l < n_layers; ++l) {
         HostLayer& hl = ht.layers[l];
-        hl.dev.w_off = total; total += round_up64(hl.w_bytes, kArenaAlign);
-        hl.dev.b_off = total; total += round_up64(hl.b_bytes, kArenaAlign);
+        hl.w_rel = total; total += round_up64(hl.w_bytes, kArenaAlign);
+        hl.b_rel = total; total += round_up64(hl.b_bytes, kArenaAlign);
     }
     if (total == 0) total = kArenaAlign;
-    uint64_t off = 0;
-    if (!arena_alloc(c, total, &off))
-        return fail(c, MT_ENOMEM, "weight arena exhausted: model needs %llu bytes, %llu of %llu in use",
-                    (unsigned long long)total, (unsigned long long)c->arena_used, (unsigned long long)c->cfg.arena_bytes);
-    ht.arena_off = off; ht.arena_len = total;
-    for (uint32_t l = 0; l < n_layers; ++l) { ht.layers[l].dev.w_off += off; ht.layers[l].dev.b_off += off; }
+    ht.arena_len = total;
+    if (total > c->cfg.arena_bytes)
+        return fail(c, MT_ENOMEM, "model needs %llu bytes, the weight arena has %llu", (unsigned long long)total, (unsigned long long)c->cfg.arena_bytes);
 
+    // the stage: pinned and kept in cache mode (models are reloaded from it), else a temporary
+    std::vector<uint8_t> temp;
+    uint8_t* stage = nullptr;
     if (!c->host_only) {
-        std::vector<uint8_t> image(total, 0);
+        HIP_TRY(c, hipSetDevice(c->cfg.device));
+        if (c->cache) {
+            if (hipHostMalloc((void**)&stage, stage_bytes(total), hipHostMallocDefault) != hipSuccess)
+                return fail(c, MT_ENOMEM, "no pinned host memory for the %llu bytes of tenant %u", (unsigned long long)total, tenant);
+            std::memset(stage, 0, stage_bytes(total));
+        } else {
+            temp.assign(stage_bytes(total), 0);
+            stage = temp.data();
+        }
         for (uint32_t l = 0; l < n_layers; ++l) {
             const HostLayer& hl = ht.layers[l];
             if (hl.dev.kind == MT_GAP) continue;
-            uint8_t* w_dst = image.data() + (hl.dev.w_off - off);
+            uint8_t* w_dst = stage + hl.w_rel;
             if (c->elem_size == 2) pack_weights<uint16_t>(hl, weights[l], w_dst); else pack_weights<float>(hl, weights[l], w_dst);
-            if (biases && biases[l]) std::memcpy(image.data() + (hl.dev.b_off - off), biases[l], (size_t)hl.dev.N * 4);
+            if (biases && biases[l]) std::memcpy(stage + hl.b_rel, biases[l], (size_t)hl.dev.N * 4);
         }
-        LayerDev rows[MT_MAX_LAYERS]{};
-        for (uint32_t l = 0; l < n_layers; ++l) rows[l] = ht.layers[l].dev;
-        TenantDev td = ht.dev; td.registered = 1;
-        hipError_t e = hipSetDevice(c->cfg.device);
-        if (e == hipSuccess) e = hipMemcpy(c->d_arena + off, image.data(), total, hipMemcpyHostToDevice);
-        if (e == hipSuccess) e = hipMemcpy(c->d_layers + (size_t)tenant * MT_MAX_LAYERS, rows, sizeof rows, hipMemcpyHostToDevice);
-        if (e == hipSuccess) e = upload_facts(c, tenant, &ht);
-        if (e == hipSuccess) e = hipMemcpy(c->d_tenants + tenant, &td, sizeof td, hipMemcpyHostToDevice);
+    }
+    auto drop_stage = [&]() { if (c->cache && stage) (void)hipHostFree(stage); };
+
+    // Registration is synchronous.  If models have to give way, every run in flight ends first.
+    uint64_t off = 0;
+    hipError_t e = hipSuccess;
+    const uint64_t stamp = ++c->use_clock;
+    if (c->cache && !c->host_only && !arena_fits(c, total)) {
+        const hipError_t es = hipDeviceSynchronize();
+        if (es != hipSuccess) { drop_stage(); return fail(c, MT_EDEVICE, "device synchronisation failed: %s", hipGetErrorString(es)); }
+    }
+    if (!make_room(c, total, stamp, nullptr, false, &off, &e)) {
+        drop_stage();
+        if (e != hipSuccess) return fail(c, MT_EDEVICE, "eviction failed: %s", hipGetErrorString(e));
+        return fail(c, MT_ENOMEM, "weight arena exhausted: model needs %llu bytes, %llu of %llu in use",
+                    (unsigned long long)total, (unsigned long long)c->arena_used, (unsigned long long)c->cfg.arena_bytes);
+    }
+    ht.arena_off = off;
+    for (uint32_t l = 0; l < n_layers; ++l) { ht.layers[l].dev.w_off = off + ht.layers[l].w_rel; ht.layers[l].dev.b_off = off + ht.layers[l].b_rel; }
+    if (!c->host_only) {
+        place_tenant(c, ht, off, stage);
+        e = upload_tenant(c, tenant, ht, stage, nullptr, false);
         if (e != hipSuccess) {
             arena_free(c, off, total);
+            drop_stage();
             return fail(c, MT_EDEVICE, "upload of tenant %u failed: %s", tenant, hipGetErrorString(e));
         }
     }
-    ht.registered = true; ht.dev.registered = 1;
+    ht.registered = true; ht.dev.registered = 1; ht.resident = true; ht.last_use = stamp;
+    ht.stage = c->cache ? stage : nullptr;
     c->tenants[tenant] = ht;
     c->n_registered++;
     recompute_bounds(c);
+    return MT_OK;
+}
+
+mt_status mt_prefetch(mt_ctx* c, const uint32_t* tenants, uint32_t n, void* hip_stream)
+{
+    if (!c || (!tenants && n)) return MT_EINVAL;
+    for (uint32_t i = 0; i < n; ++i)
+        if (tenants[i] >= c->cfg.max_tenants || !c->tenants[tenants[i]].registered)
+            return fail(c, MT_ENOTFOUND, "tenant %u has no model", tenants[i]);
+    const uint64_t stamp = ++c->use_clock;          // everything named here is used "now": none of it gives way to the rest
+    bool missing = false;
+    for (uint32_t i = 0; i < n; ++i) { c->tenants[tenants[i]].last_use = stamp; missing |= !c->tenants[tenants[i]].resident; }
+    if (!missing) return MT_OK;                     // (always the case outside cache mode)
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (!c->host_only) {
+        HIP_TRY(c, hipSetDevice(c->cfg.device));
+        // runs in flight keep their weights and tables: the changes below queue up behind them
+        for (RunSlot& r : c->slots)
+            if (r.used) HIP_TRY(c, hipStreamWaitEvent(s, r.done, 0));
+        if (c->cache_pending && c->cache_stream != s) HIP_TRY(c, hipStreamWaitEvent(s, c->cache_event, 0));
+    }
+    for (uint32_t i = 0; i < n; ++i) {
+        HostTenant& ht = c->tenants[tenants[i]];
+        if (ht.resident) continue;
+        uint64_t off = 0;
+        hipError_t e = hipSuccess;
+        if (!make_room(c, ht.arena_len, stamp, s, true, &off, &e)) {
+            if (e != hipSuccess) return fail(c, MT_EDEVICE, "eviction failed: %s", hipGetErrorString(e));
+            return fail(c, MT_ENOMEM, "the models named do not fit the weight arena together (%llu of %llu bytes in use, tenant %u needs %llu)",
+                        (unsigned long long)c->arena_used, (unsigned long long)c->cfg.arena_bytes, tenants[i], (unsigned long long)ht.arena_len);
+        }
+        if (!c->host_only) {
+            place_tenant(c, ht, off, ht.stage);
+            e = upload_tenant(c, tenants[i], ht, ht.stage, s, true);
+            if (e != hipSuccess) { arena_free(c, off, ht.arena_len); return fail(c, MT_EDEVICE, "upload of tenant %u failed: %s", tenants[i], hipGetErrorString(e)); }
+        } else {
+            ht.arena_off = off;
+        }
+        ht.resident = true;
+    }
+    if (!c->host_only) {
+        HIP_TRY(c, hipEventRecord(c->cache_event, s));
+        c->cache_pending = true; c->cache_stream = s;
+    }
     return MT_OK;
 }
 
@@ -548,13 +731,12 @@ mt_status mt_unregister_model(mt_ctx* c, uint32_t tenant)
     for (const Segment& s : c->pending)
         if (!s.ids && s.tenant == (int32_t)tenant) return fail(c, MT_ESTATE, "tenant %u has pending requests", tenant);
     if (!c->host_only) {
-        TenantDev td{};
         HIP_TRY(c, hipSetDevice(c->cfg.device));
         HIP_TRY(c, hipDeviceSynchronize());
-        HIP_TRY(c, hipMemcpy(c->d_tenants + tenant, &td, sizeof td, hipMemcpyHostToDevice));
-        HIP_TRY(c, upload_facts(c, tenant, nullptr));
+        HIP_TRY(c, hide_tenant(c, tenant, nullptr, false));
+        if (c->tenants[tenant].stage) (void)hipHostFree(c->tenants[tenant].stage);
     }
-    arena_free(c, c->tenants[tenant].arena_off, c->tenants[tenant].arena_len);
+    if (c->tenants[tenant].resident) arena_free(c, c->tenants[tenant].arena_off, c->tenants[tenant].arena_len);
     c->tenants[tenant] = HostTenant{};
     c->n_registered--;
     recompute_bounds(c);
@@ -618,6 +800,18 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     hipStream_t s = (hipStream_t)hip_stream;
     HIP_TRY(c, hipSetDevice(c->cfg.device));
 
+    // Model cache: the tenants of per-tenant submissions are made resident here (the host knows
+    // them); tenants that appear only in device-resident id arrays must have been prefetched.
+    // A residency change enqueued on another stream comes first.
+    if (c->cache) {
+        std::vector<uint32_t> named;
+        for (const Segment& sg : c->pending)
+            if (!sg.ids && (named.empty() || named.back() != (uint32_t)sg.tenant)) named.push_back((uint32_t)sg.tenant);
+        std::sort(named.begin(), named.end());
+        named.erase(std::unique(named.begin(), named.end()), named.end());
+        if (!named.empty()) { const mt_status st = mt_prefetch(c, named.data(), (uint32_t)named.size(), hip_stream); if (st != MT_OK) return st; }
+        if (c->cache_pending && c->cache_stream != s) HIP_TRY(c, hipStreamWaitEvent(s, c->cache_event, 0));
+    }
     // the run's slot of device scratch; a stream other than the one that used it last waits for that run
     RunSlot& rs = c->slots[c->run_count % c->slots.size()];
     if (rs.used && rs.stream != s) HIP_TRY(c, hipStreamWaitEvent(s, rs.done, 0));
@@ -789,6 +983,7 @@ constexpr double kUsBigFixed = 4.0, kUsBigTileFixed = 7.0, kUsBigTilePer4096 = 1
 constexpr double kUsConvFixed = 5.0, kConvMbPerUs = 3.7, kConvMflopPerUs = 0.5e3;      // 3.7 TB/s, 0.5 PFLOP/s
 constexpr double kUsSmallFixed = 3.0, kCopyMbPerUs = 3.7, kHeadMbPerUs = 5.7, kUsHeadPerRow = 0.0008;
 constexpr double kComputeUnits = 256.0;
+constexpr double kUploadBytesPerMs = 55e6, kUsUploadFixed = 20.0;     // pinned host memory to HBM over the host link: 55 GB/s measured
 
 }  // namespace
 
@@ -799,6 +994,8 @@ mt_status mt_tenant_account_get(mt_ctx* c, uint32_t tenant, mt_tenant_account* o
     if (!c->tenants[tenant].registered) return fail(c, MT_ENOTFOUND, "tenant %u has no model", tenant);
     *out = mt_tenant_account{};
     request_cost(c, c->tenants[tenant], &out->flops_per_request, &out->weight_bytes, &out->io_bytes_per_request);
+    out->resident = c->tenants[tenant].resident;
+    out->arena_bytes = c->tenants[tenant].arena_len;
     if (!c->host_only) {
         uint64_t counters[2] = {0, 0};
         HIP_TRY(c, hipSetDevice(c->cfg.device));
@@ -916,6 +1113,11 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
         launch(kUsSmallFixed + std::max(3.0 * R * c->C_pad * 4.0 / MB / kHeadMbPerUs, kUsHeadPerRow * R));
     out->launches = launches;
     out->device_ms = us * 1e-3;
+    // models that are not resident have to cross the host link first: their footprint is fixed, so
+    // that time is as predictable as the run itself (section 3.3)
+    for (uint32_t t = 0; t < T; ++t)
+        if (counts[t] && !c->tenants[t].resident) out->upload_bytes += (double)c->tenants[t].arena_len;
+    out->upload_ms = out->upload_bytes ? kUsUploadFixed * 1e-3 + out->upload_bytes / kUploadBytesPerMs : 0.0;
     return MT_OK;
 }
 
@@ -983,6 +1185,15 @@ mt_status mt_debug_poison(mt_ctx* c)
         HIP_TRY(c, hipMemset(r.d_logits, 0xFF, (size_t)c->P_cap * c->C_pad * 4));
     }
     HIP_TRY(c, hipDeviceSynchronize());
+    return MT_OK;
+}
+
+mt_status mt_cache_stats_get(const mt_ctx* c, mt_cache_stats* out)
+{
+    if (!c || !out) return MT_EINVAL;
+    *out = mt_cache_stats{};
+    for (const HostTenant& t : c->tenants) if (t.registered && t.resident) out->resident_models++;
+    out->uploads = c->n_uploads; out->upload_bytes = c->upload_bytes; out->evictions = c->n_evictions;
     return MT_OK;
 }
 

@@ -25,7 +25,8 @@ def specs_of(layers) -> list:
 
 
 def context_for(tenants: Dict[int, object], dtype: str, max_requests: int, device: int = 0,
-                max_tenants: Optional[int] = None, arena_slack: float = 1.05, run_slots: int = 1) -> B.Context:
+                max_tenants: Optional[int] = None, arena_slack: float = 1.05, run_slots: int = 1,
+                arena_bytes: Optional[int] = None, cache: bool = False) -> B.Context:
     """A context sized for the given tenant models (objects with .layers/.weights/.biases)."""
     es = 4 if dtype == "f32" else 2
     width, classes, arena = 64, 1, 0
@@ -42,8 +43,8 @@ def context_for(tenants: Dict[int, object], dtype: str, max_requests: int, devic
                 arena += (n_pad * ((k + 63) // 64 * 64) * es + 255) // 256 * 256 + (n_pad * 4 + 255) // 256 * 256
         classes = max(classes, m.layers[-1].out_len())
     T = max_tenants if max_tenants is not None else (max(tenants) + 1 if tenants else 1)
-    return B.Context(T, max_requests, width, classes, int(arena * arena_slack) + (1 << 20),
-                     B.MT_F32 if dtype == "f32" else B.MT_BF16, device, run_slots)
+    return B.Context(T, max_requests, width, classes, arena_bytes if arena_bytes is not None else int(arena * arena_slack) + (1 << 20),
+                     B.MT_F32 if dtype == "f32" else B.MT_BF16, device, run_slots, cache)
 
 
 def register_tenants(ctx: B.Context, tenants: Dict[int, object]):

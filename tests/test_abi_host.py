@@ -190,3 +190,49 @@ def test_request_cost_and_run_estimate_follow_the_model_description():
             ctx.tenant_account(0)
         assert e.value.status == 3
         ctx.close()
+
+
+def test_model_cache_bookkeeping_on_the_host():
+    # cache mode: a full arena evicts the least recently used models instead of failing; models named
+    # in one prefetch never give way to one another; a model larger than the arena can never be held
+    specs = [fc(256, 256, B.MT_ACT_RELU), fc(256, 10)]            # 256*256*2 + 1 KiB bias + 64*256*2... about 160 KiB each
+    c = B.Context(8, 64, 1024, 16, 3 * 170 * 1024, B.MT_BF16, device=-1, cache=True)
+    for t in range(5):
+        c.register_model(t, specs, *zeros_for(specs))
+    resident = [c.tenant_account(t)["resident"] for t in range(5)]
+    assert resident == [0, 0, 1, 1, 1] and c.cache_stats()["evictions"] == 2 and c.cache_stats()["resident_models"] == 3
+    c.prefetch([0, 3])                                           # 0 comes back; the oldest other model (2) gives way
+    assert [c.tenant_account(t)["resident"] for t in range(5)] == [1, 0, 0, 1, 1]
+    c.prefetch([3, 0])                                           # nothing to do
+    assert c.cache_stats()["evictions"] == 3
+    with pytest.raises(B.MtError) as e:
+        c.prefetch([0, 1, 2, 3])                                 # four models do not fit together
+    assert e.value.status == 2
+    with pytest.raises(B.MtError) as e:
+        c.prefetch([6])
+    assert e.value.status == 3
+    big = [fc(1024, 1024, B.MT_ACT_RELU), fc(1024, 10)]
+    with pytest.raises(B.MtError) as e:
+        c.register_model(7, big, *zeros_for(big))
+    assert e.value.status == 2
+    # (a prefetch that fails may already have brought in the models named first)
+    res = [c.tenant_account(t)["resident"] for t in range(5)]
+    assert sum(res) == 3
+    est = c.estimate_run([1, 1, 1, 1, 1, 0, 0, 0])               # a run over all five: two have to be brought in first
+    assert est["upload_bytes"] == 2 * c.tenant_account(1)["arena_bytes"] and est["upload_ms"] > 0
+    counts = [0] * 8
+    counts[res.index(1)] = 3
+    assert c.estimate_run(counts)["upload_bytes"] == 0 and c.estimate_run(counts)["upload_ms"] == 0
+    c.unregister_model(1)                                        # not resident: only its host image goes
+    c.unregister_model(0)
+    assert c.cache_stats()["resident_models"] == sum(c.tenant_account(t)["resident"] for t in (2, 3, 4))
+    c.close()
+    # outside cache mode a full arena is an error, as before, and prefetch only checks its arguments
+    c = B.Context(8, 64, 1024, 16, 3 * 170 * 1024, B.MT_BF16, device=-1)
+    for t in range(3):
+        c.register_model(t, specs, *zeros_for(specs))
+    with pytest.raises(B.MtError) as e:
+        c.register_model(3, specs, *zeros_for(specs))
+    assert e.value.status == 2
+    c.prefetch([0, 1, 2])
+    c.close()
