@@ -238,6 +238,18 @@ typedef struct {
 } mt_run_estimate;
 mt_status mt_estimate_run(mt_ctx* ctx, const uint32_t* counts, mt_run_estimate* out);
 
+/* Admission (paper section 3.2: because a run's cost is predictable before it runs, the
+ * system can decide what to admit so that latency targets hold and no tenant starves the
+ * others).  pending[t] = requests of tenant t waiting (HOST, max_tenants entries);
+ * budget_ms = the device time the next run may take (uploads of models that are not
+ * resident count towards it).  admitted[t] receives a max-min fair share: every tenant gets
+ * min(pending[t], level) requests, with the highest level whose predicted run
+ * (mt_estimate_run) fits the budget and max_requests; est (optional) receives the prediction
+ * for the admitted mix.  A budget that not even one request per waiting tenant fits admits
+ * nothing (level 0).  Works on a host-only context.  Errors: MT_EINVAL (null, budget <= 0),
+ * MT_ENOTFOUND (requests pending for a tenant without a model). */
+mt_status mt_admit(mt_ctx* ctx, const uint32_t* pending, double budget_ms, uint32_t* admitted, mt_run_estimate* est);
+
 mt_status mt_get_stats(const mt_ctx* ctx, mt_stats* out);
 
 /* Per-kernel timing of mt_run, for measurement.  While enabled, mt_run brackets every

@@ -99,6 +99,7 @@ def load_library() -> ctypes.CDLL:
     L.mt_get_stats.argtypes = [vp, ctypes.POINTER(mt_stats)]
     L.mt_tenant_account_get.argtypes = [vp, u32, ctypes.POINTER(mt_tenant_account)]
     L.mt_estimate_run.argtypes = [vp, ctypes.POINTER(u32), ctypes.POINTER(mt_run_estimate)]
+    L.mt_admit.argtypes = [vp, ctypes.POINTER(u32), ctypes.c_double, ctypes.POINTER(u32), ctypes.POINTER(mt_run_estimate)]
     L.mt_prefetch.argtypes = [vp, ctypes.POINTER(u32), u32, vp]
     L.mt_cache_stats_get.argtypes = [vp, ctypes.POINTER(mt_cache_stats)]
     L.mt_debug_poison.argtypes = [vp]
@@ -111,7 +112,7 @@ def load_library() -> ctypes.CDLL:
     L.mt_last_error.restype = ctypes.c_char_p
     L.mt_version.restype = ctypes.c_char_p
     for name in ("mt_create", "mt_destroy", "mt_register_model", "mt_unregister_model", "mt_submit",
-                 "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_tenant_account_get", "mt_estimate_run", "mt_prefetch", "mt_cache_stats_get", "mt_debug_poison", "mt_debug_copy",
+                 "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_tenant_account_get", "mt_estimate_run", "mt_prefetch", "mt_cache_stats_get", "mt_admit", "mt_debug_poison", "mt_debug_copy",
                  "mt_set_profiling", "mt_get_profile"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -230,6 +231,15 @@ class Context:
         e = mt_run_estimate()
         self._check(self._lib.mt_estimate_run(self._h, arr, ctypes.byref(e)))
         return {k: getattr(e, k) for k, _ in mt_run_estimate._fields_}
+
+    def admit(self, pending, budget_ms: float):
+        """(admitted counts, estimate of the admitted run) for a device-time budget."""
+        T = self.cfg.max_tenants
+        arr = (ctypes.c_uint32 * T)(*[int(x) for x in pending])
+        out = (ctypes.c_uint32 * T)()
+        e = mt_run_estimate()
+        self._check(self._lib.mt_admit(self._h, arr, float(budget_ms), out, ctypes.byref(e)))
+        return [int(x) for x in out], {k: getattr(e, k) for k, _ in mt_run_estimate._fields_}
 
     def prefetch(self, tenants, stream_ptr: int = 0) -> None:
         arr = (ctypes.c_uint32 * max(1, len(tenants)))(*[int(t) for t in tenants])

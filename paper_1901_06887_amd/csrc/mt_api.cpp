@@ -1121,6 +1121,39 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
     return MT_OK;
 }
 
+mt_status mt_admit(mt_ctx* c, const uint32_t* pending, double budget_ms, uint32_t* admitted, mt_run_estimate* est)
+{
+    if (!c || !pending || !admitted) return MT_EINVAL;
+    if (!(budget_ms > 0.0)) return fail(c, MT_EINVAL, "the budget must be positive");
+    const uint32_t T = c->cfg.max_tenants;
+    uint32_t top = 0;
+    for (uint32_t t = 0; t < T; ++t) {
+        if (pending[t] && !c->tenants[t].registered) return fail(c, MT_ENOTFOUND, "tenant %u has no model", t);
+        top = std::max(top, pending[t]);
+    }
+    std::vector<uint32_t> trial(T);
+    mt_run_estimate e{};
+    auto fits = [&](uint32_t level) {
+        uint64_t rows = 0;
+        for (uint32_t t = 0; t < T; ++t) { trial[t] = std::min(pending[t], level); rows += trial[t]; }
+        if (rows > c->cfg.max_requests) return false;
+        if (mt_estimate_run(c, trial.data(), &e) != MT_OK) return false;
+        return e.device_ms + e.upload_ms <= budget_ms;
+    };
+    // the predicted time grows with the level (up to small steps where a larger batch changes
+    // the launch plan), so the highest level that fits is found by bisection and then verified
+    uint32_t lo = 0, hi = top;                  // invariant: level lo fits (0 always does)
+    while (lo < hi) {
+        const uint32_t mid = lo + (hi - lo + 1) / 2;
+        if (fits(mid)) lo = mid; else hi = mid - 1;
+    }
+    while (lo > 0 && !fits(lo)) --lo;
+    fits(lo);
+    for (uint32_t t = 0; t < T; ++t) admitted[t] = trial[t];
+    if (est) *est = e;
+    return MT_OK;
+}
+
 mt_status mt_set_profiling(mt_ctx* c, int enable)
 {
     if (!c) return MT_EINVAL;

@@ -236,3 +236,32 @@ def test_model_cache_bookkeeping_on_the_host():
     assert e.value.status == 2
     c.prefetch([0, 1, 2])
     c.close()
+
+
+def test_admission_is_max_min_fair_within_the_budget():
+    import paper_1901_06887_amd as mt
+    import workloads as wl
+    w = wl.c3(n_tenants=40, n_requests=6000, in_dim=256, widths=(128, 256), classes=20, seed=4)
+    ctx = mt.context_for(w.tenants, w.dtype, 4000, device=-1)          # fewer rows per run than are waiting
+    mt.register_tenants(ctx, w.tenants)
+    pending = np.bincount(w.tenant_ids, minlength=ctx.cfg.max_tenants)
+    everything = ctx.estimate_run(np.minimum(pending, 50))["device_ms"]
+    last_level = -1
+    for budget in (everything * 0.3, everything * 0.6, everything * 5):
+        admitted, est = ctx.admit(pending, budget)
+        admitted = np.array(admitted)
+        level = admitted.max()
+        assert np.array_equal(admitted, np.minimum(pending, level))             # a water level: nobody is passed over
+        assert admitted.sum() <= 4000 and est["rows"] == admitted.sum()
+        assert est["device_ms"] + est["upload_ms"] <= budget
+        assert level >= last_level                                              # a larger budget never admits less
+        last_level = level
+        if level < pending.max():                                                # one more per tenant would not fit
+            more = np.minimum(pending, level + 1)
+            assert more.sum() > 4000 or ctx.estimate_run(more)["device_ms"] > budget
+    admitted, est = ctx.admit(pending, 1e-4)                                     # nothing fits 0.1 us
+    assert sum(admitted) == 0 and est["device_ms"] == 0
+    with pytest.raises(B.MtError) as e:
+        ctx.admit(pending, 0.0)
+    assert e.value.status == 1
+    ctx.close()

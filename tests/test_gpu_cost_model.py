@@ -71,3 +71,35 @@ def test_estimated_run_time_matches_the_measured_one(name):
     print("%s: estimated %.4f ms, measured %.4f ms, ratio %.2f" % (name, est["device_ms"], measured, ratio), flush=True)
     assert abs(ratio - 1.0) <= (REL_TOL if name in wl.CONFIGS else REL_TOL_OTHER)
     ctx.close()
+
+
+def test_admitted_runs_keep_the_latency_budget():
+    # more requests are waiting than a run of the target latency can serve: admit a fair share of
+    # every tenant's backlog, run it, and find the measured device time within the budget
+    w = wl.c3()
+    ctx = mt.context_for(w.tenants, w.dtype, w.n_requests)
+    mt.register_tenants(ctx, w.tenants)
+    pending = np.bincount(w.tenant_ids, minlength=ctx.cfg.max_tenants)
+    d_x = torch_io.to_device(w.inputs, w.dtype)
+    order = np.argsort(w.tenant_ids, kind="stable")
+    start = np.concatenate([[0], np.cumsum(pending)])
+    for budget in (0.47, 0.52):      # (any request of a tenant costs a pass over its weights: ~0.45 ms for one request each)
+        admitted, est = ctx.admit(pending, budget)
+        admitted = np.array(admitted)
+        assert 0 < admitted.sum() < w.n_requests and admitted.max() < pending.max()
+        rows = np.sort(np.concatenate([order[start[t]:start[t] + admitted[t]] for t in range(len(pending))]))   # arrival order
+        d_ids = torch.from_numpy(np.ascontiguousarray(w.tenant_ids[rows])).cuda()
+        x = d_x[torch.from_numpy(rows).cuda()].contiguous()
+        out = torch_io.alloc_outputs(len(rows), ctx.cfg.max_classes)
+        for _ in range(3):
+            mt.serve(ctx, d_ids, x, out=out)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(15)]
+        for e0, e1 in ev:
+            e0.record(); mt.serve(ctx, d_ids, x, out=out); e1.record()
+        torch.cuda.synchronize()
+        measured = float(np.median([e0.elapsed_time(e1) for e0, e1 in ev]))
+        print("budget %.2f ms: level %d, %d of %d requests admitted, predicted %.3f ms, measured %.3f ms" % (
+            budget, admitted.max(), admitted.sum(), w.n_requests, est["device_ms"], measured), flush=True)
+        assert measured <= budget * (1 + REL_TOL)
+    ctx.close()
