@@ -80,7 +80,7 @@ def main():
                     help="first run the library's plain copy kernel over this many MiB (byte-counter yardstick)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        print("bench.py: this program runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
