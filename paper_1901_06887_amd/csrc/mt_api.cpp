@@ -81,6 +81,10 @@ struct mt_ctx {
     uint32_t max_in_len = 0;
     // [kind][layer]: kind 0 = FC tiles, 1 = conv tiles, 2 = big FC tiles
     uint32_t max_rpr[kListKinds][MT_MAX_LAYERS]{}, max_nt[kListKinds][MT_MAX_LAYERS]{}, has_gap[MT_MAX_LAYERS]{};
+    // pool_fused[l]: layer index l + 1 is a global average pool for every registered model that is that deep, and
+    // each of their convolutions at l can pool by itself: the convolution launch writes the pooled activation
+    // and nothing runs at index l + 1 (all or nothing: the activation buffers alternate per layer index)
+    bool pool_fused[MT_MAX_LAYERS]{};
     double sum_macs = 0.0;                           // multiply-accumulates of one request, summed over the registered tenants
     uint32_t max_conv_cb[MT_MAX_LAYERS]{};
     bool conv_quad[MT_MAX_LAYERS]{};                 // every conv of a layer index has input channels in multiples of four 16-byte chunks           // widest conv tile (32-channel blocks, at most 4) of a layer index
@@ -93,6 +97,7 @@ struct mt_ctx {
     uint32_t list_mask = 0;        // bit kind*MT_MAX_LAYERS + l: some registered model has that kind at layer l
     uint32_t max_reg_classes = 0, min_reg_classes = 0;
     uint32_t no_fused_head = 0;    // tuning/testing: always run the separate head kernel
+    uint32_t no_fused_pool = 0;    // tuning/testing: always run the separate pooling kernel
     uint32_t big_min_tiles = kBigMinTiles;   // testing: MT_BIG_MIN_TILES=1 sends every qualifying tenant-layer to big tiles
     uint32_t P_cap = 0;        // packed rows incl. per-tenant padding to 32
 
@@ -322,6 +327,19 @@ bool make_room(mt_ctx* c, uint64_t len, uint64_t protect, hipStream_t s, bool as
     return true;
 }
 
+void recompute_pool_fusion(mt_ctx* c)
+{
+    for (uint32_t l = 0; l + 1 < MT_MAX_LAYERS; ++l) {
+        bool any = false, all = true;
+        for (const HostTenant& t : c->tenants) {
+            if (!t.registered || t.n_layers <= l + 1) continue;
+            any = true;
+            all = all && t.layers[l + 1].dev.kind == MT_GAP && t.layers[l].dev.pool_fill != 0;
+        }
+        c->pool_fused[l] = any && all && !c->no_fused_pool;
+    }
+}
+
 void recompute_bounds(mt_ctx* c)
 {
     c->n_layer_slots = 0;
@@ -329,7 +347,7 @@ void recompute_bounds(mt_ctx* c)
     c->fc_first_chunked = true; c->any_conv_first = c->any_fc_first = false;
     c->list_mask = 0; c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        c->has_gap[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true;
+        c->has_gap[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
         c->max_fc_per64[l] = 0;
     }
@@ -431,6 +449,10 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
             d.cin = s.in_features; d.in_h = s.in_h; d.in_w = s.in_w; d.N = s.in_features; d.N_pad = s.in_features;
             d.out_len = s.in_features;
             hl.w_bytes = hl.b_bytes = 0;
+            // the convolution before it can pool by itself when every image lies inside one wave's pixel blocks
+            LayerDev& conv = out->layers[l - 1].dev;
+            if (conv.N % kWidthAlign == 0 && (conv.rows_per_req == kBrickRows || conv.rows_per_req == 2 * kBrickRows))
+                conv.pool_fill = round_up(s.in_features, kWidthAlign);
         } else {
             return fail(c, MT_EUNSUPPORTED, "layer %u: kind %u is not in the supported set", l, s.kind);
         }
@@ -516,6 +538,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     if (const char* e = getenv("MT_FC_SPLIT_K")) c->fc_split_k = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_GATHER")) c->no_fused_gather = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_HEAD")) c->no_fused_head = atoi(e) != 0;
+    if (const char* e = getenv("MT_NO_FUSED_POOL")) c->no_fused_pool = atoi(e) != 0;
     if (const char* e = getenv("MT_BIG_MIN_TILES")) c->big_min_tiles = (uint32_t)std::max(1, atoi(e));
     c->cache = cfg->cache != 0;
     c->tenants.resize(cfg->max_tenants);
@@ -677,6 +700,7 @@ mt_status mt_register_model(mt_ctx* c, uint32_t tenant, const mt_layer_spec* spe
     c->tenants[tenant] = ht;
     c->n_registered++;
     recompute_bounds(c);
+    recompute_pool_fusion(c);
     return MT_OK;
 }
 
@@ -740,6 +764,7 @@ mt_status mt_unregister_model(mt_ctx* c, uint32_t tenant)
     c->tenants[tenant] = HostTenant{};
     c->n_registered--;
     recompute_bounds(c);
+    recompute_pool_fusion(c);
     return MT_OK;
 }
 
@@ -879,9 +904,14 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         if (c->any_conv_first) TIMED(kProfGatherImg, launch_gather_image(g, s));
     }
 
+    uint32_t cur = 0;                      // activation buffer that holds the input of the next layer index
     for (uint32_t l = 0; l < c->n_layer_slots; ++l) {
-        const void* in = c->d_act[l & 1];
-        void* outb = c->d_act[(l + 1) & 1];
+        // a pooling index that the convolutions before it have already served: nothing runs, the
+        // pooled activation is where the next index reads
+        if (l > 0 && c->pool_fused[l - 1]) continue;
+        const void* in = c->d_act[cur];
+        void* outb = c->d_act[cur ^ 1];
+        cur ^= 1;
         for (int kind = 0; kind < kListKinds; ++kind) {
             const uint64_t grid = tile_bound(c, kind, l, R);
             if (grid == 0 || (kind == 2 && (!big_enabled || grid < c->big_min_tiles))) continue;   // no big tiles possible: the batcher made none
@@ -889,7 +919,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             ga.tile_base = c->d_tile_base + ((size_t)kind * MT_MAX_LAYERS + l) * (T + 1);
             ga.T = T; ga.layer = l; ga.fc_split_k = c->fc_split_k; ga.big_layers = b.big_layers;
             ga.gather = (kind == 0 && l == 0 && fuse_gather); ga.perm = c->d_perm; ga.row_src = c->d_row_src;
-            ga.fuse_head = fuse_head; ga.out = outp;
+            ga.fuse_head = fuse_head; ga.out = outp; ga.pool = kind == 1 && c->pool_fused[l];
             ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad; ga.zeros = c->d_zeros;
             const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, 0x7ffffff0u);
@@ -1062,6 +1092,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
     if (c->any_conv_first) launch(kUsSmallFixed + (img_in_mb + img_out_mb) / kCopyMbPerUs);
 
     for (uint32_t l = 0; l < c->n_layer_slots; ++l) {
+        if (l > 0 && c->pool_fused[l - 1]) continue;           // pooled by the convolutions of the index before
         // which tenants take big tiles at this layer index (the batcher's rule)
         uint64_t big_tiles = 0;
         if (big_enabled && c->max_nt[2][l] > 0)
@@ -1094,7 +1125,8 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
                     chain = std::max(chain, kUsFcChainFixed + kUsPerKStep * k_steps);
                 }
             } else if (d.kind == MT_CONV2D) {
-                conv_mb += (M * ((double)d.in_h * d.in_w * d.cin + d.out_len) * es + (double)d.N_pad * d.K * es) / MB;
+                const double out_elems = c->pool_fused[l] ? d.N : d.out_len;      // pooled on the way out
+                conv_mb += (M * ((double)d.in_h * d.in_w * d.cin + out_elems) * es + (double)d.N_pad * d.K * es) / MB;
                 conv_mflop += 2.0 * M * d.rows_per_req * d.k_valid * d.N / 1e6;
             } else {
                 gap_mb += M * ((double)d.in_h * d.in_w * d.cin + d.out_len) * es / MB;

@@ -69,6 +69,8 @@ struct LayerDev {
     uint32_t out_len;    // elements one request's output occupies
     uint32_t out_fill;   // out_len rounded up to kWidthAlign (zero-filled tail)
     uint32_t is_last;    // outputs are the logits
+    uint32_t pool_fill;  // CONV whose next layer is a global average pool that the convolution can do itself (whole images
+                         // per wave: 32 or 64 output pixels per image, channels a multiple of 64): the pool's out_fill, else 0
     uint64_t w_off;      // byte offset of the packed weights in the arena
     uint64_t b_off;      // byte offset of the fp32 bias in the arena (N_pad entries for FC)
 };
@@ -150,6 +152,7 @@ struct GatherArgs {
 struct GemmArgs {
     const uint32_t* tile_base; uint32_t T; uint32_t layer; uint32_t fc_split_k;
     const uint32_t* big_layers;   // the batcher's decision per layer index (see BatchArgs)
+    uint32_t pool;                // conv launch: the layers with pool_fill write the pooled activation instead of their own
     // FC layer 0 can read the submitted rows itself (16-byte aligned rows whose length is a
     // whole number of 16-byte chunks), which saves the staging pass:
     uint32_t gather; const int32_t* perm; const void* const* row_src;

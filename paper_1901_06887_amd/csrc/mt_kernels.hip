@@ -1522,7 +1522,7 @@ constexpr uint32_t kConvStageBytes = 8 * kConvKC * kBrickBytes;      // 4 pixel 
 // brick order; the MFMA operand read picks its 16 bytes from there (a 2-way bank conflict, on a
 // path that has the time).
 template <typename T, int NCB, bool QUAD>
-__global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_lds_kernel(GemmArgs a)     // three workgroups per CU is what the LDS ring allows
 {
     static_assert(!QUAD || kConvKC == 2, "a quad gather covers exactly two k steps");
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
@@ -1629,6 +1629,56 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(GemmArgs a)
     uint8_t* scratch = lds + wave * unit_scratch_bytes<T>();
     const float* bias = (const float*)(a.arena + L.b_off);
     const uint32_t nbase = (nb0 + wc) * kBrickRows;
+    if (a.pool && L.pool_fill) {
+        // The next layer averages every channel over the image, and the one or two pixel blocks of an
+        // image all belong to this wave: average here, from the activations as they would have been
+        // stored (rounded to T), and write the pooled row in the brick layout the FC layers read.  The
+        // image itself is never written.  Lane (li, lh) puts its values into the scratch as
+        // [pixel][channel]; lane (c, half) then adds channel c over pixels 16 half .. 16 half + 15.
+        constexpr uint32_t RS = unit_row_stride<T>();
+        const uint32_t bpi = rpr / kBrickRows, ch = lane & 31, half = lane >> 5;
+        const uint32_t nKBp = L.pool_fill / KB;
+        const float inv = 1.0f / (float)rpr;
+        float sum = 0.0f;
+#pragma unroll
+        for (uint32_t r = 0; r < RBW; ++r) {
+            const uint32_t blk = wr * RBW + r, mb = m0 + blk * kBrickRows;    // images are whole: a block is valid or not
+            f32x4 y[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 bv = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) y[g][i] = acc[r][4 * g + i] + bv[i];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            activate_block<4>(y, L.act);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                T o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (T)y[g][e];
+                uint8_t* p = scratch + li * RS + (8 * g + 4 * lh) * sizeof(T);
+                if constexpr (sizeof(T) == 2) *(uint64_t*)p = __builtin_bit_cast(uint64_t, o);
+                else *(u32x4*)p = __builtin_bit_cast(u32x4, o);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (mb < rows_total) {
+#pragma unroll
+                for (uint32_t p = 0; p < 16; ++p) sum += (float)*(const T*)(scratch + (half * 16 + p) * RS + ch * sizeof(T));
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if ((blk + 1) % bpi == 0) {                                      // the image is complete
+                sum += __shfl_xor(sum, 32);
+                if (half == 0 && mb < rows_total) {
+                    const uint32_t req = mb / rpr, cc = nbase + ch;
+                    T* out = (T*)a.act_out + (size_t)seg0 * a.S + (size_t)(req / kBrickRows) * nKBp * 64 * EPC;
+                    out[((size_t)(cc / KB) * 64 + req % kBrickRows + 32 * ((cc % KB) / EPC)) * EPC + cc % EPC] = (T)(sum * inv);
+                }
+                sum = 0.0f;
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (uint32_t r = 0; r < RBW; ++r) {
         const uint32_t m = m0 + (wr * RBW + r) * kBrickRows + li;

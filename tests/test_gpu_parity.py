@@ -137,6 +137,56 @@ def test_more_than_1024_classes():
     run_and_compare(wl.c2(n_tenants=3, n_requests=70, dims=(64, 96, 1100)), "wide-head")
 
 
+def rect_cnn(h, w, chans, strides, classes):
+    layers, hh, ww = [], h, w
+    for i, st in enumerate(strides):
+        l = wl.LayerSpec(wl.CONV, wl.ACT_RELU, chans[i], chans[i + 1], hh, ww, st)
+        layers.append(l)
+        hh, ww = l.out_hw()
+    layers.append(wl.LayerSpec(wl.GAP, wl.ACT_NONE, chans[-1], chans[-1], hh, ww))
+    layers.append(wl.LayerSpec(wl.FC, wl.ACT_NONE, chans[-1], classes))
+    return layers
+
+
+def cnn_workload(name, layer_lists, n_requests, dtype="bf16", seed=71):
+    tenants = {t: wl.make_model(l, dtype, seed, t) for t, l in enumerate(layer_lists)}
+    in_len = layer_lists[0][0].in_len()
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((n_requests, in_len)).astype(np.float32)
+    if dtype == "bf16":
+        import torch
+        x = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    ids = rng.integers(0, len(layer_lists), n_requests).astype(np.int32)
+    return wl.Workload(name, dtype, tenants, ids, x)
+
+
+def test_pooling_done_by_the_last_convolution(monkeypatch):
+    # 64-channel-multiple convolutions whose images have 64 (8x8) or 32 (8x4) output pixels pool by
+    # themselves when every model of the fleet allows it; the separate pooling kernel must agree
+    square = rect_cnn(16, 16, (3, 16, 64, 128), (1, 1, 2), 7)          # 8x8 final map, two channel groups of 64.. 128 channels
+    narrow = rect_cnn(16, 8, (3, 16, 64, 64), (1, 1, 2), 7)            # 8x4 final map: one pixel block per image
+    for name, lists in (("pool-8x8", [square, square]), ("pool-8x4", [narrow, narrow, narrow])):
+        w = cnn_workload(name, lists, 37)
+        ctx = make_context(w)
+        assert ctx.stats()["last_run_launches"] == 0
+        fused = gpu_run(ctx, w, poison=True)
+        n_fused = ctx.stats()["last_run_launches"]
+        compare(w, fused, oracle_rows(w), what=name)
+        ctx.close()
+        monkeypatch.setenv("MT_NO_FUSED_POOL", "1")
+        ctx = make_context(w)
+        apart = gpu_run(ctx, w, poison=True)
+        assert ctx.stats()["last_run_launches"] == n_fused + 1          # the pooling launch
+        monkeypatch.delenv("MT_NO_FUSED_POOL")
+        compare(w, apart, oracle_rows(w), what=name + " (separate pooling)")
+        assert np.array_equal(fused[2], apart[2]) and np.allclose(fused[0], apart[0], rtol=0, atol=2e-2)
+        ctx.close()
+    # a fleet in which one model cannot (40 channels): nobody does, and the answers still match
+    odd = rect_cnn(16, 16, (3, 16, 24, 40), (1, 1, 2), 7)
+    w = cnn_workload("pool-mixed", [square, odd], 29)
+    run_and_compare(w, "pool-mixed")
+
+
 # ---- full-size configurations ---------------------------------------------------------------
 def test_c2_full():
     run_and_compare(wl.c2(), "c2")
