@@ -36,7 +36,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 FP32_MATRIX_PEAK_TFLOPS = 157.3
 
 
-def gemm_launch_costs(w, es, rows_of=None):
+def gemm_launch_costs(w, es, rows_of=None, pooled_by_conv=False):
     """Algorithmic flops and bytes of the grouped GEMM launch of every layer index: each active
     tenant's weights and bias read once, its input rows read once, its output rows written once
     (hidden: element type; logits: fp32).  `rows_of(rows, layer)`: the rows of a tenant-layer
@@ -59,7 +59,10 @@ def gemm_launch_costs(w, es, rows_of=None):
                 f = 2 * m_t * oh * ow * 9 * L.in_features * L.out_features
             b = model.weights[l].size * es + model.biases[l].size * 4
             b += m_t * L.in_len() * es
-            b += m_t * L.out_len() * (4 if l == n - 1 else es)
+            if pooled_by_conv and l + 1 < n and model.layers[l + 1].kind == wl.GAP:
+                b += m_t * L.out_features * es          # the launch writes the pooled activation, not the image
+            else:
+                b += m_t * L.out_len() * (4 if l == n - 1 else es)
             flops[l] = flops.get(l, 0) + f
             bytes_[l] = bytes_.get(l, 0) + b
     return flops, bytes_
@@ -188,7 +191,10 @@ def main():
     fc_ms = [float(np.mean([p["fc_ms"][l] + p["fc_big_ms"][l] for p in prof])) for l in range(n_slots)]
     big_ms = [float(np.mean([p["fc_big_ms"][l] for p in prof])) for l in range(n_slots)]
     conv_ms = [float(np.mean([p["conv_ms"][l] for p in prof])) for l in range(n_slots)]
-    flops, bytes_ = gemm_launch_costs(w, es)
+    # a mix with pooling layers but no pooling launch: the convolutions before them pooled on the way out
+    has_pool = any(L.kind == wl.GAP for m in w.tenants.values() for L in m.layers)
+    pool_ms = sum(float(np.mean([p["gap_ms"][l] for p in prof])) for l in range(n_slots))
+    flops, bytes_ = gemm_launch_costs(w, es, pooled_by_conv=has_pool and pool_ms == 0.0)
     # the dominant kernel: the grouped FC kernel, or the grouped conv kernel for the CNN mix
     dom_ms, dom_name = (fc_ms, "fc_kernel") if sum(fc_ms) >= sum(conv_ms) else (conv_ms, "conv_kernel")
     if dom_ms is fc_ms and sum(big_ms) > 0.5 * sum(fc_ms):

@@ -21,10 +21,11 @@
  *   - "HOST" pointers are ordinary process memory; "DEVICE" pointers are HIP
  *     device memory on the context's GPU (e.g. a torch tensor's data_ptr()).
  *   - A context is not thread-safe.  One mt_run may be in flight per context, or
- *     cfg.run_slots of them when they are enqueued on different streams: mt_run
- *     number i uses slot i % run_slots and first makes its stream wait for the run
- *     that used the slot before.  Result queries (mt_last_counts) refer to the run
- *     enqueued last.
+ *     cfg.run_slots of them when they are enqueued on different streams: a run
+ *     takes the slot (batch descriptors, activation buffers) that its stream used
+ *     last, else a slot not used yet, else the one used longest ago, whose run its
+ *     stream then waits for on the device.  Result queries (mt_last_counts) refer
+ *     to the run enqueued last.
  *   - Element type of weights, inputs and hidden activations is the context's
  *     dtype: MT_F32 (4 bytes) or MT_BF16 (2 bytes, bfloat16 bit patterns).
  *     Biases, logits and probabilities are always fp32.  With MT_BF16 every

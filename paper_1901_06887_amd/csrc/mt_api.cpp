@@ -60,6 +60,7 @@ struct RunSlot {
     void* d_act[2] = {nullptr, nullptr}; float* d_logits = nullptr;
     hipEvent_t done = nullptr;      // recorded behind the slot's last run
     hipStream_t stream = nullptr;   // ... which was enqueued here
+    uint64_t last_run = 0;          // ... and was the context's run number this
     bool used = false;
 };
 
@@ -838,7 +839,13 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         if (c->cache_pending && c->cache_stream != s) HIP_TRY(c, hipStreamWaitEvent(s, c->cache_event, 0));
     }
     // the run's slot of device scratch; a stream other than the one that used it last waits for that run
-    RunSlot& rs = c->slots[c->run_count % c->slots.size()];
+    // (the slot this stream used last, so that runs on one stream keep their buffers and never wait
+    // across streams; else a slot nobody has used; else the one used longest ago)
+    RunSlot* pick = nullptr;
+    for (RunSlot& r : c->slots) if (r.used && r.stream == s) { pick = &r; break; }
+    if (!pick) for (RunSlot& r : c->slots) if (!r.used) { pick = &r; break; }
+    if (!pick) { pick = &c->slots[0]; for (RunSlot& r : c->slots) if (r.last_run < pick->last_run) pick = &r; }
+    RunSlot& rs = *pick;
     if (rs.used && rs.stream != s) HIP_TRY(c, hipStreamWaitEvent(s, rs.done, 0));
     bind_slot(c, rs);
     const uint32_t slot = (uint32_t)(c->run_count % kSegSlots);
@@ -949,7 +956,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     HIP_TRY(c, hipEventRecord(c->seg_event[slot], s));
     c->seg_busy[slot] = true;
     HIP_TRY(c, hipEventRecord(rs.done, s));
-    rs.used = true; rs.stream = s;
+    rs.used = true; rs.stream = s; rs.last_run = c->run_count;
     c->run_count++;
     c->last_stream = s;
     c->pending.clear();
