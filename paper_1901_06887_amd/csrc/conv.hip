@@ -1,0 +1,450 @@
+// Grouped 3x3 convolution as implicit GEMM (see mt_device.h for the overview).
+#include "mt_device.h"
+
+namespace mt {
+
+// ---- helpers of the implicit-GEMM convolutions ---------------------------------------------
+// Quotient and remainder by a wave-uniform divisor; image sizes are mostly powers of two, and a
+// general 32-bit division costs some thirty vector instructions per lane.
+__device__ __forceinline__ void divmod_uniform(uint32_t x, uint32_t d, uint32_t* q, uint32_t* r)
+{
+    if ((d & (d - 1)) == 0) { *q = x >> __builtin_ctz(d); *r = x & (d - 1); }
+    else { *q = x / d; *r = x - *q * d; }
+}
+
+// A lane's walk through K = (kernel row, kernel column, channel), one k step at a time.  Inside
+// a kernel row the three taps of a pixel are one contiguous run of 3 * cin input elements, so the
+// position is kept as (kernel row th, offset lin inside the run) and the element offset `cur`
+// moves by KB per step plus a jump at the end of a run.  Validity is two range tests: the
+// left/right tap falls outside the image only at the image's left/right edge, the top/bottom
+// kernel row only at its top/bottom edge.  Steps past the last tap have th == 3: invalid.
+template <typename T>
+struct TapWalk {
+    static constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    uint32_t lin, th, run, lo, hi, tlo, thi, step;
+    int32_t cur, jump;
+    // first: the lane's first element inside the run; step_el: elements per call of next()
+    // (at most one run ends per call: step_el <= 3 * cin)
+    __device__ __forceinline__ void init(const LayerDev& L, int32_t ih0, int32_t iw0, bool row_ok, uint32_t first, uint32_t step_el)
+    {
+        const int32_t cin = (int32_t)L.cin;
+        run = 3 * L.cin; lin = first; th = 0; step = step_el;
+        lo = iw0 < 0 ? L.cin : 0; hi = iw0 + 2 >= (int32_t)L.in_w ? 2 * L.cin : 3 * L.cin;
+        tlo = ih0 < 0 ? 1 : 0; thi = row_ok ? (ih0 + 2 >= (int32_t)L.in_h ? 2 : 3) : 0;
+        cur = (ih0 * (int32_t)L.in_w + iw0) * cin + (int32_t)lin;
+        jump = ((int32_t)L.in_w - 3) * cin;
+    }
+    // the 16-byte chunk of this k step inside the image, or -1 when the step reads zeros; moves on
+    __device__ __forceinline__ int32_t next()
+    {
+        const bool ok = (lin >= lo) & (lin < hi) & (th >= tlo) & (th < thi);
+        const int32_t chunk = ok ? (int32_t)((uint32_t)cur / EPC) : -1;
+        lin += step; cur += (int32_t)step;
+        const bool wrap = lin >= run;
+        lin = wrap ? lin - run : lin; th += wrap ? 1u : 0u; cur = wrap ? cur + jump : cur;
+        return chunk;
+    }
+};
+
+// ---- NHWC store of one 32-pixel x 32-channel unit held in the transposed accumulator layout ----
+// After an MFMA with the filter brick as row operand, lane (li, lh) holds channels 8g + 4 lh +
+// {0..3} of pixel li: stored from there, a wave instruction writes 64 separate 8- or 16-byte
+// pieces, and the texture path counts (and takes time for) every one of them; the counters
+// showed the convolution kernels bound by exactly that rate.  So the unit goes through a
+// wave-private LDS scratch as [pixel][channel] rows and is read back so that consecutive
+// lanes hold consecutive 16-byte chunks of a pixel's row: a pixel's 64 (bf16) or 128 (fp32)
+// bytes leave in one piece.  Each pixel's destination travels through the scratch as well
+// (null for pixels past the end), so the storing lane needs no index arithmetic.
+template <typename T> constexpr uint32_t unit_row_stride() { return kBrickRows * sizeof(T) + 16; }
+template <typename T> constexpr uint32_t unit_scratch_bytes() { return kBrickRows * unit_row_stride<T>() + kBrickRows * 8; }
+
+template <typename T>
+__device__ __forceinline__ void store_unit_nhwc(const f32x4 (&y)[4], T* my_pixel_out, uint32_t n_valid, uint8_t* scratch)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), RS = unit_row_stride<T>();
+    constexpr uint32_t CP = kBrickRows / EPC;                       // 16-byte chunks per pixel row: 4 (bf16) or 8 (fp32)
+    const uint32_t lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
+    T** dests = (T**)(scratch + kBrickRows * RS);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        T o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (T)y[g][e];
+        uint8_t* p = scratch + li * RS + (8 * g + 4 * lh) * sizeof(T);
+        if constexpr (sizeof(T) == 2) *(uint64_t*)p = __builtin_bit_cast(uint64_t, o);
+        else *(u32x4*)p = __builtin_bit_cast(u32x4, o);
+    }
+    if (lh == 0) dests[li] = my_pixel_out;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // the wave's own LDS writes have landed
+#pragma unroll
+    for (uint32_t pass = 0; pass < CP / 2; ++pass) {
+        const uint32_t px = pass * (64 / CP) + lane / CP, ch = lane % CP;
+        T* dst = dests[px];
+        const u32x4 v = *(const u32x4*)(scratch + px * RS + ch * 16);
+        if (dst != nullptr && ch * EPC < n_valid) *(u32x4*)(dst + ch * EPC) = v;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // reads done before the next unit overwrites the scratch
+}
+
+// ---- grouped 3x3 convolution as implicit GEMM ---------------------------------------------
+// GEMM view: rows = (request, output pixel), columns = output channels, K = (kh, kw, c_in).
+// A workgroup takes 128 consecutive rows of one tenant and up to 128 output channels; each of
+// its four waves owns 32 rows and all the channels, and no operand is shared between waves:
+// the activation operand of a k step is gathered straight from the NHWC input into MFMA
+// registers (16 bytes per lane = 8 channels of one tap; taps outside the image read as
+// zeros), the filter bricks come from L1/L2 (a layer's filters are at most ~150 KB and shared
+// by every tile of the tenant).  The MFMA takes the filter brick as its row operand and the
+// pixels as its column operand, so a lane ends up with runs of four consecutive channels of
+// ITS pixel, whose address it already derived for its loads; the unit then leaves through the
+// wave's store scratch (store_unit_nhwc).  No barrier anywhere.
+template <typename T, int CB>
+__device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, uint32_t seg0, uint32_t m0, uint32_t rows_total, uint32_t nb0, uint8_t* scratch)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC, P = 4;
+    typedef const __attribute__((address_space(1))) u32x4* gptr_t;
+    const uint32_t lane = threadIdx.x & 63, li = lane & 31, lh = lane >> 5;
+    const uint32_t nKB = L.K / KB, nKBv = ceil_div(L.k_valid, KB);  // bricks per filter row; k steps that hold real taps
+    const uint32_t rpr = L.rows_per_req;
+
+    // this lane's GEMM row: request, output pixel, top-left input coordinate
+    const uint32_t m = m0 + li;
+    const bool row_ok = m < rows_total;
+    const uint32_t mm = row_ok ? m : m0;                           // rows past the end repeat the first one and are dropped
+    uint32_t req, pix, oh, ow;
+    divmod_uniform(mm, rpr, &req, &pix);
+    divmod_uniform(pix, L.out_w, &oh, &ow);
+    const int32_t ih0 = (int32_t)(oh * L.stride) - 1, iw0 = (int32_t)(ow * L.stride) - 1;
+    gptr_t img = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
+    gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)nb0 * nKB * 64 + lane);
+
+    // The next k step's chunk.  Taps outside the image, steps past the last tap and rows past the
+    // end read a block of zeros instead: the choice is made on the address, so nothing waits on
+    // the loaded value before its MFMA.
+    gptr_t zeros = (gptr_t)a.zeros;
+    TapWalk<T> walk;
+    walk.init(L, ih0, iw0, row_ok, lh * EPC, KB);
+    auto load_a = [&]() -> u32x4 {
+        const int32_t chunk = walk.next();
+        gptr_t p = chunk >= 0 ? img + chunk : zeros;
+        return *p;
+    };
+
+    f32x16 acc[CB];
+#pragma unroll
+    for (int c = 0; c < CB; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][v] = 0.0f;
+    // both operands of a k step travel P steps ahead of their use in register rings
+    u32x4 aq[P], wq[P][CB];
+    auto load_w = [&](uint32_t j, uint32_t kb) {
+#pragma unroll
+        for (int c = 0; c < CB; ++c) wq[j][c] = wp[((size_t)c * nKB + kb) * 64];
+    };
+#pragma unroll
+    for (uint32_t j = 0; j < P; ++j) {
+        aq[j] = load_a();
+        load_w(j, min(j, nKBv - 1));
+    }
+    const uint32_t full = nKBv / P;
+    for (uint32_t g = 0; g < full; ++g) {
+#pragma unroll
+        for (uint32_t j = 0; j < P; ++j) {
+            const uint32_t kb = g * P + j;
+#pragma unroll
+            for (int c = 0; c < CB; ++c) Mma<T>::run(acc[c], wq[j][c], aq[j]);   // rows = channels, columns = pixels
+            aq[j] = load_a();
+            load_w(j, min(kb + P, nKBv - 1));
+            __builtin_amdgcn_sched_barrier(0);                     // keeps the refills here, P steps ahead of their use
+        }
+    }
+#pragma unroll
+    for (uint32_t j = 0; j < P; ++j) {
+        const uint32_t kb = full * P + j;
+        if (kb < nKBv) {
+#pragma unroll
+            for (int c = 0; c < CB; ++c) Mma<T>::run(acc[c], wq[j][c], aq[j]);
+        }
+    }
+
+    // epilogue: the lane holds, for pixel li, channels 8g + 4 lh + {0..3} (g = 0..3) of every
+    // channel block: bias, activation, rounding, coalesced store through the wave's scratch
+    const float* bias = (const float*)(a.arena + L.b_off);
+    T* out = row_ok ? (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N : nullptr;
+#pragma unroll
+    for (int c = 0; c < CB; ++c) {
+        const uint32_t nbase = (nb0 + c) * kBrickRows;
+        f32x4 y[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 bv = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);   // bias is padded to N_pad
+#pragma unroll
+            for (int i = 0; i < 4; ++i) y[g][i] = acc[c][4 * g + i] + bv[i];
+        }
+        activate_block<4>(y, L.act);
+        // N is a multiple of 8, so the channels of this block that exist are whole 16-byte chunks for bf16 and pairs of them for fp32
+        store_unit_nhwc<T>(y, out ? out + nbase : nullptr, min((uint32_t)kBrickRows, L.N - nbase), scratch);
+    }
+}
+
+// MAXCB bounds the channel blocks of any tile in the launch: narrow layers get a kernel with
+// few registers and many resident waves, which is what hides the latency of their short K loops.
+template <typename T, int MAXCB>
+__global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
+{
+    __shared__ uint32_t base_l[kMaxTenantsPadded + 1];
+    __shared__ __attribute__((aligned(16))) uint8_t unit_scratch[4 * unit_scratch_bytes<T>()];
+    const uint32_t tid = threadIdx.x, wave = tid >> 6;
+    uint8_t* scratch = unit_scratch + wave * unit_scratch_bytes<T>();
+    const uint32_t n_tiles = a.tile_base[a.T];
+    for (uint32_t i = tid; i <= a.T; i += 256) base_l[i] = a.tile_base[i];
+    uint32_t idx;
+    if (!logical_tile(n_tiles, &idx)) return;
+    __syncthreads();
+    const uint32_t t = __builtin_amdgcn_readfirstlane(find_tenant(base_l, a.T, idx));   // uniform: the tenant's facts come through scalar loads
+    const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[t]);
+    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    const uint32_t seg0 = a.off[t];
+    const uint32_t rows_total = a.M[t] * L.rows_per_req, mt_ = ceil_div(rows_total, kConvTileRows);
+    const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
+    const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
+    // no barrier below: the waves are independent; wave w takes row blocks w, w+4, ... of the tile
+    for (uint32_t rb = wave; rb < kConvTileRows / kBrickRows; rb += 4) {
+        const uint32_t m0 = (local % mt_) * kConvTileRows + rb * kBrickRows;
+        if (m0 >= rows_total) break;
+        if constexpr (MAXCB == 1) {
+            conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0, scratch);
+        } else if constexpr (MAXCB == 2) {
+            if (ncb == 1) conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0, scratch);
+            else conv_wave<T, 2>(a, L, seg0, m0, rows_total, nb0, scratch);
+        } else {
+            if (ncb == 1) conv_wave<T, 1>(a, L, seg0, m0, rows_total, nb0, scratch);
+            else if (ncb == 2) conv_wave<T, 2>(a, L, seg0, m0, rows_total, nb0, scratch);
+            else if (ncb == 3) conv_wave<T, 3>(a, L, seg0, m0, rows_total, nb0, scratch);
+            else conv_wave<T, 4>(a, L, seg0, m0, rows_total, nb0, scratch);
+        }
+    }
+}
+
+// ---- convolution tiles of two or more channel blocks: activation operand shared through LDS --
+// Same tile (128 pixels x <= 128 channels) and tile list as conv_kernel, other division of
+// labour.  With every wave gathering its own 32 pixels, each wave also streams the whole
+// filter bank; here the waves stand side by side instead (NCB = 4: one 32-channel block and
+// all four pixel blocks per wave; NCB = 2: 2x2), so a wave streams the filters of one channel
+// block only and the gathered activation bricks are shared.  Neither operand passes through
+// registers: wave w forms the bricks of pixel block w, and fetches the filter bricks of its
+// own channel block, with direct global->LDS loads, one per k step, each lane supplying the
+// address of its 16 bytes (for the activations: 8 channels of one tap, or a block of zeros
+// for taps outside the image) and the hardware placing lane l at base + 16 l, which is brick
+// order.  K is walked in chunks of kConvKC k steps through a ring of kConvNS stages, chunks
+// kConvNS - 1 ahead of their use.
+constexpr uint32_t kConvKC = 2, kConvNS = 3;
+constexpr uint32_t kConvStageBytes = 8 * kConvKC * kBrickBytes;      // 4 pixel blocks + 4 filter areas, kConvKC k steps each
+
+// QUAD (every tenant's input channels are a multiple of 4 chunks, i.e. a pixel's share of two k
+// steps is 64 contiguous bytes): a gather instruction then takes 16 pixels with four consecutive
+// lanes on one pixel's 64 bytes, instead of 32 pixels with one 16-byte piece per lane.  The
+// texture path handles a lane quad on one cache line as one access, so the gather costs a quarter
+// of the accesses.  The hardware's lane placement then yields [pixel][chunk] order instead of
+// brick order; the MFMA operand read picks its 16 bytes from there (a 2-way bank conflict, on a
+// path that has the time).
+template <typename T, int NCB, bool QUAD>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_lds_kernel(GemmArgs a)     // three workgroups per CU is what the LDS ring allows
+{
+    static_assert(!QUAD || kConvKC == 2, "a quad gather covers exactly two k steps");
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    constexpr uint32_t WR = 4 / NCB, RBW = 4 / WR;                  // wave rows; pixel blocks per wave
+    typedef const __attribute__((address_space(1))) u32x4* gptr_t;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kConvNS * kConvStageBytes];
+    static_assert(kConvNS * kConvStageBytes >= (kMaxTenantsPadded + 1) * 4, "tile_base must fit");
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lh = lane >> 5;
+    uint32_t* base_l = (uint32_t*)lds;
+    const uint32_t n_tiles = a.tile_base[a.T];
+    for (uint32_t i = tid; i <= a.T; i += 256) base_l[i] = a.tile_base[i];
+    uint32_t idx;
+    if (!logical_tile(n_tiles, &idx)) return;
+    __syncthreads();
+    const uint32_t t = __builtin_amdgcn_readfirstlane(find_tenant(base_l, a.T, idx));   // uniform: the tenant's facts come through scalar loads
+    const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[t]);
+    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    const uint32_t seg0 = a.off[t];
+    const uint32_t rpr = L.rows_per_req;
+    const uint32_t rows_total = a.M[t] * rpr, mt_ = ceil_div(rows_total, kConvTileRows);
+    const uint32_t m0 = (local % mt_) * kConvTileRows;
+    const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
+    const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
+    const uint32_t nKB = L.K / KB, nKBv = ceil_div(L.k_valid, KB);
+    const uint32_t n_chunks = ceil_div(nKBv, kConvKC);             // n_chunks * kConvKC <= nKB: K is padded to 64
+    const uint32_t wc = wave % NCB, wr = wave / NCB;
+    const bool active = wc < ncb;                                  // idle waves still gather; they stream block 0 and drop it
+
+    // gather role: pixel block `wave`.  Plain: this lane's pixel li, 16 bytes per k step.  QUAD:
+    // pixels lane/4 and lane/4 + 16, chunk lane%4 of the 64 bytes that two k steps take of each.
+    constexpr uint32_t NPX = QUAD ? 2 : 1;
+    gptr_t zeros = (gptr_t)a.zeros;
+    gptr_t img[NPX];
+    TapWalk<T> walk[NPX];
+#pragma unroll
+    for (uint32_t i = 0; i < NPX; ++i) {
+        const uint32_t gm = m0 + wave * kBrickRows + (QUAD ? (lane >> 2) + 16 * i : li);
+        const bool row_ok = gm < rows_total;
+        const uint32_t mm = row_ok ? gm : m0;
+        uint32_t req, pix, oh, ow;
+        divmod_uniform(mm, rpr, &req, &pix);
+        divmod_uniform(pix, L.out_w, &oh, &ow);
+        img[i] = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
+        walk[i].init(L, (int32_t)(oh * L.stride) - 1, (int32_t)(ow * L.stride) - 1, row_ok,
+                     QUAD ? (lane & 3) * EPC : lh * EPC, QUAD ? 2 * KB : KB);
+    }
+    gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
+    const uint32_t last_kb = n_chunks * kConvKC - 1;
+    // The next kConvKC k steps of this wave's pixel block and of its filter block: 2 * kConvKC
+    // loads.  Chunks past the end gather zeros (th >= 3) and repeat the last filter bricks, which
+    // keeps the number of loads per round, and with it the wait below, uniform.
+    auto fetch_chunk = [&](uint32_t c) {
+        uint8_t* dst = lds + (c % kConvNS) * kConvStageBytes;
+#pragma unroll
+        for (uint32_t kk = 0; kk < kConvKC; ++kk) {
+            // plain: k step kk of all 32 pixels; QUAD: both k steps of pixels 16 kk .. 16 kk + 15
+            const int32_t chunk = walk[QUAD ? kk : 0].next();
+            gptr_t p = chunk >= 0 ? img[QUAD ? kk : 0] + chunk : zeros;
+            lds_dma16(p, dst + (wave * kConvKC + kk) * kBrickBytes);
+            lds_dma16(wp + (size_t)min(c * kConvKC + kk, last_kb) * 64, dst + ((4 + wave) * kConvKC + kk) * kBrickBytes);
+        }
+    };
+    // where lane (li, lh) finds its 16 bytes of k step kk inside a pixel block's area of a stage
+    const uint32_t a_lane = QUAD ? (li * 4 + lh) * 16 : lane * 16;
+    constexpr uint32_t a_kk = QUAD ? 32 : kBrickBytes;
+
+    f32x16 acc[RBW];
+#pragma unroll
+    for (uint32_t r = 0; r < RBW; ++r)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[r][v] = 0.0f;
+
+    __syncthreads();                                               // the lookup is over before the ring reuses the memory
+#pragma unroll
+    for (uint32_t c = 0; c < kConvNS - 1; ++c) fetch_chunk(c);
+    // when chunk c is needed, the loads of the kConvNS - 2 younger chunks may still be in flight
+    constexpr uint32_t kOut = (kConvNS - 2) * 2 * kConvKC;
+    constexpr int kWaitVm = (int)((kOut & 15) | ((kOut >> 4) << 14) | 0x0070 | 0x0F00);
+    for (uint32_t c = 0; c < n_chunks; ++c) {
+        __builtin_amdgcn_s_waitcnt(kWaitVm);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();                              // chunk c is complete for every wave; everyone is done with chunk c - 1
+        asm volatile("" ::: "memory");
+        fetch_chunk(c + kConvNS - 1);
+        const uint8_t* st = lds + (c % kConvNS) * kConvStageBytes;
+#pragma unroll
+        for (uint32_t kk = 0; kk < kConvKC; ++kk) {
+            const u32x4 wv = *(const u32x4*)(st + ((4 + wave) * kConvKC + kk) * kBrickBytes + lane * 16);
+#pragma unroll
+            for (uint32_t r = 0; r < RBW; ++r) {
+                const u32x4 av = *(const u32x4*)(st + (wr * RBW + r) * kConvKC * kBrickBytes + kk * a_kk + a_lane);
+                Mma<T>::run(acc[r], wv, av);                       // rows = channels, columns = pixels
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // this wave's LDS reads of the chunk are done before its next barrier
+    }
+    // trailing loads have landed and every wave is done with the ring: its memory now serves as
+    // the waves' store scratch
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    static_assert(kConvNS * kConvStageBytes >= 4 * unit_scratch_bytes<T>(), "store scratch aliases the ring");
+
+    // epilogue: lane holds, for pixel li of each of its pixel blocks, channels 8g + 4 lh + {0..3}
+    if (!active) return;
+    uint8_t* scratch = lds + wave * unit_scratch_bytes<T>();
+    const float* bias = (const float*)(a.arena + L.b_off);
+    const uint32_t nbase = (nb0 + wc) * kBrickRows;
+    if (a.pool && L.pool_fill) {
+        // The next layer averages every channel over the image, and the one or two pixel blocks of an
+        // image all belong to this wave: average here, from the activations as they would have been
+        // stored (rounded to T), and write the pooled row in the brick layout the FC layers read.  The
+        // image itself is never written.  Lane (li, lh) puts its values into the scratch as
+        // [pixel][channel]; lane (c, half) then adds channel c over pixels 16 half .. 16 half + 15.
+        constexpr uint32_t RS = unit_row_stride<T>();
+        const uint32_t bpi = rpr / kBrickRows, ch = lane & 31, half = lane >> 5;
+        const uint32_t nKBp = L.pool_fill / KB;
+        const float inv = 1.0f / (float)rpr;
+        float sum = 0.0f;
+#pragma unroll
+        for (uint32_t r = 0; r < RBW; ++r) {
+            const uint32_t blk = wr * RBW + r, mb = m0 + blk * kBrickRows;    // images are whole: a block is valid or not
+            f32x4 y[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 bv = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) y[g][i] = acc[r][4 * g + i] + bv[i];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            activate_block<4>(y, L.act);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                T o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (T)y[g][e];
+                uint8_t* p = scratch + li * RS + (8 * g + 4 * lh) * sizeof(T);
+                if constexpr (sizeof(T) == 2) *(uint64_t*)p = __builtin_bit_cast(uint64_t, o);
+                else *(u32x4*)p = __builtin_bit_cast(u32x4, o);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (mb < rows_total) {
+#pragma unroll
+                for (uint32_t p = 0; p < 16; ++p) sum += (float)*(const T*)(scratch + (half * 16 + p) * RS + ch * sizeof(T));
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if ((blk + 1) % bpi == 0) {                                      // the image is complete
+                sum += __shfl_xor(sum, 32);
+                if (half == 0 && mb < rows_total) {
+                    const uint32_t req = mb / rpr, cc = nbase + ch;
+                    T* out = (T*)a.act_out + (size_t)seg0 * a.S + (size_t)(req / kBrickRows) * nKBp * 64 * EPC;
+                    out[((size_t)(cc / KB) * 64 + req % kBrickRows + 32 * ((cc % KB) / EPC)) * EPC + cc % EPC] = (T)(sum * inv);
+                }
+                sum = 0.0f;
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (uint32_t r = 0; r < RBW; ++r) {
+        const uint32_t m = m0 + (wr * RBW + r) * kBrickRows + li;
+        T* out = nullptr;
+        if (m < rows_total) {
+            uint32_t req, pix;
+            divmod_uniform(m, rpr, &req, &pix);
+            out = (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N + nbase;
+        }
+        f32x4 y[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 bv = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);   // bias is padded to N_pad; re-read per block (L1) to keep registers free
+#pragma unroll
+            for (int i = 0; i < 4; ++i) y[g][i] = acc[r][4 * g + i] + bv[i];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        activate_block<4>(y, L.act);
+        store_unit_nhwc<T>(y, out, min((uint32_t)kBrickRows, L.N - nbase), scratch);
+    }
+}
+
+// ---- launcher ------------------------------------------------------------
+template <typename T>
+static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, uint32_t grid, hipStream_t s)
+{
+    if (max_cb <= 1) hipLaunchKernelGGL((conv_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a);
+    else if (max_cb == 2 && quad) hipLaunchKernelGGL((conv_lds_kernel<T, 2, true>), dim3(grid), dim3(256), 0, s, a);
+    else if (max_cb == 2) hipLaunchKernelGGL((conv_lds_kernel<T, 2, false>), dim3(grid), dim3(256), 0, s, a);
+    else if (quad) hipLaunchKernelGGL((conv_lds_kernel<T, 4, true>), dim3(grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((conv_lds_kernel<T, 4, false>), dim3(grid), dim3(256), 0, s, a);
+}
+
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t grid, hipStream_t s)
+{
+    if (grid == 0) return hipSuccess;
+    grid = (grid + 7) / 8 * 8;
+    if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, quad, grid, s);
+    else launch_conv_t<float>(a, max_cb, quad, grid, s);
+    return hipGetLastError();
+}
+
+}  // namespace mt

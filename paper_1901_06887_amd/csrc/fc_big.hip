@@ -1,0 +1,249 @@
+// Grouped FC layer, compute-bound 256x256 tiles (see mt_device.h for the overview).
+#include "mt_device.h"
+
+namespace mt {
+
+// ---- grouped FC, big tiles ---------------------------------------------------------------
+// Tenant-layers with at least kBigMinRows requests are compute bound.  They are cut into
+// 256x256 output tiles; a workgroup of eight waves (2x4, 128x64 = 4x2 MFMA blocks per wave, two
+// waves per SIMD so that one wave's operand fetches overlap the other's MFMAs) walks K two
+// bricks at a time through a ring of four 32 KiB LDS stages.  Both operands arrive as bricks, so a
+// stage is filled with straight 1 KiB copies (each wave copies two of the 16 row/column blocks) and
+// read back with conflict-free 16-byte-per-lane loads.  Per k step a workgroup moves 16 KiB from L2
+// for 64 MFMAs (half the operand traffic per flop of the 128x128 streaming tile) and reads
+// 48 KiB from LDS, ~60 % of what the LDS pipe sustains with two waves per SIMD.
+constexpr uint32_t kBigKS = 2;                                                   // k steps per stage
+constexpr uint32_t kBigNS = 4;                                                   // stages in the LDS ring
+constexpr uint32_t kBigBlocks = kBigTile / kBrickRows;                            // 8 row blocks, 8 column blocks
+constexpr uint32_t kBigStageBytes = 2 * kBigBlocks * kBigKS * kBrickBytes;        // 32 KiB
+constexpr uint32_t kBigGroup = 4;                                                 // row tiles that sweep the columns together
+
+// WV waves per workgroup: 8 (2x4, 128x64 per wave) or 4 (2x2, 128x128 per wave, one wave per SIMD
+// with its accumulators in the second half of the 512-entry register file).
+template <typename T, int WV>
+__global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
+{
+    constexpr uint32_t WN = WV / 2;                          // waves side by side
+    constexpr uint32_t CJ = kBigBlocks / WN;                 // column blocks per wave (2 or 4)
+    constexpr uint32_t BPW = 2 * kBigBlocks / WV;            // row/column blocks a wave stages (2 or 4)
+    constexpr uint32_t LPS = BPW * kBigKS;                   // loads a wave issues per stage
+    __shared__ __attribute__((aligned(16))) uint8_t stages[kBigNS * kBigStageBytes];
+    uint8_t* const stage0 = stages;
+    static_assert(kBigStageBytes >= (kMaxTenantsPadded + 1) * 4, "tile_base must fit the first stage");
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t li = lane & 31, lh = lane >> 5;
+
+    uint32_t* base_l = (uint32_t*)stage0;                   // tile_base during the lookup
+    const uint32_t n_tiles = a.tile_base[a.T];
+    for (uint32_t i = tid; i <= a.T; i += WV * 64) base_l[i] = a.tile_base[i];
+    uint32_t idx;
+    if (!logical_tile_chunked(n_tiles, &idx)) return;
+    __syncthreads();
+    const uint32_t t = __builtin_amdgcn_readfirstlane(find_tenant(base_l, a.T, idx));   // uniform: the tenant's facts come through scalar loads
+    const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[t]);
+    __syncthreads();
+    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    const uint32_t Mt = a.M[t], seg0 = a.off[t];
+    const uint32_t nKB = L.K / KB;
+    // tile order inside a tenant: groups of kBigGroup row tiles sweep all column tiles together, so
+    // the tiles that run at the same time on one XCD share few activation and weight panels (L2 reuse)
+    const uint32_t Mb = big_rows(Mt);                      // a short remainder is the streaming kernel's
+    const uint32_t mt_ = ceil_div(Mb, kBigTile), nt_ = ceil_div(L.N_pad, kBigTile);
+    const uint32_t per_group = kBigGroup * nt_, grp = local / per_group, first_m = grp * kBigGroup;
+    const uint32_t gsz = min(mt_ - first_m, kBigGroup), in_grp = local - grp * per_group;
+    const uint32_t m0 = (first_m + in_grp % gsz) * kBigTile, n0 = (in_grp / gsz) * kBigTile;
+    const uint32_t rows = min((uint32_t)kBigTile, Mb - m0), nrb = ceil_div(rows, kBrickRows);
+    const uint32_t ncb = min(kBigBlocks, L.N_pad / kBrickRows - n0 / kBrickRows);
+    const uint32_t wm = wave / WN, wn = wave % WN;
+
+    // staging: waves 0..3 copy the 8 activation row blocks, waves 4..7 the 8 weight column blocks
+    // (blocks past the tile or the layer repeat the last valid one)
+    // staging: the first half of the waves copies the 8 activation row blocks, the second half the
+    // 8 weight column blocks, BPW blocks each (blocks past the tile or the layer repeat the last valid one)
+    const u32x4* lp[BPW];
+    {
+        const u32x4* xbase = (const u32x4*)((const T*)a.act_in + (size_t)seg0 * a.S) + lane;
+        const u32x4* wbase = (const u32x4*)(a.arena + L.w_off) + lane;
+#pragma unroll
+        for (uint32_t i = 0; i < BPW; ++i) {
+            if (wave < WV / 2) lp[i] = xbase + (size_t)(m0 / kBrickRows + min(wave * BPW + i, nrb - 1)) * nKB * 64;
+            else lp[i] = wbase + (size_t)(n0 / kBrickRows + min((wave - WV / 2) * BPW + i, ncb - 1)) * nKB * 64;
+        }
+    }
+    f32x16 acc[4][CJ];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < (int)CJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // Operands travel HBM/L2 -> LDS without passing through registers (16 bytes per lane, the
+    // hardware places lane l at base + 16 l, which is exactly a brick), three stages ahead of
+    // their use.  A wave issues four such loads per stage, so "stage s has landed" is "at most
+    // eight of my loads are outstanding"; the barrier that follows extends that to every wave's
+    // share and also says that everyone is done reading the stage about to be overwritten.
+    typedef const __attribute__((address_space(1))) void* gvoid_t;
+    typedef __attribute__((address_space(3))) void* lvoid_t;
+    auto issue_stage = [&](uint32_t slot, uint32_t s) {      // data of stage s into ring slot `slot`
+        uint8_t* dst = stages + (slot % kBigNS) * kBigStageBytes + (wave * BPW) * kBigKS * kBrickBytes;
+#pragma unroll
+        for (uint32_t i = 0; i < BPW; ++i)
+#pragma unroll
+            for (uint32_t kk = 0; kk < kBigKS; ++kk)
+                __builtin_amdgcn_global_load_lds((gvoid_t)(lp[i] + (size_t)(s * kBigKS + kk) * 64),
+                                                 (lvoid_t)(dst + (i * kBigKS + kk) * kBrickBytes), 16, 0, 0);
+    };
+    // MFMA operands of one k step: 4 activation bricks and 2 weight bricks of this wave
+    auto read_ops = [&](const uint8_t* buf, uint32_t kk, u32x4 (&a4)[4], u32x4 (&b2)[CJ]) {
+        const uint8_t* ab = buf + (wm * 4 * kBigKS) * kBrickBytes + lane * 16;
+        const uint8_t* bb = buf + ((kBigBlocks + wn * CJ) * kBigKS) * kBrickBytes + lane * 16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a4[i] = *(const u32x4*)(ab + (i * kBigKS + kk) * kBrickBytes);
+#pragma unroll
+        for (int j = 0; j < (int)CJ; ++j) b2[j] = *(const u32x4*)(bb + (j * kBigKS + kk) * kBrickBytes);
+    };
+    auto mma_rows = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[CJ], int i0, int i1) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i)
+#pragma unroll
+            for (int j = 0; j < (int)CJ; ++j) Mma<T>::run(acc[i][j], b2[j], a4[i]);   // weights as the row operand: see the epilogue
+    };
+    auto mma_all = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[CJ]) { mma_rows(a4, b2, 0, 4); };
+    static_assert(kBigKS == 2, "the loop below is written for two k steps per stage");
+
+    // The two k steps of a stage use two operand register sets, X and Y.  LDS reads of one set
+    // are always issued in front of the MFMAs of the other, and the second k step of a stage is
+    // multiplied after the next stage's barrier, so neither the LDS latency nor the barrier
+    // leaves the MFMA pipe without work.
+    const uint32_t n_stages = nKB / kBigKS, last = n_stages - 1;   // nKB is a multiple of 4: at least two stages
+    // The waits are spelled with the builtin so that the compiler's own wait-count bookkeeping
+    // sees them (an asm wait is invisible to it, and it would then wait again, too strictly);
+    // the empty asm statements keep memory operations from moving across the barrier.
+    // Encoding: vmcnt in bits 3:0 (and 15:14), expcnt 6:4, lgkmcnt 11:8; a field at its maximum does not wait.
+    constexpr uint32_t kOut = 2 * LPS;                       // loads of the two younger stages may stay in flight
+    constexpr int kWaitVm = (int)((kOut & 15) | ((kOut >> 4) << 14) | 0x0070 | 0x0F00), kWaitVmLgkm0 = kWaitVm & ~0x0F00;
+    auto ring_barrier = [&](bool lds_too) {
+        if (lds_too) __builtin_amdgcn_s_waitcnt(kWaitVmLgkm0); else __builtin_amdgcn_s_waitcnt(kWaitVm);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+#pragma unroll
+    for (uint32_t s = 0; s < kBigNS - 1; ++s) issue_stage(s, min(s, last));
+    ring_barrier(false);                                                     // stage 0 is complete for every wave
+    issue_stage(kBigNS - 1, min(kBigNS - 1, last));
+    // A wave whose four row blocks all lie past the end of a ragged tile only helps with staging
+    // and barriers (its own loop, so that the working loop stays free of branches); its SIMD's
+    // MFMA pipe is left to the wave that has rows.
+    if (__builtin_amdgcn_readfirstlane(wm * 4 < nrb)) {
+        u32x4 xa[4], xb[CJ], ya[4], yb[CJ];
+        read_ops(stages, 0, xa, xb);
+        read_ops(stages, 1, ya, yb);
+        __builtin_amdgcn_sched_barrier(0);
+        mma_all(xa, xb);
+        for (uint32_t s = 1; s < n_stages; ++s) {
+            // stage s is complete for every wave; every wave holds what it needs of stage s - 1 in
+            // registers, so ring slot (s + 3) % 4 can be refilled
+            ring_barrier(true);
+            issue_stage(s + kBigNS - 1, min(s + kBigNS - 1, last));   // past the end: a harmless repeat keeps the count uniform
+            const uint8_t* buf = stages + (s % kBigNS) * kBigStageBytes;
+            read_ops(buf, 0, xa, xb);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_all(ya, yb);                                          // second k step of stage s - 1
+            __builtin_amdgcn_sched_barrier(0);
+            mma_rows(xa, xb, 0, 1);                                   // first k step of stage s; its operands had the MFMAs above to arrive
+            __builtin_amdgcn_sched_barrier(0);
+            read_ops(buf, 1, ya, yb);                                 // issued behind the wait for X, so that wait does not cover them
+            __builtin_amdgcn_sched_barrier(0);
+            mma_rows(xa, xb, 1, 4);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        mma_all(ya, yb);
+    } else {
+        for (uint32_t s = 1; s < n_stages; ++s) {
+            ring_barrier(true);
+            issue_stage(s + kBigNS - 1, min(s + kBigNS - 1, last));
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // trailing repeats landed, all reads done
+
+    // epilogue.  The MFMAs took the weight bricks as their row operand, so a lane holds, for
+    // activation row li of each block, outputs n = 8g + 4 lh + {0..3} (g = 0..3): runs of four
+    // consecutive outputs of ITS row.  fp32: a run is a lane's 16 bytes of an output brick.
+    // bf16: two lanes (lh = 0, 1) hold the halves of every 8-output run; one exchange between
+    // the wave's halves per dword (v_permlane32_swap) leaves lanes lh = 0 with runs 0 and 2 and
+    // lanes lh = 1 with runs 1 and 3, again a lane's 16 bytes of an output brick.  No LDS.  The
+    // blocks are walked with a scheduling fence after each, which keeps the register need of the
+    // epilogue at one block.
+    const float* bias = (const float*)(a.arena + L.b_off);
+    const uint32_t nKB_out = L.out_fill / KB;
+    auto block = [&](const f32x16& blk, uint32_t i, uint32_t j) {
+        const uint32_t rb = wm * 4 + i;
+        if (rb < nrb && wn * CJ + j < ncb) {
+            const uint32_t nb = n0 / kBrickRows + wn * CJ + j, nl = nb * kBrickRows + 4 * lh;   // first output of this lane's runs
+            const uint32_t mb = m0 + rb * kBrickRows;          // first row of the block inside the tenant
+            f32x4 y[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 bq = *(const f32x4*)(bias + nl + 8 * g);                            // bias is padded to N_pad
+#pragma unroll
+                for (int e = 0; e < 4; ++e) y[g][e] = blk[4 * g + e] + bq[e];
+            }
+            if (L.is_last) {
+                if (mb + li < Mt) {
+                    float* row = a.logits + (size_t)(seg0 + mb + li) * a.C_pad;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        if (nl + 8 * g < L.N) *(f32x4*)(row + nl + 8 * g) = y[g];                 // may run into the row's padding (C_pad >= N_pad)
+                }
+            } else {
+                u32x4* out = (u32x4*)((T*)a.act_out + (size_t)seg0 * a.S) +
+                             ((size_t)(mb / kBrickRows) * nKB_out + nb * (kBrickRows / KB)) * 64 + lane;
+                // outputs past N need no masking: their weight rows and bias are zero padding, and
+                // every activation of the layer set maps 0 to 0
+                activate_block<4>(y, L.act);
+                if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) out[g * 64] = __builtin_bit_cast(u32x4, y[g]);   // brick g of the block, half lh
+                } else {
+                    uint32_t pk[4][2];                                                          // run halves as two packed dwords
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        T o[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (T)y[g][e];
+                        const uint64_t q = __builtin_bit_cast(uint64_t, o);
+                        pk[g][0] = (uint32_t)q; pk[g][1] = (uint32_t)(q >> 32);
+                    }
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {                                              // runs (0,1) -> brick 0 of the block, (2,3) -> brick 1
+                        const auto s0 = __builtin_amdgcn_permlane32_swap(pk[2 * h][0], pk[2 * h + 1][0], false, false);
+                        const auto s1 = __builtin_amdgcn_permlane32_swap(pk[2 * h][1], pk[2 * h + 1][1], false, false);
+                        out[h * 64] = u32x4{s0[0], s1[0], s0[1], s1[1]};
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < (int)CJ; ++j) block(acc[i][j], i, j);
+}
+
+// ---- launcher ------------------------------------------------------------
+hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s)
+{
+    if (grid == 0) return hipSuccess;
+    grid = (grid + 8 * kXcdChunk - 1) / (8 * kXcdChunk) * (8 * kXcdChunk);
+    // (the 4-wave shape, 128x128 per wave at one wave per SIMD, reads a third less from LDS per
+    // MFMA but was measured 1.5x slower: a single wave per SIMD leaves the MFMA pipe idle at every wait)
+    if (dtype == MT_BF16) hipLaunchKernelGGL((fc_big_kernel<__bf16, 8>), dim3(grid), dim3(512), 0, s, a);
+    else hipLaunchKernelGGL((fc_big_kernel<float, 8>), dim3(grid), dim3(512), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace mt

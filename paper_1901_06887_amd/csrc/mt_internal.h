@@ -1,5 +1,5 @@
 // Internal declarations shared by the host runtime (mt_api.cpp) and the device code
-// (mt_kernels.hip).  Not part of the public ABI.
+// (the .hip files, through mt_device.h).  Not part of the public ABI.
 #pragma once
 #include <stdint.h>
 #include <hip/hip_runtime.h>
@@ -178,7 +178,7 @@ struct HeadArgs {
     uint32_t vec_ok;        // output rows can be written 16 bytes at a time (aligned buffers, row stride a multiple of 4)
 };
 
-// Launchers (defined in mt_kernels.hip).  All enqueue on `s` and return the launch status.
+// Launchers (defined next to their kernels).  All enqueue on `s` and return the launch status.
 hipError_t launch_batcher(const BatchArgs& a, hipStream_t s);   // three launches when a.n_rank_groups > 0
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
 hipError_t launch_gather_image(const GatherArgs& a, hipStream_t s);

@@ -18,7 +18,8 @@ import re
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-KERNEL_SOURCES = ("csrc/mt_kernels.hip", "csrc/mt_internal.h")
+KERNEL_SOURCES = ("csrc/mt_device.h", "csrc/batcher.hip", "csrc/fc_stream.hip", "csrc/fc_big.hip", "csrc/conv.hip", "csrc/small.hip",
+                  "csrc/mt_internal.h")
 
 
 def kernel_source_sha256() -> str:
