@@ -128,7 +128,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg);
 /* Free everything the context owns (synchronises the device first). */
 mt_status mt_destroy(mt_ctx* ctx);
 
-/* Upload a tenant's DNN (paper section 3: "users first upload a DNN").
+/* Upload a tenant's DNN (paper section 3: a tenant hands over its model before it sends requests).
  *   specs[n_layers]: layer chain; out length of layer l must equal in length of l+1.
  *   weights[l]: HOST, context dtype; FC [N][K] row-major, CONV [C_out][C_in][3][3];
  *               ignored (may be NULL) for GAP.
@@ -145,8 +145,8 @@ mt_status mt_register_model(mt_ctx* ctx, uint32_t tenant, const mt_layer_spec* s
  * mt_run that may serve the tenant is still executing.  Errors: MT_ENOTFOUND. */
 mt_status mt_unregister_model(mt_ctx* ctx, uint32_t tenant);
 
-/* Queue n_rows requests of ONE tenant for the next mt_run (paper section 3: "then
- * start sending inference requests").  inputs: DEVICE, n_rows rows of the model's
+/* Queue n_rows requests of ONE tenant for the next mt_run (paper section 3: once its
+ * model is in place a tenant sends inference requests).  inputs: DEVICE, n_rows rows of the model's
  * input length, contiguous, context dtype; borrowed until the next mt_run's stream
  * work has completed.  *first_index (optional) receives the submission index of the
  * first row.  Errors: MT_EINVAL, MT_ENOTFOUND, MT_EFULL. */
