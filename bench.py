@@ -16,6 +16,8 @@ models already resident in device memory.  Prints one JSON line.
               `traffic` is the HBM bytes per launch of that kernel from stored hardware-counter
               runs (profiles/), null when there is none for this workload or the device code
               has changed since they were taken
+  one_run_at_a_time  also carries host_enqueue_us_per_step: wall time of the K submit + run calls
+              before the final wait (an upper bound of the host's cost per step: a full queue blocks)
   device_ms   per-step device time between two events around the run (median, p99/mean), and
               the same with the caches flushed between steps (`cold`): a batch whose weights
               fit the last-level cache is otherwise partly served from it on repeated runs
@@ -122,6 +124,7 @@ def main():
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
+    host_dt = time.perf_counter() - t0          # the host's share: mt_submit_batch + mt_run through the binding, K times
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -262,7 +265,8 @@ def main():
     # headline: throughput of the timed steps with `interleave` runs in flight (every step is a whole
     # mt_run over the whole batch; nothing is shared between steps but the registered weights);
     # `one_run_at_a_time` is the same number of steps enqueued on one stream, each after the other
-    one_at_a_time = {"value": value, "unit": "inferences/sec", "ms_per_step": ms_per_step}
+    one_at_a_time = {"value": value, "unit": "inferences/sec", "ms_per_step": ms_per_step,
+                     "host_enqueue_us_per_step": host_dt / args.steps * 1e6}
     if interleaved is not None:
         value, ms_per_step = interleaved["value"], interleaved["ms_per_step"]
     line = {"metric": "inferences/sec across tenants at 1 GPU", "value": value, "unit": "inferences/sec",
