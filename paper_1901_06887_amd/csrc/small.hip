@@ -15,6 +15,32 @@ __device__ void gather_image(const GatherArgs& a, const TenantDev& td, uint32_t 
     T* dst = (T*)a.act + (size_t)p * a.S;
     const uint32_t ci = td.in_cin ? td.in_cin : kChanPad, cp = td.in_cin ? td.in_cin_pad : kChanPad;
     const uint32_t npix = td.in_len / ci;
+    if (sizeof(T) == 2 && ci == 3 && cp == 8 && npix % 2 == 0 && ((uintptr_t)src & 3) == 0) {
+        // three-channel bf16 images, the usual case: two pixels are three aligned dwords; a thread
+        // reads them, issues all its loads first, and writes two padded pixels of 16 bytes
+        const uint32_t* s32 = (const uint32_t*)src;
+        u32x4* d16 = (u32x4*)dst;
+        constexpr uint32_t kPairs = 4;                       // pixel pairs in flight per thread
+        for (uint32_t base = 0; base < npix / 2; base += kPairs * blockDim.x) {
+            uint32_t w[kPairs][3];
+#pragma unroll
+            for (uint32_t i = 0; i < kPairs; ++i) {
+                const uint32_t pp = min(base + i * blockDim.x + threadIdx.x, npix / 2 - 1);
+#pragma unroll
+                for (uint32_t j = 0; j < 3; ++j) w[i][j] = s32[(size_t)pp * 3 + j];
+            }
+#pragma unroll
+            for (uint32_t i = 0; i < kPairs; ++i) {
+                const uint32_t pp = base + i * blockDim.x + threadIdx.x;
+                if (pp < npix / 2) {
+                    d16[2 * pp] = u32x4{w[i][0], w[i][1] & 0xffffu, 0, 0};
+                    d16[2 * pp + 1] = u32x4{(w[i][1] >> 16) | (w[i][2] << 16), w[i][2] >> 16, 0, 0};
+                }
+            }
+        }
+        for (uint32_t e = npix * cp + threadIdx.x; e < td.in_fill; e += blockDim.x) dst[e] = (T)0.0f;
+        return;
+    }
     for (uint32_t pix = threadIdx.x; pix < npix; pix += blockDim.x) {
         for (uint32_t g = 0; g < cp; g += EPC) {
             alignas(16) T tmp[EPC];
