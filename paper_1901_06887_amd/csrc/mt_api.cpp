@@ -849,9 +849,13 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     if (rs.used && rs.stream != s) HIP_TRY(c, hipStreamWaitEvent(s, rs.done, 0));
     bind_slot(c, rs);
     const uint32_t slot = (uint32_t)(c->run_count % kSegSlots);
-    if (c->seg_busy[slot]) { HIP_TRY(c, hipEventSynchronize(c->seg_event[slot])); c->seg_busy[slot] = false; }
-    std::memcpy(c->h_segs[slot], c->pending.data(), c->pending.size() * sizeof(Segment));
+    // A run of one submission carries its segment in the kernel arguments; only runs of several
+    // submissions put the table into one of the pinned slots, which stays busy until the run is over.
     const uint32_t n_segs = (uint32_t)c->pending.size();
+    if (n_segs > 1) {
+        if (c->seg_busy[slot]) { HIP_TRY(c, hipEventSynchronize(c->seg_event[slot])); c->seg_busy[slot] = false; }
+        std::memcpy(c->h_segs[slot], c->pending.data(), c->pending.size() * sizeof(Segment));
+    }
     const uint32_t T = c->cfg.max_tenants;
     uint32_t launches = 0;
 
@@ -953,8 +957,10 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
 #undef TIMED
     c->prof_valid = c->profiling;
 
-    HIP_TRY(c, hipEventRecord(c->seg_event[slot], s));
-    c->seg_busy[slot] = true;
+    if (n_segs > 1) {
+        HIP_TRY(c, hipEventRecord(c->seg_event[slot], s));
+        c->seg_busy[slot] = true;
+    }
     HIP_TRY(c, hipEventRecord(rs.done, s));
     rs.used = true; rs.stream = s; rs.last_run = c->run_count;
     c->run_count++;
