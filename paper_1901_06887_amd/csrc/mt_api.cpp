@@ -196,13 +196,6 @@ bool arena_alloc(mt_ctx* c, uint64_t len, uint64_t* off)
     return false;
 }
 
-bool arena_fits(const mt_ctx* c, uint64_t len)
-{
-    len = round_up64(len, kArenaAlign);
-    for (const FreeBlock& b : c->free_list) if (b.len >= len) return true;
-    return false;
-}
-
 void arena_free(mt_ctx* c, uint64_t off, uint64_t len)
 {
     len = round_up64(len, kArenaAlign);
@@ -671,11 +664,12 @@ mt_status mt_register_model(mt_ctx* c, uint32_t tenant, const mt_layer_spec* spe
     }
     auto drop_stage = [&]() { if (c->cache && stage) (void)hipHostFree(stage); };
 
-    // Registration is synchronous.  If models have to give way, every run in flight ends first.
+    // Registration is synchronous.  In cache mode every run in flight ends first: models may have to
+    // give way, and a block that an earlier eviction freed may still be read by a run enqueued before it.
     uint64_t off = 0;
     hipError_t e = hipSuccess;
     const uint64_t stamp = ++c->use_clock;
-    if (c->cache && !c->host_only && !arena_fits(c, total)) {
+    if (c->cache && !c->host_only) {
         const hipError_t es = hipDeviceSynchronize();
         if (es != hipSuccess) { drop_stage(); return fail(c, MT_EDEVICE, "device synchronisation failed: %s", hipGetErrorString(es)); }
     }
@@ -723,30 +717,37 @@ mt_status mt_prefetch(mt_ctx* c, const uint32_t* tenants, uint32_t n, void* hip_
             if (r.used) HIP_TRY(c, hipStreamWaitEvent(s, r.done, 0));
         if (c->cache_pending && c->cache_stream != s) HIP_TRY(c, hipStreamWaitEvent(s, c->cache_event, 0));
     }
-    for (uint32_t i = 0; i < n; ++i) {
+    mt_status result = MT_OK;
+    for (uint32_t i = 0; i < n && result == MT_OK; ++i) {
         HostTenant& ht = c->tenants[tenants[i]];
         if (ht.resident) continue;
         uint64_t off = 0;
         hipError_t e = hipSuccess;
         if (!make_room(c, ht.arena_len, stamp, s, true, &off, &e)) {
-            if (e != hipSuccess) return fail(c, MT_EDEVICE, "eviction failed: %s", hipGetErrorString(e));
-            return fail(c, MT_ENOMEM, "the models named do not fit the weight arena together (%llu of %llu bytes in use, tenant %u needs %llu)",
-                        (unsigned long long)c->arena_used, (unsigned long long)c->cfg.arena_bytes, tenants[i], (unsigned long long)ht.arena_len);
+            result = e != hipSuccess ? fail(c, MT_EDEVICE, "eviction failed: %s", hipGetErrorString(e))
+                                     : fail(c, MT_ENOMEM, "the models named do not fit the weight arena together (%llu of %llu bytes in use, tenant %u needs %llu)",
+                                            (unsigned long long)c->arena_used, (unsigned long long)c->cfg.arena_bytes, tenants[i], (unsigned long long)ht.arena_len);
+            break;
         }
         if (!c->host_only) {
             place_tenant(c, ht, off, ht.stage);
             e = upload_tenant(c, tenants[i], ht, ht.stage, s, true);
-            if (e != hipSuccess) { arena_free(c, off, ht.arena_len); return fail(c, MT_EDEVICE, "upload of tenant %u failed: %s", tenants[i], hipGetErrorString(e)); }
+            if (e != hipSuccess) {
+                arena_free(c, off, ht.arena_len);
+                result = fail(c, MT_EDEVICE, "upload of tenant %u failed: %s", tenants[i], hipGetErrorString(e));
+                break;
+            }
         } else {
             ht.arena_off = off;
         }
         ht.resident = true;
     }
-    if (!c->host_only) {
-        HIP_TRY(c, hipEventRecord(c->cache_event, s));
+    if (!c->host_only) {                            // also after a failure: part of the changes may be enqueued
+        const hipError_t e = hipEventRecord(c->cache_event, s);
+        if (e != hipSuccess && result == MT_OK) result = fail(c, MT_EDEVICE, "hipEventRecord failed: %s", hipGetErrorString(e));
         c->cache_pending = true; c->cache_stream = s;
     }
-    return MT_OK;
+    return result;
 }
 
 mt_status mt_unregister_model(mt_ctx* c, uint32_t tenant)
