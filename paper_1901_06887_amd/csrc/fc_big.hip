@@ -151,13 +151,17 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
             const uint8_t* buf = stages + (s % kBigNS) * kBigStageBytes;
             read_ops(buf, 0, xa, xb);
             __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(1);                            // a wave with MFMAs to issue goes before its SIMD partner's loads and waits (~1 %)
             mma_all(ya, yb);                                          // second k step of stage s - 1
             __builtin_amdgcn_sched_barrier(0);
             mma_rows(xa, xb, 0, 1);                                   // first k step of stage s; its operands had the MFMAs above to arrive
+            __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
             read_ops(buf, 1, ya, yb);                                 // issued behind the wait for X, so that wait does not cover them
             __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(1);
             mma_rows(xa, xb, 1, 4);
+            __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
         }
         mma_all(ya, yb);
