@@ -171,6 +171,17 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
             issue_stage(s + kBigNS - 1, min(s + kBigNS - 1, last));
         }
     }
+    // the bias values of this wave's column blocks (the same for all its row blocks), fetched
+    // here so that the wait below covers them: loading them block by block in the epilogue put
+    // eight dependent L2 round trips on every tile's critical path
+    const float* bias = (const float*)(a.arena + L.b_off);
+    f32x4 bias_q[CJ][4];
+#pragma unroll
+    for (uint32_t j = 0; j < CJ; ++j) {
+        const uint32_t nb = n0 / kBrickRows + min(wn * CJ + j, ncb - 1);          // blocks past the layer repeat the last one (unused)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) bias_q[j][g] = *(const f32x4*)(bias + nb * kBrickRows + 4 * lh + 8 * g);   // bias is padded to N_pad
+    }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // trailing repeats landed, all reads done
 
     // epilogue.  The MFMAs took the weight bricks as their row operand, so a lane holds, for
@@ -181,7 +192,6 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     // lanes lh = 1 with runs 1 and 3, again a lane's 16 bytes of an output brick.  No LDS.  The
     // blocks are walked with a scheduling fence after each, which keeps the register need of the
     // epilogue at one block.
-    const float* bias = (const float*)(a.arena + L.b_off);
     const uint32_t nKB_out = L.out_fill / KB;
     auto block = [&](const f32x16& blk, uint32_t i, uint32_t j) {
         const uint32_t rb = wm * 4 + i;
@@ -191,9 +201,8 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
             f32x4 y[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const f32x4 bq = *(const f32x4*)(bias + nl + 8 * g);                            // bias is padded to N_pad
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[g][e] = blk[4 * g + e] + bq[e];
+                for (int e = 0; e < 4; ++e) y[g][e] = blk[4 * g + e] + bias_q[j][g][e];
             }
             if (L.is_last) {
                 if (mb + li < Mt) {
