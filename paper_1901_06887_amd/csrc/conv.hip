@@ -347,14 +347,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
     // trailing loads have landed and every wave is done with the ring: its memory now serves as
     // the waves' store scratch
+    // (this wave's bias values, the same for all its pixel blocks, are fetched in front of that
+    // wait: fetched block by block they put a memory round trip per block on the tile's tail)
+    const float* bias = (const float*)(a.arena + L.b_off);
+    const uint32_t nbase = (nb0 + (active ? wc : 0)) * kBrickRows;
+    f32x4 bias_q[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) bias_q[g] = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);   // bias is padded to N_pad
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     static_assert(kConvNS * kConvStageBytes >= 4 * unit_scratch_bytes<T>(), "store scratch aliases the ring");
 
     // epilogue: lane holds, for pixel li of each of its pixel blocks, channels 8g + 4 lh + {0..3}
     if (!active) return;
     uint8_t* scratch = lds + wave * unit_scratch_bytes<T>();
-    const float* bias = (const float*)(a.arena + L.b_off);
-    const uint32_t nbase = (nb0 + wc) * kBrickRows;
     if (a.pool && L.pool_fill) {
         // The next layer averages every channel over the image, and the one or two pixel blocks of an
         // image all belong to this wave: average here, from the activations as they would have been
@@ -372,9 +377,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             f32x4 y[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const f32x4 bv = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) y[g][i] = acc[r][4 * g + i] + bv[i];
+                for (int i = 0; i < 4; ++i) y[g][i] = acc[r][4 * g + i] + bias_q[g][i];
             }
             __builtin_amdgcn_sched_barrier(0);
             activate_block<4>(y, L.act);
@@ -417,9 +421,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         f32x4 y[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const f32x4 bv = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);   // bias is padded to N_pad; re-read per block (L1) to keep registers free
 #pragma unroll
-            for (int i = 0; i < 4; ++i) y[g][i] = acc[r][4 * g + i] + bv[i];
+            for (int i = 0; i < 4; ++i) y[g][i] = acc[r][4 * g + i] + bias_q[g][i];
         }
         __builtin_amdgcn_sched_barrier(0);
         activate_block<4>(y, L.act);
