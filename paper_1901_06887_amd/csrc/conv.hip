@@ -191,19 +191,19 @@ __device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, 
 template <typename T, int MAXCB>
 __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
 {
-    __shared__ uint32_t base_l[kMaxTenantsPadded + 1];
+    __shared__ uint32_t owner_part[4];
     __shared__ __attribute__((aligned(16))) uint8_t unit_scratch[4 * unit_scratch_bytes<T>()];
     const uint32_t tid = threadIdx.x, wave = tid >> 6;
     uint8_t* scratch = unit_scratch + wave * unit_scratch_bytes<T>();
+    TileOwner<256> lookup;
+    lookup.fetch(a.tile_base, a.T);
     const uint32_t n_tiles = a.tile_base[a.T];
-    for (uint32_t i = tid; i <= a.T; i += 256) base_l[i] = a.tile_base[i];
     uint32_t idx;
     if (!logical_tile(n_tiles, &idx)) return;
-    __syncthreads();
-    const uint32_t t = __builtin_amdgcn_readfirstlane(find_tenant(base_l, a.T, idx));   // uniform: the tenant's facts come through scalar loads
-    const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[t]);
+    const uint32_t t = lookup.owner(a.T, idx, owner_part);   // uniform: the tenant's facts come through scalar loads
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     const uint32_t seg0 = a.off[t];
+    const uint32_t local = idx - a.tile_base[t];
     const uint32_t rows_total = a.M[t] * L.rows_per_req, mt_ = ceil_div(rows_total, kConvTileRows);
     const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
     const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
@@ -255,18 +255,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     constexpr uint32_t WR = 4 / NCB, RBW = 4 / WR;                  // wave rows; pixel blocks per wave
     typedef const __attribute__((address_space(1))) u32x4* gptr_t;
     __shared__ __attribute__((aligned(16))) uint8_t lds[kConvNS * kConvStageBytes];
-    static_assert(kConvNS * kConvStageBytes >= (kMaxTenantsPadded + 1) * 4, "tile_base must fit");
+    __shared__ uint32_t owner_part[4];
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lh = lane >> 5;
-    uint32_t* base_l = (uint32_t*)lds;
+    TileOwner<256> lookup;
+    lookup.fetch(a.tile_base, a.T);
     const uint32_t n_tiles = a.tile_base[a.T];
-    for (uint32_t i = tid; i <= a.T; i += 256) base_l[i] = a.tile_base[i];
     uint32_t idx;
     if (!logical_tile(n_tiles, &idx)) return;
-    __syncthreads();
-    const uint32_t t = __builtin_amdgcn_readfirstlane(find_tenant(base_l, a.T, idx));   // uniform: the tenant's facts come through scalar loads
-    const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[t]);
+    const uint32_t t = lookup.owner(a.T, idx, owner_part);   // uniform: the tenant's facts come through scalar loads
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     const uint32_t seg0 = a.off[t];
+    const uint32_t local = idx - a.tile_base[t];
     const uint32_t rpr = L.rows_per_req;
     const uint32_t rows_total = a.M[t] * rpr, mt_ = ceil_div(rows_total, kConvTileRows);
     const uint32_t m0 = (local % mt_) * kConvTileRows;
@@ -321,7 +320,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[r][v] = 0.0f;
 
-    __syncthreads();                                               // the lookup is over before the ring reuses the memory
 #pragma unroll
     for (uint32_t c = 0; c < kConvNS - 1; ++c) fetch_chunk(c);
     // when chunk c is needed, the loads of the kConvNS - 2 younger chunks may still be in flight

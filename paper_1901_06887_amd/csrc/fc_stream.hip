@@ -208,9 +208,9 @@ __device__ __forceinline__ void fc_accumulate_direct(const GemmArgs& a, const Ti
 }
 
 template <typename T, int RB, int P, bool GATHER>
-__device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const LayerDev& L, uint32_t Mt, uint8_t* smem)
+__device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const LayerDev& L, uint32_t Mt, uint32_t seg0, uint8_t* smem)
 {
-    const uint32_t t = tl.tenant, split = tl.split;
+    const uint32_t split = tl.split;
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t li = lane & 31, lh = lane >> 5;
@@ -218,7 +218,6 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
     const uint32_t nb = tl.n0 / kBrickRows + (wave % split), kq = wave / split;
     const bool active = nb < L.N_pad / kBrickRows;
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
-    const uint32_t seg0 = a.off[t];
     float* red = (float*)smem;                                // both alias the stages, used after the K loop only
     uint8_t* tr = smem + kTrOffset;
 
@@ -335,20 +334,20 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
 template <typename T>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void fc_kernel(GemmArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t smem[kFcLdsBytes];    // also holds tile_base during the lookup
-    uint32_t* base_l = (uint32_t*)smem;
-    static_assert(kFcLdsBytes >= (kMaxTenantsPadded + 1) * 4, "tile_base must fit");
+    __shared__ __attribute__((aligned(16))) uint8_t smem[kFcLdsBytes];
+    __shared__ uint32_t owner_part[4];
+    TileOwner<256> lookup;
+    lookup.fetch(a.tile_base, a.T);
     const uint32_t n_tiles = a.tile_base[a.T];
-    for (uint32_t i = threadIdx.x; i <= a.T; i += 256) base_l[i] = a.tile_base[i];
     uint32_t idx;
     if (!logical_tile(n_tiles, &idx)) return;
-    __syncthreads();
     Tile tl;
-    tl.tenant = __builtin_amdgcn_readfirstlane(find_tenant(base_l, a.T, idx));   // uniform: the tenant's facts come through scalar loads
-    const uint32_t local = __builtin_amdgcn_readfirstlane(idx - base_l[tl.tenant]);
-    __syncthreads();                                          // the lookup is over before anything reuses smem
+    tl.tenant = lookup.owner(a.T, idx, owner_part);           // uniform: the tenant's facts come through scalar loads
+    // everything the tile needs to know about its tenant, fetched in one go
     const LayerDev L = a.layers[tl.tenant * MT_MAX_LAYERS + a.layer];
-    const uint32_t Mt = a.M[tl.tenant];
+    const uint32_t Mt = a.M[tl.tenant], seg0 = a.off[tl.tenant];
+    const uint32_t local = idx - a.tile_base[tl.tenant];
+    asm volatile("" :: "s"(seg0), "s"(local));                // keeps those loads here, next to the others, instead of at their first use
     uint32_t groups, trows;
     fc_shape(L.N_pad, a.fc_split_k, &tl.split, &groups, &trows);
     // where big tiles serve this tenant-layer, only the rows they leave are tiled here
@@ -360,11 +359,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     tl.n0 = (local / mt_) * tl.split * kBrickRows;
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
     if (a.gather) {
-        if (nrb <= 1) fc_tile<T, 1, 8, true>(a, tl, L, Mt, smem);
-        else fc_tile<T, 2, 4, true>(a, tl, L, Mt, smem);
+        if (nrb <= 1) fc_tile<T, 1, 8, true>(a, tl, L, Mt, seg0, smem);
+        else fc_tile<T, 2, 4, true>(a, tl, L, Mt, seg0, smem);
     } else {
-        if (nrb <= 1) fc_tile<T, 1, 8, false>(a, tl, L, Mt, smem);
-        else fc_tile<T, 2, 4, false>(a, tl, L, Mt, smem);
+        if (nrb <= 1) fc_tile<T, 1, 8, false>(a, tl, L, Mt, seg0, smem);
+        else fc_tile<T, 2, 4, false>(a, tl, L, Mt, seg0, smem);
     }
 }
 

@@ -182,12 +182,52 @@ __device__ __forceinline__ bool logical_tile_chunked(uint32_t n_tiles, uint32_t*
     return *logical < n_tiles;
 }
 
-// Tenant that owns logical tile `idx`: last t with base[t] <= idx (base is in LDS, base[T] > idx).
+// Tenant that owns logical tile `idx` by binary search over a copy of the list in LDS: last t with
+// base[t] <= idx (base[T] > idx).  Kept for the big-tile kernel, whose tiles run for ~100 us and
+// whose wait counts the compiler only keeps exact while the kernel issues no other register loads
+// than the one staging loop at its head.
 __device__ __forceinline__ uint32_t find_tenant(const uint32_t* base, uint32_t T, uint32_t idx)
 {
     uint32_t lo = 0, hi = T;
     while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (base[mid] <= idx) lo = mid; else hi = mid; }
     return lo;
 }
+
+// Tenant that owns a logical tile.  A tile list base[0..T] is non-decreasing with base[0] = 0 and
+// base[T] = the number of tiles, so the owner of tile idx is the number of entries base[1..T]
+// that are <= idx.  The workgroup counts them together: every thread fetches its entries
+// (tile_owner_fetch, all loads issued before anything waits, and before the tile index is
+// known), the waves count with one ballot per entry slot and add their counts through `part`
+// (LDS, one word per wave, not reused by the caller: no second barrier is needed).  One memory
+// round trip and one barrier; a binary search over a copy of the list in LDS took a dozen
+// dependent LDS reads and two barriers at the head of every tile.
+template <uint32_t THREADS>
+struct TileOwner {
+    static constexpr uint32_t SLOTS = kMaxTenantsPadded / THREADS;
+    uint32_t v[SLOTS];
+    __device__ __forceinline__ void fetch(const uint32_t* __restrict__ base, uint32_t T)
+    {
+#pragma unroll
+        for (uint32_t s = 0; s < SLOTS; ++s) {
+            const uint32_t j = 1 + s * THREADS + threadIdx.x;
+            v[s] = 0xffffffffu;
+            if (s * THREADS < T && j <= T) v[s] = base[j];
+        }
+    }
+    // wave-uniform result; every thread of the workgroup must call it
+    __device__ __forceinline__ uint32_t owner(uint32_t T, uint32_t idx, uint32_t* part)
+    {
+        uint32_t cnt = 0;
+#pragma unroll
+        for (uint32_t s = 0; s < SLOTS; ++s)
+            if (s * THREADS < T) cnt += (uint32_t)__builtin_popcountll(__ballot(v[s] <= idx));
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = cnt;
+        __syncthreads();
+        uint32_t t = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < THREADS / 64; ++w) t += part[w];
+        return __builtin_amdgcn_readfirstlane(t);
+    }
+};
 
 }  // namespace mt
