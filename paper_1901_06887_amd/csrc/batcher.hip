@@ -205,8 +205,9 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
         for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
             const uint32_t w0 = reg ? q[l / 2][2 * (l % 2)] : 0, w1 = q[l / 2][2 * (l % 2) + 1];
             const bool conv = w0 >> 31;
-            grp[slot][l] = w0 & 0x3fffffffu;
-            rpr[slot][l] = conv ? (w1 | 0x80000000u) : 1u + ((w0 >> 30) & 1);
+            const bool sk = a.fc_split_k && !conv && w0;    // this run's FC tiles: one column block each, 32 rows
+            grp[slot][l] = sk ? w1 / kBrickRows : w0 & 0x3fffffffu;
+            rpr[slot][l] = conv ? (w1 | 0x80000000u) : sk ? 2u : 1u + ((w0 >> 30) & 1);
             npad[slot][l] = conv ? 0 : w1;
         }
     }

@@ -254,8 +254,8 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
     const uint32_t n = nb * kBrickRows + li;
     const float* bias = (const float*)(a.arena + L.b_off);
     const float bv = writer ? bias[n] : 0.0f;
-    if (L.is_last && a.fuse_head && split == 1) {
-        // at most 32 classes: the writer wave holds whole rows of logits.  Transpose them
+    if (L.is_last && a.fuse_head && L.N <= kBrickRows) {
+        // at most 32 classes (one column block, so split == 1): the writer wave holds whole rows of logits.  Transpose them
         // through LDS so that one lane owns one request, then softmax, argmax and the outputs.
         float* trw = (float*)(smem + kTrOffset + wave * kTrBytes);
         constexpr uint32_t FRS = kTrRowBytes / 4;

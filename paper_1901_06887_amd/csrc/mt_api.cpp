@@ -91,7 +91,10 @@ struct mt_ctx {
     bool conv_quad[MT_MAX_LAYERS]{};                 // every conv of a layer index has input channels in multiples of four 16-byte chunks           // widest conv tile (32-channel blocks, at most 4) of a layer index
     uint64_t sum_nt[kListKinds][MT_MAX_LAYERS]{};
     uint32_t max_fc_per64[MT_MAX_LAYERS]{};   // streaming FC tiles per 64 rows of one tenant, maximum over the registered models
-    uint32_t fc_split_k = 0;   // tuning: FC tiles of one column block with K split four ways
+    uint64_t sum_nt_sk[MT_MAX_LAYERS]{};      // the same two figures for the K-split tile shape
+    uint32_t max_fc_per64_sk[MT_MAX_LAYERS]{};
+    uint32_t fc_split_k = 0;   // tuning: every run uses FC tiles of one column block with K split four ways
+    uint32_t no_auto_split_k = 0;   // tuning: small runs keep the ordinary tile shape
     uint32_t no_fused_gather = 0;  // tuning/testing: always stage FC inputs with the gather kernel
     bool fc_first_chunked = true;  // every registered FC-first model's input is a whole number of 16-byte chunks
     bool any_conv_first = false, any_fc_first = false;
@@ -343,7 +346,7 @@ void recompute_bounds(mt_ctx* c)
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
         c->has_gap[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
-        c->max_fc_per64[l] = 0;
+        c->max_fc_per64[l] = 0; c->max_fc_per64_sk[l] = 0; c->sum_nt_sk[l] = 0;
     }
     for (const HostTenant& t : c->tenants) {
         if (!t.registered) continue;
@@ -367,7 +370,12 @@ void recompute_bounds(mt_ctx* c)
             c->max_rpr[k][l] = std::max(c->max_rpr[k][l], L.rows_per_req);
             c->max_nt[k][l] = std::max(c->max_nt[k][l], nt);
             c->sum_nt[k][l] += nt;
-            if (k == 0) c->max_fc_per64[l] = std::max(c->max_fc_per64[l], nt * (kTileRows / fc_tile_rows(L.N_pad, c->fc_split_k)));
+            if (k == 0) {
+                c->max_fc_per64[l] = std::max(c->max_fc_per64[l], nt * (kTileRows / fc_tile_rows(L.N_pad, c->fc_split_k)));
+                const uint32_t nt_sk = fc_groups(L.N_pad, 1);
+                c->sum_nt_sk[l] += nt_sk;
+                c->max_fc_per64_sk[l] = std::max(c->max_fc_per64_sk[l], nt_sk * (kTileRows / fc_tile_rows(L.N_pad, 1)));
+            }
             if (k == 1) {
                 c->max_conv_cb[l] = std::max(c->max_conv_cb[l], std::min<uint32_t>(L.N_pad / kBrickRows, kTileCols / kBrickRows));
                 if (L.cin % (4 * (16 / c->elem_size))) c->conv_quad[l] = false;
@@ -381,14 +389,30 @@ void recompute_bounds(mt_ctx* c)
 }
 
 // Upper bound of the number of tiles of one list over any split of R rows among tenants.
-uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R)
+uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R, bool split_k = false)
 {
     if (c->max_nt[kind][l] == 0) return 0;
     if (kind == 2)      // big FC tiles: only tenants with >= kBigMinRows rows; sum ceil(M_t/256) <= R/256 + R/kBigMinRows
         return R < (uint64_t)kBigMinBatch ? 0 : (uint64_t)c->max_nt[2][l] * (R / kBigTile + R / kBigMinRows);
     // sum over tenants of ceil(M_t / rows_t) * groups_t <= R * max(groups_t / rows_t) + sum(groups_t)
+    if (kind == 0 && split_k) return ((uint64_t)c->max_fc_per64_sk[l] * R + kTileRows - 1) / kTileRows + c->sum_nt_sk[l];
     if (kind == 0) return ((uint64_t)c->max_fc_per64[l] * R + kTileRows - 1) / kTileRows + c->sum_nt[0][l];
     return (uint64_t)c->max_nt[kind][l] * (R * c->max_rpr[kind][l] / kConvTileRows) + c->sum_nt[kind][l];
+}
+
+// Tile shape of the FC layers of a run over R rows.  When no layer index can have more than
+// kSplitKMaxTiles ordinary tiles the launches fill a fraction of the chip and their duration is one
+// wave's walk through K (on the fp32 mix of four small models: 13-16 us per layer, most of it the
+// fp32 MFMAs of a 256- or 512-step K loop in a single wave).  Such runs take tiles of one column
+// block whose four waves split K (and 32 rows): four times the workgroups, a quarter of the walk.
+constexpr uint64_t kSplitKMaxTiles = 128;
+bool run_split_k(const mt_ctx* c, uint64_t R)
+{
+    if (c->fc_split_k) return true;
+    if (c->no_auto_split_k) return false;
+    uint64_t most = 0;
+    for (uint32_t l = 0; l < c->n_layer_slots; ++l) most = std::max(most, tile_bound(c, 0, l, R));
+    return most > 0 && most <= kSplitKMaxTiles;
 }
 
 // ---- validation of a layer chain; fills dev layouts (without arena offsets) -------------
@@ -530,6 +554,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     c->C_pad = round_up(cfg->max_classes, 4);
     c->P_cap = round_up(cfg->max_requests, kBrickRows) + kBrickRows * std::min(cfg->max_tenants, cfg->max_requests);
     if (const char* e = getenv("MT_FC_SPLIT_K")) c->fc_split_k = atoi(e) != 0;
+    if (const char* e = getenv("MT_NO_AUTO_SPLIT_K")) c->no_auto_split_k = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_GATHER")) c->no_fused_gather = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_HEAD")) c->no_fused_head = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_POOL")) c->no_fused_pool = atoi(e) != 0;
@@ -865,6 +890,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     // tenant in the streaming kernel (no second launch per layer, layer 0 reads submitted rows).
     const double run_flops = 2.0 * R * (c->n_registered ? c->sum_macs / c->n_registered : 0.0);
     const bool big_enabled = R >= (uint32_t)kBigMinBatch && run_flops >= kRidgeFlopsPerByte * (double)c->arena_used;
+    const bool split_k = run_split_k(c, R);
     BatchArgs b{};
     b.segs = c->d_segs[slot]; b.n_segs = n_segs; b.R = R; b.T = T; b.n_layer_slots = c->n_layer_slots;
     b.first = c->pending[0]; b.row_src = c->d_row_src; b.elem_size = c->elem_size;
@@ -877,14 +903,14 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         b.n_rank_groups = spread ? groups : 0; b.hist_g = c->d_hist_g;
     }
     b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
-    b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.big_layers = c->d_tile_base + (size_t)kListKinds * MT_MAX_LAYERS * (T + 1); b.fc_split_k = c->fc_split_k;
+    b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.big_layers = c->d_tile_base + (size_t)kListKinds * MT_MAX_LAYERS * (T + 1); b.fc_split_k = split_k;
     b.list_mask = big_enabled ? c->list_mask : c->list_mask & ((1u << (2 * MT_MAX_LAYERS)) - 1);   // no big-tile lists to build
     b.big_enabled = big_enabled; b.big_min_tiles = c->big_min_tiles;
     const OutPtrs outp{out->labels, out->probs, out->logits, out->n_classes, out->row_stride};
     b.out = outp;
     // A last layer of at most 32 classes is one column block: its FC tiles finish their rows
-    // themselves (only with the default tile shapes, where such a layer always has split 1).
-    const bool fuse_head = !c->no_fused_head && !c->fc_split_k && c->min_reg_classes <= kBrickRows;
+    // themselves.
+    const bool fuse_head = !c->no_fused_head && c->min_reg_classes <= kBrickRows;
     const uint32_t head_min_classes = fuse_head ? kBrickRows + 1 : 0;
     if (c->profiling) for (uint32_t i = 0; i < kProfSlots; ++i) c->prof_used[i] = false;
 #define TIMED(slot, call)                                                                   \
@@ -925,11 +951,11 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         void* outb = c->d_act[cur ^ 1];
         cur ^= 1;
         for (int kind = 0; kind < kListKinds; ++kind) {
-            const uint64_t grid = tile_bound(c, kind, l, R);
+            const uint64_t grid = tile_bound(c, kind, l, R, split_k);
             if (grid == 0 || (kind == 2 && (!big_enabled || grid < c->big_min_tiles))) continue;   // no big tiles possible: the batcher made none
             GemmArgs ga{};
             ga.tile_base = c->d_tile_base + ((size_t)kind * MT_MAX_LAYERS + l) * (T + 1);
-            ga.T = T; ga.layer = l; ga.fc_split_k = c->fc_split_k; ga.big_layers = b.big_layers;
+            ga.T = T; ga.layer = l; ga.fc_split_k = split_k; ga.big_layers = b.big_layers;
             ga.gather = (kind == 0 && l == 0 && fuse_gather); ga.perm = c->d_perm; ga.row_src = c->d_row_src;
             ga.fuse_head = fuse_head; ga.out = outp; ga.pool = kind == 1 && c->pool_fused[l];
             ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
@@ -1075,7 +1101,8 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
     const bool big_enabled = R >= (uint64_t)kBigMinBatch && run_flops >= kRidgeFlopsPerByte * (double)c->arena_used;
     const bool big_possible = big_enabled && c->max_nt[2][0] > 0 && tile_bound(c, 2, 0, R) >= c->big_min_tiles;
     const bool fuse_gather = c->any_fc_first && c->fc_first_chunked && !c->no_fused_gather && !big_possible;
-    const bool fuse_head = !c->no_fused_head && !c->fc_split_k && c->min_reg_classes <= (uint32_t)kBrickRows;
+    const bool fuse_head = !c->no_fused_head && c->min_reg_classes <= (uint32_t)kBrickRows;
+    const bool split_k = run_split_k(c, R);
     uint32_t Tp = 64;
     while (Tp < T) Tp <<= 1;
     const uint64_t groups_r = (R + kRankRows - 1) / kRankRows;
@@ -1128,13 +1155,13 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
                 const uint32_t Mb = big ? big_rows(counts[t]) : 0, Ms = counts[t] - Mb;
                 if (big) big_rounds_k += (double)((Mb + kBigTile - 1) / kBigTile) * ((d.N_pad + kBigTile - 1) / kBigTile) * d.K;
                 if (Ms) {
-                    const uint32_t groups = fc_groups(d.N_pad, c->fc_split_k), trows = fc_tile_rows(d.N_pad, c->fc_split_k);
+                    const uint32_t groups = fc_groups(d.N_pad, split_k), trows = fc_tile_rows(d.N_pad, split_k);
                     const double panel_mb = (double)d.N_pad * d.K * es / MB / groups;
                     const double row_tiles = (Ms + trows - 1) / trows;
                     const double act_mb = (double)Ms * d.K * es / MB;
                     w_mb += panel_mb * groups;
                     l2_mb += panel_mb * groups * (row_tiles - 1) + act_mb * groups * ((l == 0 && fuse_gather) ? 3.0 : 1.0);
-                    const uint32_t nblk = d.N_pad / kBrickRows, split = c->fc_split_k ? 1u : (nblk >= 3 ? 4u : nblk);
+                    const uint32_t nblk = d.N_pad / kBrickRows, split = split_k ? 1u : (nblk >= 3 ? 4u : nblk);
                     const double k_steps = d.K * es / 32.0 / (4 / split);       // bricks one wave walks (the waves split K when split < 4)
                     chain = std::max(chain, kUsFcChainFixed + kUsPerKStep * k_steps);
                 }

@@ -262,3 +262,32 @@ def test_two_runs_in_flight_on_two_streams():
         assert np.array_equal(o.labels.cpu().numpy(), ref[2]), i
     assert ctx.last_counts().sum() == 700
     ctx.close()
+
+
+@pytest.mark.parametrize("dtype_mix", ["f32", "bf16"])
+def test_small_runs_agree_with_the_oracle_in_both_tile_shapes(monkeypatch, dtype_mix):
+    """A run whose layer launches would be a few dozen tiles takes FC tiles of one column block with K
+    split over the waves; the ordinary shape stays available through MT_NO_AUTO_SPLIT_K.  Both must give
+    the oracle's answers, for wide hidden layers (several column blocks), a fused head and more than 32
+    classes (separate head)."""
+    if dtype_mix == "f32":
+        w = wl.c1(n_tenants=3, n_requests=70, dims=(96, 256, 160, 10), seed=61)
+    else:
+        a = wl.c2(n_tenants=2, n_requests=90, dims=(104, 256, 192, 10), seed=62)
+        b = wl.c2(n_tenants=2, n_requests=90, dims=(104, 320, 40), seed=63)                  # 40 classes: not fused
+        tenants = {0: a.tenants[0], 1: a.tenants[1], 2: b.tenants[0], 3: b.tenants[1]}
+        ids = np.concatenate([a.tenant_ids[:45], b.tenant_ids[:45] + 2]).astype(np.int32)
+        w = wl.Workload("two-shapes", "bf16", tenants, ids, np.concatenate([a.inputs[:45], b.inputs[:45]]))
+    ref = oracle_rows(w)
+    results = []
+    for env in ({"MT_NO_AUTO_SPLIT_K": "1"}, {}):
+        monkeypatch.delenv("MT_NO_AUTO_SPLIT_K", raising=False)
+        for k, v in env.items():
+            monkeypatch.setenv(k, v)
+        ctx = make_context(w)
+        gpu = gpu_run(ctx, w, poison=True)
+        compare(w, gpu, ref, what="small-run %s %s" % (dtype_mix, "ordinary" if env else "k-split"))
+        results.append(gpu)
+        ctx.close()
+    # the two shapes add the same products in different orders: close, not necessarily equal
+    np.testing.assert_allclose(results[0][0], results[1][0], rtol=5e-2, atol=5e-2)
