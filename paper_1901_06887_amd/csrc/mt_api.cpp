@@ -410,8 +410,11 @@ bool run_split_k(const mt_ctx* c, uint64_t R)
 {
     if (c->fc_split_k) return true;
     if (c->no_auto_split_k) return false;
+    // at most min(R, registered models) tenants have rows, each with one ragged row tile per column group
+    const uint64_t active = std::min<uint64_t>(R, c->n_registered);
     uint64_t most = 0;
-    for (uint32_t l = 0; l < c->n_layer_slots; ++l) most = std::max(most, tile_bound(c, 0, l, R));
+    for (uint32_t l = 0; l < c->n_layer_slots; ++l)
+        most = std::max(most, ((uint64_t)c->max_fc_per64[l] * R + kTileRows - 1) / kTileRows + active * c->max_nt[0][l]);
     return most > 0 && most <= kSplitKMaxTiles;
 }
 

@@ -291,3 +291,16 @@ def test_small_runs_agree_with_the_oracle_in_both_tile_shapes(monkeypatch, dtype
         ctx.close()
     # the two shapes add the same products in different orders: close, not necessarily equal
     np.testing.assert_allclose(results[0][0], results[1][0], rtol=5e-2, atol=5e-2)
+
+
+def test_tiny_run_among_many_registered_models():
+    """The tile shape of a run follows the tenants that can have rows (at most one per request), not the
+    number of registered models: 150 models, 40 requests to three of them."""
+    w = wl.c2(n_tenants=150, n_requests=40, dims=(64, 256, 10), s=0.3, seed=71)
+    w.tenant_ids = np.array([7, 93, 149], dtype=np.int32)[np.arange(40) % 3]
+    ctx = make_context(w)
+    gpu = gpu_run(ctx, w, poison=True)
+    counts = ctx.last_counts()
+    assert counts.sum() == 40 and counts[7] == 14 and counts[93] == 13 and counts[149] == 13
+    compare(w, gpu, oracle_rows(w), what="tiny run, many models")
+    ctx.close()
