@@ -1123,7 +1123,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
     uint32_t launches = 0;
     auto launch = [&](double t) { us += t + (launches ? kUsLaunchGap : 0.0); ++launches; };
     if (spread) { launch(20.0 + 0.15 * R / 1024.0); launches += 2; }       // ranking, scan, placement
-    else launch(10.0 + 0.7 * R / 1024.0);
+    else launch(7.0 + 1.1 * R / 1024.0);                                   // kernel trace: 7.0 us at 64 rows, 9.2 at 2048, 11.3 at 4096
 
     double fc_in_mb = 0.0, img_in_mb = 0.0, img_out_mb = 0.0;
     for (uint32_t t = 0; t < T; ++t) {
