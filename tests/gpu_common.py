@@ -9,8 +9,10 @@ binding) and through the oracle, and compare to the stated bar:
     fp64 oracle, ~1e-3 once one value sitting on a rounding boundary goes the other way,
     because that one-ulp difference is amplified by the re-quantisation of every later
     layer.  An exactly rounded fp32 accumulation shows the same (up to 2.5e-3 per row in
-    simulation), so a tensor of one or two rows cannot be held to 1e-3; it is held to
-    ROW_TOL instead;
+    simulation on the five mixes; 7.2e-3 for one request of a 33-unit-wide linear net with
+    three small logits, reproduced on the CPU by taking the other bfloat16 neighbour of the
+    one value that lies 3e-8 from a rounding boundary: tests/test_tolerance_model.py), so a
+    tensor of one or two rows cannot be held to 1e-3; it is held to ROW_TOL instead;
   * labels bit-exact wherever the oracle's top-2 logit margin exceeds 1e-2; elsewhere the
     label must be one of the oracle's two best classes.
 """
@@ -22,7 +24,7 @@ import paper_1901_06887_amd as mt
 from paper_1901_06887_amd import torch_io
 
 REL_FRO_TOL = 1e-3
-ROW_TOL = 5e-3
+ROW_TOL = 1e-2
 MIN_ROWS_PER_TENSOR = 16
 MARGIN = 1e-2
 

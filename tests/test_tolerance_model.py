@@ -1,0 +1,58 @@
+"""Why a single row is held to a looser bar than a tensor (see gpu_common.py): with bf16 hidden
+activations one hidden value that lies on a rounding boundary decides the row.  The case below came up
+in a sweep of random fleets: a five-layer linear MLP whose first layer has 33 outputs, one of which is
+3e-8 (relative) away from the midpoint of two bfloat16 values for this request.  Accumulated in fp32,
+in any order, that value can land on either side; taking the other side moves the three logits by 7e-3
+of their norm (the per-row bar is 1e-2 for that reason), with every other operation exact.  The test pins both facts on the
+CPU, from the seeded generators alone: the distance to the boundary and the size of the effect."""
+import numpy as np
+import torch
+
+import workloads as wl
+from test_gpu_random_fleets import random_model
+
+
+def bf16(v):
+    return torch.from_numpy(np.asarray(v, dtype=np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def test_one_rounding_flip_moves_a_narrow_net_by_more_than_the_row_tolerance():
+    # the fleet of seed 214, drawn exactly as tests/test_gpu_random_fleets.py draws it; accepted row 146
+    seed, tenant = 214, 1
+    rng = np.random.default_rng(seed)
+    n_tenants = int(rng.integers(3, 12))
+    kinds = [str(rng.choice(["mlp", "cnn"])) for _ in range(n_tenants)]
+    tenants = {t: random_model(rng, kinds[t], 192, "bf16", (seed, t)) for t in range(n_tenants)}
+    R = int(rng.integers(40, 700))
+    share = rng.random(n_tenants) ** 3 + 1e-3
+    ids = rng.choice(n_tenants, size=R, p=share / share.sum())
+    x = bf16(rng.standard_normal((R, 192)).astype(np.float32))
+    rejected = rng.choice(R, size=3, replace=False)
+    row = np.setdiff1d(np.arange(R), rejected)[146]
+    m = tenants[tenant]
+    assert ids[row] == tenant and [l.out_features for l in m.layers] == [33, 72, 136, 200, 3]
+    assert all(l.act == wl.ACT_NONE for l in m.layers)
+
+    def logits(flip_unit=None):
+        h = x[row]
+        for li, (W, b) in enumerate(zip(m.weights, m.biases)):
+            z = W.astype(np.float64) @ h + b.astype(np.float64)
+            if li == len(m.weights) - 1:
+                return z
+            h = bf16(z)
+            if li == 0 and flip_unit is not None:       # the other neighbour of z on the bfloat16 grid
+                j = flip_unit
+                ulp = 2.0 ** (np.floor(np.log2(abs(z[j]))) - 7)
+                lo = np.floor(abs(z[j]) / ulp) * ulp
+                h[j] = np.sign(z[j]) * (lo + ulp if abs(abs(h[j]) - lo) < 1e-12 else lo)
+
+    # distance of every first-layer value to the midpoint of its two bfloat16 neighbours, in ulps
+    z = m.weights[0].astype(np.float64) @ x[row] + m.biases[0].astype(np.float64)
+    ulp = 2.0 ** (np.floor(np.log2(np.abs(z))) - 7)
+    dist = np.abs(np.abs(z) / ulp - np.floor(np.abs(z) / ulp) - 0.5)
+    j = int(np.argmin(dist))
+    assert j == 32 and dist[j] < 1e-5                   # 1e-5 ulp is 4e-8 relative: below fp32 accumulation noise
+    assert np.sort(dist)[1] > 1e-3                      # and it is the only such value in the layer
+    exact, other = logits(), logits(flip_unit=j)
+    rel = np.linalg.norm(other - exact) / np.linalg.norm(exact)
+    assert 5e-3 < rel < 1e-2, rel
