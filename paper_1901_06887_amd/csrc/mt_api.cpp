@@ -963,7 +963,9 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             ga.fuse_head = fuse_head; ga.out = outp; ga.pool = kind == 1 && c->pool_fused[l];
             ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad; ga.zeros = c->d_zeros;
-            const uint32_t g32 = (uint32_t)std::min<uint64_t>(grid, 0x7ffffff0u);
+            if (grid > 0x7ffffff0u)          // cannot happen within the limits mt_create accepts; never launch fewer workgroups than tiles
+                return fail(c, MT_EUNSUPPORTED, "layer %u: %llu tiles exceed one launch", l, (unsigned long long)grid);
+            const uint32_t g32 = (uint32_t)grid;
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
             else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], c->conv_quad[l], g32, s));
             else TIMED(kProfBig + l, launch_fc_big(ga, c->cfg.dtype, g32, s));
