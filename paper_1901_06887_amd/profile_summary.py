@@ -133,6 +133,7 @@ def main(argv=None):
     c = sub.add_parser("counters")
     c.add_argument("csv")
     c.add_argument("--kernel", required=True)
+    c.add_argument("--each", action="store_true", help="one line per kernel whose name contains --kernel")
     a = ap.parse_args(argv)
     if a.cmd == "stats":
         print(stats(a.csv, a.top))
@@ -141,7 +142,12 @@ def main(argv=None):
     else:
         names = sorted({r["Counter_Name"] for r in csv.DictReader(open(a.csv))})
         for n in names:
-            k, (v, cnt) = pick(counter_means(a.csv, n), a.kernel)
+            means = counter_means(a.csv, n)
+            if a.each:
+                for k in sorted(k for k in means if a.kernel in k):
+                    print("%s %s: %.4g (mean of %d dispatches)" % (k, n, means[k][0], means[k][1]))
+                continue
+            k, (v, cnt) = pick(means, a.kernel)
             print("%s %s: %.4g (mean of %d dispatches)" % (k, n, v, cnt))
 
 
