@@ -428,6 +428,178 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
 }
 
+// ---- convolution tiles whose input fits LDS ----------------------------------------------------
+// Same tile (128 output pixels x <= 128 channels) and tile list again, for layers whose tiles are
+// whole output rows of one image or whole small images: the input rows a tile needs are copied
+// to LDS once, with contiguous 16-byte loads, into a frame with a zero border (one pixel left
+// and right, one row above and below where the image ends), and the nine taps of every pixel are
+// read from there.  Against gathering every tap from L2 this moves each input byte once instead
+// of 2.25 (stride 2) to 9 (stride 1) times through the texture path, and the walk through K
+// becomes scalar arithmetic: a k step lies inside one tap (cin is a multiple of a k step), so its
+// LDS offset (kernel row, kernel column, channel chunk) is the same for every lane; lanes differ
+// by the fixed address of their pixel's top-left tap.  Pixels are kept 16 bytes apart from a
+// multiple of 32 bytes, which spreads the lanes of a stride-2 read over half the banks (2-way
+// conflict; stride 1: none).  Filters stream through a register ring per wave as in conv_kernel.
+// Sub-images: a tile holds `ni` of them, each `n_oh` output rows of one image.
+template <typename T, int NCB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_img_kernel(GemmArgs a)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC, NB = 9;
+    constexpr uint32_t P = NCB == 2 ? 12 : 8;                       // filter bricks in flight per wave
+    constexpr uint32_t WR = 4 / NCB, RBW = 4 / WR;                  // wave rows; pixel blocks per wave
+    typedef const __attribute__((address_space(1))) u32x4* gptr_t;
+    extern __shared__ __attribute__((aligned(16))) uint8_t img[];
+    __shared__ uint32_t owner_part[4];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lh = lane >> 5;
+    TileOwner<256> lookup;
+    lookup.fetch(a.tile_base, a.T);
+    const uint32_t n_tiles = a.tile_base[a.T];
+    // the frame starts as zeros (its border, rows past the image, sub-images past the tenant's last request);
+    // written while the tile list is on its way, published by the barrier of the lookup
+    for (uint32_t q = tid * 16; q < a.img_lds; q += 256 * 16) *(u32x4*)(img + q) = u32x4{0, 0, 0, 0};
+    uint32_t idx;
+    if (!logical_tile(n_tiles, &idx)) return;
+    const uint32_t t = lookup.owner(a.T, idx, owner_part);   // uniform: the tenant's facts come through scalar loads
+    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    const uint32_t seg0 = a.off[t], Mt = a.M[t];
+    const uint32_t local = idx - a.tile_base[t];
+    const uint32_t rpr = L.rows_per_req;
+    const uint32_t rows_total = Mt * rpr, mt_ = ceil_div(rows_total, kConvTileRows);
+    const uint32_t m0 = (local % mt_) * kConvTileRows;
+    const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
+    const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
+    const uint32_t nKB = L.K / KB, nKBv = L.k_valid / KB;          // cin is a multiple of KB: whole k steps only
+    const uint32_t wc = wave % NCB, wr = wave / NCB;
+    const bool active = wc < ncb;
+
+    // geometry of the frame (all wave-uniform)
+    const uint32_t st = L.stride, ow_n = L.out_w, iw_n = L.in_w, ih_n = L.in_h, cin = L.cin;
+    const uint32_t PB = cin * (uint32_t)sizeof(T) + 16, RSB = (iw_n + 2) * PB;   // bytes per pixel slot, per frame row
+    const uint32_t ni = rpr >= kConvTileRows ? 1 : kConvTileRows / rpr;           // sub-images of the tile
+    const uint32_t ppi = kConvTileRows / ni;                                      // output pixels of one sub-image
+    const uint32_t n_oh = ppi / ow_n, n_ih = (n_oh - 1) * st + 3;                 // its output rows, its frame rows
+    const uint32_t SUB = n_ih * RSB;
+
+    // the first filter bricks travel while the frame is filled (idle waves stream block 0 and drop it)
+    gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
+    u32x4 wq[P];
+#pragma unroll
+    for (uint32_t j = 0; j < P; ++j) wq[j] = wp[(size_t)min(j, nKBv - 1) * 64];
+
+    const uint32_t cpp = cin * (uint32_t)sizeof(T) / 16, cpr = iw_n * cpp;       // 16-byte chunks per pixel, per image row
+    for (uint32_t i = 0; i < ni; ++i) {
+        const uint32_t gm = m0 + i * ppi;
+        if (gm >= rows_total) break;
+        uint32_t req, pix, oh0, ow0;
+        divmod_uniform(gm, rpr, &req, &pix);
+        divmod_uniform(pix, ow_n, &oh0, &ow0);
+        const int32_t ih_first = (int32_t)(oh0 * st) - 1;                        // image row of frame row 0
+        const int32_t r_lo = ih_first < 0 ? -ih_first : 0;
+        const int32_t r_hi = min((int32_t)n_ih, (int32_t)ih_n - ih_first);       // frame rows [r_lo, r_hi) lie inside the image
+        gptr_t src = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S) + (size_t)(ih_first + r_lo) * cpr;
+        const uint32_t n_chunks = (uint32_t)(r_hi - r_lo) * cpr;                 // contiguous in memory
+        uint8_t* dst = img + i * SUB + (uint32_t)r_lo * RSB + PB;                // first pixel slot after the left border
+        for (uint32_t q0 = 0; q0 < n_chunks; q0 += NB * 256) {                   // NB loads in flight per lane
+            u32x4 v[NB];
+#pragma unroll
+            for (uint32_t j = 0; j < NB; ++j) {
+                const uint32_t q = q0 + j * 256 + tid;
+                v[j] = src[q < n_chunks ? q : 0];
+            }
+#pragma unroll
+            for (uint32_t j = 0; j < NB; ++j) {
+                const uint32_t q = q0 + j * 256 + tid;
+                uint32_t r, x, col, c16;
+                divmod_uniform(q, cpr, &r, &x);
+                divmod_uniform(x, cpp, &col, &c16);
+                if (q < n_chunks) *(u32x4*)(dst + r * RSB + col * PB + c16 * 16) = v[j];
+            }
+        }
+    }
+    __syncthreads();
+
+    f32x16 acc[RBW];
+#pragma unroll
+    for (uint32_t r = 0; r < RBW; ++r)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[r][v] = 0.0f;
+    if (active) {
+        // this lane's pixel in each of the wave's pixel blocks: frame address of its top-left tap
+        uint32_t base[RBW];
+#pragma unroll
+        for (uint32_t r = 0; r < RBW; ++r) {
+            const uint32_t p = (wr * RBW + r) * kBrickRows + li;
+            uint32_t i, pl, ohl, ow;
+            divmod_uniform(p, ppi, &i, &pl);
+            divmod_uniform(pl, ow_n, &ohl, &ow);
+            base[r] = i * SUB + ohl * st * RSB + ow * st * PB + lh * 16;
+        }
+        // position in K (all scalar): channel inside the tap, kernel column, byte offset of the tap's row, of the k step
+        uint32_t ch = 0, kw = 0, row_off = 0, off = 0;
+        auto advance = [&]() {
+            ch += KB; off += KB * (uint32_t)sizeof(T);
+            if (ch == cin) {                                       // next tap
+                ch = 0; ++kw;
+                if (kw == 3) { kw = 0; row_off += RSB; }
+                off = row_off + kw * PB;
+            }
+        };
+        // the pixel operands of a k step are read one step ahead of its MFMAs (past the last tap: the frame's last row, unused)
+        u32x4 av[RBW];
+#pragma unroll
+        for (uint32_t r = 0; r < RBW; ++r) av[r] = *(const u32x4*)(img + base[r]);
+        auto step = [&](const u32x4& wv) {
+            advance();
+            const uint32_t off_n = min(off, 2 * RSB + 2 * PB + (cin - KB) * (uint32_t)sizeof(T));
+            u32x4 an[RBW];
+#pragma unroll
+            for (uint32_t r = 0; r < RBW; ++r) an[r] = *(const u32x4*)(img + base[r] + off_n);
+#pragma unroll
+            for (uint32_t r = 0; r < RBW; ++r) Mma<T>::run(acc[r], wv, av[r]);   // rows = channels, columns = pixels
+#pragma unroll
+            for (uint32_t r = 0; r < RBW; ++r) av[r] = an[r];
+        };
+        const uint32_t full = nKBv / P;
+        for (uint32_t g = 0; g < full; ++g) {
+#pragma unroll
+            for (uint32_t j = 0; j < P; ++j) {
+                step(wq[j]);
+                wq[j] = wp[(size_t)min(g * P + j + P, nKBv - 1) * 64];
+            }
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < P; ++j)
+            if (full * P + j < nKBv) step(wq[j]);
+    }
+    const float* bias = (const float*)(a.arena + L.b_off);
+    const uint32_t nbase = (nb0 + (active ? wc : 0)) * kBrickRows;
+    f32x4 bias_q[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) bias_q[g] = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);   // bias is padded to N_pad
+    __syncthreads();                                               // every wave is done with the frame: it now serves as store scratch
+    if (!active) return;
+    uint8_t* scratch = img + wave * unit_scratch_bytes<T>();
+#pragma unroll
+    for (uint32_t r = 0; r < RBW; ++r) {
+        const uint32_t m = m0 + (wr * RBW + r) * kBrickRows + li;
+        T* out = nullptr;
+        if (m < rows_total) {
+            uint32_t req, pix;
+            divmod_uniform(m, rpr, &req, &pix);
+            out = (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N + nbase;
+        }
+        f32x4 y[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) y[g][i] = acc[r][4 * g + i] + bias_q[g][i];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        activate_block<4>(y, L.act);
+        store_unit_nhwc<T>(y, out, min((uint32_t)kBrickRows, L.N - nbase), scratch);
+    }
+}
+
 // ---- launcher ------------------------------------------------------------
 template <typename T>
 static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, uint32_t grid, hipStream_t s)
@@ -439,10 +611,26 @@ static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, uint32_
     else hipLaunchKernelGGL((conv_lds_kernel<T, 4, false>), dim3(grid), dim3(256), 0, s, a);
 }
 
-hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t grid, hipStream_t s)
+template <typename T>
+static void launch_conv_img_t(const GemmArgs& a, uint32_t max_cb, uint32_t lds_bytes, uint32_t grid, hipStream_t s)
+{
+    lds_bytes = std::max<uint32_t>(lds_bytes, 4 * unit_scratch_bytes<T>());       // the frame also serves as store scratch
+    GemmArgs b = a;
+    b.img_lds = lds_bytes;
+    if (max_cb <= 2) hipLaunchKernelGGL((conv_img_kernel<T, 2>), dim3(grid), dim3(256), lds_bytes, s, b);
+    else hipLaunchKernelGGL((conv_img_kernel<T, 4>), dim3(grid), dim3(256), lds_bytes, s, b);
+}
+
+// img_lds_bytes > 0: every convolution of the layer index qualifies for the LDS-resident-input kernel, whose largest frame is that size
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, uint32_t grid, hipStream_t s)
 {
     if (grid == 0) return hipSuccess;
     grid = (grid + 7) / 8 * 8;
+    if (img_lds_bytes) {
+        if (dtype == MT_BF16) launch_conv_img_t<__bf16>(a, max_cb, img_lds_bytes, grid, s);
+        else launch_conv_img_t<float>(a, max_cb, img_lds_bytes, grid, s);
+        return hipGetLastError();
+    }
     if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, quad, grid, s);
     else launch_conv_t<float>(a, max_cb, quad, grid, s);
     return hipGetLastError();

@@ -88,6 +88,8 @@ struct mt_ctx {
     bool pool_fused[MT_MAX_LAYERS]{};
     double sum_macs = 0.0;                           // multiply-accumulates of one request, summed over the registered tenants
     uint32_t max_conv_cb[MT_MAX_LAYERS]{};
+    uint32_t conv_img_lds[MT_MAX_LAYERS]{};          // every conv of a layer index can keep its tiles' input in LDS: the largest frame in bytes, else 0
+    uint32_t no_conv_img = 0;                        // tuning: never use that kernel
     bool conv_quad[MT_MAX_LAYERS]{};                 // every conv of a layer index has input channels in multiples of four 16-byte chunks           // widest conv tile (32-channel blocks, at most 4) of a layer index
     uint64_t sum_nt[kListKinds][MT_MAX_LAYERS]{};
     uint32_t max_fc_per64[MT_MAX_LAYERS]{};   // streaming FC tiles per 64 rows of one tenant, maximum over the registered models
@@ -344,7 +346,7 @@ void recompute_bounds(mt_ctx* c)
     c->fc_first_chunked = true; c->any_conv_first = c->any_fc_first = false;
     c->list_mask = 0; c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        c->has_gap[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false;
+        c->has_gap[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
         c->max_fc_per64[l] = 0; c->max_fc_per64_sk[l] = 0; c->sum_nt_sk[l] = 0;
     }
@@ -379,6 +381,18 @@ void recompute_bounds(mt_ctx* c)
             if (k == 1) {
                 c->max_conv_cb[l] = std::max(c->max_conv_cb[l], std::min<uint32_t>(L.N_pad / kBrickRows, kTileCols / kBrickRows));
                 if (L.cin % (4 * (16 / c->elem_size))) c->conv_quad[l] = false;
+                // frame of one tile of the LDS-resident-input kernel (see conv_img_kernel): whole output rows of one
+                // image, or whole images, with a one-pixel border, pixels 16 bytes apart from cin elements
+                const uint32_t rpr = L.rows_per_req, kb = 32 / c->elem_size;
+                const bool whole = L.out_w && kConvTileRows % L.out_w == 0 && (rpr % kConvTileRows == 0 || kConvTileRows % rpr == 0);
+                const uint32_t ni = rpr >= (uint32_t)kConvTileRows ? 1 : kConvTileRows / std::max(rpr, 1u);
+                uint64_t frame = 0;
+                if (whole && ni <= 8 && L.cin % kb == 0) {
+                    const uint32_t n_oh = kConvTileRows / ni / L.out_w, n_ih = (n_oh - 1) * L.stride + 3;
+                    frame = (uint64_t)ni * n_ih * (L.in_w + 2) * (L.cin * c->elem_size + 16);
+                }
+                if (frame == 0 || frame > 49152 || c->conv_img_lds[l] == 0) c->conv_img_lds[l] = 0;
+                else c->conv_img_lds[l] = std::max<uint32_t>(c->conv_img_lds[l], (uint32_t)frame);
             }
             if (k == 0 && L.N_pad >= (uint32_t)kBigMinCols) {      // may be served with big tiles when it gets enough rows
                 c->list_mask |= 1u << (2 * MT_MAX_LAYERS + l);
@@ -561,6 +575,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     if (const char* e = getenv("MT_NO_FUSED_GATHER")) c->no_fused_gather = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_HEAD")) c->no_fused_head = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_POOL")) c->no_fused_pool = atoi(e) != 0;
+    if (const char* e = getenv("MT_NO_CONV_IMG")) c->no_conv_img = atoi(e) != 0;
     if (const char* e = getenv("MT_BIG_MIN_TILES")) c->big_min_tiles = (uint32_t)std::max(1, atoi(e));
     c->cache = cfg->cache != 0;
     c->tenants.resize(cfg->max_tenants);
@@ -967,7 +982,8 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
                 return fail(c, MT_EUNSUPPORTED, "layer %u: %llu tiles exceed one launch", l, (unsigned long long)grid);
             const uint32_t g32 = (uint32_t)grid;
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
-            else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], c->conv_quad[l], g32, s));
+            else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], c->conv_quad[l],
+                                                                    (c->conv_img_lds[l] > 1 && c->max_conv_cb[l] >= 2 && !c->pool_fused[l] && !c->no_conv_img) ? c->conv_img_lds[l] : 0, g32, s));
             else TIMED(kProfBig + l, launch_fc_big(ga, c->cfg.dtype, g32, s));
         }
         if (c->has_gap[l]) {

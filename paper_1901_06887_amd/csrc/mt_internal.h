@@ -153,6 +153,7 @@ struct GemmArgs {
     const uint32_t* tile_base; uint32_t T; uint32_t layer; uint32_t fc_split_k;
     const uint32_t* big_layers;   // the batcher's decision per layer index (see BatchArgs)
     uint32_t pool;                // conv launch: the layers with pool_fill write the pooled activation instead of their own
+    uint32_t img_lds;             // conv launch with LDS-resident input: bytes of dynamic LDS (the largest frame)
     // FC layer 0 can read the submitted rows itself (16-byte aligned rows whose length is a
     // whole number of 16-byte chunks), which saves the staging pass:
     uint32_t gather; const int32_t* perm; const void* const* row_src;
@@ -187,7 +188,7 @@ hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipSt
 // max_cb: the widest tile of this layer index over the registered tenants, in 32-channel blocks (1..4)
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s);
 // quad: every tenant's input channels at this layer index are a multiple of four 16-byte chunks
-hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t grid, hipStream_t s);
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, uint32_t grid, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, hipStream_t s);
 hipError_t launch_head(const HeadArgs& a, hipStream_t s);
 

@@ -132,6 +132,34 @@ def test_cnn_tenants_of_different_widths_share_a_launch():
     run_and_compare(wl.Workload("cnn-mixed", "bf16", tenants, ids, a.inputs), "cnn-mixed-widths")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_convolutions_with_the_input_resident_in_lds(monkeypatch, dtype):
+    """Layers whose 128-pixel tiles are whole output rows of one image (16x16 outputs: 8 rows of it) or
+    whole small images (8x8 outputs: two of them) keep the tile's input rows in LDS instead of gathering
+    every tap: stride 1 and 2, two and four channel blocks, a ragged last tile (5 images of 64 pixels),
+    tenants with frames of different size in one launch.  The answers must match the oracle, and the
+    gathering kernels' answers when that kernel is switched off."""
+    cases = [wl.c4(n_tenants=2, n_requests=5, hw=8, chans=(3, 16, 64, 128), strides=(1, 1, 1), classes=6, seed=31),
+             wl.c4(n_tenants=2, n_requests=3, hw=32, chans=(3, 32, 64, 40), strides=(1, 2, 1), classes=5, seed=32),
+             wl.c4(n_tenants=1, n_requests=4, hw=16, chans=(3, 32, 128, 72), strides=(1, 1, 2), classes=4, seed=33)]
+    a = wl.c4(n_tenants=1, n_requests=6, hw=8, chans=(3, 16, 64, 64), strides=(1, 1, 1), classes=4, seed=34)
+    b = wl.c4(n_tenants=1, n_requests=6, hw=8, chans=(3, 32, 128, 64), strides=(1, 1, 1), classes=4, seed=35)
+    cases.append(wl.Workload("two frames", "bf16", {0: a.tenants[0], 1: b.tenants[0]},
+                             np.array([0, 1, 1, 0, 1, 0], dtype=np.int32), a.inputs))
+    for w in cases:
+        w.dtype = dtype
+        ref = oracle_rows(w)
+        got = []
+        for off in ("0", "1"):
+            monkeypatch.setenv("MT_NO_CONV_IMG", off)
+            ctx = make_context(w)
+            gpu = gpu_run(ctx, w, poison=True)
+            compare(w, gpu, ref, what="%s %s conv_img %s" % (w.name, dtype, "off" if off == "1" else "on"))
+            got.append(gpu)
+            ctx.close()
+        np.testing.assert_allclose(got[0][0], got[1][0], rtol=1e-2, atol=1e-2)     # same products, possibly another order
+
+
 def test_more_than_1024_classes():
     # the head kernel holds rows of up to 1024 logits in registers; wider rows take its loop
     run_and_compare(wl.c2(n_tenants=3, n_requests=70, dims=(64, 96, 1100)), "wide-head")
