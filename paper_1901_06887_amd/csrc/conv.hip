@@ -441,11 +441,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 // multiple of 32 bytes, which spreads the lanes of a stride-2 read over half the banks (2-way
 // conflict; stride 1: none).  Filters stream through a register ring per wave as in conv_kernel.
 // Sub-images: a tile holds `ni` of them, each `n_oh` output rows of one image.
-template <typename T, int NCB>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_img_kernel(GemmArgs a)
+template <typename T, int NCB, bool TWO>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 8 : 3, NCB == 1 ? 8 : 3))) void conv_img_kernel(GemmArgs a)
 {
-    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC, NB = 9;
-    constexpr uint32_t P = NCB == 2 ? 12 : 8;                       // filter bricks in flight per wave
+    constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    constexpr uint32_t NB = NCB == 1 ? 2 : 9;                       // frame loads in flight per lane
+    constexpr uint32_t P = NCB == 1 ? 4 : NCB == 2 ? 12 : 8;        // filter bricks in flight per wave (one channel block: small tiles, many resident waves)
+    static_assert(NCB == 1 || NCB == 2 || NCB == 4, "channel blocks side by side");
     constexpr uint32_t WR = 4 / NCB, RBW = 4 / WR;                  // wave rows; pixel blocks per wave
     typedef const __attribute__((address_space(1))) u32x4* gptr_t;
     extern __shared__ __attribute__((aligned(16))) uint8_t img[];
@@ -468,13 +470,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const uint32_t m0 = (local % mt_) * kConvTileRows;
     const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
     const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
-    const uint32_t nKB = L.K / KB, nKBv = L.k_valid / KB;          // cin is a multiple of KB: whole k steps only
+    const uint32_t nKB = L.K / KB, nKBv = ceil_div(L.k_valid, KB);  // cin is a multiple of KB (whole k steps), or half of one
     const uint32_t wc = wave % NCB, wr = wave / NCB;
     const bool active = wc < ncb;
 
     // geometry of the frame (all wave-uniform)
     const uint32_t st = L.stride, ow_n = L.out_w, iw_n = L.in_w, ih_n = L.in_h, cin = L.cin;
-    const uint32_t PB = cin * (uint32_t)sizeof(T) + 16, RSB = (iw_n + 2) * PB;   // bytes per pixel slot, per frame row
+    // TWO: cin == EPC for every tenant (a padded three-channel input in bf16): a pixel is one 16-byte chunk, a k
+    // step spans two taps, and the two halves of the wave take one tap each
+    constexpr bool two = TWO;
+    const uint32_t PB = cin * (uint32_t)sizeof(T) + (two ? 0 : 16), RSB = (iw_n + 2) * PB;   // bytes per pixel slot, per frame row
     const uint32_t ni = rpr >= kConvTileRows ? 1 : kConvTileRows / rpr;           // sub-images of the tile
     const uint32_t ppi = kConvTileRows / ni;                                      // output pixels of one sub-image
     const uint32_t n_oh = ppi / ow_n, n_ih = (n_oh - 1) * st + 3;                 // its output rows, its frame rows
@@ -532,7 +537,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             uint32_t i, pl, ohl, ow;
             divmod_uniform(p, ppi, &i, &pl);
             divmod_uniform(pl, ow_n, &ohl, &ow);
-            base[r] = i * SUB + ohl * st * RSB + ow * st * PB + lh * 16;
+            base[r] = i * SUB + ohl * st * RSB + ow * st * PB + (two ? 0 : lh * 16);
         }
         // position in K (all scalar): channel inside the tap, kernel column, byte offset of the tap's row, of the k step
         uint32_t ch = 0, kw = 0, row_off = 0, off = 0;
@@ -545,12 +550,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
             }
         };
         // the pixel operands of a k step are read one step ahead of its MFMAs (past the last tap: the frame's last row, unused)
+        uint32_t kbi = 0;                                          // two taps per k step: the k step whose operands are in av
+        auto two_taps = [&](uint32_t k) -> uint32_t {              // this lane's tap of k step k (taps past the ninth meet zero filters)
+            const uint32_t tp = min(2 * k + lh, 8u);
+            return (tp / 3) * RSB + (tp % 3) * PB;
+        };
         u32x4 av[RBW];
 #pragma unroll
-        for (uint32_t r = 0; r < RBW; ++r) av[r] = *(const u32x4*)(img + base[r]);
+        for (uint32_t r = 0; r < RBW; ++r) av[r] = *(const u32x4*)(img + base[r] + (two ? two_taps(0) : 0));
         auto step = [&](const u32x4& wv) {
-            advance();
-            const uint32_t off_n = min(off, 2 * RSB + 2 * PB + (cin - KB) * (uint32_t)sizeof(T));
+            uint32_t off_n;
+            if (two) { kbi = min(kbi + 1, nKBv - 1); off_n = two_taps(kbi); }
+            else { advance(); off_n = min(off, 2 * RSB + 2 * PB + (cin - KB) * (uint32_t)sizeof(T)); }
             u32x4 an[RBW];
 #pragma unroll
             for (uint32_t r = 0; r < RBW; ++r) an[r] = *(const u32x4*)(img + base[r] + off_n);
@@ -612,23 +623,31 @@ static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, uint32_
 }
 
 template <typename T>
-static void launch_conv_img_t(const GemmArgs& a, uint32_t max_cb, uint32_t lds_bytes, uint32_t grid, hipStream_t s)
+static void launch_conv_img_t(const GemmArgs& a, uint32_t max_cb, bool two, uint32_t lds_bytes, uint32_t grid, hipStream_t s)
 {
     lds_bytes = std::max<uint32_t>(lds_bytes, 4 * unit_scratch_bytes<T>());       // the frame also serves as store scratch
     GemmArgs b = a;
     b.img_lds = lds_bytes;
-    if (max_cb <= 2) hipLaunchKernelGGL((conv_img_kernel<T, 2>), dim3(grid), dim3(256), lds_bytes, s, b);
-    else hipLaunchKernelGGL((conv_img_kernel<T, 4>), dim3(grid), dim3(256), lds_bytes, s, b);
+    if (two && sizeof(T) == 2) {
+        if (max_cb <= 1) hipLaunchKernelGGL((conv_img_kernel<T, 1, sizeof(T) == 2>), dim3(grid), dim3(256), lds_bytes, s, b);
+        else if (max_cb <= 2) hipLaunchKernelGGL((conv_img_kernel<T, 2, sizeof(T) == 2>), dim3(grid), dim3(256), lds_bytes, s, b);
+        else hipLaunchKernelGGL((conv_img_kernel<T, 4, sizeof(T) == 2>), dim3(grid), dim3(256), lds_bytes, s, b);
+    } else {
+        if (max_cb <= 1) hipLaunchKernelGGL((conv_img_kernel<T, 1, false>), dim3(grid), dim3(256), lds_bytes, s, b);
+        else if (max_cb <= 2) hipLaunchKernelGGL((conv_img_kernel<T, 2, false>), dim3(grid), dim3(256), lds_bytes, s, b);
+        else hipLaunchKernelGGL((conv_img_kernel<T, 4, false>), dim3(grid), dim3(256), lds_bytes, s, b);
+    }
 }
 
-// img_lds_bytes > 0: every convolution of the layer index qualifies for the LDS-resident-input kernel, whose largest frame is that size
-hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, uint32_t grid, hipStream_t s)
+// img_lds_bytes > 0: every convolution of the layer index qualifies for the LDS-resident-input kernel, whose largest frame is that
+// size; img_two: their pixels are one 16-byte chunk (else none is)
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, uint32_t grid, hipStream_t s)
 {
     if (grid == 0) return hipSuccess;
     grid = (grid + 7) / 8 * 8;
     if (img_lds_bytes) {
-        if (dtype == MT_BF16) launch_conv_img_t<__bf16>(a, max_cb, img_lds_bytes, grid, s);
-        else launch_conv_img_t<float>(a, max_cb, img_lds_bytes, grid, s);
+        if (dtype == MT_BF16) launch_conv_img_t<__bf16>(a, max_cb, img_two, img_lds_bytes, grid, s);
+        else launch_conv_img_t<float>(a, max_cb, img_two, img_lds_bytes, grid, s);
         return hipGetLastError();
     }
     if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, quad, grid, s);

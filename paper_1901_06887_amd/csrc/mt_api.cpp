@@ -89,6 +89,7 @@ struct mt_ctx {
     double sum_macs = 0.0;                           // multiply-accumulates of one request, summed over the registered tenants
     uint32_t max_conv_cb[MT_MAX_LAYERS]{};
     uint32_t conv_img_lds[MT_MAX_LAYERS]{};          // every conv of a layer index can keep its tiles' input in LDS: the largest frame in bytes, else 0
+    int conv_img_two[MT_MAX_LAYERS]{};               // ... and their pixels are one 16-byte chunk: 1, none is: 0 (-1: no convolution seen yet)
     uint32_t no_conv_img = 0;                        // tuning: never use that kernel
     bool conv_quad[MT_MAX_LAYERS]{};                 // every conv of a layer index has input channels in multiples of four 16-byte chunks           // widest conv tile (32-channel blocks, at most 4) of a layer index
     uint64_t sum_nt[kListKinds][MT_MAX_LAYERS]{};
@@ -346,7 +347,7 @@ void recompute_bounds(mt_ctx* c)
     c->fc_first_chunked = true; c->any_conv_first = c->any_fc_first = false;
     c->list_mask = 0; c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        c->has_gap[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1;
+        c->has_gap[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
         c->max_fc_per64[l] = 0; c->max_fc_per64_sk[l] = 0; c->sum_nt_sk[l] = 0;
     }
@@ -387,11 +388,13 @@ void recompute_bounds(mt_ctx* c)
                 const bool whole = L.out_w && kConvTileRows % L.out_w == 0 && (rpr % kConvTileRows == 0 || kConvTileRows % rpr == 0);
                 const uint32_t ni = rpr >= (uint32_t)kConvTileRows ? 1 : kConvTileRows / std::max(rpr, 1u);
                 uint64_t frame = 0;
-                if (whole && ni <= 8 && L.cin % kb == 0) {
+                const bool chunk_pixel = L.cin * c->elem_size == 16;            // a pixel is one 16-byte chunk: two taps per k step, no padding
+                if (whole && ni <= 8 && (L.cin % kb == 0 || chunk_pixel)) {
                     const uint32_t n_oh = kConvTileRows / ni / L.out_w, n_ih = (n_oh - 1) * L.stride + 3;
-                    frame = (uint64_t)ni * n_ih * (L.in_w + 2) * (L.cin * c->elem_size + 16);
+                    frame = (uint64_t)ni * n_ih * (L.in_w + 2) * (L.cin * c->elem_size + (chunk_pixel ? 0 : 16));
                 }
-                if (frame == 0 || frame > 49152 || c->conv_img_lds[l] == 0) c->conv_img_lds[l] = 0;
+                if (c->conv_img_two[l] < 0) c->conv_img_two[l] = chunk_pixel;
+                if (frame == 0 || frame > 49152 || c->conv_img_lds[l] == 0 || c->conv_img_two[l] != (int)chunk_pixel) c->conv_img_lds[l] = 0;
                 else c->conv_img_lds[l] = std::max<uint32_t>(c->conv_img_lds[l], (uint32_t)frame);
             }
             if (k == 0 && L.N_pad >= (uint32_t)kBigMinCols) {      // may be served with big tiles when it gets enough rows
@@ -983,7 +986,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
             const uint32_t g32 = (uint32_t)grid;
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
             else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], c->conv_quad[l],
-                                                                    (c->conv_img_lds[l] > 1 && c->max_conv_cb[l] >= 2 && !c->pool_fused[l] && !c->no_conv_img) ? c->conv_img_lds[l] : 0, g32, s));
+                                                                    (c->conv_img_lds[l] > 1 && !c->pool_fused[l] && !c->no_conv_img) ? c->conv_img_lds[l] : 0, c->conv_img_two[l] == 1, g32, s));
             else TIMED(kProfBig + l, launch_fc_big(ga, c->cfg.dtype, g32, s));
         }
         if (c->has_gap[l]) {
