@@ -228,7 +228,8 @@ def main():
     from paper_1901_06887_amd import profile_summary
     traffic_file = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.md" % (dom_name, w.name))
     roofline["traffic"] = profile_summary.read_traffic(traffic_file)
-    roofline.update({"kernel": "%s<%s>" % (dom_name, "bf16" if es == 2 else "float"),
+    # (the convolution launches of a step run conv_img_kernel, conv_lds_kernel or conv_kernel, by layer shape)
+    roofline.update({"kernel": "%s<%s>" % ("conv_*kernel" if dom_name == "conv_kernel" else dom_name, "bf16" if es == 2 else "float"),
                      "launches_per_step": len(launches),
                      "avg_launch_us": avg_dur_s * 1e6, "empty_bracket_us": bracket_ms * 1e3,
                      "algorithmic_bytes_per_launch": avg_bytes, "algorithmic_flops_per_launch": avg_flops})
