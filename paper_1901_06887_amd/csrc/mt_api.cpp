@@ -1073,8 +1073,8 @@ void request_cost(const mt_ctx* c, const HostTenant& ht, uint64_t* flops, uint64
 constexpr double kUsLaunchGap = 4.0;
 constexpr double kUsFcFixed = 3.7, kUsPerMbCached = 0.132, kUsPerMbHbm = 0.18, kCachedMb = 240.0;
 constexpr double kUsPerMbL2 = 0.056, kUsFcChainFixed = 4.0, kUsPerKStep = 0.12;
-constexpr double kUsBigFixed = 4.0, kUsBigTileFixed = 7.0, kUsBigTilePer4096 = 120.0;
-constexpr double kUsConvFixed = 5.0, kConvMbPerUs = 3.7, kConvMflopPerUs = 0.5e3;      // 3.7 TB/s, 0.5 PFLOP/s
+constexpr double kUsBigFixed = 4.0, kUsBigTileFixed = 7.0, kUsBigTilePer4096 = 116.0;
+constexpr double kUsConvFixed = 5.0, kConvMbPerUs = 4.0, kConvMflopPerUs = 0.5e3;      // 4.0 TB/s, 0.5 PFLOP/s
 constexpr double kUsSmallFixed = 3.0, kCopyMbPerUs = 3.7, kHeadMbPerUs = 5.7, kUsHeadPerRow = 0.0008;
 constexpr double kComputeUnits = 256.0;
 constexpr double kUploadBytesPerMs = 55e6, kUsUploadFixed = 20.0;     // pinned host memory to HBM over the host link: 55 GB/s measured
