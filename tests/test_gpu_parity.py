@@ -141,7 +141,8 @@ def test_convolutions_with_the_input_resident_in_lds(monkeypatch, dtype):
     gathering kernels' answers when that kernel is switched off."""
     cases = [wl.c4(n_tenants=2, n_requests=5, hw=8, chans=(3, 16, 64, 128), strides=(1, 1, 1), classes=6, seed=31),
              wl.c4(n_tenants=2, n_requests=3, hw=32, chans=(3, 32, 64, 40), strides=(1, 2, 1), classes=5, seed=32),
-             wl.c4(n_tenants=1, n_requests=4, hw=16, chans=(3, 32, 128, 72), strides=(1, 1, 2), classes=4, seed=33)]
+             wl.c4(n_tenants=1, n_requests=4, hw=16, chans=(3, 32, 128, 72), strides=(1, 1, 2), classes=4, seed=33),
+             wl.c4(n_tenants=2, n_requests=7, hw=15, chans=(3, 32, 64, 64), strides=(2, 1, 1), classes=5, seed=36)]   # 15x15 inputs, 8x8 outputs
     a = wl.c4(n_tenants=1, n_requests=6, hw=8, chans=(3, 16, 64, 64), strides=(1, 1, 1), classes=4, seed=34)
     b = wl.c4(n_tenants=1, n_requests=6, hw=8, chans=(3, 32, 128, 64), strides=(1, 1, 1), classes=4, seed=35)
     cases.append(wl.Workload("two frames", "bf16", {0: a.tenants[0], 1: b.tenants[0]},
