@@ -13,7 +13,10 @@
 //   conv.hip        conv_kernel (layers at most 32 channels wide: every wave gathers its own
 //                   pixels) and conv_lds_kernel (wider layers: activation bricks gathered once
 //                   per tile into LDS and shared by waves side by side over channels; pools on
-//                   the way out where it can): implicit-GEMM 3x3 convolution for all tenants
+//                   the way out where it can) and conv_img_kernel (layers whose tiles are whole
+//                   output rows of an image or whole small images: the tile's input rows are
+//                   copied to LDS once and every tap is read from there): implicit-GEMM 3x3
+//                   convolution for all tenants
 //   small.hip       gather_kernel / gather_image_kernel (submitted rows -> bricks / padded NHWC),
 //                   gap_kernel (global average pooling), head_kernel (softmax + argmax in
 //                   submission order), copy_kernel (the yardstick for byte counters)
