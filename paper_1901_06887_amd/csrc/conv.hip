@@ -234,19 +234,23 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
 // registers: wave w forms the bricks of pixel block w, and fetches the filter bricks of its
 // own channel block, with direct global->LDS loads, one per k step, each lane supplying the
 // address of its 16 bytes (for the activations: 8 channels of one tap, or a block of zeros
-// for taps outside the image) and the hardware placing lane l at base + 16 l, which is brick
-// order.  K is walked in chunks of kConvKC k steps through a ring of kConvNS stages, chunks
+// for taps outside the image) and the hardware placing lane l at base + 16 l.  The lanes of an
+// activation gather stand in pairs on a pixel's 32 bytes of the k step (lane = 2 * pixel +
+// half), so the texture path sees 32 accesses per instruction instead of 64, and the MFMA
+// operand read (lane (li, lh) takes piece 2 li + lh) touches every bank once.  K is walked in chunks of kConvKC k steps through a ring of kConvNS stages, chunks
 // kConvNS - 1 ahead of their use.
 constexpr uint32_t kConvKC = 2, kConvNS = 3;
 constexpr uint32_t kConvStageBytes = 8 * kConvKC * kBrickBytes;      // 4 pixel blocks + 4 filter areas, kConvKC k steps each
 
 // QUAD (every tenant's input channels are a multiple of 4 chunks, i.e. a pixel's share of two k
 // steps is 64 contiguous bytes): a gather instruction then takes 16 pixels with four consecutive
-// lanes on one pixel's 64 bytes, instead of 32 pixels with one 16-byte piece per lane.  The
-// texture path handles a lane quad on one cache line as one access, so the gather costs a quarter
-// of the accesses.  The hardware's lane placement then yields [pixel][chunk] order instead of
-// brick order; the MFMA operand read picks its 16 bytes from there (a 2-way bank conflict, on a
-// path that has the time).
+// lanes on one pixel's 64 bytes.  The texture path handles a lane quad on one cache line as one
+// access, so the gather costs half the accesses of the pair layout; the data then sits in LDS as
+// [pixel][chunk] and the MFMA operand read has a 2-way bank conflict.  That trade pays where a wave
+// reads two pixel blocks per k step (NCB = 2: 55.2 against 57.3 us on the 32 -> 64 channel layer
+// of the CNN mix) and not where it reads four (NCB = 4: 40.4 against 38.1 us on the 64 -> 128
+// layer, where the counters showed the conflicts as half of the LDS pipe's busy time), so the
+// launcher asks for it with two channel blocks only.
 template <typename T, int NCB, bool QUAD>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_lds_kernel(GemmArgs a)     // three workgroups per CU is what the LDS ring allows
 {
@@ -276,15 +280,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const uint32_t wc = wave % NCB, wr = wave / NCB;
     const bool active = wc < ncb;                                  // idle waves still gather; they stream block 0 and drop it
 
-    // gather role: pixel block `wave`.  Plain: this lane's pixel li, 16 bytes per k step.  QUAD:
-    // pixels lane/4 and lane/4 + 16, chunk lane%4 of the 64 bytes that two k steps take of each.
+    // gather role: pixel block `wave`.  Pairs: pixel lane/2, half lane%2 of its 32 bytes of a k step.
+    // QUAD: pixels lane/4 and lane/4 + 16, chunk lane%4 of the 64 bytes that two k steps take of each.
     constexpr uint32_t NPX = QUAD ? 2 : 1;
     gptr_t zeros = (gptr_t)a.zeros;
     gptr_t img[NPX];
     TapWalk<T> walk[NPX];
 #pragma unroll
     for (uint32_t i = 0; i < NPX; ++i) {
-        const uint32_t gm = m0 + wave * kBrickRows + (QUAD ? (lane >> 2) + 16 * i : li);
+        const uint32_t gm = m0 + wave * kBrickRows + (QUAD ? (lane >> 2) + 16 * i : (lane >> 1));
         const bool row_ok = gm < rows_total;
         const uint32_t mm = row_ok ? gm : m0;
         uint32_t req, pix, oh, ow;
@@ -292,7 +296,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         divmod_uniform(pix, L.out_w, &oh, &ow);
         img[i] = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
         walk[i].init(L, (int32_t)(oh * L.stride) - 1, (int32_t)(ow * L.stride) - 1, row_ok,
-                     QUAD ? (lane & 3) * EPC : lh * EPC, QUAD ? 2 * KB : KB);
+                     QUAD ? (lane & 3) * EPC : (lane & 1) * EPC, QUAD ? 2 * KB : KB);
     }
     gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
     const uint32_t last_kb = n_chunks * kConvKC - 1;
@@ -303,7 +307,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         uint8_t* dst = lds + (c % kConvNS) * kConvStageBytes;
 #pragma unroll
         for (uint32_t kk = 0; kk < kConvKC; ++kk) {
-            // plain: k step kk of all 32 pixels; QUAD: both k steps of pixels 16 kk .. 16 kk + 15
+            // pairs: k step kk of all 32 pixels; QUAD: both k steps of pixels 16 kk .. 16 kk + 15
             const int32_t chunk = walk[QUAD ? kk : 0].next();
             gptr_t p = chunk >= 0 ? img[QUAD ? kk : 0] + chunk : zeros;
             lds_dma16(p, dst + (wave * kConvKC + kk) * kBrickBytes);
@@ -311,7 +315,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         }
     };
     // where lane (li, lh) finds its 16 bytes of k step kk inside a pixel block's area of a stage
-    const uint32_t a_lane = QUAD ? (li * 4 + lh) * 16 : lane * 16;
+    const uint32_t a_lane = QUAD ? (li * 4 + lh) * 16 : (li * 2 + lh) * 16;
     constexpr uint32_t a_kk = QUAD ? 32 : kBrickBytes;
 
     f32x16 acc[RBW];
@@ -618,7 +622,6 @@ static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, uint32_
     if (max_cb <= 1) hipLaunchKernelGGL((conv_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a);
     else if (max_cb == 2 && quad) hipLaunchKernelGGL((conv_lds_kernel<T, 2, true>), dim3(grid), dim3(256), 0, s, a);
     else if (max_cb == 2) hipLaunchKernelGGL((conv_lds_kernel<T, 2, false>), dim3(grid), dim3(256), 0, s, a);
-    else if (quad) hipLaunchKernelGGL((conv_lds_kernel<T, 4, true>), dim3(grid), dim3(256), 0, s, a);
     else hipLaunchKernelGGL((conv_lds_kernel<T, 4, false>), dim3(grid), dim3(256), 0, s, a);
 }
 
