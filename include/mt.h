@@ -60,6 +60,7 @@ typedef enum { MT_ACT_NONE = 0, MT_ACT_RELU = 1, MT_ACT_GELU = 2 } mt_act;
 typedef enum { MT_F32 = 0, MT_BF16 = 1 } mt_dtype;
 
 #define MT_MAX_LAYERS 8
+#define MT_SEG_SLOTS 8      /* runs made of several submissions that may be in flight at once */
 
 /* One layer of a model (closed set, paper section 3.1).
  *   MT_FC:     y[n] = act(b[n] + sum_k W[n][k] x[k]); in_features = K, out_features = N.
@@ -120,9 +121,12 @@ typedef struct {
     uint32_t last_run_launches;  /* kernels the last mt_run enqueued                   */
 } mt_stats;
 
-/* Create a worker context: allocates the weight arena, the tenant table, the batch
- * descriptors and two activation buffers of max_requests * max_width elements on
- * cfg->device.  Errors: MT_EINVAL (null / zero sizes), MT_ENOMEM, MT_EDEVICE. */
+/* Create a worker context (paper section 3: a worker is a long-lived process that hosts the
+ * DNNs of many tenants at once; section 3.3: their weights stay in device memory): allocates
+ * the weight arena, the tenant table, and per run slot the batch descriptors and two
+ * activation buffers of max_requests * max_width elements on cfg->device.  Everything the
+ * later calls need on the device is allocated here; none of them allocates device memory.
+ * Errors: MT_EINVAL (null / zero sizes), MT_ENOMEM, MT_EDEVICE. */
 mt_status mt_create(mt_ctx** out, const mt_config* cfg);
 
 /* Free everything the context owns (synchronises the device first). */
@@ -152,7 +156,8 @@ mt_status mt_unregister_model(mt_ctx* ctx, uint32_t tenant);
  * first row.  Errors: MT_EINVAL, MT_ENOTFOUND, MT_EFULL. */
 mt_status mt_submit(mt_ctx* ctx, uint32_t tenant, const void* inputs, uint32_t n_rows, uint32_t* first_index);
 
-/* Queue n_rows requests of MIXED tenants in arrival order, with the tenant id of
+/* Queue n_rows requests of MIXED tenants in arrival order (paper section 3: a worker receives
+ * the incoming requests of all the tenants it hosts and multiplexes them), with the tenant id of
  * every row already in device memory (what a request front-end that lands ids and
  * payloads in GPU memory would hand over).  tenant_ids: DEVICE int32 [n_rows];
  * inputs: DEVICE, row i at inputs + i*row_stride elements, each row holding its
@@ -163,18 +168,39 @@ mt_status mt_submit(mt_ctx* ctx, uint32_t tenant, const void* inputs, uint32_t n
 mt_status mt_submit_batch(mt_ctx* ctx, const int32_t* tenant_ids, const void* inputs, uint32_t n_rows,
                           uint32_t row_stride, uint32_t* first_index);
 
-/* Serve everything pending: enqueue, on hip_stream (a hipStream_t, NULL = default
- * stream), tenant segmentation, the gather into tenant-contiguous rows, one grouped
- * launch per layer index and kind, and the softmax/argmax head; write predictions to
- * *out in submission order.  Returns without waiting for the GPU; clears the pending
- * list.  *n_rows (optional) receives the number of rows served.  With nothing pending
- * it returns MT_OK and serves 0 rows.  Errors: MT_EINVAL (out too small), MT_ESTATE,
- * MT_EDEVICE. */
+/* Serve everything pending (paper section 3: the worker multiplexes the requests of many
+ * models; section 1.1: a model is evaluated by applying its layers in turn, and the answer to
+ * a request is a vector of class probabilities): enqueue, on hip_stream (a hipStream_t, NULL =
+ * default stream), tenant segmentation, the gather into tenant-contiguous rows, one grouped
+ * launch per layer index and kind, and the softmax/argmax head; write predictions to *out in
+ * submission order.  Never waits for the GPU and allocates nothing; clears the pending list
+ * (also when it fails after part of the run has been enqueued: those rows are lost and their
+ * outputs undefined).  *n_rows (optional) receives the number of rows served.  With nothing
+ * pending it returns MT_OK and serves 0 rows.  Errors: MT_EINVAL (out too small), MT_ESTATE,
+ * MT_EFULL (the run is made of several submissions and the tables of MT_SEG_SLOTS earlier
+ * such runs are all still being read by the GPU: nothing was enqueued, the pending list is
+ * kept, call again later), MT_EDEVICE. */
 mt_status mt_run(mt_ctx* ctx, void* hip_stream, const mt_outputs* out, uint32_t* n_rows);
 
-/* After the stream work of the last mt_run has completed: copy the per-tenant row
- * counts it computed on the device to HOST counts[max_tenants] (synchronises the
- * stream it ran on).  For tests and accounting. */
+/* What a model needs of a context, from its description alone (no context, no device): the
+ * bytes its packed weights occupy in the arena (padded layouts, what mt_register_model takes
+ * from cfg.arena_bytes and what an upload moves: the fixed footprint of paper section 3.3),
+ * the max_width and max_classes a context must have to accept it, and the length of one
+ * request's input.  dtype: mt_dtype.  Errors: MT_EINVAL (null), MT_EUNSUPPORTED (a chain that
+ * mt_register_model would reject for its kinds, activations or geometry). */
+typedef struct {
+    uint64_t arena_bytes;
+    uint32_t min_width;      /* smallest cfg.max_width that accepts the model   */
+    uint32_t n_classes;      /* smallest cfg.max_classes that accepts the model */
+    uint32_t in_len;         /* elements of one request's input                 */
+    uint32_t reserved;
+} mt_model_footprint;
+mt_status mt_model_footprint_get(const mt_layer_spec* specs, uint32_t n_layers, uint32_t dtype, mt_model_footprint* out);
+
+/* The per-tenant batch sizes of the last mt_run (paper section 3.2: the cost of a run varies
+ * with the batch size of every model in it, which the device-side segmentation computes):
+ * copies the counts to HOST counts[max_tenants] after synchronising the stream the run was
+ * enqueued on.  For tests and accounting. */
 mt_status mt_last_counts(mt_ctx* ctx, uint32_t* counts);
 
 /* Model cache (cfg.cache; paper section 3.3: a worker alternates between many tenants'
@@ -252,43 +278,6 @@ mt_status mt_estimate_run(mt_ctx* ctx, const uint32_t* counts, mt_run_estimate* 
 mt_status mt_admit(mt_ctx* ctx, const uint32_t* pending, double budget_ms, uint32_t* admitted, mt_run_estimate* est);
 
 mt_status mt_get_stats(const mt_ctx* ctx, mt_stats* out);
-
-/* Per-kernel timing of mt_run, for measurement.  While enabled, mt_run brackets every
- * kernel it enqueues with HIP events on the run's stream (this costs a few microseconds
- * per kernel, so throughput is measured with it off).  mt_get_profile synchronises the
- * stream of the last profiled mt_run and fills *out with elapsed milliseconds; entries
- * of launches that did not happen are 0. */
-typedef struct {
-    float batcher_ms, gather_ms, head_ms;
-    float fc_ms[MT_MAX_LAYERS];     /* grouped FC launch of each layer index          */
-    float fc_big_ms[MT_MAX_LAYERS]; /* grouped big-tile FC launch of each layer index */
-    float conv_ms[MT_MAX_LAYERS];   /* grouped convolution launch of each layer index */
-    float gap_ms[MT_MAX_LAYERS];    /* pooling launch of each layer index             */
-    float total_ms;                 /* first kernel start to last kernel end          */
-} mt_profile;
-mt_status mt_set_profiling(mt_ctx* ctx, int enable);
-mt_status mt_get_profile(mt_ctx* ctx, mt_profile* out);
-
-/* Testing aid: fill the context's internal activation and logits buffers with NaN bit
- * patterns (synchronous).  A correct run overwrites or zero-fills everything it later
- * reads, so results must not change.  Errors: MT_ESTATE (host-only), MT_EDEVICE. */
-mt_status mt_debug_poison(mt_ctx* ctx);
-
-/* Measurement aid: one plain copy kernel (16 bytes per lane, grid-stride) of `bytes` bytes
- * (a multiple of 16) from `src` to `dst`, both device memory owned by the caller, on `stream`
- * of the current device.  It reads and writes exactly `bytes` bytes once each, which is what
- * hardware byte counters are calibrated against.  Errors: MT_EINVAL (null pointer, size not
- * a multiple of 16), MT_EDEVICE (launch failure). */
-mt_status mt_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream);
-
-/* Measurement aid: how the library would split a fully-connected layer of one tenant that
- * has `rows` requests in a run and `out_features` outputs, in a run that uses its
- * compute-bound kernel (large batches; the decision per run and per layer index is the
- * library's): the number of rows that kernel serves, the remaining rows being served by the
- * weight-streaming kernel; 0 if the layer does not qualify at all.  Pure function of its
- * arguments; needs no context and no device.  Lets a benchmark attribute flops to the
- * kernel that performed them. */
-uint32_t mt_debug_big_tile_rows(uint32_t rows, uint32_t out_features);
 
 /* Text of the last error on this context ("" if none); valid until the next call. */
 const char* mt_last_error(const mt_ctx* ctx);

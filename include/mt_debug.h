@@ -1,0 +1,63 @@
+/*
+ * mt_debug.h - measurement and testing aids of the multi-tenant worker runtime.  Not part of
+ * the serving interface (include/mt.h); exported by the same library.
+ */
+#ifndef MT_DEBUG_H
+#define MT_DEBUG_H
+
+#include "mt.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Per-kernel timing of mt_run, for measurement.  While enabled, mt_run brackets every
+ * kernel it enqueues with HIP events on the run's stream (this costs a few microseconds
+ * per kernel, so throughput is measured with it off).  mt_get_profile synchronises the
+ * stream of the last profiled mt_run and fills *out with elapsed milliseconds; entries
+ * of launches that did not happen are 0. */
+typedef struct {
+    float batcher_ms, gather_ms, head_ms;
+    float fc_ms[MT_MAX_LAYERS];     /* grouped FC launch of each layer index          */
+    float fc_big_ms[MT_MAX_LAYERS]; /* grouped big-tile FC launch of each layer index */
+    float conv_ms[MT_MAX_LAYERS];   /* grouped convolution launch of each layer index */
+    float gap_ms[MT_MAX_LAYERS];    /* pooling launch of each layer index             */
+    float total_ms;                 /* first kernel start to last kernel end          */
+} mt_profile;
+mt_status mt_set_profiling(mt_ctx* ctx, int enable);
+mt_status mt_get_profile(mt_ctx* ctx, mt_profile* out);
+
+/* Testing aid: fill the context's internal activation and logits buffers with NaN bit
+ * patterns (synchronous).  A correct run overwrites or zero-fills everything it later
+ * reads, so results must not change.  Errors: MT_ESTATE (host-only), MT_EDEVICE. */
+mt_status mt_debug_poison(mt_ctx* ctx);
+
+/* Measurement aid: one plain copy kernel (16 bytes per lane, grid-stride) of `bytes` bytes
+ * (a multiple of 16) from `src` to `dst`, both device memory owned by the caller, on `stream`
+ * of the current device.  It reads and writes exactly `bytes` bytes once each, which is what
+ * hardware byte counters are calibrated against.  Errors: MT_EINVAL (null pointer, size not
+ * a multiple of 16), MT_EDEVICE (launch failure). */
+mt_status mt_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+
+/* Measurement aid: how the library would split a fully-connected layer of one tenant that
+ * has `rows` requests in a run and `out_features` outputs, in a run that uses its
+ * compute-bound kernel (large batches; the decision per run and per layer index is the
+ * library's): the number of rows that kernel serves, the remaining rows being served by the
+ * weight-streaming kernel; 0 if the layer does not qualify at all.  Pure function of its
+ * arguments; needs no context and no device.  Lets a benchmark attribute flops to the
+ * kernel that performed them. */
+uint32_t mt_debug_big_tile_rows(uint32_t rows, uint32_t out_features);
+
+/* Measurement aid: what a loop of nothing but bf16 matrix instructions sustains on the current
+ * device.  Runs, on `stream`, a kernel in which every wavefront issues v_mfma_f32_32x32x16_bf16
+ * on pseudo-random operands (eight independent accumulators, two wavefronts per SIMD, no memory
+ * traffic) for about ten milliseconds, waits for it, and writes the rate in TFLOP/s to *tflops.
+ * The chip lowers its clock under matrix load, so this figure, not the published peak, is what a
+ * compute-bound kernel can approach.  Allocates (and frees) a small device buffer.
+ * Errors: MT_EINVAL (null), MT_EDEVICE. */
+mt_status mt_debug_mfma_rate(void* stream, double* tflops);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MT_DEBUG_H */

@@ -59,6 +59,11 @@ class mt_run_estimate(ctypes.Structure):
                 ("upload_bytes", ctypes.c_double), ("upload_ms", ctypes.c_double)]
 
 
+class mt_model_footprint(ctypes.Structure):
+    _fields_ = [("arena_bytes", ctypes.c_uint64), ("min_width", ctypes.c_uint32), ("n_classes", ctypes.c_uint32),
+                ("in_len", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
 class mt_outputs(ctypes.Structure):
     _fields_ = [("labels", ctypes.c_void_p), ("probs", ctypes.c_void_p), ("logits", ctypes.c_void_p),
                 ("n_classes", ctypes.c_void_p), ("capacity", ctypes.c_uint32), ("row_stride", ctypes.c_uint32)]
@@ -102,6 +107,8 @@ def load_library() -> ctypes.CDLL:
     L.mt_admit.argtypes = [vp, ctypes.POINTER(u32), ctypes.c_double, ctypes.POINTER(u32), ctypes.POINTER(mt_run_estimate)]
     L.mt_prefetch.argtypes = [vp, ctypes.POINTER(u32), u32, vp]
     L.mt_cache_stats_get.argtypes = [vp, ctypes.POINTER(mt_cache_stats)]
+    L.mt_model_footprint_get.argtypes = [ctypes.POINTER(mt_layer_spec), u32, u32, ctypes.POINTER(mt_model_footprint)]
+    L.mt_debug_mfma_rate.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
     L.mt_debug_poison.argtypes = [vp]
     L.mt_debug_copy.argtypes = [vp, vp, ctypes.c_uint64, vp]
     L.mt_debug_big_tile_rows.argtypes = [u32, u32]
@@ -113,7 +120,7 @@ def load_library() -> ctypes.CDLL:
     L.mt_version.restype = ctypes.c_char_p
     for name in ("mt_create", "mt_destroy", "mt_register_model", "mt_unregister_model", "mt_submit",
                  "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_tenant_account_get", "mt_estimate_run", "mt_prefetch", "mt_cache_stats_get", "mt_admit", "mt_debug_poison", "mt_debug_copy",
-                 "mt_set_profiling", "mt_get_profile"):
+                 "mt_set_profiling", "mt_get_profile", "mt_model_footprint_get", "mt_debug_mfma_rate"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -254,6 +261,25 @@ class Context:
         s = mt_stats()
         self._check(self._lib.mt_get_stats(self._h, ctypes.byref(s)))
         return {k: getattr(s, k) for k, _ in mt_stats._fields_}
+
+
+def model_footprint(specs: Sequence[mt_layer_spec], dtype: int) -> dict:
+    """mt_model_footprint_get: arena bytes, smallest max_width / max_classes, input length of a model."""
+    n = len(specs)
+    f = mt_model_footprint()
+    st = load_library().mt_model_footprint_get((mt_layer_spec * n)(*specs), n, dtype, ctypes.byref(f))
+    if st != MT_OK:
+        raise MtError(st, "mt_model_footprint_get failed")
+    return {"arena_bytes": int(f.arena_bytes), "min_width": int(f.min_width), "n_classes": int(f.n_classes), "in_len": int(f.in_len)}
+
+
+def debug_mfma_rate(stream: int = 0) -> float:
+    """TFLOP/s that a loop of nothing but bf16 matrix instructions sustains on the current device."""
+    v = ctypes.c_double(0.0)
+    st = load_library().mt_debug_mfma_rate(ctypes.c_void_p(stream or None), ctypes.byref(v))
+    if st != MT_OK:
+        raise MtError(st, "mt_debug_mfma_rate failed")
+    return v.value
 
 
 def debug_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:

@@ -57,8 +57,6 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     const uint32_t ncb = min(kBigBlocks, L.N_pad / kBrickRows - n0 / kBrickRows);
     const uint32_t wm = wave / WN, wn = wave % WN;
 
-    // staging: waves 0..3 copy the 8 activation row blocks, waves 4..7 the 8 weight column blocks
-    // (blocks past the tile or the layer repeat the last valid one)
     // staging: the first half of the waves copies the 8 activation row blocks, the second half the
     // 8 weight column blocks, BPW blocks each (blocks past the tile or the layer repeat the last valid one)
     const u32x4* lp[BPW];
@@ -209,7 +207,7 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
                     float* row = a.logits + (size_t)(seg0 + mb + li) * a.C_pad;
 #pragma unroll
                     for (int g = 0; g < 4; ++g)
-                        if (nl + 8 * g < L.N) *(f32x4*)(row + nl + 8 * g) = y[g];                 // may run into the row's padding (C_pad >= N_pad)
+                        if (nl + 8 * g < L.N) *(f32x4*)(row + nl + 8 * g) = y[g];                 // starts below N at a multiple of 4, so it ends inside the row's C_pad = round_up(classes, 4) floats
                 }
             } else {
                 u32x4* out = (u32x4*)((T*)a.act_out + (size_t)seg0 * a.S) +

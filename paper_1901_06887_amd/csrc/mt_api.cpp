@@ -11,13 +11,14 @@
 #include <vector>
 
 #include "mt_internal.h"
+#include "../../include/mt_debug.h"
 
 using namespace mt;
 
 namespace {
 
 constexpr uint32_t kMaxTenants = 2048;
-constexpr uint32_t kSegSlots = 4;
+constexpr uint32_t kSegSlots = MT_SEG_SLOTS;   // pinned segment tables: runs of several submissions in flight at once
 constexpr uint32_t kMaxRunSlots = 4;      // runs in flight at once (each with its own device scratch); <= kSegSlots
 constexpr uint64_t kArenaAlign = 256;
 // profiling slots: batcher, gather, head, then gemm and gap of every layer index
@@ -138,7 +139,6 @@ struct mt_ctx {
     // model cache
     bool cache = false;
     uint64_t use_clock = 0;                 // stamps HostTenant::last_use
-    uint8_t* h_zero_rows = nullptr;         // pinned zeros: TenantDev and facts of an evicted tenant
     hipEvent_t cache_event = nullptr;       // recorded behind the last asynchronous residency change
     hipStream_t cache_stream = nullptr;
     bool cache_pending = false;
@@ -253,6 +253,26 @@ struct StageTail {
 size_t stage_tail_offset(uint64_t arena_len) { return (size_t)round_up64(arena_len, 256); }
 size_t stage_bytes(uint64_t arena_len) { return stage_tail_offset(arena_len) + sizeof(StageTail); }
 
+// A tenant's rows of the three device tables travel inside kernel arguments: the runtime copies
+// those when the launch is enqueued, so the host may change its copy (a later placement of the same
+// model at another arena offset) while this one is still queued behind earlier work.  An asynchronous
+// copy from the host block would read it only when it executes.  The tenant row goes last, after a
+// fence: a tenant that the batcher sees has its layer rows in place.
+__global__ void install_rows_kernel(StageTail tail, LayerDev* rows, uint32_t* facts, TenantDev* td)
+{
+    const uint32_t* src_rows = (const uint32_t*)tail.rows;
+    for (uint32_t i = threadIdx.x; i < sizeof(tail.rows) / 4; i += blockDim.x) ((uint32_t*)rows)[i] = src_rows[i];
+    const uint32_t* src_facts = &tail.facts[0][0];
+    for (uint32_t i = threadIdx.x; i < sizeof(tail.facts) / 4; i += blockDim.x) facts[i] = src_facts[i];
+    __threadfence();
+    __syncthreads();
+    const uint32_t* src_td = (const uint32_t*)&tail.td;
+    for (uint32_t i = threadIdx.x; i < sizeof(tail.td) / 4; i += blockDim.x) ((uint32_t*)td)[i] = src_td[i];
+}
+static_assert(sizeof(StageTail) <= 2048, "the table rows of one tenant must fit kernel arguments");
+
+hipError_t install_rows(mt_ctx* c, uint32_t tenant, const StageTail& tail, hipStream_t s);
+
 // Point the tenant's layer descriptors at arena block `off` and refresh the table rows in its stage.
 void place_tenant(const mt_ctx* c, HostTenant& ht, uint64_t off, uint8_t* stage)
 {
@@ -268,22 +288,25 @@ void place_tenant(const mt_ctx* c, HostTenant& ht, uint64_t off, uint8_t* stage)
     fill_facts(c, ht, tail->facts);
 }
 
-// Copy a placed tenant's weights and table rows to the device: on `s` without waiting (the stage
-// must be pinned and stay untouched until the copies are done), or synchronously.
+hipError_t install_rows(mt_ctx* c, uint32_t tenant, const StageTail& tail, hipStream_t s)
+{
+    hipLaunchKernelGGL(install_rows_kernel, dim3(1), dim3(256), 0, s, tail, c->d_layers + (size_t)tenant * MT_MAX_LAYERS,
+                       c->d_facts + (size_t)tenant * 2 * MT_MAX_LAYERS, c->d_tenants + tenant);
+    return hipGetLastError();
+}
+
+// Copy a placed tenant's weights and table rows to the device: on `s` without waiting (the arena
+// image in the stage must be pinned and is never changed again; the table rows are taken from the
+// stage now, see install_rows_kernel), or synchronously.
 hipError_t upload_tenant(mt_ctx* c, uint32_t tenant, const HostTenant& ht, const uint8_t* stage, hipStream_t s, bool async)
 {
     const StageTail* tail = (const StageTail*)(stage + stage_tail_offset(ht.arena_len));
-    struct { void* dst; const void* src; size_t n; } copies[] = {
-        {c->d_arena + ht.arena_off, stage, (size_t)ht.arena_len},
-        {c->d_layers + (size_t)tenant * MT_MAX_LAYERS, tail->rows, sizeof tail->rows},
-        {c->d_facts + (size_t)tenant * 2 * MT_MAX_LAYERS, tail->facts, sizeof tail->facts},
-        {c->d_tenants + tenant, &tail->td, sizeof tail->td},          // last: the tenant becomes visible to the batcher
-    };
-    for (const auto& cp : copies) {
-        const hipError_t e = async ? hipMemcpyAsync(cp.dst, cp.src, cp.n, hipMemcpyHostToDevice, s)
-                                   : hipMemcpy(cp.dst, cp.src, cp.n, hipMemcpyHostToDevice);
-        if (e != hipSuccess) return e;
-    }
+    hipError_t e = async ? hipMemcpyAsync(c->d_arena + ht.arena_off, stage, (size_t)ht.arena_len, hipMemcpyHostToDevice, s)
+                         : hipMemcpy(c->d_arena + ht.arena_off, stage, (size_t)ht.arena_len, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return e;
+    e = install_rows(c, tenant, *tail, async ? s : nullptr);          // behind the weights on the same stream
+    if (e != hipSuccess) return e;
+    if (!async) { e = hipStreamSynchronize(nullptr); if (e != hipSuccess) return e; }
     c->n_uploads++; c->upload_bytes += ht.arena_len;
     return hipSuccess;
 }
@@ -291,18 +314,9 @@ hipError_t upload_tenant(mt_ctx* c, uint32_t tenant, const HostTenant& ht, const
 // Take a tenant's model off the device: the batcher no longer sees it, its arena block is free.
 hipError_t hide_tenant(mt_ctx* c, uint32_t tenant, hipStream_t s, bool async)
 {
-    static const StageTail zeros{};
-    const StageTail* z = async ? (const StageTail*)c->h_zero_rows : &zeros;
-    struct { void* dst; const void* src; size_t n; } copies[] = {
-        {c->d_tenants + tenant, &z->td, sizeof z->td},
-        {c->d_facts + (size_t)tenant * 2 * MT_MAX_LAYERS, z->facts, sizeof z->facts},
-    };
-    for (const auto& cp : copies) {
-        const hipError_t e = async ? hipMemcpyAsync(cp.dst, cp.src, cp.n, hipMemcpyHostToDevice, s)
-                                   : hipMemcpy(cp.dst, cp.src, cp.n, hipMemcpyHostToDevice);
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
+    const hipError_t e = install_rows(c, tenant, StageTail{}, async ? s : nullptr);
+    if (e != hipSuccess || async) return e;
+    return hipStreamSynchronize(nullptr);
 }
 
 // Find `len` bytes of arena.  In cache mode, models used least recently (and before `protect`)
@@ -549,6 +563,20 @@ void pack_weights(const HostLayer& hl, const void* w_src, uint8_t* dst)
     }
 }
 
+// Offsets of a planned model's layers inside its arena block; returns the block's length.
+uint64_t layout_model(HostTenant* ht)
+{
+    uint64_t total = 0;
+    for (uint32_t l = 0; l < ht->n_layers; ++l) {
+        HostLayer& hl = ht->layers[l];
+        hl.w_rel = total; total += round_up64(hl.w_bytes, kArenaAlign);
+        hl.b_rel = total; total += round_up64(hl.b_bytes, kArenaAlign);
+    }
+    if (total == 0) total = kArenaAlign;
+    ht->arena_len = total;
+    return total;
+}
+
 }  // namespace
 
 extern "C" {
@@ -623,8 +651,6 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     }
     bind_slot(c, c->slots[0]);
     if (c->cache) {
-        CREATE_TRY(hipHostMalloc((void**)&c->h_zero_rows, sizeof(StageTail), hipHostMallocDefault));
-        std::memset(c->h_zero_rows, 0, sizeof(StageTail));
         CREATE_TRY(hipEventCreateWithFlags(&c->cache_event, hipEventDisableTiming));
     }
     for (uint32_t i = 0; i < kSegSlots; ++i) {
@@ -656,10 +682,33 @@ mt_status mt_destroy(mt_ctx* c)
         }
         for (hipEvent_t e : c->prof_events) if (e) (void)hipEventDestroy(e);
         for (HostTenant& t : c->tenants) if (t.stage) (void)hipHostFree(t.stage);
-        if (c->h_zero_rows) (void)hipHostFree(c->h_zero_rows);
         if (c->cache_event) (void)hipEventDestroy(c->cache_event);
     }
     delete c;
+    return MT_OK;
+}
+
+mt_status mt_model_footprint_get(const mt_layer_spec* specs, uint32_t n_layers, uint32_t dtype, mt_model_footprint* out)
+{
+    if (!specs || !out || dtype > MT_BF16) return MT_EINVAL;
+    *out = mt_model_footprint{};
+    mt_ctx probe;                                   // a context without limits: the plan only depends on the element size
+    probe.elem_size = dtype == MT_BF16 ? 2 : 4;
+    probe.S = 0xffffffc0u;
+    probe.cfg.max_classes = 0xffffffffu;
+    HostTenant ht;
+    const mt_status st = plan_model(&probe, specs, n_layers, &ht);
+    if (st != MT_OK) return st;
+    out->arena_bytes = layout_model(&ht);
+    out->n_classes = ht.dev.n_classes;
+    out->in_len = ht.dev.in_len;
+    uint32_t width = ht.dev.in_fill;                // what plan_model holds against max_width
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const LayerDev& d = ht.layers[l].dev;
+        if (!d.is_last) width = std::max(width, d.out_fill);
+        if (d.kind == MT_FC) width = std::max(width, d.K);
+    }
+    out->min_width = width;
     return MT_OK;
 }
 
@@ -676,14 +725,7 @@ mt_status mt_register_model(mt_ctx* c, uint32_t tenant, const mt_layer_spec* spe
     for (uint32_t l = 0; l < n_layers; ++l)
         if (ht.layers[l].dev.kind != MT_GAP && !weights[l]) return fail(c, MT_EINVAL, "layer %u: null weights", l);
 
-    uint64_t total = 0;
-    for (uint32_t l = 0; l < n_layers; ++l) {
-        HostLayer& hl = ht.layers[l];
-        hl.w_rel = total; total += round_up64(hl.w_bytes, kArenaAlign);
-        hl.b_rel = total; total += round_up64(hl.b_bytes, kArenaAlign);
-    }
-    if (total == 0) total = kArenaAlign;
-    ht.arena_len = total;
+    const uint64_t total = layout_model(&ht);
     if (total > c->cfg.arena_bytes)
         return fail(c, MT_ENOMEM, "model needs %llu bytes, the weight arena has %llu", (unsigned long long)total, (unsigned long long)c->cfg.arena_bytes);
 
@@ -893,16 +935,28 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     if (!pick) for (RunSlot& r : c->slots) if (!r.used) { pick = &r; break; }
     if (!pick) { pick = &c->slots[0]; for (RunSlot& r : c->slots) if (r.last_run < pick->last_run) pick = &r; }
     RunSlot& rs = *pick;
-    if (rs.used && rs.stream != s) HIP_TRY(c, hipStreamWaitEvent(s, rs.done, 0));
-    bind_slot(c, rs);
-    const uint32_t slot = (uint32_t)(c->run_count % kSegSlots);
     // A run of one submission carries its segment in the kernel arguments; only runs of several
     // submissions put the table into one of the pinned slots, which stays busy until the run is over.
+    // The host never waits for one: when the GPU is still reading all of them the call is refused.
     const uint32_t n_segs = (uint32_t)c->pending.size();
+    uint32_t slot = 0;
     if (n_segs > 1) {
-        if (c->seg_busy[slot]) { HIP_TRY(c, hipEventSynchronize(c->seg_event[slot])); c->seg_busy[slot] = false; }
+        bool found = false;
+        for (uint32_t i = 0; i < kSegSlots && !found; ++i) {
+            const uint32_t cand = (uint32_t)((c->run_count + i) % kSegSlots);
+            if (c->seg_busy[cand]) {
+                const hipError_t q = hipEventQuery(c->seg_event[cand]);
+                if (q == hipErrorNotReady) continue;
+                if (q != hipSuccess) return fail(c, MT_EDEVICE, "hipEventQuery: %s", hipGetErrorString(q));
+                c->seg_busy[cand] = false;
+            }
+            slot = cand; found = true;
+        }
+        if (!found) return fail(c, MT_EFULL, "%u runs of several submissions are still in flight; call again later", kSegSlots);
         std::memcpy(c->h_segs[slot], c->pending.data(), c->pending.size() * sizeof(Segment));
     }
+    if (rs.used && rs.stream != s) HIP_TRY(c, hipStreamWaitEvent(s, rs.done, 0));
+    bind_slot(c, rs);
     const uint32_t T = c->cfg.max_tenants;
     uint32_t launches = 0;
 
@@ -934,6 +988,9 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     const bool fuse_head = !c->no_fused_head && c->min_reg_classes <= kBrickRows;
     const uint32_t head_min_classes = fuse_head ? kBrickRows + 1 : 0;
     if (c->profiling) for (uint32_t i = 0; i < kProfSlots; ++i) c->prof_used[i] = false;
+    // From here on a failure may leave part of the run enqueued: the launches sit in a body of their
+    // own, and the bookkeeping behind it (events, slot, pending list) is closed whatever it returns.
+    auto enqueue = [&]() -> mt_status {
 #define TIMED(slot, call)                                                                   \
     do {                                                                                    \
         if (c->profiling) HIP_TRY(c, hipEventRecord(c->prof_events[2 * (slot)], s));        \
@@ -1006,21 +1063,28 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         TIMED(kProfHead, launch_head(h, s));
     }
 #undef TIMED
-    c->prof_valid = c->profiling;
-
+    return MT_OK;
+    };
+    mt_status st = enqueue();
+    if (st != MT_OK && launches == 0) return st;         // nothing was enqueued: the pending list is kept
+    c->prof_valid = c->profiling && st == MT_OK;
     if (n_segs > 1) {
-        HIP_TRY(c, hipEventRecord(c->seg_event[slot], s));
+        const hipError_t e = hipEventRecord(c->seg_event[slot], s);
+        if (e != hipSuccess && st == MT_OK) st = fail(c, MT_EDEVICE, "hipEventRecord: %s", hipGetErrorString(e));
         c->seg_busy[slot] = true;
     }
-    HIP_TRY(c, hipEventRecord(rs.done, s));
+    {
+        const hipError_t e = hipEventRecord(rs.done, s);
+        if (e != hipSuccess && st == MT_OK) st = fail(c, MT_EDEVICE, "hipEventRecord: %s", hipGetErrorString(e));
+    }
     rs.used = true; rs.stream = s; rs.last_run = c->run_count;
     c->run_count++;
     c->last_stream = s;
     c->pending.clear();
     c->pending_rows = 0;
-    c->last_run_rows = R; c->last_run_launches = launches;
-    if (n_rows) *n_rows = R;
-    return MT_OK;
+    c->last_run_rows = st == MT_OK ? R : 0; c->last_run_launches = launches;
+    if (n_rows && st == MT_OK) *n_rows = R;
+    return st;
 }
 
 mt_status mt_last_counts(mt_ctx* c, uint32_t* counts)
@@ -1295,6 +1359,32 @@ mt_status mt_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream
 {
     if (!dst || !src || bytes % 16) return MT_EINVAL;
     return launch_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? MT_OK : MT_EDEVICE;
+}
+
+mt_status mt_debug_mfma_rate(void* stream, double* tflops)
+{
+    if (!tflops) return MT_EINVAL;
+    *tflops = 0.0;
+    constexpr uint32_t kGrid = 2048, kIters = 500;          // 2048 workgroups of 8 waves x 500 x 64 MFMAs: ~10 ms
+    hipStream_t s = (hipStream_t)stream;
+    float* buf = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    float ms = 0.0f;
+    hipError_t e = hipMalloc((void**)&buf, (size_t)kGrid * 512 * 4);
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e == hipSuccess) e = launch_mfma_rate(buf, kIters / 10, kGrid, s);      // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    if (e == hipSuccess) e = launch_mfma_rate(buf, kIters, kGrid, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (buf) (void)hipFree(buf);
+    if (e != hipSuccess || ms <= 0.0f) return MT_EDEVICE;
+    *tflops = (double)kGrid * 8 * kIters * 64 * 32768.0 / (ms * 1e-3) / 1e12;
+    return MT_OK;
 }
 
 uint32_t mt_debug_big_tile_rows(uint32_t rows, uint32_t out_features)

@@ -185,8 +185,9 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
 hipError_t launch_gather_image(const GatherArgs& a, hipStream_t s);
 hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
 hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
-// max_cb: the widest tile of this layer index over the registered tenants, in 32-channel blocks (1..4)
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s);
+hipError_t launch_mfma_rate(float* out, uint32_t iters, uint32_t grid, hipStream_t s);   // out: grid * 512 floats
+// max_cb: the widest tile of this layer index over the registered tenants, in 32-channel blocks (1..4)
 // quad: every tenant's input channels at this layer index are a multiple of four 16-byte chunks
 hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, uint32_t grid, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, hipStream_t s);

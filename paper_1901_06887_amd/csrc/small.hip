@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a)
 #pragma unroll
         for (uint32_t q = 0; q < 4; ++q) {
             const uint32_t c = (q * 64 + lane) * 4;
-            v[q] = c < a.C_pad ? *(const f32x4*)(z + c) : f32x4{0, 0, 0, 0};   // C_pad is a multiple of 32
+            v[q] = c < a.C_pad ? *(const f32x4*)(z + c) : f32x4{0, 0, 0, 0};   // C_pad is a multiple of 4 and c too: a 16-byte read stays inside the row
 #pragma unroll
             for (uint32_t i = 0; i < 4; ++i) {
                 if (c + i >= C) v[q][i] = -INFINITY;
@@ -283,6 +283,45 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s
     if (n == 0) return hipSuccess;
     const uint32_t grid = (uint32_t)std::min<uint64_t>((n + 255) / 256, 256 * 32);
     hipLaunchKernelGGL(copy_kernel, dim3(grid), dim3(256), 0, s, (u32x4*)dst, (const u32x4*)src, n);
+    return hipGetLastError();
+}
+
+// ---- matrix-instruction rate: what a loop of nothing but MFMAs sustains --------------------------
+// Every wave keeps eight independent 32x32 accumulators going over pseudo-random bf16 operands
+// (values of both signs and many exponents, like activations and weights: the clock the chip
+// holds under matrix load depends on how much the operands toggle).  No memory traffic in the loop.
+__global__ __launch_bounds__(512) void mfma_rate_kernel(float* out, uint32_t iters)
+{
+    constexpr int NACC = 8;
+    auto rnd = [](uint32_t x) {                    // integer hash -> roughly bell-shaped value in (-2, 2)
+        x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+        return ((float)(x & 0xffff) + (float)(x >> 16)) * (1.0f / 32768.0f) - 2.0f;
+    };
+    bf16x8 a[NACC], b[NACC];
+    for (int j = 0; j < NACC; ++j)
+        for (int i = 0; i < 8; ++i) {
+            a[j][i] = (__bf16)rnd((threadIdx.x * 8 + i) * 16 + j);
+            b[j][i] = (__bf16)(rnd((threadIdx.x * 8 + i) * 16 + j + 0x9e3779b9u) * 0.015625f);
+        }
+    f32x16 acc[NACC];
+    for (int j = 0; j < NACC; ++j)
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+    for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < NACC; ++r)
+#pragma unroll
+            for (int j = 0; j < NACC; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[(j + r) % NACC], acc[j], 0, 0, 0);
+    }
+    float sum = 0.0f;
+    for (int j = 0; j < NACC; ++j)
+        for (int v = 0; v < 16; ++v) sum += acc[j][v];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = sum;
+}
+
+// `out` holds grid * 512 floats; flops of the launch = grid * 8 waves * iters * 64 MFMAs * 32768
+hipError_t launch_mfma_rate(float* out, uint32_t iters, uint32_t grid, hipStream_t s)
+{
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(512), 0, s, out, iters);
     return hipGetLastError();
 }
 

@@ -27,24 +27,16 @@ def specs_of(layers) -> list:
 def context_for(tenants: Dict[int, object], dtype: str, max_requests: int, device: int = 0,
                 max_tenants: Optional[int] = None, arena_slack: float = 1.05, run_slots: int = 1,
                 arena_bytes: Optional[int] = None, cache: bool = False) -> B.Context:
-    """A context sized for the given tenant models (objects with .layers/.weights/.biases)."""
-    es = 4 if dtype == "f32" else 2
+    """A context sized for the given tenant models (objects with .layers/.weights/.biases); the
+    sizes come from the library's own account of every model (mt_model_footprint_get)."""
+    code = B.MT_F32 if dtype == "f32" else B.MT_BF16
     width, classes, arena = 64, 1, 0
     for m in tenants.values():
-        n = len(m.layers)
-        for i, l in enumerate(m.layers):
-            in_len = l.in_len()
-            if l.kind == B.MT_CONV2D:
-                in_len = l.in_h * l.in_w * ((l.in_features + 7) // 8 * 8)
-            width = max(width, in_len + 64, (l.out_len() + 64) if i < n - 1 else 0)
-            if m.weights[i] is not None:
-                k = l.in_features if l.kind == B.MT_FC else 9 * ((l.in_features + 7) // 8 * 8)
-                n_pad = (l.out_features + 63) // 64 * 64
-                arena += (n_pad * ((k + 63) // 64 * 64) * es + 255) // 256 * 256 + (n_pad * 4 + 255) // 256 * 256
-        classes = max(classes, m.layers[-1].out_len())
+        f = B.model_footprint(specs_of(m.layers), code)
+        width, classes, arena = max(width, f["min_width"]), max(classes, f["n_classes"]), arena + f["arena_bytes"]
     T = max_tenants if max_tenants is not None else (max(tenants) + 1 if tenants else 1)
     return B.Context(T, max_requests, width, classes, arena_bytes if arena_bytes is not None else int(arena * arena_slack) + (1 << 20),
-                     B.MT_F32 if dtype == "f32" else B.MT_BF16, device, run_slots, cache)
+                     code, device, run_slots, cache)
 
 
 def register_tenants(ctx: B.Context, tenants: Dict[int, object]):

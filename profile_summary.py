@@ -1,38 +1,25 @@
 """Turn rocprofv3 CSV output into the short text summaries kept next to the benchmarks.
 
-  python -m paper_1901_06887_amd.profile_summary stats <..._kernel_stats.csv>
+  python profile_summary.py stats <..._kernel_stats.csv>
       per-kernel calls / average / share table of a `--kernel-trace --stats` run
 
-  python -m paper_1901_06887_amd.profile_summary traffic --fetch <..._counter_collection.csv>
+  python profile_summary.py traffic --fetch <..._counter_collection.csv>
           --write <..._counter_collection.csv> --kernel fc_kernel --copy-bytes N
       HBM bytes per launch of one kernel from two `--pmc` runs (FETCH_SIZE, then WRITE_SIZE,
       both in KiB per dispatch), each scaled by what the same counter reads for the library's
-      plain copy kernel moving N bytes in the same run.  Prints `key: value` lines; the
-      benchmark reads `traffic_bytes_per_launch` and `kernel_source_sha256` back.
+      plain copy kernel moving N bytes in the same run.  Prints `key: value` lines; bench.py
+      reads `traffic_bytes_per_launch` and `kernel_source_sha256` back.
+
+  python profile_summary.py counters <..._counter_collection.csv> --kernel fc_big_kernel
+      mean of every collected counter per dispatch of one kernel
 """
 import argparse
 import csv
-import hashlib
 import os
 import re
 import sys
 
-HERE = os.path.dirname(os.path.abspath(__file__))
-KERNEL_SOURCES = ("csrc/mt_device.h", "csrc/batcher.hip", "csrc/fc_stream.hip", "csrc/fc_big.hip", "csrc/conv.hip", "csrc/small.hip",
-                  "csrc/mt_internal.h")
-
-
-def kernel_source_sha256() -> str:
-    """Fingerprint of the device code: counters taken before a change to it no longer apply.
-    Comments and white space are left out, so that editing a comment does not void a measurement."""
-    h = hashlib.sha256()
-    for rel in KERNEL_SOURCES:
-        with open(os.path.join(HERE, rel), "r") as f:
-            text = f.read()
-        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)     # block comments
-        text = re.sub(r"//[^\n]*", " ", text)                  # line comments (the sources hold no string with //)
-        h.update(" ".join(text.split()).encode())
-    return h.hexdigest()
+from bench import kernel_source_sha256      # the fingerprint bench.py checks stored counter summaries against
 
 
 def short_name(name: str) -> str:
@@ -104,19 +91,6 @@ def traffic(fetch_csv: str, write_csv: str, kernel: str, copy_bytes: int) -> str
         "kernel_source_sha256: %s" % kernel_source_sha256(),
     ]
     return "\n".join(lines)
-
-
-def read_traffic(path: str):
-    """`traffic_bytes_per_launch` of a stored summary, or None when the device code has changed since."""
-    try:
-        text = open(path).read()
-    except OSError:
-        return None
-    sha = re.search(r"^kernel_source_sha256: ([0-9a-f]{64})$", text, re.M)
-    val = re.search(r"^traffic_bytes_per_launch: (\d+)$", text, re.M)
-    if not sha or not val or sha.group(1) != kernel_source_sha256():
-        return None
-    return float(val.group(1))
 
 
 def main(argv=None):

@@ -13,6 +13,12 @@ binding) and through the oracle, and compare to the stated bar:
     three small logits, reproduced on the CPU by taking the other bfloat16 neighbour of the
     one value that lies 3e-8 from a rounding boundary: tests/test_tolerance_model.py), so a
     tensor of one or two rows cannot be held to 1e-3; it is held to ROW_TOL instead;
+  * so that the looser bar cannot hide a systematic error in the tiles that serve small
+    tenants: all rows of tenants below MIN_ROWS_PER_TENSOR, taken together as one matrix,
+    must be <= 1e-3 once there are MIN_ROWS_PER_TENSOR of them, the median error of those
+    rows must be <= CLEAN_ROW (most rows see no flip at all), and, where the caller states
+    the share of rows that must be flip-free (`min_clean_frac`, for the mixes whose nets are
+    shallow enough that flips are rare), that share of all rows must be <= CLEAN_ROW;
   * labels bit-exact wherever the oracle's top-2 logit margin exceeds 1e-2; elsewhere the
     label must be one of the oracle's two best classes.
 """
@@ -27,6 +33,7 @@ REL_FRO_TOL = 1e-3
 ROW_TOL = 1e-2
 MIN_ROWS_PER_TENSOR = 16
 MARGIN = 1e-2
+CLEAN_ROW = 1e-5        # a row without a rounding flip agrees to ~1e-7 (bf16 mixes) or ~1e-6 (fp32)
 
 
 def make_context(w, max_requests=None, max_tenants=None):
@@ -54,7 +61,7 @@ def rel_fro(g, o):
     return d / n if n > 0 else d
 
 
-def compare(w, gpu, orc, rows=None, what=""):
+def compare(w, gpu, orc, rows=None, what="", min_clean_frac=None):
     """gpu/orc = (logits, probs, labels, n_classes) over the same rows (all, or `rows`)."""
     g_lg, g_pr, g_lb, g_nc = gpu
     o_lg, o_pr, o_lb, o_nc = orc
@@ -74,6 +81,17 @@ def compare(w, gpu, orc, rows=None, what=""):
             assert e <= tol, "%s tenant %d (%d rows) rel fro %.3e" % (what, t, int(sel.sum()), e)
     row_err = np.linalg.norm(g_lg - o_lg, axis=1) / np.maximum(np.linalg.norm(o_lg, axis=1), 1e-30)
     assert row_err.max() <= ROW_TOL, "%s: a row is off by %.3e" % (what, row_err.max())
+    # the rows of small tenants, pooled: the looser per-tensor bar above must not hide a systematic error
+    ids_u, cnt_u = np.unique(ids, return_counts=True)
+    small = np.isin(ids, ids_u[cnt_u < MIN_ROWS_PER_TENSOR])
+    if int(small.sum()) >= MIN_ROWS_PER_TENSOR:
+        for g, o in ((g_lg[small], o_lg[small]), (g_pr[small], o_pr[small])):
+            assert rel_fro(g, o) <= REL_FRO_TOL, "%s: the %d rows of small tenants together are off by %.3e" % (what, int(small.sum()), rel_fro(g, o))
+        assert np.median(row_err[small]) <= CLEAN_ROW, "%s: median row error of small tenants %.3e" % (what, np.median(row_err[small]))
+    clean = float(np.mean(row_err <= CLEAN_ROW))
+    if min_clean_frac is not None:
+        assert clean >= min_clean_frac, "%s: only %.3f of the rows are free of rounding flips" % (what, clean)
+    compare.last_clean_frac = clean
     assert rel_fro(g_lg, o_lg) <= REL_FRO_TOL and rel_fro(g_pr, o_pr) <= REL_FRO_TOL, what
     # labels
     srt = np.sort(o_lg + np.where(np.arange(C)[None, :] < o_nc[:, None], 0.0, -np.inf), axis=1)
@@ -96,9 +114,10 @@ def oracle_rows(w, rows=None, threads=16):
     return lg, pr, lb, nc
 
 
-def sample_rows(w, ctx_counts, n_random, bm=128, seed=0):
+def sample_rows(w, ctx_counts, n_random, bm=32, seed=0):
     """Rows to check one by one at full size: for every tenant the first and last rows of its
-    segment and the rows around every 128-row tile boundary, plus a random sample."""
+    segment and the rows around every 32-row boundary (every tile shape of the kernels is a
+    multiple of 32 rows: 32, 64, 128 and 256), plus a random sample."""
     rng = np.random.default_rng(seed)
     pick = set(rng.choice(w.n_requests, size=min(n_random, w.n_requests), replace=False).tolist())
     for t in np.unique(w.tenant_ids):

@@ -37,8 +37,9 @@ def zeros_for(specs, dtype=B.MT_BF16):
 
 
 def test_every_declared_symbol_is_exported():
-    header = open(os.path.join(ROOT, "include", "mt.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))) if h.endswith(".h"))
     names = set(re.findall(r"\b(mt_[a-z_]+)\s*\(", header))
+    assert {"mt_debug_copy", "mt_get_profile", "mt_model_footprint_get"} <= names      # both headers were read
     assert {"mt_create", "mt_destroy", "mt_register_model", "mt_submit", "mt_submit_batch", "mt_run"} <= names
     lib = B.load_library()
     for n in names:
@@ -265,3 +266,31 @@ def test_admission_is_max_min_fair_within_the_budget():
         ctx.admit(pending, 0.0)
     assert e.value.status == 1
     ctx.close()
+
+
+def test_footprint_of_a_model_is_what_registration_takes():
+    """mt_model_footprint_get needs no context: its arena bytes are what mt_register_model takes from
+    the arena, its width and class count the smallest limits a context must have."""
+    mlp = [fc(784, 1024, B.MT_ACT_RELU), fc(1024, 100, B.MT_ACT_GELU), fc(100, 10)]
+    cnn = [B.layer_spec(B.MT_CONV2D, B.MT_ACT_RELU, 3, 32, 16, 16, 1), B.layer_spec(B.MT_CONV2D, B.MT_ACT_RELU, 32, 64, 16, 16, 2),
+           B.layer_spec(B.MT_GAP, 0, 64, 64, 8, 8), fc(64, 7)]
+    for dtype in (B.MT_BF16, B.MT_F32):
+        for specs in (mlp, cnn):
+            f = B.model_footprint(specs, dtype)
+            c = host_ctx(dtype=dtype, arena=1 << 24, max_width=f["min_width"], max_classes=f["n_classes"])
+            c.register_model(3, specs, *zeros_for(specs, dtype))
+            assert c.stats()["arena_used"] == f["arena_bytes"]
+            assert c.tenant_account(3)["arena_bytes"] == f["arena_bytes"]
+            c.close()
+            if f["min_width"] > 64:
+                c = host_ctx(dtype=dtype, arena=1 << 24, max_width=f["min_width"] - 64, max_classes=f["n_classes"])
+                with pytest.raises(B.MtError):
+                    c.register_model(3, specs, *zeros_for(specs, dtype))
+                c.close()
+    assert B.model_footprint(mlp, B.MT_BF16)["in_len"] == 784 and B.model_footprint(cnn, B.MT_BF16)["in_len"] == 16 * 16 * 3
+    es = 2
+    assert B.model_footprint(mlp, B.MT_BF16)["arena_bytes"] == sum(
+        (n * k * es + 255) // 256 * 256 + (n * 4 + 255) // 256 * 256 for n, k in ((1024, 832), (128, 1024), (32, 128)))
+    with pytest.raises(B.MtError) as e:
+        B.model_footprint([fc(64, 10, B.MT_ACT_RELU)], B.MT_BF16)       # activation on the logits layer
+    assert e.value.status == 5

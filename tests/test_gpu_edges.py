@@ -304,3 +304,24 @@ def test_tiny_run_among_many_registered_models():
     assert counts.sum() == 40 and counts[7] == 14 and counts[93] == 13 and counts[149] == 13
     compare(w, gpu, oracle_rows(w), what="tiny run, many models")
     ctx.close()
+
+
+def test_served_requests_are_counted_per_tenant():
+    w = wl.c2(n_tenants=6, n_requests=300, dims=(100, 192, 136, 10))
+    ctx = mt.context_for(w.tenants, w.dtype, w.n_requests, max_tenants=8, run_slots=2)
+    mt.register_tenants(ctx, w.tenants)
+    d_x = torch_io.to_device(w.inputs, w.dtype)
+    ids = w.tenant_ids.copy()
+    ids[[3, 77]] = [7, -1]                                  # two rejected rows: served for nobody
+    only_some = np.where(ids == 4, 2, ids)                  # second mix: tenant 4 has no traffic
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for i, v in enumerate((ids, only_some, ids)):
+        mt.serve(ctx, torch.from_numpy(v.astype(np.int32)).cuda(), d_x, stream=streams[i % 2])
+    torch.cuda.synchronize()
+    for t in range(6):
+        acc = ctx.tenant_account(t)
+        expect = 2 * int((ids == t).sum()) + int((only_some == t).sum())
+        assert acc["requests"] == expect, t
+        assert acc["runs"] == (2 if t == 4 else 3), t
+    ctx.close()

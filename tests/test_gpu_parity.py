@@ -12,14 +12,14 @@ from gpu_common import compare, gpu_run, make_context, oracle_rows, sample_rows
 pytestmark = pytest.mark.gpu
 
 
-def run_and_compare(w, what, poison=True):
+def run_and_compare(w, what, poison=True, min_clean_frac=None):
     ctx = make_context(w)
     gpu = gpu_run(ctx, w, poison=poison)
     counts = ctx.last_counts()
     exp = np.bincount(w.tenant_ids, minlength=len(counts))
     assert np.array_equal(counts, exp), what
-    worst = compare(w, gpu, oracle_rows(w), what=what)
-    print("%s: worst per-tensor rel fro %.2e" % (what, worst), flush=True)
+    worst = compare(w, gpu, oracle_rows(w), what=what, min_clean_frac=min_clean_frac)
+    print("%s: worst per-tensor rel fro %.2e, flip-free rows %.3f" % (what, worst, compare.last_clean_frac), flush=True)
     ctx.close()
 
 
@@ -218,7 +218,7 @@ def test_pooling_done_by_the_last_convolution(monkeypatch):
 
 # ---- full-size configurations ---------------------------------------------------------------
 def test_c2_full():
-    run_and_compare(wl.c2(), "c2")
+    run_and_compare(wl.c2(), "c2", min_clean_frac=0.9)
 
 
 def test_c2_full_three_runs_in_flight():
@@ -243,39 +243,41 @@ def test_c2_full_three_runs_in_flight():
     ctx.close()
 
 
-def test_c3_full_sampled():
+def test_c3_full_all_rows():
     w = wl.c3()
     ctx = make_context(w)
     gpu = gpu_run(ctx, w, poison=True)
     counts = ctx.last_counts()
     assert np.array_equal(counts, np.bincount(w.tenant_ids, minlength=len(counts)))
-    rows = sample_rows(w, counts, n_random=2048)
-    worst = compare(w, tuple(a[rows] for a in gpu), oracle_rows(w, rows), rows=rows, what="c3")
-    print("c3: %d rows checked, worst rel fro %.2e" % (len(rows), worst), flush=True)
+    # most of this mix's tenants have fewer than 16 rows: the pooled small-tenant checks of compare() carry it
+    assert int(np.sum((counts > 0) & (counts < 16))) >= 100
+    worst = compare(w, gpu, oracle_rows(w), what="c3", min_clean_frac=0.85)
+    print("c3: all %d rows checked, worst per-tensor rel fro %.2e, flip-free rows %.3f" % (w.n_requests, worst, compare.last_clean_frac), flush=True)
     ctx.close()
 
 
-def test_c4_full_sampled():
+def test_c4_full_all_rows():
     w = wl.c4()
     ctx = make_context(w)
     gpu = gpu_run(ctx, w, poison=True)
-    rows = sample_rows(w, None, n_random=256)
-    worst = compare(w, tuple(a[rows] for a in gpu), oracle_rows(w, rows), rows=rows, what="c4")
-    print("c4: %d rows checked, worst rel fro %.2e" % (len(rows), worst), flush=True)
+    worst = compare(w, gpu, oracle_rows(w), what="c4", min_clean_frac=0.85)
+    print("c4: all %d rows checked, worst per-tensor rel fro %.2e, flip-free rows %.3f" % (w.n_requests, worst, compare.last_clean_frac), flush=True)
     ctx.close()
 
 
-def test_c5_full_sampled():
+def test_c5_full_quarter_of_the_rows_and_every_tile_edge():
     w = wl.c5()
     ctx = make_context(w)
     gpu = gpu_run(ctx, w, poison=True)
     counts = ctx.last_counts()
     assert np.array_equal(counts, np.bincount(w.tenant_ids, minlength=len(counts)))
-    # every tenant's segment edges and every 128-row tile boundary, plus a random sample;
-    # the oracle needs ~54 M fp64 MACs per row, so the sample is bounded
-    rows = sample_rows(w, counts, n_random=512)
+    # every tenant's segment edges and the rows around every 32-row boundary (all tile edges of the
+    # 256-row tiles and of the streaming tiles that serve the remainders), plus a random quarter of the
+    # batch: ~10 thousand rows of ~54 M fp64 multiply-accumulates each
+    rows = sample_rows(w, counts, n_random=w.n_requests // 4)
+    assert len(rows) >= w.n_requests // 4
     worst = compare(w, tuple(a[rows] for a in gpu), oracle_rows(w, rows), rows=rows, what="c5")
-    print("c5: %d rows checked, worst rel fro %.2e" % (len(rows), worst), flush=True)
+    print("c5: %d rows checked, worst rel fro %.2e, flip-free rows %.3f" % (len(rows), worst, compare.last_clean_frac), flush=True)
     # properties that hold at any size, on all rows
     lg, pr, lb, nc = gpu
     assert np.all(nc == 1000) and np.all(np.isfinite(lg))

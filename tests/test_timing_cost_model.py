@@ -1,7 +1,12 @@
-"""Accounting and cost prediction on the GPU (paper section 3.2: the cost of inference is known a
+"""Tests that assert on measured time; the file name sorts them behind every parity test, so that a
+slow machine cannot keep those from running.
+
+Cost prediction on the GPU (paper section 3.2: the cost of inference is known a
 priori; section 1.3: users should pay for the work done).  The per-tenant counters the batcher
 keeps must equal the submitted rows exactly; the run-time estimate, computed from the registered
 descriptors before anything is enqueued, must be close to the measured device time of the run."""
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -24,27 +29,6 @@ def other_mixes():
     return {"c2-uniform": lambda: uniform, "c3-other-seed": lambda: wl.c3(seed=11), "c3-half-batch": lambda: wl.c3(n_requests=8192),
             "c4-half-batch": lambda: wl.c4(n_requests=1024), "c5-half-batch": lambda: wl.c5(n_requests=16384),
             "c5-six-tenants": lambda: wl.c5(n_tenants=6, n_requests=24576)}
-
-
-def test_served_requests_are_counted_per_tenant():
-    w = wl.c2(n_tenants=6, n_requests=300, dims=(100, 192, 136, 10))
-    ctx = mt.context_for(w.tenants, w.dtype, w.n_requests, max_tenants=8, run_slots=2)
-    mt.register_tenants(ctx, w.tenants)
-    d_x = torch_io.to_device(w.inputs, w.dtype)
-    ids = w.tenant_ids.copy()
-    ids[[3, 77]] = [7, -1]                                  # two rejected rows: served for nobody
-    only_some = np.where(ids == 4, 2, ids)                  # second mix: tenant 4 has no traffic
-    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
-    torch.cuda.synchronize()
-    for i, v in enumerate((ids, only_some, ids)):
-        mt.serve(ctx, torch.from_numpy(v.astype(np.int32)).cuda(), d_x, stream=streams[i % 2])
-    torch.cuda.synchronize()
-    for t in range(6):
-        acc = ctx.tenant_account(t)
-        expect = 2 * int((ids == t).sum()) + int((only_some == t).sum())
-        assert acc["requests"] == expect, t
-        assert acc["runs"] == (2 if t == 4 else 3), t
-    ctx.close()
 
 
 @pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5", "c2-uniform", "c3-other-seed", "c3-half-batch", "c4-half-batch",
@@ -102,4 +86,51 @@ def test_admitted_runs_keep_the_latency_budget():
         print("budget %.2f ms: level %d, %d of %d requests admitted, predicted %.3f ms, measured %.3f ms" % (
             budget, admitted.max(), admitted.sum(), w.n_requests, est["device_ms"], measured), flush=True)
         assert measured <= budget * (1 + REL_TOL_OTHER)      # partial mixes: the estimate reads 10-12 % low on these
+    ctx.close()
+
+
+def test_upload_time_follows_the_footprint():
+    # section 3.3: transfer latency is predictable because a model's footprint is fixed
+    w = wl.c5(n_tenants=3, n_requests=64, dims=(4096, 4096, 4096, 1000))        # ~75 MB per model
+    acc_bytes = None
+    ctx = mt.context_for(w.tenants, w.dtype, w.n_requests, arena_bytes=int(1.2 * 76e6), cache=True)
+    mt.register_tenants(ctx, w.tenants)
+    s = torch.cuda.current_stream().cuda_stream
+    times = []
+    for t in (0, 1, 2, 0, 1, 2):
+        assert ctx.tenant_account(t)["resident"] == 0
+        acc_bytes = ctx.tenant_account(t)["arena_bytes"]
+        counts = [0, 0, 0]; counts[t] = 10
+        predicted = ctx.estimate_run(counts)["upload_ms"]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ctx.prefetch([t], s)
+        torch.cuda.synchronize()
+        times.append((time.perf_counter() - t0) * 1e3)
+    measured = float(np.median(times))
+    print("upload of %.1f MB: measured %.3f ms (%.1f GB/s), predicted %.3f ms" % (acc_bytes / 1e6, measured, acc_bytes / measured / 1e6, predicted), flush=True)
+    assert abs(predicted / measured - 1.0) <= 0.35
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+def test_run_time_is_predictable(name):
+    """Paper section 3.2: inference time is predictable, the 99th percentile within 15 % of the mean.
+    Device time of a run between two events, 100 runs of the same batch back to back."""
+    w = wl.CONFIGS[name]()
+    ctx = mt.context_for(w.tenants, w.dtype, w.n_requests)
+    mt.register_tenants(ctx, w.tenants)
+    d_ids, d_x = torch.from_numpy(w.tenant_ids).cuda(), torch_io.to_device(w.inputs, w.dtype)
+    out = torch_io.alloc_outputs(w.n_requests, ctx.cfg.max_classes)
+    for _ in range(10):
+        mt.serve(ctx, d_ids, d_x, out=out)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(100)]
+    for e0, e1 in ev:
+        e0.record(); mt.serve(ctx, d_ids, d_x, out=out); e1.record()
+    torch.cuda.synchronize()
+    ms = np.array([e0.elapsed_time(e1) for e0, e1 in ev])
+    ratio = float(np.percentile(ms, 99) / ms.mean())
+    print("%s: mean %.4f ms, p99 %.4f ms, p99/mean %.3f, max/mean %.3f" % (name, ms.mean(), np.percentile(ms, 99), ratio, ms.max() / ms.mean()), flush=True)
+    assert ratio <= 1.15
     ctx.close()
