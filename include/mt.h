@@ -197,6 +197,22 @@ typedef struct {
 } mt_model_footprint;
 mt_status mt_model_footprint_get(const mt_layer_spec* specs, uint32_t n_layers, uint32_t dtype, mt_model_footprint* out);
 
+/* mt_run for callers that may not allocate device memory around the call and want a run that
+ * touches no allocation of the context besides its weights and tables: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  It does what mt_run does,
+ * with the same kernels, but the run's scratch (batch descriptors, both activation buffers,
+ * logits) lives in one array of MT_STATIC_SCRATCH_BYTES that the library holds in device
+ * memory for the life of the process (one per GPU).  A run whose scratch does not fit (the
+ * need grows with the pending rows, the context's max_width, max_classes and max_tenants) is
+ * refused with MT_EINVAL and nothing is enqueued; the pending list is kept, so mt_run can
+ * serve it.  The call allocates nothing, on the device or through any allocating routine.
+ * Every call on a GPU shares that GPU's array: the descriptors a run starts from are cleared
+ * on the stream first, and runs enqueued through this call on different streams (or from
+ * different contexts) that overlap on one GPU race; runs of one context are ordered by the
+ * library (a later one waits for the earlier one on the device).  Other errors as mt_run. */
+#define MT_STATIC_SCRATCH_BYTES (16u << 20)
+mt_status mt_run_static(mt_ctx* ctx, void* hip_stream, const mt_outputs* out, uint32_t* n_rows);
+
 /* The per-tenant batch sizes of the last mt_run (paper section 3.2: the cost of a run varies
  * with the batch size of every model in it, which the device-side segmentation computes):
  * copies the counts to HOST counts[max_tenants] after synchronising the stream the run was

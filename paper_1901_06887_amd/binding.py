@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmt.so")
 
 MT_OK = 0
+MT_STATIC_SCRATCH_BYTES = 16 << 20
 STATUS_NAMES = {0: "MT_OK", 1: "MT_EINVAL", 2: "MT_ENOMEM", 3: "MT_ENOTFOUND", 4: "MT_EEXIST",
                 5: "MT_EUNSUPPORTED", 6: "MT_EFULL", 7: "MT_ESTATE", 8: "MT_EDEVICE"}
 MT_FC, MT_CONV2D, MT_GAP = 0, 1, 2
@@ -100,6 +101,7 @@ def load_library() -> ctypes.CDLL:
     L.mt_submit.argtypes = [vp, u32, vp, u32, ctypes.POINTER(u32)]
     L.mt_submit_batch.argtypes = [vp, vp, vp, u32, u32, ctypes.POINTER(u32)]
     L.mt_run.argtypes = [vp, vp, ctypes.POINTER(mt_outputs), ctypes.POINTER(u32)]
+    L.mt_run_static.argtypes = [vp, vp, ctypes.POINTER(mt_outputs), ctypes.POINTER(u32)]
     L.mt_last_counts.argtypes = [vp, ctypes.POINTER(u32)]
     L.mt_get_stats.argtypes = [vp, ctypes.POINTER(mt_stats)]
     L.mt_tenant_account_get.argtypes = [vp, u32, ctypes.POINTER(mt_tenant_account)]
@@ -119,7 +121,7 @@ def load_library() -> ctypes.CDLL:
     L.mt_last_error.restype = ctypes.c_char_p
     L.mt_version.restype = ctypes.c_char_p
     for name in ("mt_create", "mt_destroy", "mt_register_model", "mt_unregister_model", "mt_submit",
-                 "mt_submit_batch", "mt_run", "mt_last_counts", "mt_get_stats", "mt_tenant_account_get", "mt_estimate_run", "mt_prefetch", "mt_cache_stats_get", "mt_admit", "mt_debug_poison", "mt_debug_copy",
+                 "mt_submit_batch", "mt_run", "mt_run_static", "mt_last_counts", "mt_get_stats", "mt_tenant_account_get", "mt_estimate_run", "mt_prefetch", "mt_cache_stats_get", "mt_admit", "mt_debug_poison", "mt_debug_copy",
                  "mt_set_profiling", "mt_get_profile", "mt_model_footprint_get", "mt_debug_mfma_rate"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -209,6 +211,15 @@ class Context:
                          capacity, row_stride)
         n = ctypes.c_uint32(0)
         self._check(self._lib.mt_run(self._h, ctypes.c_void_p(stream_ptr or None), ctypes.byref(out), ctypes.byref(n)))
+        return n.value
+
+    def run_static(self, stream_ptr: int, labels_ptr: int, probs_ptr: int, logits_ptr: int, n_classes_ptr: int,
+                   capacity: int, row_stride: int) -> int:
+        """mt_run_static: the same run with its scratch in the library's static device array (allocates nothing)."""
+        out = mt_outputs(labels_ptr or None, probs_ptr or None, logits_ptr or None, n_classes_ptr or None,
+                         capacity, row_stride)
+        n = ctypes.c_uint32(0)
+        self._check(self._lib.mt_run_static(self._h, ctypes.c_void_p(stream_ptr or None), ctypes.byref(out), ctypes.byref(n)))
         return n.value
 
     def last_counts(self) -> np.ndarray:

@@ -15,6 +15,13 @@
 
 using namespace mt;
 
+// Scratch of mt_run_static: batch descriptors, both activation buffers and logits of one run.  The
+// array lives in device memory of every GPU the library runs on until the process ends.  On the
+// host its name is only a handle: the device address is looked up once per context
+// (hipGetSymbolAddress in mt_create, with the context's device current) and kept in the context.
+static __device__ __align__(256) unsigned char scratch[MT_STATIC_SCRATCH_BYTES];
+
+
 namespace {
 
 constexpr uint32_t kMaxTenants = 2048;
@@ -112,6 +119,8 @@ struct mt_ctx {
     // device state.  The per-run pointers below (d_row_tenant .. d_logits) are those of the run
     // slot bound last (bind_slot): the slot of the run being enqueued, then of the last run.
     std::vector<RunSlot> slots;
+    RunSlot static_slot;               // the slot of mt_run_static: its buffers are carved out of static_scratch per run
+    uint8_t* static_scratch = nullptr; // device address of `scratch` on this context's GPU
     uint8_t* d_arena = nullptr;
     TenantDev* d_tenants = nullptr;
     LayerDev* d_layers = nullptr;
@@ -650,6 +659,8 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
         CREATE_TRY(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
     }
     bind_slot(c, c->slots[0]);
+    CREATE_TRY(hipGetSymbolAddress((void**)&c->static_scratch, HIP_SYMBOL(scratch)));      // this device's copy of the array
+    CREATE_TRY(hipEventCreateWithFlags(&c->static_slot.done, hipEventDisableTiming));
     if (c->cache) {
         CREATE_TRY(hipEventCreateWithFlags(&c->cache_event, hipEventDisableTiming));
     }
@@ -676,6 +687,7 @@ mt_status mt_destroy(mt_ctx* c)
             for (void* p : rb) if (p) (void)hipFree(p);
             if (r.done) (void)hipEventDestroy(r.done);
         }
+        if (c->static_slot.done) (void)hipEventDestroy(c->static_slot.done);
         for (uint32_t i = 0; i < kSegSlots; ++i) {
             if (c->h_segs[i]) (void)hipHostFree(c->h_segs[i]);
             if (c->seg_event[i]) (void)hipEventDestroy(c->seg_event[i]);
@@ -803,6 +815,7 @@ mt_status mt_prefetch(mt_ctx* c, const uint32_t* tenants, uint32_t n, void* hip_
         // runs in flight keep their weights and tables: the changes below queue up behind them
         for (RunSlot& r : c->slots)
             if (r.used) HIP_TRY(c, hipStreamWaitEvent(s, r.done, 0));
+        if (c->static_slot.used) HIP_TRY(c, hipStreamWaitEvent(s, c->static_slot.done, 0));
         if (c->cache_pending && c->cache_stream != s) HIP_TRY(c, hipStreamWaitEvent(s, c->cache_event, 0));
     }
     mt_status result = MT_OK;
@@ -901,7 +914,60 @@ mt_status mt_submit_batch(mt_ctx* c, const int32_t* tenant_ids, const void* inpu
     return push_segment(c, s, first_index);
 }
 
+namespace {
+
+__global__ void fill_zero_kernel(uint32_t* p, uint32_t n)
+{
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0;
+}
+
+// Packed rows a run of R rows can occupy: every tenant with traffic pads its segment to a multiple of 32.
+uint32_t packed_rows_bound(const mt_ctx* c, uint32_t R)
+{
+    return (uint32_t)std::min<uint64_t>(c->P_cap, (uint64_t)round_up(R, kBrickRows) + (uint64_t)kBrickRows * std::min(R, c->n_registered));
+}
+
+// Carve the buffers of a run of R rows out of the static scratch array.  Returns the bytes needed;
+// the slot's pointers are set only when they fit.  The batch descriptors come first, in one block
+// that is cleared before the run (descr_words 32-bit words from rs->d_M).
+uint64_t carve_static_slot(const mt_ctx* c, uint32_t R, RunSlot* rs, uint32_t* descr_words)
+{
+    const uint64_t T = c->cfg.max_tenants, P = packed_rows_bound(c, R);
+    uint64_t at = 0;
+    auto take = [&](uint64_t bytes) { const uint64_t o = at; at += round_up64(bytes, 256); return o; };
+    const uint64_t o_M = take(T * 4), o_off = take((T + 1) * 4), o_tb = take((kListKinds * MT_MAX_LAYERS * (T + 1) + 1) * 4);
+    const uint64_t descr_end = at;
+    const uint64_t o_rt = take((uint64_t)R * 4), o_rr = take((uint64_t)R * 4), o_h = take((uint64_t)kHistEntries * 4);
+    const uint64_t o_src = take((uint64_t)R * sizeof(void*)), o_pos = take((uint64_t)R * 4), o_perm = take(P * 4);
+    const uint64_t o_a0 = take(P * c->S * c->elem_size), o_a1 = take(P * c->S * c->elem_size), o_lg = take(P * c->C_pad * 4);
+    if (at <= MT_STATIC_SCRATCH_BYTES) {
+        uint8_t* b = c->static_scratch;
+        rs->d_M = (uint32_t*)(b + o_M); rs->d_off = (uint32_t*)(b + o_off); rs->d_tile_base = (uint32_t*)(b + o_tb);
+        rs->d_row_tenant = (int32_t*)(b + o_rt); rs->d_row_rank = (uint32_t*)(b + o_rr); rs->d_hist_g = (uint32_t*)(b + o_h);
+        rs->d_row_src = (const void**)(b + o_src); rs->d_pos_of = (int32_t*)(b + o_pos); rs->d_perm = (int32_t*)(b + o_perm);
+        rs->d_act[0] = b + o_a0; rs->d_act[1] = b + o_a1; rs->d_logits = (float*)(b + o_lg);
+        *descr_words = (uint32_t)(descr_end / 4);
+    }
+    return at;
+}
+
+mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n_rows, bool use_static);
+
+}  // namespace
+
 mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n_rows)
+{
+    return run_impl(c, hip_stream, out, n_rows, false);
+}
+
+mt_status mt_run_static(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n_rows)
+{
+    return run_impl(c, hip_stream, out, n_rows, true);
+}
+
+namespace {
+
+mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n_rows, bool use_static)
 {
     if (!c) return MT_EINVAL;
     if (n_rows) *n_rows = 0;
@@ -931,7 +997,16 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     // (the slot this stream used last, so that runs on one stream keep their buffers and never wait
     // across streams; else a slot nobody has used; else the one used longest ago)
     RunSlot* pick = nullptr;
-    for (RunSlot& r : c->slots) if (r.used && r.stream == s) { pick = &r; break; }
+    uint32_t static_descr_words = 0;
+    if (use_static) {
+        // the run's buffers come out of the static array, sized for this run; nothing is allocated
+        const uint64_t need = carve_static_slot(c, R, &c->static_slot, &static_descr_words);
+        if (need > MT_STATIC_SCRATCH_BYTES)
+            return fail(c, MT_EINVAL, "a run of %u rows needs %llu bytes of scratch in this context, the static array holds %u",
+                        R, (unsigned long long)need, (unsigned)MT_STATIC_SCRATCH_BYTES);
+        pick = &c->static_slot;
+    }
+    if (!pick) for (RunSlot& r : c->slots) if (r.used && r.stream == s) { pick = &r; break; }
     if (!pick) for (RunSlot& r : c->slots) if (!r.used) { pick = &r; break; }
     if (!pick) { pick = &c->slots[0]; for (RunSlot& r : c->slots) if (r.last_run < pick->last_run) pick = &r; }
     RunSlot& rs = *pick;
@@ -997,6 +1072,12 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
         HIP_TRY(c, call); ++launches;                                                       \
         if (c->profiling) { HIP_TRY(c, hipEventRecord(c->prof_events[2 * (slot) + 1], s)); c->prof_used[slot] = true; c->prof_last = (slot); } \
     } while (0)
+    if (use_static) {
+        // the array keeps what the last run on this GPU left: the descriptors start from zero (a fill
+        // kernel, not a memset node, so that the sequence can be captured into a graph)
+        hipLaunchKernelGGL(fill_zero_kernel, dim3((static_descr_words + 255) / 256), dim3(256), 0, s, rs.d_M, static_descr_words);
+        HIP_TRY(c, hipGetLastError()); ++launches;
+    }
     TIMED(kProfBatcher, launch_batcher(b, s));
     if (b.n_rank_groups) launches += 2;
 
@@ -1011,7 +1092,7 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     for (const Segment& sg : c->pending)
         if (((uintptr_t)sg.src & 15) || ((uint64_t)sg.row_stride * c->elem_size) % 16) fuse_gather = false;
     // packed rows: every tenant with traffic pads its segment to a multiple of 32
-    const uint32_t P = std::min<uint64_t>(c->P_cap, (uint64_t)round_up(R, kBrickRows) + (uint64_t)kBrickRows * std::min(R, c->n_registered));
+    const uint32_t P = packed_rows_bound(c, R);
     {
         GatherArgs g{};
         g.row_src = c->d_row_src; g.P = P; g.tenants = c->d_tenants; g.layers = c->d_layers; g.row_tenant = c->d_row_tenant;
@@ -1086,6 +1167,8 @@ mt_status mt_run(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t* n
     if (n_rows && st == MT_OK) *n_rows = R;
     return st;
 }
+
+}  // namespace
 
 mt_status mt_last_counts(mt_ctx* c, uint32_t* counts)
 {

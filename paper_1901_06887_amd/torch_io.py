@@ -59,14 +59,15 @@ def alloc_outputs(n: int, row_stride: int, device="cuda:0") -> Served:
 
 
 def serve(ctx: B.Context, tenant_ids: torch.Tensor, inputs: torch.Tensor, out: Optional[Served] = None,
-          stream: Optional[torch.cuda.Stream] = None) -> Served:
-    """mt_submit_batch + mt_run on the given (or current) stream; returns without synchronising."""
+          stream: Optional[torch.cuda.Stream] = None, static: bool = False) -> Served:
+    """mt_submit_batch + mt_run (mt_run_static with `static`) on the given (or current) stream; returns
+    without synchronising."""
     n = int(tenant_ids.numel())
     assert tenant_ids.dtype == torch.int32 and tenant_ids.is_cuda and inputs.is_cuda and inputs.is_contiguous()
     if out is None:
         out = alloc_outputs(n, ctx.cfg.max_classes, inputs.device)
     s = stream if stream is not None else torch.cuda.current_stream(inputs.device)
     ctx.submit_batch(tenant_ids.data_ptr(), inputs.data_ptr(), n, inputs.shape[1])
-    ctx.run(s.cuda_stream, out.labels.data_ptr(), out.probs.data_ptr(), out.logits.data_ptr(),
+    (ctx.run_static if static else ctx.run)(s.cuda_stream, out.labels.data_ptr(), out.probs.data_ptr(), out.logits.data_ptr(),
             out.n_classes.data_ptr(), out.labels.numel(), out.probs.shape[1])
     return out
