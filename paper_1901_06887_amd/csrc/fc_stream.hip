@@ -287,6 +287,81 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
         }
         return;
     }
+    if (L.is_last && a.fuse_head && L.N <= a.fuse_head_max && L.N_pad <= split * kBrickRows) {
+        // 33 .. 128 classes, all of them inside this tile (one column group): the waves put their
+        // 32x32 blocks of logits side by side in LDS as [row][class], then eight threads share a
+        // row: softmax, argmax (lowest index on ties) and the outputs in submission order.
+        constexpr uint32_t LRS = kTileCols + 4;                 // floats per row of the logits tile (16-byte aligned rows)
+        static_assert(kBrickRows * LRS * 4 <= kFcLdsBytes, "the logits tile of one row block must fit the kernel's LDS");
+        float* lt = (float*)smem;
+        const uint32_t C = L.N, tid = threadIdx.x, row = tid >> 3, part = tid & 7;
+        const bool vec = a.out_vec_ok;
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            __syncthreads();
+            if (writer && (uint32_t)r < nrb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) lt[(8 * (v >> 2) + 4 * lh + (v & 3)) * LRS + n] = acc[r][v] + bv;
+            }
+            __syncthreads();
+            const uint32_t m = tl.m0 + r * kBrickRows + row;
+            if ((uint32_t)r < nrb && m < Mt) {                   // the eight threads of a row are neighbours in one wave
+                f32x4 z[4];
+                float mx = -INFINITY; int32_t best = 0x7fffffff;
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) {
+                    z[q] = *(const f32x4*)(lt + row * LRS + part * 16 + q * 4);
+#pragma unroll
+                    for (uint32_t i = 0; i < 4; ++i) {
+                        const uint32_t c = part * 16 + q * 4 + i;
+                        if (c >= C) z[q][i] = -INFINITY;       // also hides what idle waves did not write
+                        if (z[q][i] > mx) { mx = z[q][i]; best = (int32_t)c; }      // increasing index: the first hit is the lowest
+                    }
+                }
+#pragma unroll
+                for (int d = 4; d >= 1; d >>= 1) {
+                    const float omx = __shfl_xor(mx, d);
+                    const int32_t ob = __shfl_xor(best, d);
+                    if (omx > mx || (omx == mx && ob < best)) { mx = omx; best = ob; }
+                }
+                f32x4 e[4];
+                float sum = 0.0f;
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q)
+#pragma unroll
+                    for (uint32_t i = 0; i < 4; ++i) { e[q][i] = __expf(z[q][i] - mx); sum += e[q][i]; }   // exp(-inf) = 0 past the last class
+#pragma unroll
+                for (int d = 4; d >= 1; d >>= 1) sum += __shfl_xor(sum, d);
+                const float inv = 1.0f / sum;
+                const uint32_t sub = (uint32_t)a.perm[seg0 + m];
+                if (part == 0) {
+                    a.out.labels[sub] = best;
+                    if (a.out.n_classes) a.out.n_classes[sub] = (int32_t)C;
+                }
+                float* pr = a.out.probs ? a.out.probs + (size_t)sub * a.out.row_stride : nullptr;
+                float* lg = a.out.logits ? a.out.logits + (size_t)sub * a.out.row_stride : nullptr;
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) {
+                    const uint32_t c0 = part * 16 + q * 4;
+                    f32x4 pv, lv;
+#pragma unroll
+                    for (uint32_t i = 0; i < 4; ++i) { const bool in = c0 + i < C; pv[i] = in ? e[q][i] * inv : 0.0f; lv[i] = in ? z[q][i] : 0.0f; }
+                    if (vec) {
+                        if (c0 < a.out.row_stride) { if (pr) *(f32x4*)(pr + c0) = pv; if (lg) *(f32x4*)(lg + c0) = lv; }
+                    } else {
+#pragma unroll
+                        for (uint32_t i = 0; i < 4; ++i)
+                            if (c0 + i < a.out.row_stride) { if (pr) pr[c0 + i] = pv[i]; if (lg) lg[c0 + i] = lv[i]; }
+                    }
+                }
+                for (uint32_t c = kTileCols + part; c < a.out.row_stride; c += 8) {      // wider output rows: zeros past the tile
+                    if (pr) pr[c] = 0.0f;
+                    if (lg) lg[c] = 0.0f;
+                }
+            }
+        }
+        return;
+    }
     if (L.is_last) {
         if (!writer || n >= L.N) return;
 #pragma unroll

@@ -458,6 +458,15 @@ bool run_split_k(const mt_ctx* c, uint64_t R)
     return most > 0 && most <= kSplitKMaxTiles;
 }
 
+// Most classes a last layer may have for its FC tiles to finish their rows themselves (softmax,
+// argmax, outputs) in a run: one column block (32), or a whole tile of four (128) where the run's
+// tiles are not single column blocks; 0: the head kernel does every row.
+uint32_t fused_head_classes(const mt_ctx* c, bool split_k)
+{
+    if (c->no_fused_head) return 0;
+    return split_k ? (uint32_t)kBrickRows : (uint32_t)kTileCols;
+}
+
 // ---- validation of a layer chain; fills dev layouts (without arena offsets) -------------
 mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, HostTenant* out)
 {
@@ -1060,8 +1069,12 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
     b.out = outp;
     // A last layer of at most 32 classes is one column block: its FC tiles finish their rows
     // themselves.
-    const bool fuse_head = !c->no_fused_head && c->min_reg_classes <= kBrickRows;
-    const uint32_t head_min_classes = fuse_head ? kBrickRows + 1 : 0;
+    // ... and one of at most 128 classes is one tile of four column blocks, unless this run's tiles
+    // are single column blocks (the K-split shape of small runs).
+    const uint32_t fuse_head_max = fused_head_classes(c, split_k);
+    const bool fuse_head = fuse_head_max > 0 && c->min_reg_classes <= fuse_head_max;
+    const uint32_t head_min_classes = fuse_head ? fuse_head_max + 1 : 0;
+    const bool out_vec_ok = out->row_stride % 4 == 0 && ((uintptr_t)out->probs & 15) == 0 && ((uintptr_t)out->logits & 15) == 0;
     if (c->profiling) for (uint32_t i = 0; i < kProfSlots; ++i) c->prof_used[i] = false;
     // From here on a failure may leave part of the run enqueued: the launches sit in a body of their
     // own, and the bookkeeping behind it (events, slot, pending list) is closed whatever it returns.
@@ -1116,7 +1129,7 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
             ga.tile_base = c->d_tile_base + ((size_t)kind * MT_MAX_LAYERS + l) * (T + 1);
             ga.T = T; ga.layer = l; ga.fc_split_k = split_k; ga.big_layers = b.big_layers;
             ga.gather = (kind == 0 && l == 0 && fuse_gather); ga.perm = c->d_perm; ga.row_src = c->d_row_src;
-            ga.fuse_head = fuse_head; ga.out = outp; ga.pool = kind == 1 && c->pool_fused[l];
+            ga.fuse_head = fuse_head; ga.fuse_head_max = fuse_head_max; ga.out_vec_ok = out_vec_ok; ga.out = outp; ga.pool = kind == 1 && c->pool_fused[l];
             ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad; ga.zeros = c->d_zeros;
             if (grid > 0x7ffffff0u)          // cannot happen within the limits mt_create accepts; never launch fewer workgroups than tiles
@@ -1136,11 +1149,11 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
         }
     }
 
-    if (!fuse_head || c->max_reg_classes > kBrickRows) {
+    if (!fuse_head || c->max_reg_classes > fuse_head_max) {
         HeadArgs h{};
         h.R = R; h.tenants = c->d_tenants; h.row_tenant = c->d_row_tenant; h.pos_of = c->d_pos_of; h.logits = c->d_logits;
         h.C_pad = c->C_pad; h.out = outp; h.min_classes = head_min_classes;
-        h.vec_ok = out->row_stride % 4 == 0 && ((uintptr_t)out->probs & 15) == 0 && ((uintptr_t)out->logits & 15) == 0;
+        h.vec_ok = out_vec_ok;
         TIMED(kProfHead, launch_head(h, s));
     }
 #undef TIMED
@@ -1272,8 +1285,9 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
     const bool big_enabled = R >= (uint64_t)kBigMinBatch && run_flops >= kRidgeFlopsPerByte * (double)c->arena_used;
     const bool big_possible = big_enabled && c->max_nt[2][0] > 0 && tile_bound(c, 2, 0, R) >= c->big_min_tiles;
     const bool fuse_gather = c->any_fc_first && c->fc_first_chunked && !c->no_fused_gather && !big_possible;
-    const bool fuse_head = !c->no_fused_head && c->min_reg_classes <= (uint32_t)kBrickRows;
     const bool split_k = run_split_k(c, R);
+    const uint32_t fuse_head_max = fused_head_classes(c, split_k);
+    const bool fuse_head = fuse_head_max > 0 && c->min_reg_classes <= fuse_head_max;
     uint32_t Tp = 64;
     while (Tp < T) Tp <<= 1;
     const uint64_t groups_r = (R + kRankRows - 1) / kRankRows;
@@ -1353,7 +1367,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
         }
         if (c->has_gap[l]) launch(kUsSmallFixed + gap_mb / kCopyMbPerUs);
     }
-    if (!fuse_head || c->max_reg_classes > (uint32_t)kBrickRows)
+    if (!fuse_head || c->max_reg_classes > fuse_head_max)
         launch(kUsSmallFixed + std::max(3.0 * R * c->C_pad * 4.0 / MB / kHeadMbPerUs, kUsHeadPerRow * R));
     out->launches = launches;
     out->device_ms = us * 1e-3;

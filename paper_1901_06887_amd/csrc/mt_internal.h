@@ -157,8 +157,10 @@ struct GemmArgs {
     // FC layer 0 can read the submitted rows itself (16-byte aligned rows whose length is a
     // whole number of 16-byte chunks), which saves the staging pass:
     uint32_t gather; const int32_t* perm; const void* const* row_src;
-    // a last layer of at most 32 classes finishes its rows itself (softmax, argmax, outputs):
-    uint32_t fuse_head; OutPtrs out;
+    // a last layer whose classes all lie inside one tile finishes its rows itself (softmax, argmax,
+    // outputs): at most fuse_head_max classes (32: one column block; 128: a whole tile of four, not
+    // in runs whose tiles are single column blocks); out_vec_ok: output rows take 16-byte stores
+    uint32_t fuse_head; uint32_t fuse_head_max; uint32_t out_vec_ok; OutPtrs out;
     const LayerDev* layers; const uint32_t* off; const uint32_t* M;
     const void* act_in; void* act_out; const uint8_t* arena;
     float* logits; uint32_t S; uint32_t C_pad;

@@ -325,3 +325,35 @@ def test_served_requests_are_counted_per_tenant():
         assert acc["requests"] == expect, t
         assert acc["runs"] == (2 if t == 4 else 3), t
     ctx.close()
+
+
+def test_heads_of_33_to_128_classes_are_finished_by_the_fc_tile(monkeypatch):
+    """Class counts around every boundary of the fused head (one column block: 32 | 33; one tile of
+    four: 64 | 65, 96 | 97, 128 | 129), several row tiles per tenant and ragged ones: the tile's own
+    softmax/argmax must give the oracle's answers and exactly the logits of the separate head kernel.
+    With at most 128 classes everywhere no head kernel runs at all."""
+    monkeypatch.setenv("MT_NO_AUTO_SPLIT_K", "1")                 # the ordinary tile shape also for this small run
+    for name, classes in (("no head launch", (33, 64, 65, 96, 97, 100, 128, 10)), ("head for the widest only", (40, 128, 129, 300, 32))):
+        tenants, parts = {}, []
+        for t, c in enumerate(classes):
+            m = wl.c2(n_tenants=1, n_requests=1, dims=(72, 160, c), seed=90 + t)
+            tenants[t] = m.tenants[0]
+        rng = np.random.default_rng(17)
+        ids = rng.choice(len(classes), size=900, p=np.array([8, 1, 3, 1, 5, 2, 1, 1][:len(classes)]) / sum([8, 1, 3, 1, 5, 2, 1, 1][:len(classes)])).astype(np.int32)
+        x = wl.round_to_bf16(rng.standard_normal((900, 72)).astype(np.float32))
+        w = wl.Workload(name, "bf16", tenants, ids, x)
+        ref = oracle_rows(w)
+        ctx = make_context(w)
+        fused = gpu_run(ctx, w, poison=True)
+        n_fused = ctx.stats()["last_run_launches"]
+        compare(w, fused, ref, what=name)
+        ctx.close()
+        monkeypatch.setenv("MT_NO_FUSED_HEAD", "1")
+        ctx = make_context(w)
+        plain = gpu_run(ctx, w, poison=True)
+        n_plain = ctx.stats()["last_run_launches"]
+        ctx.close()
+        monkeypatch.delenv("MT_NO_FUSED_HEAD")
+        assert n_plain - n_fused == (1 if max(classes) <= 128 else 0), name
+        assert np.array_equal(fused[0], plain[0]) and np.array_equal(fused[2], plain[2]) and np.array_equal(fused[3], plain[3])
+        assert np.allclose(fused[1], plain[1], rtol=1e-6, atol=1e-7)
