@@ -24,13 +24,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mt_oracle.c")
 _LIB = os.path.join(_HERE, "libmt_oracle.so")
 
-FC, CONV, GAP = 0, 1, 2
+FC, CONV, GAP, MAXPOOL, ADD = 0, 1, 2, 3, 4
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 
 
 class _CLayer(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("kind", "act", "in_features", "out_features", "in_h", "in_w", "stride")]
+                ("kind", "act", "in_features", "out_features", "in_h", "in_w", "stride", "ksize", "pad", "src", "src2")]
 
 
 def build(force: bool = False) -> str:
@@ -66,6 +66,12 @@ def lib():
             f.argtypes = [lp, dp, dp, dp, dp]
         L.orc_gap.restype = None
         L.orc_gap.argtypes = [lp, dp, dp]
+        L.orc_maxpool.restype = None
+        L.orc_maxpool.argtypes = [lp, dp, dp]
+        L.orc_add.restype = None
+        L.orc_add.argtypes = [lp, dp, dp, dp]
+        L.orc_fold_bn.restype = None
+        L.orc_fold_bn.argtypes = [dp, dp, ctypes.c_int, ctypes.c_int, dp, dp, dp, dp, ctypes.c_double, ctypes.c_int]
         L.orc_head.restype = None
         L.orc_head.argtypes = [dp, ctypes.c_int, dp, ip]
         L.orc_forward_one.restype = ctypes.c_uint64
@@ -92,10 +98,18 @@ class Layer:
     in_h: int = 0
     in_w: int = 0
     stride: int = 1
+    ksize: int = 3            # CONV / MAXPOOL window (k x k)
+    pad: int = 1              # CONV / MAXPOOL padding
+    src: int = 0              # j + 1: this layer reads the output of layer j; 0: the previous layer
+    src2: int = 0             # ADD: the second operand, same convention
 
     def c(self) -> _CLayer:
         return _CLayer(self.kind, self.act, self.in_features, self.out_features,
-                       self.in_h, self.in_w, self.stride)
+                       self.in_h, self.in_w, self.stride, self.ksize, self.pad, self.src, self.src2)
+
+    def out_hw(self):
+        return ((self.in_h + 2 * self.pad - self.ksize) // self.stride + 1,
+                (self.in_w + 2 * self.pad - self.ksize) // self.stride + 1)
 
     def in_len(self) -> int:
         return int(lib().orc_layer_in_len(ctypes.byref(self.c())))
@@ -106,7 +120,7 @@ class Layer:
 
 @dataclass
 class Model:
-    """layers[l] with weights[l] (FC: [N,K]; CONV: [Co,Ci,3,3]; GAP: None) and biases[l]."""
+    """layers[l] with weights[l] (FC: [N,K]; CONV: [Co,Ci,k,k]; GAP, MAXPOOL, ADD: None) and biases[l]."""
     layers: List[Layer]
     weights: List[Optional[np.ndarray]]
     biases: List[Optional[np.ndarray]]
@@ -145,10 +159,9 @@ class Model:
                 total += l.in_features * l.out_features
             elif l.kind == CONV:
                 s = l.stride
-                oh = (l.in_h + 2 - 3) // s + 1
-                ow = (l.in_w + 2 - 3) // s + 1
-                taps_h = sum(1 for o in range(oh) for k in range(3) if 0 <= o * s + k - 1 < l.in_h)
-                taps_w = sum(1 for o in range(ow) for k in range(3) if 0 <= o * s + k - 1 < l.in_w)
+                oh, ow = l.out_hw()
+                taps_h = sum(1 for o in range(oh) for k in range(l.ksize) if 0 <= o * s + k - l.pad < l.in_h)
+                taps_w = sum(1 for o in range(ow) for k in range(l.ksize) if 0 <= o * s + k - l.pad < l.in_w)
                 total += taps_h * taps_w * l.in_features * l.out_features
         return total
 
@@ -179,9 +192,35 @@ def conv(layer: Layer, W, b, h, via_im2col: bool = False) -> np.ndarray:
     z = np.empty(layer.out_len(), dtype=np.float64)
     fn = lib().orc_conv_via_im2col if via_im2col else lib().orc_conv
     fn(ctypes.byref(layer.c()), _dp(W), _dp(b), _dp(h), _dp(z))
-    oh = (layer.in_h + 2 - 3) // layer.stride + 1
-    ow = (layer.in_w + 2 - 3) // layer.stride + 1
+    oh, ow = layer.out_hw()
     return z.reshape(oh, ow, layer.out_features)
+
+
+def maxpool(layer: Layer, h) -> np.ndarray:
+    h = np.ascontiguousarray(h, dtype=np.float64)
+    z = np.empty(layer.out_len(), dtype=np.float64)
+    lib().orc_maxpool(ctypes.byref(layer.c()), _dp(h), _dp(z))
+    oh, ow = layer.out_hw()
+    return z.reshape(oh, ow, layer.in_features)
+
+
+def add(layer: Layer, a, b) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    b = np.ascontiguousarray(b, dtype=np.float64)
+    z = np.empty(layer.out_len(), dtype=np.float64)
+    lib().orc_add(ctypes.byref(layer.c()), _dp(a), _dp(b), _dp(z))
+    return z.reshape(layer.in_h, layer.in_w, layer.in_features)
+
+
+def fold_bn(W, b, gamma, beta, mean, var, eps: float, to_bf16: bool):
+    """Filters [Co, ...] and bias [Co] of a convolution with the batch normalisation behind it folded in
+    (fp64 arithmetic, filters rounded once to bfloat16 or fp32, bias to fp32).  Returns new arrays."""
+    W2 = np.array(W, dtype=np.float64, order="C", copy=True)
+    Co = W2.shape[0]
+    b2 = np.zeros(Co) if b is None else np.array(b, dtype=np.float64, copy=True)
+    g, be, mu, va = (np.ascontiguousarray(v, dtype=np.float64) for v in (gamma, beta, mean, var))
+    lib().orc_fold_bn(_dp(W2), _dp(b2), Co, int(W2.size // Co), _dp(g), _dp(be), _dp(mu), _dp(va), float(eps), int(to_bf16))
+    return W2, b2
 
 
 def gap(layer: Layer, h) -> np.ndarray:
@@ -260,7 +299,12 @@ def models_from_workload(w) -> Dict[int, Model]:
     """Oracle models for a ``workloads.Workload`` (duck-typed: nothing is imported from it)."""
     out = {}
     for t, tm in w.tenants.items():
-        layers = [Layer(l.kind, l.act, l.in_features, l.out_features, l.in_h, l.in_w, l.stride)
+        layers = [Layer(l.kind, l.act, l.in_features, l.out_features, l.in_h, l.in_w, l.stride,
+                        getattr(l, "ksize", 3), getattr(l, "pad", 1), getattr(l, "src", 0), getattr(l, "src2", 0))
                   for l in tm.layers]
-        out[int(t)] = Model(layers, list(tm.weights), list(tm.biases), round_bf16=(w.dtype == "bf16"))
+        weights, biases = list(tm.weights), list(tm.biases)
+        for i, bn in enumerate(getattr(tm, "bn", None) or []):
+            if bn is not None:              # (gamma, beta, mean, var) behind convolution i: fold it
+                weights[i], biases[i] = fold_bn(weights[i], biases[i], *bn, getattr(tm, "bn_eps", 1e-5), w.dtype == "bf16")
+        out[int(t)] = Model(layers, weights, biases, round_bf16=(w.dtype == "bf16"))
     return out

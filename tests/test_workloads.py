@@ -59,3 +59,27 @@ def test_c2_cost_matches_closed_form():
     assert cost["flops"] == 50 * 2 * (20 * 30 + 30 * 5)
     active = len(w.counts())
     assert cost["weight_bytes"] == active * ((20 * 30 + 30 * 5) * 2 + 35 * 4)
+
+
+def test_resnet18_shaped_layer_graph():
+    """17 convolutions of 3x3 and the 7x7 stem, 3 projections of 1x1, one max-pool, 8 residual
+    additions, pooling, FC; every layer's input shape is the output shape of the layer it names."""
+    L = wl.resnet18_layers(64, 3, (64, 128, 256, 512), 1000)
+    kinds = [l.kind for l in L]
+    assert kinds.count(wl.CONV) == 20 and kinds.count(wl.ADD) == 8 and kinds.count(wl.MAXPOOL) == 1 and kinds[-2:] == [wl.GAP, wl.FC]
+    assert sorted((l.ksize for l in L if l.kind == wl.CONV), reverse=True)[:4] == [7, 3, 3, 3] and sum(1 for l in L if l.kind == wl.CONV and l.ksize == 1) == 3
+    def out_shape(j):            # (h, w, c) of the output of layer j
+        l = L[j]
+        h, w = l.out_hw()
+        return (h, w, l.out_features if l.kind == wl.CONV else l.in_features)
+    for i, l in enumerate(L):
+        if i == 0 or l.kind == wl.FC:
+            continue
+        src = l.src - 1 if l.src else i - 1
+        assert src < i and out_shape(src) == (l.in_h, l.in_w, l.in_features), i
+        if l.kind == wl.ADD:
+            assert 0 < l.src2 <= i and out_shape(l.src2 - 1) == (l.in_h, l.in_w, l.in_features), i
+    assert out_shape(len(L) - 3) == (2, 2, 512)           # 64 -> 32 (stem) -> 16 (pool) -> 16, 8, 4, 2
+    w = wl.resnet(n_tenants=2, n_requests=5, hw=32, widths=(8, 16, 24, 32), classes=7)
+    assert all(b is not None for l, b in zip(w.tenants[0].layers, w.tenants[0].bn) if l.kind == wl.CONV)
+    assert w.tenants[0].weights[0].shape == (8, 3, 7, 7) and w.inputs.shape == (5, 32 * 32 * 3)

@@ -38,7 +38,7 @@ from typing import Dict, List, Optional
 import numpy as np
 import torch
 
-FC, CONV, GAP = 0, 1, 2
+FC, CONV, GAP, MAXPOOL, ADD = 0, 1, 2, 3, 4
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 
 BASE_SEED = 190106887
@@ -53,11 +53,18 @@ class LayerSpec:
     in_h: int = 0
     in_w: int = 0
     stride: int = 1
+    ksize: int = 3            # CONV, MAXPOOL: window k x k
+    pad: int = 1              # CONV, MAXPOOL
+    src: int = 0              # j + 1: reads the output of layer j; 0: the previous layer
+    src2: int = 0             # ADD: the second operand, same convention
 
     def out_hw(self):
-        if self.kind != CONV:
+        if self.kind == ADD:
+            return (self.in_h, self.in_w)
+        if self.kind not in (CONV, MAXPOOL):
             return (1, 1)
-        return ((self.in_h + 2 - 3) // self.stride + 1, (self.in_w + 2 - 3) // self.stride + 1)
+        return ((self.in_h + 2 * self.pad - self.ksize) // self.stride + 1,
+                (self.in_w + 2 * self.pad - self.ksize) // self.stride + 1)
 
     def in_len(self) -> int:
         return self.in_features if self.kind == FC else self.in_h * self.in_w * self.in_features
@@ -68,7 +75,7 @@ class LayerSpec:
         if self.kind == GAP:
             return self.in_features
         oh, ow = self.out_hw()
-        return oh * ow * self.out_features
+        return oh * ow * (self.out_features if self.kind == CONV else self.in_features)
 
 
 @dataclass
@@ -76,6 +83,10 @@ class TenantModel:
     layers: List[LayerSpec]
     weights: List[Optional[np.ndarray]]   # float32 arrays holding representable values
     biases: List[Optional[np.ndarray]]    # float32
+    # batch normalisation behind convolution l, to be folded into it at registration:
+    # bn[l] = (gamma, beta, mean, var), float32 [C_out] each, or None; absent: no layer has one
+    bn: Optional[List[Optional[tuple]]] = None
+    bn_eps: float = 1e-5
 
     @property
     def in_len(self) -> int:
@@ -143,13 +154,30 @@ def make_model(layers: List[LayerSpec], dtype: str, *key) -> TenantModel:
         if l.kind == FC:
             w = _normal(rng, (l.out_features, l.in_features), l.in_features ** -0.5, dtype)
         elif l.kind == CONV:
-            w = _normal(rng, (l.out_features, l.in_features, 3, 3), (9 * l.in_features) ** -0.5, dtype)
+            k = l.ksize
+            w = _normal(rng, (l.out_features, l.in_features, k, k), (k * k * l.in_features) ** -0.5, dtype)
         else:
             weights.append(None); biases.append(None)
             continue
         b = rng.standard_normal(l.out_features, dtype=np.float32) * np.float32(0.1)
         weights.append(w); biases.append(b.astype(np.float32))
     return TenantModel(layers, weights, biases)
+
+
+def with_batchnorm(model: TenantModel, *key) -> TenantModel:
+    """Give every convolution of the model a batch normalisation (gamma ~ U(0.5, 1.5), beta ~ N(0, 0.01),
+    running mean ~ N(0, 0.01), running variance ~ U(0.5, 1.5)), to be folded in at registration."""
+    bn = []
+    for li, l in enumerate(model.layers):
+        if l.kind != CONV:
+            bn.append(None)
+            continue
+        rng = _rng(*key, li, 7005)
+        c = l.out_features
+        bn.append(((0.5 + rng.random(c, dtype=np.float32)), rng.standard_normal(c, dtype=np.float32) * np.float32(0.1),
+                   rng.standard_normal(c, dtype=np.float32) * np.float32(0.1), (0.5 + rng.random(c, dtype=np.float32))))
+    model.bn = bn
+    return model
 
 
 def mlp_layers(dims: List[int], act: int) -> List[LayerSpec]:
@@ -166,6 +194,42 @@ def cnn_layers(hw: int = 32, chans=(3, 32, 64, 128), strides=(1, 2, 2), classes:
     layers.append(LayerSpec(GAP, ACT_NONE, chans[-1], chans[-1], h, h))
     layers.append(LayerSpec(FC, ACT_NONE, chans[-1], classes))
     return layers
+
+
+def resnet18_layers(hw: int = 32, chans: int = 3, widths=(64, 128, 256, 512), classes: int = 1000,
+                    stem_kernel: int = 7) -> List[LayerSpec]:
+    """The layer graph of an 18-layer residual network (the paper's running example, section 1.1) as a
+    layer list with skip sources: 7x7 stride-2 stem, 3x3 stride-2 max-pool, four stages of two basic blocks
+    (3x3 convolution, ReLU, 3x3 convolution, plus the block's input, ReLU; the first block of stages 2-4
+    halves the image and takes its input through a 1x1 stride-2 convolution), global average pool, FC.
+    Every convolution is followed by a batch normalisation, which `with_batchnorm` supplies and
+    registration folds in.  The shape only: image size, widths and class count are free."""
+    L: List[LayerSpec] = []
+    stem = LayerSpec(CONV, ACT_RELU, chans, widths[0], hw, hw, 2, ksize=stem_kernel, pad=(stem_kernel - 1) // 2)
+    L.append(stem)
+    h = stem.out_hw()[0]
+    pool = LayerSpec(MAXPOOL, ACT_NONE, widths[0], widths[0], h, h, 2, ksize=3, pad=1)
+    L.append(pool)
+    h = pool.out_hw()[0]
+    c_in = widths[0]
+    for stage, c in enumerate(widths):
+        for block in range(2):
+            stride = 2 if (stage > 0 and block == 0) else 1
+            x_idx = len(L)                                     # src code of the block's input: the output of layer len(L) - 1
+            conv1 = LayerSpec(CONV, ACT_RELU, c_in, c, h, h, stride, ksize=3, pad=1)
+            L.append(conv1)
+            h2 = conv1.out_hw()[0]
+            L.append(LayerSpec(CONV, ACT_NONE, c, c, h2, h2, 1, ksize=3, pad=1))
+            main_idx = len(L)                                  # src code of the main branch's output
+            if stride != 1 or c_in != c:
+                L.append(LayerSpec(CONV, ACT_NONE, c_in, c, h, h, stride, ksize=1, pad=0, src=x_idx))
+                L.append(LayerSpec(ADD, ACT_RELU, c, c, h2, h2, src=main_idx, src2=len(L)))
+            else:
+                L.append(LayerSpec(ADD, ACT_RELU, c, c, h2, h2, src2=x_idx))
+            c_in, h = c, h2
+    L.append(LayerSpec(GAP, ACT_NONE, c_in, c_in, h, h))
+    L.append(LayerSpec(FC, ACT_NONE, c_in, classes))
+    return L
 
 
 def uniform_ids(n_tenants: int, n_requests: int, *key) -> np.ndarray:
@@ -229,6 +293,15 @@ def c5(n_tenants=8, n_requests=32768, dims=(4096, 4096, 4096, 4096, 1000), seed=
                     _inputs("normal", (n_requests, dims[0]), "bf16", seed))
 
 
+def resnet(n_tenants=4, n_requests=64, hw=32, widths=(64, 128, 256, 512), classes=1000, dtype="bf16", seed=6) -> Workload:
+    """Tenants with resnet18-shaped models (synthetic weights; the trained ones are not available
+    offline), batch normalisation behind every convolution, requests uniform over tenants."""
+    tenants = {t: with_batchnorm(make_model(resnet18_layers(hw, 3, widths, classes), dtype, seed, t), seed, t)
+               for t in range(n_tenants)}
+    return Workload("resnet18-shaped", dtype, tenants, uniform_ids(n_tenants, n_requests, seed),
+                    _inputs("normal", (n_requests, hw * hw * 3), dtype, seed))
+
+
 CONFIGS = {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5}
 
 
@@ -247,7 +320,7 @@ def algorithmic_cost(w: Workload) -> dict:
                 flops += 2 * m_t * l.in_features * l.out_features
             elif l.kind == CONV:
                 oh, ow = l.out_hw()
-                flops += 2 * m_t * oh * ow * 9 * l.in_features * l.out_features
+                flops += 2 * m_t * oh * ow * l.ksize * l.ksize * l.in_features * l.out_features
             if model.weights[li] is not None:
                 wbytes += model.weights[li].size * es + model.biases[li].size * 4
             if li == 0:
