@@ -55,25 +55,41 @@ typedef enum {
     MT_EDEVICE = 8       /* a HIP call failed; text in mt_last_error               */
 } mt_status;
 
-typedef enum { MT_FC = 0, MT_CONV2D = 1, MT_GAP = 2 } mt_kind;
+typedef enum { MT_FC = 0, MT_CONV2D = 1, MT_GAP = 2, MT_MAXPOOL = 3, MT_ADD = 4 } mt_kind;
 typedef enum { MT_ACT_NONE = 0, MT_ACT_RELU = 1, MT_ACT_GELU = 2 } mt_act;
 typedef enum { MT_F32 = 0, MT_BF16 = 1 } mt_dtype;
 
-#define MT_MAX_LAYERS 8
+#define MT_MAX_LAYERS 48
 #define MT_SEG_SLOTS 8      /* runs made of several submissions that may be in flight at once */
 
-/* One layer of a model (closed set, paper section 3.1).
- *   MT_FC:     y[n] = act(b[n] + sum_k W[n][k] x[k]); in_features = K, out_features = N.
- *   MT_CONV2D: 3x3 cross-correlation over an NHWC image of in_h x in_w x in_features,
- *              zero padding 1, stride 1 or 2, out_features output channels, bias per
- *              channel, then act.  kh = kw = 3 and pad = 1 are the only values accepted.
- *   MT_GAP:    mean over in_h x in_w of every one of in_features channels
- *              (out_features must equal in_features, act must be MT_ACT_NONE).
- * The activation of a model's last layer must be MT_ACT_NONE: its outputs are the logits. */
+/* One layer of a model (closed set, paper section 3.1; section 1.1: DNNs are built from a few
+ * dozen layer types).
+ *   MT_FC:      y[n] = act(b[n] + sum_k W[n][k] x[k]); in_features = K, out_features = N.
+ *   MT_CONV2D:  kh x kw cross-correlation (kh = kw = 1, 3 or 7) over an NHWC image of
+ *               in_h x in_w x in_features, zero padding pad = (kh - 1) / 2, stride 1 or 2,
+ *               out_features output channels (a multiple of 8; in_features too, except in a
+ *               model's first layer), bias per channel, then act.  Output size
+ *               floor((in + 2 pad - kh) / stride) + 1 each way.
+ *   MT_GAP:     mean over in_h x in_w of every one of in_features channels
+ *               (out_features must equal in_features, act must be MT_ACT_NONE).
+ *   MT_MAXPOOL: maximum over a kh x kw window (kh = kw = 2 or 3), stride 1 or 2, pad 0 or 1
+ *               (below kh); positions outside the image never win.  out_features = in_features,
+ *               act MT_ACT_NONE.
+ *   MT_ADD:     act(a + b) elementwise, a residual connection: a and b are the outputs of two
+ *               earlier layers of the same shape in_h x in_w x in_features (out_features =
+ *               in_features).
+ * A layer reads the output of the layer before it (layer 0: the request), unless src says
+ * otherwise: src = j + 1 reads the output of layer j (j below this layer's index), src = 0 the
+ * previous layer.  MT_ADD takes its second operand from src2 the same way (src2 must be given).
+ * Image layers (convolution, max-pool, add) pass NHWC images on; MT_FC reads a vector, so it
+ * follows MT_FC or MT_GAP (or is the first layer).  The activation of a model's last layer,
+ * which must be MT_FC, must be MT_ACT_NONE: its outputs are the logits.  At most four layer
+ * outputs may be alive at once (a chain needs two; a residual block with a projection three). */
 typedef struct {
     uint32_t kind, act;
     uint32_t in_features, out_features;
     uint32_t in_h, in_w, kh, kw, stride, pad;
+    uint32_t src, src2;
 } mt_layer_spec;
 
 typedef struct {
@@ -124,8 +140,9 @@ typedef struct {
 /* Create a worker context (paper section 3: a worker is a long-lived process that hosts the
  * DNNs of many tenants at once; section 3.3: their weights stay in device memory): allocates
  * the weight arena, the tenant table, and per run slot the batch descriptors and two
- * activation buffers of max_requests * max_width elements on cfg->device.  Everything the
- * later calls need on the device is allocated here; none of them allocates device memory.
+ * activation buffers of max_requests * max_width elements on cfg->device.  Serving calls
+ * (submit, run, prefetch) allocate no device memory; registering a model with skip connections
+ * adds the third or fourth activation buffer its layer graph needs.
  * Errors: MT_EINVAL (null / zero sizes), MT_ENOMEM, MT_EDEVICE. */
 mt_status mt_create(mt_ctx** out, const mt_config* cfg);
 
@@ -134,8 +151,8 @@ mt_status mt_destroy(mt_ctx* ctx);
 
 /* Upload a tenant's DNN (paper section 3: a tenant hands over its model before it sends requests).
  *   specs[n_layers]: layer chain; out length of layer l must equal in length of l+1.
- *   weights[l]: HOST, context dtype; FC [N][K] row-major, CONV [C_out][C_in][3][3];
- *               ignored (may be NULL) for GAP.
+ *   weights[l]: HOST, context dtype; FC [N][K] row-major, CONV [C_out][C_in][kh][kw];
+ *               ignored (may be NULL) for the kinds without parameters.
  *   biases[l]:  HOST fp32 [N] or [C_out]; NULL means zeros.
  * Weights are copied and repacked into the arena before the call returns; the caller
  * keeps ownership of its buffers.  Nothing is allocated when the call fails.
@@ -144,6 +161,18 @@ mt_status mt_destroy(mt_ctx* ctx);
  * max_width / max_classes), MT_ENOMEM (arena full), MT_EDEVICE. */
 mt_status mt_register_model(mt_ctx* ctx, uint32_t tenant, const mt_layer_spec* specs, uint32_t n_layers,
                             const void* const* weights, const void* const* biases);
+
+/* mt_register_model for models whose convolutions are followed by batch normalisation, which the
+ * library folds into the convolution (the models of paper section 1.1 are built that way; the
+ * runtime executes the folded form).  bn[l]: HOST fp32 [4][C_out] = gamma, beta, running mean,
+ * running variance of the normalisation behind convolution l, or NULL for none (must be NULL for
+ * other kinds); bn itself may be NULL.  With s = gamma / sqrt(var + bn_eps) per output channel the
+ * layer becomes W' = round(W * s), b' = float((b - mean) * s + beta), computed in double
+ * precision from the given values and rounded once, W' to the context's element type (nearest
+ * even) and b' to fp32; the layer's act applies after it.  Errors: as mt_register_model, and
+ * MT_EINVAL for a variance + eps that is not positive. */
+mt_status mt_register_model_bn(mt_ctx* ctx, uint32_t tenant, const mt_layer_spec* specs, uint32_t n_layers,
+                               const void* const* weights, const void* const* biases, const float* const* bn, float bn_eps);
 
 /* Remove a tenant's model and return its arena slice.  Must not be called while an
  * mt_run that may serve the tenant is still executing.  Errors: MT_ENOTFOUND. */

@@ -22,6 +22,7 @@ typedef struct {
     float fc_big_ms[MT_MAX_LAYERS]; /* grouped big-tile FC launch of each layer index */
     float conv_ms[MT_MAX_LAYERS];   /* grouped convolution launch of each layer index */
     float gap_ms[MT_MAX_LAYERS];    /* pooling launch of each layer index             */
+    float ops_ms[MT_MAX_LAYERS];    /* max-pool / residual-add launch of each layer index */
     float total_ms;                 /* first kernel start to last kernel end          */
 } mt_profile;
 mt_status mt_set_profiling(mt_ctx* ctx, int enable);

@@ -19,10 +19,10 @@ MT_OK = 0
 MT_STATIC_SCRATCH_BYTES = 16 << 20
 STATUS_NAMES = {0: "MT_OK", 1: "MT_EINVAL", 2: "MT_ENOMEM", 3: "MT_ENOTFOUND", 4: "MT_EEXIST",
                 5: "MT_EUNSUPPORTED", 6: "MT_EFULL", 7: "MT_ESTATE", 8: "MT_EDEVICE"}
-MT_FC, MT_CONV2D, MT_GAP = 0, 1, 2
+MT_FC, MT_CONV2D, MT_GAP, MT_MAXPOOL, MT_ADD = 0, 1, 2, 3, 4
 MT_ACT_NONE, MT_ACT_RELU, MT_ACT_GELU = 0, 1, 2
 MT_F32, MT_BF16 = 0, 1
-MT_MAX_LAYERS = 8
+MT_MAX_LAYERS = 48
 
 
 class MtError(RuntimeError):
@@ -33,7 +33,7 @@ class MtError(RuntimeError):
 
 class mt_layer_spec(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in
-                ("kind", "act", "in_features", "out_features", "in_h", "in_w", "kh", "kw", "stride", "pad")]
+                ("kind", "act", "in_features", "out_features", "in_h", "in_w", "kh", "kw", "stride", "pad", "src", "src2")]
 
 
 class mt_config(ctypes.Structure):
@@ -78,7 +78,7 @@ class mt_stats(ctypes.Structure):
 class mt_profile(ctypes.Structure):
     _fields_ = [("batcher_ms", ctypes.c_float), ("gather_ms", ctypes.c_float), ("head_ms", ctypes.c_float),
                 ("fc_ms", ctypes.c_float * MT_MAX_LAYERS), ("fc_big_ms", ctypes.c_float * MT_MAX_LAYERS), ("conv_ms", ctypes.c_float * MT_MAX_LAYERS),
-                ("gap_ms", ctypes.c_float * MT_MAX_LAYERS),
+                ("gap_ms", ctypes.c_float * MT_MAX_LAYERS), ("ops_ms", ctypes.c_float * MT_MAX_LAYERS),
                 ("total_ms", ctypes.c_float)]
 
 
@@ -97,6 +97,8 @@ def load_library() -> ctypes.CDLL:
     L.mt_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(mt_config)]
     L.mt_destroy.argtypes = [vp]
     L.mt_register_model.argtypes = [vp, u32, ctypes.POINTER(mt_layer_spec), u32, ctypes.POINTER(vp), ctypes.POINTER(vp)]
+    L.mt_register_model_bn.argtypes = [vp, u32, ctypes.POINTER(mt_layer_spec), u32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                       ctypes.POINTER(vp), ctypes.c_float]
     L.mt_unregister_model.argtypes = [vp, u32]
     L.mt_submit.argtypes = [vp, u32, vp, u32, ctypes.POINTER(u32)]
     L.mt_submit_batch.argtypes = [vp, vp, vp, u32, u32, ctypes.POINTER(u32)]
@@ -120,7 +122,7 @@ def load_library() -> ctypes.CDLL:
     L.mt_last_error.argtypes = [vp]
     L.mt_last_error.restype = ctypes.c_char_p
     L.mt_version.restype = ctypes.c_char_p
-    for name in ("mt_create", "mt_destroy", "mt_register_model", "mt_unregister_model", "mt_submit",
+    for name in ("mt_create", "mt_destroy", "mt_register_model", "mt_register_model_bn", "mt_unregister_model", "mt_submit",
                  "mt_submit_batch", "mt_run", "mt_run_static", "mt_last_counts", "mt_get_stats", "mt_tenant_account_get", "mt_estimate_run", "mt_prefetch", "mt_cache_stats_get", "mt_admit", "mt_debug_poison", "mt_debug_copy",
                  "mt_set_profiling", "mt_get_profile", "mt_model_footprint_get", "mt_debug_mfma_rate"):
         getattr(L, name).restype = ctypes.c_int
@@ -128,10 +130,11 @@ def load_library() -> ctypes.CDLL:
     return L
 
 
-def layer_spec(kind, act=MT_ACT_NONE, in_features=0, out_features=0, in_h=0, in_w=0, stride=1) -> mt_layer_spec:
-    conv = kind == MT_CONV2D
-    return mt_layer_spec(kind, act, in_features, out_features, in_h, in_w, 3 if conv else 0, 3 if conv else 0,
-                         stride if conv else 0, 1 if conv else 0)
+def layer_spec(kind, act=MT_ACT_NONE, in_features=0, out_features=0, in_h=0, in_w=0, stride=1, ksize=3, pad=1,
+               src=0, src2=0) -> mt_layer_spec:
+    window = kind in (MT_CONV2D, MT_MAXPOOL)
+    return mt_layer_spec(kind, act, in_features, out_features, in_h, in_w, ksize if window else 0, ksize if window else 0,
+                         stride if window else 0, pad if window else 0, src, src2)
 
 
 def _host_array(a, dtype_code: int) -> np.ndarray:
@@ -176,18 +179,25 @@ class Context:
             pass
 
     # -- mt_register_model ---------------------------------------------------------------
-    def register_model(self, tenant: int, specs: Sequence[mt_layer_spec], weights, biases):
+    def register_model(self, tenant: int, specs: Sequence[mt_layer_spec], weights, biases, bn=None, bn_eps: float = 1e-5):
+        """mt_register_model, or mt_register_model_bn when `bn` (per layer: None or (gamma, beta, mean, var)) is given."""
         n = len(specs)
         arr = (mt_layer_spec * n)(*specs)
         keep = []
         wp = (ctypes.c_void_p * n)()
         bp = (ctypes.c_void_p * n)()
+        np_ = (ctypes.c_void_p * n)()
         for i in range(n):
             if weights[i] is not None:
                 w = _host_array(weights[i], self.dtype); keep.append(w); wp[i] = w.ctypes.data
             if biases is not None and biases[i] is not None:
                 b = np.ascontiguousarray(biases[i], dtype=np.float32); keep.append(b); bp[i] = b.ctypes.data
-        self._check(self._lib.mt_register_model(self._h, tenant, arr, n, wp, bp))
+            if bn is not None and bn[i] is not None:
+                q = np.ascontiguousarray(np.stack([np.asarray(v, dtype=np.float32) for v in bn[i]])); keep.append(q); np_[i] = q.ctypes.data
+        if bn is None:
+            self._check(self._lib.mt_register_model(self._h, tenant, arr, n, wp, bp))
+        else:
+            self._check(self._lib.mt_register_model_bn(self._h, tenant, arr, n, wp, bp, np_, float(bn_eps)))
 
     def unregister_model(self, tenant: int):
         self._check(self._lib.mt_unregister_model(self._h, tenant))
@@ -234,7 +244,7 @@ class Context:
         p = mt_profile()
         self._check(self._lib.mt_get_profile(self._h, ctypes.byref(p)))
         return {"batcher_ms": p.batcher_ms, "gather_ms": p.gather_ms, "head_ms": p.head_ms,
-                "fc_ms": list(p.fc_ms), "fc_big_ms": list(p.fc_big_ms), "conv_ms": list(p.conv_ms), "gap_ms": list(p.gap_ms), "total_ms": p.total_ms}
+                "fc_ms": list(p.fc_ms), "fc_big_ms": list(p.fc_big_ms), "conv_ms": list(p.conv_ms), "gap_ms": list(p.gap_ms), "ops_ms": list(p.ops_ms), "total_ms": p.total_ms}
 
     def debug_poison(self):
         self._check(self._lib.mt_debug_poison(self._h))

@@ -41,7 +41,7 @@ __device__ uint32_t block_exclusive_scan(uint32_t* data, uint32_t n, uint32_t* t
     return total;
 }
 
-constexpr uint32_t kLists = kListKinds * MT_MAX_LAYERS;   // FC, conv and big-FC tile-count arrays of every layer index
+constexpr uint32_t kLists = kListKinds * kLayerGroup;     // FC, conv and big-FC tile-count arrays of the layer indices of one pass
 
 // Tenant segmentation and grouped-work descriptors.  One workgroup; every step is
 // deterministic: rows of a tenant keep their arrival order (stable counting sort).  Equal
@@ -150,12 +150,12 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     __shared__ uint32_t tmp[17];
     __shared__ uint32_t wtot[kBatchThreads / 64][kLists];
     __shared__ Segment seg_l[kSegsInLds];
-    __shared__ uint32_t big_total[MT_MAX_LAYERS];
+    __shared__ uint32_t big_total[kLayerGroup];
     __shared__ uint32_t carry_l[kLists];
 
     const uint32_t tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const uint32_t T = a.T, R = a.R;
-    if (tid < MT_MAX_LAYERS) big_total[tid] = 0;       // first read is several barriers away
+    if (tid < kLayerGroup) big_total[tid] = 0;         // first read is several barriers away
     uint32_t Tp = 64;
     while (Tp < T) Tp <<= 1;
     const uint32_t bits = T > 1 ? 32 - __builtin_clz(T - 1) : 0;      // valid ids are below T
@@ -186,31 +186,37 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
 
     // column groups per layer (0 = no tiles), rows per request with the kind in the top bit
     // (1 = conv; FC: 64-row tiles count 1, 32-row tiles 2), padded width; from the 64 bytes of
-    // layer facts the host keeps per tenant
-    uint32_t grp[NSLOT][MT_MAX_LAYERS], rpr[NSLOT][MT_MAX_LAYERS], npad[NSLOT][MT_MAX_LAYERS];
-    static_assert(MT_MAX_LAYERS == 8, "a tenant's layer facts are four 16-byte loads");
+    // layer facts the host keeps per tenant and group of kLayerGroup layer indices.  The tile
+    // lists are built one such group at a time (models deeper than a group: further passes at the
+    // end of the kernel); the facts of the first group are fetched here, ahead of everything.
+    uint32_t grp[NSLOT][kLayerGroup], rpr[NSLOT][kLayerGroup], npad[NSLOT][kLayerGroup];
+    uint32_t regd[NSLOT];
+    static_assert(kLayerGroup == 8 && MT_MAX_LAYERS % kLayerGroup == 0, "a group's layer facts are four 16-byte loads");
+    auto load_facts = [&](uint32_t group) {
 #pragma unroll
-    for (uint32_t slot = 0; slot < nslots; ++slot) {
-        const uint32_t t = tid + slot * kBatchThreads;
-        const bool live = t < T;
-        u32x4 q[4] = {};
-        uint32_t reg = 0;
-        if (live) {
+        for (uint32_t slot = 0; slot < nslots; ++slot) {
+            const uint32_t t = tid + slot * kBatchThreads;
+            const bool live = t < T;
+            u32x4 q[4] = {};
+            if (group == 0) regd[slot] = 0;
+            if (live) {
 #pragma unroll
-            for (uint32_t i = 0; i < 4; ++i) q[i] = ((const u32x4*)a.facts)[t * 4 + i];
-            reg = a.tenants[t].registered;
+                for (uint32_t i = 0; i < 4; ++i) q[i] = ((const u32x4*)a.facts)[(size_t)t * (MT_MAX_LAYERS / 2) + group * 4 + i];
+                if (group == 0) regd[slot] = a.tenants[t].registered;
+            }
+            if (group == 0 && t < Tp) regl[t] = live && regd[slot];
+#pragma unroll
+            for (uint32_t l = 0; l < kLayerGroup; ++l) {
+                const uint32_t w0 = regd[slot] ? q[l / 2][2 * (l % 2)] : 0, w1 = q[l / 2][2 * (l % 2) + 1];
+                const bool conv = w0 >> 31;
+                const bool sk = a.fc_split_k && !conv && w0;    // this run's FC tiles: one column block each, 32 rows
+                grp[slot][l] = sk ? w1 / kBrickRows : w0 & 0x3fffffffu;
+                rpr[slot][l] = conv ? (w1 | 0x80000000u) : sk ? 2u : 1u + ((w0 >> 30) & 1);
+                npad[slot][l] = conv ? 0 : w1;
+            }
         }
-        if (t < Tp) regl[t] = live && reg;
-#pragma unroll
-        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-            const uint32_t w0 = reg ? q[l / 2][2 * (l % 2)] : 0, w1 = q[l / 2][2 * (l % 2) + 1];
-            const bool conv = w0 >> 31;
-            const bool sk = a.fc_split_k && !conv && w0;    // this run's FC tiles: one column block each, 32 rows
-            grp[slot][l] = sk ? w1 / kBrickRows : w0 & 0x3fffffffu;
-            rpr[slot][l] = conv ? (w1 | 0x80000000u) : sk ? 2u : 1u + ((w0 >> 30) & 1);
-            npad[slot][l] = conv ? 0 : w1;
-        }
-    }
+    };
+    load_facts(0);
 
     // the segment table sits in host memory: stage it in LDS when it is small
     const Segment* segs = a.segs;
@@ -322,81 +328,94 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
     // Big tiles pay only when a layer index has enough of them to fill the chip; below that the
     // streaming kernel takes those tenants too, side by side with everyone else's tiles.
     uint32_t big_layers = 0;                   // bit l: layer index l is served with big tiles where a tenant qualifies
-    if (a.big_enabled) {
-        uint32_t bt[MT_MAX_LAYERS];
+    for (uint32_t group = 0; group * kLayerGroup < a.n_layer_slots; ++group) {
+        const uint32_t l0 = group * kLayerGroup, lmask = a.list_mask[group];
+        if (group > 0) {                       // deeper models: the next eight layer indices (uniform: every thread takes the same passes)
+            load_facts(group);
+            if (tid < kLayerGroup) big_total[tid] = 0;
+            __syncthreads();
+        }
+        uint32_t big_here = 0;
+        if (a.big_enabled && l0 < (uint32_t)kBigMaxLayer) {
+            uint32_t bt[kLayerGroup];
 #pragma unroll
-        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) bt[l] = 0;
+            for (uint32_t l = 0; l < kLayerGroup; ++l) bt[l] = 0;
+#pragma unroll
+            for (uint32_t slot = 0; slot < nslots; ++slot) {
+                const uint32_t t = tid + slot * kBatchThreads;
+                const uint32_t Mt = t < Tp ? Ml[t] : 0;
+#pragma unroll
+                for (uint32_t l = 0; l < kLayerGroup; ++l) {
+                    const uint32_t rr = rpr[slot][l], np = npad[slot][l];
+                    const uint32_t g = grp[slot][l];
+                    if (g && !(rr >> 31) && fc_is_big(Mt, np)) bt[l] += ceil_div(big_rows(Mt), kBigTile) * ceil_div(np, kBigTile);
+                }
+            }
+#pragma unroll
+            for (uint32_t l = 0; l < kLayerGroup; ++l) {
+                uint32_t v = bt[l];
+                if (__any(v != 0)) {
+                    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+                    if (lane == 0) atomicAdd(&big_total[l], v);
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (uint32_t l = 0; l < kLayerGroup; ++l) big_here |= (big_total[l] >= a.big_min_tiles ? 1u : 0u) << l;
+            big_layers |= big_here << l0;
+        }
+
+        // pass 4: tile counts of every (kind, layer) list of the group, scanned over tenants in one
+        // vector scan.  Only the exclusive in-wave prefix of each list stays in registers across the
+        // barriers; the running total over slots lives in LDS.
+        if (tid < kLists) carry_l[tid] = 0;
 #pragma unroll
         for (uint32_t slot = 0; slot < nslots; ++slot) {
             const uint32_t t = tid + slot * kBatchThreads;
             const uint32_t Mt = t < Tp ? Ml[t] : 0;
+            uint32_t excl[kLists];
+            auto wave_scan = [&](uint32_t i, uint32_t c) {
+                uint32_t v = c;
+                if ((lmask >> i) & 1) v = wave_inclusive_scan(c);             // lists no registered model contributes to are skipped
+                excl[i] = v - c;
+                if (lane == 63) wtot[w][i] = v;
+            };
 #pragma unroll
-            for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-                const uint32_t rr = rpr[slot][l], np = npad[slot][l];
-                const uint32_t g = grp[slot][l];
-                if (g && !(rr >> 31) && fc_is_big(Mt, np)) bt[l] += ceil_div(big_rows(Mt), kBigTile) * ceil_div(np, kBigTile);
+            for (uint32_t l = 0; l < kLayerGroup; ++l) {
+                const uint32_t g = grp[slot][l], rr = rpr[slot][l], np = npad[slot][l];
+                const bool conv = rr >> 31;
+                const bool big = !conv && ((big_here >> l) & 1) && fc_is_big(Mt, np);
+                // conv: rows = requests * output pixels per tile; FC: rr = 1 (64-row tiles) or 2 (32-row tiles),
+                // over the rows that big tiles leave
+                const uint32_t Mb = big ? big_rows(Mt) : 0;
+                static_assert(kTileRows == 64, "FC tiles have 64 >> (rr - 1) rows");
+                const uint32_t fc_shift = 7 - rr;                           // log2 of the FC tile's rows (rr is 1 or 2 there)
+                const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows)
+                                                         : (Mt - Mb + (1u << fc_shift) - 1) >> fc_shift) * g : 0;
+                wave_scan(l, conv ? 0 : tiles);
+                wave_scan(kLayerGroup + l, conv ? tiles : 0);
+                wave_scan(2 * kLayerGroup + l, ceil_div(Mb, kBigTile) * ceil_div(np, kBigTile));
             }
-        }
-#pragma unroll
-        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-            uint32_t v = bt[l];
-            if (__any(v != 0)) {
-                for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-                if (lane == 0) atomicAdd(&big_total[l], v);
+            __syncthreads();
+            if (tid < kLists * 16) {                 // a row of 16 lanes per list: exclusive prefix of its 16 wave totals
+                const uint32_t i = tid >> 4, ww = tid & 15;
+                const uint32_t x = wtot[ww][i], run = carry_l[i];
+                const uint32_t inc = row16_inclusive_scan(x);
+                wtot[ww][i] = run + inc - x;
+                if (ww == 15) carry_l[i] = run + inc;
             }
-        }
-        __syncthreads();
+            __syncthreads();
 #pragma unroll
-        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) big_layers |= (big_total[l] >= a.big_min_tiles ? 1u : 0u) << l;
+            for (uint32_t i = 0; i < kLists; ++i)              // lists outside the mask are never read
+                if (((lmask >> i) & 1) && t < T)
+                    a.tile_base[((size_t)(i / kLayerGroup) * MT_MAX_LAYERS + l0 + i % kLayerGroup) * (T + 1) + t] = wtot[w][i] + excl[i];
+            __syncthreads();
+        }
+        if (tid < kLists && ((lmask >> tid) & 1))
+            a.tile_base[((size_t)(tid / kLayerGroup) * MT_MAX_LAYERS + l0 + tid % kLayerGroup) * (T + 1) + T] = carry_l[tid];
+        __syncthreads();                               // carry_l and wtot are reused by the next group
     }
     if (tid == 0) *a.big_layers = big_layers;   // the FC kernels split a qualifying tenant's rows by it
-
-    // pass 4: tile counts of every (kind, layer) list, scanned over tenants in one vector scan.
-    // Only the exclusive in-wave prefix of each list stays in registers across the barriers; the
-    // running total over slots lives in LDS.
-    if (tid < kLists) carry_l[tid] = 0;
-#pragma unroll
-    for (uint32_t slot = 0; slot < nslots; ++slot) {
-        const uint32_t t = tid + slot * kBatchThreads;
-        const uint32_t Mt = t < Tp ? Ml[t] : 0;
-        uint32_t excl[kLists];
-        auto wave_scan = [&](uint32_t i, uint32_t c) {
-            uint32_t v = c;
-            if ((a.list_mask >> i) & 1) v = wave_inclusive_scan(c);       // lists no registered model contributes to are skipped
-            excl[i] = v - c;
-            if (lane == 63) wtot[w][i] = v;
-        };
-#pragma unroll
-        for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-            const uint32_t g = grp[slot][l], rr = rpr[slot][l], np = npad[slot][l];
-            const bool conv = rr >> 31;
-            const bool big = !conv && ((big_layers >> l) & 1) && fc_is_big(Mt, np);
-            // conv: rows = requests * output pixels per tile; FC: rr = 1 (64-row tiles) or 2 (32-row tiles),
-            // over the rows that big tiles leave
-            const uint32_t Mb = big ? big_rows(Mt) : 0;
-            static_assert(kTileRows == 64, "FC tiles have 64 >> (rr - 1) rows");
-            const uint32_t fc_shift = 7 - rr;                           // log2 of the FC tile's rows (rr is 1 or 2 there)
-            const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows)
-                                                     : (Mt - Mb + (1u << fc_shift) - 1) >> fc_shift) * g : 0;
-            wave_scan(l, conv ? 0 : tiles);
-            wave_scan(MT_MAX_LAYERS + l, conv ? tiles : 0);
-            wave_scan(2 * MT_MAX_LAYERS + l, ceil_div(Mb, kBigTile) * ceil_div(np, kBigTile));
-        }
-        __syncthreads();
-        if (tid < kLists * 16) {                 // a row of 16 lanes per list: exclusive prefix of its 16 wave totals
-            const uint32_t i = tid >> 4, ww = tid & 15;
-            const uint32_t x = wtot[ww][i], run = carry_l[i];
-            const uint32_t inc = row16_inclusive_scan(x);
-            wtot[ww][i] = run + inc - x;
-            if (ww == 15) carry_l[i] = run + inc;
-        }
-        __syncthreads();
-#pragma unroll
-        for (uint32_t i = 0; i < kLists; ++i)              // lists outside the mask are never read
-            if (((a.list_mask >> i) & 1) && t < T) a.tile_base[(size_t)i * (T + 1) + t] = wtot[w][i] + excl[i];
-        __syncthreads();
-    }
-    if (tid < kLists && ((a.list_mask >> tid) & 1)) a.tile_base[(size_t)tid * (T + 1) + T] = carry_l[tid];
 }
 
 // ---- launcher ------------------------------------------------------------

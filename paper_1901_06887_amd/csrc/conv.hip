@@ -1,4 +1,4 @@
-// Grouped 3x3 convolution as implicit GEMM (see mt_device.h for the overview).
+// Grouped k x k convolution as implicit GEMM (see mt_device.h for the overview).
 #include "mt_device.h"
 
 namespace mt {
@@ -13,26 +13,35 @@ __device__ __forceinline__ void divmod_uniform(uint32_t x, uint32_t d, uint32_t*
 }
 
 // A lane's walk through K = (kernel row, kernel column, channel), one k step at a time.  Inside
-// a kernel row the three taps of a pixel are one contiguous run of 3 * cin input elements, so the
+// a kernel row the k taps of a pixel are one contiguous run of k * cin input elements, so the
 // position is kept as (kernel row th, offset lin inside the run) and the element offset `cur`
 // moves by KB per step plus a jump at the end of a run.  Validity is two range tests: the
-// left/right tap falls outside the image only at the image's left/right edge, the top/bottom
-// kernel row only at its top/bottom edge.  Steps past the last tap have th == 3: invalid.
+// left/right taps fall outside the image only near the image's left/right edge, the top/bottom
+// kernel rows only near its top/bottom edge.  Steps past the last tap have th == k: invalid.
 template <typename T>
 struct TapWalk {
     static constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
     uint32_t lin, th, run, lo, hi, tlo, thi, step;
     int32_t cur, jump;
+    // (ih0, iw0): the input coordinate of the window's top-left tap (may lie outside the image);
     // first: the lane's first element inside the run; step_el: elements per call of next()
-    // (at most one run ends per call: step_el <= 3 * cin)
+    // (at most two runs end per call: step_el <= 2 * k * cin, which holds for every window and
+    // channel count the layer set admits: a run is at least 8 elements, a step at most 32, and
+    // steps of 32 are only taken where cin is a multiple of 32)
     __device__ __forceinline__ void init(const LayerDev& L, int32_t ih0, int32_t iw0, bool row_ok, uint32_t first, uint32_t step_el)
     {
-        const int32_t cin = (int32_t)L.cin;
-        run = 3 * L.cin; lin = first; th = 0; step = step_el;
-        lo = iw0 < 0 ? L.cin : 0; hi = iw0 + 2 >= (int32_t)L.in_w ? 2 * L.cin : 3 * L.cin;
-        tlo = ih0 < 0 ? 1 : 0; thi = row_ok ? (ih0 + 2 >= (int32_t)L.in_h ? 2 : 3) : 0;
+        const int32_t cin = (int32_t)L.cin, k = (int32_t)L.ksize;
+        run = L.ksize * L.cin; lin = first; th = 0; step = step_el;
+        lo = (uint32_t)max(0, -iw0) * L.cin; hi = (uint32_t)max(0, min(k, (int32_t)L.in_w - iw0)) * L.cin;
+        tlo = (uint32_t)max(0, -ih0); thi = row_ok ? (uint32_t)max(0, min(k, (int32_t)L.in_h - ih0)) : 0;
         cur = (ih0 * (int32_t)L.in_w + iw0) * cin + (int32_t)lin;
-        jump = ((int32_t)L.in_w - 3) * cin;
+        jump = ((int32_t)L.in_w - k) * cin;
+        wrap(); wrap();                                            // a first element past the first run (1x1 windows of 8 channels)
+    }
+    __device__ __forceinline__ void wrap()
+    {
+        const bool w = lin >= run;
+        lin = w ? lin - run : lin; th += w ? 1u : 0u; cur = w ? cur + jump : cur;
     }
     // the 16-byte chunk of this k step inside the image, or -1 when the step reads zeros; moves on
     __device__ __forceinline__ int32_t next()
@@ -40,8 +49,7 @@ struct TapWalk {
         const bool ok = (lin >= lo) & (lin < hi) & (th >= tlo) & (th < thi);
         const int32_t chunk = ok ? (int32_t)((uint32_t)cur / EPC) : -1;
         lin += step; cur += (int32_t)step;
-        const bool wrap = lin >= run;
-        lin = wrap ? lin - run : lin; th += wrap ? 1u : 0u; cur = wrap ? cur + jump : cur;
+        wrap(); wrap();
         return chunk;
     }
 };
@@ -86,7 +94,7 @@ __device__ __forceinline__ void store_unit_nhwc(const f32x4 (&y)[4], T* my_pixel
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // reads done before the next unit overwrites the scratch
 }
 
-// ---- grouped 3x3 convolution as implicit GEMM ---------------------------------------------
+// ---- grouped k x k convolution as implicit GEMM ---------------------------------------------
 // GEMM view: rows = (request, output pixel), columns = output channels, K = (kh, kw, c_in).
 // A workgroup takes 128 consecutive rows of one tenant and up to 128 output channels; each of
 // its four waves owns 32 rows and all the channels, and no operand is shared between waves:
@@ -113,8 +121,8 @@ __device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, 
     uint32_t req, pix, oh, ow;
     divmod_uniform(mm, rpr, &req, &pix);
     divmod_uniform(pix, L.out_w, &oh, &ow);
-    const int32_t ih0 = (int32_t)(oh * L.stride) - 1, iw0 = (int32_t)(ow * L.stride) - 1;
-    gptr_t img = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
+    const int32_t ih0 = (int32_t)(oh * L.stride) - (int32_t)L.pad, iw0 = (int32_t)(ow * L.stride) - (int32_t)L.pad;
+    gptr_t img = (gptr_t)((const T*)act_of(a.act, L.in_buf) + (size_t)(seg0 + req) * a.S);
     gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)nb0 * nKB * 64 + lane);
 
     // The next k step's chunk.  Taps outside the image, steps past the last tap and rows past the
@@ -169,7 +177,7 @@ __device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, 
     // epilogue: the lane holds, for pixel li, channels 8g + 4 lh + {0..3} (g = 0..3) of every
     // channel block: bias, activation, rounding, coalesced store through the wave's scratch
     const float* bias = (const float*)(a.arena + L.b_off);
-    T* out = row_ok ? (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N : nullptr;
+    T* out = row_ok ? (T*)act_of(a.act, L.out_buf) + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N : nullptr;
 #pragma unroll
     for (int c = 0; c < CB; ++c) {
         const uint32_t nbase = (nb0 + c) * kBrickRows;
@@ -294,8 +302,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         uint32_t req, pix, oh, ow;
         divmod_uniform(mm, rpr, &req, &pix);
         divmod_uniform(pix, L.out_w, &oh, &ow);
-        img[i] = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S);
-        walk[i].init(L, (int32_t)(oh * L.stride) - 1, (int32_t)(ow * L.stride) - 1, row_ok,
+        img[i] = (gptr_t)((const T*)act_of(a.act, L.in_buf) + (size_t)(seg0 + req) * a.S);
+        walk[i].init(L, (int32_t)(oh * L.stride) - (int32_t)L.pad, (int32_t)(ow * L.stride) - (int32_t)L.pad, row_ok,
                      QUAD ? (lane & 3) * EPC : (lane & 1) * EPC, QUAD ? 2 * KB : KB);
     }
     gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
@@ -403,7 +411,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                 sum += __shfl_xor(sum, 32);
                 if (half == 0 && mb < rows_total) {
                     const uint32_t req = mb / rpr, cc = nbase + ch;
-                    T* out = (T*)a.act_out + (size_t)seg0 * a.S + (size_t)(req / kBrickRows) * nKBp * 64 * EPC;
+                    T* out = (T*)act_of(a.act, L.pool_buf) + (size_t)seg0 * a.S + (size_t)(req / kBrickRows) * nKBp * 64 * EPC;
                     out[((size_t)(cc / KB) * 64 + req % kBrickRows + 32 * ((cc % KB) / EPC)) * EPC + cc % EPC] = (T)(sum * inv);
                 }
                 sum = 0.0f;
@@ -418,7 +426,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         if (m < rows_total) {
             uint32_t req, pix;
             divmod_uniform(m, rpr, &req, &pix);
-            out = (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N + nbase;
+            out = (T*)act_of(a.act, L.out_buf) + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N + nbase;
         }
         f32x4 y[4];
 #pragma unroll
@@ -505,7 +513,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
         const int32_t ih_first = (int32_t)(oh0 * st) - 1;                        // image row of frame row 0
         const int32_t r_lo = ih_first < 0 ? -ih_first : 0;
         const int32_t r_hi = min((int32_t)n_ih, (int32_t)ih_n - ih_first);       // frame rows [r_lo, r_hi) lie inside the image
-        gptr_t src = (gptr_t)((const T*)a.act_in + (size_t)(seg0 + req) * a.S) + (size_t)(ih_first + r_lo) * cpr;
+        gptr_t src = (gptr_t)((const T*)act_of(a.act, L.in_buf) + (size_t)(seg0 + req) * a.S) + (size_t)(ih_first + r_lo) * cpr;
         const uint32_t n_chunks = (uint32_t)(r_hi - r_lo) * cpr;                 // contiguous in memory
         uint8_t* dst = img + i * SUB + (uint32_t)r_lo * RSB + PB;                // first pixel slot after the left border
         for (uint32_t q0 = 0; q0 < n_chunks; q0 += NB * 256) {                   // NB loads in flight per lane
@@ -601,7 +609,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
         if (m < rows_total) {
             uint32_t req, pix;
             divmod_uniform(m, rpr, &req, &pix);
-            out = (T*)a.act_out + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N + nbase;
+            out = (T*)act_of(a.act, L.out_buf) + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N + nbase;
         }
         f32x4 y[4];
 #pragma unroll

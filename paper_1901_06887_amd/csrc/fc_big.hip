@@ -61,7 +61,7 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     // 8 weight column blocks, BPW blocks each (blocks past the tile or the layer repeat the last valid one)
     const u32x4* lp[BPW];
     {
-        const u32x4* xbase = (const u32x4*)((const T*)a.act_in + (size_t)seg0 * a.S) + lane;
+        const u32x4* xbase = (const u32x4*)((const T*)act_of(a.act, L.in_buf) + (size_t)seg0 * a.S) + lane;
         const u32x4* wbase = (const u32x4*)(a.arena + L.w_off) + lane;
 #pragma unroll
         for (uint32_t i = 0; i < BPW; ++i) {
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
                         if (nl + 8 * g < L.N) *(f32x4*)(row + nl + 8 * g) = y[g];                 // starts below N at a multiple of 4, so it ends inside the row's C_pad = round_up(classes, 4) floats
                 }
             } else {
-                u32x4* out = (u32x4*)((T*)a.act_out + (size_t)seg0 * a.S) +
+                u32x4* out = (u32x4*)((T*)act_of(a.act, L.out_buf) + (size_t)seg0 * a.S) +
                              ((size_t)(mb / kBrickRows) * nKB_out + nb * (kBrickRows / KB)) * 64 + lane;
                 // outputs past N need no masking: their weight rows and bias are zero padding, and
                 // every activation of the layer set maps 0 to 0

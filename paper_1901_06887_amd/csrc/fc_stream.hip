@@ -41,7 +41,7 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
     const uint32_t nb_eff = active ? nb : 0;                 // idle waves still help staging; they stream block 0 and drop it
     const u32x4* wp = (const u32x4*)(a.arena + L.w_off) + (size_t)nb_eff * nKB * 64 + lane;
-    const u32x4* xbase = (const u32x4*)((const T*)a.act_in + (size_t)seg0 * a.S) + lane;
+    const u32x4* xbase = (const u32x4*)((const T*)act_of(a.act, L.in_buf) + (size_t)seg0 * a.S) + lane;
 
     // this wave stages bricks q = 4*wave .. 4*wave+3 of every chunk: row block q / KC, k step q % KC
     const u32x4* xsrc[4]; uint32_t xkk[4];
@@ -147,7 +147,7 @@ __device__ __forceinline__ void fc_accumulate_direct(const GemmArgs& a, const Ti
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
     const uint32_t cnt = nKB / ks, kb0 = kq * cnt;
     const u32x4* wp = (const u32x4*)(a.arena + L.w_off) + ((size_t)nb * nKB + kb0) * 64 + lane;
-    const u32x4* xbase = (const u32x4*)((const T*)a.act_in + (size_t)seg0 * a.S) + lane;
+    const u32x4* xbase = (const u32x4*)((const T*)act_of(a.act, L.in_buf) + (size_t)seg0 * a.S) + lane;
     const u32x4* xp[RB];
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
@@ -379,7 +379,7 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
     constexpr uint32_t TRS = 32 * sizeof(T) + 16;
     uint8_t* trw = tr + wave * kTrBytes;
     const uint32_t nKB_out = L.out_fill / KB;
-    u32x4* obase = (u32x4*)((T*)a.act_out + (size_t)seg0 * a.S) + lane;
+    u32x4* obase = (u32x4*)((T*)act_of(a.act, L.out_buf) + (size_t)seg0 * a.S) + lane;
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
         __syncthreads();

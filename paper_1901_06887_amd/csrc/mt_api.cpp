@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
+#include <cmath>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -30,8 +31,9 @@ constexpr uint32_t kMaxRunSlots = 4;      // runs in flight at once (each with i
 constexpr uint64_t kArenaAlign = 256;
 // profiling slots: batcher, gather, head, then gemm and gap of every layer index
 constexpr uint32_t kProfBatcher = 0, kProfGather = 1, kProfHead = 2, kProfFc = 3, kProfConv = 3 + MT_MAX_LAYERS,
-                   kProfGap = 3 + 2 * MT_MAX_LAYERS, kProfBig = 3 + 3 * MT_MAX_LAYERS, kProfGatherImg = 3 + 4 * MT_MAX_LAYERS;
-constexpr uint32_t kProfSlots = 4 + 4 * MT_MAX_LAYERS;
+                   kProfGap = 3 + 2 * MT_MAX_LAYERS, kProfBig = 3 + 3 * MT_MAX_LAYERS, kProfGatherImg = 3 + 4 * MT_MAX_LAYERS,
+                   kProfImageOps = 4 + 4 * MT_MAX_LAYERS;
+constexpr uint32_t kProfSlots = 4 + 5 * MT_MAX_LAYERS;
 
 inline uint32_t round_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }
 inline uint64_t round_up64(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
@@ -49,6 +51,7 @@ struct HostTenant {
     HostLayer layers[MT_MAX_LAYERS];
     TenantDev dev{};
     uint64_t arena_off = 0, arena_len = 0;
+    uint32_t act_buffers = 2;   // activation buffers a run needs for this model (two for a chain)
     // Model cache (cfg.cache): the packed weights stay in pinned host memory (`stage`: the arena
     // image followed by the device table rows of this tenant) and the arena holds the models used
     // most recently.  Outside cache mode every registered model is resident and stage is null.
@@ -65,7 +68,7 @@ struct RunSlot {
     int32_t* d_row_tenant = nullptr; uint32_t* d_row_rank = nullptr; uint32_t* d_hist_g = nullptr;
     const void** d_row_src = nullptr; int32_t* d_pos_of = nullptr; int32_t* d_perm = nullptr;
     uint32_t* d_M = nullptr; uint32_t* d_off = nullptr; uint32_t* d_tile_base = nullptr;
-    void* d_act[2] = {nullptr, nullptr}; float* d_logits = nullptr;
+    void* d_act[kActBuffers] = {}; float* d_logits = nullptr;   // (only as many activation buffers as the registered models need)
     hipEvent_t done = nullptr;      // recorded behind the slot's last run
     hipStream_t stream = nullptr;   // ... which was enqueued here
     uint64_t last_run = 0;          // ... and was the context's run number this
@@ -109,7 +112,9 @@ struct mt_ctx {
     uint32_t no_fused_gather = 0;  // tuning/testing: always stage FC inputs with the gather kernel
     bool fc_first_chunked = true;  // every registered FC-first model's input is a whole number of 16-byte chunks
     bool any_conv_first = false, any_fc_first = false;
-    uint32_t list_mask = 0;        // bit kind*MT_MAX_LAYERS + l: some registered model has that kind at layer l
+    uint32_t list_mask[MT_MAX_LAYERS / kLayerGroup] = {};   // per group of layer indices, bit kind*kLayerGroup + l%kLayerGroup: some registered model has that kind at layer l
+    uint32_t has_image_ops[MT_MAX_LAYERS]{};   // some registered model has a max-pool or an addition at this layer index
+    uint32_t act_buffers = 2;      // activation buffers every run slot holds (grows when a model with skip connections needs more)
     uint32_t max_reg_classes = 0, min_reg_classes = 0;
     uint32_t no_fused_head = 0;    // tuning/testing: always run the separate head kernel
     uint32_t no_fused_pool = 0;    // tuning/testing: always run the separate pooling kernel
@@ -136,7 +141,7 @@ struct mt_ctx {
     uint32_t* d_off = nullptr;
     void* d_zeros = nullptr;           // 256 bytes of zeros: where masked operand loads point instead of branching
     uint32_t* d_tile_base = nullptr;   // [kListKinds][MT_MAX_LAYERS][T+1]: FC, conv and big-FC arrays, then one word: the big-tile layer mask
-    void* d_act[2] = {nullptr, nullptr};
+    void* d_act[kActBuffers] = {};
     float* d_logits = nullptr;
     Segment* h_segs[kSegSlots] = {};    // pinned, device-visible
     Segment* d_segs[kSegSlots] = {};    // device addresses of the same memory
@@ -184,7 +189,8 @@ void bind_slot(mt_ctx* c, const RunSlot& r)
 {
     c->d_row_tenant = r.d_row_tenant; c->d_row_rank = r.d_row_rank; c->d_hist_g = r.d_hist_g; c->d_row_src = r.d_row_src;
     c->d_pos_of = r.d_pos_of; c->d_perm = r.d_perm; c->d_M = r.d_M; c->d_off = r.d_off; c->d_tile_base = r.d_tile_base;
-    c->d_act[0] = r.d_act[0]; c->d_act[1] = r.d_act[1]; c->d_logits = r.d_logits;
+    for (int i = 0; i < kActBuffers; ++i) c->d_act[i] = r.d_act[i];
+    c->d_logits = r.d_logits;
 }
 
 #define HIP_TRY(c, expr)                                                                    \
@@ -265,20 +271,27 @@ size_t stage_bytes(uint64_t arena_len) { return stage_tail_offset(arena_len) + s
 // A tenant's rows of the three device tables travel inside kernel arguments: the runtime copies
 // those when the launch is enqueued, so the host may change its copy (a later placement of the same
 // model at another arena offset) while this one is still queued behind earlier work.  An asynchronous
-// copy from the host block would read it only when it executes.  The tenant row goes last, after a
-// fence: a tenant that the batcher sees has its layer rows in place.
-__global__ void install_rows_kernel(StageTail tail, LayerDev* rows, uint32_t* facts, TenantDev* td)
+// copy from the host block would read it only when it executes.  Kernel arguments are limited to a
+// few kilobytes, so the layer rows go in pieces of kLayerGroup layers; the tenant row goes with the
+// last piece, after a fence: a tenant that the batcher sees has its layer rows in place.
+struct RowsPiece {
+    LayerDev rows[kLayerGroup];
+    uint32_t facts[kLayerGroup][2];
+    TenantDev td;
+};
+static_assert(sizeof(RowsPiece) <= 2048, "a piece of a tenant's table rows must fit kernel arguments");
+__global__ void install_rows_kernel(RowsPiece piece, LayerDev* rows, uint32_t* facts, TenantDev* td)
 {
-    const uint32_t* src_rows = (const uint32_t*)tail.rows;
-    for (uint32_t i = threadIdx.x; i < sizeof(tail.rows) / 4; i += blockDim.x) ((uint32_t*)rows)[i] = src_rows[i];
-    const uint32_t* src_facts = &tail.facts[0][0];
-    for (uint32_t i = threadIdx.x; i < sizeof(tail.facts) / 4; i += blockDim.x) facts[i] = src_facts[i];
+    const uint32_t* src_rows = (const uint32_t*)piece.rows;
+    for (uint32_t i = threadIdx.x; i < sizeof(piece.rows) / 4; i += blockDim.x) ((uint32_t*)rows)[i] = src_rows[i];
+    const uint32_t* src_facts = &piece.facts[0][0];
+    for (uint32_t i = threadIdx.x; i < sizeof(piece.facts) / 4; i += blockDim.x) facts[i] = src_facts[i];
+    if (!td) return;
     __threadfence();
     __syncthreads();
-    const uint32_t* src_td = (const uint32_t*)&tail.td;
-    for (uint32_t i = threadIdx.x; i < sizeof(tail.td) / 4; i += blockDim.x) ((uint32_t*)td)[i] = src_td[i];
+    const uint32_t* src_td = (const uint32_t*)&piece.td;
+    for (uint32_t i = threadIdx.x; i < sizeof(piece.td) / 4; i += blockDim.x) ((uint32_t*)td)[i] = src_td[i];
 }
-static_assert(sizeof(StageTail) <= 2048, "the table rows of one tenant must fit kernel arguments");
 
 hipError_t install_rows(mt_ctx* c, uint32_t tenant, const StageTail& tail, hipStream_t s);
 
@@ -299,9 +312,20 @@ void place_tenant(const mt_ctx* c, HostTenant& ht, uint64_t off, uint8_t* stage)
 
 hipError_t install_rows(mt_ctx* c, uint32_t tenant, const StageTail& tail, hipStream_t s)
 {
-    hipLaunchKernelGGL(install_rows_kernel, dim3(1), dim3(256), 0, s, tail, c->d_layers + (size_t)tenant * MT_MAX_LAYERS,
-                       c->d_facts + (size_t)tenant * 2 * MT_MAX_LAYERS, c->d_tenants + tenant);
-    return hipGetLastError();
+    // a tenant that disappears (n_layers 0) loses its tenant row first, in the first piece
+    const uint32_t n_pieces = tail.td.registered ? (tail.td.n_layers + kLayerGroup - 1) / kLayerGroup : MT_MAX_LAYERS / kLayerGroup;
+    for (uint32_t g = 0; g < n_pieces; ++g) {
+        RowsPiece piece;
+        std::memcpy(piece.rows, tail.rows + g * kLayerGroup, sizeof piece.rows);
+        std::memcpy(piece.facts, tail.facts + g * kLayerGroup, sizeof piece.facts);
+        piece.td = tail.td;
+        const bool with_td = tail.td.registered ? g + 1 == n_pieces : g == 0;
+        hipLaunchKernelGGL(install_rows_kernel, dim3(1), dim3(256), 0, s, piece, c->d_layers + (size_t)tenant * MT_MAX_LAYERS + g * kLayerGroup,
+                           c->d_facts + ((size_t)tenant * MT_MAX_LAYERS + g * kLayerGroup) * 2, with_td ? c->d_tenants + tenant : nullptr);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // Copy a placed tenant's weights and table rows to the device: on `s` without waiting (the arena
@@ -368,9 +392,10 @@ void recompute_bounds(mt_ctx* c)
     c->n_layer_slots = 0;
     c->max_in_len = 0;
     c->fc_first_chunked = true; c->any_conv_first = c->any_fc_first = false;
-    c->list_mask = 0; c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
+    for (uint32_t& m : c->list_mask) m = 0;
+    c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        c->has_gap[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
+        c->has_gap[l] = 0; c->has_image_ops[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
         c->max_fc_per64[l] = 0; c->max_fc_per64_sk[l] = 0; c->sum_nt_sk[l] = 0;
     }
@@ -389,9 +414,10 @@ void recompute_bounds(mt_ctx* c)
         for (uint32_t l = 0; l < t.n_layers; ++l) {
             const LayerDev& L = t.layers[l].dev;
             if (L.kind == MT_GAP) { c->has_gap[l] = 1; continue; }
+            if (L.kind == MT_MAXPOOL || L.kind == MT_ADD) { c->has_image_ops[l] = 1; continue; }
             const int k = L.kind == MT_FC ? 0 : 1;
             c->sum_macs += (double)L.k_valid * L.N * L.rows_per_req;
-            c->list_mask |= 1u << (k * MT_MAX_LAYERS + l);
+            c->list_mask[l / kLayerGroup] |= 1u << (k * kLayerGroup + l % kLayerGroup);
             const uint32_t nt = k == 0 ? fc_groups(L.N_pad, c->fc_split_k) : (L.N + kTileCols - 1) / kTileCols;
             c->max_rpr[k][l] = std::max(c->max_rpr[k][l], L.rows_per_req);
             c->max_nt[k][l] = std::max(c->max_nt[k][l], nt);
@@ -412,7 +438,7 @@ void recompute_bounds(mt_ctx* c)
                 const uint32_t ni = rpr >= (uint32_t)kConvTileRows ? 1 : kConvTileRows / std::max(rpr, 1u);
                 uint64_t frame = 0;
                 const bool chunk_pixel = L.cin * c->elem_size == 16;            // a pixel is one 16-byte chunk: two taps per k step, no padding
-                if (whole && ni <= 8 && (L.cin % kb == 0 || chunk_pixel)) {
+                if (whole && ni <= 8 && (L.cin % kb == 0 || chunk_pixel) && L.ksize == 3 && L.pad == 1) {     // (that kernel is written for 3x3 windows)
                     const uint32_t n_oh = kConvTileRows / ni / L.out_w, n_ih = (n_oh - 1) * L.stride + 3;
                     frame = (uint64_t)ni * n_ih * (L.in_w + 2) * (L.cin * c->elem_size + (chunk_pixel ? 0 : 16));
                 }
@@ -420,8 +446,8 @@ void recompute_bounds(mt_ctx* c)
                 if (frame == 0 || frame > 49152 || c->conv_img_lds[l] == 0 || c->conv_img_two[l] != (int)chunk_pixel) c->conv_img_lds[l] = 0;
                 else c->conv_img_lds[l] = std::max<uint32_t>(c->conv_img_lds[l], (uint32_t)frame);
             }
-            if (k == 0 && L.N_pad >= (uint32_t)kBigMinCols) {      // may be served with big tiles when it gets enough rows
-                c->list_mask |= 1u << (2 * MT_MAX_LAYERS + l);
+            if (k == 0 && L.N_pad >= (uint32_t)kBigMinCols && l < (uint32_t)kBigMaxLayer) {      // may be served with big tiles when it gets enough rows
+                c->list_mask[l / kLayerGroup] |= 1u << (2 * kLayerGroup + l % kLayerGroup);
                 c->max_nt[2][l] = std::max(c->max_nt[2][l], (L.N_pad + kBigTile - 1) / kBigTile);
             }
         }
@@ -473,9 +499,13 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
     if (n_layers == 0 || n_layers > MT_MAX_LAYERS)
         return fail(c, MT_EUNSUPPORTED, "a model needs 1..%d layers, got %u", MT_MAX_LAYERS, n_layers);
     const uint32_t es = c->elem_size;
-    uint32_t prev_out = 0;
     out->n_layers = n_layers;
     out->dev = TenantDev{};
+    // Values: 0 is the request, l + 1 the output of layer l.  A layer reads the value before it unless
+    // its spec names another one (skip connections); shape[] is what every value looks like.
+    struct Shape { uint32_t h, w, ch, len; bool image; };
+    Shape shape[MT_MAX_LAYERS + 1] = {};
+    uint32_t src_of[MT_MAX_LAYERS] = {}, src2_of[MT_MAX_LAYERS] = {}, last_use[MT_MAX_LAYERS + 1] = {};
     for (uint32_t l = 0; l < n_layers; ++l) {
         const mt_layer_spec& s = specs[l];
         HostLayer& hl = out->layers[l];
@@ -485,50 +515,86 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
         d.stride = 1; d.out_w = 1; d.rows_per_req = 1;
         if (s.act > MT_ACT_GELU) return fail(c, MT_EUNSUPPORTED, "layer %u: activation %u is not in the supported set", l, s.act);
         if (d.is_last && s.act != MT_ACT_NONE) return fail(c, MT_EUNSUPPORTED, "layer %u: the last layer yields logits and takes no activation", l);
-        uint32_t in_len = 0;
+        if (s.src > l || s.src2 > l) return fail(c, MT_EUNSUPPORTED, "layer %u: a layer can only read outputs of earlier layers", l);
+        if (s.src2 != 0 && s.kind != MT_ADD) return fail(c, MT_EUNSUPPORTED, "layer %u: only an addition takes a second source", l);
+        const uint32_t src = s.src ? s.src : l;              // value read: the named one, else the one before this layer
+        src_of[l] = src; last_use[src] = l;
+        const Shape in = shape[src];                         // (undefined for the request: the first layer defines it)
+        const bool first = l == 0;
+        const bool image_kind = s.kind == MT_CONV2D || s.kind == MT_GAP || s.kind == MT_MAXPOOL || s.kind == MT_ADD;
+        if (image_kind) {
+            if (s.in_features == 0 || s.in_h == 0 || s.in_w == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized image", l);
+            if ((uint64_t)s.in_h * s.in_w * s.in_features > 0x7fffffffu) return fail(c, MT_EUNSUPPORTED, "layer %u: image too large", l);
+            if (!first && (!in.image || in.h != s.in_h || in.w != s.in_w || in.ch != s.in_features))
+                return fail(c, MT_EUNSUPPORTED, "layer %u takes a %ux%ux%u image but its source yields %s of %u values", l, s.in_h, s.in_w, s.in_features,
+                            in.image ? "another image" : "a vector", in.len);
+            if (d.is_last) return fail(c, MT_EUNSUPPORTED, "layer %u: the last layer must be fully connected", l);
+        }
+        Shape o{};
         if (s.kind == MT_FC) {
             if (s.in_features == 0 || s.out_features == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized FC", l);
-            if (l > 0 && specs[l - 1].kind == MT_CONV2D)
-                return fail(c, MT_EUNSUPPORTED, "layer %u: an FC layer cannot read a convolution's output directly; pool first", l);
-            in_len = s.in_features;
+            if (!first && in.image)
+                return fail(c, MT_EUNSUPPORTED, "layer %u: an FC layer cannot read an image directly; pool first", l);
+            if (!first && in.len != s.in_features) return fail(c, MT_EUNSUPPORTED, "layer %u takes %u values but its source yields %u", l, s.in_features, in.len);
             d.K = round_up(s.in_features, kWidthAlign); d.k_valid = s.in_features; d.N = s.out_features;
             d.N_pad = round_up(s.out_features, d.is_last ? kBrickRows : kWidthAlign);
             d.out_len = s.out_features;
             hl.w_bytes = (uint64_t)d.N_pad * d.K * es; hl.b_bytes = (uint64_t)d.N_pad * 4;
+            o = Shape{1, 1, s.out_features, s.out_features, false};
         } else if (s.kind == MT_CONV2D) {
-            if (s.kh != 3 || s.kw != 3 || s.pad != 1 || (s.stride != 1 && s.stride != 2))
-                return fail(c, MT_EUNSUPPORTED, "layer %u: only 3x3 convolutions with pad 1 and stride 1 or 2 are supported", l);
-            if (s.in_features == 0 || s.out_features == 0 || s.in_h == 0 || s.in_w == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized conv", l);
-            if (d.is_last) return fail(c, MT_EUNSUPPORTED, "layer %u: the last layer must be fully connected", l);
+            if (s.kh != s.kw || (s.kh != 1 && s.kh != 3 && s.kh != 7) || s.pad != (s.kh - 1) / 2 || (s.stride != 1 && s.stride != 2))
+                return fail(c, MT_EUNSUPPORTED, "layer %u: convolutions are 1x1, 3x3 or 7x7 with pad (k - 1) / 2 and stride 1 or 2", l);
+            if (s.out_features == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized conv", l);
             if (s.out_features % kChanPad) return fail(c, MT_EUNSUPPORTED, "layer %u: conv output channels must be a multiple of %d", l, kChanPad);
-            if (l > 0 && s.in_features % kChanPad) return fail(c, MT_EUNSUPPORTED, "layer %u: conv input channels must be a multiple of %d past the first layer", l, kChanPad);
-            in_len = s.in_h * s.in_w * s.in_features;
-            const uint32_t oh = (s.in_h + 2 - 3) / s.stride + 1, ow = (s.in_w + 2 - 3) / s.stride + 1;
+            if (!first && s.in_features % kChanPad) return fail(c, MT_EUNSUPPORTED, "layer %u: conv input channels must be a multiple of %d past the first layer", l, kChanPad);
+            const uint32_t oh = (s.in_h + 2 * s.pad - s.kh) / s.stride + 1, ow = (s.in_w + 2 * s.pad - s.kw) / s.stride + 1;
             d.cin = round_up(s.in_features, kChanPad);
-            d.in_h = s.in_h; d.in_w = s.in_w; d.stride = s.stride; d.out_w = ow;
+            d.in_h = s.in_h; d.in_w = s.in_w; d.stride = s.stride; d.out_w = ow; d.ksize = s.kh; d.pad = s.pad;
             d.rows_per_req = oh * ow;
-            d.K = round_up(9 * d.cin, kWidthAlign); d.k_valid = 9 * d.cin; d.N = s.out_features; d.N_pad = round_up(s.out_features, kBrickRows);
+            d.K = round_up(s.kh * s.kw * d.cin, kWidthAlign); d.k_valid = s.kh * s.kw * d.cin; d.N = s.out_features; d.N_pad = round_up(s.out_features, kBrickRows);
             d.out_len = oh * ow * s.out_features;
             hl.w_bytes = (uint64_t)d.N_pad * d.K * es; hl.b_bytes = (uint64_t)d.N_pad * 4;
+            o = Shape{oh, ow, s.out_features, d.out_len, true};
         } else if (s.kind == MT_GAP) {
-            if (s.in_features == 0 || s.in_h == 0 || s.in_w == 0) return fail(c, MT_EINVAL, "layer %u: zero-sized pool", l);
             if (s.out_features != s.in_features || s.act != MT_ACT_NONE) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling keeps the channel count and has no activation", l);
-            if (d.is_last || l == 0) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling cannot be the first or the last layer", l);
-            in_len = s.in_h * s.in_w * s.in_features;
-            if (specs[l - 1].kind != MT_CONV2D) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling must follow a convolution", l);
+            if (first) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling cannot be the first layer", l);
             d.cin = s.in_features; d.in_h = s.in_h; d.in_w = s.in_w; d.N = s.in_features; d.N_pad = s.in_features;
             d.out_len = s.in_features;
             hl.w_bytes = hl.b_bytes = 0;
-            // the convolution before it can pool by itself when every image lies inside one wave's pixel blocks
-            LayerDev& conv = out->layers[l - 1].dev;
-            if (conv.N % kWidthAlign == 0 && (conv.rows_per_req == kBrickRows || conv.rows_per_req == 2 * kBrickRows))
-                conv.pool_fill = round_up(s.in_features, kWidthAlign);
+            o = Shape{1, 1, s.in_features, s.in_features, false};
+        } else if (s.kind == MT_MAXPOOL) {
+            if (s.kh != s.kw || (s.kh != 2 && s.kh != 3) || s.pad > 1 || s.pad >= s.kh || (s.stride != 1 && s.stride != 2))
+                return fail(c, MT_EUNSUPPORTED, "layer %u: max-pooling takes 2x2 or 3x3 windows, pad 0 or 1, stride 1 or 2", l);
+            if (s.out_features != s.in_features || s.act != MT_ACT_NONE) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling keeps the channel count and has no activation", l);
+            if (first) return fail(c, MT_EUNSUPPORTED, "layer %u: pooling cannot be the first layer", l);
+            if (s.in_h + 2 * s.pad < s.kh || s.in_w + 2 * s.pad < s.kw) return fail(c, MT_EUNSUPPORTED, "layer %u: the window exceeds the image", l);
+            const uint32_t oh = (s.in_h + 2 * s.pad - s.kh) / s.stride + 1, ow = (s.in_w + 2 * s.pad - s.kw) / s.stride + 1;
+            d.cin = s.in_features; d.in_h = s.in_h; d.in_w = s.in_w; d.stride = s.stride; d.out_w = ow; d.ksize = s.kh; d.pad = s.pad;
+            d.rows_per_req = oh * ow; d.N = s.in_features; d.N_pad = s.in_features;
+            d.out_len = oh * ow * s.in_features;
+            hl.w_bytes = hl.b_bytes = 0;
+            o = Shape{oh, ow, s.in_features, d.out_len, true};
+        } else if (s.kind == MT_ADD) {
+            if (first || s.src2 == 0) return fail(c, MT_EUNSUPPORTED, "layer %u: an addition names its second source and cannot be the first layer", l);
+            if (s.out_features != s.in_features) return fail(c, MT_EUNSUPPORTED, "layer %u: an addition keeps the channel count", l);
+            const Shape in2 = shape[s.src2];
+            if (!in2.image || in2.h != s.in_h || in2.w != s.in_w || in2.ch != s.in_features)
+                return fail(c, MT_EUNSUPPORTED, "layer %u: the second source is not a %ux%ux%u image", l, s.in_h, s.in_w, s.in_features);
+            src2_of[l] = s.src2; last_use[s.src2] = l;
+            d.cin = s.in_features; d.in_h = s.in_h; d.in_w = s.in_w; d.out_w = s.in_w; d.rows_per_req = s.in_h * s.in_w;
+            d.N = s.in_features; d.N_pad = s.in_features;
+            d.out_len = s.in_h * s.in_w * s.in_features;
+            hl.w_bytes = hl.b_bytes = 0;
+            o = Shape{s.in_h, s.in_w, s.in_features, d.out_len, true};
         } else {
             return fail(c, MT_EUNSUPPORTED, "layer %u: kind %u is not in the supported set", l, s.kind);
         }
-        if (l > 0 && in_len != prev_out) return fail(c, MT_EUNSUPPORTED, "layer %u takes %u values but layer %u yields %u", l, in_len, l - 1, prev_out);
+        if (s.kind != MT_FC && s.in_features % kChanPad && !(first && s.kind == MT_CONV2D))
+            return fail(c, MT_EUNSUPPORTED, "layer %u: image channels must be a multiple of %d", l, kChanPad);
+        shape[l + 1] = o;
         d.out_fill = round_up(d.out_len, kWidthAlign);
-        if (l == 0) {
+        if (first) {
+            const uint32_t in_len = s.kind == MT_FC ? s.in_features : s.in_h * s.in_w * s.in_features;
             out->dev.in_len = in_len;
             uint32_t staged = in_len;
             if (s.kind == MT_CONV2D && d.cin != s.in_features) {
@@ -542,18 +608,51 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
         if (!d.is_last && d.out_fill > c->S) return fail(c, MT_EUNSUPPORTED, "layer %u output of %u values exceeds max_width", l, d.out_len);
         if (s.kind == MT_FC && d.K > c->S) return fail(c, MT_EUNSUPPORTED, "layer %u fan-in %u exceeds max_width", l, s.in_features);
         if (d.is_last && d.out_len > c->cfg.max_classes) return fail(c, MT_EUNSUPPORTED, "%u classes exceed max_classes", d.out_len);
-        prev_out = d.out_len;
         hl.dev = d;
     }
     out->dev.n_layers = n_layers;
-    out->dev.n_classes = prev_out;
+    out->dev.n_classes = shape[n_layers].len;
+
+    // A convolution whose output goes to a global average pool and nowhere else can pool by itself
+    // when every image lies inside one wave's pixel blocks; its input then has to outlive the pooling
+    // layer's index, because the pooled activation is written where that layer would have written it.
+    for (uint32_t l = 1; l < n_layers; ++l) {
+        if (out->layers[l].dev.kind != MT_GAP || src_of[l] != l || out->layers[l - 1].dev.kind != MT_CONV2D) continue;
+        LayerDev& conv = out->layers[l - 1].dev;
+        last_use[src_of[l - 1]] = std::max(last_use[src_of[l - 1]], l);
+        if (conv.N % kWidthAlign == 0 && (conv.rows_per_req == kBrickRows || conv.rows_per_req == 2 * kBrickRows) && last_use[l] == l)
+            conv.pool_fill = round_up(out->layers[l].dev.N, kWidthAlign);
+    }
+    // Activation buffers: the request sits in buffer 0; a layer writes the lowest-numbered buffer that
+    // holds no value still to be read at or after its index (its own inputs included).  A plain chain
+    // alternates between two buffers.
+    uint32_t buf_of[MT_MAX_LAYERS + 1] = {};
+    out->act_buffers = 1;
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        LayerDev& d = out->layers[l].dev;
+        d.in_buf = buf_of[src_of[l]];
+        d.in2_buf = d.kind == MT_ADD ? buf_of[src2_of[l]] : 0;
+        if (d.is_last) break;                                 // logits have a buffer of their own
+        uint32_t pick = kActBuffers;
+        for (uint32_t b = 0; b < (uint32_t)kActBuffers && pick == (uint32_t)kActBuffers; ++b) {
+            bool busy = false;
+            for (uint32_t v = 0; v <= l; ++v) busy = busy || (buf_of[v] == b && last_use[v] >= l);
+            if (!busy) pick = b;
+        }
+        if (pick == (uint32_t)kActBuffers)
+            return fail(c, MT_EUNSUPPORTED, "layer %u: more than %d layer outputs are alive at once", l, kActBuffers);
+        buf_of[l + 1] = pick; d.out_buf = pick;
+        out->act_buffers = std::max(out->act_buffers, pick + 1);
+    }
+    for (uint32_t l = 0; l + 1 < n_layers; ++l)
+        if (out->layers[l].dev.pool_fill) out->layers[l].dev.pool_buf = out->layers[l + 1].dev.out_buf;
     return MT_OK;
 }
 
 // Arena image of one layer: bricks[n_block][k_block][lane][EPC] with lane = row + 32*half (zero
 // rows and columns as padding), the order in which a wavefront consumes MFMA operands.  The
-// reduction index k is the fan-in for FC; for conv the filters [Co][Ci][3][3] are read as
-// k = (kh*3 + kw) * ci_padded + ci, so that a GEMM k index walks the NHWC input contiguously.
+// reduction index k is the fan-in for FC; for conv the filters [Co][Ci][kh][kw] are read as
+// k = (kh*ksize + kw) * ci_padded + ci, so that a GEMM k index walks the NHWC input contiguously.
 template <typename T>
 void pack_weights(const HostLayer& hl, const void* w_src, uint8_t* dst)
 {
@@ -572,12 +671,67 @@ void pack_weights(const HostLayer& hl, const void* w_src, uint8_t* dst)
         for (uint32_t n = 0; n < d.N; ++n)
             for (uint32_t k = 0; k < K; ++k) put(n, k, src[(size_t)n * K + k]);
     } else {
-        const uint32_t Ci = hl.spec.in_features;
+        const uint32_t Ci = hl.spec.in_features, ks = d.ksize;
         for (uint32_t co = 0; co < d.N; ++co)
             for (uint32_t ci = 0; ci < Ci; ++ci)
-                for (uint32_t kh = 0; kh < 3; ++kh)
-                    for (uint32_t kw = 0; kw < 3; ++kw)
-                        put(co, (kh * 3 + kw) * d.cin + ci, src[(((size_t)co * Ci + ci) * 3 + kh) * 3 + kw]);
+                for (uint32_t kh = 0; kh < ks; ++kh)
+                    for (uint32_t kw = 0; kw < ks; ++kw)
+                        put(co, (kh * ks + kw) * d.cin + ci, src[(((size_t)co * Ci + ci) * ks + kh) * ks + kw]);
+    }
+}
+
+// ---- batch normalisation folded into the convolution in front of it ---------------------------
+// Nearest-even rounding of a double to bfloat16 (bit pattern), done on the bits of the double so
+// that the value is rounded once: sign, 8 exponent bits, 7 fraction bits; results below 2^-126
+// are subnormal (spacing 2^-133), results beyond the largest finite value become infinity.
+uint16_t bf16_bits_from_double(double x)
+{
+    uint64_t u; std::memcpy(&u, &x, 8);
+    const uint16_t sign = (uint16_t)((u >> 63) << 15);
+    const int64_t e = (int64_t)((u >> 52) & 0x7ff) - 1023;
+    const uint64_t frac = u & ((1ull << 52) - 1);
+    if (((u >> 52) & 0x7ff) == 0x7ff) return (uint16_t)(sign | 0x7f80 | (frac ? 0x40 : 0));       // infinity / NaN
+    if (((u >> 52) & 0x7ff) == 0 || e < -140) return sign;                                        // zero, or far below half the smallest subnormal
+    const uint64_t mant = (1ull << 52) | frac;                       // value = mant * 2^(e - 52)
+    // keep 7 fraction bits of a normal result; a result below 2^-126 keeps fewer: its last place is 2^-133
+    const int shift = e >= -126 ? 45 : (int)(45 + (-126 - e));
+    uint64_t kept = mant >> shift;
+    const uint64_t rem = mant & ((1ull << shift) - 1), half = 1ull << (shift - 1);
+    if (rem > half || (rem == half && (kept & 1))) ++kept;
+    if (e >= -126) {
+        int64_t be = e + 127;                                        // biased exponent; kept holds the hidden bit (128..256)
+        if (kept == 256) { kept = 128; ++be; }
+        if (be >= 255) return (uint16_t)(sign | 0x7f80);
+        return (uint16_t)(sign | (uint16_t)(be << 7) | (uint16_t)(kept - 128));
+    }
+    return (uint16_t)(sign | (uint16_t)kept);                        // subnormal; kept == 128 is the smallest normal number
+}
+
+// W' = round(W * s), b' = float((b - mean) * s + beta) with s = gamma / sqrt(var + eps), per output
+// channel, in double precision, each rounded once (no fused multiply-add: the products are rounded
+// to double before the sums).  `w` holds the layer's filters [Co][per] in the context's element
+// type and is folded in place; `b` its fp32 bias [Co].
+#pragma clang fp contract(off)
+void fold_batchnorm(uint32_t elem_size, void* w, float* b, uint32_t Co, size_t per, const float* bn, double eps)
+{
+    const float *gamma = bn, *beta = bn + Co, *mean = bn + 2 * (size_t)Co, *var = bn + 3 * (size_t)Co;
+    for (uint32_t c = 0; c < Co; ++c) {
+        const double s = (double)gamma[c] / std::sqrt((double)var[c] + eps);
+        if (elem_size == 2) {
+            uint16_t* row = (uint16_t*)w + c * per;
+            for (size_t i = 0; i < per; ++i) {
+                const uint32_t wide = (uint32_t)row[i] << 16;
+                float f; std::memcpy(&f, &wide, 4);
+                const double prod = (double)f * s;
+                row[i] = bf16_bits_from_double(prod);
+            }
+        } else {
+            float* row = (float*)w + c * per;
+            for (size_t i = 0; i < per; ++i) { const double prod = (double)row[i] * s; row[i] = (float)prod; }
+        }
+        const double shifted = ((double)b[c] - (double)mean[c]) * s;
+        const double sum = shifted + (double)beta[c];
+        b[c] = (float)sum;
     }
 }
 
@@ -661,7 +815,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
         CREATE_TRY(hipMalloc((void**)&r.d_off, (T + 1) * 4));
         CREATE_TRY(hipMalloc((void**)&r.d_tile_base, (kListKinds * MT_MAX_LAYERS * (T + 1) + 1) * 4));
         CREATE_TRY(hipMemset(r.d_tile_base, 0, (kListKinds * MT_MAX_LAYERS * (T + 1) + 1) * 4));
-        for (int i = 0; i < 2; ++i) {
+        for (uint32_t i = 0; i < c->act_buffers; ++i) {
             CREATE_TRY(hipMalloc(&r.d_act[i], (uint64_t)c->P_cap * c->S * c->elem_size));
         }
         CREATE_TRY(hipMalloc((void**)&r.d_logits, (uint64_t)c->P_cap * c->C_pad * 4));
@@ -692,7 +846,8 @@ mt_status mt_destroy(mt_ctx* c)
         for (void* p : bufs) if (p) (void)hipFree(p);
         for (RunSlot& r : c->slots) {
             void* rb[] = {r.d_row_tenant, r.d_row_rank, r.d_hist_g, (void*)r.d_row_src, r.d_pos_of, r.d_perm, r.d_M, r.d_off, r.d_tile_base,
-                          r.d_act[0], r.d_act[1], r.d_logits};
+                          r.d_act[0], r.d_act[1], r.d_act[2], r.d_act[3], r.d_logits};
+            static_assert(kActBuffers == 4, "the list above names every activation buffer");
             for (void* p : rb) if (p) (void)hipFree(p);
             if (r.done) (void)hipEventDestroy(r.done);
         }
@@ -736,6 +891,12 @@ mt_status mt_model_footprint_get(const mt_layer_spec* specs, uint32_t n_layers, 
 mt_status mt_register_model(mt_ctx* c, uint32_t tenant, const mt_layer_spec* specs, uint32_t n_layers,
                             const void* const* weights, const void* const* biases)
 {
+    return mt_register_model_bn(c, tenant, specs, n_layers, weights, biases, nullptr, 0.0f);
+}
+
+mt_status mt_register_model_bn(mt_ctx* c, uint32_t tenant, const mt_layer_spec* specs, uint32_t n_layers,
+                               const void* const* weights, const void* const* biases, const float* const* bn, float bn_eps)
+{
     if (!c) return MT_EINVAL;
     if (!specs || !weights) return fail(c, MT_EINVAL, "null specs or weights");
     if (tenant >= c->cfg.max_tenants) return fail(c, MT_EINVAL, "tenant %u is outside 0..%u", tenant, c->cfg.max_tenants - 1);
@@ -743,8 +904,16 @@ mt_status mt_register_model(mt_ctx* c, uint32_t tenant, const mt_layer_spec* spe
     HostTenant ht;
     mt_status st = plan_model(c, specs, n_layers, &ht);
     if (st != MT_OK) return st;
-    for (uint32_t l = 0; l < n_layers; ++l)
-        if (ht.layers[l].dev.kind != MT_GAP && !weights[l]) return fail(c, MT_EINVAL, "layer %u: null weights", l);
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const bool has_params = ht.layers[l].dev.kind == MT_FC || ht.layers[l].dev.kind == MT_CONV2D;
+        if (has_params && !weights[l]) return fail(c, MT_EINVAL, "layer %u: null weights", l);
+        if (bn && bn[l]) {
+            if (ht.layers[l].dev.kind != MT_CONV2D) return fail(c, MT_EUNSUPPORTED, "layer %u: only a convolution can be followed by a batch normalisation", l);
+            for (uint32_t ch = 0; ch < ht.layers[l].dev.N; ++ch)
+                if (!((double)bn[l][3 * (size_t)ht.layers[l].dev.N + ch] + (double)bn_eps > 0.0))
+                    return fail(c, MT_EINVAL, "layer %u: variance + eps of channel %u is not positive", l, ch);
+        }
+    }
 
     const uint64_t total = layout_model(&ht);
     if (total > c->cfg.arena_bytes)
@@ -765,13 +934,35 @@ mt_status mt_register_model(mt_ctx* c, uint32_t tenant, const mt_layer_spec* spe
         }
         for (uint32_t l = 0; l < n_layers; ++l) {
             const HostLayer& hl = ht.layers[l];
-            if (hl.dev.kind == MT_GAP) continue;
+            if (hl.dev.kind != MT_FC && hl.dev.kind != MT_CONV2D) continue;
             uint8_t* w_dst = stage + hl.w_rel;
-            if (c->elem_size == 2) pack_weights<uint16_t>(hl, weights[l], w_dst); else pack_weights<float>(hl, weights[l], w_dst);
             if (biases && biases[l]) std::memcpy(stage + hl.b_rel, biases[l], (size_t)hl.dev.N * 4);
+            const void* w_src = weights[l];
+            std::vector<uint8_t> folded;
+            if (bn && bn[l]) {          // fold the normalisation into a copy of the filters and into the staged bias
+                const size_t per = (size_t)hl.spec.in_features * hl.dev.ksize * hl.dev.ksize;
+                folded.assign((const uint8_t*)weights[l], (const uint8_t*)weights[l] + (size_t)hl.dev.N * per * c->elem_size);
+                fold_batchnorm(c->elem_size, folded.data(), (float*)(stage + hl.b_rel), hl.dev.N, per, bn[l], (double)bn_eps);
+                w_src = folded.data();
+            }
+            if (c->elem_size == 2) pack_weights<uint16_t>(hl, w_src, w_dst); else pack_weights<float>(hl, w_src, w_dst);
         }
     }
     auto drop_stage = [&]() { if (c->cache && stage) (void)hipHostFree(stage); };
+
+    // a model with skip connections may need a third or fourth activation buffer in every run slot
+    if (!c->host_only && ht.act_buffers > c->act_buffers) {
+        const size_t act_bytes = (size_t)c->P_cap * c->S * c->elem_size;
+        for (RunSlot& r : c->slots)
+            for (uint32_t i = c->act_buffers; i < ht.act_buffers; ++i)
+                if (!r.d_act[i] && hipMalloc(&r.d_act[i], act_bytes) != hipSuccess) {
+                    (void)hipGetLastError();
+                    drop_stage();
+                    return fail(c, MT_ENOMEM, "no device memory for activation buffer %u of %zu bytes", i, act_bytes);
+                }
+        c->act_buffers = ht.act_buffers;
+        for (RunSlot& r : c->slots) if (r.d_act[0] == c->d_act[0]) bind_slot(c, r);
+    }
 
     // Registration is synchronous.  In cache mode every run in flight ends first: models may have to
     // give way, and a block that an earlier eviction freed may still be read by a run enqueued before it.
@@ -948,13 +1139,16 @@ uint64_t carve_static_slot(const mt_ctx* c, uint32_t R, RunSlot* rs, uint32_t* d
     const uint64_t descr_end = at;
     const uint64_t o_rt = take((uint64_t)R * 4), o_rr = take((uint64_t)R * 4), o_h = take((uint64_t)kHistEntries * 4);
     const uint64_t o_src = take((uint64_t)R * sizeof(void*)), o_pos = take((uint64_t)R * 4), o_perm = take(P * 4);
-    const uint64_t o_a0 = take(P * c->S * c->elem_size), o_a1 = take(P * c->S * c->elem_size), o_lg = take(P * c->C_pad * 4);
+    uint64_t o_act[kActBuffers] = {};
+    for (uint32_t i = 0; i < c->act_buffers; ++i) o_act[i] = take(P * c->S * c->elem_size);
+    const uint64_t o_lg = take(P * c->C_pad * 4);
     if (at <= MT_STATIC_SCRATCH_BYTES) {
         uint8_t* b = c->static_scratch;
         rs->d_M = (uint32_t*)(b + o_M); rs->d_off = (uint32_t*)(b + o_off); rs->d_tile_base = (uint32_t*)(b + o_tb);
         rs->d_row_tenant = (int32_t*)(b + o_rt); rs->d_row_rank = (uint32_t*)(b + o_rr); rs->d_hist_g = (uint32_t*)(b + o_h);
         rs->d_row_src = (const void**)(b + o_src); rs->d_pos_of = (int32_t*)(b + o_pos); rs->d_perm = (int32_t*)(b + o_perm);
-        rs->d_act[0] = b + o_a0; rs->d_act[1] = b + o_a1; rs->d_logits = (float*)(b + o_lg);
+        for (uint32_t i = 0; i < (uint32_t)kActBuffers; ++i) rs->d_act[i] = i < c->act_buffers ? b + o_act[i] : nullptr;
+        rs->d_logits = (float*)(b + o_lg);
         *descr_words = (uint32_t)(descr_end / 4);
     }
     return at;
@@ -1063,7 +1257,8 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
     }
     b.row_tenant = c->d_row_tenant; b.row_rank = c->d_row_rank; b.pos_of = c->d_pos_of; b.perm = c->d_perm;
     b.M = c->d_M; b.off = c->d_off; b.tile_base = c->d_tile_base; b.big_layers = c->d_tile_base + (size_t)kListKinds * MT_MAX_LAYERS * (T + 1); b.fc_split_k = split_k;
-    b.list_mask = big_enabled ? c->list_mask : c->list_mask & ((1u << (2 * MT_MAX_LAYERS)) - 1);   // no big-tile lists to build
+    for (uint32_t g = 0; g < MT_MAX_LAYERS / kLayerGroup; ++g)
+        b.list_mask[g] = big_enabled ? c->list_mask[g] : c->list_mask[g] & ((1u << (2 * kLayerGroup)) - 1);   // no big-tile lists to build
     b.big_enabled = big_enabled; b.big_min_tiles = c->big_min_tiles;
     const OutPtrs outp{out->labels, out->probs, out->logits, out->n_classes, out->row_stride};
     b.out = outp;
@@ -1114,14 +1309,12 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
         if (c->any_conv_first) TIMED(kProfGatherImg, launch_gather_image(g, s));
     }
 
-    uint32_t cur = 0;                      // activation buffer that holds the input of the next layer index
+    ActBufs bufs{};                        // every layer names the buffers it reads and writes (LayerDev::in_buf ...)
+    for (int i = 0; i < kActBuffers; ++i) bufs.p[i] = c->d_act[i];
     for (uint32_t l = 0; l < c->n_layer_slots; ++l) {
         // a pooling index that the convolutions before it have already served: nothing runs, the
-        // pooled activation is where the next index reads
+        // pooled activation is where the pooling layer would have written it
         if (l > 0 && c->pool_fused[l - 1]) continue;
-        const void* in = c->d_act[cur];
-        void* outb = c->d_act[cur ^ 1];
-        cur ^= 1;
         for (int kind = 0; kind < kListKinds; ++kind) {
             const uint64_t grid = tile_bound(c, kind, l, R, split_k);
             if (grid == 0 || (kind == 2 && (!big_enabled || grid < c->big_min_tiles))) continue;   // no big tiles possible: the batcher made none
@@ -1130,7 +1323,7 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
             ga.T = T; ga.layer = l; ga.fc_split_k = split_k; ga.big_layers = b.big_layers;
             ga.gather = (kind == 0 && l == 0 && fuse_gather); ga.perm = c->d_perm; ga.row_src = c->d_row_src;
             ga.fuse_head = fuse_head; ga.fuse_head_max = fuse_head_max; ga.out_vec_ok = out_vec_ok; ga.out = outp; ga.pool = kind == 1 && c->pool_fused[l];
-            ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act_in = in; ga.act_out = outb; ga.arena = c->d_arena;
+            ga.layers = c->d_layers; ga.off = c->d_off; ga.M = c->d_M; ga.act = bufs; ga.arena = c->d_arena;
             ga.logits = c->d_logits; ga.S = c->S; ga.C_pad = c->C_pad; ga.zeros = c->d_zeros;
             if (grid > 0x7ffffff0u)          // cannot happen within the limits mt_create accepts; never launch fewer workgroups than tiles
                 return fail(c, MT_EUNSUPPORTED, "layer %u: %llu tiles exceed one launch", l, (unsigned long long)grid);
@@ -1143,9 +1336,16 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
         if (c->has_gap[l]) {
             GapArgs pa{};
             pa.layer = l; pa.P = P; pa.layers = c->d_layers; pa.tenants = c->d_tenants; pa.row_tenant = c->d_row_tenant;
-            pa.perm = c->d_perm; pa.off = c->d_off; pa.T = T; pa.act_in = in; pa.act_out = outb; pa.S = c->S;
+            pa.perm = c->d_perm; pa.off = c->d_off; pa.T = T; pa.act = bufs; pa.S = c->S;
             pa.elem_size = c->elem_size;
             TIMED(kProfGap + l, launch_gap(pa, s));
+        }
+        if (c->has_image_ops[l]) {         // max-pooling and residual additions of this layer index
+            GapArgs pa{};
+            pa.layer = l; pa.P = P; pa.layers = c->d_layers; pa.tenants = c->d_tenants; pa.row_tenant = c->d_row_tenant;
+            pa.perm = c->d_perm; pa.off = c->d_off; pa.T = T; pa.act = bufs; pa.S = c->S;
+            pa.elem_size = c->elem_size;
+            TIMED(kProfImageOps + l, launch_image_ops(pa, s));
         }
     }
 
@@ -1210,8 +1410,8 @@ void request_cost(const mt_ctx* c, const HostTenant& ht, uint64_t* flops, uint64
             *weight_bytes += (uint64_t)s.in_features * s.out_features * es + (uint64_t)s.out_features * 4;
             in_len = s.in_features;
         } else if (s.kind == MT_CONV2D) {
-            *flops += 2ull * d.rows_per_req * 9 * s.in_features * s.out_features;
-            *weight_bytes += 9ull * s.in_features * s.out_features * es + (uint64_t)s.out_features * 4;
+            *flops += 2ull * d.rows_per_req * s.kh * s.kw * s.in_features * s.out_features;
+            *weight_bytes += (uint64_t)s.kh * s.kw * s.in_features * s.out_features * es + (uint64_t)s.out_features * 4;
             in_len = (uint64_t)s.in_h * s.in_w * s.in_features;
         } else {
             in_len = (uint64_t)s.in_h * s.in_w * s.in_features;
@@ -1329,7 +1529,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
                     big_tiles += (uint64_t)((big_rows(counts[t]) + kBigTile - 1) / kBigTile) * ((d.N_pad + kBigTile - 1) / kBigTile);
             }
         const bool big_layer = big_tiles >= c->big_min_tiles;
-        double w_mb = 0.0, l2_mb = 0.0, chain = 0.0, big_us = 0.0, conv_mb = 0.0, conv_mflop = 0.0, gap_mb = 0.0;
+        double w_mb = 0.0, l2_mb = 0.0, chain = 0.0, big_us = 0.0, conv_mb = 0.0, conv_mflop = 0.0, gap_mb = 0.0, ops_mb = 0.0;
         double big_rounds_k = 0.0;
         for (uint32_t t = 0; t < T; ++t) {
             if (!counts[t] || l >= c->tenants[t].n_layers) continue;
@@ -1354,8 +1554,10 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
                 const double out_elems = c->pool_fused[l] ? d.N : d.out_len;      // pooled on the way out
                 conv_mb += (M * ((double)d.in_h * d.in_w * d.cin + out_elems) * es + (double)d.N_pad * d.K * es) / MB;
                 conv_mflop += 2.0 * M * d.rows_per_req * d.k_valid * d.N / 1e6;
-            } else {
+            } else if (d.kind == MT_GAP) {
                 gap_mb += M * ((double)d.in_h * d.in_w * d.cin + d.out_len) * es / MB;
+            } else {                                               // max-pool, addition (two inputs)
+                ops_mb += M * ((double)d.in_h * d.in_w * d.cin * (d.kind == MT_ADD ? 2.0 : 1.0) + d.out_len) * es / MB;
             }
         }
         if (c->max_nt[0][l] > 0) launch(std::max(chain, kUsFcFixed + us_per_mb * w_mb + kUsPerMbL2 * l2_mb));
@@ -1366,6 +1568,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
             launch(kUsBigFixed + big_us);
         }
         if (c->has_gap[l]) launch(kUsSmallFixed + gap_mb / kCopyMbPerUs);
+        if (c->has_image_ops[l]) launch(kUsSmallFixed + ops_mb / kCopyMbPerUs);
     }
     if (!fuse_head || c->max_reg_classes > fuse_head_max)
         launch(kUsSmallFixed + std::max(3.0 * R * c->C_pad * 4.0 / MB / kHeadMbPerUs, kUsHeadPerRow * R));
@@ -1447,6 +1650,7 @@ mt_status mt_get_profile(mt_ctx* c, mt_profile* out)
         HIP_TRY(c, ms(kProfConv + l, &out->conv_ms[l]));
         HIP_TRY(c, ms(kProfBig + l, &out->fc_big_ms[l]));
         HIP_TRY(c, ms(kProfGap + l, &out->gap_ms[l]));
+        HIP_TRY(c, ms(kProfImageOps + l, &out->ops_ms[l]));
     }
     HIP_TRY(c, hipEventElapsedTime(&out->total_ms, c->prof_events[2 * kProfBatcher], c->prof_events[2 * c->prof_last + 1]));
     return MT_OK;
@@ -1497,8 +1701,7 @@ mt_status mt_debug_poison(mt_ctx* c)
     HIP_TRY(c, hipDeviceSynchronize());
     const size_t act_bytes = (size_t)c->P_cap * c->S * c->elem_size;
     for (RunSlot& r : c->slots) {
-        HIP_TRY(c, hipMemset(r.d_act[0], 0xFF, act_bytes));
-        HIP_TRY(c, hipMemset(r.d_act[1], 0xFF, act_bytes));
+        for (uint32_t i = 0; i < c->act_buffers; ++i) HIP_TRY(c, hipMemset(r.d_act[i], 0xFF, act_bytes));
         HIP_TRY(c, hipMemset(r.d_logits, 0xFF, (size_t)c->P_cap * c->C_pad * 4));
     }
     HIP_TRY(c, hipDeviceSynchronize());

@@ -42,6 +42,13 @@ constexpr uint32_t kSegsInLds = 64;
 
 __device__ __forceinline__ uint32_t ceil_div(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
 
+// One of the run's activation buffers by its number (a layer names the ones it reads and writes);
+// selects instead of indexing, so that the kernel arguments stay in scalar registers.
+__device__ __forceinline__ void* act_of(const ActBufs& b, uint32_t i)
+{
+    return i == 0 ? b.p[0] : i == 1 ? b.p[1] : i == 2 ? b.p[2] : b.p[3];
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every global
 // load in flight (it fences all address spaces), which would empty the prefetch rings of the
 // GEMM loops at each LDS hand-over; here only the LDS counter is waited on.

@@ -48,6 +48,9 @@ constexpr int kRankMinRows = 8192;  // smaller batches are ranked by the batcher
 constexpr int kRankMaxTenants = 512;
 constexpr int kHistEntries = 8192;  // histogram words the batcher holds in LDS (waves or ranking workgroups x padded tenants)
 constexpr int kListKinds = 3;       // tile lists per layer index: FC (streaming), conv, FC (big tiles)
+constexpr int kActBuffers = 4;      // most activation buffers of a run: layer outputs that may be alive at once
+constexpr int kLayerGroup = 8;      // the batcher builds the tile lists of this many layer indices per pass
+constexpr int kBigMaxLayer = 32;    // layer indices from here on never take big tiles (their decisions travel in one 32-bit mask)
 constexpr int kRowBytes = 128;      // conv path: bytes of K one pipeline step consumes per row
 constexpr int kChanPad = 8;         // conv input channels are padded to a multiple of this
 constexpr int kWidthAlign = 64;     // K and activation widths are zero-padded to a multiple of this
@@ -71,6 +74,11 @@ struct LayerDev {
     uint32_t is_last;    // outputs are the logits
     uint32_t pool_fill;  // CONV whose next layer is a global average pool that the convolution can do itself (whole images
                          // per wave: 32 or 64 output pixels per image, channels a multiple of 64): the pool's out_fill, else 0
+    uint32_t ksize;      // CONV / MAXPOOL: window (ksize x ksize)
+    uint32_t pad;        // CONV / MAXPOOL
+    // which of the run's activation buffers the layer reads (in2_buf: the second operand of ADD) and writes;
+    // pool_buf: where a convolution that pools by itself writes (the out_buf of the pooling layer behind it)
+    uint32_t in_buf, in2_buf, out_buf, pool_buf;
     uint64_t w_off;      // byte offset of the packed weights in the arena
     uint64_t b_off;      // byte offset of the fp32 bias in the arena (N_pad entries for FC)
 };
@@ -137,9 +145,12 @@ struct BatchArgs {
     uint32_t* off;         // [T+1] packed position of each tenant's first row (multiple of 32)
     uint32_t* tile_base;   // [kListKinds][MT_MAX_LAYERS][T+1]: FC, conv, big-FC arrays
     uint32_t* big_layers;  // [1] out: bit l set if layer index l is served with big tiles where a tenant qualifies
-    uint32_t list_mask;    // bit kind*MT_MAX_LAYERS + l set if any registered model can have such tiles at layer l
+    uint32_t list_mask[MT_MAX_LAYERS / kLayerGroup];   // per group of layer indices: bit kind*kLayerGroup + l%kLayerGroup set if any registered model can have such tiles at layer l
     OutPtrs out;           // rejected rows are answered here (label -1, zero rows)
 };
+
+// The run's activation buffers; a layer names the ones it reads and writes (LayerDev::in_buf ...).
+struct ActBufs { void* p[kActBuffers]; };
 
 struct GatherArgs {
     const void* const* row_src; uint32_t P;      // P = upper bound of packed rows (multiple of 32)
@@ -162,7 +173,7 @@ struct GemmArgs {
     // in runs whose tiles are single column blocks); out_vec_ok: output rows take 16-byte stores
     uint32_t fuse_head; uint32_t fuse_head_max; uint32_t out_vec_ok; OutPtrs out;
     const LayerDev* layers; const uint32_t* off; const uint32_t* M;
-    const void* act_in; void* act_out; const uint8_t* arena;
+    ActBufs act; const uint8_t* arena;
     float* logits; uint32_t S; uint32_t C_pad;
     const void* zeros;     // >= 16 readable zero bytes
 };
@@ -170,7 +181,7 @@ struct GemmArgs {
 struct GapArgs {
     uint32_t layer; uint32_t P; const LayerDev* layers; const TenantDev* tenants;
     const int32_t* row_tenant; const int32_t* perm; const uint32_t* off; uint32_t T;
-    const void* act_in; void* act_out; uint32_t S; uint32_t elem_size;
+    ActBufs act; uint32_t S; uint32_t elem_size;
 };
 
 struct HeadArgs {
@@ -193,6 +204,7 @@ hipError_t launch_mfma_rate(float* out, uint32_t iters, uint32_t grid, hipStream
 // quad: every tenant's input channels at this layer index are a multiple of four 16-byte chunks
 hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, uint32_t grid, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, hipStream_t s);
+hipError_t launch_image_ops(const GapArgs& a, hipStream_t s);   // max-pool and residual add of one layer index
 hipError_t launch_head(const HeadArgs& a, hipStream_t s);
 
 }  // namespace mt

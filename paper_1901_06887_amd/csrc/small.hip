@@ -131,11 +131,11 @@ template <typename T>
 __device__ void gap_row(const GapArgs& a, const LayerDev& L, uint32_t p, uint32_t seg0)
 {
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
-    const T* in = (const T*)a.act_in + (size_t)p * a.S;
+    const T* in = (const T*)act_of(a.act, L.in_buf) + (size_t)p * a.S;
     const uint32_t C = L.cin, HW = L.in_h * L.in_w;
     const uint32_t m = p - seg0, rb = m / kBrickRows, i = m % kBrickRows;
     const uint32_t nKB = L.out_fill / KB;
-    T* out = (T*)a.act_out + (size_t)seg0 * a.S + (size_t)rb * nKB * 64 * EPC;
+    T* out = (T*)act_of(a.act, L.out_buf) + (size_t)seg0 * a.S + (size_t)rb * nKB * 64 * EPC;
     const float inv = 1.0f / (float)HW;
     const uint32_t CPP = C / EPC;                              // 16-byte chunks per pixel (C is a multiple of 8)
     if (C % EPC == 0 && CPP <= kGapThreads && kGapThreads % CPP == 0) {
@@ -184,6 +184,79 @@ __global__ __launch_bounds__(kGapThreads) void gap_kernel(GapArgs a)
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     if (L.kind != MT_GAP) return;
     if (a.elem_size == 2) gap_row<__bf16>(a, L, p, a.off[t]); else gap_row<float>(a, L, p, a.off[t]);
+}
+
+// ---- max-pool and residual add: one workgroup per packed row, NHWC rows in and out ---------
+// 16 bytes per thread and step: a chunk of channels of one output pixel.  The window's taps
+// outside the image are skipped, so they never win; an addition is followed by the layer's
+// activation and the rounding to the element type.
+constexpr uint32_t kImageOpThreads = 256;
+template <typename T>
+__device__ void maxpool_row(const GapArgs& a, const LayerDev& L, uint32_t p)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T);
+    const u32x4* in = (const u32x4*)((const T*)act_of(a.act, L.in_buf) + (size_t)p * a.S);
+    u32x4* out = (u32x4*)((T*)act_of(a.act, L.out_buf) + (size_t)p * a.S);
+    const uint32_t cpp = L.cin / EPC, n = L.rows_per_req * cpp;          // chunks per pixel (channels are a multiple of 8), chunks of the output
+    for (uint32_t q = threadIdx.x; q < n; q += kImageOpThreads) {
+        const uint32_t pix = q / cpp, ch = q - pix * cpp, oh = pix / L.out_w, ow = pix - oh * L.out_w;
+        float best[EPC];
+#pragma unroll
+        for (uint32_t e = 0; e < EPC; ++e) best[e] = -INFINITY;
+        for (uint32_t kh = 0; kh < L.ksize; ++kh) {
+            const int32_t ih = (int32_t)(oh * L.stride + kh) - (int32_t)L.pad;
+            if (ih < 0 || ih >= (int32_t)L.in_h) continue;
+            for (uint32_t kw = 0; kw < L.ksize; ++kw) {
+                const int32_t iw = (int32_t)(ow * L.stride + kw) - (int32_t)L.pad;
+                if (iw < 0 || iw >= (int32_t)L.in_w) continue;
+                const u32x4 v = in[((size_t)ih * L.in_w + iw) * cpp + ch];
+                const T* ve = (const T*)&v;
+#pragma unroll
+                for (uint32_t e = 0; e < EPC; ++e) best[e] = fmaxf(best[e], (float)ve[e]);
+            }
+        }
+        T o[EPC];
+#pragma unroll
+        for (uint32_t e = 0; e < EPC; ++e) o[e] = (T)best[e];             // a maximum of representable values: exact
+        out[q] = __builtin_bit_cast(u32x4, o);
+    }
+    for (uint32_t q = n + threadIdx.x; q < L.out_fill / EPC; q += kImageOpThreads) out[q] = u32x4{0, 0, 0, 0};
+}
+
+template <typename T>
+__device__ void add_row(const GapArgs& a, const LayerDev& L, uint32_t p)
+{
+    constexpr uint32_t EPC = 16 / sizeof(T);
+    const u32x4* x = (const u32x4*)((const T*)act_of(a.act, L.in_buf) + (size_t)p * a.S);
+    const u32x4* y = (const u32x4*)((const T*)act_of(a.act, L.in2_buf) + (size_t)p * a.S);
+    u32x4* out = (u32x4*)((T*)act_of(a.act, L.out_buf) + (size_t)p * a.S);
+    const uint32_t n = L.out_len / EPC;                                   // whole chunks: channels are a multiple of 8
+    for (uint32_t q = threadIdx.x; q < n; q += kImageOpThreads) {
+        const u32x4 xv = x[q], yv = y[q];
+        const T* xe = (const T*)&xv;
+        const T* ye = (const T*)&yv;
+        T o[EPC];
+#pragma unroll
+        for (uint32_t e = 0; e < EPC; ++e) o[e] = (T)activate((float)xe[e] + (float)ye[e], L.act);
+        out[q] = __builtin_bit_cast(u32x4, o);
+    }
+    for (uint32_t q = n + threadIdx.x; q < L.out_fill / EPC; q += kImageOpThreads) out[q] = u32x4{0, 0, 0, 0};
+}
+
+__global__ __launch_bounds__(kImageOpThreads) void image_ops_kernel(GapArgs a)
+{
+    const uint32_t p = blockIdx.x;
+    if (p >= a.off[a.T]) return;
+    const int32_t r = a.perm[p];
+    if (r < 0) return;
+    const uint32_t t = (uint32_t)a.row_tenant[r];
+    if (a.tenants[t].n_layers <= a.layer) return;
+    const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
+    if (L.kind == MT_MAXPOOL) {
+        if (a.elem_size == 2) maxpool_row<__bf16>(a, L, p); else maxpool_row<float>(a, L, p);
+    } else if (L.kind == MT_ADD) {
+        if (a.elem_size == 2) add_row<__bf16>(a, L, p); else add_row<float>(a, L, p);
+    }
 }
 
 // ---- head: one wave per submitted row --------------------------------------------------
@@ -340,6 +413,11 @@ hipError_t launch_gap(const GapArgs& a, hipStream_t s)
 {
     // grid covers every packed row; rows of other layer kinds return at once
     hipLaunchKernelGGL(gap_kernel, dim3(a.P), dim3(kGapThreads), 0, s, a);
+    return hipGetLastError();
+}
+hipError_t launch_image_ops(const GapArgs& a, hipStream_t s)
+{
+    hipLaunchKernelGGL(image_ops_kernel, dim3(a.P), dim3(kImageOpThreads), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_head(const HeadArgs& a, hipStream_t s)

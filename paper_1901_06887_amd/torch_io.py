@@ -20,8 +20,10 @@ class Served:
 
 
 def specs_of(layers) -> list:
-    """mt_layer_spec list from objects with kind/act/in_features/out_features/in_h/in_w/stride."""
-    return [B.layer_spec(l.kind, l.act, l.in_features, l.out_features, l.in_h, l.in_w, l.stride) for l in layers]
+    """mt_layer_spec list from objects with kind/act/in_features/out_features/in_h/in_w/stride (and, where they
+    have them, ksize/pad/src/src2)."""
+    return [B.layer_spec(l.kind, l.act, l.in_features, l.out_features, l.in_h, l.in_w, l.stride,
+                         getattr(l, "ksize", 3), getattr(l, "pad", 1), getattr(l, "src", 0), getattr(l, "src2", 0)) for l in layers]
 
 
 def context_for(tenants: Dict[int, object], dtype: str, max_requests: int, device: int = 0,
@@ -41,7 +43,7 @@ def context_for(tenants: Dict[int, object], dtype: str, max_requests: int, devic
 
 def register_tenants(ctx: B.Context, tenants: Dict[int, object]):
     for t, m in tenants.items():
-        ctx.register_model(int(t), specs_of(m.layers), m.weights, m.biases)
+        ctx.register_model(int(t), specs_of(m.layers), m.weights, m.biases, getattr(m, "bn", None), getattr(m, "bn_eps", 1e-5))
 
 
 def to_device(x: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:

@@ -24,6 +24,12 @@ binding) and through the oracle, and compare to the stated bar:
     rows must be <= CLEAN_ROW (most rows see no flip at all), and, where the caller states
     the share of rows that must be flip-free (`min_clean_frac`, for the mixes whose nets are
     shallow enough that flips are rare), that share of all rows must be <= CLEAN_ROW;
+  * deep bf16 nets (`deep=True`; the resnet18-shaped tenants: twenty convolutions, up to millions of
+    hidden values per request) are compared at DEEP_REL_TOL per tensor and DEEP_ROW_TOL per row: with
+    that many rounded values most rows hold several flips, and their effects add up to a few 1e-3
+    (on the reduced net the GPU's one flipped row of 40, 6.59e-3, is exactly the row and the value
+    that the exactly-rounded-fp32 evaluation of tests/test_tolerance_model.py gets, and already puts
+    the 40-row tensor at 1.26e-3).  The kernels themselves are held to ~1e-6 on the same nets in fp32;
   * labels bit-exact wherever the oracle's top-2 logit margin exceeds 1e-2; elsewhere the
     label must be one of the oracle's two best classes.
 """
@@ -39,6 +45,8 @@ ROW_TOL = 1e-2
 MIN_ROWS_PER_TENSOR = 16
 ONE_FLIP_ROWS = 100     # (ROW_TOL / REL_FRO_TOL) ** 2: from here on one row at the row bar cannot move a tensor past 1e-3
 MARGIN = 1e-2
+DEEP_REL_TOL = 1e-2     # deep bf16 nets: flips in most rows, see above
+DEEP_ROW_TOL = 3e-2
 CLEAN_ROW = 1e-5        # a row without a rounding flip agrees to ~1e-7 (bf16 mixes) or ~1e-6 (fp32)
 
 
@@ -67,8 +75,9 @@ def rel_fro(g, o):
     return d / n if n > 0 else d
 
 
-def compare(w, gpu, orc, rows=None, what="", min_clean_frac=None):
+def compare(w, gpu, orc, rows=None, what="", min_clean_frac=None, deep=False):
     """gpu/orc = (logits, probs, labels, n_classes) over the same rows (all, or `rows`)."""
+    rel_tol, row_tol = (DEEP_REL_TOL, DEEP_ROW_TOL) if deep else (REL_FRO_TOL, ROW_TOL)
     g_lg, g_pr, g_lb, g_nc = gpu
     o_lg, o_pr, o_lb, o_nc = orc
     ids = w.tenant_ids if rows is None else w.tenant_ids[rows]
@@ -81,7 +90,7 @@ def compare(w, gpu, orc, rows=None, what="", min_clean_frac=None):
     for t in np.unique(ids):
         sel = ids == t
         n_t = int(sel.sum())
-        tol = REL_FRO_TOL if n_t >= MIN_ROWS_PER_TENSOR else ROW_TOL
+        tol = rel_tol if n_t >= MIN_ROWS_PER_TENSOR else row_tol
         for g, o in ((g_lg[sel], o_lg[sel]), (g_pr[sel], o_pr[sel])):
             e = rel_fro(g, o)
             if e > tol and MIN_ROWS_PER_TENSOR <= n_t < ONE_FLIP_ROWS:
@@ -92,19 +101,20 @@ def compare(w, gpu, orc, rows=None, what="", min_clean_frac=None):
             worst = max(worst, e)
             assert e <= tol, "%s tenant %d (%d rows) rel fro %.3e" % (what, t, n_t, e)
     row_err = np.linalg.norm(g_lg - o_lg, axis=1) / np.maximum(np.linalg.norm(o_lg, axis=1), 1e-30)
-    assert row_err.max() <= ROW_TOL, "%s: a row is off by %.3e" % (what, row_err.max())
+    assert row_err.max() <= row_tol, "%s: a row is off by %.3e" % (what, row_err.max())
     # the rows of small tenants, pooled: the looser per-tensor bar above must not hide a systematic error
     ids_u, cnt_u = np.unique(ids, return_counts=True)
     small = np.isin(ids, ids_u[cnt_u < MIN_ROWS_PER_TENSOR])
     if int(small.sum()) >= MIN_ROWS_PER_TENSOR:
         for g, o in ((g_lg[small], o_lg[small]), (g_pr[small], o_pr[small])):
-            assert rel_fro(g, o) <= REL_FRO_TOL, "%s: the %d rows of small tenants together are off by %.3e" % (what, int(small.sum()), rel_fro(g, o))
-        assert np.median(row_err[small]) <= CLEAN_ROW, "%s: median row error of small tenants %.3e" % (what, np.median(row_err[small]))
+            assert rel_fro(g, o) <= rel_tol, "%s: the %d rows of small tenants together are off by %.3e" % (what, int(small.sum()), rel_fro(g, o))
+        if not deep:
+            assert np.median(row_err[small]) <= CLEAN_ROW, "%s: median row error of small tenants %.3e" % (what, np.median(row_err[small]))
     clean = float(np.mean(row_err <= CLEAN_ROW))
     if min_clean_frac is not None:
         assert clean >= min_clean_frac, "%s: only %.3f of the rows are free of rounding flips" % (what, clean)
     compare.last_clean_frac = clean
-    assert rel_fro(g_lg, o_lg) <= REL_FRO_TOL and rel_fro(g_pr, o_pr) <= REL_FRO_TOL, what
+    assert rel_fro(g_lg, o_lg) <= rel_tol and rel_fro(g_pr, o_pr) <= rel_tol, what
     # labels
     srt = np.sort(o_lg + np.where(np.arange(C)[None, :] < o_nc[:, None], 0.0, -np.inf), axis=1)
     margin = srt[:, -1] - srt[:, -2] if C > 1 else np.full(len(ids), np.inf)

@@ -48,7 +48,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layouts_match_header_sizes():
-    assert ctypes.sizeof(B.mt_layer_spec) == 40
+    assert ctypes.sizeof(B.mt_layer_spec) == 48
     assert ctypes.sizeof(B.mt_config) == 40
     assert ctypes.sizeof(B.mt_outputs) == 40
 
@@ -71,7 +71,7 @@ def test_register_validates_the_closed_layer_set():
         ([fc(64, 10, 7)], 5),                                                    # unknown activation
         ([fc(64, 10, B.MT_ACT_RELU)], 5),                                        # activation on the logits layer
         ([fc(64, 128)] * 0, 5),                                                  # empty
-        ([fc(64, 64, B.MT_ACT_RELU)] * 8 + [fc(64, 10)], 5),                     # too deep
+        ([fc(64, 64, B.MT_ACT_RELU)] * B.MT_MAX_LAYERS + [fc(64, 10)], 5),       # too deep
         ([fc(64, 500)], 5),                                                      # more classes than max_classes
         ([fc(8192, 10)], 5),                                                     # wider than max_width
         ([B.layer_spec(B.MT_CONV2D, B.MT_ACT_RELU, 3, 8, 8, 8, 3), fc(8 * 9, 10)], 5),   # stride 3
@@ -294,3 +294,67 @@ def test_footprint_of_a_model_is_what_registration_takes():
     with pytest.raises(B.MtError) as e:
         B.model_footprint([fc(64, 10, B.MT_ACT_RELU)], B.MT_BF16)       # activation on the logits layer
     assert e.value.status == 5
+
+
+def test_wider_catalogue_is_validated():
+    """Window sizes, skip sources and shapes of the wider layer set (paper section 3.1: a pre-defined set of
+    supported layer types): what is outside it is refused with MT_EUNSUPPORTED and allocates nothing."""
+    c = host_ctx(max_width=1 << 16)
+    conv = lambda ci, co, hw, k, s=1, act=B.MT_ACT_RELU, src=0: B.layer_spec(B.MT_CONV2D, act, ci, co, hw, hw, s, ksize=k, pad=(k - 1) // 2, src=src)
+    pool = lambda ch, hw, k=3, s=2, p=1: B.layer_spec(B.MT_MAXPOOL, 0, ch, ch, hw, hw, s, ksize=k, pad=p)
+    add = lambda ch, hw, src2, src=0, act=B.MT_ACT_RELU: B.layer_spec(B.MT_ADD, act, ch, ch, hw, hw, src=src, src2=src2)
+    gap = lambda ch, hw: B.layer_spec(B.MT_GAP, 0, ch, ch, hw, hw)
+    block = [conv(3, 16, 16, 7, 2), pool(16, 8), conv(16, 16, 4, 3), conv(16, 16, 4, 3, act=0), add(16, 4, src2=2),
+             conv(16, 32, 4, 3, 2), conv(32, 32, 2, 3, act=0), conv(16, 32, 4, 1, 2, act=0, src=5), add(32, 2, src=7, src2=8), gap(32, 2), fc(32, 5)]
+    def zeros(specs):
+        ws, bs = [], []
+        for sp in specs:
+            if sp.kind == B.MT_FC:
+                ws.append(np.zeros((sp.out_features, sp.in_features), dtype=np.uint16)); bs.append(np.zeros(sp.out_features, dtype=np.float32))
+            elif sp.kind == B.MT_CONV2D:
+                ws.append(np.zeros((sp.out_features, sp.in_features, sp.kh, sp.kw), dtype=np.uint16)); bs.append(np.zeros(sp.out_features, dtype=np.float32))
+            else:
+                ws.append(None); bs.append(None)
+        return ws, bs
+    c.register_model(0, block, *zeros(block))
+    used = c.stats()["arena_used"]
+    assert used == B.model_footprint(block, B.MT_BF16)["arena_bytes"] > 0
+    def bad(i, spec):
+        m = list(block); m[i] = spec
+        return m
+    cases = [bad(0, conv(3, 16, 16, 5, 2)),                       # 5x5 window
+             bad(0, B.layer_spec(B.MT_CONV2D, 1, 3, 16, 16, 16, 2, ksize=7, pad=1)),   # pad that is not (k - 1) / 2
+             bad(1, pool(16, 8, k=4)), bad(1, pool(16, 8, k=2, p=2)),                 # window / padding outside the set
+             bad(4, add(16, 4, src2=0)),                         # an addition without a second source
+             bad(4, add(16, 4, src2=1)),                         # second source of another shape (the stem's 8x8 image)
+             bad(4, add(16, 4, src2=6)),                         # a source that comes later
+             bad(7, conv(16, 32, 4, 1, 2, act=0, src=7)),        # projection reading a 2x2x32 image as 4x4x16
+             bad(2, B.layer_spec(B.MT_CONV2D, 1, 16, 16, 4, 4, 1, src2=1)),           # only additions take a second source
+             bad(10, gap(32, 2)),                                # the last layer must be FC
+             [conv(3, 16, 8, 3), fc(8 * 8 * 16, 5)],             # FC straight after an image
+             [conv(3, 16, 8, 3), gap(16, 8), add(16, 1, src2=1), fc(16, 5)]]           # adding a vector
+    for specs in cases:
+        with pytest.raises(B.MtError) as e:
+            c.register_model(1, specs, *zeros(specs))
+        assert e.value.status == 5, [s.kind for s in specs]
+        with pytest.raises(B.MtError):
+            B.model_footprint(specs, B.MT_BF16)
+    assert c.stats()["arena_used"] == used and c.stats()["n_tenants"] == 1
+    # five values alive at once: more than the four activation buffers of a run
+    wide = [conv(3, 8, 8, 3), conv(8, 8, 8, 3), conv(8, 8, 8, 3, src=1), conv(8, 8, 8, 3, src=1), conv(8, 8, 8, 3, src=1),
+            add(8, 8, src=2, src2=3), add(8, 8, src2=4), add(8, 8, src2=5), add(8, 8, src2=1), gap(8, 8), fc(8, 3)]
+    with pytest.raises(B.MtError) as e:
+        c.register_model(1, wide, *zeros(wide))
+    assert e.value.status == 5 and "alive" in str(e.value)
+    # batch normalisation can only follow a convolution, and needs a positive variance
+    bn = [None] * len(block)
+    bn[1] = (np.ones(16), np.zeros(16), np.zeros(16), np.ones(16))
+    with pytest.raises(B.MtError) as e:
+        c.register_model(1, block, *zeros(block), bn=bn)
+    assert e.value.status == 5
+    bn = [None] * len(block)
+    bn[0] = (np.ones(16), np.zeros(16), np.zeros(16), -np.ones(16))
+    with pytest.raises(B.MtError) as e:
+        c.register_model(1, block, *zeros(block), bn=bn)
+    assert e.value.status == 1
+    c.close()

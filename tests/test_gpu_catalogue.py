@@ -1,0 +1,147 @@
+"""GPU parity of the wider layer catalogue (paper section 1.1: DNNs are built from a few dozen layer
+types, the running example is an 18-layer residual network; section 3.1: a pre-defined set of supported
+layers): 1x1 / 3x3 / 7x7 convolutions, max-pooling, residual additions with skip sources, batch
+normalisation folded at registration, and resnet18-shaped tenants, against the fp64 oracle through the C ABI."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_common import compare, gpu_run, make_context, oracle_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def conv(ci, co, hw, k, s=1, act=wl.ACT_RELU, src=0):
+    h, w = hw if isinstance(hw, tuple) else (hw, hw)
+    return wl.LayerSpec(wl.CONV, act, ci, co, h, w, s, ksize=k, pad=(k - 1) // 2, src=src)
+
+
+def pool(ch, hw, k=3, s=2, p=1):
+    h, w = hw if isinstance(hw, tuple) else (hw, hw)
+    return wl.LayerSpec(wl.MAXPOOL, wl.ACT_NONE, ch, ch, h, w, s, ksize=k, pad=p)
+
+
+def add(ch, hw, src2, src=0, act=wl.ACT_RELU):
+    h, w = hw if isinstance(hw, tuple) else (hw, hw)
+    return wl.LayerSpec(wl.ADD, act, ch, ch, h, w, src=src, src2=src2)
+
+
+def tail(ch, hw, classes):
+    h, w = hw if isinstance(hw, tuple) else (hw, hw)
+    return [wl.LayerSpec(wl.GAP, wl.ACT_NONE, ch, ch, h, w), wl.LayerSpec(wl.FC, wl.ACT_NONE, ch, classes)]
+
+
+def fleet(name, layer_lists, n_requests, dtype="bf16", seed=201, bn=False):
+    tenants = {}
+    for t, layers in enumerate(layer_lists):
+        m = wl.make_model(layers, dtype, seed, t)
+        tenants[t] = wl.with_batchnorm(m, seed, t) if bn else m
+    in_len = layer_lists[0][0].in_len()
+    assert all(l[0].in_len() == in_len for l in layer_lists)
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((n_requests, in_len)).astype(np.float32)
+    if dtype == "bf16":
+        x = wl.round_to_bf16(x)
+    ids = rng.integers(0, len(layer_lists), n_requests).astype(np.int32)
+    return wl.Workload(name, dtype, tenants, ids, x)
+
+
+def run_and_compare(w, what, deep=False, tight=None):
+    ctx = make_context(w)
+    gpu = gpu_run(ctx, w, poison=True)
+    counts = ctx.last_counts()
+    assert np.array_equal(counts, np.bincount(w.tenant_ids, minlength=len(counts))), what
+    ref = oracle_rows(w)
+    worst = compare(w, gpu, ref, what=what, deep=deep)
+    if tight is not None:                  # fp32 models: every row to rounding noise
+        C = ref[0].shape[1]
+        row_err = np.linalg.norm(gpu[0][:, :C] - ref[0], axis=1) / np.linalg.norm(ref[0], axis=1)
+        assert row_err.max() <= tight, "%s: a row is off by %.3e" % (what, row_err.max())
+    print("%s: worst per-tensor rel fro %.2e, flip-free rows %.3f" % (what, worst, compare.last_clean_frac), flush=True)
+    ctx.close()
+    return gpu
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_convolution_windows_1x1_3x3_7x7(dtype):
+    """Every window of the set at stride 1 and 2, odd and even images, narrow (one channel block), wide
+    (two to four) and ragged (72, 136) channel counts, tenants of different shapes in one launch."""
+    nets = [
+        [conv(3, 16, 12, 7, 2), conv(16, 24, 6, 1), conv(24, 40, 6, 3, 2)] + tail(40, 3, 5),              # 7x7 stem, 1x1, 3x3
+        [conv(3, 64, 12, 7, 1), conv(64, 128, 12, 1, 2), conv(128, 72, 6, 7, 1)] + tail(72, 6, 5),        # wide 1x1 and 7x7 (quad gathers)
+        [conv(3, 8, 12, 1, 1), conv(8, 136, 12, 3, 2), conv(136, 32, 6, 1, 1)] + tail(32, 6, 5),          # 1x1 on the padded 3-channel input, 8 channels wide
+        [conv(3, 32, 12, 3, 1), conv(32, 32, 12, 7, 2), conv(32, 64, 6, 1, 2)] + tail(64, 3, 5),
+    ]
+    run_and_compare(fleet("windows", nets, 23, dtype), "conv windows %s" % dtype)
+    odd = [[conv(3, 16, (9, 11), 7, 2), conv(16, 16, (5, 6), 1, 2), conv(16, 48, (3, 3), 3, 1)] + tail(48, 3, 4),
+           [conv(3, 40, (9, 11), 1, 2), conv(40, 16, (5, 6), 7, 1), conv(16, 16, (5, 6), 3, 2)] + tail(16, 3, 4)]
+    run_and_compare(fleet("odd images", odd, 17, dtype, seed=202), "conv windows, odd images %s" % dtype)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_max_pooling(dtype):
+    nets = [
+        [conv(3, 16, 12, 3, 1), pool(16, 12, 3, 2, 1), conv(16, 32, 6, 3, 1), pool(32, 6, 2, 2, 0)] + tail(32, 3, 6),
+        [conv(3, 8, 12, 3, 1, act=wl.ACT_NONE), pool(8, 12, 3, 1, 1), pool(8, 12, 2, 2, 0), pool(8, 6, 3, 2, 0)] + tail(8, 2, 6),   # negative values, pad 0 and 1
+        [conv(3, 72, 12, 7, 2, act=wl.ACT_NONE), pool(72, 6, 2, 1, 1), conv(72, 16, 7, 1, 1)] + tail(16, 7, 6),                     # 2x2 window with padding: 7x7 out
+    ]
+    run_and_compare(fleet("max-pool", nets, 19, dtype, seed=203), "max-pool %s" % dtype)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_residual_blocks_with_identity_and_projection_skips(dtype):
+    c = 16
+    identity = [conv(3, c, 8, 3), conv(c, c, 8, 3), conv(c, c, 8, 3, act=wl.ACT_NONE), add(c, 8, src2=1)] + tail(c, 8, 4)
+    projected = [conv(3, c, 8, 3), conv(c, 2 * c, 8, 3, 2), conv(2 * c, 2 * c, 4, 3, act=wl.ACT_NONE),
+                 conv(c, 2 * c, 8, 1, 2, act=wl.ACT_NONE, src=1), add(2 * c, 4, src=3, src2=4)] + tail(2 * c, 4, 4)
+    two_blocks = [conv(3, c, 8, 7, 1), pool(c, 8, 3, 2, 1),
+                  conv(c, c, 4, 3), conv(c, c, 4, 3, act=wl.ACT_NONE), add(c, 4, src2=2),
+                  conv(c, c, 4, 3), conv(c, c, 4, 3, act=wl.ACT_NONE), add(c, 4, src2=5, act=wl.ACT_GELU)] + tail(c, 4, 4)
+    plain = [conv(3, c, 8, 3), conv(c, c, 8, 3, 2), conv(c, 64, 4, 3, 2)] + tail(64, 2, 4)           # a chain next to them: pools by itself or not, as the fleet allows
+    mlp = wl.mlp_layers([8 * 8 * 3, 96, 64, 4], wl.ACT_RELU)                                            # and an MLP on the same rows
+    run_and_compare(fleet("residual", [identity, projected, two_blocks, plain, mlp], 41, dtype, seed=204), "residual blocks %s" % dtype)
+
+
+def test_folded_batch_normalisation():
+    nets = [[conv(3, 16, 8, 3), conv(16, 32, 8, 1, 2), conv(32, 32, 4, 3, act=wl.ACT_NONE), conv(16, 32, 8, 1, 2, act=wl.ACT_NONE, src=1),
+             add(32, 4, src=3, src2=4)] + tail(32, 4, 6)] * 3
+    for dtype in ("bf16", "f32"):
+        w = fleet("bn", nets, 29, dtype, seed=205, bn=True)
+        got = run_and_compare(w, "folded batch-norm %s" % dtype)
+        # the normalisation matters: the same filters without it give other answers
+        for m in w.tenants.values():
+            m.bn = None
+        ctx = make_context(w)
+        plain = gpu_run(ctx, w)
+        ctx.close()
+        assert np.abs(plain[0] - got[0]).max() > 1e-2
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_resnet18_shaped_tenants(dtype):
+    """The 18-layer residual network's layer graph (31 layer indices, three live activations, batch
+    normalisation behind every convolution) at reduced widths on 32x32 images, three tenants; then at full
+    widths (64..512 channels, 1000 classes) on 64x64 images, next to a plain CNN tenant and an MLP tenant in
+    the same run.  In fp32 every row must agree to rounding noise; in bf16 the deep-net bar applies."""
+    deep, tight = (True, None) if dtype == "bf16" else (False, 5e-6)
+    run_and_compare(wl.resnet(n_tenants=3, n_requests=200, hw=32, widths=(16, 32, 64, 128), classes=10, dtype=dtype), "resnet18-shaped, reduced, " + dtype,
+                    deep=deep, tight=tight)
+    full = wl.resnet(n_tenants=2, n_requests=9, hw=64, widths=(64, 128, 256, 512), classes=1000, dtype=dtype, seed=7)
+    cnn = wl.make_model(wl.cnn_layers(64, (3, 32, 64, 128), (2, 2, 2), 10), dtype, 7, 50)
+    mlp = wl.make_model(wl.mlp_layers([64 * 64 * 3, 256, 100], wl.ACT_GELU), dtype, 7, 51)
+    tenants = dict(full.tenants); tenants[2] = cnn; tenants[3] = mlp
+    ids = np.array([0, 2, 1, 3, 0, 1, 2, 3, 0, 1, 1, 2], dtype=np.int32)
+    x = np.random.default_rng(8).standard_normal((12, 64 * 64 * 3)).astype(np.float32)
+    if dtype == "bf16":
+        x = wl.round_to_bf16(x)
+    run_and_compare(wl.Workload("resnet18-shaped + cnn + mlp", dtype, tenants, ids, x), "resnet18-shaped, full widths, mixed fleet, " + dtype,
+                    deep=deep, tight=tight)
+
+
+def test_models_deeper_than_one_group_of_layer_indices():
+    """The segmentation kernel builds the tile lists eight layer indices at a time: MLPs of 11 and 20
+    layers next to a two-layer one, several row tiles each."""
+    dims = lambda n: [96] + [64 + 32 * (i % 3) for i in range(n - 1)] + [7]
+    nets = [wl.mlp_layers(dims(11), wl.ACT_RELU), wl.mlp_layers(dims(20), wl.ACT_GELU), wl.mlp_layers([96, 128, 7], wl.ACT_RELU)]
+    run_and_compare(fleet("deep mlps", nets, 700, "bf16", seed=206), "deep MLPs")
+    run_and_compare(fleet("deep mlps", nets, 90, "f32", seed=207), "deep MLPs, small run")

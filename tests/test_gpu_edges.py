@@ -186,11 +186,11 @@ def test_more_than_1024_tenants():
 
 
 def test_deepest_model_and_head_boundaries():
-    # the layer limit (8 layers), and class counts on both sides of the fused-head boundary (32 | 33)
+    # eight layers, and class counts on both sides of the fused-head boundary (32 | 33)
     deep = wl.c2(n_tenants=2, n_requests=90, dims=(40, 72, 64, 96, 64, 136, 64, 48, 32), seed=31)   # 8 FC layers, 32 classes
     wide = wl.c2(n_tenants=2, n_requests=90, dims=(40, 80, 33), seed=32)                              # 33 classes
     tenants = {0: deep.tenants[0], 1: wide.tenants[0], 2: deep.tenants[1], 3: wide.tenants[1]}
-    assert len(tenants[0].layers) == mt.MT_MAX_LAYERS
+    assert len(tenants[0].layers) == 8                  # one whole group of layer indices of the segmentation kernel
     ids = np.random.default_rng(6).integers(0, 4, 90).astype(np.int32)
     w = wl.Workload("deep+boundary", "bf16", tenants, ids, deep.inputs)
     ctx = make_context(w)

@@ -85,3 +85,39 @@ def test_exactly_rounded_fp32_accumulation_already_shows_the_two_kinds_of_rows()
     assert np.sum(err > 1e-3) >= 2 and err.max() < 5e-3 # rows with a flip: beyond 1e-3, far inside the 1e-2 row bar
     assert np.mean((err >= 1e-6) & (err <= 1e-5)) == 0  # nothing in between the two kinds
     assert np.linalg.norm(g - lg[:, :100]) / np.linalg.norm(lg[:, :100]) < 1e-3     # the run's tensor holds the bar
+
+
+def test_a_deep_narrow_net_turns_one_flip_into_more_than_the_tensor_bar():
+    """The resnet18-shaped tenants at reduced widths (20 convolutions, the last ones on 1x1 images of 128
+    channels): evaluated layer by layer with every layer's result *exactly rounded to fp32* before the
+    activation and the bfloat16 rounding, 39 of 40 requests agree with the fp64 oracle to ~1e-8 and one
+    is 6.6e-3 off, which alone puts the 40-row tensor at 1.26e-3.  The GPU path gives the same row and
+    the same value; deep bf16 nets are therefore compared at the wider bar of tests/gpu_common.py."""
+    import oracle
+    w = wl.resnet(n_tenants=3, n_requests=40, hw=32, widths=(16, 32, 64, 128), classes=10)
+    models = oracle.models_from_workload(w)
+    lg = oracle.run_batch(models, w.tenant_ids, w.inputs.astype(np.float64), threads=8)[0]
+
+    def fp32_path(m, x):
+        outs = [bf16(x)]
+        for l, L in enumerate(m.layers):
+            src = outs[L.src if L.src > 0 else l]
+            if L.kind == oracle.CONV:
+                z = oracle.conv(L, m.weights[l], m.biases[l], src).reshape(-1)
+            elif L.kind == oracle.FC:
+                z = oracle.fc(L, m.weights[l], m.biases[l], src)
+            elif L.kind == oracle.MAXPOOL:
+                z = oracle.maxpool(L, src).reshape(-1)
+            elif L.kind == oracle.ADD:
+                z = oracle.add(L, src, outs[L.src2 if L.src2 > 0 else l]).reshape(-1)
+            else:
+                z = oracle.gap(L, src)
+            z = z.astype(np.float32).astype(np.float64)
+            if l == len(m.layers) - 1:
+                return z
+            outs.append(bf16(np.maximum(z, 0) if L.act == oracle.ACT_RELU else z))
+
+    g = np.stack([fp32_path(models[int(t)], x) for t, x in zip(w.tenant_ids, w.inputs.astype(np.float64))])
+    err = np.linalg.norm(g - lg, axis=1) / np.linalg.norm(lg, axis=1)
+    assert np.sum(err > 1e-5) == 1 and 5e-3 < err.max() < 8e-3 and np.median(err) < 1e-6
+    assert np.linalg.norm(g - lg) / np.linalg.norm(lg) > 1e-3
