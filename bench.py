@@ -6,8 +6,9 @@ One step = one pass of the whole path over one synthetic batch: mt_submit_batch 
 models already resident in device memory.  Prints one JSON line.
 
 With no --config the headline is the largest mix (c5: 8 tenants x 4096 requests, compute
-bound) and `per_config` carries the same measurements for c1..c4; with --config cX only that
-mix is measured (the form the rocprofv3 summaries under profiles/ are made with).
+bound) and `per_config` carries the same measurements for c1..c4 and for r18 (four tenants with
+resnet18-shaped models, the wider layer catalogue); with --config X only that mix is measured
+(the form the rocprofv3 summaries under profiles/ are made with).
 
   value        inferences/sec over the K timed steps, one run at a time: the K steps are
                enqueued on one stream, each run after the other, and timed by the wall clock
@@ -89,7 +90,7 @@ def gemm_launch_costs(w, es, rows_of=None, pooled_by_conv=False):
         model = w.tenants[t]
         n = len(model.layers)
         for l, L in enumerate(model.layers):
-            if L.kind == wl.GAP:
+            if L.kind not in (wl.FC, wl.CONV):
                 continue
             m_t = rows_t if rows_of is None else rows_of(rows_t, L)
             if m_t == 0:
@@ -98,7 +99,7 @@ def gemm_launch_costs(w, es, rows_of=None, pooled_by_conv=False):
                 f = 2 * m_t * L.in_features * L.out_features
             else:
                 oh, ow = L.out_hw()
-                f = 2 * m_t * oh * ow * 9 * L.in_features * L.out_features
+                f = 2 * m_t * oh * ow * L.ksize * L.ksize * L.in_features * L.out_features
             b = model.weights[l].size * es + model.biases[l].size * 4
             b += m_t * L.in_len() * es
             if pooled_by_conv and l + 1 < n and model.layers[l + 1].kind == wl.GAP:
@@ -321,7 +322,7 @@ def measure(name, steps, warmup, interleave, cpu_seconds, calibrate_copy_mib=0):
 
 
 # steps / warm-up / oracle seconds of the mixes reported next to the headline
-SIDE = {"c1": (200, 20, 3.0), "c2": (200, 20, 4.0), "c3": (100, 10, 5.0), "c4": (100, 10, 4.0)}
+SIDE = {"c1": (200, 20, 3.0), "c2": (200, 20, 4.0), "c3": (100, 10, 5.0), "c4": (100, 10, 4.0), "r18": (50, 5, 3.0)}
 
 
 def main():
@@ -329,8 +330,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default=None, choices=["c1", "c2", "c3", "c4", "c5"],
-                    help="measure this mix only (default: c5 as the headline, c1..c4 in per_config)")
+    ap.add_argument("--config", default=None, choices=["c1", "c2", "c3", "c4", "c5", "r18"],
+                    help="measure this mix only (default: c5 as the headline, c1..c4 and r18 in per_config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--interleave", type=int, default=3,
                     help="runs in flight in the secondary interleaved pass, each on a stream of its own (1: pass left out)")

@@ -145,3 +145,8 @@ def test_models_deeper_than_one_group_of_layer_indices():
     nets = [wl.mlp_layers(dims(11), wl.ACT_RELU), wl.mlp_layers(dims(20), wl.ACT_GELU), wl.mlp_layers([96, 128, 7], wl.ACT_RELU)]
     run_and_compare(fleet("deep mlps", nets, 700, "bf16", seed=206), "deep MLPs")
     run_and_compare(fleet("deep mlps", nets, 90, "f32", seed=207), "deep MLPs, small run")
+
+
+def test_r18_as_the_benchmark_runs_it():
+    """Four resnet18-shaped tenants on 224x224 images, 64 requests: the configuration bench.py times."""
+    run_and_compare(wl.r18(), "r18", deep=True)

@@ -21,6 +21,8 @@ in for them.  The five named mixes:
       each, global average pool, FC 128-10, bf16; 2048 requests uniform; x ~ N(0,1)
   c5  8 tenants, MLP 4096-4096-4096-4096-1000, GELU, bf16; 32768 requests uniform;
       x ~ N(0,1)
+and, for the wider layer catalogue, r18: 4 tenants with resnet18-shaped models (the paper's
+running example, section 1.1) on 224x224x3 inputs, bf16, 64 requests uniform.
 
 Readings: weights ~ N(0, 1/fan_in) and biases ~ N(0, 0.01) where the second argument
 is a variance (std fan_in^-1/2 and 0.1; fan_in = K for FC, 9*C_in for conv), for all
@@ -302,7 +304,15 @@ def resnet(n_tenants=4, n_requests=64, hw=32, widths=(64, 128, 256, 512), classe
                     _inputs("normal", (n_requests, hw * hw * 3), dtype, seed))
 
 
-CONFIGS = {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5}
+def r18(n_tenants=4, n_requests=64, seed=6) -> Workload:
+    """The paper's running example as a multi-tenant mix: resnet18-shaped models (224x224x3 images, 64..512
+    channels, 1000 classes, ~1.8 GFLOP per request) of several tenants, each with weights of its own."""
+    w = resnet(n_tenants, n_requests, 224, (64, 128, 256, 512), 1000, "bf16", seed)
+    w.name = "r18"
+    return w
+
+
+CONFIGS = {"r18": r18, "c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5}
 
 
 # ---- algorithmic cost of a run (exact flops are known a priori: section 3.2) -
