@@ -12,6 +12,9 @@
 
   python profile_summary.py counters <..._counter_collection.csv> --kernel fc_big_kernel
       mean of every collected counter per dispatch of one kernel
+
+  python profile_summary.py split <..._kernel_trace.csv> --kernel fc_kernel
+      average duration of one kernel in the benchmark's warm steps and in its cache-flushed steps
 """
 import argparse
 import csv
@@ -45,6 +48,31 @@ def stats(path: str, top: int = 12) -> str:
         out.append("%-44s %8d %12.2f %10.2f %10.2f %7.2f" % (
             short_name(r["Name"])[:44], int(r["Calls"]), float(r["AverageNs"]) / 1e3, float(r["MinNs"]) / 1e3,
             float(r["MaxNs"]) / 1e3, float(r["Percentage"])))
+    return "\n".join(out)
+
+
+def split_warm_cold(trace_csv: str, kernel: str) -> str:
+    """Average duration of one kernel's dispatches in a `--kernel-trace` run of bench.py, apart for the
+    steps that ran right after the benchmark's cache flush (a large elementwise kernel in front of the
+    step's segmentation kernel) and for all other steps."""
+    rows = sorted(csv.DictReader(open(trace_csv)), key=lambda r: int(r["Start_Timestamp"]))
+    flushed, step_cold = False, False
+    acc = {False: [], True: []}
+    for r in rows:
+        name = r["Kernel_Name"]
+        dur = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
+        if "elementwise_kernel" in name and dur > 100.0:
+            flushed = True                       # the benchmark's 1 GiB rewrite in front of a step
+        elif "batcher_kernel" in name:           # every step has exactly one
+            step_cold, flushed = flushed, False
+        elif kernel in short_name(name):
+            acc[step_cold].append(dur)
+    out = []
+    for cold in (False, True):
+        v = acc[cold]
+        if v:
+            out.append("%s %s: %d dispatches, avg %.2f us, min %.2f us, max %.2f us" % (
+                kernel, "after a cache flush" if cold else "warm (steps back to back)", len(v), sum(v) / len(v), min(v), max(v)))
     return "\n".join(out)
 
 
@@ -104,6 +132,9 @@ def main(argv=None):
     t.add_argument("--write", required=True)
     t.add_argument("--kernel", required=True)
     t.add_argument("--copy-bytes", type=int, required=True)
+    w = sub.add_parser("split")
+    w.add_argument("csv")
+    w.add_argument("--kernel", required=True)
     c = sub.add_parser("counters")
     c.add_argument("csv")
     c.add_argument("--kernel", required=True)
@@ -111,6 +142,8 @@ def main(argv=None):
     a = ap.parse_args(argv)
     if a.cmd == "stats":
         print(stats(a.csv, a.top))
+    elif a.cmd == "split":
+        print(split_warm_cold(a.csv, a.kernel))
     elif a.cmd == "traffic":
         print(traffic(a.fetch, a.write, a.kernel, a.copy_bytes))
     else:
