@@ -84,23 +84,30 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     // share and also says that everyone is done reading the stage about to be overwritten.
     typedef const __attribute__((address_space(1))) void* gvoid_t;
     typedef __attribute__((address_space(3))) void* lvoid_t;
-    auto issue_stage = [&](uint32_t slot, uint32_t s) {      // data of stage s into ring slot `slot`
+    auto issue_one = [&](uint32_t slot, uint32_t s, uint32_t q) {   // load q (of LPS) of stage s into ring slot `slot`
         uint8_t* dst = stages + (slot % kBigNS) * kBigStageBytes + (wave * BPW) * kBigKS * kBrickBytes;
+        const uint32_t i = q / kBigKS, kk = q % kBigKS;
+        __builtin_amdgcn_global_load_lds((gvoid_t)(lp[i] + (size_t)(s * kBigKS + kk) * 64),
+                                         (lvoid_t)(dst + (i * kBigKS + kk) * kBrickBytes), 16, 0, 0);
+    };
+    auto issue_stage = [&](uint32_t slot, uint32_t s) {
 #pragma unroll
-        for (uint32_t i = 0; i < BPW; ++i)
-#pragma unroll
-            for (uint32_t kk = 0; kk < kBigKS; ++kk)
-                __builtin_amdgcn_global_load_lds((gvoid_t)(lp[i] + (size_t)(s * kBigKS + kk) * 64),
-                                                 (lvoid_t)(dst + (i * kBigKS + kk) * kBrickBytes), 16, 0, 0);
+        for (uint32_t q = 0; q < LPS; ++q) issue_one(slot, s, q);
     };
     // MFMA operands of one k step: 4 activation bricks and 2 weight bricks of this wave
-    auto read_ops = [&](const uint8_t* buf, uint32_t kk, u32x4 (&a4)[4], u32x4 (&b2)[CJ]) {
+    auto read_a = [&](const uint8_t* buf, uint32_t kk, u32x4 (&a4)[4], int i0, int i1) {
         const uint8_t* ab = buf + (wm * 4 * kBigKS) * kBrickBytes + lane * 16;
+#pragma unroll
+        for (int i = i0; i < i1; ++i) a4[i] = *(const u32x4*)(ab + (i * kBigKS + kk) * kBrickBytes);
+    };
+    auto read_b = [&](const uint8_t* buf, uint32_t kk, u32x4 (&b2)[CJ]) {
         const uint8_t* bb = buf + ((kBigBlocks + wn * CJ) * kBigKS) * kBrickBytes + lane * 16;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a4[i] = *(const u32x4*)(ab + (i * kBigKS + kk) * kBrickBytes);
-#pragma unroll
         for (int j = 0; j < (int)CJ; ++j) b2[j] = *(const u32x4*)(bb + (j * kBigKS + kk) * kBrickBytes);
+    };
+    auto read_ops = [&](const uint8_t* buf, uint32_t kk, u32x4 (&a4)[4], u32x4 (&b2)[CJ]) {
+        read_a(buf, kk, a4, 0, 4);
+        read_b(buf, kk, b2);
     };
     auto mma_rows = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[CJ], int i0, int i1) {
 #pragma unroll
@@ -111,10 +118,15 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     auto mma_all = [&](const u32x4 (&a4)[4], const u32x4 (&b2)[CJ]) { mma_rows(a4, b2, 0, 4); };
     static_assert(kBigKS == 2, "the loop below is written for two k steps per stage");
 
-    // The two k steps of a stage use two operand register sets, X and Y.  LDS reads of one set
-    // are always issued in front of the MFMAs of the other, and the second k step of a stage is
-    // multiplied after the next stage's barrier, so neither the LDS latency nor the barrier
-    // leaves the MFMA pipe without work.
+    // The two k steps of a stage use two operand register sets, X and Y; the second k step of a
+    // stage is multiplied after the next stage's barrier, so the MFMA pipe has work the moment the
+    // barrier opens.  Between the barriers the 16 MFMAs of a wave are issued in pairs and the
+    // stage's four global->LDS loads and twelve LDS reads are dealt out between the pairs, in the
+    // shadow of an MFMA already in the pipe.  Issued as one burst behind the barrier (all eight
+    // waves at once: 32 KiB, which the L2 -> LDS path takes ~250 ns to accept) the loads held every
+    // wave at its load instructions while the pipes ran dry: 16 % more clocks per tile.
+    static_assert(LPS == 4, "the schedule below deals out four loads per wave and stage");
+    auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
     const uint32_t n_stages = nKB / kBigKS, last = n_stages - 1;   // nKB is a multiple of 4: at least two stages
     // The waits are spelled with the builtin so that the compiler's own wait-count bookkeeping
     // sees them (an asm wait is invisible to it, and it would then wait again, too strictly);
@@ -145,22 +157,35 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
             // stage s is complete for every wave; every wave holds what it needs of stage s - 1 in
             // registers, so ring slot (s + 3) % 4 can be refilled
             ring_barrier(true);
-            issue_stage(s + kBigNS - 1, min(s + kBigNS - 1, last));   // past the end: a harmless repeat keeps the count uniform
             const uint8_t* buf = stages + (s % kBigNS) * kBigStageBytes;
-            read_ops(buf, 0, xa, xb);
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_setprio(1);                            // a wave with MFMAs to issue goes before its SIMD partner's loads and waits (~1 %)
-            mma_all(ya, yb);                                          // second k step of stage s - 1
-            __builtin_amdgcn_sched_barrier(0);
-            mma_rows(xa, xb, 0, 1);                                   // first k step of stage s; its operands had the MFMAs above to arrive
-            __builtin_amdgcn_s_setprio(0);
-            __builtin_amdgcn_sched_barrier(0);
-            read_ops(buf, 1, ya, yb);                                 // issued behind the wait for X, so that wait does not cover them
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_setprio(1);
-            mma_rows(xa, xb, 1, 4);
-            __builtin_amdgcn_s_setprio(0);
-            __builtin_amdgcn_sched_barrier(0);
+            const uint32_t slot = s + kBigNS - 1, nxt = min(slot, last);   // past the end: a harmless repeat keeps the count uniform
+            fence();
+            mma_rows(ya, yb, 0, 1);                                   // second k step of stage s - 1: the pipe has work the moment the barrier opens
+            fence();
+            issue_one(slot, nxt, 0);
+            fence();
+            mma_rows(ya, yb, 1, 2);
+            fence();
+            read_a(buf, 0, xa, 0, 1); read_b(buf, 0, xb);             // first k step of stage s
+            fence();
+            mma_rows(ya, yb, 2, 3);
+            fence();
+            issue_one(slot, nxt, 1); read_a(buf, 0, xa, 1, 4);
+            fence();
+            mma_rows(ya, yb, 3, 4);
+            fence();
+            issue_one(slot, nxt, 2);
+            fence();
+            mma_rows(xa, xb, 0, 1);
+            fence();
+            read_a(buf, 1, ya, 0, 1); read_b(buf, 1, yb); issue_one(slot, nxt, 3);   // Y is free: its last MFMA has been issued
+            fence();
+            mma_rows(xa, xb, 1, 2);
+            fence();
+            read_a(buf, 1, ya, 1, 4);
+            fence();
+            mma_rows(xa, xb, 2, 4);
+            fence();
         }
         mma_all(ya, yb);
     } else {
