@@ -31,7 +31,7 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     uint8_t* const stage0 = stages;
     static_assert(kBigStageBytes >= (kMaxTenantsPadded + 1) * 4, "tile_base must fit the first stage");
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the wave index as a scalar: staging addresses and LDS offsets become scalar arithmetic
     const uint32_t li = lane & 31, lh = lane >> 5;
 
     uint32_t* base_l = (uint32_t*)stage0;                   // tile_base during the lookup
@@ -59,14 +59,15 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
 
     // staging: the first half of the waves copies the 8 activation row blocks, the second half the
     // 8 weight column blocks, BPW blocks each (blocks past the tile or the layer repeat the last valid one)
-    const u32x4* lp[BPW];
+    const uint8_t* lp[BPW];                                 // uniform: the lane's 16 bytes are added as a 32-bit offset
+    const uint32_t lane_off = lane * 16;
     {
-        const u32x4* xbase = (const u32x4*)((const T*)act_of(a.act, L.in_buf) + (size_t)seg0 * a.S) + lane;
-        const u32x4* wbase = (const u32x4*)(a.arena + L.w_off) + lane;
+        const uint8_t* xbase = (const uint8_t*)((const T*)act_of(a.act, L.in_buf) + (size_t)seg0 * a.S);
+        const uint8_t* wbase = a.arena + L.w_off;
 #pragma unroll
         for (uint32_t i = 0; i < BPW; ++i) {
-            if (wave < WV / 2) lp[i] = xbase + (size_t)(m0 / kBrickRows + min(wave * BPW + i, nrb - 1)) * nKB * 64;
-            else lp[i] = wbase + (size_t)(n0 / kBrickRows + min((wave - WV / 2) * BPW + i, ncb - 1)) * nKB * 64;
+            if (wave < WV / 2) lp[i] = xbase + (size_t)(m0 / kBrickRows + min(wave * BPW + i, nrb - 1)) * nKB * kBrickBytes;
+            else lp[i] = wbase + (size_t)(n0 / kBrickRows + min((wave - WV / 2) * BPW + i, ncb - 1)) * nKB * kBrickBytes;
         }
     }
     f32x16 acc[4][CJ];
@@ -87,7 +88,9 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
     auto issue_one = [&](uint32_t slot, uint32_t s, uint32_t q) {   // load q (of LPS) of stage s into ring slot `slot`
         uint8_t* dst = stages + (slot % kBigNS) * kBigStageBytes + (wave * BPW) * kBigKS * kBrickBytes;
         const uint32_t i = q / kBigKS, kk = q % kBigKS;
-        __builtin_amdgcn_global_load_lds((gvoid_t)(lp[i] + (size_t)(s * kBigKS + kk) * 64),
+        uint32_t lo = lane_off;
+        asm("" : "+v"(lo));                                   // keeps base and lane offset apart: scalar base + 32-bit lane offset is one addressing mode
+        __builtin_amdgcn_global_load_lds((gvoid_t)(lp[i] + (size_t)(s * kBigKS + kk) * kBrickBytes + lo),
                                          (lvoid_t)(dst + (i * kBigKS + kk) * kBrickBytes), 16, 0, 0);
     };
     auto issue_stage = [&](uint32_t slot, uint32_t s) {
