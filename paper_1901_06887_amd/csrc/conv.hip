@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
 {
     __shared__ uint32_t owner_part[4];
     __shared__ __attribute__((aligned(16))) uint8_t unit_scratch[4 * unit_scratch_bytes<T>()];
-    const uint32_t tid = threadIdx.x, wave = tid >> 6;
+    const uint32_t tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     uint8_t* scratch = unit_scratch + wave * unit_scratch_bytes<T>();
     TileOwner<256> lookup;
     lookup.fetch(a.tile_base, a.T);
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     typedef const __attribute__((address_space(1))) u32x4* gptr_t;
     __shared__ __attribute__((aligned(16))) uint8_t lds[kConvNS * kConvStageBytes];
     __shared__ uint32_t owner_part[4];
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lh = lane >> 5;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), li = lane & 31, lh = lane >> 5;
     TileOwner<256> lookup;
     lookup.fetch(a.tile_base, a.T);
     const uint32_t n_tiles = a.tile_base[a.T];
@@ -464,7 +464,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
     typedef const __attribute__((address_space(1))) u32x4* gptr_t;
     extern __shared__ __attribute__((aligned(16))) uint8_t img[];
     __shared__ uint32_t owner_part[4];
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lh = lane >> 5;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), li = lane & 31, lh = lane >> 5;
     TileOwner<256> lookup;
     lookup.fetch(a.tile_base, a.T);
     const uint32_t n_tiles = a.tile_base[a.T];

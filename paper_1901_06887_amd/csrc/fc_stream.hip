@@ -36,7 +36,7 @@ __device__ __forceinline__ void fc_accumulate_shared(const GemmArgs& a, const Ti
     constexpr uint32_t P = 16;                               // weight bricks in flight per wave
     constexpr uint32_t U = P > KC ? P : KC;                  // unrolled block of k steps
     static_assert(U == P && U % KC == 0, "the tail relies on U == P");
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t nKB = L.K / KB;
     const uint32_t nrb = (tl.rows + kBrickRows - 1) / kBrickRows;
     const uint32_t nb_eff = active ? nb : 0;                 // idle waves still help staging; they stream block 0 and drop it
@@ -212,7 +212,7 @@ __device__ __forceinline__ void fc_tile(const GemmArgs& a, const Tile& tl, const
 {
     const uint32_t split = tl.split;
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t li = lane & 31, lh = lane >> 5;
     const uint32_t ks = 4 / split;
     const uint32_t nb = tl.n0 / kBrickRows + (wave % split), kq = wave / split;
