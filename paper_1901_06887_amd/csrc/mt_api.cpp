@@ -114,6 +114,8 @@ struct mt_ctx {
     bool any_conv_first = false, any_fc_first = false;
     uint32_t list_mask[MT_MAX_LAYERS / kLayerGroup] = {};   // per group of layer indices, bit kind*kLayerGroup + l%kLayerGroup: some registered model has that kind at layer l
     uint32_t has_image_ops[MT_MAX_LAYERS]{};   // some registered model has a max-pool or an addition at this layer index
+    uint32_t image_op_fill[MT_MAX_LAYERS]{};   // ... and the longest output row (elements) among them
+    uint32_t max_image_pixels = 0;             // most pixels in a submitted image (models whose first layer is a convolution)
     uint32_t act_buffers = 2;      // activation buffers every run slot holds (grows when a model with skip connections needs more)
     uint32_t max_reg_classes = 0, min_reg_classes = 0;
     uint32_t no_fused_head = 0;    // tuning/testing: always run the separate head kernel
@@ -390,12 +392,12 @@ void recompute_pool_fusion(mt_ctx* c)
 void recompute_bounds(mt_ctx* c)
 {
     c->n_layer_slots = 0;
-    c->max_in_len = 0;
+    c->max_in_len = 0; c->max_image_pixels = 0;
     c->fc_first_chunked = true; c->any_conv_first = c->any_fc_first = false;
     for (uint32_t& m : c->list_mask) m = 0;
     c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        c->has_gap[l] = 0; c->has_image_ops[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
+        c->has_gap[l] = 0; c->has_image_ops[l] = 0; c->image_op_fill[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
         c->max_fc_per64[l] = 0; c->max_fc_per64_sk[l] = 0; c->sum_nt_sk[l] = 0;
     }
@@ -410,11 +412,12 @@ void recompute_bounds(mt_ctx* c)
             if ((t.dev.in_len * c->elem_size) % 16) c->fc_first_chunked = false;
         } else {
             c->any_conv_first = true;
+            c->max_image_pixels = std::max(c->max_image_pixels, t.dev.in_len / (t.dev.in_cin ? t.dev.in_cin : (uint32_t)kChanPad));
         }
         for (uint32_t l = 0; l < t.n_layers; ++l) {
             const LayerDev& L = t.layers[l].dev;
             if (L.kind == MT_GAP) { c->has_gap[l] = 1; continue; }
-            if (L.kind == MT_MAXPOOL || L.kind == MT_ADD) { c->has_image_ops[l] = 1; continue; }
+            if (L.kind == MT_MAXPOOL || L.kind == MT_ADD) { c->has_image_ops[l] = 1; c->image_op_fill[l] = std::max(c->image_op_fill[l], L.out_fill); continue; }
             const int k = L.kind == MT_FC ? 0 : 1;
             c->sum_macs += (double)L.k_valid * L.N * L.rows_per_req;
             c->list_mask[l / kLayerGroup] |= 1u << (k * kLayerGroup + l % kLayerGroup);
@@ -1122,6 +1125,12 @@ __global__ void fill_zero_kernel(uint32_t* p, uint32_t n)
 }
 
 // Packed rows a run of R rows can occupy: every tenant with traffic pads its segment to a multiple of 32.
+// Workgroups that share one packed row in the per-row kernels: `per_wg` units of work each, at most 64.
+static uint32_t row_slices(uint64_t units, uint32_t per_wg)
+{
+    return (uint32_t)std::min<uint64_t>(std::max<uint64_t>((units + per_wg - 1) / per_wg, 1), 64);
+}
+
 uint32_t packed_rows_bound(const mt_ctx* c, uint32_t R)
 {
     return (uint32_t)std::min<uint64_t>(c->P_cap, (uint64_t)round_up(R, kBrickRows) + (uint64_t)kBrickRows * std::min(R, c->n_registered));
@@ -1306,7 +1315,8 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
         g.row_src = c->d_row_src; g.P = P; g.tenants = c->d_tenants; g.layers = c->d_layers; g.row_tenant = c->d_row_tenant;
         g.perm = c->d_perm; g.off = c->d_off; g.T = T; g.act = c->d_act[0]; g.S = c->S; g.elem_size = c->elem_size; g.zeros = c->d_zeros;
         if (c->any_fc_first && !fuse_gather) TIMED(kProfGather, launch_gather(g, s));
-        if (c->any_conv_first) TIMED(kProfGatherImg, launch_gather_image(g, s));
+        // workgroups per image row: each takes ~2048 pixels (eight per thread), so that a few large images fill the chip too
+        if (c->any_conv_first) TIMED(kProfGatherImg, launch_gather_image(g, row_slices(c->max_image_pixels, 2048), s));
     }
 
     ActBufs bufs{};                        // every layer names the buffers it reads and writes (LayerDev::in_buf ...)
@@ -1345,7 +1355,7 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
             pa.layer = l; pa.P = P; pa.layers = c->d_layers; pa.tenants = c->d_tenants; pa.row_tenant = c->d_row_tenant;
             pa.perm = c->d_perm; pa.off = c->d_off; pa.T = T; pa.act = bufs; pa.S = c->S;
             pa.elem_size = c->elem_size;
-            TIMED(kProfImageOps + l, launch_image_ops(pa, s));
+            TIMED(kProfImageOps + l, launch_image_ops(pa, row_slices(c->image_op_fill[l] * c->elem_size / 16, 2048), s));   // eight 16-byte chunks per thread
         }
     }
 

@@ -195,7 +195,7 @@ struct HeadArgs {
 // Launchers (defined next to their kernels).  All enqueue on `s` and return the launch status.
 hipError_t launch_batcher(const BatchArgs& a, hipStream_t s);   // three launches when a.n_rank_groups > 0
 hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
-hipError_t launch_gather_image(const GatherArgs& a, hipStream_t s);
+hipError_t launch_gather_image(const GatherArgs& a, uint32_t slices, hipStream_t s);   // `slices` workgroups share a row
 hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
 hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s);
@@ -204,7 +204,7 @@ hipError_t launch_mfma_rate(float* out, uint32_t iters, uint32_t grid, hipStream
 // quad: every tenant's input channels at this layer index are a multiple of four 16-byte chunks
 hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, uint32_t grid, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, hipStream_t s);
-hipError_t launch_image_ops(const GapArgs& a, hipStream_t s);   // max-pool and residual add of one layer index
+hipError_t launch_image_ops(const GapArgs& a, uint32_t slices, hipStream_t s);   // max-pool and residual add of one layer index
 hipError_t launch_head(const HeadArgs& a, hipStream_t s);
 
 }  // namespace mt

@@ -4,7 +4,8 @@
 namespace mt {
 
 // ---- gather ------------------------------------------------------------------------------
-// Images (first layer is a convolution): one workgroup per packed row, one thread per pixel;
+// Images (first layer is a convolution): gridDim.y workgroups per packed row, which deal the
+// row's pixels out among themselves (a 224x224 image is 50176 pixels), one thread per pixel;
 // channels are padded with zeros to a multiple of 8 so that every tap of the implicit GEMM is
 // a whole number of 16-byte chunks.
 template <typename T>
@@ -21,7 +22,7 @@ __device__ void gather_image(const GatherArgs& a, const TenantDev& td, uint32_t 
         const uint32_t* s32 = (const uint32_t*)src;
         u32x4* d16 = (u32x4*)dst;
         constexpr uint32_t kPairs = 4;                       // pixel pairs in flight per thread
-        for (uint32_t base = 0; base < npix / 2; base += kPairs * blockDim.x) {
+        for (uint32_t base = blockIdx.y * kPairs * blockDim.x; base < npix / 2; base += gridDim.y * kPairs * blockDim.x) {
             uint32_t w[kPairs][3];
 #pragma unroll
             for (uint32_t i = 0; i < kPairs; ++i) {
@@ -38,10 +39,10 @@ __device__ void gather_image(const GatherArgs& a, const TenantDev& td, uint32_t 
                 }
             }
         }
-        for (uint32_t e = npix * cp + threadIdx.x; e < td.in_fill; e += blockDim.x) dst[e] = (T)0.0f;
+        for (uint32_t e = npix * cp + blockIdx.y * blockDim.x + threadIdx.x; e < td.in_fill; e += gridDim.y * blockDim.x) dst[e] = (T)0.0f;
         return;
     }
-    for (uint32_t pix = threadIdx.x; pix < npix; pix += blockDim.x) {
+    for (uint32_t pix = blockIdx.y * blockDim.x + threadIdx.x; pix < npix; pix += gridDim.y * blockDim.x) {
         for (uint32_t g = 0; g < cp; g += EPC) {
             alignas(16) T tmp[EPC];
 #pragma unroll
@@ -49,7 +50,7 @@ __device__ void gather_image(const GatherArgs& a, const TenantDev& td, uint32_t 
             *(u32x4*)(dst + (size_t)pix * cp + g) = *(const u32x4*)tmp;
         }
     }
-    for (uint32_t e = npix * cp + threadIdx.x; e < td.in_fill; e += blockDim.x) dst[e] = (T)0.0f;
+    for (uint32_t e = npix * cp + blockIdx.y * blockDim.x + threadIdx.x; e < td.in_fill; e += gridDim.y * blockDim.x) dst[e] = (T)0.0f;
 }
 
 __global__ __launch_bounds__(256) void gather_image_kernel(GatherArgs a)
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(kGapThreads) void gap_kernel(GapArgs a)
     if (a.elem_size == 2) gap_row<__bf16>(a, L, p, a.off[t]); else gap_row<float>(a, L, p, a.off[t]);
 }
 
-// ---- max-pool and residual add: one workgroup per packed row, NHWC rows in and out ---------
+// ---- max-pool and residual add: gridDim.y workgroups per packed row, NHWC rows in and out ----
 // 16 bytes per thread and step: a chunk of channels of one output pixel.  The window's taps
 // outside the image are skipped, so they never win; an addition is followed by the layer's
 // activation and the rounding to the element type.
@@ -198,7 +199,7 @@ __device__ void maxpool_row(const GapArgs& a, const LayerDev& L, uint32_t p)
     const u32x4* in = (const u32x4*)((const T*)act_of(a.act, L.in_buf) + (size_t)p * a.S);
     u32x4* out = (u32x4*)((T*)act_of(a.act, L.out_buf) + (size_t)p * a.S);
     const uint32_t cpp = L.cin / EPC, n = L.rows_per_req * cpp;          // chunks per pixel (channels are a multiple of 8), chunks of the output
-    for (uint32_t q = threadIdx.x; q < n; q += kImageOpThreads) {
+    for (uint32_t q = blockIdx.y * kImageOpThreads + threadIdx.x; q < n; q += gridDim.y * kImageOpThreads) {
         const uint32_t pix = q / cpp, ch = q - pix * cpp, oh = pix / L.out_w, ow = pix - oh * L.out_w;
         float best[EPC];
 #pragma unroll
@@ -220,7 +221,7 @@ __device__ void maxpool_row(const GapArgs& a, const LayerDev& L, uint32_t p)
         for (uint32_t e = 0; e < EPC; ++e) o[e] = (T)best[e];             // a maximum of representable values: exact
         out[q] = __builtin_bit_cast(u32x4, o);
     }
-    for (uint32_t q = n + threadIdx.x; q < L.out_fill / EPC; q += kImageOpThreads) out[q] = u32x4{0, 0, 0, 0};
+    for (uint32_t q = n + blockIdx.y * kImageOpThreads + threadIdx.x; q < L.out_fill / EPC; q += gridDim.y * kImageOpThreads) out[q] = u32x4{0, 0, 0, 0};
 }
 
 template <typename T>
@@ -231,7 +232,7 @@ __device__ void add_row(const GapArgs& a, const LayerDev& L, uint32_t p)
     const u32x4* y = (const u32x4*)((const T*)act_of(a.act, L.in2_buf) + (size_t)p * a.S);
     u32x4* out = (u32x4*)((T*)act_of(a.act, L.out_buf) + (size_t)p * a.S);
     const uint32_t n = L.out_len / EPC;                                   // whole chunks: channels are a multiple of 8
-    for (uint32_t q = threadIdx.x; q < n; q += kImageOpThreads) {
+    for (uint32_t q = blockIdx.y * kImageOpThreads + threadIdx.x; q < n; q += gridDim.y * kImageOpThreads) {
         const u32x4 xv = x[q], yv = y[q];
         const T* xe = (const T*)&xv;
         const T* ye = (const T*)&yv;
@@ -240,7 +241,7 @@ __device__ void add_row(const GapArgs& a, const LayerDev& L, uint32_t p)
         for (uint32_t e = 0; e < EPC; ++e) o[e] = (T)activate((float)xe[e] + (float)ye[e], L.act);
         out[q] = __builtin_bit_cast(u32x4, o);
     }
-    for (uint32_t q = n + threadIdx.x; q < L.out_fill / EPC; q += kImageOpThreads) out[q] = u32x4{0, 0, 0, 0};
+    for (uint32_t q = n + blockIdx.y * kImageOpThreads + threadIdx.x; q < L.out_fill / EPC; q += gridDim.y * kImageOpThreads) out[q] = u32x4{0, 0, 0, 0};
 }
 
 __global__ __launch_bounds__(kImageOpThreads) void image_ops_kernel(GapArgs a)
@@ -404,9 +405,9 @@ hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
     hipLaunchKernelGGL(gather_kernel, dim3(a.P / kBrickRows), dim3(256), 0, s, a);
     return hipGetLastError();
 }
-hipError_t launch_gather_image(const GatherArgs& a, hipStream_t s)
+hipError_t launch_gather_image(const GatherArgs& a, uint32_t slices, hipStream_t s)
 {
-    hipLaunchKernelGGL(gather_image_kernel, dim3(a.P), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(gather_image_kernel, dim3(a.P, slices), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_gap(const GapArgs& a, hipStream_t s)
@@ -415,9 +416,9 @@ hipError_t launch_gap(const GapArgs& a, hipStream_t s)
     hipLaunchKernelGGL(gap_kernel, dim3(a.P), dim3(kGapThreads), 0, s, a);
     return hipGetLastError();
 }
-hipError_t launch_image_ops(const GapArgs& a, hipStream_t s)
+hipError_t launch_image_ops(const GapArgs& a, uint32_t slices, hipStream_t s)
 {
-    hipLaunchKernelGGL(image_ops_kernel, dim3(a.P), dim3(kImageOpThreads), 0, s, a);
+    hipLaunchKernelGGL(image_ops_kernel, dim3(a.P, slices), dim3(kImageOpThreads), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_head(const HeadArgs& a, hipStream_t s)
