@@ -301,6 +301,7 @@ def measure(name, steps, warmup, interleave, cpu_seconds, calibrate_copy_mib=0):
                   "fc_big_by_layer": [g * 1e3 for g in big_ms if g > 0],
                   "conv_by_layer": [g * 1e3 for g in conv_ms if g > 0],
                   "gap": float(np.sum([np.mean([p["gap_ms"][l] for p in prof]) for l in range(n_slots)])) * 1e3,
+                  "image_ops_by_layer": [g * 1e3 for g in (float(np.mean([p["ops_ms"][l] for p in prof])) for l in range(n_slots)) if g > 0],
                   "head": float(np.mean([p["head_ms"] for p in prof])) * 1e3,
                   "device_total": float(np.mean([p["total_ms"] for p in prof])) * 1e3}
     ctx.close()
