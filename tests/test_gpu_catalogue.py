@@ -102,6 +102,22 @@ def test_residual_blocks_with_identity_and_projection_skips(dtype):
     run_and_compare(fleet("residual", [identity, projected, two_blocks, plain, mlp], 41, dtype, seed=204), "residual blocks %s" % dtype)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_large_images_share_a_row_among_workgroups(dtype):
+    """Images of more than 2048 pixels: several workgroups share one packed row in the image gather (three-channel
+    rows with an even and with an odd pixel count, and eight-channel rows, which take the generic path), in the
+    max-pool (window over a 53 x 61 image: the slices end inside an image row) and in the residual addition."""
+    c = 16
+    three = [conv(3, c, (53, 61), 3, 1), pool(c, (53, 61), 3, 2, 1), conv(c, c, (27, 31), 3, act=wl.ACT_NONE), add(c, (27, 31), src2=2)] + tail(c, (27, 31), 5)
+    wide = [conv(3, 8, (53, 61), 1, 1, act=wl.ACT_NONE), pool(8, (53, 61), 2, 1, 0), conv(8, 24, (52, 60), 3, 2),
+            conv(24, 24, (26, 30), 3, act=wl.ACT_NONE), add(24, (26, 30), src2=3, act=wl.ACT_NONE)] + tail(24, (26, 30), 5)
+    run_and_compare(fleet("large three-channel images", [three, wide], 7, dtype, seed=206), "large images, 3 channels, %s" % dtype)
+    eight = [conv(8, c, (48, 50), 3, 2), pool(c, (24, 25), 3, 1, 1), conv(c, c, (24, 25), 3, act=wl.ACT_NONE), add(c, (24, 25), src2=2)] + tail(c, (24, 25), 5)
+    run_and_compare(fleet("large eight-channel images", [eight, eight], 5, dtype, seed=207), "large images, 8 channels, %s" % dtype)
+    even = [conv(3, c, (54, 60), 3, 2), conv(c, c, (27, 30), 3)] + tail(c, (27, 30), 5)
+    run_and_compare(fleet("large three-channel images, pixel pairs", [even], 4, dtype, seed=208), "large images, even pixel count, %s" % dtype)
+
+
 def test_folded_batch_normalisation():
     nets = [[conv(3, 16, 8, 3), conv(16, 32, 8, 1, 2), conv(32, 32, 4, 3, act=wl.ACT_NONE), conv(16, 32, 8, 1, 2, act=wl.ACT_NONE, src=1),
              add(32, 4, src=3, src2=4)] + tail(32, 4, 6)] * 3
