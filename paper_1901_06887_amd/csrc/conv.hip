@@ -190,7 +190,10 @@ __device__ __forceinline__ void conv_wave(const GemmArgs& a, const LayerDev& L, 
         }
         activate_block<4>(y, L.act);
         // N is a multiple of 8, so the channels of this block that exist are whole 16-byte chunks for bf16 and pairs of them for fp32
-        store_unit_nhwc<T>(y, out ? out + nbase : nullptr, min((uint32_t)kBrickRows, L.N - nbase), scratch);
+        const uint32_t nvalid = min((uint32_t)kBrickRows, L.N - nbase);
+        if (L.fuse_add)
+            add_residual<T>(y, out ? (const T*)act_of(a.act, L.in2_buf) + (out - (T*)act_of(a.act, L.out_buf)) + nbase : nullptr, lh, nvalid, L.fuse_add - 1);
+        store_unit_nhwc<T>(y, out ? out + nbase : nullptr, nvalid, scratch);
     }
 }
 
@@ -436,7 +439,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         }
         __builtin_amdgcn_sched_barrier(0);
         activate_block<4>(y, L.act);
-        store_unit_nhwc<T>(y, out, min((uint32_t)kBrickRows, L.N - nbase), scratch);
+        const uint32_t nvalid = min((uint32_t)kBrickRows, L.N - nbase);
+        if (L.fuse_add)
+            add_residual<T>(y, out ? (const T*)act_of(a.act, L.in2_buf) + (out - (T*)act_of(a.act, L.out_buf)) : nullptr, lh, nvalid, L.fuse_add - 1);
+        store_unit_nhwc<T>(y, out, nvalid, scratch);
     }
 }
 
@@ -619,7 +625,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
         }
         __builtin_amdgcn_sched_barrier(0);
         activate_block<4>(y, L.act);
-        store_unit_nhwc<T>(y, out, min((uint32_t)kBrickRows, L.N - nbase), scratch);
+        const uint32_t nvalid = min((uint32_t)kBrickRows, L.N - nbase);
+        if (L.fuse_add)
+            add_residual<T>(y, out ? (const T*)act_of(a.act, L.in2_buf) + (out - (T*)act_of(a.act, L.out_buf)) : nullptr, lh, nvalid, L.fuse_add - 1);
+        store_unit_nhwc<T>(y, out, nvalid, scratch);
     }
 }
 

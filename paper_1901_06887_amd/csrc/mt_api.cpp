@@ -120,6 +120,7 @@ struct mt_ctx {
     uint32_t max_reg_classes = 0, min_reg_classes = 0;
     uint32_t no_fused_head = 0;    // tuning/testing: always run the separate head kernel
     uint32_t no_fused_pool = 0;    // tuning/testing: always run the separate pooling kernel
+    uint32_t no_fused_add = 0;     // tuning/testing: residual additions always run as launches of their own
     uint32_t big_min_tiles = kBigMinTiles;   // testing: MT_BIG_MIN_TILES=1 sends every qualifying tenant-layer to big tiles
     uint32_t P_cap = 0;        // packed rows incl. per-tenant padding to 32
 
@@ -416,6 +417,7 @@ void recompute_bounds(mt_ctx* c)
         }
         for (uint32_t l = 0; l < t.n_layers; ++l) {
             const LayerDev& L = t.layers[l].dev;
+            if (L.kind == kKindNone) continue;
             if (L.kind == MT_GAP) { c->has_gap[l] = 1; continue; }
             if (L.kind == MT_MAXPOOL || L.kind == MT_ADD) { c->has_image_ops[l] = 1; c->image_op_fill[l] = std::max(c->image_op_fill[l], L.out_fill); continue; }
             const int k = L.kind == MT_FC ? 0 : 1;
@@ -626,6 +628,21 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
         if (conv.N % kWidthAlign == 0 && (conv.rows_per_req == kBrickRows || conv.rows_per_req == 2 * kBrickRows) && last_use[l] == l)
             conv.pool_fill = round_up(out->layers[l].dev.N, kWidthAlign);
     }
+    // A convolution whose output goes to a residual addition right behind it and nowhere else adds the
+    // other operand itself (rounding its own output first, as the addition would have read it) and writes
+    // what the addition would have written; the addition's index is then empty for this tenant.
+    bool fused_add[MT_MAX_LAYERS] = {};
+    for (uint32_t l = 1; l < n_layers && !c->no_fused_add; ++l) {
+        const LayerDev& add = out->layers[l].dev;
+        LayerDev& conv = out->layers[l - 1].dev;
+        if (add.kind != MT_ADD || conv.kind != MT_CONV2D || conv.pool_fill || last_use[l] != l) continue;
+        if (src_of[l] != l && src2_of[l] != l) continue;                            // neither operand is that convolution's output
+        const uint32_t other = src_of[l] == l ? src2_of[l] : src_of[l];
+        if (other == l) continue;                                                   // x + x
+        fused_add[l] = true;
+        conv.fuse_add = 1 + add.act;
+        src2_of[l - 1] = other;                                                     // the convolution reads it now
+    }
     // Activation buffers: the request sits in buffer 0; a layer writes the lowest-numbered buffer that
     // holds no value still to be read at or after its index (its own inputs included).  A plain chain
     // alternates between two buffers.
@@ -634,8 +651,12 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
     for (uint32_t l = 0; l < n_layers; ++l) {
         LayerDev& d = out->layers[l].dev;
         d.in_buf = buf_of[src_of[l]];
-        d.in2_buf = d.kind == MT_ADD ? buf_of[src2_of[l]] : 0;
+        d.in2_buf = (d.kind == MT_ADD || d.fuse_add) ? buf_of[src2_of[l]] : 0;
         if (d.is_last) break;                                 // logits have a buffer of their own
+        if (fused_add[l]) {                                   // the sum is where the convolution before wrote it
+            buf_of[l + 1] = buf_of[l]; d.out_buf = buf_of[l]; d.kind = kKindNone;
+            continue;
+        }
         uint32_t pick = kActBuffers;
         for (uint32_t b = 0; b < (uint32_t)kActBuffers && pick == (uint32_t)kActBuffers; ++b) {
             bool busy = false;
@@ -782,6 +803,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     if (const char* e = getenv("MT_NO_FUSED_HEAD")) c->no_fused_head = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_POOL")) c->no_fused_pool = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_CONV_IMG")) c->no_conv_img = atoi(e) != 0;
+    if (const char* e = getenv("MT_NO_FUSED_ADD")) c->no_fused_add = atoi(e) != 0;
     if (const char* e = getenv("MT_BIG_MIN_TILES")) c->big_min_tiles = (uint32_t)std::max(1, atoi(e));
     c->cache = cfg->cache != 0;
     c->tenants.resize(cfg->max_tenants);
@@ -1561,12 +1583,12 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
                     chain = std::max(chain, kUsFcChainFixed + kUsPerKStep * k_steps);
                 }
             } else if (d.kind == MT_CONV2D) {
-                const double out_elems = c->pool_fused[l] ? d.N : d.out_len;      // pooled on the way out
+                const double out_elems = (c->pool_fused[l] ? d.N : d.out_len) + (d.fuse_add ? d.out_len : 0);      // pooled on the way out; the other operand of an addition done here
                 conv_mb += (M * ((double)d.in_h * d.in_w * d.cin + out_elems) * es + (double)d.N_pad * d.K * es) / MB;
                 conv_mflop += 2.0 * M * d.rows_per_req * d.k_valid * d.N / 1e6;
             } else if (d.kind == MT_GAP) {
                 gap_mb += M * ((double)d.in_h * d.in_w * d.cin + d.out_len) * es / MB;
-            } else {                                               // max-pool, addition (two inputs)
+            } else if (d.kind == MT_MAXPOOL || d.kind == MT_ADD) {    // an addition has two inputs
                 ops_mb += M * ((double)d.in_h * d.in_w * d.cin * (d.kind == MT_ADD ? 2.0 : 1.0) + d.out_len) * es / MB;
             }
         }

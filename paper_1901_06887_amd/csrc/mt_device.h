@@ -143,6 +143,27 @@ __device__ __forceinline__ void activate_block(f32x4 (&y)[G], uint32_t act)
     }
 }
 
+// A residual addition done by the convolution in front of it.  y holds this lane's four runs of four
+// channels (8 g + 4 lh + {0..3}) of one pixel, bias and the convolution's activation applied: they are
+// rounded to T, as the addition would have read them, the other operand's values of the same pixel and
+// channels are added, and the addition's activation follows.  `skip` points into the other operand
+// where `out` points into the output (null for lanes without a pixel); channels from `nvalid` on do not exist.
+template <typename T>
+__device__ __forceinline__ void add_residual(f32x4 (&y)[4], const T* skip, uint32_t lh, uint32_t nvalid, uint32_t act)
+{
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        if (skip != nullptr && 8 * g + 4 * lh < nvalid) {        // channel counts are multiples of 8: a run exists whole or not at all
+            T sv[4];
+            if constexpr (sizeof(T) == 2) *(uint64_t*)sv = *(const uint64_t*)(skip + 8 * g + 4 * lh);
+            else *(u32x4*)sv = *(const u32x4*)(skip + 8 * g + 4 * lh);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[g][e] = (float)(T)y[g][e] + (float)sv[e];
+        }
+    }
+    activate_block<4>(y, act);
+}
+
 template <typename T> struct Mma;
 // bf16: one 16-byte chunk is a whole MFMA operand (8 consecutive k of one row).
 template <> struct Mma<__bf16> {

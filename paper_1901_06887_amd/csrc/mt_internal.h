@@ -56,6 +56,7 @@ constexpr int kChanPad = 8;         // conv input channels are padded to a multi
 constexpr int kWidthAlign = 64;     // K and activation widths are zero-padded to a multiple of this
 
 enum : uint32_t { kLayoutRows = 0, kLayoutBricks = 1 };
+constexpr uint32_t kKindNone = 0xffu;     // a layer index at which this tenant has nothing to run (its work was taken over by the layer before)
 
 // One layer of one tenant, as the kernels see it (lives in device memory).
 struct LayerDev {
@@ -79,6 +80,11 @@ struct LayerDev {
     // which of the run's activation buffers the layer reads (in2_buf: the second operand of ADD) and writes;
     // pool_buf: where a convolution that pools by itself writes (the out_buf of the pooling layer behind it)
     uint32_t in_buf, in2_buf, out_buf, pool_buf;
+    // CONV whose output goes to a residual addition and nowhere else: the convolution adds the other operand
+    // (buffer in2_buf, same pixel and channel) to its rounded output itself and applies the addition's
+    // activation; 1 + that activation, else 0.  The addition's own row then has kind kKindNone.
+    uint32_t fuse_add;
+    uint32_t reserved_;
     uint64_t w_off;      // byte offset of the packed weights in the arena
     uint64_t b_off;      // byte offset of the fp32 bias in the arena (N_pad entries for FC)
 };

@@ -118,6 +118,36 @@ def test_large_images_share_a_row_among_workgroups(dtype):
     run_and_compare(fleet("large three-channel images, pixel pairs", [even], 4, dtype, seed=208), "large images, even pixel count, %s" % dtype)
 
 
+def test_additions_done_by_the_convolution_in_front_of_them(monkeypatch):
+    """A convolution whose output feeds only the residual addition behind it adds the other operand itself
+    (either operand order, identity and projected skips, an activation on the convolution as well, ragged
+    channel counts); an addition whose first operand has another reader, or follows a pooling layer, stays a
+    launch of its own.  With the takeover switched off the outputs are the same to the bit, and the run
+    has more launches."""
+    c = 24
+    swapped = [conv(3, c, 8, 3), conv(c, c, 8, 3), conv(c, c, 8, 3, act=wl.ACT_GELU), add(c, 8, src=1, src2=3, act=wl.ACT_NONE)] + tail(c, 8, 4)       # the convolution's output as second operand, activations on both
+    projected = [conv(3, 16, 8, 3), conv(16, 72, 8, 3, 2), conv(72, 72, 4, 3, act=wl.ACT_NONE),
+                 conv(16, 72, 8, 1, 2, act=wl.ACT_NONE, src=1), add(72, 4, src=3, src2=4)] + tail(72, 4, 4)               # the 1x1 projection takes the sum; 72 channels: a ragged block
+    shared = [conv(3, c, 8, 3), conv(c, c, 8, 3, act=wl.ACT_NONE), add(c, 8, src2=1), add(c, 8, src=2, src2=3)] + tail(c, 8, 4)      # the convolution's output is read twice: not taken over
+    pooled = [conv(3, c, 8, 3), conv(c, c, 8, 3), pool(c, 8, 3, 1, 1), add(c, 8, src2=1)] + tail(c, 8, 4)                   # behind a pooling layer
+    for dtype in ("bf16", "f32"):
+        w = fleet("additions", [swapped, projected, shared, pooled], 37, dtype, seed=209)
+        counts = np.bincount(w.tenant_ids, minlength=4).astype(np.uint32)
+        monkeypatch.delenv("MT_NO_FUSED_ADD", raising=False)
+        ctx = make_context(w)
+        fused_launches = ctx.estimate_run(counts)["launches"]
+        ctx.close()
+        fused = run_and_compare(w, "additions taken over, %s" % dtype)
+        monkeypatch.setenv("MT_NO_FUSED_ADD", "1")
+        ctx = make_context(w)
+        plain_launches = ctx.estimate_run(counts)["launches"]
+        plain = gpu_run(ctx, w, poison=True)
+        ctx.close()
+        monkeypatch.delenv("MT_NO_FUSED_ADD")
+        assert np.array_equal(fused[0], plain[0]) and np.array_equal(fused[2], plain[2]), dtype
+        assert fused_launches < plain_launches, (fused_launches, plain_launches)
+
+
 def test_folded_batch_normalisation():
     nets = [[conv(3, 16, 8, 3), conv(16, 32, 8, 1, 2), conv(32, 32, 4, 3, act=wl.ACT_NONE), conv(16, 32, 8, 1, 2, act=wl.ACT_NONE, src=1),
              add(32, 4, src=3, src2=4)] + tail(32, 4, 6)] * 3
