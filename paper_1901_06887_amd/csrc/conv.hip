@@ -311,53 +311,98 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
     gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
     const uint32_t last_kb = n_chunks * kConvKC - 1;
-    // The next kConvKC k steps of this wave's pixel block and of its filter block: 2 * kConvKC
-    // loads.  Chunks past the end gather zeros (th >= 3) and repeat the last filter bricks, which
-    // keeps the number of loads per round, and with it the wait below, uniform.
+    // one k step of a chunk: the gather of this wave's pixel block, the brick of its filter block
+    // (pairs: k step kk of all 32 pixels; QUAD: both k steps of pixels 16 kk .. 16 kk + 15)
+    auto fetch_gather = [&](uint32_t c, uint32_t kk) {
+        const int32_t chunk = walk[QUAD ? kk : 0].next();
+        gptr_t p = chunk >= 0 ? img[QUAD ? kk : 0] + chunk : zeros;
+        lds_dma16(p, lds + (c % kConvNS) * kConvStageBytes + (wave * kConvKC + kk) * kBrickBytes);
+    };
+    auto fetch_filter = [&](uint32_t c, uint32_t kk) {
+        lds_dma16(wp + (size_t)min(c * kConvKC + kk, last_kb) * 64, lds + (c % kConvNS) * kConvStageBytes + ((4 + wave) * kConvKC + kk) * kBrickBytes);
+    };
     auto fetch_chunk = [&](uint32_t c) {
-        uint8_t* dst = lds + (c % kConvNS) * kConvStageBytes;
 #pragma unroll
-        for (uint32_t kk = 0; kk < kConvKC; ++kk) {
-            // pairs: k step kk of all 32 pixels; QUAD: both k steps of pixels 16 kk .. 16 kk + 15
-            const int32_t chunk = walk[QUAD ? kk : 0].next();
-            gptr_t p = chunk >= 0 ? img[QUAD ? kk : 0] + chunk : zeros;
-            lds_dma16(p, dst + (wave * kConvKC + kk) * kBrickBytes);
-            lds_dma16(wp + (size_t)min(c * kConvKC + kk, last_kb) * 64, dst + ((4 + wave) * kConvKC + kk) * kBrickBytes);
-        }
+        for (uint32_t kk = 0; kk < kConvKC; ++kk) { fetch_gather(c, kk); fetch_filter(c, kk); }
     };
     // where lane (li, lh) finds its 16 bytes of k step kk inside a pixel block's area of a stage
     const uint32_t a_lane = QUAD ? (li * 4 + lh) * 16 : (li * 2 + lh) * 16;
     constexpr uint32_t a_kk = QUAD ? 32 : kBrickBytes;
+    auto read_w = [&](const uint8_t* st, uint32_t kk, u32x4& wv) { wv = *(const u32x4*)(st + ((4 + wave) * kConvKC + kk) * kBrickBytes + lane * 16); };
+    auto read_a = [&](const uint8_t* st, uint32_t kk, u32x4 (&av)[RBW], uint32_t r0, uint32_t r1) {
+#pragma unroll
+        for (uint32_t r = r0; r < r1; ++r) av[r] = *(const u32x4*)(st + (wr * RBW + r) * kConvKC * kBrickBytes + kk * a_kk + a_lane);
+    };
 
     f32x16 acc[RBW];
 #pragma unroll
     for (uint32_t r = 0; r < RBW; ++r)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[r][v] = 0.0f;
-
+    auto mma = [&](const u32x4& wv, const u32x4 (&av)[RBW], uint32_t r0, uint32_t r1) {
 #pragma unroll
-    for (uint32_t c = 0; c < kConvNS - 1; ++c) fetch_chunk(c);
+        for (uint32_t r = r0; r < r1; ++r) Mma<T>::run(acc[r], wv, av[r]);       // rows = channels, columns = pixels
+    };
+    auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+    static_assert(kConvKC == 2 && kConvNS == 3 && (RBW == 2 || RBW == 4), "the schedule below is written for chunks of two k steps, two ahead");
+
     // when chunk c is needed, the loads of the kConvNS - 2 younger chunks may still be in flight
     constexpr uint32_t kOut = (kConvNS - 2) * 2 * kConvKC;
     constexpr int kWaitVm = (int)((kOut & 15) | ((kOut >> 4) << 14) | 0x0070 | 0x0F00);
-    for (uint32_t c = 0; c < n_chunks; ++c) {
+    auto chunk_barrier = [&] {                                     // chunk c is complete for every wave; every wave holds what it needs of chunk c - 1 in registers
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // this wave's LDS reads are done before the slot is handed back
         __builtin_amdgcn_s_waitcnt(kWaitVm);
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();                              // chunk c is complete for every wave; everyone is done with chunk c - 1
+        __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        fetch_chunk(c + kConvNS - 1);
+    };
+    // The two k steps of a chunk use two operand register sets, X and Y, and the second k step of a
+    // chunk is multiplied after the next chunk's barrier, so the MFMA pipe has work the moment the
+    // barrier opens; the chunk's four global->LDS loads (with the walk through the window that finds
+    // the gather's addresses) and its LDS reads are dealt out between the MFMAs, in the shadow of one
+    // already in the pipe.  Issued as one burst behind the barrier, the workgroup's sixteen loads take
+    // the L1 -> LDS path ~270 clocks to accept, during which every wave stood at its load instructions
+    // with no MFMA in flight: a workgroup alone on its CU spent as long on that as on its MFMAs.
+#pragma unroll
+    for (uint32_t c = 0; c < kConvNS - 1; ++c) fetch_chunk(c);
+    chunk_barrier();
+    fetch_chunk(kConvNS - 1);
+    u32x4 xw, yw, xa[RBW], ya[RBW];
+    read_w(lds, 0, xw); read_a(lds, 0, xa, 0, RBW);
+    read_w(lds, 1, yw); read_a(lds, 1, ya, 0, RBW);
+    fence();
+    mma(xw, xa, 0, RBW);
+    for (uint32_t c = 1; c < n_chunks; ++c) {
+        chunk_barrier();
         const uint8_t* st = lds + (c % kConvNS) * kConvStageBytes;
-#pragma unroll
-        for (uint32_t kk = 0; kk < kConvKC; ++kk) {
-            const u32x4 wv = *(const u32x4*)(st + ((4 + wave) * kConvKC + kk) * kBrickBytes + lane * 16);
-#pragma unroll
-            for (uint32_t r = 0; r < RBW; ++r) {
-                const u32x4 av = *(const u32x4*)(st + (wr * RBW + r) * kConvKC * kBrickBytes + kk * a_kk + a_lane);
-                Mma<T>::run(acc[r], wv, av);                       // rows = channels, columns = pixels
-            }
+        const uint32_t nx = c + kConvNS - 1;                       // its slot held chunk c - 1
+        fence();
+        if constexpr (RBW == 4) {
+            mma(yw, ya, 0, 1); fence();
+            fetch_gather(nx, 0); fence();
+            mma(yw, ya, 1, 2); fence();
+            read_w(st, 0, xw); read_a(st, 0, xa, 0, 1); fence();
+            mma(yw, ya, 2, 3); fence();
+            fetch_filter(nx, 0); read_a(st, 0, xa, 1, 4); fence();
+            mma(yw, ya, 3, 4); fence();
+            fetch_gather(nx, 1); fence();
+            mma(xw, xa, 0, 1); fence();
+            read_w(st, 1, yw); read_a(st, 1, ya, 0, 1); fetch_filter(nx, 1); fence();
+            mma(xw, xa, 1, 2); fence();
+            read_a(st, 1, ya, 1, 4); fence();
+            mma(xw, xa, 2, 4); fence();
+        } else {
+            mma(yw, ya, 0, 1); fence();
+            fetch_gather(nx, 0); read_w(st, 0, xw); read_a(st, 0, xa, 0, 1); fence();
+            mma(yw, ya, 1, 2); fence();
+            fetch_filter(nx, 0); read_a(st, 0, xa, 1, 2); fence();
+            mma(xw, xa, 0, 1); fence();
+            fetch_gather(nx, 1); read_w(st, 1, yw); read_a(st, 1, ya, 0, 1); fence();
+            mma(xw, xa, 1, 2); fence();
+            fetch_filter(nx, 1); read_a(st, 1, ya, 1, 2); fence();
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // this wave's LDS reads of the chunk are done before its next barrier
     }
+    mma(yw, ya, 0, RBW);
     // trailing loads have landed and every wave is done with the ring: its memory now serves as
     // the waves' store scratch
     // (this wave's bias values, the same for all its pixel blocks, are fetched in front of that
