@@ -1467,6 +1467,7 @@ constexpr double kUsFcFixed = 3.7, kUsPerMbCached = 0.132, kUsPerMbHbm = 0.18, k
 constexpr double kUsPerMbL2 = 0.056, kUsFcChainFixed = 4.0, kUsPerKStep = 0.12;
 constexpr double kUsBigFixed = 4.0, kUsBigTileFixed = 7.0, kUsBigTilePer4096 = 116.0;
 constexpr double kUsConvFixed = 5.0, kConvMbPerUs = 4.0, kConvMflopPerUs = 0.5e3;      // 4.0 TB/s, 0.5 PFLOP/s
+constexpr double kUsConvPerKStep = 0.21;     // a convolution tile's walk through K, per k-step of 32 bytes per pixel: a launch lasts at least as long as its longest tile
 constexpr double kUsSmallFixed = 3.0, kCopyMbPerUs = 3.7, kHeadMbPerUs = 5.7, kUsHeadPerRow = 0.0008;
 constexpr double kComputeUnits = 256.0;
 constexpr double kUploadBytesPerMs = 55e6, kUsUploadFixed = 20.0;     // pinned host memory to HBM over the host link: 55 GB/s measured
@@ -1562,7 +1563,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
             }
         const bool big_layer = big_tiles >= c->big_min_tiles;
         double w_mb = 0.0, l2_mb = 0.0, chain = 0.0, big_us = 0.0, conv_mb = 0.0, conv_mflop = 0.0, gap_mb = 0.0, ops_mb = 0.0;
-        double big_rounds_k = 0.0;
+        double big_rounds_k = 0.0, conv_chain = 0.0;
         for (uint32_t t = 0; t < T; ++t) {
             if (!counts[t] || l >= c->tenants[t].n_layers) continue;
             const LayerDev& d = c->tenants[t].layers[l].dev;
@@ -1586,6 +1587,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
                 const double out_elems = (c->pool_fused[l] ? d.N : d.out_len) + (d.fuse_add ? d.out_len : 0);      // pooled on the way out; the other operand of an addition done here
                 conv_mb += (M * ((double)d.in_h * d.in_w * d.cin + out_elems) * es + (double)d.N_pad * d.K * es) / MB;
                 conv_mflop += 2.0 * M * d.rows_per_req * d.k_valid * d.N / 1e6;
+                conv_chain = std::max(conv_chain, kUsConvPerKStep * d.k_valid * es / 32.0);
             } else if (d.kind == MT_GAP) {
                 gap_mb += M * ((double)d.in_h * d.in_w * d.cin + d.out_len) * es / MB;
             } else if (d.kind == MT_MAXPOOL || d.kind == MT_ADD) {    // an addition has two inputs
@@ -1593,7 +1595,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
             }
         }
         if (c->max_nt[0][l] > 0) launch(std::max(chain, kUsFcFixed + us_per_mb * w_mb + kUsPerMbL2 * l2_mb));
-        if (c->max_nt[1][l] > 0) launch(kUsConvFixed + std::max(conv_mb / kConvMbPerUs, conv_mflop / kConvMflopPerUs));
+        if (c->max_nt[1][l] > 0) launch(kUsConvFixed + std::max(conv_chain, std::max(conv_mb / kConvMbPerUs, conv_mflop / kConvMflopPerUs)));
         if (big_enabled && c->max_nt[2][l] > 0 && tile_bound(c, 2, l, R) >= c->big_min_tiles) {
             // tiles share the chip in rounds of one per compute unit; a tile's time grows with K
             if (big_layer) big_us = std::ceil(big_tiles / kComputeUnits) * kUsBigTileFixed + big_rounds_k / kComputeUnits / 4096.0 * kUsBigTilePer4096;
