@@ -358,3 +358,32 @@ def test_wider_catalogue_is_validated():
         c.register_model(1, block, *zeros(block), bn=bn)
     assert e.value.status == 1
     c.close()
+
+
+def test_additions_are_planned_into_the_convolution_in_front_of_them(monkeypatch):
+    """Host planning only: an addition whose operand is the output of the convolution right before it, read by nothing
+    else, costs no launch (the run estimate counts launches as mt_run enqueues them); one whose convolution output has a
+    second reader, or that follows a pooling layer, keeps its launch; MT_NO_FUSED_ADD=1 keeps them all."""
+    import workloads as wl
+    conv = lambda ci, co, hw, k=3, s=1, act=wl.ACT_RELU, src=0: wl.LayerSpec(wl.CONV, act, ci, co, hw, hw, s, ksize=k, pad=(k - 1) // 2, src=src)
+    add = lambda ch, hw, src2, src=0, act=wl.ACT_RELU: wl.LayerSpec(wl.ADD, act, ch, ch, hw, hw, src=src, src2=src2)
+    pool = lambda ch, hw: wl.LayerSpec(wl.MAXPOOL, wl.ACT_NONE, ch, ch, hw, hw, 1, ksize=3, pad=1)
+    tail = lambda ch, hw: [wl.LayerSpec(wl.GAP, wl.ACT_NONE, ch, ch, hw, hw), wl.LayerSpec(wl.FC, wl.ACT_NONE, ch, 4)]
+    c = 16
+    taken = [conv(3, c, 8), conv(c, c, 8), conv(c, c, 8, act=wl.ACT_NONE), add(c, 8, src2=1)] + tail(c, 8)                 # 1 addition, taken over
+    swapped = [conv(3, c, 8), conv(c, c, 8), conv(c, c, 8, act=wl.ACT_NONE), add(c, 8, src=1, src2=3)] + tail(c, 8)       # the same with the operands swapped
+    shared = [conv(3, c, 8), conv(c, c, 8, act=wl.ACT_NONE), add(c, 8, src2=1), add(c, 8, src=2, src2=3)] + tail(c, 8)     # the convolution's output has two readers
+    pooled = [conv(3, c, 8), conv(c, c, 8), pool(c, 8), add(c, 8, src2=1)] + tail(c, 8)                                   # the addition follows a pooling layer
+    def launches(layers):
+        w = wl.Workload("m", "bf16", {0: wl.make_model(layers, "bf16", 5, 0)}, np.zeros(3, dtype=np.int32), np.zeros((3, 8 * 8 * 3), dtype=np.float32))
+        ctx = mt.context_for(w.tenants, w.dtype, 3, device=-1)
+        mt.register_tenants(ctx, w.tenants)
+        n = ctx.estimate_run(np.array([3], dtype=np.uint32))["launches"]
+        ctx.close()
+        return n
+    monkeypatch.setenv("MT_NO_FUSED_ADD", "1")
+    plain = {k: launches(v) for k, v in (("taken", taken), ("swapped", swapped), ("shared", shared), ("pooled", pooled))}
+    monkeypatch.delenv("MT_NO_FUSED_ADD")
+    fused = {k: launches(v) for k, v in (("taken", taken), ("swapped", swapped), ("shared", shared), ("pooled", pooled))}
+    assert fused["taken"] == plain["taken"] - 1 and fused["swapped"] == plain["swapped"] - 1
+    assert fused["shared"] == plain["shared"] and fused["pooled"] == plain["pooled"]
