@@ -251,7 +251,7 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
 // operand read (lane (li, lh) takes piece 2 li + lh) touches every bank once.  K is walked in chunks of kConvKC k steps through a ring of kConvNS stages, chunks
 // kConvNS - 1 ahead of their use.
 constexpr uint32_t kConvKC = 2, kConvNS = 3;
-constexpr uint32_t kConvStageBytes = 8 * kConvKC * kBrickBytes;      // 4 pixel blocks + 4 filter areas, kConvKC k steps each
+constexpr uint32_t kConvDeepKC = 4, kConvDeepNS = 4;   // chunks and ring of a workgroup that is alone on its CU (see PW below): 128 KiB
 
 // QUAD (every tenant's input channels are a multiple of 4 chunks, i.e. a pixel's share of two k
 // steps is 64 contiguous bytes): a gather instruction then takes 16 pixels with four consecutive
@@ -262,17 +262,25 @@ constexpr uint32_t kConvStageBytes = 8 * kConvKC * kBrickBytes;      // 4 pixel 
 // of the CNN mix) and not where it reads four (NCB = 4: 40.4 against 38.1 us on the 64 -> 128
 // layer, where the counters showed the conflicts as half of the LDS pipe's busy time), so the
 // launcher asks for it with two channel blocks only.
-template <typename T, int NCB, bool QUAD>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_lds_kernel(GemmArgs a)     // three workgroups per CU is what the LDS ring allows
+// PW = 1: eight waves; waves 4..7 issue the loads (wave 4 + w what wave w would have issued: the gather of pixel
+// block w, the bricks of filter block w) and do nothing else, waves 0..3 read and multiply.  For launches of few
+// tiles with a long K (deep layers of small batches): their workgroups sit alone on their CUs, one wave per SIMD,
+// and a wave that issues its own loads stands at every one of them for ~100 clocks with no MFMA in the pipe.
+template <typename T, int NCB, bool QUAD, int PW>
+__global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(PW ? 2 : 3, 3))) void conv_lds_kernel(GemmArgs a)     // PW = 0: three workgroups per CU is what the LDS ring allows
 {
-    static_assert(!QUAD || kConvKC == 2, "a quad gather covers exactly two k steps");
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
+    constexpr uint32_t KC = PW ? kConvDeepKC : kConvKC, NS = PW ? kConvDeepNS : kConvNS;   // k steps per chunk; stages of the ring (chunks are fetched NS - 1 ahead)
+    constexpr uint32_t kStageBytes = 8 * KC * kBrickBytes;             // 4 pixel blocks + 4 filter areas, KC k steps each
+    static_assert(!QUAD || KC == 2, "a quad gather covers exactly two k steps");
     constexpr uint32_t WR = 4 / NCB, RBW = 4 / WR;                  // wave rows; pixel blocks per wave
     typedef const __attribute__((address_space(1))) u32x4* gptr_t;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kConvNS * kConvStageBytes];
-    __shared__ uint32_t owner_part[4];
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), li = lane & 31, lh = lane >> 5;
-    TileOwner<256> lookup;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[NS * kStageBytes];
+    __shared__ uint32_t owner_part[4 * (1 + PW)];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    const uint32_t wave_all = __builtin_amdgcn_readfirstlane(tid >> 6), wave = wave_all % 4;
+    const bool loader = !PW || wave_all >= 4, worker = !PW || wave_all < 4;     // who issues the loads, who multiplies
+    TileOwner<256 * (1 + PW)> lookup;
     lookup.fetch(a.tile_base, a.T);
     const uint32_t n_tiles = a.tile_base[a.T];
     uint32_t idx;
@@ -287,7 +295,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
     const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
     const uint32_t nKB = L.K / KB, nKBv = ceil_div(L.k_valid, KB);
-    const uint32_t n_chunks = ceil_div(nKBv, kConvKC);             // n_chunks * kConvKC <= nKB: K is padded to 64
+    const uint32_t n_chunks = ceil_div(nKBv, KC);             // n_chunks * KC <= nKB: K is padded to 64
     const uint32_t wc = wave % NCB, wr = wave / NCB;
     const bool active = wc < ncb;                                  // idle waves still gather; they stream block 0 and drop it
 
@@ -310,28 +318,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
                      QUAD ? (lane & 3) * EPC : (lane & 1) * EPC, QUAD ? 2 * KB : KB);
     }
     gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
-    const uint32_t last_kb = n_chunks * kConvKC - 1;
+    const uint32_t last_kb = n_chunks * KC - 1;
     // one k step of a chunk: the gather of this wave's pixel block, the brick of its filter block
     // (pairs: k step kk of all 32 pixels; QUAD: both k steps of pixels 16 kk .. 16 kk + 15)
     auto fetch_gather = [&](uint32_t c, uint32_t kk) {
         const int32_t chunk = walk[QUAD ? kk : 0].next();
         gptr_t p = chunk >= 0 ? img[QUAD ? kk : 0] + chunk : zeros;
-        lds_dma16(p, lds + (c % kConvNS) * kConvStageBytes + (wave * kConvKC + kk) * kBrickBytes);
+        lds_dma16(p, lds + (c % NS) * kStageBytes + (wave * KC + kk) * kBrickBytes);
     };
     auto fetch_filter = [&](uint32_t c, uint32_t kk) {
-        lds_dma16(wp + (size_t)min(c * kConvKC + kk, last_kb) * 64, lds + (c % kConvNS) * kConvStageBytes + ((4 + wave) * kConvKC + kk) * kBrickBytes);
+        lds_dma16(wp + (size_t)min(c * KC + kk, last_kb) * 64, lds + (c % NS) * kStageBytes + ((4 + wave) * KC + kk) * kBrickBytes);
     };
     auto fetch_chunk = [&](uint32_t c) {
 #pragma unroll
-        for (uint32_t kk = 0; kk < kConvKC; ++kk) { fetch_gather(c, kk); fetch_filter(c, kk); }
+        for (uint32_t kk = 0; kk < KC; ++kk) { fetch_gather(c, kk); fetch_filter(c, kk); }
     };
     // where lane (li, lh) finds its 16 bytes of k step kk inside a pixel block's area of a stage
     const uint32_t a_lane = QUAD ? (li * 4 + lh) * 16 : (li * 2 + lh) * 16;
     constexpr uint32_t a_kk = QUAD ? 32 : kBrickBytes;
-    auto read_w = [&](const uint8_t* st, uint32_t kk, u32x4& wv) { wv = *(const u32x4*)(st + ((4 + wave) * kConvKC + kk) * kBrickBytes + lane * 16); };
+    auto read_w = [&](const uint8_t* st, uint32_t kk, u32x4& wv) { wv = *(const u32x4*)(st + ((4 + wave) * KC + kk) * kBrickBytes + lane * 16); };
     auto read_a = [&](const uint8_t* st, uint32_t kk, u32x4 (&av)[RBW], uint32_t r0, uint32_t r1) {
 #pragma unroll
-        for (uint32_t r = r0; r < r1; ++r) av[r] = *(const u32x4*)(st + (wr * RBW + r) * kConvKC * kBrickBytes + kk * a_kk + a_lane);
+        for (uint32_t r = r0; r < r1; ++r) av[r] = *(const u32x4*)(st + (wr * RBW + r) * KC * kBrickBytes + kk * a_kk + a_lane);
     };
 
     f32x16 acc[RBW];
@@ -344,10 +352,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         for (uint32_t r = r0; r < r1; ++r) Mma<T>::run(acc[r], wv, av[r]);       // rows = channels, columns = pixels
     };
     auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
-    static_assert(kConvKC == 2 && kConvNS == 3 && (RBW == 2 || RBW == 4), "the schedule below is written for chunks of two k steps, two ahead");
+    static_assert((PW || KC == 2) && KC % 2 == 0 && (RBW == 2 || RBW == 4), "the schedules below: chunks of two k steps, or an even number with loader waves");
 
-    // when chunk c is needed, the loads of the kConvNS - 2 younger chunks may still be in flight
-    constexpr uint32_t kOut = (kConvNS - 2) * 2 * kConvKC;
+    // when chunk c is needed, the loads of the NS - 2 younger chunks may still be in flight
+    constexpr uint32_t kOut = (NS - 2) * 2 * KC;
     constexpr int kWaitVm = (int)((kOut & 15) | ((kOut >> 4) << 14) | 0x0070 | 0x0F00);
     auto chunk_barrier = [&] {                                     // chunk c is complete for every wave; every wave holds what it needs of chunk c - 1 in registers
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // this wave's LDS reads are done before the slot is handed back
@@ -363,46 +371,78 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     // already in the pipe.  Issued as one burst behind the barrier, the workgroup's sixteen loads take
     // the L1 -> LDS path ~270 clocks to accept, during which every wave stood at its load instructions
     // with no MFMA in flight: a workgroup alone on its CU spent as long on that as on its MFMAs.
+    if (loader) {
 #pragma unroll
-    for (uint32_t c = 0; c < kConvNS - 1; ++c) fetch_chunk(c);
+        for (uint32_t c = 0; c < NS - 1; ++c) fetch_chunk(c);
+    }
     chunk_barrier();
-    fetch_chunk(kConvNS - 1);
-    u32x4 xw, yw, xa[RBW], ya[RBW];
-    read_w(lds, 0, xw); read_a(lds, 0, xa, 0, RBW);
-    read_w(lds, 1, yw); read_a(lds, 1, ya, 0, RBW);
-    fence();
-    mma(xw, xa, 0, RBW);
-    for (uint32_t c = 1; c < n_chunks; ++c) {
-        chunk_barrier();
-        const uint8_t* st = lds + (c % kConvNS) * kConvStageBytes;
-        const uint32_t nx = c + kConvNS - 1;                       // its slot held chunk c - 1
+    if (loader) fetch_chunk(NS - 1);
+    auto load_gather = [&](uint32_t c, uint32_t kk) { if constexpr (!PW) fetch_gather(c, kk); };
+    auto load_filter = [&](uint32_t c, uint32_t kk) { if constexpr (!PW) fetch_filter(c, kk); };
+    if (worker && PW) {
+        // loads are someone else's business: a plain pipeline, the operands of a k step are read while the step
+        // before it multiplies, and the barrier of the next chunk stands in front of the read of its first step
+        u32x4 w[2], av[2][RBW];
+        read_w(lds, 0, w[0]); read_a(lds, 0, av[0], 0, RBW);
+        for (uint32_t c = 0; c < n_chunks; ++c) {
+            const uint8_t* st = lds + (c % NS) * kStageBytes;
+#pragma unroll
+            for (uint32_t kk = 0; kk < KC; ++kk) {
+                if (kk + 1 < KC) {
+                    read_w(st, kk + 1, w[(kk + 1) % 2]); read_a(st, kk + 1, av[(kk + 1) % 2], 0, RBW);
+                } else if (c + 1 < n_chunks) {
+                    chunk_barrier();
+                    const uint8_t* nst = lds + ((c + 1) % NS) * kStageBytes;
+                    read_w(nst, 0, w[0]); read_a(nst, 0, av[0], 0, RBW);
+                }
+                fence();
+                mma(w[kk % 2], av[kk % 2], 0, RBW);
+                fence();
+            }
+        }
+    } else if (worker) {
+        u32x4 xw, yw, xa[RBW], ya[RBW];
+        read_w(lds, 0, xw); read_a(lds, 0, xa, 0, RBW);
+        read_w(lds, 1, yw); read_a(lds, 1, ya, 0, RBW);
         fence();
-        if constexpr (RBW == 4) {
-            mma(yw, ya, 0, 1); fence();
-            fetch_gather(nx, 0); fence();
-            mma(yw, ya, 1, 2); fence();
-            read_w(st, 0, xw); read_a(st, 0, xa, 0, 1); fence();
-            mma(yw, ya, 2, 3); fence();
-            fetch_filter(nx, 0); read_a(st, 0, xa, 1, 4); fence();
-            mma(yw, ya, 3, 4); fence();
-            fetch_gather(nx, 1); fence();
-            mma(xw, xa, 0, 1); fence();
-            read_w(st, 1, yw); read_a(st, 1, ya, 0, 1); fetch_filter(nx, 1); fence();
-            mma(xw, xa, 1, 2); fence();
-            read_a(st, 1, ya, 1, 4); fence();
-            mma(xw, xa, 2, 4); fence();
-        } else {
-            mma(yw, ya, 0, 1); fence();
-            fetch_gather(nx, 0); read_w(st, 0, xw); read_a(st, 0, xa, 0, 1); fence();
-            mma(yw, ya, 1, 2); fence();
-            fetch_filter(nx, 0); read_a(st, 0, xa, 1, 2); fence();
-            mma(xw, xa, 0, 1); fence();
-            fetch_gather(nx, 1); read_w(st, 1, yw); read_a(st, 1, ya, 0, 1); fence();
-            mma(xw, xa, 1, 2); fence();
-            fetch_filter(nx, 1); read_a(st, 1, ya, 1, 2); fence();
+        mma(xw, xa, 0, RBW);
+        for (uint32_t c = 1; c < n_chunks; ++c) {
+            chunk_barrier();
+            const uint8_t* st = lds + (c % NS) * kStageBytes;
+            const uint32_t nx = c + NS - 1;                       // its slot held chunk c - 1
+            fence();
+            if constexpr (RBW == 4) {
+                mma(yw, ya, 0, 1); fence();
+                load_gather(nx, 0); fence();
+                mma(yw, ya, 1, 2); fence();
+                read_w(st, 0, xw); read_a(st, 0, xa, 0, 1); fence();
+                mma(yw, ya, 2, 3); fence();
+                load_filter(nx, 0); read_a(st, 0, xa, 1, 4); fence();
+                mma(yw, ya, 3, 4); fence();
+                load_gather(nx, 1); fence();
+                mma(xw, xa, 0, 1); fence();
+                read_w(st, 1, yw); read_a(st, 1, ya, 0, 1); load_filter(nx, 1); fence();
+                mma(xw, xa, 1, 2); fence();
+                read_a(st, 1, ya, 1, 4); fence();
+                mma(xw, xa, 2, 4); fence();
+            } else {
+                mma(yw, ya, 0, 1); fence();
+                load_gather(nx, 0); read_w(st, 0, xw); read_a(st, 0, xa, 0, 1); fence();
+                mma(yw, ya, 1, 2); fence();
+                load_filter(nx, 0); read_a(st, 0, xa, 1, 2); fence();
+                mma(xw, xa, 0, 1); fence();
+                load_gather(nx, 1); read_w(st, 1, yw); read_a(st, 1, ya, 0, 1); fence();
+                mma(xw, xa, 1, 2); fence();
+                load_filter(nx, 1); read_a(st, 1, ya, 1, 2); fence();
+            }
+        }
+        mma(yw, ya, 0, RBW);
+    } else {
+        for (uint32_t c = 1; c < n_chunks; ++c) {                     // the loaders' loop: as many barriers as the workers'
+            chunk_barrier();
+            fetch_chunk(c + NS - 1);
         }
     }
-    mma(yw, ya, 0, RBW);
     // trailing loads have landed and every wave is done with the ring: its memory now serves as
     // the waves' store scratch
     // (this wave's bias values, the same for all its pixel blocks, are fetched in front of that
@@ -413,7 +453,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 #pragma unroll
     for (int g = 0; g < 4; ++g) bias_q[g] = *(const f32x4*)(bias + nbase + 8 * g + 4 * lh);   // bias is padded to N_pad
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    static_assert(kConvNS * kConvStageBytes >= 4 * unit_scratch_bytes<T>(), "store scratch aliases the ring");
+    static_assert(NS * kStageBytes >= 4 * unit_scratch_bytes<T>(), "store scratch aliases the ring");
+    if (!worker) return;
 
     // epilogue: lane holds, for pixel li of each of its pixel blocks, channels 8g + 4 lh + {0..3}
     if (!active) return;
@@ -679,12 +720,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
 
 // ---- launcher ------------------------------------------------------------
 template <typename T>
-static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, uint32_t grid, hipStream_t s)
+static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, bool loaders, uint32_t grid, hipStream_t s)
 {
     if (max_cb <= 1) hipLaunchKernelGGL((conv_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a);
-    else if (max_cb == 2 && quad) hipLaunchKernelGGL((conv_lds_kernel<T, 2, true>), dim3(grid), dim3(256), 0, s, a);
-    else if (max_cb == 2) hipLaunchKernelGGL((conv_lds_kernel<T, 2, false>), dim3(grid), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((conv_lds_kernel<T, 4, false>), dim3(grid), dim3(256), 0, s, a);
+    else if (max_cb == 2 && quad) hipLaunchKernelGGL((conv_lds_kernel<T, 2, true, 0>), dim3(grid), dim3(256), 0, s, a);
+    else if (max_cb == 2) hipLaunchKernelGGL((conv_lds_kernel<T, 2, false, 0>), dim3(grid), dim3(256), 0, s, a);
+    else if (loaders) hipLaunchKernelGGL((conv_lds_kernel<T, 4, false, 1>), dim3(grid), dim3(512), 0, s, a);
+    else hipLaunchKernelGGL((conv_lds_kernel<T, 4, false, 0>), dim3(grid), dim3(256), 0, s, a);
 }
 
 template <typename T>
@@ -706,17 +748,18 @@ static void launch_conv_img_t(const GemmArgs& a, uint32_t max_cb, bool two, uint
 
 // img_lds_bytes > 0: every convolution of the layer index qualifies for the LDS-resident-input kernel, whose largest frame is that
 // size; img_two: their pixels are one 16-byte chunk (else none is)
-hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, uint32_t grid, hipStream_t s)
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, bool long_k, uint32_t grid, hipStream_t s)
 {
     if (grid == 0) return hipSuccess;
     grid = (grid + 7) / 8 * 8;
+    const bool loaders = long_k && grid <= 256;                      // at most one tile per CU, every tenant's K long: waves of their own for the loads
     if (img_lds_bytes) {
         if (dtype == MT_BF16) launch_conv_img_t<__bf16>(a, max_cb, img_two, img_lds_bytes, grid, s);
         else launch_conv_img_t<float>(a, max_cb, img_two, img_lds_bytes, grid, s);
         return hipGetLastError();
     }
-    if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, quad, grid, s);
-    else launch_conv_t<float>(a, max_cb, quad, grid, s);
+    if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, quad, loaders, grid, s);
+    else launch_conv_t<float>(a, max_cb, quad, loaders, grid, s);
     return hipGetLastError();
 }
 

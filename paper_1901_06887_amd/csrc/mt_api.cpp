@@ -121,6 +121,8 @@ struct mt_ctx {
     uint32_t no_fused_head = 0;    // tuning/testing: always run the separate head kernel
     uint32_t no_fused_pool = 0;    // tuning/testing: always run the separate pooling kernel
     uint32_t no_fused_add = 0;     // tuning/testing: residual additions always run as launches of their own
+    uint32_t no_conv_loaders = 0;  // tuning/testing: convolution tiles never get waves of their own for the loads
+    uint32_t min_conv_k[MT_MAX_LAYERS]{};      // shortest reduction among the registered convolutions of a layer index
     uint32_t big_min_tiles = kBigMinTiles;   // testing: MT_BIG_MIN_TILES=1 sends every qualifying tenant-layer to big tiles
     uint32_t P_cap = 0;        // packed rows incl. per-tenant padding to 32
 
@@ -398,7 +400,7 @@ void recompute_bounds(mt_ctx* c)
     for (uint32_t& m : c->list_mask) m = 0;
     c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        c->has_gap[l] = 0; c->has_image_ops[l] = 0; c->image_op_fill[l] = 0; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
+        c->has_gap[l] = 0; c->has_image_ops[l] = 0; c->image_op_fill[l] = 0; c->min_conv_k[l] = 0xffffffffu; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
         c->max_fc_per64[l] = 0; c->max_fc_per64_sk[l] = 0; c->sum_nt_sk[l] = 0;
     }
@@ -434,6 +436,7 @@ void recompute_bounds(mt_ctx* c)
                 c->max_fc_per64_sk[l] = std::max(c->max_fc_per64_sk[l], nt_sk * (kTileRows / fc_tile_rows(L.N_pad, 1)));
             }
             if (k == 1) {
+                c->min_conv_k[l] = std::min(c->min_conv_k[l], L.k_valid);
                 c->max_conv_cb[l] = std::max(c->max_conv_cb[l], std::min<uint32_t>(L.N_pad / kBrickRows, kTileCols / kBrickRows));
                 if (L.cin % (4 * (16 / c->elem_size))) c->conv_quad[l] = false;
                 // frame of one tile of the LDS-resident-input kernel (see conv_img_kernel): whole output rows of one
@@ -804,6 +807,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     if (const char* e = getenv("MT_NO_FUSED_POOL")) c->no_fused_pool = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_CONV_IMG")) c->no_conv_img = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_ADD")) c->no_fused_add = atoi(e) != 0;
+    if (const char* e = getenv("MT_NO_CONV_LOADERS")) c->no_conv_loaders = atoi(e) != 0;
     if (const char* e = getenv("MT_BIG_MIN_TILES")) c->big_min_tiles = (uint32_t)std::max(1, atoi(e));
     c->cache = cfg->cache != 0;
     c->tenants.resize(cfg->max_tenants);
@@ -1147,6 +1151,8 @@ __global__ void fill_zero_kernel(uint32_t* p, uint32_t n)
 }
 
 // Packed rows a run of R rows can occupy: every tenant with traffic pads its segment to a multiple of 32.
+constexpr uint32_t kConvLongK = 1024;      // reductions from here on are worth loader waves when a launch has at most one tile per CU
+
 // Workgroups that share one packed row in the per-row kernels: `per_wg` units of work each, at most 64.
 static uint32_t row_slices(uint64_t units, uint32_t per_wg)
 {
@@ -1362,7 +1368,8 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
             const uint32_t g32 = (uint32_t)grid;
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
             else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], c->conv_quad[l],
-                                                                    (c->conv_img_lds[l] > 1 && !c->pool_fused[l] && !c->no_conv_img) ? c->conv_img_lds[l] : 0, c->conv_img_two[l] == 1, g32, s));
+                                                                    (c->conv_img_lds[l] > 1 && !c->pool_fused[l] && !c->no_conv_img) ? c->conv_img_lds[l] : 0, c->conv_img_two[l] == 1,
+                                                                    !c->no_conv_loaders && c->min_conv_k[l] >= kConvLongK, g32, s));
             else TIMED(kProfBig + l, launch_fc_big(ga, c->cfg.dtype, g32, s));
         }
         if (c->has_gap[l]) {
