@@ -27,9 +27,9 @@ from bench import kernel_source_sha256      # the fingerprint bench.py checks st
 
 def short_name(name: str) -> str:
     """'_ZN2mt9fc_kernelIDF16bEEvNS_8GemmArgsE' or 'mt::fc_kernel<__bf16>(...)' -> a readable name."""
-    m = re.match(r"_ZN2mt\d+([a-z_]+)I(DF16b|f)(?:Li(\d+))?(?:Lb([01]))?", name)
+    m = re.match(r"_ZN2mt\d+([a-z_]+)I(DF16b|f)((?:L[ib]\d+E)*)", name)
     if m:
-        args = ["bf16" if m.group(2) == "DF16b" else "float"] + [g for g in m.groups()[2:] if g is not None]
+        args = ["bf16" if m.group(2) == "DF16b" else "float"] + re.findall(r"L[ib](\d+)E", m.group(3))
         return "mt::%s<%s>" % (m.group(1), ",".join(args))
     m = re.match(r"_ZN2mt\d+([a-z_]+)ILb([01])", name)
     if m:
