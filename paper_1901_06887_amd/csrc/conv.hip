@@ -267,11 +267,11 @@ constexpr uint32_t kConvDeepKC = 4, kConvDeepNS = 4;   // chunks and ring of a w
 // tiles with a long K (deep layers of small batches): their workgroups sit alone on their CUs, one wave per SIMD,
 // and a wave that issues its own loads stands at every one of them for ~100 clocks with no MFMA in the pipe.
 template <typename T, int NCB, bool QUAD, int PW>
-__global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(PW ? 2 : 3, 3))) void conv_lds_kernel(GemmArgs a)     // PW = 0: three workgroups per CU is what the LDS ring allows
+__global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(PW ? 2 : NCB == 2 ? 4 : 3, NCB == 2 && !PW ? 4 : 3))) void conv_lds_kernel(GemmArgs a)     // PW = 0: as many workgroups per CU as the LDS ring allows: three (48 KiB), four with two filter blocks (36 KiB)
 {
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
     constexpr uint32_t KC = PW ? kConvDeepKC : kConvKC, NS = PW ? kConvDeepNS : kConvNS;   // k steps per chunk; stages of the ring (chunks are fetched NS - 1 ahead)
-    constexpr uint32_t kStageBytes = 8 * KC * kBrickBytes;             // 4 pixel blocks + 4 filter areas, KC k steps each
+    constexpr uint32_t kStageBytes = (4 + NCB) * KC * kBrickBytes;     // 4 pixel blocks + the tile's NCB filter blocks, KC k steps each
     static_assert(!QUAD || KC == 2, "a quad gather covers exactly two k steps");
     constexpr uint32_t WR = 4 / NCB, RBW = 4 / WR;                  // wave rows; pixel blocks per wave
     typedef const __attribute__((address_space(1))) u32x4* gptr_t;
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(
         lds_dma16(p, lds + (c % NS) * kStageBytes + (wave * KC + kk) * kBrickBytes);
     };
     auto fetch_filter = [&](uint32_t c, uint32_t kk) {
-        lds_dma16(wp + (size_t)min(c * KC + kk, last_kb) * 64, lds + (c % NS) * kStageBytes + ((4 + wave) * KC + kk) * kBrickBytes);
+        if (wr == 0) lds_dma16(wp + (size_t)min(c * KC + kk, last_kb) * 64, lds + (c % NS) * kStageBytes + ((4 + wc) * KC + kk) * kBrickBytes);   // a filter block is fetched once, by the first wave row
     };
     auto fetch_chunk = [&](uint32_t c) {
 #pragma unroll
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(
     // where lane (li, lh) finds its 16 bytes of k step kk inside a pixel block's area of a stage
     const uint32_t a_lane = QUAD ? (li * 4 + lh) * 16 : (li * 2 + lh) * 16;
     constexpr uint32_t a_kk = QUAD ? 32 : kBrickBytes;
-    auto read_w = [&](const uint8_t* st, uint32_t kk, u32x4& wv) { wv = *(const u32x4*)(st + ((4 + wave) * KC + kk) * kBrickBytes + lane * 16); };
+    auto read_w = [&](const uint8_t* st, uint32_t kk, u32x4& wv) { wv = *(const u32x4*)(st + ((4 + wc) * KC + kk) * kBrickBytes + lane * 16); };
     auto read_a = [&](const uint8_t* st, uint32_t kk, u32x4 (&av)[RBW], uint32_t r0, uint32_t r1) {
 #pragma unroll
         for (uint32_t r = r0; r < r1; ++r) av[r] = *(const u32x4*)(st + (wr * RBW + r) * KC * kBrickBytes + kk * a_kk + a_lane);
@@ -355,11 +355,12 @@ __global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(
     static_assert((PW || KC == 2) && KC % 2 == 0 && (RBW == 2 || RBW == 4), "the schedules below: chunks of two k steps, or an even number with loader waves");
 
     // when chunk c is needed, the loads of the NS - 2 younger chunks may still be in flight
-    constexpr uint32_t kOut = (NS - 2) * 2 * KC;
-    constexpr int kWaitVm = (int)((kOut & 15) | ((kOut >> 4) << 14) | 0x0070 | 0x0F00);
+    // (waves of the first wave row issue two loads per k step, gather and filter brick, the others one)
+    constexpr uint32_t kOut = (NS - 2) * 2 * KC, kOutG = (NS - 2) * KC;
+    constexpr int kWaitVm = (int)((kOut & 15) | ((kOut >> 4) << 14) | 0x0070 | 0x0F00), kWaitVmG = (int)((kOutG & 15) | ((kOutG >> 4) << 14) | 0x0070 | 0x0F00);
     auto chunk_barrier = [&] {                                     // chunk c is complete for every wave; every wave holds what it needs of chunk c - 1 in registers
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // this wave's LDS reads are done before the slot is handed back
-        __builtin_amdgcn_s_waitcnt(kWaitVm);
+        if (wr == 0) __builtin_amdgcn_s_waitcnt(kWaitVm); else __builtin_amdgcn_s_waitcnt(kWaitVmG);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
