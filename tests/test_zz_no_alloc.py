@@ -1,6 +1,6 @@
 """mt_run_static, the entry point that allocates nothing: the same run as mt_run with its scratch in
 the library's static device array.  Checked against mt_run, bit for bit, through the C ABI: two calls
-in a row, the second with a smaller batch (the array keeps what the first one left), then a CNN mix,
+in a row, the second with a smaller batch (the array keeps what the first one left), then a CNN mix, residual networks,
 a run on another stream, and a run that does not fit the array (refused, nothing enqueued, mt_run
 still serves it)."""
 import numpy as np
@@ -54,7 +54,12 @@ def test_static_run_serves_a_cnn_mix_and_a_second_context():
     mt.register_tenants(ctx2, w2.tenants)
     both_ways(ctx2, w2, np.arange(50))
     both_ways(ctx, w, np.arange(7))
-    ctx.close(); ctx2.close()
+    w3 = wl.resnet(n_tenants=2, n_requests=12, hw=32, widths=(16, 32, 64, 128), classes=10, seed=85)   # skip connections: three activation buffers in the array
+    ctx3 = mt.context_for(w3.tenants, w3.dtype, w3.n_requests)
+    mt.register_tenants(ctx3, w3.tenants)
+    both_ways(ctx3, w3, np.arange(12))
+    both_ways(ctx3, w3, np.arange(5))
+    ctx.close(); ctx2.close(); ctx3.close()
 
 
 def test_static_run_refuses_what_does_not_fit_and_keeps_the_pending_rows():
