@@ -357,3 +357,34 @@ def test_heads_of_33_to_128_classes_are_finished_by_the_fc_tile(monkeypatch):
         assert n_plain - n_fused == (1 if max(classes) <= 128 else 0), name
         assert np.array_equal(fused[0], plain[0]) and np.array_equal(fused[2], plain[2]) and np.array_equal(fused[3], plain[3])
         assert np.allclose(fused[1], plain[1], rtol=1e-6, atol=1e-7)
+
+
+@pytest.mark.parametrize("static", [False, True])
+def test_a_run_captured_in_a_graph_replays_to_the_same_answers(static):
+    """Callers with launch-bound loops capture a run in a HIP graph: the run makes no call that a capturing stream
+    refuses (mt_run_static, which allocates nothing, clears with kernels), and every replay gives the bits of the
+    eager run, with eager runs and synchronisations of the same context between the replays."""
+    w = wl.resnet(n_tenants=2, n_requests=6, hw=16, widths=(16, 32, 64, 128), classes=10, seed=301) if not static else wl.c1(n_tenants=5, n_requests=300, seed=302)
+    ctx = make_context(w)
+    ids = torch.from_numpy(w.tenant_ids).cuda()
+    x = torch_io.to_device(w.inputs, w.dtype)
+    eager = torch_io.alloc_outputs(w.n_requests, ctx.cfg.max_classes)
+    replayed = torch_io.alloc_outputs(w.n_requests, ctx.cfg.max_classes)
+    mt.serve(ctx, ids, x, out=eager, static=static)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(g, stream=s):
+        mt.serve(ctx, ids, x, out=replayed, stream=s, static=static)
+    torch.cuda.synchronize()
+    for _ in range(4):
+        replayed.logits.zero_(); replayed.probs.zero_(); replayed.labels.fill_(-7)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(replayed.logits, eager.logits) and torch.equal(replayed.labels, eager.labels) and torch.equal(replayed.probs, eager.probs)
+        half = mt.serve(ctx, ids[: w.n_requests // 2].contiguous(), x[: w.n_requests // 2].contiguous(), static=static)    # eager work of another size in between
+        torch.cuda.synchronize()
+        assert torch.equal(half.labels, eager.labels[: w.n_requests // 2])
+    assert np.array_equal(eager.labels.cpu().numpy(), oracle_rows(w)[2])
+    ctx.close()
