@@ -148,6 +148,21 @@ def test_additions_done_by_the_convolution_in_front_of_them(monkeypatch):
         assert fused_launches < plain_launches, (fused_launches, plain_launches)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_long_reductions_in_launches_of_few_tiles(dtype):
+    """Deep layers of small batches: at most one tile per CU and K >= 1024, the shape that gets loader waves, here
+    with the pooling done by the convolution (8x8 and 4x8 images of 128 and 192 channels in front of the global
+    average), with a residual addition taken over by it, and with tenants of unequal widths in one launch."""
+    pooled = [conv(3, 32, 16, 3), conv(32, 128, 16, 3, 2), conv(128, 128, 8, 3)] + tail(128, 8, 7)
+    wide = [conv(3, 32, 16, 3), conv(32, 128, 16, 3, 2), conv(128, 192, 8, 3)] + tail(192, 8, 7)
+    rect = [conv(3, 32, (8, 16), 3), conv(32, 128, (8, 16), 3, 2), conv(128, 128, (4, 8), 3)] + tail(128, (4, 8), 7)
+    run_and_compare(fleet("long K, pooled", [pooled, wide], 21, dtype, seed=210), "long K, few tiles, pooled, %s" % dtype)
+    run_and_compare(fleet("long K, pooled, 4x8", [rect, rect], 9, dtype, seed=212), "long K, few tiles, pooled 4x8 images, %s" % dtype)
+    block = [conv(3, 32, 16, 3), conv(32, 128, 16, 3, 2), conv(128, 128, 8, 3), conv(128, 128, 8, 3, act=wl.ACT_NONE), add(128, 8, src2=2),
+             conv(128, 256, 8, 3, 2), conv(256, 256, 4, 3, act=wl.ACT_NONE), conv(128, 256, 8, 1, 2, act=wl.ACT_NONE, src=5), add(256, 4, src=7, src2=8)] + tail(256, 4, 7)
+    run_and_compare(fleet("long K, residual", [block, block], 5, dtype, seed=211), "long K, few tiles, residual, %s" % dtype, deep=(dtype == "bf16"))
+
+
 def test_folded_batch_normalisation():
     nets = [[conv(3, 16, 8, 3), conv(16, 32, 8, 1, 2), conv(32, 32, 4, 3, act=wl.ACT_NONE), conv(16, 32, 8, 1, 2, act=wl.ACT_NONE, src=1),
              add(32, 4, src=3, src2=4)] + tail(32, 4, 6)] * 3
