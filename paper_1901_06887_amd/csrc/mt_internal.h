@@ -200,7 +200,7 @@ struct HeadArgs {
 
 // Launchers (defined next to their kernels).  All enqueue on `s` and return the launch status.
 hipError_t launch_batcher(const BatchArgs& a, hipStream_t s);   // three launches when a.n_rank_groups > 0
-hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
+hipError_t launch_gather(const GatherArgs& a, uint32_t slices, hipStream_t s);   // `slices` workgroups share a block of 32 rows
 hipError_t launch_gather_image(const GatherArgs& a, uint32_t slices, hipStream_t s);   // `slices` workgroups share a row
 hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
 hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);

@@ -85,7 +85,7 @@ __device__ void gather_bricks(const GatherArgs& a, const TenantDev& td, uint32_t
         typedef const __attribute__((address_space(1))) u32x4* gptr_t;
         gptr_t row = (gptr_t)src, zeros = (gptr_t)a.zeros;
         const uint32_t nch = src ? n / EPC : 0;              // chunks this lane may read
-        for (uint32_t kb0 = wave; kb0 < nKB; kb0 += 16) {
+        for (uint32_t kb0 = wave + 16 * blockIdx.y; kb0 < nKB; kb0 += 16 * gridDim.y) {
             u32x4 v[4];
 #pragma unroll
             for (uint32_t j = 0; j < 4; ++j) {
@@ -98,7 +98,7 @@ __device__ void gather_bricks(const GatherArgs& a, const TenantDev& td, uint32_t
         }
         return;
     }
-    for (uint32_t kb = wave; kb < nKB; kb += 4) {
+    for (uint32_t kb = wave + 4 * blockIdx.y; kb < nKB; kb += 4 * gridDim.y) {
         const uint32_t k = kb * KB + lh * EPC;
         u32x4 v = {0, 0, 0, 0};
         if (src && k < n) {
@@ -400,9 +400,9 @@ hipError_t launch_mfma_rate(float* out, uint32_t iters, uint32_t grid, hipStream
 }
 
 // ---- launchers ------------------------------------------------------------
-hipError_t launch_gather(const GatherArgs& a, hipStream_t s)
+hipError_t launch_gather(const GatherArgs& a, uint32_t slices, hipStream_t s)
 {
-    hipLaunchKernelGGL(gather_kernel, dim3(a.P / kBrickRows), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(gather_kernel, dim3(a.P / kBrickRows, slices), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 hipError_t launch_gather_image(const GatherArgs& a, uint32_t slices, hipStream_t s)
