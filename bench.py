@@ -261,7 +261,9 @@ def measure(name, steps, warmup, interleave, cpu_seconds, calibrate_copy_mib=0):
     # the dominant kernel: the grouped FC kernel, or the grouped conv kernel for the CNN mix
     dom_ms, dom_name = (fc_ms, "fc_kernel") if sum(fc_ms) >= sum(conv_ms) else (conv_ms, "conv_kernel")
     if dom_ms is fc_ms and sum(big_ms) > 0.5 * sum(fc_ms):
-        dom_ms, dom_name = big_ms, "fc_big_kernel"
+        walked = os.environ.get("MT_BIG_WALK", "1") != "0" and all(
+            mt.debug_big_tile_walk(L.in_features) for m in w.tenants.values() for L in m.layers if L.kind == wl.FC)
+        dom_ms, dom_name = big_ms, ("fc_big_walk_kernel" if walked else "fc_big_kernel")
         # the big-tile kernel is credited only with the rows it serves (a short remainder of a
         # tenant's rows goes to the streaming kernel)
         flops, bytes_ = gemm_launch_costs(w, es, lambda rows, L: mt.debug_big_tile_rows(rows, L.out_features) if L.kind == wl.FC else 0)

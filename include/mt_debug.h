@@ -49,6 +49,14 @@ mt_status mt_debug_copy(void* dst, const void* src, uint64_t bytes, void* stream
  * kernel that performed them. */
 uint32_t mt_debug_big_tile_rows(uint32_t rows, uint32_t out_features);
 
+/* Measurement aid: which of the two compute-bound FC kernels serves a layer index whose shortest
+ * fan-in among the registered models is `in_features`: 1 if one workgroup per compute unit walks
+ * the 256x256 tiles (mt::fc_big_walk_kernel), 0 if every tile gets a workgroup of its own
+ * (mt::fc_big_kernel; also what MT_BIG_WALK=0 in the environment of mt_create selects).  Pure
+ * function of its argument; needs no context and no device.  Lets a benchmark name the kernel
+ * whose launches it timed. */
+uint32_t mt_debug_big_tile_walk(uint32_t in_features);
+
 /* Measurement aid: what a loop of nothing but bf16 matrix instructions sustains on the current
  * device.  Runs, on `stream`, a kernel in which every wavefront issues v_mfma_f32_32x32x16_bf16
  * on pseudo-random operands (eight independent accumulators, two wavefronts per SIMD, no memory

@@ -117,6 +117,8 @@ def load_library() -> ctypes.CDLL:
     L.mt_debug_copy.argtypes = [vp, vp, ctypes.c_uint64, vp]
     L.mt_debug_big_tile_rows.argtypes = [u32, u32]
     L.mt_debug_big_tile_rows.restype = u32
+    L.mt_debug_big_tile_walk.argtypes = [u32]
+    L.mt_debug_big_tile_walk.restype = u32
     L.mt_set_profiling.argtypes = [vp, ctypes.c_int]
     L.mt_get_profile.argtypes = [vp, ctypes.POINTER(mt_profile)]
     L.mt_last_error.argtypes = [vp]
@@ -313,6 +315,11 @@ def debug_copy(dst: int, src: int, nbytes: int, stream: int = 0) -> None:
 def debug_big_tile_rows(rows: int, out_features: int) -> int:
     """Rows of a tenant's FC layer that the compute-bound kernel serves when a run uses it (0: none)."""
     return int(load_library().mt_debug_big_tile_rows(rows, out_features))
+
+
+def debug_big_tile_walk(in_features: int) -> bool:
+    """Whether the big tiles of a layer index with this shortest fan-in are walked by one workgroup per compute unit."""
+    return bool(load_library().mt_debug_big_tile_walk(in_features))
 
 
 def version() -> str:

@@ -121,6 +121,9 @@ struct mt_ctx {
     uint32_t no_fused_head = 0;    // tuning/testing: always run the separate head kernel
     uint32_t no_fused_pool = 0;    // tuning/testing: always run the separate pooling kernel
     uint32_t no_fused_add = 0;     // tuning/testing: residual additions always run as launches of their own
+    uint32_t big_walk = 1;         // big FC tiles: one workgroup per CU walks several tiles (tuning/testing: MT_BIG_WALK=0 gives every tile a workgroup of its own)
+    uint32_t n_cus = 256;          // compute units of the device, rounded down to a multiple of 8
+    uint32_t min_fc_k[MT_MAX_LAYERS]{};        // shortest padded fan-in among the registered FC layers of a layer index
     uint32_t no_conv_loaders = 0;  // tuning/testing: convolution tiles never get waves of their own for the loads
     uint32_t min_conv_k[MT_MAX_LAYERS]{};      // shortest reduction among the registered convolutions of a layer index
     uint32_t big_min_tiles = kBigMinTiles;   // testing: MT_BIG_MIN_TILES=1 sends every qualifying tenant-layer to big tiles
@@ -400,7 +403,7 @@ void recompute_bounds(mt_ctx* c)
     for (uint32_t& m : c->list_mask) m = 0;
     c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        c->has_gap[l] = 0; c->has_image_ops[l] = 0; c->image_op_fill[l] = 0; c->min_conv_k[l] = 0xffffffffu; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
+        c->has_gap[l] = 0; c->has_image_ops[l] = 0; c->image_op_fill[l] = 0; c->min_conv_k[l] = 0xffffffffu; c->min_fc_k[l] = 0xffffffffu; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
         c->max_fc_per64[l] = 0; c->max_fc_per64_sk[l] = 0; c->sum_nt_sk[l] = 0;
     }
@@ -430,6 +433,7 @@ void recompute_bounds(mt_ctx* c)
             c->max_nt[k][l] = std::max(c->max_nt[k][l], nt);
             c->sum_nt[k][l] += nt;
             if (k == 0) {
+                c->min_fc_k[l] = std::min(c->min_fc_k[l], L.K);
                 c->max_fc_per64[l] = std::max(c->max_fc_per64[l], nt * (kTileRows / fc_tile_rows(L.N_pad, c->fc_split_k)));
                 const uint32_t nt_sk = fc_groups(L.N_pad, 1);
                 c->sum_nt_sk[l] += nt_sk;
@@ -807,6 +811,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     if (const char* e = getenv("MT_NO_FUSED_POOL")) c->no_fused_pool = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_CONV_IMG")) c->no_conv_img = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_FUSED_ADD")) c->no_fused_add = atoi(e) != 0;
+    if (const char* e = getenv("MT_BIG_WALK")) c->big_walk = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_CONV_LOADERS")) c->no_conv_loaders = atoi(e) != 0;
     if (const char* e = getenv("MT_BIG_MIN_TILES")) c->big_min_tiles = (uint32_t)std::max(1, atoi(e));
     c->cache = cfg->cache != 0;
@@ -819,6 +824,11 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     auto bail = [&](mt_status st) { mt_destroy(c); *out = nullptr; return st; };
 #define CREATE_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) { fprintf(stderr, "mt_create: %s: %s\n", #expr, hipGetErrorString(e_)); return bail(e_ == hipErrorOutOfMemory ? MT_ENOMEM : MT_EDEVICE); } } while (0)
     CREATE_TRY(hipSetDevice(cfg->device));
+    {
+        int cus = 0;
+        CREATE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device));
+        c->n_cus = (uint32_t)std::max(cus, 8) / 8 * 8;
+    }
     const uint64_t R = cfg->max_requests, T = cfg->max_tenants;
     CREATE_TRY(hipMalloc((void**)&c->d_arena, c->cfg.arena_bytes));
     CREATE_TRY(hipMalloc((void**)&c->d_tenants, T * sizeof(TenantDev)));
@@ -1151,6 +1161,7 @@ __global__ void fill_zero_kernel(uint32_t* p, uint32_t n)
 }
 
 // Packed rows a run of R rows can occupy: every tenant with traffic pads its segment to a multiple of 32.
+constexpr uint32_t kBigWalkMinK = 256;     // the walking big-tile kernel needs seven stages of 32 (bf16) or 16 (fp32) per tile
 constexpr uint32_t kConvLongK = 1024;      // reductions from here on are worth loader waves when a launch has at most one tile per CU
 
 // Workgroups that share one packed row in the per-row kernels: `per_wg` units of work each, at most 64.
@@ -1372,7 +1383,7 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
             else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], c->conv_quad[l],
                                                                     (c->conv_img_lds[l] > 1 && !c->pool_fused[l] && !c->no_conv_img) ? c->conv_img_lds[l] : 0, c->conv_img_two[l] == 1,
                                                                     !c->no_conv_loaders && c->min_conv_k[l] >= kConvLongK, g32, s));
-            else TIMED(kProfBig + l, launch_fc_big(ga, c->cfg.dtype, g32, s));
+            else TIMED(kProfBig + l, launch_fc_big(ga, c->cfg.dtype, g32, (c->big_walk && c->min_fc_k[l] >= kBigWalkMinK) ? c->n_cus : 0, s));
         }
         if (c->has_gap[l]) {
             GapArgs pa{};
@@ -1734,6 +1745,11 @@ mt_status mt_debug_mfma_rate(void* stream, double* tflops)
 uint32_t mt_debug_big_tile_rows(uint32_t rows, uint32_t out_features)
 {
     return fc_is_big(rows, round_up(out_features, (uint32_t)kBrickRows)) ? big_rows(rows) : 0;
+}
+
+uint32_t mt_debug_big_tile_walk(uint32_t in_features)
+{
+    return round_up(in_features, (uint32_t)kWidthAlign) >= kBigWalkMinK ? 1 : 0;
 }
 
 mt_status mt_debug_poison(mt_ctx* c)

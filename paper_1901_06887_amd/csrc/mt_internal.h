@@ -169,6 +169,7 @@ struct GatherArgs {
 struct GemmArgs {
     const uint32_t* tile_base; uint32_t T; uint32_t layer; uint32_t fc_split_k;
     const uint32_t* big_layers;   // the batcher's decision per layer index (see BatchArgs)
+    uint32_t big_vgrid;           // big-tile launch whose workgroups walk several tiles: the grid of one tile per workgroup that they walk
     uint32_t pool;                // conv launch: the layers with pool_fill write the pooled activation instead of their own
     uint32_t img_lds;             // conv launch with LDS-resident input: bytes of dynamic LDS (the largest frame)
     // FC layer 0 can read the submitted rows itself (16-byte aligned rows whose length is a
@@ -203,7 +204,7 @@ hipError_t launch_batcher(const BatchArgs& a, hipStream_t s);   // three launche
 hipError_t launch_gather(const GatherArgs& a, uint32_t slices, hipStream_t s);   // `slices` workgroups share a block of 32 rows
 hipError_t launch_gather_image(const GatherArgs& a, uint32_t slices, hipStream_t s);   // `slices` workgroups share a row
 hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
-hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream_t s);
+hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, uint32_t walk_grid, hipStream_t s);   // walk_grid > 0: that many workgroups walk the tiles (a multiple of 8)
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s);
 hipError_t launch_mfma_rate(float* out, uint32_t iters, uint32_t grid, hipStream_t s);   // out: grid * 512 floats
 // max_cb: the widest tile of this layer index over the registered tenants, in 32-channel blocks (1..4)

@@ -387,3 +387,13 @@ def test_additions_are_planned_into_the_convolution_in_front_of_them(monkeypatch
     fused = {k: launches(v) for k, v in (("taken", taken), ("swapped", swapped), ("shared", shared), ("pooled", pooled))}
     assert fused["taken"] == plain["taken"] - 1 and fused["swapped"] == plain["swapped"] - 1
     assert fused["shared"] == plain["shared"] and fused["pooled"] == plain["pooled"]
+
+
+def test_which_rows_and_layers_the_compute_bound_kernels_take():
+    """The two pure functions that let a benchmark attribute flops and launches: a tenant-layer takes big tiles
+    from 2048 rows and 192 (padded) outputs on, a last row tile of at most 128 rows is left to the streaming kernel,
+    and the tiles are walked by one workgroup per compute unit when the fan-in, padded to 64, is at least 256."""
+    assert mt.debug_big_tile_rows(2047, 4096) == 0 and mt.debug_big_tile_rows(4096, 160) == 0
+    assert mt.debug_big_tile_rows(2048, 192) == 2048 and mt.debug_big_tile_rows(2048, 161) == 2048
+    assert mt.debug_big_tile_rows(4096 + 128, 4096) == 4096 and mt.debug_big_tile_rows(4096 + 129, 4096) == 4096 + 129
+    assert [mt.debug_big_tile_walk(k) for k in (64, 192, 193, 256, 4096)] == [False, False, True, True, True]

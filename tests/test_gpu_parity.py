@@ -104,6 +104,35 @@ def test_fp32_big_tiles(big_tiles_always):
     run_and_compare(w, "fp32-big")
 
 
+def test_big_tiles_long_reductions(big_tiles_always):
+    # K = 2048 (64 stages of the operand ring per tile, walked by one workgroup per CU): 9 row tiles with a
+    # ragged last one (5 row blocks), 9 full ones beside a streamed remainder, 16; a ragged second column
+    # tile (320 outputs), a logits epilogue (200 classes, 7 column blocks), and a short layer in between (K = 320)
+    counts = [2048 + 129, 2304 + 128, 4096 + 4]
+    base = wl.c5(n_tenants=3, n_requests=sum(counts), dims=(2048, 320, 2048, 200), seed=31)
+    ids = np.random.default_rng(31).permutation(np.repeat(np.arange(3), counts)).astype(np.int32)
+    w = wl.Workload("long-k", base.dtype, base.tenants, ids, base.inputs)
+    ctx = make_context(w)
+    gpu = gpu_run(ctx, w, poison=True)
+    got = ctx.last_counts()
+    assert [int(got[t]) for t in range(3)] == counts
+    rows = sample_rows(w, got, n_random=400)
+    worst = compare(w, tuple(a[rows] for a in gpu), oracle_rows(w, rows), rows=rows, what="long-k")
+    print("long-k: %d rows checked, worst rel fro %.2e, flip-free rows %.3f" % (len(rows), worst, compare.last_clean_frac), flush=True)
+    lg, pr, lb, nc = gpu
+    assert np.all(np.isfinite(lg)) and np.array_equal(lb, np.argmax(lg, axis=1))
+    ctx.close()
+
+
+@pytest.mark.parametrize("walk", ["1", "0"])
+def test_fp32_big_tiles_long_reductions(big_tiles_always, monkeypatch, walk):
+    # both ways of handing out big tiles: walked by one workgroup per CU, and a workgroup per tile
+    monkeypatch.setenv("MT_BIG_WALK", walk)
+    w = wl.c1(n_tenants=2, n_requests=4400, dims=(2048, 256, 10))
+    assert min(w.counts().values()) >= 2048
+    run_and_compare(w, "fp32-long-k")
+
+
 def test_fp32_cnn_and_gelu():
     w = wl.c4(n_tenants=2, n_requests=6, hw=8, chans=(3, 8, 16, 16), classes=4)
     w.dtype = "f32"
