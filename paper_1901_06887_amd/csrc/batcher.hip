@@ -390,8 +390,12 @@ __global__ __launch_bounds__(kBatchThreads) void batcher_kernel(BatchArgs a)
                 const uint32_t Mb = big ? big_rows(Mt) : 0;
                 static_assert(kTileRows == 64, "FC tiles have 64 >> (rr - 1) rows");
                 const uint32_t fc_shift = 7 - rr;                           // log2 of the FC tile's rows (rr is 1 or 2 there)
-                const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows)
-                                                         : (Mt - Mb + (1u << fc_shift) - 1) >> fc_shift) * g : 0;
+                // (the few rows that big tiles leave in a narrow layer are tiled one column block and 32 rows at a time,
+                // with K split among the waves: see big_remainder_split_k)
+                const bool rem_sk = big && big_remainder_split_k(np);
+                const uint32_t sh = rem_sk ? 5 : fc_shift, gq = rem_sk ? np / kBrickRows : g;
+                const uint32_t tiles = (g && Mt) ? (conv ? ceil_div(Mt * (rr & 0x7fffffffu), kConvTileRows) * g
+                                                         : ((Mt - Mb + (1u << sh) - 1) >> sh) * gq) : 0;
                 wave_scan(l, conv ? 0 : tiles);
                 wave_scan(kLayerGroup + l, conv ? tiles : 0);
                 wave_scan(2 * kLayerGroup + l, ceil_div(Mb, kBigTile) * ceil_div(np, kBigTile));

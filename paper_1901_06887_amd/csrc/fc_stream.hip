@@ -423,10 +423,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const uint32_t Mt = a.M[tl.tenant], seg0 = a.off[tl.tenant];
     const uint32_t local = idx - a.tile_base[tl.tenant];
     asm volatile("" :: "s"(seg0), "s"(local));                // keeps those loads here, next to the others, instead of at their first use
-    uint32_t groups, trows;
-    fc_shape(L.N_pad, a.fc_split_k, &tl.split, &groups, &trows);
-    // where big tiles serve this tenant-layer, only the rows they leave are tiled here
+    // where big tiles serve this tenant-layer, only the rows they leave are tiled here (in the shape that
+    // big_remainder_split_k says: the batcher counted the tiles by the same rule)
     const bool big = ((*a.big_layers >> a.layer) & 1) && fc_is_big(Mt, L.N_pad);
+    uint32_t groups, trows;
+    fc_shape(L.N_pad, a.fc_split_k || (big && big_remainder_split_k(L.N_pad)), &tl.split, &groups, &trows);
     const uint32_t first = big ? big_rows(Mt) : 0;
     const uint32_t mt_ = ceil_div(Mt - first, trows);
     tl.m0 = first + (local % mt_) * trows;

@@ -107,6 +107,7 @@ struct mt_ctx {
     uint32_t max_fc_per64[MT_MAX_LAYERS]{};   // streaming FC tiles per 64 rows of one tenant, maximum over the registered models
     uint64_t sum_nt_sk[MT_MAX_LAYERS]{};      // the same two figures for the K-split tile shape
     uint32_t max_fc_per64_sk[MT_MAX_LAYERS]{};
+    uint32_t max_big_blocks[MT_MAX_LAYERS]{};  // most column blocks of a registered FC layer whose rows past the big tiles take K-split tiles
     uint32_t fc_split_k = 0;   // tuning: every run uses FC tiles of one column block with K split four ways
     uint32_t no_auto_split_k = 0;   // tuning: small runs keep the ordinary tile shape
     uint32_t no_fused_gather = 0;  // tuning/testing: always stage FC inputs with the gather kernel
@@ -405,7 +406,7 @@ void recompute_bounds(mt_ctx* c)
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
         c->has_gap[l] = 0; c->has_image_ops[l] = 0; c->image_op_fill[l] = 0; c->min_conv_k[l] = 0xffffffffu; c->min_fc_k[l] = 0xffffffffu; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
-        c->max_fc_per64[l] = 0; c->max_fc_per64_sk[l] = 0; c->sum_nt_sk[l] = 0;
+        c->max_fc_per64[l] = 0; c->max_fc_per64_sk[l] = 0; c->sum_nt_sk[l] = 0; c->max_big_blocks[l] = 0;
     }
     for (const HostTenant& t : c->tenants) {
         if (!t.registered) continue;
@@ -461,15 +462,20 @@ void recompute_bounds(mt_ctx* c)
             if (k == 0 && L.N_pad >= (uint32_t)kBigMinCols && l < (uint32_t)kBigMaxLayer) {      // may be served with big tiles when it gets enough rows
                 c->list_mask[l / kLayerGroup] |= 1u << (2 * kLayerGroup + l % kLayerGroup);
                 c->max_nt[2][l] = std::max(c->max_nt[2][l], (L.N_pad + kBigTile - 1) / kBigTile);
+                if (big_remainder_split_k(L.N_pad)) c->max_big_blocks[l] = std::max(c->max_big_blocks[l], L.N_pad / kBrickRows);
             }
         }
     }
 }
 
 // Upper bound of the number of tiles of one list over any split of R rows among tenants.
-uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R, bool split_k = false)
+uint64_t tile_bound(const mt_ctx* c, int kind, uint32_t l, uint64_t R, bool split_k = false, bool big_enabled = false)
 {
     if (c->max_nt[kind][l] == 0) return 0;
+    // streaming tiles of a run with big tiles: the tenants that big tiles serve (at most R / kBigMinRows of them) leave
+    // at most kBigRemRows rows each, in narrow layers tiled 32 rows and one column block at a time
+    if (kind == 0 && big_enabled && !split_k)
+        return tile_bound(c, 0, l, R) + (R / kBigMinRows) * (kBigRemRows / kBrickRows) * c->max_big_blocks[l];
     if (kind == 2)      // big FC tiles: only tenants with >= kBigMinRows rows; sum ceil(M_t/256) <= R/256 + R/kBigMinRows
         return R < (uint64_t)kBigMinBatch ? 0 : (uint64_t)c->max_nt[2][l] * (R / kBigTile + R / kBigMinRows);
     // sum over tenants of ceil(M_t / rows_t) * groups_t <= R * max(groups_t / rows_t) + sum(groups_t)
@@ -1367,7 +1373,7 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
         // pooled activation is where the pooling layer would have written it
         if (l > 0 && c->pool_fused[l - 1]) continue;
         for (int kind = 0; kind < kListKinds; ++kind) {
-            const uint64_t grid = tile_bound(c, kind, l, R, split_k);
+            const uint64_t grid = tile_bound(c, kind, l, R, split_k, big_enabled);
             if (grid == 0 || (kind == 2 && (!big_enabled || grid < c->big_min_tiles))) continue;   // no big tiles possible: the batcher made none
             GemmArgs ga{};
             ga.tile_base = c->d_tile_base + ((size_t)kind * MT_MAX_LAYERS + l) * (T + 1);

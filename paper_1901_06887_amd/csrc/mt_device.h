@@ -246,7 +246,7 @@ struct TileOwner {
         }
     }
     // wave-uniform result; every thread of the workgroup must call it
-    __device__ __forceinline__ uint32_t owner(uint32_t T, uint32_t idx, uint32_t* part)
+    __device__ __forceinline__ uint32_t owner(uint32_t T, uint32_t idx, uint32_t* part) const
     {
         uint32_t cnt = 0;
 #pragma unroll

@@ -43,6 +43,14 @@ inline __host__ __device__ uint32_t big_rows(uint32_t rows)
     const uint32_t rem = rows % kBigTile;
     return rem && rem <= (uint32_t)kBigRemRows ? rows - rem : rows;
 }
+// The rows that big tiles leave to the streaming kernel (at most kBigRemRows per tenant) meet the whole of the
+// layer's weights.  Where the layer has many column groups those tiles fill the chip and are bound by the weight
+// stream, which ordinary 64-row tiles read the fewest times.  A narrow layer (the 1000 classes of the last one:
+// 8 column groups, a few dozen tiles) leaves most of the chip idle while each tile walks all of K: there the rows
+// are tiled 32 at a time and one column block wide with K split among the waves, as in runs of few tiles
+// (c5's last layer: 35 -> 19 us; the hidden layers would go from 39 to 44 us, their weights read once more).
+constexpr int kBigRemSplitMaxCols = 1024;
+inline __host__ __device__ bool big_remainder_split_k(uint32_t n_pad) { return n_pad <= (uint32_t)kBigRemSplitMaxCols; }
 constexpr int kRankRows = 1024;     // rows per workgroup of the ranking kernel
 constexpr int kRankMinRows = 8192;  // smaller batches are ranked by the batcher's single workgroup (one launch less)
 constexpr int kRankMaxTenants = 512;
