@@ -281,7 +281,7 @@ __global__ __launch_bounds__(WV * 64) void fc_big_kernel(GemmArgs a)
 // three stages of the next tile, and the barrier that opens the next tile is passed before the epilogue of
 // this one, so the epilogue's stores and the next tile's loads are both in flight while the other proceeds.
 // What a tile needs besides its operands comes through global->LDS loads too (the next tile's facts at the
-// head of a tile, its bias values at the end): the kernel issues no load into registers after its first
+// head of a tile, its bias values, from which its sums start, before the last three stages): the kernel issues no load into registers after its first
 // tile, and "how many of my loads are outstanding" keeps meaning what the ring needs it to mean.  The
 // epilogue's stores count as well, which only makes the waits stricter by the stores of the tile before.
 // Tiles need at least seven stages (the host checks K): the facts are read after the barrier of stage 3.
@@ -299,9 +299,9 @@ __global__ __launch_bounds__(512) void fc_big_walk_kernel(GemmArgs a)
     constexpr uint32_t WV = 8, WN = 4, CJ = 2, BPW = 2, LPS = 4;
     static_assert(kBigKS == 2 && kBigNS == 4 && kBigBlocks == 8, "written for the 256x256 tile, two k steps per stage, four stages");
     // The ring, and behind it, in the same array (the compiler's wait counts stay exact only while all global->LDS
-    // loads of a kernel go to one object): per wave twice 1 KiB for the bias values of the current and of the next
-    // tile and 256 bytes for the next tile's facts, which every wave fetches for itself; then the copy of the tile list.
-    constexpr uint32_t kRing = kBigNS * kBigStageBytes, kBiasBytes = 2 * WV * kBigTile * 4, kFactBytes = WV * 256;
+    // loads of a kernel go to one object): per wave 1 KiB for the bias values of the next tile and 256 bytes for
+    // its facts, which every wave fetches for itself; then the copy of the tile list.
+    constexpr uint32_t kRing = kBigNS * kBigStageBytes, kBiasBytes = WV * kBigTile * 4, kFactBytes = WV * 256;
     constexpr uint32_t kFactWords = sizeof(LayerDev) / 4;    // lanes 0..: the layer's row; then the tenant's row count and first row
     static_assert(sizeof(LayerDev) % 4 == 0 && kFactWords + 2 <= 64, "one dword per lane");
     __shared__ __attribute__((aligned(16))) uint8_t stages[kRing + kBiasBytes + kFactBytes + (kMaxTenantsPadded + 1) * 4];
@@ -378,14 +378,14 @@ __global__ __launch_bounds__(512) void fc_big_walk_kernel(GemmArgs a)
         asm volatile("" ::: "memory");
     };
 
-    // a tile's 256 bias values into half `pb` of this wave's bias area, 16 bytes per lane (the last lanes of a narrow
+    // a tile's 256 bias values into this wave's bias area, 16 bytes per lane (the last lanes of a narrow
     // last tile repeat its last four)
-    auto issue_bias = [&](const BigTile& q, uint32_t pb) {
+    auto issue_bias = [&](const BigTile& q) {
         uint32_t off = min(q.n0 + 4 * lane, q.N_pad - 4) * 4;
         uint64_t base = (uint64_t)(a.arena + q.b_off);
         asm("" : "+v"(off));
         asm("" : "+s"(base));
-        __builtin_amdgcn_global_load_lds((gvoid_t)((const uint8_t*)base + off), (lvoid_t)(bias_l + (pb * WV + wave) * kBigTile), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gvoid_t)((const uint8_t*)base + off), (lvoid_t)(bias_l + wave * kBigTile), 16, 0, 0);
     };
     // the facts of the tile with block index vt, one dword per lane, into this wave's fact area
     auto issue_facts = [&](uint32_t vt) {
@@ -412,17 +412,17 @@ __global__ __launch_bounds__(512) void fc_big_walk_kernel(GemmArgs a)
         cur = make_tile(v, t, a.M[t], a.off[t], a.layers[t * MT_MAX_LAYERS + a.layer]);
     }
     uint32_t g0 = 0;                                         // ring stage of the current tile's stage 0: the ring runs on from tile to tile
-    uint32_t pb = 0;                                         // half of the bias area that holds the current tile's values
     {
         const uint8_t* f0 = feed(cur, 0); const uint8_t* f1 = feed(cur, 1);
+        issue_bias(cur);                                     // first, so that it has landed when stage 0 has
 #pragma unroll
         for (uint32_t s = 0; s < kBigNS; ++s) {              // the first tile's first four stages (tiles have more)
-            if (s == kBigNS - 1) { issue_bias(cur, 0); ring_barrier(false); }     // stage 0 is complete for every wave
+            if (s == kBigNS - 1) ring_barrier(false);        // the bias values and stage 0 are complete for every wave
 #pragma unroll
             for (uint32_t q = 0; q < LPS; ++q) load_brick((q / kBigKS ? f1 : f0) + (size_t)(s * kBigKS + q % kBigKS) * kBrickBytes, s, q / kBigKS, q % kBigKS);
         }
     }
-    // Per tile, from here: its stage 0 is complete for every wave, its stages 1..3 and its bias values are on their way.
+    // Per tile, from here: its bias values and its stage 0 are complete for every wave, its stages 1..3 are on their way.
     for (;;) {
         const uint32_t vn = next_valid(v + gridDim.x);
         const bool has_next = vn < a.big_vgrid;
@@ -441,13 +441,22 @@ __global__ __launch_bounds__(512) void fc_big_walk_kernel(GemmArgs a)
             const uint8_t* src = own ? cf[i] + (size_t)sa * (kBigKS * kBrickBytes) : nf[i] + (size_t)(sa - n) * nstep;
             load_brick(src + kk * kBrickBytes, g0 + sa, i, kk);
         };
+        // The sums start from the bias: a lane's sixteen values of a block are four runs of four output columns (see
+        // the epilogue of fc_big_kernel), the same columns in each of the wave's four row blocks.
         f32x16 acc[4][CJ];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
+        {
+            const float* bias_w = bias_l + wave * kBigTile;
 #pragma unroll
             for (int j = 0; j < (int)CJ; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 bq = *(const f32x4*)(bias_w + (wn * CJ + j) * kBrickRows + 4 * lh + 8 * g);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] = bq[e];
+                }
+        }
         auto read_a = [&](const uint8_t* buf, uint32_t kk, u32x4 (&a4)[4], int i0, int i1) {
             const uint8_t* ab = buf + (wm * 4 * kBigKS) * kBrickBytes + lane * 16;
 #pragma unroll
@@ -520,6 +529,8 @@ __global__ __launch_bounds__(512) void fc_big_walk_kernel(GemmArgs a)
 #pragma unroll
             for (uint32_t i = 0; i < BPW; ++i) nf[i] = feed(nxt, i);
             nstep = kBigKS * kBrickBytes;
+            issue_bias(nxt);                                 // this tile took its own at its head; older than the twelve loads that follow, so it
+                                                             // has landed when the barrier that opens the next tile is passed
         }
         if (rows) {
             for (uint32_t s = n - (kBigNS - 1); s < n; ++s) step(s, false);
@@ -531,15 +542,12 @@ __global__ __launch_bounds__(512) void fc_big_walk_kernel(GemmArgs a)
         // next tile's stage 0 has landed, its stage 3 can go into the slot of the stage just read.  The epilogue's
         // stores then drain under the next tile's K loop instead of in front of a barrier.
         if (has_next) {
-            issue_bias(nxt, pb ^ 1);
             ring_barrier(true);
 #pragma unroll
             for (uint32_t q = 0; q < LPS; ++q) load_brick(feed(nxt, q / kBigKS) + (size_t)((kBigNS - 1) * kBigKS + q % kBigKS) * kBrickBytes, g0 + n + kBigNS - 1, q / kBigKS, q % kBigKS);
         }
 
-        // epilogue (see fc_big_kernel): no LDS besides the bias values, which landed long ago (they are older than
-        // the loads that the barriers of the K loop have waited for)
-        const float* bias_w = bias_l + (pb * WV + wave) * kBigTile;
+        // epilogue (see fc_big_kernel; the bias is in the sums already): no LDS
         const uint32_t nKB_out = cur.out_fill / KB;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -551,11 +559,9 @@ __global__ __launch_bounds__(512) void fc_big_walk_kernel(GemmArgs a)
                     const uint32_t mb = cur.m0 + rb * kBrickRows;
                     f32x4 y[4];
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const f32x4 bq = *(const f32x4*)(bias_w + cb * kBrickRows + 4 * lh + 8 * g);
+                    for (int g = 0; g < 4; ++g)
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) y[g][e] = acc[i][j][4 * g + e] + bq[e];
-                    }
+                        for (int e = 0; e < 4; ++e) y[g][e] = acc[i][j][4 * g + e];
                     if (cur.is_last) {
                         if (mb + li < cur.Mt) {
                             float* row = a.logits + (size_t)(cur.seg0 + mb + li) * a.C_pad;
@@ -592,7 +598,7 @@ __global__ __launch_bounds__(512) void fc_big_walk_kernel(GemmArgs a)
                 __builtin_amdgcn_sched_barrier(0);
             }
         if (!has_next) break;
-        g0 += n; cur = nxt; v = vn; pb ^= 1;
+        g0 += n; cur = nxt; v = vn;
     }
     __builtin_amdgcn_s_waitcnt(0);                           // the repeats behind the last tile have landed before the workgroup gives its LDS back
 }

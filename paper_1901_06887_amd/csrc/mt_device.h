@@ -107,6 +107,15 @@ __device__ __forceinline__ void fc_shape(uint32_t n_pad, uint32_t split_k, uint3
 // sqrt(log2 e) so that exp(-z^2) is one multiply and one exp2; the 1/2 sits in the polynomial's
 // coefficients.  The error is far below half a bfloat16 ulp of the result, and a library erf
 // costs four times as much, which showed in the epilogue of the compute-bound tiles.
+// max(x, 0) in one instruction: the compiler's own maximum first quiets a possible signalling NaN with a second
+// v_max (it cannot know that MFMA results hold none), one issue slot in fifteen of the GELU below.
+__device__ __forceinline__ float max0(float x)
+{
+    float r;
+    asm("v_max_f32 %0, 0, %1" : "=v"(r) : "v"(x));
+    return r;
+}
+
 __device__ __forceinline__ float gelu(float x)
 {
     constexpr float kScale = 0.84932180028801904f;           // sqrt(log2(e) / 2): zs = z * sqrt(log2 e)
@@ -116,12 +125,12 @@ __device__ __forceinline__ float gelu(float x)
     const float t = __builtin_amdgcn_rcpf(fmaf(kP, zs, 1.0f));   // one instruction, within 1 ulp: far inside the formula's own 1.5e-7
     const float poly = t * (0.127414796f + t * (-0.142248368f + t * (0.7107068705f + t * (-0.7265760135f + t * 0.5307027145f))));
     const float h = poly * __builtin_amdgcn_exp2f(-zs * zs);
-    return fmaf(-ax, h, fmaxf(x, 0.0f));
+    return fmaf(-ax, h, max0(x));
 }
 
 __device__ __forceinline__ float activate(float z, uint32_t act)
 {
-    if (act == MT_ACT_RELU) return fmaxf(z, 0.0f);
+    if (act == MT_ACT_RELU) return max0(z);
     if (act == MT_ACT_GELU) return gelu(z);
     return z;
 }
@@ -139,7 +148,7 @@ __device__ __forceinline__ void activate_block(f32x4 (&y)[G], uint32_t act)
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) y[g][e] = fmaxf(y[g][e], 0.0f);
+            for (int e = 0; e < 4; ++e) y[g][e] = max0(y[g][e]);
     }
 }
 
