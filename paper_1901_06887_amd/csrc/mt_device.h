@@ -8,8 +8,9 @@
 //                   bricks go from memory into MFMA operands through a register ring, activation
 //                   bricks are shared through LDS; fused bias + activation (+ rounding), brick
 //                   output, fp32 logits, or softmax/argmax for at most 32 classes
-//   fc_big.hip      fc_big_kernel: the same layer index, compute-bound tenant-layers: 256x256
-//                   tiles, both operands through an LDS ring filled by direct global->LDS loads
+//   fc_big.hip      fc_big_walk_kernel / fc_big_kernel: the same layer index, compute-bound tenant-layers:
+//                   256x256 tiles, both operands through an LDS ring filled by direct global->LDS loads;
+//                   one workgroup per compute unit walks the tiles (or, for short K, one workgroup per tile)
 //   conv.hip        conv_kernel (layers at most 32 channels wide: every wave gathers its own
 //                   pixels) and conv_lds_kernel (wider layers: activation bricks gathered once
 //                   per tile into LDS and shared by waves side by side over channels; pools on

@@ -10,7 +10,7 @@
       plain copy kernel moving N bytes in the same run.  Prints `key: value` lines; bench.py
       reads `traffic_bytes_per_launch` and `kernel_source_sha256` back.
 
-  python profile_summary.py counters <..._counter_collection.csv> --kernel fc_big_kernel
+  python profile_summary.py counters <..._counter_collection.csv> --kernel fc_big_walk_kernel
       mean of every collected counter per dispatch of one kernel
 
   python profile_summary.py split <..._kernel_trace.csv> --kernel fc_kernel

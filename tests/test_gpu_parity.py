@@ -84,6 +84,20 @@ def test_big_tenants_leave_a_short_remainder_to_the_streaming_kernel(big_tiles_a
     run_and_compare(w, "big+remainder")
 
 
+def test_big_tiles_of_tenants_with_different_layer_shapes(big_tiles_always):
+    # four tenants, each with >= 2048 rows, whose layers at the same index differ in fan-in, width and activation:
+    # the workgroups that walk the big tiles pass from a tile of one reduction length to a tile of another (10, 14,
+    # 16, 20 stages of the operand ring), from GELU to ReLU, from a full column tile to a ragged one; the third
+    # tenant's second layer (K = 192) keeps the whole layer index on the one-tile-per-workgroup kernel
+    dims = [(320, 512, 384, 100), (320, 448, 640, 50), (320, 320, 192, 40), (320, 640, 256, 200)]
+    acts = [wl.ACT_GELU, wl.ACT_RELU, wl.ACT_GELU, wl.ACT_RELU]
+    tenants = {t: wl.make_model(wl.mlp_layers(list(d), a), "bf16", 33, t) for t, (d, a) in enumerate(zip(dims, acts))}
+    counts = [2048 + 300, 2304, 2048 + 64, 2560 + 129]
+    ids = np.random.default_rng(33).permutation(np.repeat(np.arange(4), counts)).astype(np.int32)
+    x = wl.round_to_bf16(np.random.default_rng(34).standard_normal((sum(counts), 320)).astype(np.float32))
+    run_and_compare(wl.Workload("big-mixed-shapes", "bf16", tenants, ids, x), "big-mixed-shapes")
+
+
 def test_big_and_streaming_tenants_in_one_run(big_tiles_always):
     w = wl.c2(n_tenants=5, n_requests=8300, dims=(128, 320, 256, 40), s=2.2)    # one tenant dominates
     c = w.counts()
