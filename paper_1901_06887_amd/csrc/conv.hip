@@ -54,6 +54,43 @@ struct TapWalk {
     }
 };
 
+// The same walk for a whole wave at once, where a step never straddles two taps (cin a multiple of the step): the
+// position (tap, offset from the window's top-left tap) is then the same for every lane and lives in scalar
+// registers; what differs between lanes is where their window starts and which taps fall outside the image, a
+// 64-bit mask per lane (windows up to 7 x 7; steps past the last tap meet no bit).  A lane's load offset is one
+// addition and one select: lanes outside the image ask for an offset outside the buffer and get zeros
+// (lds_dma16_buffer).  TapWalk::next costs some twenty vector instructions per gathered brick, ten times the MFMAs
+// the brick feeds; counters showed the vector unit busy half the time of a convolution launch.
+struct UniformTapWalk {
+    uint32_t tp, kw, ch, off;                    // tap index kh * k + kw; channel inside the tap; element offset from the top-left tap
+    uint32_t cin, k, row_jump, step;
+    __device__ __forceinline__ void init(const LayerDev& L, uint32_t step_el)
+    {
+        tp = 0; kw = 0; ch = 0; off = 0;
+        cin = L.cin; k = L.ksize; row_jump = (L.in_w - L.ksize) * L.cin; step = step_el;
+    }
+    __device__ __forceinline__ void advance()
+    {
+        ch += step; off += step;
+        if (ch == cin) {
+            ch = 0; ++tp; ++kw;
+            if (kw == k) { kw = 0; off += row_jump; }
+        }
+    }
+};
+// taps of a k x k window at (ih0, iw0) that lie inside the image, bit kh * k + kw
+__device__ __forceinline__ uint64_t taps_inside(const LayerDev& L, int32_t ih0, int32_t iw0, bool row_ok)
+{
+    const int32_t k = (int32_t)L.ksize;
+    const int32_t w_lo = max(0, -iw0), w_hi = max(0, min(k, (int32_t)L.in_w - iw0));
+    const int32_t h_lo = max(0, -ih0), h_hi = row_ok ? max(0, min(k, (int32_t)L.in_h - ih0)) : 0;
+    const uint64_t cols = w_hi > w_lo ? ((1ull << w_hi) - 1) & ~((1ull << w_lo) - 1) : 0;
+    uint64_t m = 0;
+    for (int32_t kh = 0; kh < k; ++kh)
+        if (kh >= h_lo && kh < h_hi) m |= cols << (uint32_t)(kh * k);
+    return m;
+}
+
 // ---- NHWC store of one 32-pixel x 32-channel unit held in the transposed accumulator layout ----
 // After an MFMA with the filter brick as row operand, lane (li, lh) holds channels 8g + 4 lh +
 // {0..3} of pixel li: stored from there, a wave instruction writes 64 separate 8- or 16-byte
@@ -266,7 +303,9 @@ constexpr uint32_t kConvDeepKC = 4, kConvDeepNS = 4;   // chunks and ring of a w
 // block w, the bricks of filter block w) and do nothing else, waves 0..3 read and multiply.  For launches of few
 // tiles with a long K (deep layers of small batches): their workgroups sit alone on their CUs, one wave per SIMD,
 // and a wave that issues its own loads stands at every one of them for ~100 clocks with no MFMA in the pipe.
-template <typename T, int NCB, bool QUAD, int PW>
+// FAST: the gather's walk through the window is shared by the wave (UniformTapWalk): every tenant's cin is a
+// multiple of the elements a lane group takes per step, and a tenant's activations are less than 2 GiB.
+template <typename T, int NCB, bool QUAD, int PW, bool FAST>
 __global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(PW ? 2 : NCB == 2 ? 4 : 3, NCB == 2 && !PW ? 4 : 3))) void conv_lds_kernel(GemmArgs a)     // PW = 0: as many workgroups per CU as the LDS ring allows: three (48 KiB), four with two filter blocks (36 KiB)
 {
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
@@ -305,6 +344,13 @@ __global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(
     gptr_t zeros = (gptr_t)a.zeros;
     gptr_t img[NPX];
     TapWalk<T> walk[NPX];
+    // FAST: the tenant's activations as one buffer; per lane the byte offset of its first element at the window's
+    // top-left tap (negative where that tap lies in front of the buffer: such taps are never asked for) and its taps
+    UniformTapWalk uwalk[NPX];
+    u32x4 in_desc{};
+    int32_t lane_off[NPX];
+    uint32_t taps_lo[NPX], taps_hi[NPX];
+    if constexpr (FAST) in_desc = buffer_descriptor((const T*)act_of(a.act, L.in_buf) + (size_t)seg0 * a.S, a.M[t] * a.S * (uint32_t)sizeof(T));
 #pragma unroll
     for (uint32_t i = 0; i < NPX; ++i) {
         const uint32_t gm = m0 + wave * kBrickRows + (QUAD ? (lane >> 2) + 16 * i : (lane >> 1));
@@ -313,18 +359,36 @@ __global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(
         uint32_t req, pix, oh, ow;
         divmod_uniform(mm, rpr, &req, &pix);
         divmod_uniform(pix, L.out_w, &oh, &ow);
-        img[i] = (gptr_t)((const T*)act_of(a.act, L.in_buf) + (size_t)(seg0 + req) * a.S);
-        walk[i].init(L, (int32_t)(oh * L.stride) - (int32_t)L.pad, (int32_t)(ow * L.stride) - (int32_t)L.pad, row_ok,
-                     QUAD ? (lane & 3) * EPC : (lane & 1) * EPC, QUAD ? 2 * KB : KB);
+        const int32_t ih0 = (int32_t)(oh * L.stride) - (int32_t)L.pad, iw0 = (int32_t)(ow * L.stride) - (int32_t)L.pad;
+        const uint32_t first = QUAD ? (lane & 3) * EPC : (lane & 1) * EPC;
+        if constexpr (FAST) {
+            uwalk[i].init(L, QUAD ? 2 * KB : KB);
+            lane_off[i] = (int32_t)(req * a.S * (uint32_t)sizeof(T)) + ((ih0 * (int32_t)L.in_w + iw0) * (int32_t)L.cin + (int32_t)first) * (int32_t)sizeof(T);
+            const uint64_t m = taps_inside(L, ih0, iw0, row_ok);
+            taps_lo[i] = (uint32_t)m; taps_hi[i] = (uint32_t)(m >> 32);
+        } else {
+            img[i] = (gptr_t)((const T*)act_of(a.act, L.in_buf) + (size_t)(seg0 + req) * a.S);
+            walk[i].init(L, ih0, iw0, row_ok, first, QUAD ? 2 * KB : KB);
+        }
     }
     gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
     const uint32_t last_kb = n_chunks * KC - 1;
     // one k step of a chunk: the gather of this wave's pixel block, the brick of its filter block
     // (pairs: k step kk of all 32 pixels; QUAD: both k steps of pixels 16 kk .. 16 kk + 15)
     auto fetch_gather = [&](uint32_t c, uint32_t kk) {
-        const int32_t chunk = walk[QUAD ? kk : 0].next();
-        gptr_t p = chunk >= 0 ? img[QUAD ? kk : 0] + chunk : zeros;
-        lds_dma16(p, lds + (c % NS) * kStageBytes + (wave * KC + kk) * kBrickBytes);
+        uint8_t* dst = lds + (c % NS) * kStageBytes + (wave * KC + kk) * kBrickBytes;
+        if constexpr (FAST) {
+            UniformTapWalk& u = uwalk[QUAD ? kk : 0];
+            const uint32_t tp = u.tp, word = tp < 32 ? taps_lo[QUAD ? kk : 0] : taps_hi[QUAD ? kk : 0];
+            const bool inside = (int32_t)(word << (31 - (tp & 31))) < 0;
+            const uint32_t voff = inside ? (uint32_t)(lane_off[QUAD ? kk : 0] + (int32_t)(u.off * (uint32_t)sizeof(T))) : 0x80000000u;
+            u.advance();
+            lds_dma16_buffer(in_desc, voff, dst);
+        } else {
+            const int32_t chunk = walk[QUAD ? kk : 0].next();
+            gptr_t p = chunk >= 0 ? img[QUAD ? kk : 0] + chunk : zeros;
+            lds_dma16(p, dst);
+        }
     };
     auto fetch_filter = [&](uint32_t c, uint32_t kk) {
         if (wr == 0) lds_dma16(wp + (size_t)min(c * KC + kk, last_kb) * 64, lds + (c % NS) * kStageBytes + ((4 + wc) * KC + kk) * kBrickBytes);   // a filter block is fetched once, by the first wave row
@@ -720,14 +784,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
 }
 
 // ---- launcher ------------------------------------------------------------
+template <typename T, bool FAST>
+static void launch_conv_lds_t(const GemmArgs& a, uint32_t max_cb, bool quad, bool loaders, uint32_t grid, hipStream_t s)
+{
+    if (max_cb == 2 && quad) hipLaunchKernelGGL((conv_lds_kernel<T, 2, true, 0, FAST>), dim3(grid), dim3(256), 0, s, a);
+    else if (max_cb == 2) hipLaunchKernelGGL((conv_lds_kernel<T, 2, false, 0, FAST>), dim3(grid), dim3(256), 0, s, a);
+    else if (loaders) hipLaunchKernelGGL((conv_lds_kernel<T, 4, false, 1, FAST>), dim3(grid), dim3(512), 0, s, a);
+    else hipLaunchKernelGGL((conv_lds_kernel<T, 4, false, 0, FAST>), dim3(grid), dim3(256), 0, s, a);
+}
+
 template <typename T>
-static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, bool loaders, uint32_t grid, hipStream_t s)
+static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, bool loaders, bool fast, uint32_t grid, hipStream_t s)
 {
     if (max_cb <= 1) hipLaunchKernelGGL((conv_kernel<T, 1>), dim3(grid), dim3(256), 0, s, a);
-    else if (max_cb == 2 && quad) hipLaunchKernelGGL((conv_lds_kernel<T, 2, true, 0>), dim3(grid), dim3(256), 0, s, a);
-    else if (max_cb == 2) hipLaunchKernelGGL((conv_lds_kernel<T, 2, false, 0>), dim3(grid), dim3(256), 0, s, a);
-    else if (loaders) hipLaunchKernelGGL((conv_lds_kernel<T, 4, false, 1>), dim3(grid), dim3(512), 0, s, a);
-    else hipLaunchKernelGGL((conv_lds_kernel<T, 4, false, 0>), dim3(grid), dim3(256), 0, s, a);
+    else if (fast) launch_conv_lds_t<T, true>(a, max_cb, quad, loaders, grid, s);
+    else launch_conv_lds_t<T, false>(a, max_cb, quad, loaders, grid, s);
 }
 
 template <typename T>
@@ -749,7 +820,7 @@ static void launch_conv_img_t(const GemmArgs& a, uint32_t max_cb, bool two, uint
 
 // img_lds_bytes > 0: every convolution of the layer index qualifies for the LDS-resident-input kernel, whose largest frame is that
 // size; img_two: their pixels are one 16-byte chunk (else none is)
-hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, bool long_k, uint32_t grid, hipStream_t s)
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, bool long_k, bool uniform_walk, uint32_t grid, hipStream_t s)
 {
     if (grid == 0) return hipSuccess;
     grid = (grid + 7) / 8 * 8;
@@ -759,8 +830,8 @@ hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool 
         else launch_conv_img_t<float>(a, max_cb, img_two, img_lds_bytes, grid, s);
         return hipGetLastError();
     }
-    if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, quad, loaders, grid, s);
-    else launch_conv_t<float>(a, max_cb, quad, loaders, grid, s);
+    if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, quad, loaders, uniform_walk, grid, s);
+    else launch_conv_t<float>(a, max_cb, quad, loaders, uniform_walk, grid, s);
     return hipGetLastError();
 }
 

@@ -102,6 +102,7 @@ struct mt_ctx {
     uint32_t conv_img_lds[MT_MAX_LAYERS]{};          // every conv of a layer index can keep its tiles' input in LDS: the largest frame in bytes, else 0
     int conv_img_two[MT_MAX_LAYERS]{};               // ... and their pixels are one 16-byte chunk: 1, none is: 0 (-1: no convolution seen yet)
     uint32_t no_conv_img = 0;                        // tuning: never use that kernel
+    bool conv_uniform[MT_MAX_LAYERS]{};              // every conv of a layer index has input channels in multiples of a k step, and a window of at most 64 taps
     bool conv_quad[MT_MAX_LAYERS]{};                 // every conv of a layer index has input channels in multiples of four 16-byte chunks           // widest conv tile (32-channel blocks, at most 4) of a layer index
     uint64_t sum_nt[kListKinds][MT_MAX_LAYERS]{};
     uint32_t max_fc_per64[MT_MAX_LAYERS]{};   // streaming FC tiles per 64 rows of one tenant, maximum over the registered models
@@ -125,6 +126,7 @@ struct mt_ctx {
     uint32_t big_walk = 1;         // big FC tiles: one workgroup per CU walks several tiles (tuning/testing: MT_BIG_WALK=0 gives every tile a workgroup of its own)
     uint32_t n_cus = 256;          // compute units of the device, rounded down to a multiple of 8
     uint32_t min_fc_k[MT_MAX_LAYERS]{};        // shortest padded fan-in among the registered FC layers of a layer index
+    uint32_t no_conv_uniform = 0;  // tuning/testing: convolution gathers always walk the window lane by lane
     uint32_t no_conv_loaders = 0;  // tuning/testing: convolution tiles never get waves of their own for the loads
     uint32_t min_conv_k[MT_MAX_LAYERS]{};      // shortest reduction among the registered convolutions of a layer index
     uint32_t big_min_tiles = kBigMinTiles;   // testing: MT_BIG_MIN_TILES=1 sends every qualifying tenant-layer to big tiles
@@ -404,7 +406,7 @@ void recompute_bounds(mt_ctx* c)
     for (uint32_t& m : c->list_mask) m = 0;
     c->max_reg_classes = 0; c->min_reg_classes = 0xffffffffu; c->sum_macs = 0.0;
     for (uint32_t l = 0; l < MT_MAX_LAYERS; ++l) {
-        c->has_gap[l] = 0; c->has_image_ops[l] = 0; c->image_op_fill[l] = 0; c->min_conv_k[l] = 0xffffffffu; c->min_fc_k[l] = 0xffffffffu; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
+        c->has_gap[l] = 0; c->has_image_ops[l] = 0; c->image_op_fill[l] = 0; c->min_conv_k[l] = 0xffffffffu; c->min_fc_k[l] = 0xffffffffu; c->max_conv_cb[l] = 0; c->conv_quad[l] = true; c->conv_uniform[l] = true; c->pool_fused[l] = false; c->conv_img_lds[l] = 1; c->conv_img_two[l] = -1;
         for (int k = 0; k < kListKinds; ++k) { c->max_rpr[k][l] = c->max_nt[k][l] = 0; c->sum_nt[k][l] = 0; }
         c->max_fc_per64[l] = 0; c->max_fc_per64_sk[l] = 0; c->sum_nt_sk[l] = 0; c->max_big_blocks[l] = 0;
     }
@@ -444,6 +446,7 @@ void recompute_bounds(mt_ctx* c)
                 c->min_conv_k[l] = std::min(c->min_conv_k[l], L.k_valid);
                 c->max_conv_cb[l] = std::max(c->max_conv_cb[l], std::min<uint32_t>(L.N_pad / kBrickRows, kTileCols / kBrickRows));
                 if (L.cin % (4 * (16 / c->elem_size))) c->conv_quad[l] = false;
+                if (L.cin % (2 * (16 / c->elem_size)) || L.ksize * L.ksize > 64) c->conv_uniform[l] = false;
                 // frame of one tile of the LDS-resident-input kernel (see conv_img_kernel): whole output rows of one
                 // image, or whole images, with a one-pixel border, pixels 16 bytes apart from cin elements
                 const uint32_t rpr = L.rows_per_req, kb = 32 / c->elem_size;
@@ -819,6 +822,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
     if (const char* e = getenv("MT_NO_FUSED_ADD")) c->no_fused_add = atoi(e) != 0;
     if (const char* e = getenv("MT_BIG_WALK")) c->big_walk = atoi(e) != 0;
     if (const char* e = getenv("MT_NO_CONV_LOADERS")) c->no_conv_loaders = atoi(e) != 0;
+    if (const char* e = getenv("MT_NO_CONV_UNIFORM")) c->no_conv_uniform = atoi(e) != 0;
     if (const char* e = getenv("MT_BIG_MIN_TILES")) c->big_min_tiles = (uint32_t)std::max(1, atoi(e));
     c->cache = cfg->cache != 0;
     c->tenants.resize(cfg->max_tenants);
@@ -1388,7 +1392,8 @@ mt_status run_impl(mt_ctx* c, void* hip_stream, const mt_outputs* out, uint32_t*
             if (kind == 0) TIMED(kProfFc + l, launch_fc(ga, c->cfg.dtype, g32, s));
             else if (kind == 1) TIMED(kProfConv + l, launch_conv(ga, c->cfg.dtype, c->max_conv_cb[l], c->conv_quad[l],
                                                                     (c->conv_img_lds[l] > 1 && !c->pool_fused[l] && !c->no_conv_img) ? c->conv_img_lds[l] : 0, c->conv_img_two[l] == 1,
-                                                                    !c->no_conv_loaders && c->min_conv_k[l] >= kConvLongK, g32, s));
+                                                                    !c->no_conv_loaders && c->min_conv_k[l] >= kConvLongK,
+                                                                    c->conv_uniform[l] && !c->no_conv_uniform && (uint64_t)c->cfg.max_requests * c->S * c->elem_size < (1ull << 31), g32, s));
             else TIMED(kProfBig + l, launch_fc_big(ga, c->cfg.dtype, g32, (c->big_walk && c->min_fc_k[l] >= kBigWalkMinK) ? c->n_cus : 0, s));
         }
         if (c->has_gap[l]) {

@@ -67,6 +67,26 @@ __device__ __forceinline__ void lds_dma16(const __attribute__((address_space(1))
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(m0v), "v"(src) : "memory", "m0");
 }
 
+// The same through a buffer descriptor: lane l's 16 bytes at byte `voff` of the buffer land at lds_dst + 16 l, and a
+// lane whose offset lies outside the buffer gets zeros (the hardware's range check of untyped buffers; checked on
+// the device: the lane layout is that of the global form, offsets from num_records - 15 on deliver zeros).
+// The descriptor: base address, stride 0 (untyped), size in bytes, 32-bit data format.
+__device__ __forceinline__ u32x4 buffer_descriptor(const void* base, uint32_t bytes)
+{
+    const uint64_t b = (uint64_t)base;
+    u32x4 d;
+    d[0] = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    d[1] = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32) & 0xffffu);
+    d[2] = __builtin_amdgcn_readfirstlane(bytes);
+    d[3] = 0x00020000u;
+    return d;
+}
+__device__ __forceinline__ void lds_dma16_buffer(const u32x4& desc, uint32_t voff, void* lds_dst)
+{
+    const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds_dst);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" :: "s"(m0v), "v"(voff), "s"(desc) : "memory", "m0");
+}
+
 // Inclusive prefix sums across lanes with data-parallel-primitive moves (no LDS traffic): shifts
 // by 1, 2, 4, 8 inside each row of 16 lanes (lanes without a source add 0), then lane 15 of rows
 // 0 and 2 is added to rows 1 and 3, then lane 31 to the upper half.

@@ -217,7 +217,7 @@ hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s
 hipError_t launch_mfma_rate(float* out, uint32_t iters, uint32_t grid, hipStream_t s);   // out: grid * 512 floats
 // max_cb: the widest tile of this layer index over the registered tenants, in 32-channel blocks (1..4)
 // quad: every tenant's input channels at this layer index are a multiple of four 16-byte chunks
-hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, bool long_k, uint32_t grid, hipStream_t s);
+hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, bool long_k, bool uniform_walk, uint32_t grid, hipStream_t s);
 hipError_t launch_gap(const GapArgs& a, hipStream_t s);
 hipError_t launch_image_ops(const GapArgs& a, uint32_t slices, hipStream_t s);   // max-pool and residual add of one layer index
 hipError_t launch_head(const HeadArgs& a, hipStream_t s);
