@@ -252,7 +252,8 @@ __global__ __launch_bounds__(256) void conv_kernel(GemmArgs a)
     const LayerDev L = a.layers[t * MT_MAX_LAYERS + a.layer];
     const uint32_t seg0 = a.off[t];
     const uint32_t local = idx - a.tile_base[t];
-    const uint32_t rows_total = a.M[t] * L.rows_per_req, mt_ = ceil_div(rows_total, kConvTileRows);
+    // (a row-tiled layer's list counts more tiles than its pixels fill: those beyond the last pixel have nothing to do)
+    const uint32_t rows_total = a.M[t] * L.rows_per_req, mt_ = ceil_div(a.M[t] * conv_tile_rows(L.rows_per_req, L.row_tiles), kConvTileRows);
     const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
     const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
     // no barrier below: the waves are independent; wave w takes row blocks w, w+4, ... of the tile
@@ -329,8 +330,9 @@ __global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(
     const uint32_t seg0 = a.off[t];
     const uint32_t local = idx - a.tile_base[t];
     const uint32_t rpr = L.rows_per_req;
-    const uint32_t rows_total = a.M[t] * rpr, mt_ = ceil_div(rows_total, kConvTileRows);
+    const uint32_t rows_total = a.M[t] * rpr, mt_ = ceil_div(a.M[t] * conv_tile_rows(rpr, L.row_tiles), kConvTileRows);
     const uint32_t m0 = (local % mt_) * kConvTileRows;
+    if (m0 >= rows_total) return;                             // a row-tiled layer's list counts more tiles than its pixels fill
     const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
     const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
     const uint32_t nKB = L.K / KB, nKBv = ceil_div(L.k_valid, KB);
@@ -598,8 +600,8 @@ __global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(
 }
 
 // ---- convolution tiles whose input fits LDS ----------------------------------------------------
-// Same tile (128 output pixels x <= 128 channels) and tile list again, for layers whose tiles are
-// whole output rows of one image or whole small images: the input rows a tile needs are copied
+// Tiles of whole output rows of one image, or of whole small images (RowTiling: up to 128 pixel slots, some of
+// them empty where the rows do not fill them; x <= 128 channels), for 3x3 layers: the input rows a tile needs are copied
 // to LDS once, with contiguous 16-byte loads, into a frame with a zero border (one pixel left
 // and right, one row above and below where the image ends), and the nine taps of every pixel are
 // read from there.  Against gathering every tap from L2 this moves each input byte once instead
@@ -611,11 +613,11 @@ __global__ __launch_bounds__(256 * (1 + PW)) __attribute__((amdgpu_waves_per_eu(
 // conflict; stride 1: none).  Filters stream through a register ring per wave as in conv_kernel.
 // Sub-images: a tile holds `ni` of them, each `n_oh` output rows of one image.
 template <typename T, int NCB, bool TWO>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 8 : 3, NCB == 1 ? 8 : 3))) void conv_img_kernel(GemmArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 8 : NCB == 2 ? 4 : 3, NCB == 1 ? 8 : NCB == 2 ? 4 : 3))) void conv_img_kernel(GemmArgs a)
 {
     constexpr uint32_t EPC = 16 / sizeof(T), KB = 2 * EPC;
-    constexpr uint32_t NB = NCB == 1 ? 2 : 9;                       // frame loads in flight per lane
-    constexpr uint32_t P = NCB == 1 ? 4 : NCB == 2 ? 12 : 8;        // filter bricks in flight per wave (one channel block: small tiles, many resident waves)
+    constexpr uint32_t NB = NCB == 1 ? 2 : NCB == 2 ? 5 : 9;        // frame loads in flight per lane
+    constexpr uint32_t P = NCB == 1 ? 4 : 8;                        // filter bricks in flight per wave (one channel block: small tiles, many resident waves)
     static_assert(NCB == 1 || NCB == 2 || NCB == 4, "channel blocks side by side");
     constexpr uint32_t WR = 4 / NCB, RBW = 4 / WR;                  // wave rows; pixel blocks per wave
     typedef const __attribute__((address_space(1))) u32x4* gptr_t;
@@ -635,8 +637,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
     const uint32_t seg0 = a.off[t], Mt = a.M[t];
     const uint32_t local = idx - a.tile_base[t];
     const uint32_t rpr = L.rows_per_req;
-    const uint32_t rows_total = Mt * rpr, mt_ = ceil_div(rows_total, kConvTileRows);
-    const uint32_t m0 = (local % mt_) * kConvTileRows;
+    const RowTiling rt = unpack_row_tiling(L.row_tiles);     // every tenant of such a launch has one
+    const uint32_t mt_ = ceil_div(Mt * conv_tile_rows(rpr, L.row_tiles), kConvTileRows);
+    const uint32_t tm = local % mt_;
     const uint32_t nb0 = (local / mt_) * (kTileCols / kBrickRows);
     const uint32_t ncb = min((uint32_t)(kTileCols / kBrickRows), L.N_pad / kBrickRows - nb0);
     const uint32_t nKB = L.K / KB, nKBv = ceil_div(L.k_valid, KB);  // cin is a multiple of KB (whole k steps), or half of one
@@ -649,10 +652,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
     // step spans two taps, and the two halves of the wave take one tap each
     constexpr bool two = TWO;
     const uint32_t PB = cin * (uint32_t)sizeof(T) + (two ? 0 : 16), RSB = (iw_n + 2) * PB;   // bytes per pixel slot, per frame row
-    const uint32_t ni = rpr >= kConvTileRows ? 1 : kConvTileRows / rpr;           // sub-images of the tile
-    const uint32_t ppi = kConvTileRows / ni;                                      // output pixels of one sub-image
-    const uint32_t n_oh = ppi / ow_n, n_ih = (n_oh - 1) * st + 3;                 // its output rows, its frame rows
+    const uint32_t ni = rt.ni, spi = kConvTileRows / ni;                          // sub-images of the tile; pixel slots of one
+    const uint32_t n_oh = rt.n_oh, n_ih = (n_oh - 1) * st + 3;                    // its output rows, its frame rows
     const uint32_t SUB = n_ih * RSB;
+    uint32_t req0 = tm * ni, oh_first = 0;                                        // the first sub-image's request; first output row of the sub-images
+    if (ni == 1) { divmod_uniform(tm, rt.tpi, &req0, &oh_first); oh_first *= n_oh; }
+    const uint32_t px_t = min(n_oh * ow_n, rpr - oh_first * ow_n);                // pixels of a sub-image in this tile (an image's last tile may be short)
 
     // the first filter bricks travel while the frame is filled (idle waves stream block 0 and drop it)
     gptr_t wp = (gptr_t)((const u32x4*)(a.arena + L.w_off) + (size_t)(nb0 + (active ? wc : 0)) * nKB * 64 + lane);
@@ -662,12 +667,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
 
     const uint32_t cpp = cin * (uint32_t)sizeof(T) / 16, cpr = iw_n * cpp;       // 16-byte chunks per pixel, per image row
     for (uint32_t i = 0; i < ni; ++i) {
-        const uint32_t gm = m0 + i * ppi;
-        if (gm >= rows_total) break;
-        uint32_t req, pix, oh0, ow0;
-        divmod_uniform(gm, rpr, &req, &pix);
-        divmod_uniform(pix, ow_n, &oh0, &ow0);
-        const int32_t ih_first = (int32_t)(oh0 * st) - 1;                        // image row of frame row 0
+        const uint32_t req = req0 + i;
+        if (req >= Mt) break;
+        const int32_t ih_first = (int32_t)(oh_first * st) - 1;                   // image row of frame row 0
         const int32_t r_lo = ih_first < 0 ? -ih_first : 0;
         const int32_t r_hi = min((int32_t)n_ih, (int32_t)ih_n - ih_first);       // frame rows [r_lo, r_hi) lie inside the image
         gptr_t src = (gptr_t)((const T*)act_of(a.act, L.in_buf) + (size_t)(seg0 + req) * a.S) + (size_t)(ih_first + r_lo) * cpr;
@@ -704,7 +706,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
         for (uint32_t r = 0; r < RBW; ++r) {
             const uint32_t p = (wr * RBW + r) * kBrickRows + li;
             uint32_t i, pl, ohl, ow;
-            divmod_uniform(p, ppi, &i, &pl);
+            divmod_uniform(p, spi, &i, &pl);
+            if (pl >= px_t) { i = 0; pl = 0; }                                   // an empty slot multiplies the first pixel; nothing is stored for it
             divmod_uniform(pl, ow_n, &ohl, &ow);
             base[r] = i * SUB + ohl * st * RSB + ow * st * PB + (two ? 0 : lh * 16);
         }
@@ -761,13 +764,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
     uint8_t* scratch = img + wave * unit_scratch_bytes<T>();
 #pragma unroll
     for (uint32_t r = 0; r < RBW; ++r) {
-        const uint32_t m = m0 + (wr * RBW + r) * kBrickRows + li;
+        uint32_t i, pl;
+        divmod_uniform((wr * RBW + r) * kBrickRows + li, spi, &i, &pl);
         T* out = nullptr;
-        if (m < rows_total) {
-            uint32_t req, pix;
-            divmod_uniform(m, rpr, &req, &pix);
-            out = (T*)act_of(a.act, L.out_buf) + (size_t)(seg0 + req) * a.S + (size_t)pix * L.N + nbase;
-        }
+        if (pl < px_t && req0 + i < Mt)
+            out = (T*)act_of(a.act, L.out_buf) + (size_t)(seg0 + req0 + i) * a.S + (size_t)(oh_first * ow_n + pl) * L.N + nbase;
         f32x4 y[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -801,8 +802,15 @@ static void launch_conv_t(const GemmArgs& a, uint32_t max_cb, bool quad, bool lo
     else launch_conv_lds_t<T, false>(a, max_cb, quad, loaders, grid, s);
 }
 
+// A launch may ask for more dynamic LDS than the 64 KiB a kernel gets without saying so; said once per kernel.
+template <typename K>
+static hipError_t allow_frame(K kernel)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kConvFrameMaxBytes);
+}
+
 template <typename T>
-static void launch_conv_img_t(const GemmArgs& a, uint32_t max_cb, bool two, uint32_t lds_bytes, uint32_t grid, hipStream_t s)
+static hipError_t launch_conv_img_t(const GemmArgs& a, uint32_t max_cb, bool two, uint32_t lds_bytes, uint32_t grid, hipStream_t s)
 {
     lds_bytes = std::max<uint32_t>(lds_bytes, 4 * unit_scratch_bytes<T>());       // the frame also serves as store scratch
     GemmArgs b = a;
@@ -816,7 +824,19 @@ static void launch_conv_img_t(const GemmArgs& a, uint32_t max_cb, bool two, uint
         else if (max_cb <= 2) hipLaunchKernelGGL((conv_img_kernel<T, 2, false>), dim3(grid), dim3(256), lds_bytes, s, b);
         else hipLaunchKernelGGL((conv_img_kernel<T, 4, false>), dim3(grid), dim3(256), lds_bytes, s, b);
     }
+    return hipGetLastError();
 }
+
+template <typename T>
+static hipError_t prepare_conv_t()
+{
+    hipError_t e = hipSuccess;
+    auto also = [&](hipError_t x) { if (e == hipSuccess) e = x; };
+    also(allow_frame(conv_img_kernel<T, 1, false>)); also(allow_frame(conv_img_kernel<T, 2, false>)); also(allow_frame(conv_img_kernel<T, 4, false>));
+    also(allow_frame(conv_img_kernel<T, 1, sizeof(T) == 2>)); also(allow_frame(conv_img_kernel<T, 2, sizeof(T) == 2>)); also(allow_frame(conv_img_kernel<T, 4, sizeof(T) == 2>));
+    return e;
+}
+hipError_t prepare_conv(uint32_t dtype) { return dtype == MT_BF16 ? prepare_conv_t<__bf16>() : prepare_conv_t<float>(); }
 
 // img_lds_bytes > 0: every convolution of the layer index qualifies for the LDS-resident-input kernel, whose largest frame is that
 // size; img_two: their pixels are one 16-byte chunk (else none is)
@@ -826,9 +846,8 @@ hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool 
     grid = (grid + 7) / 8 * 8;
     const bool loaders = long_k && grid <= 256;                      // at most one tile per CU, every tenant's K long: waves of their own for the loads
     if (img_lds_bytes) {
-        if (dtype == MT_BF16) launch_conv_img_t<__bf16>(a, max_cb, img_two, img_lds_bytes, grid, s);
-        else launch_conv_img_t<float>(a, max_cb, img_two, img_lds_bytes, grid, s);
-        return hipGetLastError();
+        return dtype == MT_BF16 ? launch_conv_img_t<__bf16>(a, max_cb, img_two, img_lds_bytes, grid, s)
+                                : launch_conv_img_t<float>(a, max_cb, img_two, img_lds_bytes, grid, s);
     }
     if (dtype == MT_BF16) launch_conv_t<__bf16>(a, max_cb, quad, loaders, uniform_walk, grid, s);
     else launch_conv_t<float>(a, max_cb, quad, loaders, uniform_walk, grid, s);

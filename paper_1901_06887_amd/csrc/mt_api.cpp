@@ -253,6 +253,41 @@ uint32_t fc_tile_rows(uint32_t n_pad, uint32_t split_k)
     return (!split_k && n_pad / kBrickRows >= 3) ? kTileRows : kTileRows / 2;
 }
 
+// Bytes of LDS that the input rows of one row tile take (conv_img_kernel's frame): per sub-image the input rows of
+// its output rows and one more above and below, a pixel slot left and right, pixels 16 bytes apart from cin
+// elements (a padded three-channel pixel of 16 bytes stands alone).
+uint64_t row_tile_frame_bytes(const LayerDev& L, uint32_t es, RowTiling r)
+{
+    const bool chunk_pixel = L.cin * es == 16;
+    const uint32_t n_ih = (r.n_oh - 1) * L.stride + 3;
+    return (uint64_t)r.ni * n_ih * (L.in_w + 2) * (L.cin * es + (chunk_pixel ? 0 : 16));
+}
+
+// Row tiling of a 3x3 convolution (0: none): the most output rows per tile, or the most whole small images (a power
+// of two), whose input rows fit the frame.  Tiles of fewer than 128 pixels leave MFMA columns idle; the gathering
+// kernels they replace move every input byte nine times through the texture path at a quarter of the rate of a
+// contiguous load.
+uint32_t choose_row_tiling(const LayerDev& L, uint32_t es)
+{
+    // (stride 2: a tile's frame is four times its output rows, its workgroups sit alone on their CUs with the
+    // zeroing, the copy and the K loop in a row; measured slower than the gathers on every such layer of r18 and c4)
+    if (L.stride != 1) return 0;
+    const uint64_t budget = kConvFrameMaxBytes;
+    const uint32_t kb = 32 / es, rpr = L.rows_per_req;
+    if (L.ksize != 3 || L.pad != 1 || L.out_w == 0 || L.out_w > (uint32_t)kConvTileRows) return 0;
+    if (L.cin % kb != 0 && L.cin * es != 16) return 0;
+    const uint32_t H = rpr / L.out_w;
+    for (uint32_t ni = 8; ni >= 2; ni >>= 1) {               // whole images side by side
+        const RowTiling r{H, ni, 1};
+        if (rpr * ni <= (uint32_t)kConvTileRows && row_tile_frame_bytes(L, es, r) <= budget) return pack_row_tiling(r);
+    }
+    for (uint32_t n_oh = std::min<uint32_t>(H, (uint32_t)kConvTileRows / L.out_w); n_oh >= 1; --n_oh) {
+        const RowTiling r{n_oh, 1, (H + n_oh - 1) / n_oh};
+        if (r.tpi < 65536 && row_tile_frame_bytes(L, es, r) <= budget) return pack_row_tiling(r);
+    }
+    return 0;
+}
+
 // The batcher's two words per layer of one tenant (see BatchArgs::facts).
 void fill_facts(const mt_ctx* c, const HostTenant& ht, uint32_t (*w)[2])
 {
@@ -264,7 +299,7 @@ void fill_facts(const mt_ctx* c, const HostTenant& ht, uint32_t (*w)[2])
             w[l][1] = L.N_pad;
         } else if (L.kind == MT_CONV2D) {
             w[l][0] = (L.N + kTileCols - 1) / kTileCols | 1u << 31;
-            w[l][1] = L.rows_per_req;
+            w[l][1] = conv_tile_rows(L.rows_per_req, L.row_tiles);
         }
     }
 }
@@ -432,7 +467,7 @@ void recompute_bounds(mt_ctx* c)
             c->sum_macs += (double)L.k_valid * L.N * L.rows_per_req;
             c->list_mask[l / kLayerGroup] |= 1u << (k * kLayerGroup + l % kLayerGroup);
             const uint32_t nt = k == 0 ? fc_groups(L.N_pad, c->fc_split_k) : (L.N + kTileCols - 1) / kTileCols;
-            c->max_rpr[k][l] = std::max(c->max_rpr[k][l], L.rows_per_req);
+            c->max_rpr[k][l] = std::max(c->max_rpr[k][l], k == 1 ? conv_tile_rows(L.rows_per_req, L.row_tiles) : L.rows_per_req);
             c->max_nt[k][l] = std::max(c->max_nt[k][l], nt);
             c->sum_nt[k][l] += nt;
             if (k == 0) {
@@ -447,19 +482,12 @@ void recompute_bounds(mt_ctx* c)
                 c->max_conv_cb[l] = std::max(c->max_conv_cb[l], std::min<uint32_t>(L.N_pad / kBrickRows, kTileCols / kBrickRows));
                 if (L.cin % (4 * (16 / c->elem_size))) c->conv_quad[l] = false;
                 if (L.cin % (2 * (16 / c->elem_size)) || L.ksize * L.ksize > 64) c->conv_uniform[l] = false;
-                // frame of one tile of the LDS-resident-input kernel (see conv_img_kernel): whole output rows of one
-                // image, or whole images, with a one-pixel border, pixels 16 bytes apart from cin elements
-                const uint32_t rpr = L.rows_per_req, kb = 32 / c->elem_size;
-                const bool whole = L.out_w && kConvTileRows % L.out_w == 0 && (rpr % kConvTileRows == 0 || kConvTileRows % rpr == 0);
-                const uint32_t ni = rpr >= (uint32_t)kConvTileRows ? 1 : kConvTileRows / std::max(rpr, 1u);
-                uint64_t frame = 0;
+                // frame of one tile of the LDS-resident-input kernel (conv_img_kernel), which serves the layer index
+                // when every tenant's layer is row-tiled
                 const bool chunk_pixel = L.cin * c->elem_size == 16;            // a pixel is one 16-byte chunk: two taps per k step, no padding
-                if (whole && ni <= 8 && (L.cin % kb == 0 || chunk_pixel) && L.ksize == 3 && L.pad == 1) {     // (that kernel is written for 3x3 windows)
-                    const uint32_t n_oh = kConvTileRows / ni / L.out_w, n_ih = (n_oh - 1) * L.stride + 3;
-                    frame = (uint64_t)ni * n_ih * (L.in_w + 2) * (L.cin * c->elem_size + (chunk_pixel ? 0 : 16));
-                }
+                const uint64_t frame = L.row_tiles ? row_tile_frame_bytes(L, c->elem_size, unpack_row_tiling(L.row_tiles)) : 0;
                 if (c->conv_img_two[l] < 0) c->conv_img_two[l] = chunk_pixel;
-                if (frame == 0 || frame > 49152 || c->conv_img_lds[l] == 0 || c->conv_img_two[l] != (int)chunk_pixel) c->conv_img_lds[l] = 0;
+                if (frame == 0 || c->conv_img_lds[l] == 0 || c->conv_img_two[l] != (int)chunk_pixel) c->conv_img_lds[l] = 0;
                 else c->conv_img_lds[l] = std::max<uint32_t>(c->conv_img_lds[l], (uint32_t)frame);
             }
             if (k == 0 && L.N_pad >= (uint32_t)kBigMinCols && l < (uint32_t)kBigMaxLayer) {      // may be served with big tiles when it gets enough rows
@@ -686,6 +714,10 @@ mt_status plan_model(mt_ctx* c, const mt_layer_spec* specs, uint32_t n_layers, H
     }
     for (uint32_t l = 0; l + 1 < n_layers; ++l)
         if (out->layers[l].dev.pool_fill) out->layers[l].dev.pool_buf = out->layers[l + 1].dev.out_buf;
+    for (uint32_t l = 0; l < n_layers && !c->no_conv_img; ++l) {
+        LayerDev& d = out->layers[l].dev;
+        if (d.kind == MT_CONV2D && !d.pool_fill) d.row_tiles = choose_row_tiling(d, es);
+    }
     return MT_OK;
 }
 
@@ -839,6 +871,7 @@ mt_status mt_create(mt_ctx** out, const mt_config* cfg)
         CREATE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device));
         c->n_cus = (uint32_t)std::max(cus, 8) / 8 * 8;
     }
+    CREATE_TRY(prepare_conv(cfg->dtype));
     const uint64_t R = cfg->max_requests, T = cfg->max_tenants;
     CREATE_TRY(hipMalloc((void**)&c->d_arena, c->cfg.arena_bytes));
     CREATE_TRY(hipMalloc((void**)&c->d_tenants, T * sizeof(TenantDev)));
@@ -1498,6 +1531,7 @@ constexpr double kUsFcFixed = 3.7, kUsPerMbCached = 0.132, kUsPerMbHbm = 0.18, k
 constexpr double kUsPerMbL2 = 0.056, kUsFcChainFixed = 4.0, kUsPerKStep = 0.12;
 constexpr double kUsBigFixed = 4.0, kUsBigTileFixed = 7.0, kUsBigTilePer4096 = 116.0;
 constexpr double kUsConvFixed = 5.0, kConvMbPerUs = 4.0, kConvMflopPerUs = 0.5e3;      // 4.0 TB/s, 0.5 PFLOP/s
+constexpr double kUsConvFramePerKStep = 0.13, kConvFrameMflopPerUs = 0.6e3;   // the same for layer indices served from LDS frames: filter bricks are the only loads in the K loop
 constexpr double kUsConvPerKStep = 0.21;     // a convolution tile's walk through K, per k-step of 32 bytes per pixel: a launch lasts at least as long as its longest tile
 constexpr double kUsSmallFixed = 3.0, kCopyMbPerUs = 3.7, kHeadMbPerUs = 5.7, kUsHeadPerRow = 0.0008;
 constexpr double kComputeUnits = 256.0;
@@ -1595,6 +1629,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
         const bool big_layer = big_tiles >= c->big_min_tiles;
         double w_mb = 0.0, l2_mb = 0.0, chain = 0.0, big_us = 0.0, conv_mb = 0.0, conv_mflop = 0.0, gap_mb = 0.0, ops_mb = 0.0;
         double big_rounds_k = 0.0, conv_chain = 0.0;
+        const bool conv_frames = c->conv_img_lds[l] > 1 && !c->pool_fused[l] && !c->no_conv_img;     // the launch decision of run_impl
         for (uint32_t t = 0; t < T; ++t) {
             if (!counts[t] || l >= c->tenants[t].n_layers) continue;
             const LayerDev& d = c->tenants[t].layers[l].dev;
@@ -1618,7 +1653,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
                 const double out_elems = (c->pool_fused[l] ? d.N : d.out_len) + (d.fuse_add ? d.out_len : 0);      // pooled on the way out; the other operand of an addition done here
                 conv_mb += (M * ((double)d.in_h * d.in_w * d.cin + out_elems) * es + (double)d.N_pad * d.K * es) / MB;
                 conv_mflop += 2.0 * M * d.rows_per_req * d.k_valid * d.N / 1e6;
-                conv_chain = std::max(conv_chain, kUsConvPerKStep * d.k_valid * es / 32.0);
+                conv_chain = std::max(conv_chain, (conv_frames ? kUsConvFramePerKStep : kUsConvPerKStep) * d.k_valid * es / 32.0);
             } else if (d.kind == MT_GAP) {
                 gap_mb += M * ((double)d.in_h * d.in_w * d.cin + d.out_len) * es / MB;
             } else if (d.kind == MT_MAXPOOL || d.kind == MT_ADD) {    // an addition has two inputs
@@ -1626,7 +1661,7 @@ mt_status mt_estimate_run(mt_ctx* c, const uint32_t* counts, mt_run_estimate* ou
             }
         }
         if (c->max_nt[0][l] > 0) launch(std::max(chain, kUsFcFixed + us_per_mb * w_mb + kUsPerMbL2 * l2_mb));
-        if (c->max_nt[1][l] > 0) launch(kUsConvFixed + std::max(conv_chain, std::max(conv_mb / kConvMbPerUs, conv_mflop / kConvMflopPerUs)));
+        if (c->max_nt[1][l] > 0) launch(kUsConvFixed + std::max(conv_chain, std::max(conv_mb / kConvMbPerUs, conv_mflop / (conv_frames ? kConvFrameMflopPerUs : kConvMflopPerUs))));
         if (big_enabled && c->max_nt[2][l] > 0 && tile_bound(c, 2, l, R) >= c->big_min_tiles) {
             // tiles share the chip in rounds of one per compute unit; a tile's time grows with K
             if (big_layer) big_us = std::ceil(big_tiles / kComputeUnits) * kUsBigTileFixed + big_rounds_k / kComputeUnits / 4096.0 * kUsBigTilePer4096;

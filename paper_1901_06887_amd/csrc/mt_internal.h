@@ -63,6 +63,22 @@ constexpr int kRowBytes = 128;      // conv path: bytes of K one pipeline step c
 constexpr int kChanPad = 8;         // conv input channels are padded to a multiple of this
 constexpr int kWidthAlign = 64;     // K and activation widths are zero-padded to a multiple of this
 
+// How a convolution layer is cut into tiles of whole output rows: a tile holds `ni` sub-images, each `n_oh` output
+// rows of one image (ni > 1: whole images of at most 128 / ni pixels, n_oh = the image's height); an image takes
+// `tpi` tiles.  Pixel slot p of a tile (0..127): sub-image p / (128 / ni), pixel p % (128 / ni) of its n_oh rows.
+struct RowTiling { uint32_t n_oh, ni, tpi; };
+inline __host__ __device__ uint32_t pack_row_tiling(RowTiling r) { return r.n_oh | r.ni << 8 | r.tpi << 16; }
+inline __host__ __device__ RowTiling unpack_row_tiling(uint32_t p) { return RowTiling{p & 0xffu, (p >> 8) & 0xffu, p >> 16}; }
+// GEMM rows per request by which the tile lists count a convolution layer's tiles (128 per tile): the layer's
+// output pixels, or, with row tiling, 128 per tile of an image (tiles may be partly empty), 128 / ni for small images.
+inline __host__ __device__ uint32_t conv_tile_rows(uint32_t rows_per_req, uint32_t row_tiles)
+{
+    if (!row_tiles) return rows_per_req;
+    const RowTiling r = unpack_row_tiling(row_tiles);
+    return r.ni > 1 ? (uint32_t)kConvTileRows / r.ni : r.tpi * (uint32_t)kConvTileRows;
+}
+constexpr uint32_t kConvFrameMaxBytes = 96 * 1024;   // most LDS that the input rows of one such tile may take
+
 enum : uint32_t { kLayoutRows = 0, kLayoutBricks = 1 };
 constexpr uint32_t kKindNone = 0xffu;     // a layer index at which this tenant has nothing to run (its work was taken over by the layer before)
 
@@ -92,7 +108,10 @@ struct LayerDev {
     // (buffer in2_buf, same pixel and channel) to its rounded output itself and applies the addition's
     // activation; 1 + that activation, else 0.  The addition's own row then has kind kKindNone.
     uint32_t fuse_add;
-    uint32_t reserved_;
+    // CONV whose tiles can be whole output rows of one image, or whole small images, with the input rows they need
+    // held in LDS (RowTiling, packed; 0: its tiles are runs of 128 pixels).  The tile lists count such a layer's
+    // tiles by conv_tile_rows() whichever kernel serves the layer index.
+    uint32_t row_tiles;
     uint64_t w_off;      // byte offset of the packed weights in the arena
     uint64_t b_off;      // byte offset of the fp32 bias in the arena (N_pad entries for FC)
 };
@@ -215,6 +234,7 @@ hipError_t launch_fc(const GemmArgs& a, uint32_t dtype, uint32_t grid, hipStream
 hipError_t launch_fc_big(const GemmArgs& a, uint32_t dtype, uint32_t grid, uint32_t walk_grid, hipStream_t s);   // walk_grid > 0: that many workgroups walk the tiles (a multiple of 8)
 hipError_t launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s);
 hipError_t launch_mfma_rate(float* out, uint32_t iters, uint32_t grid, hipStream_t s);   // out: grid * 512 floats
+hipError_t prepare_conv(uint32_t dtype);   // once per device, before the first launch_conv: lets the frame kernels ask for more than 64 KiB of LDS
 // max_cb: the widest tile of this layer index over the registered tenants, in 32-channel blocks (1..4)
 // quad: every tenant's input channels at this layer index are a multiple of four 16-byte chunks
 hipError_t launch_conv(const GemmArgs& a, uint32_t dtype, uint32_t max_cb, bool quad, uint32_t img_lds_bytes, bool img_two, bool long_k, bool uniform_walk, uint32_t grid, hipStream_t s);
