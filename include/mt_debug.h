@@ -57,6 +57,17 @@ uint32_t mt_debug_big_tile_rows(uint32_t rows, uint32_t out_features);
  * whose launches it timed. */
 uint32_t mt_debug_big_tile_walk(uint32_t in_features);
 
+/* Measurement and test aid: how a convolution layer is cut into tiles (paper section 3.1: the layer set is closed,
+ * so the library can choose a tiling per layer shape when a model is registered).  A k x k convolution of an
+ * in_h x in_w image with in_channels channels (padded to a multiple of 8) and pad (k - 1) / 2, elements of
+ * elem_size bytes (2 or 4).  Returns 1 and writes the tiling if the layer's tiles are whole output rows whose input
+ * rows are held in LDS: *rows_per_tile output rows of one image per tile, or, if *images_per_tile > 1, that many
+ * whole images of *rows_per_tile rows each; *tiles_per_image tiles cover an image; *frame_bytes is the LDS the
+ * input rows of a tile take.  Returns 0 (and writes zeros) if the layer's tiles are runs of 128 output pixels
+ * gathered tap by tap.  Pure function of its arguments; needs no context and no device; NULL outputs are skipped. */
+int mt_debug_conv_row_tiling(uint32_t in_h, uint32_t in_w, uint32_t in_channels, uint32_t ksize, uint32_t stride, uint32_t elem_size,
+                             uint32_t* rows_per_tile, uint32_t* images_per_tile, uint32_t* tiles_per_image, uint64_t* frame_bytes);
+
 /* Measurement aid: what a loop of nothing but bf16 matrix instructions sustains on the current
  * device.  Runs, on `stream`, a kernel in which every wavefront issues v_mfma_f32_32x32x16_bf16
  * on pseudo-random operands (eight independent accumulators, two wavefronts per SIMD, no memory

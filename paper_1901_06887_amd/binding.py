@@ -119,6 +119,8 @@ def load_library() -> ctypes.CDLL:
     L.mt_debug_big_tile_rows.restype = u32
     L.mt_debug_big_tile_walk.argtypes = [u32]
     L.mt_debug_big_tile_walk.restype = u32
+    L.mt_debug_conv_row_tiling.argtypes = [u32, u32, u32, u32, u32, u32, ctypes.POINTER(u32), ctypes.POINTER(u32), ctypes.POINTER(u32), ctypes.POINTER(ctypes.c_uint64)]
+    L.mt_debug_conv_row_tiling.restype = ctypes.c_int
     L.mt_set_profiling.argtypes = [vp, ctypes.c_int]
     L.mt_get_profile.argtypes = [vp, ctypes.POINTER(mt_profile)]
     L.mt_last_error.argtypes = [vp]
@@ -320,6 +322,16 @@ def debug_big_tile_rows(rows: int, out_features: int) -> int:
 def debug_big_tile_walk(in_features: int) -> bool:
     """Whether the big tiles of a layer index with this shortest fan-in are walked by one workgroup per compute unit."""
     return bool(load_library().mt_debug_big_tile_walk(in_features))
+
+
+def debug_conv_row_tiling(in_h: int, in_w: int, in_channels: int, ksize: int = 3, stride: int = 1, elem_size: int = 2):
+    """How a convolution layer is tiled: None (runs of 128 pixels, gathered), or a dict with the output rows per tile,
+    the whole images per tile, the tiles per image and the bytes of LDS that a tile's input rows take."""
+    n_oh, ni, tpi, frame = ctypes.c_uint32(), ctypes.c_uint32(), ctypes.c_uint32(), ctypes.c_uint64()
+    if not load_library().mt_debug_conv_row_tiling(in_h, in_w, in_channels, ksize, stride, elem_size,
+                                                   ctypes.byref(n_oh), ctypes.byref(ni), ctypes.byref(tpi), ctypes.byref(frame)):
+        return None
+    return {"rows_per_tile": n_oh.value, "images_per_tile": ni.value, "tiles_per_image": tpi.value, "frame_bytes": frame.value}
 
 
 def version() -> str:

@@ -1798,6 +1798,27 @@ uint32_t mt_debug_big_tile_walk(uint32_t in_features)
     return round_up(in_features, (uint32_t)kWidthAlign) >= kBigWalkMinK ? 1 : 0;
 }
 
+int mt_debug_conv_row_tiling(uint32_t in_h, uint32_t in_w, uint32_t in_channels, uint32_t ksize, uint32_t stride, uint32_t elem_size,
+                             uint32_t* rows_per_tile, uint32_t* images_per_tile, uint32_t* tiles_per_image, uint64_t* frame_bytes)
+{
+    RowTiling r{0, 0, 0};
+    uint64_t frame = 0;
+    if (ksize >= 1 && (ksize & 1) && (stride == 1 || stride == 2) && (elem_size == 2 || elem_size == 4) && in_h && in_w && in_channels) {
+        LayerDev d{};
+        const uint32_t pad = (ksize - 1) / 2;
+        const uint32_t oh = (in_h + 2 * pad - ksize) / stride + 1, ow = (in_w + 2 * pad - ksize) / stride + 1;
+        d.kind = MT_CONV2D; d.cin = round_up(in_channels, (uint32_t)kChanPad); d.in_h = in_h; d.in_w = in_w; d.stride = stride;
+        d.out_w = ow; d.ksize = ksize; d.pad = pad; d.rows_per_req = oh * ow;
+        const uint32_t packed = choose_row_tiling(d, elem_size);
+        if (packed) { r = unpack_row_tiling(packed); frame = row_tile_frame_bytes(d, elem_size, r); }
+    }
+    if (rows_per_tile) *rows_per_tile = r.n_oh;
+    if (images_per_tile) *images_per_tile = r.ni;
+    if (tiles_per_image) *tiles_per_image = r.tpi;
+    if (frame_bytes) *frame_bytes = frame;
+    return r.n_oh != 0;
+}
+
 mt_status mt_debug_poison(mt_ctx* c)
 {
     if (!c) return MT_EINVAL;

@@ -397,3 +397,24 @@ def test_which_rows_and_layers_the_compute_bound_kernels_take():
     assert mt.debug_big_tile_rows(2048, 192) == 2048 and mt.debug_big_tile_rows(2048, 161) == 2048
     assert mt.debug_big_tile_rows(4096 + 128, 4096) == 4096 and mt.debug_big_tile_rows(4096 + 129, 4096) == 4096 + 129
     assert [mt.debug_big_tile_walk(k) for k in (64, 192, 193, 256, 4096)] == [False, False, True, True, True]
+
+
+def test_row_tiling_of_convolution_layers():
+    """3x3 convolutions at stride 1 are cut into tiles of whole output rows whose input rows (the tile's rows, one above,
+    one below, a pixel left and right, 16 bytes of padding per pixel) fit 96 KiB of LDS: as many rows as fit 128 pixels,
+    fewer when the frame would not fit; images of at most 64 pixels share a tile, 2, 4 or 8 of them.  Everything else
+    (stride 2, other windows, rows wider than a tile) is left to the gathering kernels."""
+    t = mt.debug_conv_row_tiling
+    frame = lambda rows, images, w, cin, es=2: images * (rows + 2) * (w + 2) * (cin * es + 16)
+    assert t(56, 56, 64) == {"rows_per_tile": 2, "images_per_tile": 1, "tiles_per_image": 28, "frame_bytes": frame(2, 1, 56, 64)}
+    assert t(28, 28, 128) == {"rows_per_tile": 4, "images_per_tile": 1, "tiles_per_image": 7, "frame_bytes": frame(4, 1, 28, 128)}
+    assert t(14, 14, 256) == {"rows_per_tile": 9, "images_per_tile": 1, "tiles_per_image": 2, "frame_bytes": frame(9, 1, 14, 256)}
+    assert t(7, 7, 512) == {"rows_per_tile": 7, "images_per_tile": 1, "tiles_per_image": 1, "frame_bytes": frame(7, 1, 7, 512)}   # two images would take 168 KiB
+    assert t(7, 7, 64) == {"rows_per_tile": 7, "images_per_tile": 2, "tiles_per_image": 1, "frame_bytes": frame(7, 2, 7, 64)}
+    assert t(4, 4, 32)["images_per_tile"] == 8 and t(6, 6, 32)["images_per_tile"] == 2 and t(8, 8, 16)["images_per_tile"] == 2
+    assert t(32, 32, 3) == {"rows_per_tile": 4, "images_per_tile": 1, "tiles_per_image": 8, "frame_bytes": 6 * 34 * 16}        # a padded 3-channel pixel is one 16-byte chunk
+    assert t(12, 12, 24) is None and t(12, 12, 24, elem_size=4)["rows_per_tile"] == 10     # channels in whole k steps: 16 bf16, 8 fp32 elements
+    assert t(14, 14, 512)["rows_per_tile"] == 3 and t(14, 14, 512)["frame_bytes"] == frame(3, 1, 14, 512) <= 96 * 1024           # rows given up until the frame fits
+    assert t(14, 14, 1024) is None                                                                                             # not even one row does
+    assert t(56, 56, 64, stride=2) is None and t(56, 56, 64, ksize=1) is None and t(224, 224, 3, ksize=7, stride=2) is None
+    assert t(8, 200, 16) is None                                                                                               # a row is wider than a tile

@@ -149,6 +149,28 @@ def test_additions_done_by_the_convolution_in_front_of_them(monkeypatch):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_tiles_of_whole_output_rows(dtype):
+    """3x3 layers at stride 1 whose tiles are whole output rows with the input rows in LDS, on shapes that fill a
+    tile badly: 14-pixel rows (9 rows per tile, an image's second tile has 5), 10x6 images (two per tile, an odd
+    number of requests per tenant), 20-pixel rows of 10 (6 + 4), a residual addition taken over by such a layer;
+    and layer indices at which one tenant's layer is row-tiled and another's is not (a 1x1 window, stride 2), so
+    that the launch falls back to the gathering kernels, whose lists count the row-tiled tenant's tiles generously."""
+    nets = [
+        [conv(3, 16, 14, 3), conv(16, 32, 14, 3), conv(32, 32, 14, 3), conv(32, 64, 14, 3, 2)] + tail(64, 7, 6),
+        [conv(3, 32, 14, 3), conv(32, 32, 14, 3, act=wl.ACT_NONE), conv(32, 32, 14, 1), conv(32, 48, 14, 3)] + tail(48, 14, 6),
+        [conv(3, 16, 14, 3), conv(16, 16, 14, 3, act=wl.ACT_NONE), add(16, 14, src2=1), conv(16, 32, 14, 3)] + tail(32, 14, 6),
+    ]
+    run_and_compare(fleet("row tiles, 14x14", nets, 23, dtype, seed=231), "row tiles 14x14", tight=2e-5 if dtype == "f32" else None)
+    small = [
+        [conv(3, 16, (10, 6), 3), conv(16, 32, (10, 6), 3), conv(32, 32, (10, 6), 3)] + tail(32, (10, 6), 5),
+        [conv(3, 32, (10, 6), 3), conv(32, 64, (10, 6), 3), conv(64, 16, (10, 6), 3)] + tail(16, (10, 6), 5),
+    ]
+    run_and_compare(fleet("row tiles, two images per tile", small, 31, dtype, seed=232), "row tiles 10x6", tight=2e-5 if dtype == "f32" else None)
+    wide = [[conv(3, 16, (10, 20), 3), conv(16, 128, (10, 20), 3), conv(128, 32, (10, 20), 3)] + tail(32, (10, 20), 5)] * 2
+    run_and_compare(fleet("row tiles, 20-pixel rows", wide, 9, dtype, seed=233), "row tiles 10x20", tight=2e-5 if dtype == "f32" else None)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_long_reductions_in_launches_of_few_tiles(dtype):
     """Deep layers of small batches: at most one tile per CU and K >= 1024, the shape that gets loader waves, here
     with the pooling done by the convolution (8x8 and 4x8 images of 128 and 192 channels in front of the global
