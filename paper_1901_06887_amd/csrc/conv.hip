@@ -1,5 +1,6 @@
 // Grouped k x k convolution as implicit GEMM (see mt_device.h for the overview).
 #include "mt_device.h"
+#include <type_traits>
 
 namespace mt {
 
@@ -727,32 +728,40 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 
             const uint32_t tp = min(2 * k + lh, 8u);
             return (tp / 3) * RSB + (tp % 3) * PB;
         };
-        u32x4 av[RBW];
+        // The K loop over the first NR of the wave's pixel blocks: a tile whose pixels fill only half of them (one 7x7
+        // image: 49 of 128 slots) spends half the MFMAs and LDS reads.
+        auto k_loop = [&](auto NR_) {
+            constexpr uint32_t NR = decltype(NR_)::value;
+            u32x4 av[NR];
 #pragma unroll
-        for (uint32_t r = 0; r < RBW; ++r) av[r] = *(const u32x4*)(img + base[r] + (two ? two_taps(0) : 0));
-        auto step = [&](const u32x4& wv) {
-            uint32_t off_n;
-            if (two) { kbi = min(kbi + 1, nKBv - 1); off_n = two_taps(kbi); }
-            else { advance(); off_n = min(off, 2 * RSB + 2 * PB + (cin - KB) * (uint32_t)sizeof(T)); }
-            u32x4 an[RBW];
+            for (uint32_t r = 0; r < NR; ++r) av[r] = *(const u32x4*)(img + base[r] + (two ? two_taps(0) : 0));
+            auto step = [&](const u32x4& wv) {
+                uint32_t off_n;
+                if (two) { kbi = min(kbi + 1, nKBv - 1); off_n = two_taps(kbi); }
+                else { advance(); off_n = min(off, 2 * RSB + 2 * PB + (cin - KB) * (uint32_t)sizeof(T)); }
+                u32x4 an[NR];
 #pragma unroll
-            for (uint32_t r = 0; r < RBW; ++r) an[r] = *(const u32x4*)(img + base[r] + off_n);
+                for (uint32_t r = 0; r < NR; ++r) an[r] = *(const u32x4*)(img + base[r] + off_n);
 #pragma unroll
-            for (uint32_t r = 0; r < RBW; ++r) Mma<T>::run(acc[r], wv, av[r]);   // rows = channels, columns = pixels
+                for (uint32_t r = 0; r < NR; ++r) Mma<T>::run(acc[r], wv, av[r]);   // rows = channels, columns = pixels
 #pragma unroll
-            for (uint32_t r = 0; r < RBW; ++r) av[r] = an[r];
-        };
-        const uint32_t full = nKBv / P;
-        for (uint32_t g = 0; g < full; ++g) {
+                for (uint32_t r = 0; r < NR; ++r) av[r] = an[r];
+            };
+            const uint32_t full = nKBv / P;
+            for (uint32_t g = 0; g < full; ++g) {
 #pragma unroll
-            for (uint32_t j = 0; j < P; ++j) {
-                step(wq[j]);
-                wq[j] = wp[(size_t)min(g * P + j + P, nKBv - 1) * 64];
+                for (uint32_t j = 0; j < P; ++j) {
+                    step(wq[j]);
+                    wq[j] = wp[(size_t)min(g * P + j + P, nKBv - 1) * 64];
+                }
             }
-        }
 #pragma unroll
-        for (uint32_t j = 0; j < P; ++j)
-            if (full * P + j < nKBv) step(wq[j]);
+            for (uint32_t j = 0; j < P; ++j)
+                if (full * P + j < nKBv) step(wq[j]);
+        };
+        const uint32_t blocks_used = ceil_div((ni - 1) * spi + px_t, kBrickRows);     // pixel blocks of the tile with a pixel in them
+        if (RBW > 1 && blocks_used <= wr * RBW + RBW / 2) k_loop(std::integral_constant<uint32_t, (RBW > 1 ? RBW / 2 : 1)>{});
+        else k_loop(std::integral_constant<uint32_t, RBW>{});
     }
     const float* bias = (const float*)(a.arena + L.b_off);
     const uint32_t nbase = (nb0 + (active ? wc : 0)) * kBrickRows;
